@@ -1,0 +1,393 @@
+"""Pins for the CPU oracle: closed forms, truth tables, dense brute force, finite differences.
+
+None of these re-types the oracle's own loops: each compares it with something fixed by the
+mathematics (a closed form, an integer bit permutation, a Kronecker-product matrix, a central
+finite difference, an analytic identity), so that a dropped term, wrong sign, wrong qubit order or
+transposed matrix anywhere in the oracle fails at least one of them.
+"""
+import itertools
+import os
+
+import numpy as np
+import pytest
+
+from tests import dense_bruteforce as dense
+
+RX, RY, RZ = 1, 2, 3
+NONE, RING, LADDER = 0, 1, 2
+HERE = os.path.dirname(os.path.abspath(__file__))
+
+
+def rng(seed):
+    return np.random.Generator(np.random.PCG64(seed))
+
+
+# ------------------------------------------------------------------ encoding
+def test_encode_closed_form_and_padding(oracle):
+    x = rng(1).standard_normal((5, 11)).astype(np.float32)
+    st, nrm = oracle.amp_encode(x, 4)
+    xd = x.astype(np.float64)
+    assert np.allclose(nrm, np.sqrt((xd ** 2).sum(1)), rtol=1e-14)
+    p = oracle.probs(st)
+    assert np.allclose(p[:, :11], xd ** 2 / (xd ** 2).sum(1, keepdims=True), atol=1e-15)
+    assert np.all(p[:, 11:] == 0.0) and np.all(st.imag == 0.0)
+    assert np.allclose(p.sum(1), 1.0, atol=1e-14)
+    # sign of the amplitudes is the sign of x
+    assert np.all(np.sign(st.real[:, :11]) == np.sign(xd))
+
+
+def test_encode_idempotent_and_zero_vector(oracle):
+    x = rng(2).standard_normal((3, 8)).astype(np.float32)
+    st, _ = oracle.amp_encode(x, 3)
+    st2, _ = oracle.amp_encode((3.5 * x).astype(np.float32), 3)
+    assert np.allclose(st, st2, atol=1e-7)
+    x[1] = 0.0
+    st, nrm = oracle.amp_encode(x, 3)
+    assert nrm[1] == 0.0 and np.all(st[1] == 0.0) and not np.isnan(st).any()
+
+
+def test_encode_rejects_bad_dim(oracle):
+    with pytest.raises(ValueError):
+        oracle.amp_encode(np.ones((1, 9), np.float32), 3)
+
+
+# ------------------------------------------------------------------ single gates, closed forms
+@pytest.mark.parametrize("theta", [0.0, 0.3, 1.0, np.pi / 2, 2.5, np.pi, 4.0, 6.0])
+def test_ry_closed_form(oracle, theta):
+    st = oracle.zero_state(1, 3)
+    oracle.gate_rot(st, RY, 1, theta)
+    p = oracle.probs(st)[0]
+    assert abs(p[0] - np.cos(theta / 2) ** 2) < 1e-15      # P(0) = cos^2(theta/2)
+    assert abs(p[2] - np.sin(theta / 2) ** 2) < 1e-15      # qubit 1 <-> index bit 1
+    assert abs(oracle.expz_all(st)[0, 1] - np.cos(theta)) < 1e-15
+    assert abs(st[0, 2].real - np.sin(theta / 2)) < 1e-15 and st[0, 2].imag == 0.0  # sign of s
+
+
+@pytest.mark.parametrize("theta", [0.4, np.pi / 2, np.pi, 5.0])
+def test_rx_closed_form(oracle, theta):
+    st = oracle.zero_state(1, 2)
+    oracle.gate_rot(st, RX, 0, theta)
+    assert abs(oracle.probs(st)[0, 1] - np.sin(theta / 2) ** 2) < 1e-15
+    assert abs(st[0, 1] - (-1j * np.sin(theta / 2))) < 1e-15  # RX(pi)|0> = -i|1>
+    assert abs(st[0, 0] - np.cos(theta / 2)) < 1e-15
+
+
+@pytest.mark.parametrize("phi", [0.3, 1.7, np.pi, 4.4])
+def test_rz_phase(oracle, phi):
+    x = rng(3).standard_normal((2, 8)).astype(np.float32)
+    st, _ = oracle.amp_encode(x, 3)
+    p0 = oracle.probs(st)
+    ref = st.copy()
+    oracle.gate_rot(st, RZ, 2, phi)
+    assert np.allclose(oracle.probs(st), p0, atol=1e-15)   # diagonal: probabilities unchanged
+    # amplitudes with qubit 2 = 0 pick up e^{-i phi/2}, the others e^{+i phi/2}
+    assert np.allclose(st[:, :4], ref[:, :4] * np.exp(-0.5j * phi), atol=1e-15)
+    assert np.allclose(st[:, 4:], ref[:, 4:] * np.exp(+0.5j * phi), atol=1e-15)
+    oracle.gate_rot(st, RZ, 2, -phi)
+    assert np.allclose(st, ref, atol=1e-15)
+    # relative phase seen through RY(pi/2) RZ(phi) RY(-pi/2) on |0>: P(0) = cos^2(phi/2)
+    s = oracle.zero_state(1, 1)
+    oracle.gate_rot(s, RY, 0, -np.pi / 2)
+    oracle.gate_rot(s, RZ, 0, phi)
+    oracle.gate_rot(s, RY, 0, np.pi / 2)
+    assert abs(oracle.probs(s)[0, 0] - np.cos(phi / 2) ** 2) < 1e-15
+
+
+def test_rotation_matrix_orientation(oracle):
+    """RY on |1> gives (-s, c): catches a transposed 2x2."""
+    st = np.zeros((1, 2), dtype=np.complex128)
+    st[0, 1] = 1.0
+    oracle.gate_rot(st, RY, 0, 0.7)
+    assert np.allclose(st[0], [-np.sin(0.35), np.cos(0.35)], atol=1e-15)
+
+
+# ------------------------------------------------------------------ entanglers
+def test_cnot_truth_table(oracle):
+    n = 3
+    for ctrl, tgt in itertools.permutations(range(n), 2):
+        for k in range(1 << n):
+            st = np.zeros((1, 1 << n), dtype=np.complex128)
+            st[0, k] = 1.0
+            oracle.gate_cnot(st, ctrl, tgt)
+            k2 = k ^ (1 << tgt) if (k >> ctrl) & 1 else k
+            assert st[0, k2] == 1.0 and np.count_nonzero(st) == 1
+
+
+def ring_image(k, n):
+    """Image of basis state k under CNOT(0,1), CNOT(1,2), ..., CNOT(n-1,0), by bit operations."""
+    b = [(k >> q) & 1 for q in range(n)]
+    for q in range(n):
+        b[(q + 1) % n] ^= b[q]
+    return sum(v << q for q, v in enumerate(b))
+
+
+@pytest.mark.parametrize("n", [2, 3, 4, 5, 7])
+def test_cnot_ring_permutation(oracle, n):
+    circ = oracle.make_circuit(1, [], RING)
+    N = 1 << n
+    st = np.eye(N, dtype=np.complex128)          # sample k = basis state k
+    oracle.apply_layers(st, circ, np.zeros(0))
+    for k in range(N):
+        assert st[k, ring_image(k, n)] == 1.0 and np.count_nonzero(st[k]) == 1
+    # closed form of the ring: prefix XOR, then bit 0 ^= parity of all bits
+    k = 0b1011 if n >= 4 else 0b11
+    b = [(k >> q) & 1 for q in range(n)]
+    pre = np.bitwise_xor.accumulate(b)
+    pre[0] = b[0] ^ pre[n - 1]
+    assert ring_image(k, n) == sum(int(v) << q for q, v in enumerate(pre))
+    oracle.apply_layers(st, circ, np.zeros(0), inverse=True)
+    assert np.array_equal(st, np.eye(N))
+
+
+def test_ghz_from_chain(oracle):
+    n = 4
+    st = oracle.zero_state(1, n)
+    oracle.gate_rot(st, RY, 0, np.pi / 2)
+    for q in range(n - 1):
+        oracle.gate_cnot(st, q, q + 1)
+    p = oracle.probs(st)[0]
+    assert abs(p[0] - 0.5) < 1e-15 and abs(p[-1] - 0.5) < 1e-15
+    assert np.allclose(oracle.expz_all(st), 0.0, atol=1e-15)
+    gold = np.loadtxt(os.path.join(HERE, "golden", "ghz4_probs.txt"))
+    assert np.allclose(p, gold, atol=1e-15)
+
+
+@pytest.mark.parametrize("n", [2, 3, 5])
+def test_cz_ladder(oracle, n):
+    circ = oracle.make_circuit(1, [], LADDER)
+    st = np.eye(1 << n, dtype=np.complex128)
+    oracle.apply_layers(st, circ, np.zeros(0))
+    for k in range(1 << n):
+        sign = (-1) ** bin(k & (k >> 1)).count("1")
+        assert st[k, k] == sign and np.count_nonzero(st[k]) == 1
+    plus = oracle.zero_state(1, n)
+    for q in range(n):
+        oracle.gate_rot(plus, RY, q, np.pi / 2)
+    oracle.apply_layers(plus, circ, np.zeros(0))
+    assert np.allclose(oracle.probs(plus), 2.0 ** -n, atol=1e-15)
+    assert np.allclose(oracle.expz_all(plus), 0.0, atol=1e-15)
+
+
+# ------------------------------------------------------------------ whole circuits, dense brute force
+CASES = [
+    (2, 2, (RY, RZ), RING, 0), (3, 2, (RY, RZ), RING, 0), (4, 2, (RY, RZ), RING, 0),
+    (5, 3, (RX, RY, RZ), RING, 0), (6, 2, (RX, RY, RZ), RING, 0),
+    (4, 3, (RY, RZ), LADDER, 0), (6, 2, (RY, RZ), LADDER, 0),
+    (3, 2, (RZ, RX), NONE, 0), (1, 3, (RX, RY, RZ), RING, 0),
+    (4, 3, (RY, RZ), RING, 1), (5, 2, (RY, RZ), LADDER, 1), (3, 2, (), RING, 1),
+]
+
+
+@pytest.mark.parametrize("n,L,rot,ent,reup", CASES)
+@pytest.mark.parametrize("inverse", [False, True])
+def test_circuit_vs_dense(oracle, n, L, rot, ent, reup, inverse):
+    g = rng(100 + n * 7 + L + ent + reup)
+    circ = oracle.make_circuit(L, list(rot), ent, reup)
+    P = oracle.num_params(circ, n)
+    assert P == L * (reup + len(rot)) * n
+    params = g.uniform(0, 2 * np.pi, P)
+    B = 3
+    x = g.standard_normal((B, 1 << n)).astype(np.float32)
+    feats = g.standard_normal((B, n)) if reup else None
+    st, _ = oracle.amp_encode(x, n)
+    start = st.copy()
+    oracle.apply_layers(st, circ, params, feats, inverse=inverse)
+    for b in range(B):
+        U = dense.circuit_unitary(n, L, rot, ent, reup, params, feats[b] if reup else None)
+        if inverse:
+            U = U.conj().T
+        assert np.allclose(st[b], U @ start[b], atol=1e-13)
+    assert np.allclose(oracle.probs(st).sum(1), 1.0, atol=1e-12)     # norm preservation
+
+
+@pytest.mark.parametrize("n,L,rot,ent,reup", CASES)
+def test_encoder_times_inverse_is_identity(oracle, n, L, rot, ent, reup):
+    g = rng(200 + n)
+    circ = oracle.make_circuit(L, list(rot), ent, reup)
+    params = g.uniform(0, 2 * np.pi, oracle.num_params(circ, n))
+    x = g.standard_normal((4, 1 << n)).astype(np.float32)
+    feats = g.standard_normal((4, n)) if reup else None
+    st, _ = oracle.amp_encode(x, n)
+    start = st.copy()
+    oracle.apply_layers(st, circ, params, feats)
+    assert not np.allclose(st, start, atol=1e-3) or L == 0
+    oracle.apply_layers(st, circ, params, feats, inverse=True)
+    assert np.allclose(st, start, atol=1e-13)
+    xd = x.astype(np.float64)
+    assert np.allclose(oracle.probs(st), xd ** 2 / (xd ** 2).sum(1, keepdims=True), atol=1e-13)
+
+
+def test_larger_n_unitarity_and_inverse(oracle):
+    """n = 12: too large for the dense check, pinned by norm and by U^-1 U = I."""
+    n, g = 12, rng(7)
+    circ = oracle.make_circuit(4, [RX, RY, RZ], RING)
+    params = g.uniform(0, 2 * np.pi, oracle.num_params(circ, n))
+    x = g.standard_normal((2, 1 << n)).astype(np.float32)
+    st, _ = oracle.amp_encode(x, n)
+    start = st.copy()
+    oracle.apply_layers(st, circ, params)
+    assert np.allclose(oracle.probs(st).sum(1), 1.0, atol=1e-12)
+    oracle.apply_layers(st, circ, params, inverse=True)
+    assert np.allclose(st, start, atol=1e-12)
+
+
+# ------------------------------------------------------------------ measurement
+def test_expz_from_probs_and_range(oracle):
+    n, g = 6, rng(8)
+    circ = oracle.make_circuit(2, [RY, RZ], RING)
+    st, _ = oracle.amp_encode(g.standard_normal((3, 1 << n)).astype(np.float32), n)
+    oracle.apply_layers(st, circ, g.uniform(0, 6.28, oracle.num_params(circ, n)))
+    p, z = oracle.probs(st), oracle.expz_all(st)
+    k = np.arange(1 << n)
+    for q in range(n):
+        assert np.allclose(z[:, q], (p * (1 - 2 * ((k >> q) & 1))).sum(1), atol=1e-14)
+    assert np.all(np.abs(z) <= 1.0 + 1e-14)
+
+
+@pytest.mark.parametrize("mask", [0b000001, 0b110000, 0b101010, 0b011110, 0b111111])
+def test_marginal_and_projection(oracle, mask):
+    n, g = 6, rng(9)
+    circ = oracle.make_circuit(2, [RY, RZ], RING)
+    x = g.standard_normal((3, 1 << n)).astype(np.float32)
+    params = g.uniform(0, 6.28, oracle.num_params(circ, n))
+    st, _ = oracle.amp_encode(x, n)
+    oracle.apply_layers(st, circ, params)
+    p = oracle.probs(st)
+    marg = oracle.marginal(st, mask)
+    assert np.allclose(marg.sum(1), 1.0, atol=1e-13)
+    # brute force by string manipulation of the index
+    bits = [q for q in range(n) if (mask >> q) & 1]
+    ref = np.zeros_like(marg)
+    for k in range(1 << n):
+        v = sum(((k >> q) & 1) << j for j, q in enumerate(bits))
+        ref[:, v] += p[:, k]
+    assert np.allclose(marg, ref, atol=1e-14)
+    # projection with and without renormalisation; fidelity invariants F = P0, P0^2, 1
+    keep = (np.arange(1 << n) & mask) == 0
+    for renorm, power in ((True, 1), (False, 2)):
+        s2 = st.copy()
+        p0 = oracle.project_zero(s2, mask, renormalise=renorm)
+        assert np.allclose(p0, marg[:, 0], atol=1e-14)
+        assert np.all(s2[:, ~keep] == 0)
+        scale = 1 / np.sqrt(p0)[:, None] if renorm else 1.0
+        assert np.allclose(s2[:, keep], st[:, keep] * scale, atol=1e-14)
+        oracle.apply_layers(s2, circ, params, inverse=True)
+        assert np.allclose(oracle.fidelity(s2, x), p0 ** power, atol=1e-13)
+    s3 = st.copy()
+    oracle.apply_layers(s3, circ, params, inverse=True)
+    assert np.allclose(oracle.fidelity(s3, x), 1.0, atol=1e-13)
+
+
+def test_fidelity_definition(oracle):
+    g = rng(10)
+    x = g.standard_normal((2, 8)).astype(np.float32)
+    st = (g.standard_normal((2, 8)) + 1j * g.standard_normal((2, 8)))
+    st /= np.linalg.norm(st, axis=1, keepdims=True)
+    st = np.ascontiguousarray(st)
+    xd = x.astype(np.float64)
+    ain = xd / np.linalg.norm(xd, axis=1, keepdims=True)
+    ref = np.abs((ain.conj() * st).sum(1)) ** 2
+    assert np.allclose(oracle.fidelity(st, x), ref, atol=1e-14)
+
+
+# ------------------------------------------------------------------ parameter shift
+def test_param_shift_single_ry_closed_form(oracle):
+    circ = oracle.make_circuit(1, [RY], NONE)
+    x = np.array([[1.0, 0.0]], dtype=np.float32)          # |0>
+    for theta in (0.2, 1.1, 2.9, 5.0):
+        loss, grad = oracle.param_shift_grad(x, 1, circ, [theta])
+        assert abs(loss[0] - np.cos(theta)) < 1e-15
+        assert abs(grad[0, 0] + np.sin(theta)) < 1e-15     # d cos / d theta = -sin
+
+
+@pytest.mark.parametrize("n,L,rot,ent,reup", [
+    (3, 2, (RY, RZ), LADDER, 0), (4, 2, (RX, RY, RZ), RING, 0), (3, 2, (RY, RZ), RING, 1)])
+def test_param_shift_vs_finite_difference(oracle, n, L, rot, ent, reup):
+    g = rng(11 + n + reup)
+    circ = oracle.make_circuit(L, list(rot), ent, reup)
+    P = oracle.num_params(circ, n)
+    params = g.uniform(0, 2 * np.pi, P)
+    B = 2
+    x = g.standard_normal((B, 1 << n)).astype(np.float32)
+    feats = g.standard_normal((B, n)) if reup else None
+    obs = 1
+    loss, grad = oracle.param_shift_grad(x, n, circ, params, feats, obs_qubit=obs)
+
+    def f(pv):
+        st, _ = oracle.amp_encode(x, n)
+        oracle.apply_layers(st, circ, pv, feats)
+        return oracle.expz_all(st)[:, obs]
+
+    assert np.allclose(loss, f(params), atol=1e-14)
+    h = 1e-4
+    for p in range(P):
+        e = np.zeros(P)
+        e[p] = h
+        fd = (f(params + e) - f(params - e)) / (2 * h)
+        assert np.allclose(grad[:, p], fd, atol=1e-7), p
+    # subset interface returns the same columns
+    sub = [P - 1, 0, 3]
+    _, gs = oracle.param_shift_grad(x, n, circ, params, feats, obs_qubit=obs, subset=sub)
+    assert np.array_equal(gs, grad[:, sub])
+
+
+# ------------------------------------------------------------------ sampler
+def test_sampler_uniform_closed_form(oracle):
+    n = 10
+    p = np.full((2, 1 << n), 2.0 ** -n, dtype=np.float32)
+    u = rng(12).random((2, 500))
+    s = oracle.sample(p, u)
+    assert np.array_equal(s, np.floor(u * (1 << n)).astype(np.int64))
+
+
+def test_sampler_basis_state_and_zero_weights(oracle):
+    n = 8
+    p = np.zeros((1, 1 << n), dtype=np.float32)
+    p[0, 77] = 1.0
+    u = rng(13).random((1, 100))
+    assert np.all(oracle.sample(p, u) == 77)
+    p[0, 77] = 0.25
+    p[0, 200] = 0.75
+    s = oracle.sample(p, np.array([[0.0, 0.2499999, 0.25, 0.9999999]]))
+    assert s.tolist() == [[77, 77, 200, 200]]
+    p[:] = 0
+    assert np.all(oracle.sample(p, u) == -1)
+
+
+def test_sampler_matches_python_integers_and_histogram(oracle):
+    n, g = 7, rng(14)
+    w = g.random(1 << n)
+    w[g.random(1 << n) < 0.2] = 0.0
+    p = (w / w.sum()).astype(np.float32)[None, :]
+    u = g.random((1, 20000))
+    s = oracle.sample(p, u)
+    # exact rule re-done with Python's arbitrary-precision integers
+    wk = [int(np.floor(np.ldexp(np.float64(v), 60))) for v in p[0]]
+    cum = np.cumsum(np.array(wk, dtype=object))
+    total = int(cum[-1])
+    for j in range(0, 20000, 37):
+        r = int(np.floor(np.ldexp(u[0, j], 53)))
+        t = (r * total) >> 53
+        k = next(i for i, c in enumerate(cum) if c > t)
+        assert s[0, j] == k
+    assert not np.any(p[0, s[0]] == 0.0)                       # zero-weight outcomes never drawn
+    hist = np.bincount(s[0], minlength=1 << n) / 20000.0
+    sigma = np.sqrt(p[0] * (1 - p[0]) / 20000.0)
+    assert np.all(np.abs(hist - p[0]) <= 5 * sigma + 1e-9)
+
+
+# ------------------------------------------------------------------ threading
+def test_threads_do_not_change_results(oracle):
+    g = rng(15)
+    for n in (5, 18):
+        circ = oracle.make_circuit(2, [RX, RY, RZ], RING)
+        params = g.uniform(0, 6.28, oracle.num_params(circ, n))
+        x = g.standard_normal((2, 1 << n)).astype(np.float32)
+        outs = []
+        for t in (1, oracle.max_threads()):
+            oracle.set_threads(t)
+            st, _ = oracle.amp_encode(x, n)
+            oracle.apply_layers(st, circ, params)
+            outs.append(st)
+        oracle.set_threads(oracle.max_threads())
+        assert np.array_equal(outs[0], outs[1])
