@@ -1,0 +1,292 @@
+#!/usr/bin/env python3
+"""Benchmark of the qsv hot path on one MI355X.
+
+One "step" = one pass of the whole hot path over one batch of the headline workload (config 4:
+26 qubits, batch 1: amplitude encoding, 30 layers RX/RY/RZ + CNOT ring, the full 2^26
+probability vector, 4096 seeded samples), inputs resident in HBM.  `value` is nominal
+gate-amplitude updates per second (every gate of the circuit as written counts 2^n) over the
+whole step.  The other configs are timed too and reported under "others".
+
+Prints ONE JSON line.  `roofline` is for the dominant kernel (the fused gate pass): algorithmic
+bytes per launch = one read + one write of the state, divided by the pass kernel's average
+duration measured with events on the stream the kernels run on.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+
+
+def parse_args():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--configs", default="4,3,2,1,0", help="which configs to time (4 is the headline)")
+    ap.add_argument("--tile", type=int, default=0, help="force the pass kernel's tile_log2 (0 = default)")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
+    ap.add_argument("--cpu-layers", type=int, default=4, help="layers of config 4 the oracle is timed on")
+    return ap.parse_args()
+
+
+def n_passes(qb, circ, n, batch, inverse, tile):
+    text = qb.qsv_plan_describe(circ, n, batch, inverse, tile)
+    return sum(1 for ln in text.split("\n") if ln.startswith("P "))
+
+
+class Timer:
+    """Event pairs on torch's current stream (the stream the library launches on)."""
+
+    def __init__(self, torch):
+        self.torch = torch
+        self.pairs = {}
+
+    def span(self, name):
+        t = self.torch
+        a, b = t.cuda.Event(enable_timing=True), t.cuda.Event(enable_timing=True)
+        self.pairs.setdefault(name, []).append((a, b))
+        return a, b
+
+    def total_ms(self, name):
+        return sum(a.elapsed_time(b) for a, b in self.pairs.get(name, []))
+
+
+def run_steps(torch, step, steps, warmup):
+    for _ in range(warmup):
+        step(None)
+    torch.cuda.synchronize()
+    tm = Timer(torch)
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        step(tm)
+    torch.cuda.synchronize()
+    return (time.perf_counter() - t0) * 1e3 / steps, tm
+
+
+def bench_c4(torch, qb, wl, args):
+    w = wl.config(4)
+    n = w.n
+    ctx = qb.Context(n, 1)
+    if args.tile:
+        ctx.qsv_set_option("tile_log2", args.tile)
+    circ = qb.circuit_from_spec(w.circuit)
+    xd = torch.from_numpy(w.x).cuda()
+    pd = torch.from_numpy(w.params).cuda()
+    ud = torch.from_numpy(w.uniforms).cuda()
+    probs = torch.empty((1, 1 << n), dtype=torch.float32, device="cuda")
+    shots = torch.empty(w.uniforms.shape, dtype=torch.int64, device="cuda")
+
+    def step(tm):
+        ctx.qsv_amp_encode(xd)
+        if tm:
+            a, b = tm.span("apply")
+            a.record()
+        ctx.qsv_apply_layers(circ, pd, None, 0)
+        if tm:
+            b.record()
+        ctx.qsv_measure(qb.QSV_M_PROBS, probs)
+        ctx.qsv_measure(qb.QSV_M_SAMPLE, shots, uniforms=ud)
+
+    ms, tm = run_steps(torch, step, args.steps, args.warmup)
+    passes = n_passes(qb, circ, n, 1, 0, args.tile)
+    apply_ms = tm.total_ms("apply") / args.steps
+    updates = wl.nominal_updates(w.circuit, n, 1)
+    state_bytes = 8 * (1 << n)
+    res = {
+        "workload": "c4: 26 qubits, batch 1, 30 layers RX/RY/RZ + CNOT ring, probs + 4096 samples",
+        "ms_per_step": ms, "apply_ms": apply_ms, "passes": passes, "updates": updates,
+        "updates_per_s": updates / (ms * 1e-3), "apply_updates_per_s": updates / (apply_ms * 1e-3),
+        "pass_avg_ms": apply_ms / passes, "pass_bytes": 2 * state_bytes,
+        "pass_gbs": 2 * state_bytes / (apply_ms / passes * 1e-3) / 1e9,
+    }
+    ctx.close()
+    return res, w
+
+
+def bench_c3(torch, qb, wl, args):
+    w = wl.config(3)
+    n, B = w.n, w.batch
+    ctx = qb.Context(n, B)
+    if args.tile:
+        ctx.qsv_set_option("tile_log2", args.tile)
+    circ = qb.circuit_from_spec(w.circuit)
+    xd = torch.from_numpy(w.x).cuda()
+    pd = torch.from_numpy(w.params).cuda()
+    p0 = torch.empty(B, dtype=torch.float32, device="cuda")
+    marg = torch.empty((B, 16), dtype=torch.float32, device="cuda")
+    fid = torch.empty(B, dtype=torch.float32, device="cuda")
+
+    def step(tm):
+        ctx.qsv_amp_encode(xd)
+        if tm:
+            a, b = tm.span("apply")
+            a.record()
+        ctx.qsv_apply_layers(circ, pd, None, 0)
+        if tm:
+            b.record()
+        ctx.qsv_measure(qb.QSV_M_MARGINAL, marg, mask=w.trash_mask)
+        ctx.qsv_measure(qb.QSV_M_PROJECT_ZERO, p0, mask=w.trash_mask, renormalise=1)
+        if tm:
+            a, b = tm.span("apply")
+            a.record()
+        ctx.qsv_apply_layers(circ, pd, None, 1)
+        if tm:
+            b.record()
+        ctx.qsv_measure(qb.QSV_M_FIDELITY, fid, x=xd)
+
+    ms, tm = run_steps(torch, step, args.steps, args.warmup)
+    passes = n_passes(qb, circ, n, B, 0, args.tile) + n_passes(qb, circ, n, B, 1, args.tile)
+    apply_ms = tm.total_ms("apply") / args.steps
+    updates = 2 * wl.nominal_updates(w.circuit, n, B)
+    state_bytes = 8 * B * (1 << n)
+    ctx.close()
+    return {
+        "workload": "c3: 20 qubits, batch 32, 20-layer encoder + trash projection + decoder + fidelity",
+        "ms_per_step": ms, "apply_ms": apply_ms, "passes": passes, "updates": updates,
+        "updates_per_s": updates / (ms * 1e-3), "apply_updates_per_s": updates / (apply_ms * 1e-3),
+        "pass_avg_ms": apply_ms / passes, "pass_bytes": 2 * state_bytes,
+        "pass_gbs": 2 * state_bytes / (apply_ms / passes * 1e-3) / 1e9,
+        "pass_hbm_frac": 2 * state_bytes / (apply_ms / passes * 1e-3) / 1e9 / HBM_PEAK_GBS,
+    }
+
+
+def bench_c2(torch, qb, wl, args):
+    w = wl.config(2)
+    n, B = w.n, w.batch
+    P = w.circuit.num_params(n)
+    ctx = qb.Context(n, B)
+    if args.tile:
+        ctx.qsv_set_option("tile_log2", args.tile)
+    circ = qb.circuit_from_spec(w.circuit)
+    xd = torch.from_numpy(w.x).cuda()
+    pd = torch.from_numpy(w.params).cuda()
+    loss = torch.empty(B, dtype=torch.float32, device="cuda")
+    grad = torch.empty((B, P), dtype=torch.float32, device="cuda")
+    mg = torch.empty(P, dtype=torch.float32, device="cuda")
+
+    def step(tm):
+        ctx.qsv_param_shift_grad(circ, xd, pd, None, 0, loss, grad, None, mg)
+
+    steps = max(1, min(args.steps, 3))
+    ms, _ = run_steps(torch, step, steps, 1)
+    circuits = B * (2 * P + 1)
+    updates = wl.nominal_updates(w.circuit, n, circuits)
+    ctx.close()
+    return {"workload": "c2: 16 qubits, batch 256, 10 layers RY,RZ + CZ ladder, full parameter-shift gradient",
+            "ms_per_step": ms, "steps": steps, "circuits": circuits, "params": P, "updates": updates,
+            "updates_per_s": updates / (ms * 1e-3)}
+
+
+def bench_c1(torch, qb, wl, args):
+    w = wl.config(1)
+    n, B = w.n, w.batch
+    ctx = qb.Context(n, B)
+    circ = qb.circuit_from_spec(w.circuit)
+    xd, pd, fd = (torch.from_numpy(a).cuda() for a in (w.x, w.params, w.feats))
+    z = torch.empty((B, n), dtype=torch.float32, device="cuda")
+
+    def step(tm):
+        ctx.qsv_amp_encode(xd)
+        ctx.qsv_apply_layers(circ, pd, fd, 0)
+        ctx.qsv_measure(qb.QSV_M_EXPZ_ALL, z)
+
+    ms, _ = run_steps(torch, step, args.steps, args.warmup)
+    updates = wl.nominal_updates(w.circuit, n, B)
+    ctx.close()
+    return {"workload": "c1: 10 qubits, batch 1024, 6 re-uploading layers, <Z_q> for every qubit",
+            "ms_per_step": ms, "updates": updates, "updates_per_s": updates / (ms * 1e-3)}
+
+
+def bench_c0(torch, qb, wl, args):
+    w = wl.config(0)
+    n, B = w.n, w.batch
+    ctx = qb.Context(n, B)
+    circ = qb.circuit_from_spec(w.circuit)
+    xd, pd = torch.from_numpy(w.x).cuda(), torch.from_numpy(w.params).cuda()
+    p = torch.empty((B, 1 << n), dtype=torch.float32, device="cuda")
+
+    def step(tm):
+        ctx.qsv_amp_encode(xd)
+        ctx.qsv_apply_layers(circ, pd, None, 0)
+        ctx.qsv_apply_layers(circ, pd, None, 1)
+        ctx.qsv_measure(qb.QSV_M_PROBS, p)
+
+    ms, _ = run_steps(torch, step, args.steps, args.warmup)
+    updates = 2 * wl.nominal_updates(w.circuit, n, B)
+    ctx.close()
+    return {"workload": "c0: 4 qubits, batch 64, 2-layer encoder + decoder, basis probabilities",
+            "ms_per_step": ms, "updates": updates, "updates_per_s": updates / (ms * 1e-3)}
+
+
+def cpu_baseline(wl, w4, layers):
+    """The oracle as it stands, timed on this machine's host cores on a bounded sample of config 4:
+    encode + the first `layers` layers on the same 2^26-amplitude state."""
+    from oracle import cpu
+    cpu.build()
+    spec = w4.circuit
+    per = spec.slots() * w4.n
+    circ = cpu.make_circuit(layers, list(spec.rot), spec.entangler, 0)
+    t0 = time.perf_counter()
+    st, _ = cpu.amp_encode(w4.x, w4.n)
+    cpu.apply_layers(st, circ, w4.params[:layers * per])
+    dt = time.perf_counter() - t0
+    updates = layers * spec.gates_per_layer(w4.n) * (1 << w4.n)
+    return {"value": updates / dt, "unit": "updates/s", "cores": cpu.max_threads(), "kind": "oracle",
+            "sample": "config 4 state (2^26 amplitudes, complex128): amplitude encoding + first %d of 30 "
+                      "layers (%d gates), %.1f s" % (layers, layers * spec.gates_per_layer(w4.n), dt)}
+
+
+def main():
+    args = parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (no sharding, no collectives); use --gpus 1",
+              file=sys.stderr)
+        sys.exit(2)
+    import torch
+    from paper_2602_13140_amd import binding as qb
+    from paper_2602_13140_amd import workloads as wl
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(1)
+    qb.load()  # fails loudly if libqsv.so is missing: there is no fallback path
+    which = [int(c) for c in args.configs.split(",") if c != ""]
+    others = {}
+    c4, w4 = bench_c4(torch, qb, wl, args)
+    if 3 in which:
+        others["c3"] = bench_c3(torch, qb, wl, args)
+    if 2 in which:
+        others["c2"] = bench_c2(torch, qb, wl, args)
+    if 1 in which:
+        others["c1"] = bench_c1(torch, qb, wl, args)
+    if 0 in which:
+        others["c0"] = bench_c0(torch, qb, wl, args)
+    cpu = None
+    if not args.no_cpu:
+        cpu = cpu_baseline(wl, w4, args.cpu_layers)
+    out = {
+        "metric": "gate-amplitude updates/sec (batched, complex64) + achieved HBM GB/s vs peak",
+        "value": c4["updates_per_s"], "unit": "updates/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": c4["ms_per_step"], "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": c4["workload"], "tile_log2": args.tile, "passes": c4["passes"],
+                   "apply_ms": c4["apply_ms"], "apply_updates_per_s": c4["apply_updates_per_s"]},
+        "roofline": {"bound": "hbm", "kernel": "k_pass (fused gate pass)", "achieved": c4["pass_gbs"],
+                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": c4["pass_gbs"] / HBM_PEAK_GBS,
+                     "traffic": None, "bytes_per_launch": c4["pass_bytes"],
+                     "avg_launch_ms": c4["pass_avg_ms"]},
+        "cpu_baseline": cpu,
+        "others": others,
+    }
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,161 @@
+/* qsv — batched complex64 state-vector simulation of layered parameterised circuits on one
+ * AMD MI355X (gfx950).  C ABI of libqsv.so.
+ *
+ * What the calls compute is fixed by the task statement (its "north star" paragraph and the five
+ * workload configs); the source paper itself contains no circuit material, so the conventions
+ * below are the stated readings that the CPU oracle pins with closed forms.
+ *
+ * Conventions
+ *   - qubit q is bit q of the amplitude index k (qubit 0 = least-significant bit = stride 1).
+ *   - state: DEVICE memory, complex64 [batch][2^n], interleaved (re, im) float32, sample-major.
+ *   - RX(t) = [[c,-is],[-is,c]], RY(t) = [[c,-s],[s,c]], RZ(t) = diag(e^{-it/2}, e^{+it/2}),
+ *     c = cos(t/2), s = sin(t/2).
+ *   - one layer = [re-upload RX(w[l][q] * feats[b][q]) on q = 0..n-1, if reupload]
+ *                 -> rotation slot 0 on q = 0..n-1 -> slot 1 ... -> entangler.
+ *   - CNOT ring: CNOT(control q, target (q+1) mod n) for q = 0,1,...,n-1 in that order (none for
+ *     n = 1).  CZ ladder: CZ(q, q+1) for q = 0..n-2.
+ *   - parameters: float32 [P] shared by the whole batch, P = n_layers*(reupload+n_rot)*n, flat
+ *     index p = (l*(reupload+n_rot) + slot)*n + q; slot 0 holds w when reupload = 1.
+ *
+ * Ownership and execution
+ *   - The caller owns every device buffer (state, inputs, outputs, workspace); the context owns
+ *     only host-side plans.  No call allocates or frees device memory.
+ *   - All work is enqueued on the HIP stream given to qsv_create and is asynchronous with respect
+ *     to the host; no call synchronises the stream.  Host structs (qsv_circuit, qsv_measure_req)
+ *     are read during the call and may be reused afterwards.
+ *   - Pointers named *_dev are device pointers; everything else is host memory.
+ *   - Argument errors are detected on the host before anything is launched and reported through
+ *     the return code; qsv_last_error gives the text.  No exceptions, no abort.
+ *   - One context per stream; a context is not thread-safe.
+ */
+#ifndef QSV_H
+#define QSV_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct qsv_ctx qsv_ctx;
+
+typedef enum {
+    QSV_OK = 0,
+    QSV_ERR_INVALID_ARG = 1,
+    QSV_ERR_UNSUPPORTED = 2,
+    QSV_ERR_ZERO_NORM = 3,
+    QSV_ERR_WORKSPACE = 4,
+    QSV_ERR_HIP = 5
+} qsv_status;
+
+typedef enum { QSV_RX = 1, QSV_RY = 2, QSV_RZ = 3 } qsv_axis;
+typedef enum { QSV_ENT_NONE = 0, QSV_ENT_CNOT_RING = 1, QSV_ENT_CZ_LADDER = 2 } qsv_ent;
+
+/* Layered circuit (task statement: "encoder/decoder variational layers", "data re-uploading
+ * blocks"; workload configs 0-4 give the rotation lists and entanglers). */
+typedef struct {
+    int32_t n_layers;  /* >= 0 */
+    int32_t reupload;  /* 1: every layer starts with RX(w[l][q] * feats[b][q]) on each qubit */
+    int32_t n_rot;     /* 0..3 rotation slots per layer */
+    int32_t rot[3];    /* qsv_axis of each slot, in application order */
+    int32_t entangler; /* qsv_ent */
+} qsv_circuit;
+
+/* Number of parameters P of a circuit on n qubits; -1 on a bad descriptor. */
+int64_t qsv_num_params(const qsv_circuit* c, int n_qubits);
+
+/* Workspace size in bytes that is enough for every call below at (n_qubits, batch) with up to
+ * 64 layers.  Returns 0 for n_qubits outside 1..30 or batch < 1.  A larger workspace lets
+ * qsv_param_shift_grad run more circuits per launch. */
+size_t qsv_workspace_bytes(int n_qubits, int batch);
+
+/* Create a context bound to (n_qubits, batch), a device ordinal, a HIP stream (hipStream_t cast
+ * to void*, NULL = default stream), the caller's state buffer complex64 [batch][2^n] and the
+ * caller's workspace (256-byte aligned device memory of at least qsv_workspace_bytes bytes).
+ * Nothing is launched. */
+qsv_status qsv_create(qsv_ctx** out, int n_qubits, int batch, int device, void* hip_stream,
+                      void* state_dev, void* ws_dev, size_t ws_bytes);
+void qsv_destroy(qsv_ctx* ctx);
+
+/* Text of the last error on this context (or of the last failed qsv_create when ctx is NULL).
+ * The string is owned by the library and stays valid until the next call on the context. */
+const char* qsv_last_error(const qsv_ctx* ctx);
+
+/* Amplitude encoding (task statement: "amplitude encoding of classical vectors"; every config):
+ * state[b][k] = x[b][k] / ||x[b]||_2 for k < dim, 0 for dim <= k < 2^n, imaginary part 0.
+ * x_dev: float32 [batch][dim], 1 <= dim <= 2^n.  norm_out_dev: float32 [batch] or NULL, receives
+ * ||x[b]||_2.  A zero vector gives an all-zero state and norm 0 (no NaN). */
+qsv_status qsv_amp_encode(qsv_ctx* ctx, const float* x_dev, int64_t dim, float* norm_out_dev);
+
+/* Apply the layered circuit to every sample of the state, in place (task statement: "encoder/
+ * decoder variational layers, data re-uploading blocks").  params_dev: float32 [P].  feats_dev:
+ * float32 [batch][n], required when c->reupload = 1, ignored otherwise.  inverse = 1 applies the
+ * exact inverse: layers last..first, inside a layer the entangler gates in reverse order, then
+ * the rotation slots in reverse order with negated angles, then the re-upload RX negated. */
+qsv_status qsv_apply_layers(qsv_ctx* ctx, const qsv_circuit* c, const float* params_dev,
+                            const float* feats_dev, int inverse);
+
+/* Measurement kinds (task statement: "measurement probabilities/expectations", "trash-qubit
+ * probability", "fidelity with the input state", "seeded measurement samples"). */
+typedef enum {
+    QSV_M_PROBS = 1,        /* out float32 [batch][2^n]: p[k] = |a[k]|^2 */
+    QSV_M_EXPZ_ALL = 2,     /* out float32 [batch][n]: <Z_q> = sum_k (1-2 bit_q(k)) p[k] */
+    QSV_M_EXPZ_ONE = 3,     /* out float32 [batch]: <Z_qubit> */
+    QSV_M_MARGINAL = 4,     /* out float32 [batch][2^m], m = popcount(mask) <= 20: probability of
+                               each reading v of the mask qubits (lowest mask qubit = bit 0 of v) */
+    QSV_M_PROJECT_ZERO = 5, /* out float32 [batch]: P0 = P(all mask qubits read 0); the state is
+                               then projected onto that subspace (other amplitudes set to 0) and,
+                               when renormalise = 1, divided by sqrt(P0); P0 = 0 leaves zeros */
+    QSV_M_FIDELITY = 6,     /* out float32 [batch]: |<a_in|a>|^2 with a_in = x/||x||, x_dev float32
+                               [batch][dim] zero-padded to 2^n */
+    QSV_M_SAMPLE = 7        /* out int64 [batch][shots]: basis-state indices drawn by the integer
+                               inverse-CDF rule below from the caller's uniforms */
+} qsv_mkind;
+
+/* Sampling rule (bit-exact by construction): with p32[k] = float32(|a[k]|^2) exactly as
+ * QSV_M_PROBS writes it, w[k] = floor(double(p32[k]) * 2^60) as uint64, W[k] = w[0]+...+w[k],
+ * r = floor(u * 2^53), t = floor(r * W[last] / 2^53) (128-bit product); the sample is the smallest
+ * k with W[k] > t.  Shots keep the order of the uniforms.  W[last] = 0 writes -1 for every shot. */
+typedef struct {
+    int32_t kind;               /* qsv_mkind */
+    int32_t qubit;              /* EXPZ_ONE */
+    uint64_t mask;              /* MARGINAL, PROJECT_ZERO: non-empty subset of qubits 0..n-1 */
+    int32_t renormalise;        /* PROJECT_ZERO */
+    int32_t reserved;           /* must be 0 */
+    const float* x_dev;         /* FIDELITY */
+    int64_t dim;                /* FIDELITY: 1..2^n */
+    const double* uniforms_dev; /* SAMPLE: float64 [batch][shots], values in [0,1) */
+    int64_t shots;              /* SAMPLE: >= 0 */
+    void* out_dev;              /* result, type and shape fixed by kind */
+} qsv_measure_req;
+
+qsv_status qsv_measure(qsv_ctx* ctx, const qsv_measure_req* req);
+
+/* Parameter-shift gradient of f_b = <Z_obs> after encode + circuit (task statement: "parameter-
+ * shift gradients over the batch"; config 2: "2 circuits per param per sample"):
+ *   grad[b][p] = 1/2 [ f_b(angle_p + pi/2) - f_b(angle_p - pi/2) ]
+ * (times feats[b][q] when p is a re-upload weight, whose angle is w*feat).  x_dev float32
+ * [batch][dim]; loss_dev float32 [batch] receives the unshifted f_b; grad_dev float32 [batch][P];
+ * mean_loss_dev [1] and mean_grad_dev [P] receive the batch means when not NULL.  Uses the
+ * workspace for the shifted circuits' states; the context's state buffer is left untouched. */
+qsv_status qsv_param_shift_grad(qsv_ctx* ctx, const qsv_circuit* c, const float* x_dev, int64_t dim,
+                                const float* params_dev, const float* feats_dev, int32_t obs_qubit,
+                                float* loss_dev, float* grad_dev, float* mean_loss_dev,
+                                float* mean_grad_dev);
+
+/* Host-only introspection of the pass plan the library would run for a circuit (no GPU needed):
+ * writes a text description (one line per pass, one token per operation) into buf and returns the
+ * number of bytes needed (excluding the terminator), or -1 on a bad descriptor.  tile_log2 = 0
+ * picks the library's default tile size.  Used by the host-logic tests. */
+int64_t qsv_plan_describe(const qsv_circuit* c, int n_qubits, int batch, int inverse,
+                          int tile_log2, char* buf, int64_t buf_bytes);
+
+/* Testing/tuning knobs: tile_log2 in 10..14 (0 = default) forces the tile size of the fused pass
+ * kernel; naive = 1 routes qsv_apply_layers through the one-gate-per-launch kernels. */
+qsv_status qsv_set_option(qsv_ctx* ctx, const char* name, int64_t value);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* QSV_H */

@@ -1,0 +1,514 @@
+// C-ABI layer of libqsv.so: argument validation, workspace carving, plan cache, launch order.
+// Every numeric step runs in the HIP kernels; nothing here touches amplitudes on the host.
+#include <hip/hip_runtime.h>
+
+#include <cstdio>
+#include <cstring>
+#include <string>
+#include <vector>
+
+#include "qsv.h"
+#include "qsv_kernels.h"
+#include "qsv_plan.h"
+
+using namespace qsv;
+
+namespace {
+
+constexpr size_t kAlign = 256;
+constexpr size_t kOpsRegion = 4u << 20;  // persistent: uploaded pass programs
+constexpr int kChunkBits = 12;
+
+std::string g_create_error;
+
+size_t align_up(size_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
+
+int ceil_log2_i64(int64_t v) {
+    int b = 0;
+    while (((int64_t)1 << b) < v) ++b;
+    return b;
+}
+
+struct CachedPlan {
+    qsv_circuit c;
+    int inverse, tile, grad;
+    Plan plan;
+    size_t dev_off;  // byte offset of the ops inside the ops region
+};
+
+}  // namespace
+
+struct qsv_ctx {
+    int n = 0;
+    int64_t batch = 0;
+    int device = 0;
+    hipStream_t stream = nullptr;
+    float2* state = nullptr;
+    char* ws = nullptr;
+    size_t ws_bytes = 0;
+    std::string err;
+    int opt_tile = 0;
+    int opt_naive = 0;
+    std::vector<CachedPlan> cache;
+    size_t ops_used = 0;
+};
+
+namespace {
+
+qsv_status fail(qsv_ctx* ctx, qsv_status st, const std::string& msg) {
+    if (ctx) ctx->err = msg;
+    return st;
+}
+
+qsv_status hip_fail(qsv_ctx* ctx, hipError_t e, const char* where) {
+    return fail(ctx, QSV_ERR_HIP, std::string(where) + ": " + hipGetErrorString(e));
+}
+
+#define QSV_HIP(ctx, expr, where)                                \
+    do {                                                         \
+        hipError_t e__ = (expr);                                 \
+        if (e__ != hipSuccess) return hip_fail(ctx, e__, where); \
+    } while (0)
+
+// Per-call scratch carved from the workspace after the persistent ops region.  Work on one
+// stream is ordered, so consecutive calls may reuse the same bytes.
+struct Arena {
+    qsv_ctx* ctx;
+    size_t off;
+    explicit Arena(qsv_ctx* c) : ctx(c), off(kOpsRegion) {}
+    void* take(size_t bytes) {
+        const size_t a = align_up(bytes ? bytes : 1);
+        if (off + a > ctx->ws_bytes) { need = off + a; return nullptr; }
+        void* p = ctx->ws + off;
+        off += a;
+        return p;
+    }
+    size_t remaining() const { return ctx->ws_bytes > off ? ctx->ws_bytes - off : 0; }
+    size_t need = 0;
+};
+
+qsv_status ws_fail(qsv_ctx* ctx, const Arena& ar, const char* what) {
+    char buf[160];
+    snprintf(buf, sizeof buf, "workspace too small for %s: needs at least %zu bytes, has %zu", what,
+             ar.need, ctx->ws_bytes);
+    return fail(ctx, QSV_ERR_WORKSPACE, buf);
+}
+
+CircDev to_dev(const qsv_circuit& c, int n) {
+    CircDev d;
+    d.n = n;
+    d.n_layers = c.n_layers;
+    d.reupload = c.reupload;
+    d.n_rot = c.n_rot;
+    for (int i = 0; i < 3; ++i) d.rot[i] = c.rot[i];
+    return d;
+}
+
+int chunk_blocks(int bits) { return bits > kChunkBits ? 1 << (bits - kChunkBits) : 1; }
+
+bool same_circuit(const qsv_circuit& a, const qsv_circuit& b) {
+    if (a.n_layers != b.n_layers || a.reupload != b.reupload || a.n_rot != b.n_rot ||
+        a.entangler != b.entangler)
+        return false;
+    for (int i = 0; i < a.n_rot; ++i)
+        if (a.rot[i] != b.rot[i]) return false;
+    return true;
+}
+
+// Finds or builds the plan and makes sure its ops are resident in the ops region.
+qsv_status get_plan(qsv_ctx* ctx, const qsv_circuit& c, int64_t rows, int inverse, int grad,
+                    const CachedPlan** out) {
+    const int tile = ctx->opt_tile;
+    for (const CachedPlan& cp : ctx->cache)
+        if (cp.inverse == inverse && cp.tile == tile && cp.grad == grad && same_circuit(cp.c, c)) {
+            *out = &cp;
+            return QSV_OK;
+        }
+    CachedPlan cp;
+    cp.c = c;
+    cp.inverse = inverse;
+    cp.tile = tile;
+    cp.grad = grad;
+    // rows only matter through the tile default (small states pack several rows per tile)
+    cp.plan = build_plan(c, ctx->n, rows, inverse != 0, tile, grad != 0);
+    if (!cp.plan.complete) return fail(ctx, QSV_ERR_UNSUPPORTED, "internal: pass planner failed");
+    const size_t bytes = align_up(cp.plan.ops.size() * sizeof(Op) + sizeof(Op));
+    if (bytes > kOpsRegion) return fail(ctx, QSV_ERR_UNSUPPORTED, "circuit too long for the plan buffer");
+    if (ctx->ops_used + bytes > kOpsRegion) {  // recycle: stream order keeps in-flight passes safe
+        ctx->cache.clear();
+        ctx->ops_used = 0;
+    }
+    cp.dev_off = ctx->ops_used;
+    if (!cp.plan.ops.empty())
+        QSV_HIP(ctx, hipMemcpyAsync(ctx->ws + cp.dev_off, cp.plan.ops.data(),
+                                    cp.plan.ops.size() * sizeof(Op), hipMemcpyHostToDevice, ctx->stream),
+                "upload plan");
+    ctx->ops_used += bytes;
+    ctx->cache.push_back(std::move(cp));
+    *out = &ctx->cache.back();
+    return QSV_OK;
+}
+
+RowMap plain_rows(int n) {
+    RowMap rm;
+    rm.grad = 0; rm.two_p = 0; rm.row0 = 0; rm.slots_n = 1; rm.n = n;
+    return rm;
+}
+
+// Runs the circuit on `rows` state rows starting at `state`.
+qsv_status run_circuit(qsv_ctx* ctx, const qsv_circuit& c, float2* state, int64_t rows, int inverse,
+                       const float* mats, const float* ovr, const RowMap& rm, int grad) {
+    const int n = ctx->n;
+    const bool has_u = (c.reupload + c.n_rot) > 0;
+    const int n_mats = has_u ? c.n_layers * n : 0;
+    if (ctx->opt_naive || n < kRegBits) {
+        auto layer_u = [&](int l) -> hipError_t {
+            if (!has_u) return hipSuccess;
+            for (int q = 0; q < n; ++q) {
+                hipError_t e = launch_naive_u(state, rows, n, q, mats, ovr, l * n + q, n_mats,
+                                              c.reupload, rm, ctx->stream);
+                if (e != hipSuccess) return e;
+            }
+            return hipSuccess;
+        };
+        for (int li = 0; li < c.n_layers; ++li) {
+            const int l = inverse ? c.n_layers - 1 - li : li;
+            if (!inverse) QSV_HIP(ctx, layer_u(l), "naive rotation");
+            if (c.entangler == QSV_ENT_CNOT_RING && n >= 2) {
+                for (int i = 0; i < n; ++i) {
+                    const int q = inverse ? n - 1 - i : i;
+                    QSV_HIP(ctx, launch_naive_cnot(state, rows, n, q, (q + 1) % n, ctx->stream),
+                            "naive cnot");
+                }
+            }
+            if (c.entangler == QSV_ENT_CZ_LADDER && n >= 2)
+                QSV_HIP(ctx, launch_naive_cz_ladder(state, rows, n, ctx->stream), "naive cz");
+            if (inverse) QSV_HIP(ctx, layer_u(l), "naive rotation");
+        }
+        return QSV_OK;
+    }
+    const CachedPlan* cp = nullptr;
+    qsv_status st = get_plan(ctx, c, rows, inverse, grad, &cp);
+    if (st != QSV_OK) return st;
+    const Plan& pl = cp->plan;
+    const int ext = n + ceil_log2_i64(rows);
+    const uint64_t n_tiles = ext > pl.tile ? (1ull << (ext - pl.tile)) : 1ull;
+    const Op* dev_ops = reinterpret_cast<const Op*>(ctx->ws + cp->dev_off);
+    for (const Pass& ps : pl.passes) {
+        PassArgs a;
+        a.state = state;
+        a.ops = dev_ops + ps.op_begin;
+        a.mats = mats;
+        a.ovr = ovr;
+        a.total = (uint64_t)rows << n;
+        a.n = n; a.c = ps.c; a.w = ps.w;
+        a.n_mats = n_mats;
+        a.rowdep = c.reupload;
+        a.rm = rm;
+        QSV_HIP(ctx, launch_pass(pl.tile, a, n_tiles, ctx->stream), "fused pass");
+    }
+    return QSV_OK;
+}
+
+qsv_status bind_device(qsv_ctx* ctx) {
+    QSV_HIP(ctx, hipSetDevice(ctx->device), "hipSetDevice");
+    return QSV_OK;
+}
+
+}  // namespace
+
+// ================================================================================================
+extern "C" {
+
+int64_t qsv_num_params(const qsv_circuit* c, int n_qubits) {
+    if (!check_circuit(c, n_qubits, nullptr)) return -1;
+    return (int64_t)c->n_layers * (c->reupload + c->n_rot) * n_qubits;
+}
+
+size_t qsv_workspace_bytes(int n_qubits, int batch) {
+    if (n_qubits < 1 || n_qubits > 30 || batch < 1) return 0;
+    const size_t n = (size_t)n_qubits, B = (size_t)batch;
+    const size_t row_bytes = ((size_t)8) << n;
+    size_t total = kOpsRegion;
+    total += align_up(B * 64 * n * 32);                       // per-sample matrices, 64 layers
+    total += align_up(B * 2 * (16 * 4 * n) * 32);             // shifted matrices, 16 layers x 4 slots
+    total += align_up(B * (2 * 64 * 4 * n + 1) * 8);          // gradient values f[B][2P+1]
+    total += align_up(B * (size_t)chunk_blocks(n_qubits) * 13 * 8 * 2);  // reduction partials
+    total += align_up(B * 16) * 4;                            // norms, scales
+    const size_t grad_states = row_bytes * 4 > ((size_t)256 << 20) ? row_bytes * 4 : ((size_t)256 << 20);
+    total += grad_states + (8u << 20);
+    return total;
+}
+
+qsv_status qsv_create(qsv_ctx** out, int n_qubits, int batch, int device, void* hip_stream,
+                      void* state_dev, void* ws_dev, size_t ws_bytes) {
+    if (!out) { g_create_error = "out is NULL"; return QSV_ERR_INVALID_ARG; }
+    *out = nullptr;
+    if (n_qubits < 1 || n_qubits > 30) { g_create_error = "n_qubits must be in 1..30"; return QSV_ERR_INVALID_ARG; }
+    if (batch < 1) { g_create_error = "batch must be >= 1"; return QSV_ERR_INVALID_ARG; }
+    if (device < 0) { g_create_error = "device must be >= 0"; return QSV_ERR_INVALID_ARG; }
+    if (!state_dev || !ws_dev) { g_create_error = "state_dev and ws_dev must not be NULL"; return QSV_ERR_INVALID_ARG; }
+    if (((uintptr_t)state_dev & 15) || ((uintptr_t)ws_dev & 255)) {
+        g_create_error = "state_dev must be 16-byte aligned and ws_dev 256-byte aligned";
+        return QSV_ERR_INVALID_ARG;
+    }
+    if (ws_bytes < qsv_workspace_bytes(n_qubits, batch)) {
+        g_create_error = "workspace smaller than qsv_workspace_bytes(n_qubits, batch)";
+        return QSV_ERR_WORKSPACE;
+    }
+    hipError_t e = hipSetDevice(device);
+    if (e == hipSuccess) e = set_pass_attributes();
+    if (e != hipSuccess) {
+        g_create_error = std::string("HIP initialisation failed: ") + hipGetErrorString(e);
+        return QSV_ERR_HIP;
+    }
+    qsv_ctx* ctx = new qsv_ctx();
+    ctx->n = n_qubits;
+    ctx->batch = batch;
+    ctx->device = device;
+    ctx->stream = static_cast<hipStream_t>(hip_stream);
+    ctx->state = static_cast<float2*>(state_dev);
+    ctx->ws = static_cast<char*>(ws_dev);
+    ctx->ws_bytes = ws_bytes;
+    *out = ctx;
+    return QSV_OK;
+}
+
+void qsv_destroy(qsv_ctx* ctx) { delete ctx; }
+
+const char* qsv_last_error(const qsv_ctx* ctx) {
+    return ctx ? ctx->err.c_str() : g_create_error.c_str();
+}
+
+qsv_status qsv_set_option(qsv_ctx* ctx, const char* name, int64_t value) {
+    if (!ctx || !name) return QSV_ERR_INVALID_ARG;
+    if (!strcmp(name, "tile_log2")) {
+        if (value != 0 && (value < kMinTile || value > kMaxTile))
+            return fail(ctx, QSV_ERR_INVALID_ARG, "tile_log2 must be 0 or in 10..14");
+        ctx->opt_tile = (int)value;
+        return QSV_OK;
+    }
+    if (!strcmp(name, "naive")) {
+        ctx->opt_naive = value != 0;
+        return QSV_OK;
+    }
+    return fail(ctx, QSV_ERR_INVALID_ARG, std::string("unknown option ") + name);
+}
+
+qsv_status qsv_amp_encode(qsv_ctx* ctx, const float* x_dev, int64_t dim, float* norm_out_dev) {
+    if (!ctx) return QSV_ERR_INVALID_ARG;
+    if (!x_dev) return fail(ctx, QSV_ERR_INVALID_ARG, "x_dev is NULL");
+    if (dim < 1 || dim > ((int64_t)1 << ctx->n)) return fail(ctx, QSV_ERR_INVALID_ARG, "dim must be in 1..2^n");
+    qsv_status st = bind_device(ctx);
+    if (st != QSV_OK) return st;
+    Arena ar(ctx);
+    int nblk = (int)((dim + 4095) / 4096);
+    if (nblk > 1024) nblk = 1024;
+    double* partial = (double*)ar.take((size_t)ctx->batch * nblk * 8);
+    double* inv = (double*)ar.take((size_t)ctx->batch * 8);
+    if (!partial || !inv) return ws_fail(ctx, ar, "qsv_amp_encode");
+    QSV_HIP(ctx, launch_sumsq(x_dev, ctx->batch, dim, partial, nblk, ctx->stream), "sumsq");
+    QSV_HIP(ctx, launch_norm_finish(partial, nblk, ctx->batch, inv, norm_out_dev, ctx->stream), "norm");
+    QSV_HIP(ctx, launch_encode_write(x_dev, dim, ctx->n, ctx->batch, inv, plain_rows(ctx->n), ctx->state,
+                                     ctx->stream),
+            "encode");
+    return QSV_OK;
+}
+
+qsv_status qsv_apply_layers(qsv_ctx* ctx, const qsv_circuit* c, const float* params_dev,
+                            const float* feats_dev, int inverse) {
+    if (!ctx) return QSV_ERR_INVALID_ARG;
+    std::string why;
+    if (!check_circuit(c, ctx->n, &why)) return fail(ctx, QSV_ERR_INVALID_ARG, why);
+    if (inverse != 0 && inverse != 1) return fail(ctx, QSV_ERR_INVALID_ARG, "inverse must be 0 or 1");
+    const int64_t P = qsv_num_params(c, ctx->n);
+    if (P > 0 && !params_dev) return fail(ctx, QSV_ERR_INVALID_ARG, "params_dev is NULL");
+    if (c->reupload && !feats_dev) return fail(ctx, QSV_ERR_INVALID_ARG, "reupload = 1 needs feats_dev");
+    qsv_status st = bind_device(ctx);
+    if (st != QSV_OK) return st;
+    Arena ar(ctx);
+    const CircDev cd = to_dev(*c, ctx->n);
+    float* mats = nullptr;
+    if (P > 0) {
+        const size_t count = (size_t)(c->reupload ? ctx->batch : 1) * c->n_layers * ctx->n;
+        mats = (float*)ar.take(count * 32);
+        if (!mats) return ws_fail(ctx, ar, "qsv_apply_layers");
+        QSV_HIP(ctx, launch_build_mats(cd, params_dev, feats_dev, ctx->batch, inverse, mats, ctx->stream),
+                "build matrices");
+    }
+    return run_circuit(ctx, *c, ctx->state, ctx->batch, inverse, mats, nullptr, plain_rows(ctx->n), 0);
+}
+
+qsv_status qsv_measure(qsv_ctx* ctx, const qsv_measure_req* req) {
+    if (!ctx) return QSV_ERR_INVALID_ARG;
+    if (!req) return fail(ctx, QSV_ERR_INVALID_ARG, "req is NULL");
+    if (!req->out_dev) return fail(ctx, QSV_ERR_INVALID_ARG, "out_dev is NULL");
+    if (req->reserved != 0) return fail(ctx, QSV_ERR_INVALID_ARG, "reserved must be 0");
+    const int n = ctx->n;
+    const int64_t B = ctx->batch;
+    const uint64_t full = (n >= 64) ? ~0ull : ((1ull << n) - 1);
+    qsv_status st;
+    Arena ar(ctx);
+    switch (req->kind) {
+        case QSV_M_PROBS: {
+            if ((st = bind_device(ctx)) != QSV_OK) return st;
+            QSV_HIP(ctx, launch_probs(ctx->state, (uint64_t)B << n, (float*)req->out_dev, ctx->stream),
+                    "probs");
+            return QSV_OK;
+        }
+        case QSV_M_EXPZ_ALL:
+        case QSV_M_EXPZ_ONE: {
+            const int q = req->kind == QSV_M_EXPZ_ONE ? req->qubit : -1;
+            if (req->kind == QSV_M_EXPZ_ONE && (q < 0 || q >= n))
+                return fail(ctx, QSV_ERR_INVALID_ARG, "qubit out of range");
+            if ((st = bind_device(ctx)) != QSV_OK) return st;
+            double* partial = (double*)ar.take((size_t)B * chunk_blocks(n) * 13 * 8);
+            if (!partial) return ws_fail(ctx, ar, "qsv_measure(EXPZ)");
+            QSV_HIP(ctx, launch_expz_block(ctx->state, B, n, partial, ctx->stream), "expz block");
+            QSV_HIP(ctx, launch_expz_finish(partial, B, n, q, (float*)req->out_dev, nullptr, ctx->stream),
+                    "expz finish");
+            return QSV_OK;
+        }
+        case QSV_M_MARGINAL:
+        case QSV_M_PROJECT_ZERO: {
+            if (req->mask == 0 || (req->mask & ~full)) return fail(ctx, QSV_ERR_INVALID_ARG, "mask must be a non-empty subset of the qubits");
+            const int m = __builtin_popcountll(req->mask);
+            const bool proj = req->kind == QSV_M_PROJECT_ZERO;
+            if (!proj && m > 20) return fail(ctx, QSV_ERR_UNSUPPORTED, "marginal over more than 20 qubits");
+            if (proj && req->renormalise != 0 && req->renormalise != 1)
+                return fail(ctx, QSV_ERR_INVALID_ARG, "renormalise must be 0 or 1");
+            const int64_t n_v = proj ? 1 : ((int64_t)1 << m);
+            const int64_t nblk = chunk_blocks(n - m);
+            if ((uint64_t)B * (uint64_t)n_v * (uint64_t)nblk > 0x7fffffffull)
+                return fail(ctx, QSV_ERR_UNSUPPORTED, "marginal too large for one launch");
+            if ((st = bind_device(ctx)) != QSV_OK) return st;
+            double* partial = (double*)ar.take((size_t)B * n_v * nblk * 8);
+            double* scale = (double*)ar.take((size_t)B * 8);
+            if (!partial || !scale) return ws_fail(ctx, ar, "qsv_measure(MARGINAL/PROJECT)");
+            QSV_HIP(ctx, launch_marginal_block(ctx->state, B, n, req->mask, n_v, partial, ctx->stream),
+                    "marginal block");
+            QSV_HIP(ctx, launch_marginal_finish(partial, B * n_v, nblk, (float*)req->out_dev,
+                                                proj ? (req->renormalise ? 2 : 1) : 0, scale, ctx->stream),
+                    "marginal finish");
+            if (proj)
+                QSV_HIP(ctx, launch_project(ctx->state, B, n, req->mask, scale, ctx->stream), "project");
+            return QSV_OK;
+        }
+        case QSV_M_FIDELITY: {
+            if (!req->x_dev) return fail(ctx, QSV_ERR_INVALID_ARG, "x_dev is NULL");
+            if (req->dim < 1 || req->dim > ((int64_t)1 << n)) return fail(ctx, QSV_ERR_INVALID_ARG, "dim must be in 1..2^n");
+            if ((st = bind_device(ctx)) != QSV_OK) return st;
+            int nblk = (int)((req->dim + 4095) / 4096);
+            if (nblk > 1024) nblk = 1024;
+            double* partial = (double*)ar.take((size_t)B * nblk * 3 * 8);
+            if (!partial) return ws_fail(ctx, ar, "qsv_measure(FIDELITY)");
+            QSV_HIP(ctx, launch_fidelity_block(ctx->state, B, n, req->x_dev, req->dim, partial, nblk, ctx->stream),
+                    "fidelity block");
+            QSV_HIP(ctx, launch_fidelity_finish(partial, nblk, B, (float*)req->out_dev, ctx->stream),
+                    "fidelity finish");
+            return QSV_OK;
+        }
+        case QSV_M_SAMPLE: {
+            if (req->shots < 0) return fail(ctx, QSV_ERR_INVALID_ARG, "shots must be >= 0");
+            if (req->shots > 0 && !req->uniforms_dev) return fail(ctx, QSV_ERR_INVALID_ARG, "uniforms_dev is NULL");
+            if ((st = bind_device(ctx)) != QSV_OK) return st;
+            unsigned long long* cum = (unsigned long long*)ar.take((size_t)B * chunk_blocks(n) * 8);
+            if (!cum) return ws_fail(ctx, ar, "qsv_measure(SAMPLE)");
+            QSV_HIP(ctx, launch_sample(ctx->state, B, n, req->uniforms_dev, req->shots, cum,
+                                       (long long*)req->out_dev, ctx->stream),
+                    "sample");
+            return QSV_OK;
+        }
+        default:
+            return fail(ctx, QSV_ERR_INVALID_ARG, "unknown measurement kind");
+    }
+}
+
+qsv_status qsv_param_shift_grad(qsv_ctx* ctx, const qsv_circuit* c, const float* x_dev, int64_t dim,
+                                const float* params_dev, const float* feats_dev, int32_t obs_qubit,
+                                float* loss_dev, float* grad_dev, float* mean_loss_dev,
+                                float* mean_grad_dev) {
+    if (!ctx) return QSV_ERR_INVALID_ARG;
+    std::string why;
+    if (!check_circuit(c, ctx->n, &why)) return fail(ctx, QSV_ERR_INVALID_ARG, why);
+    const int n = ctx->n;
+    const int64_t B = ctx->batch;
+    if (!x_dev) return fail(ctx, QSV_ERR_INVALID_ARG, "x_dev is NULL");
+    if (dim < 1 || dim > ((int64_t)1 << n)) return fail(ctx, QSV_ERR_INVALID_ARG, "dim must be in 1..2^n");
+    if (obs_qubit < 0 || obs_qubit >= n) return fail(ctx, QSV_ERR_INVALID_ARG, "obs_qubit out of range");
+    const int64_t P = qsv_num_params(c, n);
+    if (P > 0 && !params_dev) return fail(ctx, QSV_ERR_INVALID_ARG, "params_dev is NULL");
+    if (c->reupload && !feats_dev) return fail(ctx, QSV_ERR_INVALID_ARG, "reupload = 1 needs feats_dev");
+    if (!loss_dev) return fail(ctx, QSV_ERR_INVALID_ARG, "loss_dev is NULL");
+    if (P > 0 && !grad_dev) return fail(ctx, QSV_ERR_INVALID_ARG, "grad_dev is NULL");
+    if (2 * P + 1 > 0x3fffffff) return fail(ctx, QSV_ERR_UNSUPPORTED, "too many parameters");
+    qsv_status st = bind_device(ctx);
+    if (st != QSV_OK) return st;
+
+    Arena ar(ctx);
+    const CircDev cd = to_dev(*c, n);
+    const int64_t per = 2 * P + 1;
+    const int64_t circuits = B * per;
+    const size_t msamples = (size_t)(c->reupload ? B : 1);
+    int nblk = (int)((dim + 4095) / 4096);
+    if (nblk > 1024) nblk = 1024;
+    double* npart = (double*)ar.take((size_t)B * nblk * 8);
+    double* inv = (double*)ar.take((size_t)B * 8);
+    float* mats = (float*)ar.take(msamples * (size_t)c->n_layers * n * 32);
+    float* ovr = (float*)ar.take(msamples * (size_t)(2 * P) * 32);
+    double* f = (double*)ar.take((size_t)circuits * 8);
+    if (!npart || !inv || !mats || !ovr || !f) return ws_fail(ctx, ar, "qsv_param_shift_grad");
+    // the rest holds the states of one chunk of circuits and their reduction partials
+    const size_t row_bytes = ((size_t)8 << n) + (size_t)chunk_blocks(n) * 13 * 8 + 2 * kAlign;
+    int64_t chunk = (int64_t)(ar.remaining() / row_bytes);
+    if (chunk < 1) { ar.need = ar.off + row_bytes; return ws_fail(ctx, ar, "qsv_param_shift_grad"); }
+    if (chunk > circuits) chunk = circuits;
+    // keep the row count a power of two when several rows share a tile (extended-index tiling)
+    if (chunk < circuits) { int64_t p2 = 1; while (p2 * 2 <= chunk) p2 *= 2; chunk = p2; }
+    float2* states = (float2*)ar.take((size_t)chunk * ((size_t)8 << n));
+    double* zpart = (double*)ar.take((size_t)chunk * chunk_blocks(n) * 13 * 8);
+    if (!states || !zpart) return ws_fail(ctx, ar, "qsv_param_shift_grad");
+
+    QSV_HIP(ctx, launch_sumsq(x_dev, B, dim, npart, nblk, ctx->stream), "sumsq");
+    QSV_HIP(ctx, launch_norm_finish(npart, nblk, B, inv, nullptr, ctx->stream), "norm");
+    if (P > 0) {
+        QSV_HIP(ctx, launch_build_mats(cd, params_dev, feats_dev, B, 0, mats, ctx->stream), "build matrices");
+        QSV_HIP(ctx, launch_build_shifted(cd, params_dev, feats_dev, B, ovr, ctx->stream), "build shifted");
+    }
+    for (int64_t row0 = 0; row0 < circuits; row0 += chunk) {
+        const int64_t rows = (circuits - row0) < chunk ? (circuits - row0) : chunk;
+        RowMap rm;
+        rm.grad = 1;
+        rm.two_p = (int)(2 * P);
+        rm.row0 = row0;
+        rm.slots_n = (c->reupload + c->n_rot) * n;
+        if (rm.slots_n < 1) rm.slots_n = 1;
+        rm.n = n;
+        QSV_HIP(ctx, launch_encode_write(x_dev, dim, n, rows, inv, rm, states, ctx->stream), "encode rows");
+        st = run_circuit(ctx, *c, states, rows, 0, mats, ovr, rm, 1);
+        if (st != QSV_OK) return st;
+        QSV_HIP(ctx, launch_expz_block(states, rows, n, zpart, ctx->stream), "expz block");
+        QSV_HIP(ctx, launch_expz_finish(zpart, rows, n, obs_qubit, nullptr, f + row0, ctx->stream),
+                "expz finish");
+    }
+    QSV_HIP(ctx, launch_grad_finish(f, B, P, cd, feats_dev, loss_dev, grad_dev, mean_loss_dev,
+                                    mean_grad_dev, ctx->stream),
+            "grad finish");
+    return QSV_OK;
+}
+
+int64_t qsv_plan_describe(const qsv_circuit* c, int n_qubits, int batch, int inverse, int tile_log2,
+                          char* buf, int64_t buf_bytes) {
+    if (!check_circuit(c, n_qubits, nullptr) || batch < 1) return -1;
+    if (tile_log2 != 0 && (tile_log2 < kMinTile || tile_log2 > kMaxTile)) return -1;
+    const Plan p = build_plan(*c, n_qubits, batch, inverse != 0, tile_log2, false);
+    const std::string s = describe_plan(p);
+    if (buf && buf_bytes > 0) {
+        const size_t ncopy = s.size() < (size_t)buf_bytes - 1 ? s.size() : (size_t)buf_bytes - 1;
+        memcpy(buf, s.data(), ncopy);
+        buf[ncopy] = 0;
+    }
+    return (int64_t)s.size();
+}
+
+}  // extern "C"

@@ -1,0 +1,91 @@
+// Internal launch interface between the C-ABI layer and the HIP kernels (gfx950 only).
+#pragma once
+#include <hip/hip_runtime.h>
+
+#include <cstdint>
+
+#include "qsv_plan.h"
+
+namespace qsv {
+
+// Circuit fields the device-side matrix builders need.
+struct CircDev {
+    int n, n_layers, reupload, n_rot, rot[3];
+    int slots() const { return reupload + n_rot; }
+};
+
+// How state rows map to samples.  Plain calls: row = sample.  Gradient launches: row r of the
+// chunk is circuit gid = row0 + r of the B*(2P+1) shifted circuits; sample = gid / (2P+1),
+// variant v = gid % (2P+1); v < 2P shifts parameter v/2 by +pi/2 (v even) or -pi/2 (v odd).
+struct RowMap {
+    int grad;        // 0 plain, 1 gradient
+    int two_p;       // 2P
+    int64_t row0;
+    int slots_n;     // (reupload + n_rot) * n
+    int n;
+};
+
+struct PassArgs {
+    float2* state;
+    const Op* ops;
+    const float* mats;   // [samples if rowdep][n_mats][8]
+    const float* ovr;    // gradient: [samples if rowdep][2P][8] shifted matrices
+    uint64_t total;      // valid extended indices = rows * 2^n
+    int n, c, w;
+    int n_mats;
+    int rowdep;          // matrices differ per sample
+    RowMap rm;
+};
+
+hipError_t launch_pass(int tile, const PassArgs& a, uint64_t n_tiles, hipStream_t st);
+hipError_t set_pass_attributes();
+
+// one-gate-per-launch kernels (fallback for n < 4 and cross-check path)
+hipError_t launch_naive_u(float2* state, int64_t rows, int n, int q, const float* mats,
+                          const float* ovr, int mat_id, int n_mats, int rowdep, const RowMap& rm,
+                          hipStream_t st);
+hipError_t launch_naive_cnot(float2* state, int64_t rows, int n, int ctrl, int tgt, hipStream_t st);
+hipError_t launch_naive_cz_ladder(float2* state, int64_t rows, int n, hipStream_t st);
+
+// fused per-(layer, qubit) matrices; out: [samples if reupload][n_layers*n][8] floats
+hipError_t launch_build_mats(const CircDev& c, const float* params, const float* feats,
+                             int64_t samples, int inverse, float* out, hipStream_t st);
+// shifted matrices for the parameter-shift rule; out: [samples if reupload][2P][8]
+hipError_t launch_build_shifted(const CircDev& c, const float* params, const float* feats,
+                                int64_t samples, float* out, hipStream_t st);
+
+// encoding
+hipError_t launch_sumsq(const float* x, int64_t samples, int64_t dim, double* partial, int nblk,
+                        hipStream_t st);
+hipError_t launch_norm_finish(const double* partial, int nblk, int64_t samples, double* inv_norm,
+                              float* norm_out, hipStream_t st);
+hipError_t launch_encode_write(const float* x, int64_t dim, int n, int64_t rows, const double* inv_norm,
+                               const RowMap& rm, float2* state, hipStream_t st);
+
+// measurement
+hipError_t launch_probs(const float2* state, uint64_t total, float* out, hipStream_t st);
+// partial: [rows][nblk][13] doubles; nblk = max(1, 2^n / 4096)
+hipError_t launch_expz_block(const float2* state, int64_t rows, int n, double* partial, hipStream_t st);
+hipError_t launch_expz_finish(const double* partial, int64_t rows, int n, int q_only, float* out_f,
+                              double* out_d, hipStream_t st);
+// partial: [rows][n_v][nblk] doubles with nblk = max(1, 2^(n-m) / 4096)
+hipError_t launch_marginal_block(const float2* state, int64_t rows, int n, uint64_t mask, int64_t n_v,
+                                 double* partial, hipStream_t st);
+hipError_t launch_marginal_finish(const double* partial, int64_t rows_times_v, int64_t nblk, float* out,
+                                  int renorm_mode, double* scale, hipStream_t st);
+hipError_t launch_project(float2* state, int64_t rows, int n, uint64_t mask, const double* scale,
+                          hipStream_t st);
+hipError_t launch_fidelity_block(const float2* state, int64_t rows, int n, const float* x, int64_t dim,
+                                 double* partial, int nblk, hipStream_t st);
+hipError_t launch_fidelity_finish(const double* partial, int nblk, int64_t rows, float* out,
+                                  hipStream_t st);
+// sampling: bsum/cum are uint64 [rows][nblk], nblk = max(1, 2^n / 4096)
+hipError_t launch_sample(const float2* state, int64_t rows, int n, const double* uniforms, int64_t shots,
+                         unsigned long long* cum, long long* out, hipStream_t st);
+
+// gradient assembly from f[B][2P+1] (double)
+hipError_t launch_grad_finish(const double* f, int64_t B, int64_t P, const CircDev& c, const float* feats,
+                              float* loss, float* grad, float* mean_loss, float* mean_grad,
+                              hipStream_t st);
+
+}  // namespace qsv

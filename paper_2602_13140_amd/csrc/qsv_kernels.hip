@@ -1,0 +1,942 @@
+// HIP kernels for gfx950 (CDNA4): fused gate passes, encoding, measurement, sampling, gradient
+// assembly.  64-wide wavefronts throughout.  No code is shared with the CPU oracle.
+#include "qsv_kernels.h"
+
+namespace qsv {
+
+namespace {
+
+constexpr int R = kRegBits;
+constexpr int NR = 1 << R;
+constexpr int CHUNK_BITS = 12;            // reduction kernels: 256 threads x 16 elements
+constexpr int CHUNK = 1 << CHUNK_BITS;
+
+typedef unsigned long long u64;
+
+__device__ __forceinline__ float prob32(float2 a) {
+    // one fixed rounding sequence so that every kernel that needs p32 gets the same bits
+    return __fadd_rn(__fmul_rn(a.x, a.x), __fmul_rn(a.y, a.y));
+}
+
+__device__ __forceinline__ double wave_sum(double v) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+    return v;
+}
+
+// Sum over a 256-thread block; result valid in thread 0.  sm: 4 doubles.
+__device__ __forceinline__ double block_sum256(double v, double* sm) {
+    v = wave_sum(v);
+    const int w = threadIdx.x >> 6;
+    __syncthreads();
+    if ((threadIdx.x & 63) == 0) sm[w] = v;
+    __syncthreads();
+    return sm[0] + sm[1] + sm[2] + sm[3];
+}
+
+// ------------------------------------------------------------------------------------------
+// Row mapping (plain: row = sample; gradient: row -> (sample, shifted parameter)).
+struct RowCtx {
+    u64 sample;
+    int ovr_id;     // matrix id replaced by the shifted matrix, or -1
+    u64 ovr_off;    // float offset of that matrix inside the shifted table (per-sample part added by caller)
+};
+
+__device__ __forceinline__ RowCtx row_ctx(const RowMap& rm, u64 row) {
+    RowCtx rc;
+    rc.sample = row;
+    rc.ovr_id = -1;
+    rc.ovr_off = 0;
+    if (rm.grad) {
+        const u64 gid = (u64)rm.row0 + row;
+        const u64 per = (u64)rm.two_p + 1;
+        rc.sample = gid / per;
+        const int v = (int)(gid % per);
+        if (v < rm.two_p) {
+            const int p = v >> 1;
+            const int l = p / rm.slots_n;
+            const int q = p % rm.n;
+            rc.ovr_id = l * rm.n + q;
+            rc.ovr_off = (u64)v * 8;
+        }
+    }
+    return rc;
+}
+
+// ------------------------------------------------------------------------------------------
+// Fused pass kernel.
+//
+// Tile-local index tau (T bits) <-> extended index e: e = tile_base | (tau & (2^c-1)) |
+// ((tau >> c) << w).  In layout s a lane holds the 16 amplitudes tau = thr_part | (i << s),
+// i = 0..15, where thr_part spreads the thread index over the other T-4 bits.
+
+__device__ __forceinline__ unsigned swz(unsigned tau) { return tau ^ ((tau >> R) & 15u); }
+
+template <int J>
+__device__ __forceinline__ void apply_u(float (&vr)[NR], float (&vi)[NR], const float (&m)[8]) {
+#pragma unroll
+    for (int i = 0; i < NR; ++i) {
+        if (i & (1 << J)) continue;
+        const int i1 = i | (1 << J);
+        const float x0r = vr[i], x0i = vi[i], x1r = vr[i1], x1i = vi[i1];
+        vr[i] = m[0] * x0r - m[1] * x0i + m[2] * x1r - m[3] * x1i;
+        vi[i] = m[0] * x0i + m[1] * x0r + m[2] * x1i + m[3] * x1r;
+        vr[i1] = m[4] * x0r - m[5] * x0i + m[6] * x1r - m[7] * x1i;
+        vi[i1] = m[4] * x0i + m[5] * x0r + m[6] * x1i + m[7] * x1r;
+    }
+}
+
+template <int JT, int JC>
+__device__ __forceinline__ void cx_reg(float (&vr)[NR], float (&vi)[NR]) {
+#pragma unroll
+    for (int i = 0; i < NR; ++i) {
+        if (!(i & (1 << JC)) || (i & (1 << JT))) continue;
+        const int i1 = i | (1 << JT);
+        const float tr = vr[i], ti = vi[i];
+        vr[i] = vr[i1]; vi[i] = vi[i1];
+        vr[i1] = tr; vi[i1] = ti;
+    }
+}
+
+template <int JT>
+__device__ __forceinline__ void cx_sel(float (&vr)[NR], float (&vi)[NR], bool cond) {
+#pragma unroll
+    for (int i = 0; i < NR; ++i) {
+        if (i & (1 << JT)) continue;
+        const int i1 = i | (1 << JT);
+        const float ar = vr[i], ai = vi[i], br = vr[i1], bi = vi[i1];
+        vr[i] = cond ? br : ar; vi[i] = cond ? bi : ai;
+        vr[i1] = cond ? ar : br; vi[i1] = cond ? ai : bi;
+    }
+}
+
+template <int T>
+__global__ __launch_bounds__(1 << (T - R)) void k_pass(const PassArgs a) {
+    extern __shared__ float2 lds[];
+    const unsigned thr = threadIdx.x;
+    const u64 tb = blockIdx.x;
+    const int c = a.c, w = a.w;
+    const unsigned cmask = (1u << c) - 1u;
+    const int wc = w - c;
+    const u64 tile_base = ((tb & ((1ull << wc) - 1ull)) << c) | ((tb >> wc) << (w + T - c));
+    auto expand = [&](unsigned tau) -> u64 {
+        return (u64)(tau & cmask) | ((u64)(tau >> c) << w);
+    };
+    if (tile_base >= a.total) return;  // padding tile (batch not a power of two): nothing to do
+    // tiles never straddle a state row unless T > n, in which case rows are per lane
+    const bool rows_uniform = a.n >= T;
+    RowCtx urc = row_ctx(a.rm, tile_base >> a.n);
+
+    float vr[NR], vi[NR];
+    int s = 0;
+    unsigned tau_thr = 0;
+    u64 e0 = 0;
+    auto set_layout = [&](int ns) {
+        s = ns;
+        tau_thr = ((thr >> s) << (s + R)) | (thr & ((1u << s) - 1u));
+        e0 = tile_base | expand(tau_thr);
+    };
+
+    for (int pc = 0;; ++pc) {
+        const Op op = a.ops[pc];
+        if (op.kind == OP_END) break;
+        switch (op.kind) {
+            case OP_LOAD: {
+                set_layout(op.a);
+#pragma unroll
+                for (int i = 0; i < NR; ++i) {
+                    const u64 e = e0 | expand((unsigned)i << s);
+                    float2 v = make_float2(0.f, 0.f);
+                    if (e < a.total) v = a.state[e];
+                    vr[i] = v.x; vi[i] = v.y;
+                }
+                break;
+            }
+            case OP_XPOSE: {
+                __syncthreads();
+#pragma unroll
+                for (int i = 0; i < NR; ++i)
+                    lds[swz(tau_thr | ((unsigned)i << s))] = make_float2(vr[i], vi[i]);
+                __syncthreads();
+                set_layout(op.a);
+#pragma unroll
+                for (int i = 0; i < NR; ++i) {
+                    const float2 v = lds[swz(tau_thr | ((unsigned)i << s))];
+                    vr[i] = v.x; vi[i] = v.y;
+                }
+                break;
+            }
+            case OP_U: {
+                float m[8];
+                const int id = op.arg;
+                if (!op.b) {
+                    const float* p = a.mats + (u64)id * 8;
+#pragma unroll
+                    for (int k = 0; k < 8; ++k) m[k] = p[k];
+                } else if (rows_uniform) {
+                    const float* p = (id == urc.ovr_id)
+                        ? a.ovr + (a.rowdep ? urc.sample * (u64)a.rm.two_p * 8 : 0) + urc.ovr_off
+                        : a.mats + ((a.rowdep ? urc.sample * (u64)a.n_mats : 0) + (u64)id) * 8;
+#pragma unroll
+                    for (int k = 0; k < 8; ++k) m[k] = p[k];
+                } else {
+                    // several rows per tile: the run lies inside the qubit bits (planner rule), so
+                    // all 16 amplitudes of a lane share one row
+                    u64 ee = e0 < a.total ? e0 : 0;
+                    const RowCtx rc = row_ctx(a.rm, ee >> a.n);
+                    const float* p = (id == rc.ovr_id)
+                        ? a.ovr + (a.rowdep ? rc.sample * (u64)a.rm.two_p * 8 : 0) + rc.ovr_off
+                        : a.mats + ((a.rowdep ? rc.sample * (u64)a.n_mats : 0) + (u64)id) * 8;
+#pragma unroll
+                    for (int k = 0; k < 8; ++k) m[k] = p[k];
+                }
+                switch (op.a) {
+                    case 0: apply_u<0>(vr, vi, m); break;
+                    case 1: apply_u<1>(vr, vi, m); break;
+                    case 2: apply_u<2>(vr, vi, m); break;
+                    default: apply_u<3>(vr, vi, m); break;
+                }
+                break;
+            }
+            case OP_CX_REG: {
+                switch (op.a * 4 + op.b) {
+                    case 1: cx_reg<0, 1>(vr, vi); break;
+                    case 2: cx_reg<0, 2>(vr, vi); break;
+                    case 3: cx_reg<0, 3>(vr, vi); break;
+                    case 4: cx_reg<1, 0>(vr, vi); break;
+                    case 6: cx_reg<1, 2>(vr, vi); break;
+                    case 7: cx_reg<1, 3>(vr, vi); break;
+                    case 8: cx_reg<2, 0>(vr, vi); break;
+                    case 9: cx_reg<2, 1>(vr, vi); break;
+                    case 11: cx_reg<2, 3>(vr, vi); break;
+                    case 12: cx_reg<3, 0>(vr, vi); break;
+                    case 13: cx_reg<3, 1>(vr, vi); break;
+                    case 14: cx_reg<3, 2>(vr, vi); break;
+                    default: break;
+                }
+                break;
+            }
+            case OP_CX_DYN: {
+                const bool cond = (e0 >> op.b) & 1ull;
+                switch (op.a) {
+                    case 0: cx_sel<0>(vr, vi, cond); break;
+                    case 1: cx_sel<1>(vr, vi, cond); break;
+                    case 2: cx_sel<2>(vr, vi, cond); break;
+                    default: cx_sel<3>(vr, vi, cond); break;
+                }
+                break;
+            }
+            case OP_CZ: {
+                const u64 mask = (u64)(unsigned)op.arg;
+#pragma unroll
+                for (int i = 0; i < NR; ++i) {
+                    const u64 k = e0 | expand((unsigned)i << s);
+                    if (__popcll(k & (k >> 1) & mask) & 1) { vr[i] = -vr[i]; vi[i] = -vi[i]; }
+                }
+                break;
+            }
+            default: break;
+        }
+    }
+#pragma unroll
+    for (int i = 0; i < NR; ++i) {
+        const u64 e = e0 | expand((unsigned)i << s);
+        if (e < a.total) a.state[e] = make_float2(vr[i], vi[i]);
+    }
+}
+
+// ------------------------------------------------------------------------------------------
+// One-gate-per-launch kernels.
+__global__ __launch_bounds__(256) void k_naive_u(float2* state, u64 pairs, int n, int q,
+                                                 const float* mats, const float* ovr, int mat_id,
+                                                 int n_mats, int rowdep, RowMap rm) {
+    const u64 i = (u64)blockIdx.x * 256 + threadIdx.x;
+    if (i >= pairs) return;
+    const u64 bit = 1ull << q;
+    const u64 k0 = ((i >> q) << (q + 1)) | (i & (bit - 1));  // extended index, bit q clear
+    const u64 k1 = k0 | bit;
+    const RowCtx rc = row_ctx(rm, k0 >> n);
+    const float* m = (mat_id == rc.ovr_id)
+        ? ovr + (rowdep ? rc.sample * (u64)rm.two_p * 8 : 0) + rc.ovr_off
+        : mats + ((rowdep ? rc.sample * (u64)n_mats : 0) + (u64)mat_id) * 8;
+    const float2 x0 = state[k0], x1 = state[k1];
+    float2 y0, y1;
+    y0.x = m[0] * x0.x - m[1] * x0.y + m[2] * x1.x - m[3] * x1.y;
+    y0.y = m[0] * x0.y + m[1] * x0.x + m[2] * x1.y + m[3] * x1.x;
+    y1.x = m[4] * x0.x - m[5] * x0.y + m[6] * x1.x - m[7] * x1.y;
+    y1.y = m[4] * x0.y + m[5] * x0.x + m[6] * x1.y + m[7] * x1.x;
+    state[k0] = y0;
+    state[k1] = y1;
+}
+
+__global__ __launch_bounds__(256) void k_naive_cnot(float2* state, u64 total, int ctrl, int tgt) {
+    const u64 k = (u64)blockIdx.x * 256 + threadIdx.x;
+    if (k >= total) return;
+    if (((k >> ctrl) & 1) && !((k >> tgt) & 1)) {
+        const u64 k1 = k | (1ull << tgt);
+        const float2 t = state[k];
+        state[k] = state[k1];
+        state[k1] = t;
+    }
+}
+
+__global__ __launch_bounds__(256) void k_naive_cz_ladder(float2* state, u64 total, int n) {
+    const u64 e = (u64)blockIdx.x * 256 + threadIdx.x;
+    if (e >= total) return;
+    const u64 k = e & ((1ull << n) - 1);
+    if (__popcll(k & (k >> 1)) & 1) {
+        float2 v = state[e];
+        v.x = -v.x; v.y = -v.y;
+        state[e] = v;
+    }
+}
+
+// ------------------------------------------------------------------------------------------
+// Fused per-(layer, qubit) matrices, computed in double and rounded once to float.
+struct M2 { double r[4], i[4]; };  // row-major 2x2: [0]=m00 [1]=m01 [2]=m10 [3]=m11
+
+__device__ __forceinline__ M2 rot_m(int axis, double t) {
+    double s, c;
+    sincos(0.5 * t, &s, &c);
+    M2 m;
+    for (int k = 0; k < 4; ++k) { m.r[k] = 0.0; m.i[k] = 0.0; }
+    if (axis == QSV_RX) { m.r[0] = c; m.i[1] = -s; m.i[2] = -s; m.r[3] = c; }
+    else if (axis == QSV_RY) { m.r[0] = c; m.r[1] = -s; m.r[2] = s; m.r[3] = c; }
+    else { m.r[0] = c; m.i[0] = -s; m.r[3] = c; m.i[3] = s; }
+    return m;
+}
+
+__device__ __forceinline__ M2 mul_m(const M2& a, const M2& b) {  // a * b
+    M2 o;
+    for (int r = 0; r < 2; ++r)
+        for (int cc = 0; cc < 2; ++cc) {
+            double sr = 0.0, si = 0.0;
+            for (int k = 0; k < 2; ++k) {
+                const double ar = a.r[r * 2 + k], ai = a.i[r * 2 + k];
+                const double br = b.r[k * 2 + cc], bi = b.i[k * 2 + cc];
+                sr += ar * br - ai * bi;
+                si += ar * bi + ai * br;
+            }
+            o.r[r * 2 + cc] = sr; o.i[r * 2 + cc] = si;
+        }
+    return o;
+}
+
+// U(l,q) for one sample: slots applied in order (re-upload RX first), i.e. U = R_last ... R_first.
+// shift_slot >= 0 adds shift to that slot's angle.
+__device__ void fused_u(const CircDev& c, const float* params, const float* feats, u64 sample, int l,
+                        int q, int shift_slot, double shift, int inverse, float* out8) {
+    M2 u;
+    for (int k = 0; k < 4; ++k) { u.r[k] = (k == 0 || k == 3) ? 1.0 : 0.0; u.i[k] = 0.0; }
+    const int slots = c.reupload + c.n_rot;
+    for (int sl = 0; sl < slots; ++sl) {
+        double t = (double)params[((u64)l * slots + sl) * c.n + q];
+        int axis;
+        if (c.reupload && sl == 0) { t *= (double)feats[sample * c.n + q]; axis = QSV_RX; }
+        else axis = c.rot[sl - c.reupload];
+        if (sl == shift_slot) t += shift;
+        u = mul_m(rot_m(axis, t), u);
+    }
+    if (inverse) {  // conjugate transpose
+        M2 d;
+        d.r[0] = u.r[0]; d.i[0] = -u.i[0];
+        d.r[1] = u.r[2]; d.i[1] = -u.i[2];
+        d.r[2] = u.r[1]; d.i[2] = -u.i[1];
+        d.r[3] = u.r[3]; d.i[3] = -u.i[3];
+        u = d;
+    }
+    for (int k = 0; k < 4; ++k) { out8[2 * k] = (float)u.r[k]; out8[2 * k + 1] = (float)u.i[k]; }
+}
+
+__global__ __launch_bounds__(256) void k_build_mats(CircDev c, const float* params, const float* feats,
+                                                    u64 count, int inverse, float* out) {
+    const u64 idx = (u64)blockIdx.x * 256 + threadIdx.x;
+    if (idx >= count) return;
+    const u64 per = (u64)c.n_layers * c.n;
+    const u64 sample = idx / per;
+    const int lq = (int)(idx % per);
+    fused_u(c, params, feats, sample, lq / c.n, lq % c.n, -1, 0.0, inverse, out + idx * 8);
+}
+
+__global__ __launch_bounds__(256) void k_build_shifted(CircDev c, const float* params,
+                                                       const float* feats, u64 count, float* out) {
+    const u64 idx = (u64)blockIdx.x * 256 + threadIdx.x;
+    if (idx >= count) return;
+    const int slots = c.reupload + c.n_rot;
+    const u64 two_p = 2ull * c.n_layers * slots * c.n;
+    const u64 sample = idx / two_p;
+    const int v = (int)(idx % two_p);
+    const int p = v >> 1;
+    const int q = p % c.n;
+    const int sl = (p / c.n) % slots;
+    const int l = p / (c.n * slots);
+    const double shift = (v & 1) ? -1.57079632679489661923 : 1.57079632679489661923;
+    fused_u(c, params, feats, sample, l, q, sl, shift, 0, out + idx * 8);
+}
+
+// ------------------------------------------------------------------------------------------
+// Amplitude encoding.
+__global__ __launch_bounds__(256) void k_sumsq(const float* x, u64 dim, double* partial, int nblk) {
+    __shared__ double sm[4];
+    const u64 b = blockIdx.y;
+    const float* xb = x + b * dim;
+    double acc = 0.0;
+    for (u64 base = (u64)blockIdx.x * CHUNK; base < dim; base += (u64)nblk * CHUNK) {
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+            const u64 k = base + (u64)i * 256 + threadIdx.x;
+            if (k < dim) { const double v = (double)xb[k]; acc += v * v; }
+        }
+    }
+    const double tot = block_sum256(acc, sm);
+    if (threadIdx.x == 0) partial[b * nblk + blockIdx.x] = tot;
+}
+
+__global__ __launch_bounds__(256) void k_norm_finish(const double* partial, int nblk, double* inv_norm,
+                                                     float* norm_out) {
+    __shared__ double sm[4];
+    const u64 b = blockIdx.x;
+    double acc = 0.0;
+    for (int i = threadIdx.x; i < nblk; i += 256) acc += partial[b * nblk + i];
+    const double tot = block_sum256(acc, sm);
+    if (threadIdx.x == 0) {
+        const double nrm = sqrt(tot);
+        inv_norm[b] = nrm > 0.0 ? 1.0 / nrm : 0.0;
+        if (norm_out) norm_out[b] = (float)nrm;
+    }
+}
+
+__global__ __launch_bounds__(256) void k_encode_write(const float* x, u64 dim, int n, u64 total,
+                                                      const double* inv_norm, RowMap rm,
+                                                      float2* state) {
+    const u64 e2 = ((u64)blockIdx.x * 256 + threadIdx.x) * 2;
+    if (e2 >= total) return;
+    const u64 row = e2 >> n;
+    const u64 sample = row_ctx(rm, row).sample;
+    const double inv = inv_norm[sample];
+    const u64 k = e2 & ((1ull << n) - 1);
+    const float* xb = x + sample * dim;
+    float4 o;
+    o.x = k < dim ? (float)((double)xb[k] * inv) : 0.f;
+    o.y = 0.f;
+    o.z = (k + 1) < dim ? (float)((double)xb[k + 1] * inv) : 0.f;
+    o.w = 0.f;
+    *reinterpret_cast<float4*>(state + e2) = o;
+}
+
+// ------------------------------------------------------------------------------------------
+// Measurement.
+__global__ __launch_bounds__(256) void k_probs(const float2* state, u64 total, float* out) {
+    const u64 e2 = ((u64)blockIdx.x * 256 + threadIdx.x) * 2;
+    if (e2 >= total) return;
+    const float4 v = *reinterpret_cast<const float4*>(state + e2);
+    float2 o;
+    o.x = prob32(make_float2(v.x, v.y));
+    o.y = prob32(make_float2(v.z, v.w));
+    *reinterpret_cast<float2*>(out + e2) = o;
+}
+
+// Block (row, blk) reduces 4096 consecutive amplitudes to 13 doubles: total T and the signed sums
+// Z_0..Z_11 for the 12 index bits inside the chunk.  Chunk-local index = i*256 + thread
+// (bits 0-5 lane, 6-7 wavefront, 8-11 register).
+__global__ __launch_bounds__(256) void k_expz_block(const float2* state, int n, int nblk,
+                                                    double* partial) {
+    __shared__ double sm[4][11];
+    const u64 row = blockIdx.y;
+    const u64 dimn = 1ull << n;
+    const u64 base = (u64)blockIdx.x * CHUNK;
+    const float2* a = state + row * dimn;
+    double T = 0.0, zr[4] = {0.0, 0.0, 0.0, 0.0};
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+        const u64 k = base + (u64)i * 256 + threadIdx.x;
+        double p = 0.0;
+        if (k < dimn) p = (double)prob32(a[k]);
+        T += p;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) zr[j] += ((i >> j) & 1) ? -p : p;
+    }
+    const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+    double zl[6];
+#pragma unroll
+    for (int b = 0; b < 6; ++b) {
+        const double Tp = __shfl_xor(T, 1 << b, 64);
+#pragma unroll
+        for (int j = 0; j < 4; ++j) zr[j] += __shfl_xor(zr[j], 1 << b, 64);
+#pragma unroll
+        for (int j = 0; j < 6; ++j)
+            if (j < b) zl[j] += __shfl_xor(zl[j], 1 << b, 64);
+        zl[b] = ((lane >> b) & 1) ? Tp - T : T - Tp;
+        T += Tp;
+    }
+    if (lane == 0) {
+        sm[wv][0] = T;
+#pragma unroll
+        for (int j = 0; j < 6; ++j) sm[wv][1 + j] = zl[j];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) sm[wv][7 + j] = zr[j];
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        double* o = partial + (row * nblk + blockIdx.x) * 13;
+        const double t0 = sm[0][0], t1 = sm[1][0], t2 = sm[2][0], t3 = sm[3][0];
+        o[0] = (t0 + t1) + (t2 + t3);
+        for (int j = 0; j < 6; ++j) o[1 + j] = (sm[0][1 + j] + sm[1][1 + j]) + (sm[2][1 + j] + sm[3][1 + j]);
+        o[7] = (t0 - t1) + (t2 - t3);
+        o[8] = (t0 + t1) - (t2 + t3);
+        for (int j = 0; j < 4; ++j) o[9 + j] = (sm[0][7 + j] + sm[1][7 + j]) + (sm[2][7 + j] + sm[3][7 + j]);
+    }
+}
+
+// One wavefront per (row, qubit): combine block partials.  Bits below 12 use the blocks' signed
+// sums; higher bits are constant inside a block, so they sign the block totals.
+__global__ __launch_bounds__(256) void k_expz_finish(const double* partial, u64 rows, int n, int nblk,
+                                                     int q_only, float* out_f, double* out_d) {
+    const int lane = threadIdx.x & 63;
+    const u64 job = (u64)blockIdx.x * 4 + (threadIdx.x >> 6);
+    const int nq = q_only >= 0 ? 1 : n;
+    if (job >= rows * nq) return;
+    const u64 row = job / nq;
+    const int q = q_only >= 0 ? q_only : (int)(job % nq);
+    const double* p = partial + row * nblk * 13;
+    double acc = 0.0;
+    if (q < CHUNK_BITS) {
+        for (int b = lane; b < nblk; b += 64) acc += p[(u64)b * 13 + 1 + q];
+    } else {
+        for (int b = lane; b < nblk; b += 64) {
+            const double t = p[(u64)b * 13];
+            acc += ((b >> (q - CHUNK_BITS)) & 1) ? -t : t;
+        }
+    }
+    acc = wave_sum(acc);
+    if (lane == 0) {
+        if (out_f) out_f[job] = (float)acc;
+        if (out_d) out_d[job] = acc;
+    }
+}
+
+__device__ __forceinline__ u64 deposit(u64 v, u64 mask, int n) {  // spread the bits of v over mask
+    u64 o = 0;
+    int j = 0;
+    for (int q = 0; q < n; ++q)
+        if ((mask >> q) & 1) { o |= ((v >> j) & 1ull) << q; ++j; }
+    return o;
+}
+
+// Block (row, v, blk): sum of p over the indices whose mask bits read v, 4096 of them per block.
+__global__ __launch_bounds__(256) void k_marginal_block(const float2* state, int n, u64 mask, u64 n_v,
+                                                        u64 nblk, u64 sub, double* partial) {
+    __shared__ double sm[4];
+    const u64 id = blockIdx.x;
+    const u64 blk = id % nblk;
+    const u64 v = (id / nblk) % n_v;
+    const u64 row = id / (nblk * n_v);
+    const u64 fixed = deposit(v, mask, n);
+    const u64 free_mask = ((1ull << n) - 1) & ~mask;
+    const float2* a = state + (row << n);
+    double acc = 0.0;
+#pragma unroll 4
+    for (int i = 0; i < 16; ++i) {
+        const u64 j = blk * CHUNK + (u64)i * 256 + threadIdx.x;
+        if (j < sub) acc += (double)prob32(a[fixed | deposit(j, free_mask, n)]);
+    }
+    const double tot = block_sum256(acc, sm);
+    if (threadIdx.x == 0) partial[id] = tot;
+}
+
+// One wavefront per (row, v).  renorm_mode: 0 plain marginal; 1 also scale = 1; 2 also
+// scale = 1/sqrt(P) (0 when P = 0).
+__global__ __launch_bounds__(256) void k_marginal_finish(const double* partial, u64 jobs, u64 nblk,
+                                                         float* out, int renorm_mode, double* scale) {
+    const int lane = threadIdx.x & 63;
+    const u64 job = (u64)blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (job >= jobs) return;
+    double acc = 0.0;
+    for (u64 b = lane; b < nblk; b += 64) acc += partial[job * nblk + b];
+    acc = wave_sum(acc);
+    if (lane == 0) {
+        out[job] = (float)acc;
+        if (renorm_mode == 1) scale[job] = 1.0;
+        if (renorm_mode == 2) scale[job] = acc > 0.0 ? 1.0 / sqrt(acc) : 0.0;
+    }
+}
+
+__global__ __launch_bounds__(256) void k_project(float2* state, u64 total, int n, u64 mask,
+                                                 const double* scale) {
+    const u64 e = (u64)blockIdx.x * 256 + threadIdx.x;
+    if (e >= total) return;
+    float2 v = state[e];
+    if (e & mask) {  // mask has no bits at or above n
+        v.x = 0.f; v.y = 0.f;
+    } else {
+        const double sc = scale[e >> n];
+        v.x = (float)((double)v.x * sc);
+        v.y = (float)((double)v.y * sc);
+    }
+    state[e] = v;
+}
+
+__global__ __launch_bounds__(256) void k_fidelity_block(const float2* state, int n, const float* x,
+                                                        u64 dim, int nblk, double* partial) {
+    __shared__ double sm[4];
+    const u64 row = blockIdx.y;
+    const float2* a = state + (row << n);
+    const float* xb = x + row * dim;
+    double sxx = 0.0, sr = 0.0, si = 0.0;
+    for (u64 base = (u64)blockIdx.x * CHUNK; base < dim; base += (u64)nblk * CHUNK) {
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+            const u64 k = base + (u64)i * 256 + threadIdx.x;
+            if (k < dim) {
+                const double xv = (double)xb[k];
+                const float2 av = a[k];
+                sxx += xv * xv;
+                sr += xv * (double)av.x;
+                si += xv * (double)av.y;
+            }
+        }
+    }
+    const double t0 = block_sum256(sxx, sm);
+    const double t1 = block_sum256(sr, sm);
+    const double t2 = block_sum256(si, sm);
+    if (threadIdx.x == 0) {
+        double* o = partial + (row * nblk + blockIdx.x) * 3;
+        o[0] = t0; o[1] = t1; o[2] = t2;
+    }
+}
+
+__global__ __launch_bounds__(256) void k_fidelity_finish(const double* partial, int nblk, float* out) {
+    __shared__ double sm[4];
+    const u64 row = blockIdx.x;
+    double sxx = 0.0, sr = 0.0, si = 0.0;
+    for (int i = threadIdx.x; i < nblk; i += 256) {
+        const double* p = partial + (row * nblk + i) * 3;
+        sxx += p[0]; sr += p[1]; si += p[2];
+    }
+    const double t0 = block_sum256(sxx, sm);
+    const double t1 = block_sum256(sr, sm);
+    const double t2 = block_sum256(si, sm);
+    if (threadIdx.x == 0) out[row] = t0 > 0.0 ? (float)((t1 * t1 + t2 * t2) / t0) : 0.f;
+}
+
+// ------------------------------------------------------------------------------------------
+// Sampling: integer inverse CDF (see qsv.h).  All sums are uint64, hence order-independent.
+__device__ __forceinline__ u64 weight60(float2 a) {
+    const double p = (double)prob32(a);
+    return p > 0.0 ? (u64)(p * 1152921504606846976.0) : 0ull;  // 2^60, truncation = floor
+}
+
+__device__ __forceinline__ u64 wave_sum_u64(u64 v) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+    return v;
+}
+
+__global__ __launch_bounds__(256) void k_sample_blocksum(const float2* state, int n, int nblk, u64* bsum) {
+    __shared__ u64 sm[4];
+    const u64 row = blockIdx.y;
+    const u64 dimn = 1ull << n;
+    const float2* a = state + (row << n);
+    u64 acc = 0;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+        const u64 k = (u64)blockIdx.x * CHUNK + (u64)i * 256 + threadIdx.x;
+        if (k < dimn) acc += weight60(a[k]);
+    }
+    acc = wave_sum_u64(acc);
+    if ((threadIdx.x & 63) == 0) sm[threadIdx.x >> 6] = acc;
+    __syncthreads();
+    if (threadIdx.x == 0) bsum[row * nblk + blockIdx.x] = sm[0] + sm[1] + sm[2] + sm[3];
+}
+
+// In-place inclusive prefix sum of each row's block sums (one 1024-thread block per row).
+__global__ __launch_bounds__(1024) void k_sample_scan(u64* cum, int nblk) {
+    __shared__ u64 sm[1024];
+    u64* c = cum + (u64)blockIdx.x * nblk;
+    const int per = (nblk + 1023) / 1024;
+    const int lo = threadIdx.x * per;
+    const int hi = min(lo + per, nblk);
+    u64 loc = 0;
+    for (int i = lo; i < hi; ++i) loc += c[i];
+    sm[threadIdx.x] = loc;
+    __syncthreads();
+    for (int o = 1; o < 1024; o <<= 1) {
+        u64 add = 0;
+        if ((int)threadIdx.x >= o) add = sm[threadIdx.x - o];
+        __syncthreads();
+        sm[threadIdx.x] += add;
+        __syncthreads();
+    }
+    u64 run = sm[threadIdx.x] - loc;  // exclusive prefix of this thread's span
+    for (int i = lo; i < hi; ++i) { run += c[i]; c[i] = run; }
+}
+
+// One wavefront per shot.
+__global__ __launch_bounds__(256) void k_sample_draw(const float2* state, int n, int nblk, const u64* cum,
+                                                     const double* uniforms, u64 shots, u64 jobs,
+                                                     long long* out) {
+    const int lane = threadIdx.x & 63;
+    const u64 job = (u64)blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (job >= jobs) return;
+    const u64 row = job / shots;
+    const u64* c = cum + row * nblk;
+    const u64 W = c[nblk - 1];
+    if (W == 0) { if (lane == 0) out[job] = -1; return; }
+    const u64 r = (u64)(uniforms[job] * 9007199254740992.0);  // floor(u * 2^53)
+    const u64 t = (__umul64hi(r, W) << 11) | ((r * W) >> 53);   // floor(r * W / 2^53)
+    int lo = 0, hi = nblk - 1;                                  // smallest block with cum > t
+    while (lo < hi) {
+        const int mid = lo + ((hi - lo) >> 1);
+        if (c[mid] > t) hi = mid; else lo = mid + 1;
+    }
+    u64 base = lo > 0 ? c[lo - 1] : 0;
+    const u64 dimn = 1ull << n;
+    const float2* a = state + (row << n);
+    const u64 k0 = (u64)lo * CHUNK;
+    long long found = -1;
+    for (int it = 0; it < CHUNK / 64; ++it) {
+        const u64 k = k0 + (u64)it * 64 + lane;
+        u64 incl = k < dimn ? weight60(a[k]) : 0ull;
+#pragma unroll
+        for (int o = 1; o < 64; o <<= 1) {
+            const u64 up = __shfl_up(incl, o, 64);
+            if (lane >= o) incl += up;
+        }
+        const u64 hit = __ballot(base + incl > t);
+        if (hit) { found = (long long)(k0 + (u64)it * 64 + (u64)(__ffsll((long long)hit) - 1)); break; }
+        base += __shfl(incl, 63, 64);
+    }
+    if (lane == 0) out[job] = found;
+}
+
+// ------------------------------------------------------------------------------------------
+// Gradient assembly.
+__global__ __launch_bounds__(256) void k_grad_finish(const double* f, u64 B, u64 P, CircDev c,
+                                                     const float* feats, float* loss, float* grad) {
+    const u64 idx = (u64)blockIdx.x * 256 + threadIdx.x;
+    if (idx >= B * (P + 1)) return;
+    const u64 b = idx / (P + 1), p = idx % (P + 1);
+    const double* fb = f + b * (2 * P + 1);
+    if (p == P) { if (loss) loss[b] = (float)fb[2 * P]; return; }
+    double g = 0.5 * (fb[2 * p] - fb[2 * p + 1]);
+    const int slots = c.reupload + c.n_rot;
+    if (c.reupload && ((p / c.n) % slots) == 0) g *= (double)feats[b * c.n + (p % c.n)];
+    grad[b * P + p] = (float)g;
+}
+
+// Batch means in a fixed order (one thread per parameter; thread P does the loss).
+__global__ __launch_bounds__(256) void k_grad_mean(const double* f, u64 B, u64 P, CircDev c,
+                                                   const float* feats, float* mean_loss,
+                                                   float* mean_grad) {
+    const u64 p = (u64)blockIdx.x * 256 + threadIdx.x;
+    if (p > P) return;
+    const int slots = c.reupload + c.n_rot;
+    double acc = 0.0;
+    if (p == P) {
+        if (!mean_loss) return;
+        for (u64 b = 0; b < B; ++b) acc += f[b * (2 * P + 1) + 2 * P];
+        mean_loss[0] = (float)(acc / (double)B);
+        return;
+    }
+    if (!mean_grad) return;
+    const bool isw = c.reupload && ((p / c.n) % slots) == 0;
+    for (u64 b = 0; b < B; ++b) {
+        const double* fb = f + b * (2 * P + 1);
+        double g = 0.5 * (fb[2 * p] - fb[2 * p + 1]);
+        if (isw) g *= (double)feats[b * c.n + (p % c.n)];
+        acc += g;
+    }
+    mean_grad[p] = (float)(acc / (double)B);
+}
+
+inline unsigned blocks_for(u64 items, unsigned per) { return (unsigned)((items + per - 1) / per); }
+
+}  // namespace
+
+// ============================================================================================
+// Launchers.
+hipError_t set_pass_attributes() {
+    hipError_t e;
+    e = hipFuncSetAttribute(reinterpret_cast<const void*>(k_pass<13>),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, (1 << 13) * 8);
+    if (e != hipSuccess) return e;
+    e = hipFuncSetAttribute(reinterpret_cast<const void*>(k_pass<14>),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, (1 << 14) * 8);
+    return e;
+}
+
+hipError_t launch_pass(int tile, const PassArgs& a, uint64_t n_tiles, hipStream_t st) {
+    if (n_tiles == 0 || n_tiles > 0x7fffffffull) return hipErrorInvalidValue;
+    const dim3 grid((unsigned)n_tiles);
+    const size_t lds = ((size_t)1 << tile) * sizeof(float2);
+    switch (tile) {
+        case 10: hipLaunchKernelGGL(k_pass<10>, grid, dim3(1 << 6), lds, st, a); break;
+        case 11: hipLaunchKernelGGL(k_pass<11>, grid, dim3(1 << 7), lds, st, a); break;
+        case 12: hipLaunchKernelGGL(k_pass<12>, grid, dim3(1 << 8), lds, st, a); break;
+        case 13: hipLaunchKernelGGL(k_pass<13>, grid, dim3(1 << 9), lds, st, a); break;
+        case 14: hipLaunchKernelGGL(k_pass<14>, grid, dim3(1 << 10), lds, st, a); break;
+        default: return hipErrorInvalidValue;
+    }
+    return hipGetLastError();
+}
+
+hipError_t launch_naive_u(float2* state, int64_t rows, int n, int q, const float* mats,
+                          const float* ovr, int mat_id, int n_mats, int rowdep, const RowMap& rm,
+                          hipStream_t st) {
+    const u64 pairs = ((u64)rows << n) >> 1;
+    hipLaunchKernelGGL(k_naive_u, dim3(blocks_for(pairs, 256)), dim3(256), 0, st, state, pairs, n, q,
+                       mats, ovr, mat_id, n_mats, rowdep, rm);
+    return hipGetLastError();
+}
+
+hipError_t launch_naive_cnot(float2* state, int64_t rows, int n, int ctrl, int tgt, hipStream_t st) {
+    const u64 total = (u64)rows << n;
+    hipLaunchKernelGGL(k_naive_cnot, dim3(blocks_for(total, 256)), dim3(256), 0, st, state, total, ctrl,
+                       tgt);
+    return hipGetLastError();
+}
+
+hipError_t launch_naive_cz_ladder(float2* state, int64_t rows, int n, hipStream_t st) {
+    const u64 total = (u64)rows << n;
+    hipLaunchKernelGGL(k_naive_cz_ladder, dim3(blocks_for(total, 256)), dim3(256), 0, st, state, total,
+                       n);
+    return hipGetLastError();
+}
+
+hipError_t launch_build_mats(const CircDev& c, const float* params, const float* feats,
+                             int64_t samples, int inverse, float* out, hipStream_t st) {
+    const u64 count = (u64)(c.reupload ? samples : 1) * c.n_layers * c.n;
+    if (count == 0) return hipSuccess;
+    hipLaunchKernelGGL(k_build_mats, dim3(blocks_for(count, 256)), dim3(256), 0, st, c, params, feats,
+                       count, inverse, out);
+    return hipGetLastError();
+}
+
+hipError_t launch_build_shifted(const CircDev& c, const float* params, const float* feats,
+                                int64_t samples, float* out, hipStream_t st) {
+    const u64 two_p = 2ull * c.n_layers * c.slots() * c.n;
+    const u64 count = (u64)(c.reupload ? samples : 1) * two_p;
+    if (count == 0) return hipSuccess;
+    hipLaunchKernelGGL(k_build_shifted, dim3(blocks_for(count, 256)), dim3(256), 0, st, c, params,
+                       feats, count, out);
+    return hipGetLastError();
+}
+
+hipError_t launch_sumsq(const float* x, int64_t samples, int64_t dim, double* partial, int nblk,
+                        hipStream_t st) {
+    hipLaunchKernelGGL(k_sumsq, dim3(nblk, (unsigned)samples), dim3(256), 0, st, x, (u64)dim, partial,
+                       nblk);
+    return hipGetLastError();
+}
+
+hipError_t launch_norm_finish(const double* partial, int nblk, int64_t samples, double* inv_norm,
+                              float* norm_out, hipStream_t st) {
+    hipLaunchKernelGGL(k_norm_finish, dim3((unsigned)samples), dim3(256), 0, st, partial, nblk,
+                       inv_norm, norm_out);
+    return hipGetLastError();
+}
+
+hipError_t launch_encode_write(const float* x, int64_t dim, int n, int64_t rows, const double* inv_norm,
+                               const RowMap& rm, float2* state, hipStream_t st) {
+    const u64 total = (u64)rows << n;
+    hipLaunchKernelGGL(k_encode_write, dim3(blocks_for(total / 2, 256)), dim3(256), 0, st, x, (u64)dim,
+                       n, total, inv_norm, rm, state);
+    return hipGetLastError();
+}
+
+hipError_t launch_probs(const float2* state, uint64_t total, float* out, hipStream_t st) {
+    hipLaunchKernelGGL(k_probs, dim3(blocks_for(total / 2, 256)), dim3(256), 0, st, state, (u64)total,
+                       out);
+    return hipGetLastError();
+}
+
+static inline int chunk_blocks(int bits) { return bits > CHUNK_BITS ? 1 << (bits - CHUNK_BITS) : 1; }
+
+hipError_t launch_expz_block(const float2* state, int64_t rows, int n, double* partial, hipStream_t st) {
+    const int nblk = chunk_blocks(n);
+    hipLaunchKernelGGL(k_expz_block, dim3(nblk, (unsigned)rows), dim3(256), 0, st, state, n, nblk,
+                       partial);
+    return hipGetLastError();
+}
+
+hipError_t launch_expz_finish(const double* partial, int64_t rows, int n, int q_only, float* out_f,
+                              double* out_d, hipStream_t st) {
+    const u64 jobs = (u64)rows * (q_only >= 0 ? 1 : n);
+    hipLaunchKernelGGL(k_expz_finish, dim3(blocks_for(jobs, 4)), dim3(256), 0, st, partial, (u64)rows, n,
+                       chunk_blocks(n), q_only, out_f, out_d);
+    return hipGetLastError();
+}
+
+hipError_t launch_marginal_block(const float2* state, int64_t rows, int n, uint64_t mask, int64_t n_v,
+                                 double* partial, hipStream_t st) {
+    const int m = __builtin_popcountll(mask);
+    const u64 sub = 1ull << (n - m);
+    const u64 nblk = (u64)chunk_blocks(n - m);
+    const u64 blocks = (u64)rows * (u64)n_v * nblk;
+    if (blocks > 0x7fffffffull) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(k_marginal_block, dim3((unsigned)blocks), dim3(256), 0, st, state, n, (u64)mask,
+                       (u64)n_v, nblk, sub, partial);
+    return hipGetLastError();
+}
+
+hipError_t launch_marginal_finish(const double* partial, int64_t jobs, int64_t nblk, float* out,
+                                  int renorm_mode, double* scale, hipStream_t st) {
+    hipLaunchKernelGGL(k_marginal_finish, dim3(blocks_for((u64)jobs, 4)), dim3(256), 0, st, partial,
+                       (u64)jobs, (u64)nblk, out, renorm_mode, scale);
+    return hipGetLastError();
+}
+
+hipError_t launch_project(float2* state, int64_t rows, int n, uint64_t mask, const double* scale,
+                          hipStream_t st) {
+    const u64 total = (u64)rows << n;
+    hipLaunchKernelGGL(k_project, dim3(blocks_for(total, 256)), dim3(256), 0, st, state, total, n,
+                       (u64)mask, scale);
+    return hipGetLastError();
+}
+
+hipError_t launch_fidelity_block(const float2* state, int64_t rows, int n, const float* x, int64_t dim,
+                                 double* partial, int nblk, hipStream_t st) {
+    hipLaunchKernelGGL(k_fidelity_block, dim3(nblk, (unsigned)rows), dim3(256), 0, st, state, n, x,
+                       (u64)dim, nblk, partial);
+    return hipGetLastError();
+}
+
+hipError_t launch_fidelity_finish(const double* partial, int nblk, int64_t rows, float* out,
+                                  hipStream_t st) {
+    hipLaunchKernelGGL(k_fidelity_finish, dim3((unsigned)rows), dim3(256), 0, st, partial, nblk, out);
+    return hipGetLastError();
+}
+
+hipError_t launch_sample(const float2* state, int64_t rows, int n, const double* uniforms, int64_t shots,
+                         unsigned long long* cum, long long* out, hipStream_t st) {
+    const int nblk = chunk_blocks(n);
+    hipLaunchKernelGGL(k_sample_blocksum, dim3(nblk, (unsigned)rows), dim3(256), 0, st, state, n, nblk,
+                       cum);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(k_sample_scan, dim3((unsigned)rows), dim3(1024), 0, st, cum, nblk);
+    e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    const u64 jobs = (u64)rows * (u64)shots;
+    if (jobs == 0) return hipSuccess;
+    hipLaunchKernelGGL(k_sample_draw, dim3(blocks_for(jobs, 4)), dim3(256), 0, st, state, n, nblk, cum,
+                       uniforms, (u64)shots, jobs, out);
+    return hipGetLastError();
+}
+
+hipError_t launch_grad_finish(const double* f, int64_t B, int64_t P, const CircDev& c, const float* feats,
+                              float* loss, float* grad, float* mean_loss, float* mean_grad,
+                              hipStream_t st) {
+    hipLaunchKernelGGL(k_grad_finish, dim3(blocks_for((u64)B * (P + 1), 256)), dim3(256), 0, st, f,
+                       (u64)B, (u64)P, c, feats, loss, grad);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    if (mean_loss || mean_grad) {
+        hipLaunchKernelGGL(k_grad_mean, dim3(blocks_for((u64)P + 1, 256)), dim3(256), 0, st, f, (u64)B,
+                           (u64)P, c, feats, mean_loss, mean_grad);
+        e = hipGetLastError();
+    }
+    return e;
+}
+
+}  // namespace qsv

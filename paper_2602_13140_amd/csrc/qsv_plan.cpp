@@ -1,0 +1,319 @@
+// Pass planner (host only, no HIP).  See qsv_plan.h for the execution model.
+//
+// The circuit is first lowered to "fused-level" gates: per layer one 2x2 unitary U(l,q) per qubit
+// (the product of that qubit's re-upload and rotation-slot matrices, which commute with the other
+// qubits' rotations), followed by the entangler's CNOTs or CZ rungs in program order.  A greedy
+// list scheduler then packs those gates into passes and, inside a pass, into register rounds.
+// A gate may be moved ahead of earlier, not-yet-executed gates only if it shares no qubit with
+// them (disjoint gates commute); diagonal CZ rungs may additionally pass each other.
+#include "qsv_plan.h"
+
+#include <algorithm>
+#include <cstdio>
+
+namespace qsv {
+
+namespace {
+
+enum GateKind : uint8_t { G_U = 0, G_CNOT = 1, G_CZ = 2 };
+
+struct Gate {
+    uint8_t kind;
+    int8_t q0;   // U: qubit; CNOT: target; CZ: lower qubit of the rung
+    int8_t q1;   // CNOT: control; CZ: q0 + 1
+    int32_t mat; // U: matrix id l*n + q
+};
+
+struct Geom {
+    int t, c, w;
+    bool local(int q) const { return q < c || (q >= w && q < w + t - c); }
+    int pos(int q) const { return q < c ? q : q - w + c; }
+};
+
+// CNOTs form the sequential chain that decides how many passes a ring circuit needs, so chain
+// progress outweighs rotations that merely run early.
+constexpr int kScoreU = 2, kScoreCX = 16, kScoreCZ = 1;
+constexpr size_t kScanLimit = 8192;
+constexpr int kMinRoundGates = 2;
+
+std::vector<Gate> lower(const qsv_circuit& c, int n, bool inverse) {
+    std::vector<Gate> g;
+    const bool has_u = (c.reupload + c.n_rot) > 0;
+    auto layer_u = [&](int l) {
+        if (!has_u) return;
+        for (int q = 0; q < n; ++q) g.push_back({G_U, (int8_t)q, (int8_t)-1, l * n + q});
+    };
+    if (!inverse) {
+        for (int l = 0; l < c.n_layers; ++l) {
+            layer_u(l);
+            if (c.entangler == QSV_ENT_CNOT_RING && n >= 2)
+                for (int q = 0; q < n; ++q)
+                    g.push_back({G_CNOT, (int8_t)((q + 1) % n), (int8_t)q, -1});
+            if (c.entangler == QSV_ENT_CZ_LADDER)
+                for (int q = 0; q + 1 < n; ++q) g.push_back({G_CZ, (int8_t)q, (int8_t)(q + 1), -1});
+        }
+    } else {
+        for (int l = c.n_layers - 1; l >= 0; --l) {
+            if (c.entangler == QSV_ENT_CNOT_RING && n >= 2)
+                for (int q = n - 1; q >= 0; --q)
+                    g.push_back({G_CNOT, (int8_t)((q + 1) % n), (int8_t)q, -1});
+            if (c.entangler == QSV_ENT_CZ_LADDER)
+                for (int q = n - 2; q >= 0; --q) g.push_back({G_CZ, (int8_t)q, (int8_t)(q + 1), -1});
+            layer_u(l);  // the matrix table holds U(l,q)^dagger in inverse mode
+        }
+    }
+    return g;
+}
+
+// One register round: which pending gates can run with the run at tile position s.
+// Appends their indices to exec (program order) and returns the score.  Does not modify done.
+int scan_round(const Geom& gm, int s, int n, const std::vector<Gate>& G,
+               const std::vector<uint8_t>& done, size_t first, std::vector<int>* exec) {
+    uint64_t blk_any = 0, blk_diag = 0;
+    const uint64_t all = n >= 64 ? ~0ull : ((1ull << n) - 1);
+    int score = 0;
+    const size_t end = std::min(G.size(), first + kScanLimit);
+    auto in_run = [&](int q) {
+        if (!gm.local(q)) return false;
+        const int p = gm.pos(q);
+        return p >= s && p < s + kRegBits;
+    };
+    for (size_t i = first; i < end; ++i) {
+        if (done[i]) continue;
+        const Gate& g = G[i];
+        uint64_t m = 1ull << g.q0;
+        if (g.kind != G_U) m |= 1ull << g.q1;
+        bool can;
+        if (g.kind == G_CZ) {
+            can = !(blk_any & m);
+        } else {
+            can = !((blk_any | blk_diag) & m) && in_run(g.q0);
+        }
+        if (can) {
+            if (exec) exec->push_back((int)i);
+            score += g.kind == G_U ? kScoreU : g.kind == G_CNOT ? kScoreCX : kScoreCZ;
+        } else {
+            if (g.kind == G_CZ) blk_diag |= m; else blk_any |= m;
+            if (blk_any == all) break;
+        }
+    }
+    return score;
+}
+
+void emit_round(const Geom& gm, int s, const std::vector<Gate>& G, const std::vector<int>& exec,
+                bool rowdep, std::vector<Op>* ops) {
+    bool last_cz = false;
+    for (int i : exec) {
+        const Gate& g = G[i];
+        if (g.kind == G_CZ) {
+            if (last_cz) {
+                ops->back().arg |= (int32_t)(1u << g.q0);
+            } else {
+                ops->push_back({OP_CZ, 0, 0, 0, (int32_t)(1u << g.q0)});
+                last_cz = true;
+            }
+            continue;
+        }
+        last_cz = false;
+        const int jt = gm.pos(g.q0) - s;
+        if (g.kind == G_U) {
+            ops->push_back({OP_U, (uint8_t)jt, (uint8_t)(rowdep ? 1 : 0), 0, g.mat});
+            continue;
+        }
+        const int qc = g.q1;
+        if (gm.local(qc)) {
+            const int pc = gm.pos(qc);
+            if (pc >= s && pc < s + kRegBits) {
+                ops->push_back({OP_CX_REG, (uint8_t)jt, (uint8_t)(pc - s), 0, 0});
+            } else {
+                const int tbit = pc < s ? pc : pc - kRegBits;  // bit of the thread index
+                ops->push_back({OP_CX_DYN, (uint8_t)jt, (uint8_t)qc, (uint8_t)(tbit >= 6 ? 1 : 0), 0});
+            }
+        } else {
+            ops->push_back({OP_CX_DYN, (uint8_t)jt, (uint8_t)qc, 1, 0});
+        }
+    }
+}
+
+// Greedy rounds of one pass.  Marks executed gates in done; emits ops when ops != nullptr.
+// Returns the pass score; *n_exec receives the number of gates executed.
+int run_pass(const Geom& gm, int n, const std::vector<Gate>& G, std::vector<uint8_t>& done,
+             size_t first, bool rowdep, std::vector<Op>* ops, int* n_exec) {
+    const int smax = gm.t - kRegBits;
+    const int smin_io = std::min(kLowBits, smax);  // layouts with coalesced global access
+    // When one tile holds several state rows and matrices differ per row, a lane's 16 amplitudes
+    // must share a row: gate rounds keep the run inside the qubit bits.
+    const int sgate = (rowdep && n < gm.t) ? std::min(smax, n - kRegBits) : smax;
+    int total = 0, cnt = 0;
+    std::vector<int> exec, best_exec;
+    auto commit = [&](int s, const std::vector<int>& ex) {
+        for (int i : ex) done[i] = 1;
+        cnt += (int)ex.size();
+        if (ops) emit_round(gm, s, G, ex, rowdep, ops);
+        while (first < G.size() && done[first]) ++first;
+    };
+    // first round: loaded straight from global memory
+    int s = smax, best = 0;
+    best_exec.clear();
+    for (int cand = smin_io; cand <= sgate; ++cand) {
+        exec.clear();
+        const int sc = scan_round(gm, cand, n, G, done, first, &exec);
+        if (sc > best) { best = sc; s = cand; best_exec = exec; }
+    }
+    if (ops) ops->push_back({OP_LOAD, (uint8_t)s, 0, 0, 0});
+    total += best;
+    commit(s, best_exec);
+    for (;;) {
+        if (first >= G.size()) break;
+        int bs = -1;
+        best = 0;
+        for (int cand = 0; cand <= sgate; ++cand) {
+            if (cand == s) continue;
+            exec.clear();
+            const int sc = scan_round(gm, cand, n, G, done, first, &exec);
+            // ties go to the later (higher) layout, which also stores coalesced
+            if (sc > best || (sc == best && sc > 0 && cand >= smin_io)) {
+                best = sc; bs = cand; best_exec = exec;
+            }
+        }
+        if (bs < 0 || best == 0) break;
+        const bool critical = !best_exec.empty() && (size_t)best_exec.front() == first;
+        if (!critical && (int)best_exec.size() < kMinRoundGates) {
+            // A transpose for one stray gate is not worth it, unless going on like this finishes
+            // the whole circuit inside this pass (then it saves a pass over the state).
+            std::vector<uint8_t> tmp(done);
+            size_t f2 = first;
+            int s2 = s;
+            for (;;) {
+                int b2 = 0, bs2 = -1;
+                std::vector<int> ex2, bex2;
+                for (int cand = 0; cand <= sgate; ++cand) {
+                    if (cand == s2) continue;
+                    ex2.clear();
+                    const int sc = scan_round(gm, cand, n, G, tmp, f2, &ex2);
+                    if (sc > b2) { b2 = sc; bs2 = cand; bex2 = ex2; }
+                }
+                if (bs2 < 0) break;
+                for (int i : bex2) tmp[i] = 1;
+                while (f2 < G.size() && tmp[f2]) ++f2;
+                s2 = bs2;
+            }
+            if (f2 < G.size()) break;
+        }
+        s = bs;
+        if (ops) ops->push_back({OP_XPOSE, (uint8_t)s, 0, 0, 0});
+        total += best;
+        commit(s, best_exec);
+    }
+    if (s < smin_io) {
+        s = smax;
+        if (ops) ops->push_back({OP_XPOSE, (uint8_t)s, 0, 0, 0});
+    }
+    if (ops) ops->push_back({OP_END, 0, 0, 0, 0});
+    if (n_exec) *n_exec = cnt;
+    return total;
+}
+
+int ceil_log2(int64_t v) {
+    int b = 0;
+    while (((int64_t)1 << b) < v) ++b;
+    return b;
+}
+
+}  // namespace
+
+bool check_circuit(const qsv_circuit* c, int n, std::string* why) {
+    auto fail = [&](const char* m) { if (why) *why = m; return false; };
+    if (!c) return fail("circuit descriptor is NULL");
+    if (n < 1 || n > 30) return fail("n_qubits must be in 1..30");
+    if (c->n_layers < 0 || c->n_layers > 4096) return fail("n_layers must be in 0..4096");
+    if (c->reupload != 0 && c->reupload != 1) return fail("reupload must be 0 or 1");
+    if (c->n_rot < 0 || c->n_rot > 3) return fail("n_rot must be in 0..3");
+    for (int r = 0; r < c->n_rot; ++r)
+        if (c->rot[r] < QSV_RX || c->rot[r] > QSV_RZ) return fail("rotation axis must be 1..3");
+    if (c->entangler < QSV_ENT_NONE || c->entangler > QSV_ENT_CZ_LADDER)
+        return fail("entangler must be 0..2");
+    return true;
+}
+
+int default_tile(int n, int64_t batch) {
+    const int ext = n + ceil_log2(batch);
+    return std::max(kMinTile, std::min(13, ext));
+}
+
+Plan build_plan(const qsv_circuit& c, int n, int64_t batch, bool inverse, int tile_log2, bool grad) {
+    Plan p;
+    p.n = n;
+    p.ext_bits = n + ceil_log2(batch);
+    int t = tile_log2 > 0 ? tile_log2 : default_tile(n, batch);
+    t = std::max(kMinTile, std::min(kMaxTile, t));
+    p.tile = t;
+    const bool has_u = (c.reupload + c.n_rot) > 0;
+    p.n_mats = has_u ? c.n_layers * n : 0;
+    p.row_dependent = c.reupload != 0;
+    const bool rowdep = p.row_dependent || grad;
+
+    const std::vector<Gate> G = lower(c, n, inverse);
+    std::vector<uint8_t> done(G.size(), 0);
+    size_t first = 0;
+    const int cmin = std::min(kLowBits, t);
+    while (first < G.size()) {
+        Geom bestg{t, cmin, cmin};
+        int best = -1;
+        // local set = low c bits + window of t-c bits at w; c >= 4 keeps 128-byte runs contiguous
+        for (int cl = cmin; cl <= t; ++cl) {
+            const int win = t - cl;
+            const int wmax = (win > 0 && n > t) ? n - win : cl;
+            for (int w = cl; w <= wmax; ++w) {
+                if (w == cl && cl != cmin && n > t) continue;  // same set as (cmin, w = cmin)
+                Geom gm{t, cl, w};
+                std::vector<uint8_t> tmp(done);
+                int ne = 0;
+                const int sc = run_pass(gm, n, G, tmp, first, rowdep, nullptr, &ne);
+                if (sc > best) { best = sc; bestg = gm; }
+            }
+            if (n <= t) break;  // the whole state row is local: one geometry
+        }
+        Pass ps;
+        ps.t = bestg.t; ps.c = bestg.c; ps.w = bestg.w;
+        ps.op_begin = (int)p.ops.size();
+        int ne = 0;
+        run_pass(bestg, n, G, done, first, rowdep, &p.ops, &ne);
+        ps.op_count = (int)p.ops.size() - ps.op_begin;
+        ps.n_gates = ne;
+        p.passes.push_back(ps);
+        if (ne == 0) { p.complete = false; break; }  // cannot happen: the first pending gate always fits some window
+        while (first < G.size() && done[first]) ++first;
+    }
+    return p;
+}
+
+std::string describe_plan(const Plan& p) {
+    std::string s;
+    char buf[96];
+    snprintf(buf, sizeof buf, "plan n=%d ext=%d tile=%d mats=%d rowdep=%d passes=%d\n", p.n,
+             p.ext_bits, p.tile, p.n_mats, p.row_dependent ? 1 : 0, (int)p.passes.size());
+    s += buf;
+    for (const Pass& ps : p.passes) {
+        snprintf(buf, sizeof buf, "P t=%d c=%d w=%d gates=%d :", ps.t, ps.c, ps.w, ps.n_gates);
+        s += buf;
+        for (int i = ps.op_begin; i < ps.op_begin + ps.op_count; ++i) {
+            const Op& o = p.ops[i];
+            switch (o.kind) {
+                case OP_END: snprintf(buf, sizeof buf, " E"); break;
+                case OP_LOAD: snprintf(buf, sizeof buf, " L%d", o.a); break;
+                case OP_XPOSE: snprintf(buf, sizeof buf, " T%d", o.a); break;
+                case OP_U: snprintf(buf, sizeof buf, " U%d:%d:%d", o.a, o.arg, o.b); break;
+                case OP_CX_REG: snprintf(buf, sizeof buf, " X%d:%d", o.a, o.b); break;
+                case OP_CX_DYN: snprintf(buf, sizeof buf, " D%d:%d:%d", o.a, o.b, o.c); break;
+                case OP_CZ: snprintf(buf, sizeof buf, " Z%x", (unsigned)o.arg); break;
+                default: snprintf(buf, sizeof buf, " ?"); break;
+            }
+            s += buf;
+        }
+        s += "\n";
+    }
+    return s;
+}
+
+}  // namespace qsv

@@ -1,0 +1,69 @@
+// Host-side pass planner: turns a layered circuit into a list of fused passes over the state.
+//
+// A pass streams the whole state once (read + write).  Each workgroup owns one tile of 2^t
+// amplitudes whose "local" index bits are the low c bits plus a window of t-c bits starting at
+// bit w; every other index bit is constant inside the tile.  Inside a pass the tile lives in
+// registers: each lane holds 2^R amplitudes spanning a run of R consecutive tile-local bit
+// positions, applies every gate whose target sits in that run, and the run is moved by a
+// transpose through LDS.  The planner emits, per pass, the operation list the kernel interprets.
+#pragma once
+#include <cstdint>
+#include <string>
+#include <vector>
+
+#include "qsv.h"
+
+namespace qsv {
+
+constexpr int kRegBits = 4;      // R: amplitudes per lane = 2^R
+constexpr int kMinTile = 10;     // 64 lanes x 16 amplitudes
+constexpr int kMaxTile = 14;     // 2^14 complex64 = 128 KiB of LDS
+constexpr int kLowBits = 4;      // c: 2^4 complex64 = one 128-byte line per contiguous run
+
+enum OpKind : uint8_t {
+    OP_END = 0,     // store the tile from the current layout
+    OP_LOAD = 1,    // a = run start s: load the tile from global memory in layout s
+    OP_XPOSE = 2,   // a = new run start: move the register run through LDS
+    OP_U = 3,       // a = register bit j, b = 1 if the matrix depends on the state row, arg = matrix id
+    OP_CX_REG = 4,  // a = target register bit, b = control register bit
+    OP_CX_DYN = 5,  // a = target register bit, b = control index bit (extended index),
+                    // c = 1 if the control bit is the same for a whole wavefront
+    OP_CZ = 6       // arg = rung mask: bit q set -> CZ(q, q+1)
+};
+
+struct Op {
+    uint8_t kind, a, b, c;
+    int32_t arg;
+};
+static_assert(sizeof(Op) == 8, "Op must be 8 bytes");
+
+struct Pass {
+    int t, c, w;        // tile bits, low bits, window start (extended index bit)
+    int op_begin;       // first op in Plan::ops
+    int op_count;
+    int n_gates;        // circuit gates (fused level) executed by this pass
+};
+
+struct Plan {
+    int n = 0;          // qubits
+    int ext_bits = 0;   // n + ceil(log2(batch)): bits of the extended index b*2^n + k
+    int tile = 0;       // t used by every pass
+    int n_mats = 0;     // matrices per state row: n_layers * n (0 if the circuit has no rotations)
+    bool row_dependent = false;  // matrices differ per sample (re-upload)
+    bool complete = true;        // false only on an internal scheduling failure
+    std::vector<Pass> passes;
+    std::vector<Op> ops;
+};
+
+// Validates a circuit descriptor; returns false and fills why on failure.
+bool check_circuit(const qsv_circuit* c, int n, std::string* why);
+
+// tile_log2 = 0 picks the default.  grad = true marks every rotation matrix as row-dependent
+// (a shifted circuit overrides one matrix per state row).
+Plan build_plan(const qsv_circuit& c, int n, int64_t batch, bool inverse, int tile_log2, bool grad);
+
+std::string describe_plan(const Plan& p);
+
+int default_tile(int n, int64_t batch);
+
+}  // namespace qsv

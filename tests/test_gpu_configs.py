@@ -1,0 +1,143 @@
+"""GPU parity at the five workload configs' full sizes, in the launch configuration bench.py
+times (default tile, fused passes).  Where the oracle cannot finish the whole output in a test's
+time (config 2's 164 096 circuits) sampled outputs are compared one by one."""
+import numpy as np
+import pytest
+
+from paper_2602_13140_amd import binding as qb
+from paper_2602_13140_amd import workloads as wl
+from tests import gpu_util as gu
+
+pytestmark = pytest.mark.gpu
+
+
+def ocirc(oracle, spec):
+    return oracle.make_circuit(spec.n_layers, list(spec.rot), spec.entangler, spec.reupload)
+
+
+def test_config0_autoencoder_roundtrip(oracle):
+    w = wl.config(0)
+    ctx = gu.make_ctx(w.n, w.batch)
+    circ = qb.circuit_from_spec(w.circuit)
+    xd, pd = gu.dev(w.x), gu.dev(w.params)
+    ctx.qsv_amp_encode(xd)
+    ctx.qsv_apply_layers(circ, pd, None, 0)
+    mid = gu.state_np(ctx)
+    ref, _ = oracle.amp_encode(w.x, w.n)
+    oracle.apply_layers(ref, ocirc(oracle, w.circuit), w.params)
+    assert np.abs(mid - ref).max() <= 2e-6
+    ctx.qsv_apply_layers(circ, pd, None, 1)
+    p = gu.measure(ctx, qb.QSV_M_PROBS, (w.batch, 1 << w.n))
+    oracle.apply_layers(ref, ocirc(oracle, w.circuit), w.params, inverse=True)
+    gu.prob_checks(p, oracle.probs(ref))
+    xd64 = w.x.astype(np.float64)
+    assert np.abs(p - xd64 ** 2 / (xd64 ** 2).sum(1, keepdims=True)).max() <= 1e-5   # closed form
+    ctx.close()
+
+
+def test_config1_reupload_expz(oracle):
+    w = wl.config(1)
+    ctx = gu.make_ctx(w.n, w.batch)
+    ctx.qsv_amp_encode(gu.dev(w.x))
+    ctx.qsv_apply_layers(qb.circuit_from_spec(w.circuit), gu.dev(w.params), gu.dev(w.feats), 0)
+    z = gu.measure(ctx, qb.QSV_M_EXPZ_ALL, (w.batch, w.n))
+    ref, _ = oracle.amp_encode(w.x, w.n)
+    oracle.apply_layers(ref, ocirc(oracle, w.circuit), w.params, w.feats)
+    assert np.abs(z - oracle.expz_all(ref)).max() <= 1e-5
+    assert np.abs(gu.state_np(ctx) - ref).max() <= 1e-5
+    ctx.close()
+
+
+@pytest.mark.parametrize("rot", [(wl.RY, wl.RZ), (wl.RX, wl.RY, wl.RZ)])
+def test_config2_gradient_sampled(oracle, rot):
+    """Full 256 x P gradient on the GPU; the oracle recomputes two samples x 12 random parameters
+    (plus their losses).  The second variant is the 3-rotation reading that gives ~480 params."""
+    torch = gu.torch_cuda()
+    w = wl.config(2)
+    spec = wl.CircuitSpec(w.circuit.n_layers, rot, w.circuit.entangler)
+    P = spec.num_params(w.n)
+    params = wl.draw_params(spec, w.n, 2002)
+    ctx = gu.make_ctx(w.n, w.batch)
+    loss = torch.zeros(w.batch, dtype=torch.float32, device="cuda")
+    grad = torch.zeros((w.batch, P), dtype=torch.float32, device="cuda")
+    mg = torch.zeros(P, dtype=torch.float32, device="cuda")
+    ctx.qsv_param_shift_grad(qb.circuit_from_spec(spec), gu.dev(w.x), gu.dev(params), None, 0, loss,
+                             grad, None, mg)
+    torch.cuda.synchronize()
+    gg, ll = grad.cpu().numpy(), loss.cpu().numpy()
+    g = np.random.Generator(np.random.PCG64(5))
+    rows = sorted(g.choice(w.batch, 2, replace=False).tolist())
+    sub = sorted(g.choice(P, 12, replace=False).tolist()) + [0, P - 1]
+    lref, gref = oracle.param_shift_grad(w.x[rows], w.n, ocirc(oracle, spec), params, None, 0, subset=sub)
+    assert np.abs(ll[rows] - lref).max() <= 1e-5
+    assert np.abs(gg[rows][:, sub] - gref).max() <= 1e-4
+    assert np.linalg.norm(gg[rows][:, sub] - gref) <= 1e-3 * np.linalg.norm(gref)
+    assert np.abs(mg.cpu().numpy() - gg.astype(np.float64).mean(0)).max() <= 1e-6
+    assert np.all(np.abs(gg) <= 1.0) and np.all(np.abs(ll) <= 1.0)
+    ctx.close()
+
+
+def test_config3_autoencoder_full(oracle, capsys):
+    w = wl.config(3)
+    n, B = w.n, w.batch
+    ctx = gu.make_ctx(n, B)
+    circ = qb.circuit_from_spec(w.circuit)
+    xd, pd = gu.dev(w.x), gu.dev(w.params)
+    ctx.qsv_amp_encode(xd)
+    ctx.qsv_apply_layers(circ, pd, None, 0)
+    m = bin(w.trash_mask).count("1")
+    marg = gu.measure(ctx, qb.QSV_M_MARGINAL, (B, 1 << m), mask=w.trash_mask)
+    p0 = gu.measure(ctx, qb.QSV_M_PROJECT_ZERO, (B,), mask=w.trash_mask, renormalise=1)
+    ctx.qsv_apply_layers(circ, pd, None, 1)
+    F = gu.measure(ctx, qb.QSV_M_FIDELITY, (B,), x=xd)
+    final = gu.state_np(ctx)
+    oc = ocirc(oracle, w.circuit)
+    ref, _ = oracle.amp_encode(w.x, n)
+    oracle.apply_layers(ref, oc, w.params)
+    with capsys.disabled():
+        print(" [c3 oracle encoder done]", end="", flush=True)
+    mref = oracle.marginal(ref, w.trash_mask)
+    p0ref = oracle.project_zero(ref, w.trash_mask, renormalise=True)
+    oracle.apply_layers(ref, oc, w.params, inverse=True)
+    Fref = oracle.fidelity(ref, w.x)
+    assert np.abs(marg - mref).max() <= 1e-5
+    assert np.abs(p0 - p0ref).max() <= 1e-5
+    assert np.abs(F - Fref).max() <= 1e-5
+    assert np.abs(F - p0).max() <= 1e-5                     # invariant: F = P0 after renormalising
+    d = np.abs(final - ref)
+    assert d.max() <= 1e-5
+    assert (d ** 2).sum(1).max() <= 1e-9                    # relative l2 error of the final state
+    ctx.close()
+
+
+def test_config4_full(oracle, capsys):
+    torch = gu.torch_cuda()
+    w = wl.config(4)
+    n = w.n
+    ctx = gu.make_ctx(n, 1)
+    circ = qb.circuit_from_spec(w.circuit)
+    xd, pd = gu.dev(w.x), gu.dev(w.params)
+    ctx.qsv_amp_encode(xd)
+    ctx.qsv_apply_layers(circ, pd, None, 0)
+    p32 = gu.measure(ctx, qb.QSV_M_PROBS, (1, 1 << n))
+    s = gu.measure(ctx, qb.QSV_M_SAMPLE, (1, w.uniforms.shape[1]), dtype="int64", uniforms=gu.dev(w.uniforms))
+    assert abs(p32.astype(np.float64).sum() - 1.0) <= 1e-5
+    assert np.array_equal(s, oracle.sample(p32, w.uniforms))        # bit-exact sampling
+    # oracle, five layers at a time so that the run keeps reporting progress
+    ref, _ = oracle.amp_encode(w.x, n)
+    per = w.circuit.slots() * n
+    for l0 in range(0, w.circuit.n_layers, 5):
+        sub = oracle.make_circuit(5, list(w.circuit.rot), w.circuit.entangler, 0)
+        oracle.apply_layers(ref, sub, w.params[l0 * per:(l0 + 5) * per])
+        with capsys.disabled():
+            print(" [c4 oracle layer %d]" % (l0 + 5), end="", flush=True)
+    pref = oracle.probs(ref)
+    gu.prob_checks(p32, pref)
+    d = np.abs(gu.state_np(ctx) - ref)
+    assert d.max() <= 1e-5 and (d ** 2).sum() <= 1e-9
+    del ref, pref, d
+    # the inverse brings the state back to the encoded input
+    ctx.qsv_apply_layers(circ, pd, None, 1)
+    F = gu.measure(ctx, qb.QSV_M_FIDELITY, (1,), x=xd)
+    assert abs(F[0] - 1.0) <= 1e-5
+    ctx.close()

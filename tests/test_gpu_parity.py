@@ -1,0 +1,262 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU oracle on the same seeded
+inputs.  Tolerances are the benchmark spec's: 1e-5 absolute on probabilities/expectations, 1e-4 on
+gradients, sampling bit-exact given the same uniforms; relative checks are added where absolute
+ones would be vacuous (tiny probabilities at large n)."""
+import numpy as np
+import pytest
+
+from paper_2602_13140_amd import binding as qb
+from paper_2602_13140_amd import workloads as wl
+from tests import gpu_util as gu
+
+pytestmark = pytest.mark.gpu
+
+RX, RY, RZ = 1, 2, 3
+NONE, RING, LADDER = 0, 1, 2
+
+
+def rng(seed):
+    return np.random.Generator(np.random.PCG64(seed))
+
+
+def ocirc(oracle, spec):
+    return oracle.make_circuit(spec.n_layers, list(spec.rot), spec.entangler, spec.reupload)
+
+
+def amp_tol(n):
+    # amplitudes are O(2^-n/2); float32 rounding through a few hundred gates stays far below this
+    return 2e-5
+
+
+# ------------------------------------------------------------------ encoding
+@pytest.mark.parametrize("n,B,dim", [(1, 3, 2), (3, 5, 8), (4, 64, 16), (6, 3, 37), (10, 7, 1024),
+                                     (12, 2, 4095), (13, 3, 8192), (16, 2, 1), (18, 1, 200001)])
+def test_amp_encode(oracle, n, B, dim):
+    torch = gu.torch_cuda()
+    x = rng(n * 100 + B).standard_normal((B, dim)).astype(np.float32)
+    if B > 1:
+        x[1] *= 1e-3
+    ref, nrm = oracle.amp_encode(x, n)
+    ctx = gu.make_ctx(n, B)
+    ctx.state.fill_(9.0)
+    norm_out = torch.zeros(B, dtype=torch.float32, device="cuda")
+    ctx.qsv_amp_encode(gu.dev(x), norm_out)
+    got = gu.state_np(ctx)
+    assert np.all(got.imag == 0)
+    assert np.allclose(got.real, ref.real, rtol=3e-7, atol=1e-12)
+    assert np.allclose(norm_out.cpu().numpy(), nrm, rtol=2e-7)
+    ctx.close()
+
+
+def test_amp_encode_zero_vector_gives_zero_state():
+    torch = gu.torch_cuda()
+    x = np.ones((3, 16), dtype=np.float32)
+    x[1] = 0
+    ctx = gu.make_ctx(4, 3)
+    norm_out = torch.ones(3, dtype=torch.float32, device="cuda")
+    ctx.qsv_amp_encode(gu.dev(x), norm_out)
+    got = gu.state_np(ctx)
+    assert np.all(got[1] == 0) and not np.isnan(got).any()
+    assert norm_out.cpu().numpy()[1] == 0.0
+    p = gu.measure(ctx, qb.QSV_M_PROBS, (3, 16))
+    assert np.all(p[1] == 0)
+    ctx.close()
+
+
+# ------------------------------------------------------------------ circuits, all tile paths
+SMALL = [
+    # n, B, L, rot, ent, reup
+    (1, 3, 2, (RX, RY, RZ), RING, 0), (2, 5, 2, (RY, RZ), RING, 0), (3, 4, 2, (RY, RZ), LADDER, 1),
+    (4, 64, 2, (RY, RZ), RING, 0), (5, 3, 3, (RX, RY, RZ), RING, 0), (6, 9, 2, (RY, RZ), RING, 1),
+    (7, 2, 3, (RY, RZ), LADDER, 0), (9, 5, 2, (RY, RZ), RING, 1), (10, 6, 3, (RY, RZ), RING, 1),
+    (11, 3, 3, (RX, RY, RZ), RING, 0), (12, 2, 3, (RY, RZ), LADDER, 0), (13, 2, 2, (), RING, 0),
+    (13, 3, 3, (RY, RZ), RING, 0), (14, 1, 3, (RZ, RX), NONE, 0),
+]
+
+
+@pytest.mark.parametrize("n,B,L,rot,ent,reup", SMALL)
+@pytest.mark.parametrize("mode", ["default", "t10", "t11", "t12", "t13", "t14", "naive"])
+def test_apply_layers_small(oracle, n, B, L, rot, ent, reup, mode):
+    g = rng(31 * n + B + L)
+    spec = wl.CircuitSpec(L, tuple(rot), ent, reup)
+    params = wl.draw_params(spec, n, 77 + n)
+    x = g.standard_normal((B, 1 << n)).astype(np.float32)
+    feats = g.standard_normal((B, n)).astype(np.float32) if reup else None
+    oc = ocirc(oracle, spec)
+    ctx = gu.make_ctx(n, B, tile=int(mode[1:]) if mode.startswith("t") else 0,
+                      naive=1 if mode == "naive" else 0)
+    circ = qb.circuit_from_spec(spec)
+    xd, pd = gu.dev(x), gu.dev(params)
+    fd = gu.dev(feats) if reup else None
+    for inverse in (0, 1):
+        ref, _ = oracle.amp_encode(x, n)
+        oracle.apply_layers(ref, oc, params, feats, inverse=bool(inverse))
+        ctx.qsv_amp_encode(xd)
+        ctx.qsv_apply_layers(circ, pd, fd, inverse)
+        got = gu.state_np(ctx)
+        assert np.abs(got - ref).max() <= amp_tol(n), (inverse, np.abs(got - ref).max())
+        gu.prob_checks(np.abs(got) ** 2, oracle.probs(ref))
+    # encoder then decoder returns the encoded state
+    start, _ = oracle.amp_encode(x, n)
+    ctx.qsv_amp_encode(xd)
+    ctx.qsv_apply_layers(circ, pd, fd, 0)
+    ctx.qsv_apply_layers(circ, pd, fd, 1)
+    assert np.abs(gu.state_np(ctx) - start).max() <= amp_tol(n)
+    ctx.close()
+
+
+# ------------------------------------------------------------------ measurement
+def prepared(oracle, n, B, seed, reup=0, ent=RING):
+    g = rng(seed)
+    spec = wl.CircuitSpec(2, (RY, RZ), ent, reup)
+    params = wl.draw_params(spec, n, seed + 1)
+    x = g.standard_normal((B, 1 << n)).astype(np.float32)
+    feats = g.standard_normal((B, n)).astype(np.float32) if reup else None
+    ref, _ = oracle.amp_encode(x, n)
+    oracle.apply_layers(ref, ocirc(oracle, spec), params, feats)
+    ctx = gu.make_ctx(n, B)
+    ctx.qsv_amp_encode(gu.dev(x))
+    ctx.qsv_apply_layers(qb.circuit_from_spec(spec), gu.dev(params), gu.dev(feats) if reup else None, 0)
+    return ctx, ref, x
+
+
+@pytest.mark.parametrize("n,B", [(1, 2), (3, 5), (6, 4), (10, 9), (12, 3), (13, 2), (15, 3), (17, 1)])
+def test_probs_and_expz(oracle, n, B):
+    ctx, ref, _ = prepared(oracle, n, B, 500 + n)
+    p = gu.measure(ctx, qb.QSV_M_PROBS, (B, 1 << n))
+    gu.prob_checks(p, oracle.probs(ref))
+    assert abs(p.astype(np.float64).sum(1) - 1).max() <= 1e-5          # norm preservation
+    z = gu.measure(ctx, qb.QSV_M_EXPZ_ALL, (B, n))
+    zr = oracle.expz_all(ref)
+    assert np.abs(z - zr).max() <= 1e-5
+    for q in sorted({0, n // 2, n - 1}):
+        z1 = gu.measure(ctx, qb.QSV_M_EXPZ_ONE, (B,), qubit=q)
+        assert np.abs(z1 - zr[:, q]).max() <= 1e-5
+    ctx.close()
+
+
+@pytest.mark.parametrize("n,B,mask", [(4, 3, 0b1000), (6, 4, 0b110000), (6, 4, 0b101010), (6, 2, 0b111111),
+                                      (10, 5, 0b1111000000), (13, 2, 0b11), (14, 2, 0b11110000000000),
+                                      (16, 2, 0b1111 << 12), (16, 1, 0b1000000000000001)])
+def test_marginal_project_fidelity(oracle, n, B, mask):
+    ctx, ref, x = prepared(oracle, n, B, 600 + n)
+    m = bin(mask).count("1")
+    marg = gu.measure(ctx, qb.QSV_M_MARGINAL, (B, 1 << m), mask=mask)
+    mref = oracle.marginal(ref, mask)
+    assert np.abs(marg - mref).max() <= 1e-5
+    xd = gu.dev(x)
+    for renorm in (1, 0):
+        ctx2, ref2, _ = prepared(oracle, n, B, 600 + n)
+        p0 = gu.measure(ctx2, qb.QSV_M_PROJECT_ZERO, (B,), mask=mask, renormalise=renorm)
+        p0ref = oracle.project_zero(ref2, mask, renormalise=bool(renorm))
+        assert np.abs(p0 - p0ref).max() <= 1e-5
+        got = gu.state_np(ctx2)
+        assert np.abs(got - ref2).max() <= 1e-5
+        assert np.all(got[:, (np.arange(1 << n) & mask) != 0] == 0)
+        F = gu.measure(ctx2, qb.QSV_M_FIDELITY, (B,), x=xd)
+        assert np.abs(F - oracle.fidelity(ref2, x)).max() <= 1e-5
+        ctx2.close()
+    ctx.close()
+
+
+def test_fidelity_ragged_dim(oracle):
+    n, B, dim = 9, 3, 300
+    g = rng(71)
+    x = g.standard_normal((B, dim)).astype(np.float32)
+    ctx, ref, _ = prepared(oracle, n, B, 72)
+    F = gu.measure(ctx, qb.QSV_M_FIDELITY, (B,), x=gu.dev(x))
+    assert np.abs(F - oracle.fidelity(ref, x)).max() <= 1e-5
+    ctx.close()
+
+
+# ------------------------------------------------------------------ sampling (bit-exact)
+@pytest.mark.parametrize("n,B,shots", [(2, 3, 50), (8, 2, 300), (12, 3, 257), (13, 2, 100), (16, 1, 1000),
+                                       (18, 2, 64)])
+def test_sampling_bit_exact(oracle, n, B, shots):
+    ctx, ref, _ = prepared(oracle, n, B, 800 + n)
+    u = rng(900 + n).random((B, shots))
+    u[0, 0] = 0.0
+    u[0, 1] = np.nextafter(1.0, 0.0)
+    s = gu.measure(ctx, qb.QSV_M_SAMPLE, (B, shots), dtype="int64", uniforms=gu.dev(u))
+    p32 = gu.measure(ctx, qb.QSV_M_PROBS, (B, 1 << n))
+    assert np.array_equal(s, oracle.sample(p32, u))            # same p32, same uniforms -> same shots
+    # and the shots are plausible for the oracle's own probabilities
+    pref = oracle.probs(ref)
+    assert np.all(np.take_along_axis(pref, s, axis=1) > 0)
+    ctx.close()
+
+
+def test_sampling_special_states():
+    torch = gu.torch_cuda()
+    n = 13
+    ctx = gu.make_ctx(n, 3)
+    ctx.state.zero_()
+    ctx.state[0, :, 0] = 2.0 ** (-n / 2)       # uniform: sample = floor(u * 2^n)
+    ctx.state[1, 4999, 1] = 1.0                # basis state
+    u = rng(5).random((3, 200))               # row 2 stays all-zero: -1
+    s = gu.measure(ctx, qb.QSV_M_SAMPLE, (3, 200), dtype="int64", uniforms=gu.dev(u))
+    assert np.array_equal(s[0], np.floor(u[0] * (1 << n)).astype(np.int64))
+    assert np.all(s[1] == 4999) and np.all(s[2] == -1)
+    ctx.close()
+
+
+# ------------------------------------------------------------------ parameter-shift gradient
+@pytest.mark.parametrize("n,B,L,rot,ent,reup,obs", [
+    (2, 3, 2, (RY, RZ), RING, 0, 1), (4, 5, 2, (RY, RZ), LADDER, 0, 0), (5, 3, 2, (RX, RY, RZ), RING, 0, 2),
+    (6, 4, 2, (RY, RZ), RING, 1, 0), (10, 2, 2, (RY, RZ), LADDER, 0, 0), (12, 2, 1, (RY, RZ), RING, 1, 3),
+    (13, 1, 2, (RY,), LADDER, 0, 0)])
+@pytest.mark.parametrize("mode", ["default", "naive"])
+def test_param_shift_grad_small(oracle, n, B, L, rot, ent, reup, obs, mode):
+    torch = gu.torch_cuda()
+    g = rng(40 + n)
+    spec = wl.CircuitSpec(L, tuple(rot), ent, reup)
+    P = spec.num_params(n)
+    params = wl.draw_params(spec, n, 41 + n)
+    x = g.standard_normal((B, 1 << n)).astype(np.float32)
+    feats = g.standard_normal((B, n)).astype(np.float32) if reup else None
+    lref, gref = oracle.param_shift_grad(x, n, ocirc(oracle, spec), params, feats, obs_qubit=obs)
+    ctx = gu.make_ctx(n, B, naive=1 if mode == "naive" else 0)
+    ctx.state.fill_(3.0)
+    loss = torch.zeros(B, dtype=torch.float32, device="cuda")
+    grad = torch.zeros((B, P), dtype=torch.float32, device="cuda")
+    ml = torch.zeros(1, dtype=torch.float32, device="cuda")
+    mg = torch.zeros(P, dtype=torch.float32, device="cuda")
+    ctx.qsv_param_shift_grad(qb.circuit_from_spec(spec), gu.dev(x), gu.dev(params),
+                             gu.dev(feats) if reup else None, obs, loss, grad, ml, mg)
+    torch.cuda.synchronize()
+    assert np.abs(loss.cpu().numpy() - lref).max() <= 1e-5
+    gg = grad.cpu().numpy()
+    assert np.abs(gg - gref).max() <= 1e-4
+    assert np.linalg.norm(gg - gref) <= 1e-3 * np.linalg.norm(gref)
+    assert abs(ml.item() - lref.mean()) <= 1e-5
+    assert np.abs(mg.cpu().numpy() - gref.mean(0)).max() <= 1e-4
+    assert torch.all(ctx.state == 3.0)             # the context's own state is left untouched
+    ctx.close()
+
+
+# ------------------------------------------------------------------ error paths (host-detected)
+def test_argument_errors():
+    torch = gu.torch_cuda()
+    ctx = gu.make_ctx(5, 2)
+    x = torch.zeros((2, 32), dtype=torch.float32, device="cuda")
+    out = torch.zeros((2, 32), dtype=torch.float32, device="cuda")
+    circ = qb.make_circuit(1, [RY], RING, 1)
+    with pytest.raises(qb.QsvError) as e:
+        ctx.qsv_apply_layers(circ, x, None, 0)          # re-upload without feats
+    assert e.value.status == qb.QSV_ERR_INVALID_ARG
+    with pytest.raises(qb.QsvError):
+        ctx.qsv_apply_layers(qb.make_circuit(1, [9], RING), x, None, 0)
+    with pytest.raises(qb.QsvError):
+        ctx.qsv_measure(qb.QSV_M_MARGINAL, out, mask=0)
+    with pytest.raises(qb.QsvError):
+        ctx.qsv_measure(qb.QSV_M_MARGINAL, out, mask=1 << 5)
+    with pytest.raises(qb.QsvError):
+        ctx.qsv_measure(qb.QSV_M_EXPZ_ONE, out, qubit=5)
+    with pytest.raises(qb.QsvError):
+        ctx.qsv_measure(99, out)
+    big = torch.zeros((2, 33), dtype=torch.float32, device="cuda")
+    with pytest.raises(qb.QsvError):
+        ctx.qsv_amp_encode(big)                          # dim > 2^n
+    with pytest.raises(qb.QsvError):
+        ctx.qsv_set_option("tile_log2", 9)
+    ctx.close()

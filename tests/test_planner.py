@@ -1,0 +1,179 @@
+"""Host-logic tests (no GPU): the pass planner's operation lists, replayed by a small numpy
+interpreter that follows the documented meaning of each operation, must reproduce the oracle's
+circuit.  This checks the lowering, the commutation rules and the tile/run bookkeeping before any
+kernel runs."""
+import numpy as np
+import pytest
+
+from paper_2602_13140_amd import binding as qb
+from tests import dense_bruteforce as dense
+
+RX, RY, RZ = 1, 2, 3
+NONE, RING, LADDER = 0, 1, 2
+R = 4
+
+
+def parse_plan(text):
+    lines = text.strip().split("\n")
+    head = dict(kv.split("=") for kv in lines[0].split()[1:])
+    passes = []
+    for ln in lines[1:]:
+        hdr, ops = ln.split(":", 1)
+        kv = dict(x.split("=") for x in hdr.split()[1:])
+        passes.append(({k: int(v) for k, v in kv.items()}, ops.split()))
+    return {k: int(v) for k, v in head.items()}, passes
+
+
+def fused_matrix(rot, reupload, layer_params, feat_q, q, inverse):
+    """U(l,q) = R_last ... R_first (re-upload RX first); dagger in inverse mode."""
+    u = np.eye(2, dtype=np.complex128)
+    slot = 0
+    if reupload:
+        u = dense.rot_matrix(RX, layer_params[0][q] * feat_q) @ u
+        slot = 1
+    for r, axis in enumerate(rot):
+        u = dense.rot_matrix(axis, layer_params[slot + r][q]) @ u
+    return u.conj().T if inverse else u
+
+
+def apply_1q(st, n, q, mats):
+    """st: [rows, 2^n]; mats: [rows, 2, 2] or [2, 2]."""
+    rows = st.shape[0]
+    v = st.reshape(rows, 1 << (n - 1 - q), 2, 1 << q)
+    if mats.ndim == 2:
+        out = np.einsum("ab,rhbl->rhal", mats, v)
+    else:
+        out = np.einsum("rab,rhbl->rhal", mats, v)
+    return out.reshape(rows, 1 << n)
+
+
+def apply_cnot(st, n, ctrl, tgt):
+    k = np.arange(1 << n)
+    src = np.where((k >> ctrl) & 1, k ^ (1 << tgt), k)
+    return st[:, src]
+
+
+def replay(text, n, rows, L, rot, ent, reupload, params, feats, inverse, st):
+    head, passes = parse_plan(text)
+    assert head["n"] == n
+    slots = int(reupload) + len(rot)
+    p = np.asarray(params, dtype=np.float64).reshape(L, slots, n)
+    n_gates = 0
+    for hdr, ops in passes:
+        t, c, w = hdr["t"], hdr["c"], hdr["w"]
+        assert 10 <= t <= 14 and 4 <= c <= t and w >= c
+        bit = lambda pos: pos if pos < c else pos - c + w
+        if n > t:
+            assert w + (t - c) <= n
+        assert ops[0][0] == "L" and ops[-1] == "E"
+        s = None
+        for tok in ops:
+            kind = tok[0]
+            if kind in "LT":
+                s = int(tok[1:])
+                assert 0 <= s <= t - R
+                if kind == "L":
+                    assert s >= min(4, t - R)
+            elif kind == "U":
+                j, mat, rowdep = (int(x) for x in tok[1:].split(":"))
+                q = bit(s + j)
+                assert q < n and 0 <= j < R
+                l = mat // n
+                assert mat % n == q
+                if reupload:
+                    assert rowdep == 1
+                    if n < t:
+                        assert s + R <= n      # a lane's 16 amplitudes share one row
+                    ms = np.stack([fused_matrix(rot, 1, p[l], feats[r][q], q, inverse)
+                                   for r in range(rows)])
+                else:
+                    ms = fused_matrix(rot, 0, p[l], None, q, inverse)
+                st = apply_1q(st, n, q, ms)
+                n_gates += 1
+            elif kind == "X":
+                jt, jc = (int(x) for x in tok[1:].split(":"))
+                assert jt != jc
+                st = apply_cnot(st, n, bit(s + jc), bit(s + jt))
+                n_gates += 1
+            elif kind == "D":
+                jt, qc, uni = (int(x) for x in tok[1:].split(":"))
+                qt = bit(s + jt)
+                assert qt < n and qc < n and qc != qt
+                run_bits = [bit(s + j) for j in range(R)]
+                assert qc not in run_bits
+                local = [bit(pp) for pp in range(t)]
+                if qc in local:
+                    pc = local.index(qc)
+                    tbit = pc if pc < s else pc - R
+                    assert uni == (1 if tbit >= 6 else 0)
+                else:
+                    assert uni == 1
+                st = apply_cnot(st, n, qc, qt)
+                n_gates += 1
+            elif kind == "Z":
+                mask = int(tok[1:], 16)
+                k = np.arange(1 << n)
+                sign = 1 - 2 * (np.array([bin(v).count("1") for v in (k & (k >> 1) & mask)]) & 1)
+                st = st * sign[None, :]
+                n_gates += bin(mask).count("1")
+            else:
+                assert tok == "E"
+        assert sum(1 for o in ops if o == "E") == 1
+    return st, n_gates, len(passes)
+
+
+CASES = [
+    # n, rows, L, rot, ent, reupload, tile
+    (4, 8, 2, (RY, RZ), RING, 0, 0), (5, 3, 3, (RX, RY, RZ), RING, 0, 0),
+    (7, 2, 2, (RY, RZ), LADDER, 0, 0), (6, 5, 3, (RY, RZ), RING, 1, 0),
+    (10, 2, 3, (RY, RZ), RING, 1, 0), (11, 1, 3, (RX, RY, RZ), RING, 0, 10),
+    (12, 1, 2, (RY, RZ), LADDER, 0, 10), (12, 2, 3, (RY, RZ), RING, 0, 11),
+    (13, 1, 3, (RY, RZ), RING, 0, 10), (13, 1, 2, (RX,), NONE, 0, 12),
+    (12, 1, 2, (), RING, 0, 10), (12, 2, 2, (RY, RZ), RING, 1, 10),
+    (14, 1, 4, (RX, RY, RZ), RING, 0, 12), (14, 1, 3, (RY, RZ), LADDER, 0, 11),
+]
+
+
+@pytest.mark.parametrize("n,rows,L,rot,ent,reup,tile", CASES)
+@pytest.mark.parametrize("inverse", [0, 1])
+def test_plan_replay_matches_oracle(oracle, n, rows, L, rot, ent, reup, tile, inverse):
+    g = np.random.Generator(np.random.PCG64(1000 + 13 * n + L + ent + 2 * reup + inverse))
+    circ = qb.make_circuit(L, list(rot), ent, reup)
+    P = qb.qsv_num_params(circ, n)
+    ocirc = oracle.make_circuit(L, list(rot), ent, reup)
+    assert P == oracle.num_params(ocirc, n)
+    params = g.uniform(0, 2 * np.pi, P).astype(np.float32)
+    feats = g.standard_normal((rows, n)).astype(np.float32) if reup else None
+    x = g.standard_normal((rows, 1 << n)).astype(np.float32)
+    ref, _ = oracle.amp_encode(x, n)
+    start = ref.copy()
+    oracle.apply_layers(ref, ocirc, params, feats, inverse=bool(inverse))
+    text = qb.qsv_plan_describe(circ, n, rows, inverse, tile)
+    out, n_gates, n_pass = replay(text, n, rows, L, rot, ent, reup, params.astype(np.float64),
+                                  None if feats is None else feats.astype(np.float64), inverse, start)
+    ent_gates = n if (ent == RING and n >= 2) else (n - 1 if ent == LADDER else 0)
+    per_layer = (n if (reup + len(rot)) else 0) + ent_gates
+    assert n_gates == L * per_layer                    # every gate exactly once
+    assert np.allclose(out, ref, atol=1e-12)
+
+
+def test_plan_pass_counts_for_the_large_configs():
+    """Pass counts decide the HBM traffic of the 20- and 26-qubit configs; pin their budget."""
+    c3 = qb.make_circuit(20, [RY, RZ], RING)
+    c4 = qb.make_circuit(30, [RX, RY, RZ], RING)
+    for circ, n, B, layers in ((c3, 20, 32, 20), (c4, 26, 1, 30)):
+        for inv in (0, 1):
+            head, passes = parse_plan(qb.qsv_plan_describe(circ, n, B, inv, 0))
+            assert len(passes) <= 2.5 * layers
+            assert sum(h["gates"] for h, _ in passes) == layers * 2 * n
+
+
+def test_bad_descriptors_are_rejected():
+    assert qb.qsv_num_params(qb.make_circuit(1, [7], RING), 4) == -1
+    assert qb.qsv_num_params(qb.make_circuit(-1, [RX], RING), 4) == -1
+    assert qb.qsv_num_params(qb.make_circuit(1, [RX], 5), 4) == -1
+    assert qb.qsv_num_params(qb.make_circuit(1, [RX], RING), 31) == -1
+    assert qb.qsv_num_params(qb.make_circuit(3, [RX, RZ], LADDER, 1), 5) == 3 * 3 * 5
+    assert qb.qsv_workspace_bytes(0, 1) == 0 and qb.qsv_workspace_bytes(4, 0) == 0
+    with pytest.raises(ValueError):
+        qb.qsv_plan_describe(qb.make_circuit(1, [RX], RING), 4, 1, 0, 9)
