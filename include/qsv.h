@@ -73,7 +73,7 @@ size_t qsv_workspace_bytes(int n_qubits, int batch);
 /* Create a context bound to (n_qubits, batch), a device ordinal, a HIP stream (hipStream_t cast
  * to void*, NULL = default stream), the caller's state buffer complex64 [batch][2^n] and the
  * caller's workspace (256-byte aligned device memory of at least qsv_workspace_bytes bytes).
- * Nothing is launched. */
+ * batch must be in 1..65535.  Nothing is launched. */
 qsv_status qsv_create(qsv_ctx** out, int n_qubits, int batch, int device, void* hip_stream,
                       void* state_dev, void* ws_dev, size_t ws_bytes);
 void qsv_destroy(qsv_ctx* ctx);

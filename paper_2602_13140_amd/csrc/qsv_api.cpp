@@ -134,7 +134,9 @@ qsv_status get_plan(qsv_ctx* ctx, const qsv_circuit& c, int64_t rows, int invers
     if (!cp.plan.complete) return fail(ctx, QSV_ERR_UNSUPPORTED, "internal: pass planner failed");
     const size_t bytes = align_up(cp.plan.ops.size() * sizeof(Op) + sizeof(Op));
     if (bytes > kOpsRegion) return fail(ctx, QSV_ERR_UNSUPPORTED, "circuit too long for the plan buffer");
-    if (ctx->ops_used + bytes > kOpsRegion) {  // recycle: stream order keeps in-flight passes safe
+    if (ctx->ops_used + bytes > kOpsRegion) {
+        // recycle the region; wait first so no pending upload still reads a cached plan's memory
+        QSV_HIP(ctx, hipStreamSynchronize(ctx->stream), "recycle plan buffer");
         ctx->cache.clear();
         ctx->ops_used = 0;
     }
@@ -245,7 +247,7 @@ qsv_status qsv_create(qsv_ctx** out, int n_qubits, int batch, int device, void* 
     if (!out) { g_create_error = "out is NULL"; return QSV_ERR_INVALID_ARG; }
     *out = nullptr;
     if (n_qubits < 1 || n_qubits > 30) { g_create_error = "n_qubits must be in 1..30"; return QSV_ERR_INVALID_ARG; }
-    if (batch < 1) { g_create_error = "batch must be >= 1"; return QSV_ERR_INVALID_ARG; }
+    if (batch < 1 || batch > 65535) { g_create_error = "batch must be in 1..65535"; return QSV_ERR_INVALID_ARG; }
     if (device < 0) { g_create_error = "device must be >= 0"; return QSV_ERR_INVALID_ARG; }
     if (!state_dev || !ws_dev) { g_create_error = "state_dev and ws_dev must not be NULL"; return QSV_ERR_INVALID_ARG; }
     if (((uintptr_t)state_dev & 15) || ((uintptr_t)ws_dev & 255)) {
@@ -463,6 +465,7 @@ qsv_status qsv_param_shift_grad(qsv_ctx* ctx, const qsv_circuit* c, const float*
     int64_t chunk = (int64_t)(ar.remaining() / row_bytes);
     if (chunk < 1) { ar.need = ar.off + row_bytes; return ws_fail(ctx, ar, "qsv_param_shift_grad"); }
     if (chunk > circuits) chunk = circuits;
+    if (chunk > 32768) chunk = 32768;  // rows index a grid dimension
     // keep the row count a power of two when several rows share a tile (extended-index tiling)
     if (chunk < circuits) { int64_t p2 = 1; while (p2 * 2 <= chunk) p2 *= 2; chunk = p2; }
     float2* states = (float2*)ar.take((size_t)chunk * ((size_t)8 << n));

@@ -72,18 +72,71 @@ __device__ __forceinline__ RowCtx row_ctx(const RowMap& rm, u64 row) {
 
 __device__ __forceinline__ unsigned swz(unsigned tau) { return tau ^ ((tau >> R) & 15u); }
 
-template <int J>
+// One 2x2 complex matrix times one amplitude pair, in place.  (a,b) = (re,im) of the amplitude
+// whose target bit is 0, (c,d) of the one whose bit is 1; m = (m00r,m00i,m01r,m01i,m10r,m10i,m11r,
+// m11i).  Written as one asm block with tied operands so that the 32 amplitude registers never
+// move: four interleaved accumulation chains whose last step overwrites an input that is dead by
+// then.  16 VALU instructions per pair, none of them a copy.
+#define QSV_U_PAIR_BODY                      \
+    "v_mul_f32 %4, %8, %0\n\t"               \
+    "v_mul_f32 %5, %9, %0\n\t"               \
+    "v_mul_f32 %6, %12, %0\n\t"              \
+    "v_mul_f32 %7, %13, %0\n\t"              \
+    "v_fma_f32 %4, -%9, %1, %4\n\t"          \
+    "v_fma_f32 %5, %8, %1, %5\n\t"           \
+    "v_fma_f32 %6, -%13, %1, %6\n\t"         \
+    "v_fma_f32 %7, %12, %1, %7\n\t"          \
+    "v_fma_f32 %4, %10, %2, %4\n\t"          \
+    "v_fma_f32 %5, %11, %2, %5\n\t"          \
+    "v_fma_f32 %6, %14, %2, %6\n\t"          \
+    "v_fma_f32 %7, %15, %2, %7\n\t"          \
+    "v_fma_f32 %0, -%11, %3, %4\n\t"         \
+    "v_fma_f32 %1, %10, %3, %5\n\t"          \
+    "v_fma_f32 %2, -%15, %3, %6\n\t"         \
+    "v_fma_f32 %3, %14, %3, %7\n\t"
+
+// matrix in scalar registers (same for the whole wavefront)
+__device__ __forceinline__ void u_pair_s(float& a, float& b, float& c, float& d, const float (&m)[8]) {
+    float t0, t1, t2, t3;
+    asm volatile(QSV_U_PAIR_BODY
+                 : "+v"(a), "+v"(b), "+v"(c), "+v"(d), "=&v"(t0), "=&v"(t1), "=&v"(t2), "=&v"(t3)
+                 : "s"(m[0]), "s"(m[1]), "s"(m[2]), "s"(m[3]), "s"(m[4]), "s"(m[5]), "s"(m[6]), "s"(m[7]));
+}
+
+// matrix in vector registers (differs per lane: several state rows share a tile)
+__device__ __forceinline__ void u_pair_v(float& a, float& b, float& c, float& d, const float (&m)[8]) {
+    float t0, t1, t2, t3;
+    asm volatile(QSV_U_PAIR_BODY
+                 : "+v"(a), "+v"(b), "+v"(c), "+v"(d), "=&v"(t0), "=&v"(t1), "=&v"(t2), "=&v"(t3)
+                 : "v"(m[0]), "v"(m[1]), "v"(m[2]), "v"(m[3]), "v"(m[4]), "v"(m[5]), "v"(m[6]), "v"(m[7]));
+}
+
+template <int J, bool SCALAR>
 __device__ __forceinline__ void apply_u(float (&vr)[NR], float (&vi)[NR], const float (&m)[8]) {
 #pragma unroll
     for (int i = 0; i < NR; ++i) {
         if (i & (1 << J)) continue;
         const int i1 = i | (1 << J);
-        const float x0r = vr[i], x0i = vi[i], x1r = vr[i1], x1i = vi[i1];
-        vr[i] = m[0] * x0r - m[1] * x0i + m[2] * x1r - m[3] * x1i;
-        vi[i] = m[0] * x0i + m[1] * x0r + m[2] * x1i + m[3] * x1r;
-        vr[i1] = m[4] * x0r - m[5] * x0i + m[6] * x1r - m[7] * x1i;
-        vi[i1] = m[4] * x0i + m[5] * x0r + m[6] * x1i + m[7] * x1r;
+        if (SCALAR) u_pair_s(vr[i], vi[i], vr[i1], vi[i1], m);
+        else u_pair_v(vr[i], vi[i], vr[i1], vi[i1], m);
     }
+}
+
+template <bool SCALAR>
+__device__ __forceinline__ void apply_u_any(int j, float (&vr)[NR], float (&vi)[NR], const float (&m)[8]) {
+    switch (j) {
+        case 0: apply_u<0, SCALAR>(vr, vi, m); break;
+        case 1: apply_u<1, SCALAR>(vr, vi, m); break;
+        case 2: apply_u<2, SCALAR>(vr, vi, m); break;
+        default: apply_u<3, SCALAR>(vr, vi, m); break;
+    }
+}
+
+// Register swaps are done with real v_swap_b32 instructions: a swap expressed as C++ assignments
+// would be resolved by renaming registers, and the renamed state would have to be copied back at
+// every merge point of the interpreter loop.
+__device__ __forceinline__ void vswap(float& a, float& b) {
+    asm volatile("v_swap_b32 %0, %1" : "+v"(a), "+v"(b));
 }
 
 template <int JT, int JC>
@@ -92,23 +145,27 @@ __device__ __forceinline__ void cx_reg(float (&vr)[NR], float (&vi)[NR]) {
     for (int i = 0; i < NR; ++i) {
         if (!(i & (1 << JC)) || (i & (1 << JT))) continue;
         const int i1 = i | (1 << JT);
-        const float tr = vr[i], ti = vi[i];
-        vr[i] = vr[i1]; vi[i] = vi[i1];
-        vr[i1] = tr; vi[i1] = ti;
+        vswap(vr[i], vr[i1]);
+        vswap(vi[i], vi[i1]);
     }
 }
 
 template <int JT>
-__device__ __forceinline__ void cx_sel(float (&vr)[NR], float (&vi)[NR], bool cond) {
+__device__ __forceinline__ void cx_all(float (&vr)[NR], float (&vi)[NR]) {
 #pragma unroll
     for (int i = 0; i < NR; ++i) {
         if (i & (1 << JT)) continue;
         const int i1 = i | (1 << JT);
-        const float ar = vr[i], ai = vi[i], br = vr[i1], bi = vi[i1];
-        vr[i] = cond ? br : ar; vi[i] = cond ? bi : ai;
-        vr[i1] = cond ? ar : br; vi[i1] = cond ? ai : bi;
+        vswap(vr[i], vr[i1]);
+        vswap(vi[i], vi[i1]);
     }
 }
+
+// constant-address-space views: uniform loads through them become scalar loads
+typedef unsigned u32x2 __attribute__((ext_vector_type(2)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef const __attribute__((address_space(4))) u32x2* cuint2_p;
+typedef const __attribute__((address_space(4))) f32x4* cfloat4_p;
 
 template <int T>
 __global__ __launch_bounds__(1 << (T - R)) void k_pass(const PassArgs a) {
@@ -123,9 +180,13 @@ __global__ __launch_bounds__(1 << (T - R)) void k_pass(const PassArgs a) {
         return (u64)(tau & cmask) | ((u64)(tau >> c) << w);
     };
     if (tile_base >= a.total) return;  // padding tile (batch not a power of two): nothing to do
+    // every element of the tile in range? (false only for the last tile of a ragged batch)
+    const bool full = (tile_base | expand((1u << T) - 1u)) < a.total;
     // tiles never straddle a state row unless T > n, in which case rows are per lane
     const bool rows_uniform = a.n >= T;
-    RowCtx urc = row_ctx(a.rm, tile_base >> a.n);
+    const RowCtx urc = row_ctx(a.rm, tile_base >> a.n);
+    // Operations are read as one aligned 64-bit word each and decoded with shifts.
+    const cuint2_p ops = (cuint2_p)(uintptr_t)a.ops;
 
     float vr[NR], vi[NR];
     int s = 0;
@@ -138,110 +199,118 @@ __global__ __launch_bounds__(1 << (T - R)) void k_pass(const PassArgs a) {
     };
 
     for (int pc = 0;; ++pc) {
-        const Op op = a.ops[pc];
-        if (op.kind == OP_END) break;
-        switch (op.kind) {
-            case OP_LOAD: {
-                set_layout(op.a);
+        const u32x2 word = ops[pc];
+        const unsigned kind = word.x & 0xffu, oa = (word.x >> 8) & 0xffu, ob = (word.x >> 16) & 0xffu,
+                       oc = word.x >> 24;
+        const int arg = (int)word.y;
+        if (kind == OP_END) break;
+        if (kind == OP_LOAD) {
+            set_layout((int)oa);
+            if (full) {
+#pragma unroll
+                for (int i = 0; i < NR; ++i) {
+                    const float2 v = a.state[e0 | expand((unsigned)i << s)];
+                    vr[i] = v.x; vi[i] = v.y;
+                }
+            } else {
 #pragma unroll
                 for (int i = 0; i < NR; ++i) {
                     const u64 e = e0 | expand((unsigned)i << s);
-                    float2 v = make_float2(0.f, 0.f);
-                    if (e < a.total) v = a.state[e];
-                    vr[i] = v.x; vi[i] = v.y;
+                    const float2 v = a.state[e < a.total ? e : 0];
+                    vr[i] = e < a.total ? v.x : 0.f; vi[i] = e < a.total ? v.y : 0.f;
                 }
-                break;
             }
-            case OP_XPOSE: {
-                __syncthreads();
+        } else if (kind == OP_XPOSE) {
+            __syncthreads();
 #pragma unroll
-                for (int i = 0; i < NR; ++i)
-                    lds[swz(tau_thr | ((unsigned)i << s))] = make_float2(vr[i], vi[i]);
-                __syncthreads();
-                set_layout(op.a);
+            for (int i = 0; i < NR; ++i)
+                lds[swz(tau_thr | ((unsigned)i << s))] = make_float2(vr[i], vi[i]);
+            __syncthreads();
+            set_layout((int)oa);
 #pragma unroll
-                for (int i = 0; i < NR; ++i) {
-                    const float2 v = lds[swz(tau_thr | ((unsigned)i << s))];
-                    vr[i] = v.x; vi[i] = v.y;
-                }
-                break;
+            for (int i = 0; i < NR; ++i) {
+                const float2 v = lds[swz(tau_thr | ((unsigned)i << s))];
+                vr[i] = v.x; vi[i] = v.y;
             }
-            case OP_U: {
-                float m[8];
-                const int id = op.arg;
-                if (!op.b) {
-                    const float* p = a.mats + (u64)id * 8;
-#pragma unroll
-                    for (int k = 0; k < 8; ++k) m[k] = p[k];
-                } else if (rows_uniform) {
-                    const float* p = (id == urc.ovr_id)
+        } else if (kind == OP_U) {
+            float m[8];
+            const int id = arg;
+            if (!ob || rows_uniform) {
+                const float* p;
+                if (!ob) {
+                    p = a.mats + (u64)id * 8;
+                } else {
+                    p = (id == urc.ovr_id)
                         ? a.ovr + (a.rowdep ? urc.sample * (u64)a.rm.two_p * 8 : 0) + urc.ovr_off
                         : a.mats + ((a.rowdep ? urc.sample * (u64)a.n_mats : 0) + (u64)id) * 8;
+                }
+                const cfloat4_p cp = (cfloat4_p)(uintptr_t)p;
+                const f32x4 lo = cp[0], hi = cp[1];
+                m[0] = lo.x; m[1] = lo.y; m[2] = lo.z; m[3] = lo.w;
+                m[4] = hi.x; m[5] = hi.y; m[6] = hi.z; m[7] = hi.w;
+                apply_u_any<true>((int)oa, vr, vi, m);
+            } else {
+                // several rows per tile: the run lies inside the qubit bits (planner rule), so
+                // all 16 amplitudes of a lane share one row
+                const u64 ee = e0 < a.total ? e0 : 0;
+                const RowCtx rc = row_ctx(a.rm, ee >> a.n);
+                const float* p = (id == rc.ovr_id)
+                    ? a.ovr + (a.rowdep ? rc.sample * (u64)a.rm.two_p * 8 : 0) + rc.ovr_off
+                    : a.mats + ((a.rowdep ? rc.sample * (u64)a.n_mats : 0) + (u64)id) * 8;
+                const float4 lo = *reinterpret_cast<const float4*>(p);
+                const float4 hi = *reinterpret_cast<const float4*>(p + 4);
+                m[0] = lo.x; m[1] = lo.y; m[2] = lo.z; m[3] = lo.w;
+                m[4] = hi.x; m[5] = hi.y; m[6] = hi.z; m[7] = hi.w;
+                apply_u_any<false>((int)oa, vr, vi, m);
+            }
+        } else if (kind == OP_CX_REG) {
+            switch (oa * 4 + ob) {
+                case 1: cx_reg<0, 1>(vr, vi); break;
+                case 2: cx_reg<0, 2>(vr, vi); break;
+                case 3: cx_reg<0, 3>(vr, vi); break;
+                case 4: cx_reg<1, 0>(vr, vi); break;
+                case 6: cx_reg<1, 2>(vr, vi); break;
+                case 7: cx_reg<1, 3>(vr, vi); break;
+                case 8: cx_reg<2, 0>(vr, vi); break;
+                case 9: cx_reg<2, 1>(vr, vi); break;
+                case 11: cx_reg<2, 3>(vr, vi); break;
+                case 12: cx_reg<3, 0>(vr, vi); break;
+                case 13: cx_reg<3, 1>(vr, vi); break;
+                case 14: cx_reg<3, 2>(vr, vi); break;
+                default: break;
+            }
+        } else if (kind == OP_CX_DYN) {
+            // conditional X: lanes whose control bit is set swap their pairs (the compiler masks
+            // the swaps with exec; when the bit is wavefront-uniform the branch is simply skipped)
+            if ((e0 >> ob) & 1ull) {
+                switch (oa) {
+                    case 0: cx_all<0>(vr, vi); break;
+                    case 1: cx_all<1>(vr, vi); break;
+                    case 2: cx_all<2>(vr, vi); break;
+                    default: cx_all<3>(vr, vi); break;
+                }
+            }
+        } else if (kind == OP_CZ) {
+            const u64 mask = (u64)(unsigned)arg;
 #pragma unroll
-                    for (int k = 0; k < 8; ++k) m[k] = p[k];
-                } else {
-                    // several rows per tile: the run lies inside the qubit bits (planner rule), so
-                    // all 16 amplitudes of a lane share one row
-                    u64 ee = e0 < a.total ? e0 : 0;
-                    const RowCtx rc = row_ctx(a.rm, ee >> a.n);
-                    const float* p = (id == rc.ovr_id)
-                        ? a.ovr + (a.rowdep ? rc.sample * (u64)a.rm.two_p * 8 : 0) + rc.ovr_off
-                        : a.mats + ((a.rowdep ? rc.sample * (u64)a.n_mats : 0) + (u64)id) * 8;
-#pragma unroll
-                    for (int k = 0; k < 8; ++k) m[k] = p[k];
-                }
-                switch (op.a) {
-                    case 0: apply_u<0>(vr, vi, m); break;
-                    case 1: apply_u<1>(vr, vi, m); break;
-                    case 2: apply_u<2>(vr, vi, m); break;
-                    default: apply_u<3>(vr, vi, m); break;
-                }
-                break;
+            for (int i = 0; i < NR; ++i) {
+                const u64 k = e0 | expand((unsigned)i << s);
+                const unsigned flip = (unsigned)(__popcll(k & (k >> 1) & mask) & 1) << 31;
+                vr[i] = __uint_as_float(__float_as_uint(vr[i]) ^ flip);
+                vi[i] = __uint_as_float(__float_as_uint(vi[i]) ^ flip);
             }
-            case OP_CX_REG: {
-                switch (op.a * 4 + op.b) {
-                    case 1: cx_reg<0, 1>(vr, vi); break;
-                    case 2: cx_reg<0, 2>(vr, vi); break;
-                    case 3: cx_reg<0, 3>(vr, vi); break;
-                    case 4: cx_reg<1, 0>(vr, vi); break;
-                    case 6: cx_reg<1, 2>(vr, vi); break;
-                    case 7: cx_reg<1, 3>(vr, vi); break;
-                    case 8: cx_reg<2, 0>(vr, vi); break;
-                    case 9: cx_reg<2, 1>(vr, vi); break;
-                    case 11: cx_reg<2, 3>(vr, vi); break;
-                    case 12: cx_reg<3, 0>(vr, vi); break;
-                    case 13: cx_reg<3, 1>(vr, vi); break;
-                    case 14: cx_reg<3, 2>(vr, vi); break;
-                    default: break;
-                }
-                break;
-            }
-            case OP_CX_DYN: {
-                const bool cond = (e0 >> op.b) & 1ull;
-                switch (op.a) {
-                    case 0: cx_sel<0>(vr, vi, cond); break;
-                    case 1: cx_sel<1>(vr, vi, cond); break;
-                    case 2: cx_sel<2>(vr, vi, cond); break;
-                    default: cx_sel<3>(vr, vi, cond); break;
-                }
-                break;
-            }
-            case OP_CZ: {
-                const u64 mask = (u64)(unsigned)op.arg;
-#pragma unroll
-                for (int i = 0; i < NR; ++i) {
-                    const u64 k = e0 | expand((unsigned)i << s);
-                    if (__popcll(k & (k >> 1) & mask) & 1) { vr[i] = -vr[i]; vi[i] = -vi[i]; }
-                }
-                break;
-            }
-            default: break;
         }
     }
+    if (full) {
 #pragma unroll
-    for (int i = 0; i < NR; ++i) {
-        const u64 e = e0 | expand((unsigned)i << s);
-        if (e < a.total) a.state[e] = make_float2(vr[i], vi[i]);
+        for (int i = 0; i < NR; ++i)
+            a.state[e0 | expand((unsigned)i << s)] = make_float2(vr[i], vi[i]);
+    } else {
+#pragma unroll
+        for (int i = 0; i < NR; ++i) {
+            const u64 e = e0 | expand((unsigned)i << s);
+            if (e < a.total) a.state[e] = make_float2(vr[i], vi[i]);
+        }
     }
 }
 
