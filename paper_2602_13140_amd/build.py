@@ -3,12 +3,14 @@ import os
 import subprocess
 import sys
 
+sys.path.insert(0, os.path.dirname(os.path.dirname(os.path.abspath(__file__))))
+
 HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libqsv.so")
 SOURCES = ["qsv_api.cpp", "qsv_plan.cpp", "qsv_kernels.hip"]
-HEADERS = ["qsv_plan.h", "qsv_kernels.h", os.path.join(ROOT, "include", "qsv.h")]
+HEADERS = ["qsv_plan.h", "qsv_kernels.h", "gen_gate_asm.py", os.path.join(ROOT, "include", "qsv.h")]
 
 
 def hipcc():
@@ -31,6 +33,8 @@ def build(force=True, verbose=False):
     """Compile for gfx950.  Packed-FP32 instruction selection is switched off on purpose."""
     if not force and not needs_build():
         return LIB
+    from paper_2602_13140_amd.csrc import gen_gate_asm  # noqa: E402  (regenerate the asm header)
+    gen_gate_asm.write()
     cmd = [hipcc(), "--offload-arch=gfx950", "-O3", "-std=c++17", "-shared", "-fPIC",
            "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
            "-x", "hip",

@@ -1,6 +1,7 @@
 // HIP kernels for gfx950 (CDNA4): fused gate passes, encoding, measurement, sampling, gradient
 // assembly.  64-wide wavefronts throughout.  No code is shared with the CPU oracle.
 #include "qsv_kernels.h"
+#include "qsv_gate_asm.h"
 
 namespace qsv {
 
@@ -132,40 +133,23 @@ __device__ __forceinline__ void apply_u_any(int j, float (&vr)[NR], float (&vi)[
     }
 }
 
-// Register swaps are done with real v_swap_b32 instructions: a swap expressed as C++ assignments
-// would be resolved by renaming registers, and the renamed state would have to be copied back at
-// every merge point of the interpreter loop.
-__device__ __forceinline__ void vswap(float& a, float& b) {
-    asm volatile("v_swap_b32 %0, %1" : "+v"(a), "+v"(b));
-}
-
-template <int JT, int JC>
-__device__ __forceinline__ void cx_reg(float (&vr)[NR], float (&vi)[NR]) {
-#pragma unroll
-    for (int i = 0; i < NR; ++i) {
-        if (!(i & (1 << JC)) || (i & (1 << JT))) continue;
-        const int i1 = i | (1 << JT);
-        vswap(vr[i], vr[i1]);
-        vswap(vi[i], vi[i1]);
-    }
-}
-
-template <int JT>
-__device__ __forceinline__ void cx_all(float (&vr)[NR], float (&vi)[NR]) {
-#pragma unroll
-    for (int i = 0; i < NR; ++i) {
-        if (i & (1 << JT)) continue;
-        const int i1 = i | (1 << JT);
-        vswap(vr[i], vr[i1]);
-        vswap(vi[i], vi[i1]);
-    }
-}
-
 // constant-address-space views: uniform loads through them become scalar loads
 typedef unsigned u32x2 __attribute__((ext_vector_type(2)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef const __attribute__((address_space(4))) u32x2* cuint2_p;
 typedef const __attribute__((address_space(4))) f32x4* cfloat4_p;
+
+// A value that is certainly held in a scalar register (an "s" input constraint alone is not
+// enough: the compiler may hand a vector register to the asm).
+__device__ __forceinline__ unsigned to_sgpr(unsigned v) {
+    unsigned r;
+    // The compiler cannot see into the asm, so it does not pad the one wait state this chip needs
+    // between a vector write of a register and a readfirstlane of it; s_nop covers it.
+    asm volatile("s_nop 4\n\tv_readfirstlane_b32 %0, %1\n\ts_nop 1" : "=s"(r) : "v"(v));
+    return r;
+}
+
+#define QSV_RV(k) [r##k] "+v"(vr[k]), [i##k] "+v"(vi[k])
 
 template <int T>
 __global__ __launch_bounds__(1 << (T - R)) void k_pass(const PassArgs a) {
@@ -185,8 +169,14 @@ __global__ __launch_bounds__(1 << (T - R)) void k_pass(const PassArgs a) {
     // tiles never straddle a state row unless T > n, in which case rows are per lane
     const bool rows_uniform = a.n >= T;
     const RowCtx urc = row_ctx(a.rm, tile_base >> a.n);
-    // Operations are read as one aligned 64-bit word each and decoded with shifts.
-    const cuint2_p ops = (cuint2_p)(uintptr_t)a.ops;
+    // scalar operands of the gate interpreter
+    const u64 mbase = (u64)(uintptr_t)(a.mats + (a.rowdep && rows_uniform ? urc.sample * (u64)a.n_mats * 8 : 0));
+    const u64 ovrp = (u64)(uintptr_t)(a.ovr + (a.rowdep && rows_uniform ? urc.sample * (u64)a.rm.two_p * 8 : 0) + urc.ovr_off);
+    const unsigned mlo = to_sgpr((unsigned)mbase), mhi = to_sgpr((unsigned)(mbase >> 32));
+    const unsigned olo = to_sgpr((unsigned)ovrp), ohi = to_sgpr((unsigned)(ovrp >> 32));
+    const unsigned ovr_id = to_sgpr((unsigned)(rows_uniform ? urc.ovr_id : -1));
+    const unsigned nonuni = to_sgpr(rows_uniform ? 0u : 1u);
+    unsigned opslo = to_sgpr((unsigned)(uintptr_t)a.ops), opshi = to_sgpr((unsigned)((u64)(uintptr_t)a.ops >> 32));
 
     float vr[NR], vi[NR];
     int s = 0;
@@ -198,10 +188,11 @@ __global__ __launch_bounds__(1 << (T - R)) void k_pass(const PassArgs a) {
         e0 = tile_base | expand(tau_thr);
     };
 
-    for (int pc = 0;; ++pc) {
-        const u32x2 word = ops[pc];
-        const unsigned kind = word.x & 0xffu, oa = (word.x >> 8) & 0xffu, ob = (word.x >> 16) & 0xffu,
-                       oc = word.x >> 24;
+    for (;;) {
+        // Operations are read as one aligned 64-bit word each and decoded with shifts.
+        const u64 opp = ((u64)opshi << 32) | opslo;
+        const u32x2 word = *(cuint2_p)(uintptr_t)opp;
+        const unsigned kind = word.x & 0xffu, oa = (word.x >> 8) & 0xffu;
         const int arg = (int)word.y;
         if (kind == OP_END) break;
         if (kind == OP_LOAD) {
@@ -220,6 +211,7 @@ __global__ __launch_bounds__(1 << (T - R)) void k_pass(const PassArgs a) {
                     vr[i] = e < a.total ? v.x : 0.f; vi[i] = e < a.total ? v.y : 0.f;
                 }
             }
+            { const u64 nx = opp + 8; opslo = (unsigned)nx; opshi = (unsigned)(nx >> 32); }
         } else if (kind == OP_XPOSE) {
             __syncthreads();
 #pragma unroll
@@ -232,64 +224,7 @@ __global__ __launch_bounds__(1 << (T - R)) void k_pass(const PassArgs a) {
                 const float2 v = lds[swz(tau_thr | ((unsigned)i << s))];
                 vr[i] = v.x; vi[i] = v.y;
             }
-        } else if (kind == OP_U) {
-            float m[8];
-            const int id = arg;
-            if (!ob || rows_uniform) {
-                const float* p;
-                if (!ob) {
-                    p = a.mats + (u64)id * 8;
-                } else {
-                    p = (id == urc.ovr_id)
-                        ? a.ovr + (a.rowdep ? urc.sample * (u64)a.rm.two_p * 8 : 0) + urc.ovr_off
-                        : a.mats + ((a.rowdep ? urc.sample * (u64)a.n_mats : 0) + (u64)id) * 8;
-                }
-                const cfloat4_p cp = (cfloat4_p)(uintptr_t)p;
-                const f32x4 lo = cp[0], hi = cp[1];
-                m[0] = lo.x; m[1] = lo.y; m[2] = lo.z; m[3] = lo.w;
-                m[4] = hi.x; m[5] = hi.y; m[6] = hi.z; m[7] = hi.w;
-                apply_u_any<true>((int)oa, vr, vi, m);
-            } else {
-                // several rows per tile: the run lies inside the qubit bits (planner rule), so
-                // all 16 amplitudes of a lane share one row
-                const u64 ee = e0 < a.total ? e0 : 0;
-                const RowCtx rc = row_ctx(a.rm, ee >> a.n);
-                const float* p = (id == rc.ovr_id)
-                    ? a.ovr + (a.rowdep ? rc.sample * (u64)a.rm.two_p * 8 : 0) + rc.ovr_off
-                    : a.mats + ((a.rowdep ? rc.sample * (u64)a.n_mats : 0) + (u64)id) * 8;
-                const float4 lo = *reinterpret_cast<const float4*>(p);
-                const float4 hi = *reinterpret_cast<const float4*>(p + 4);
-                m[0] = lo.x; m[1] = lo.y; m[2] = lo.z; m[3] = lo.w;
-                m[4] = hi.x; m[5] = hi.y; m[6] = hi.z; m[7] = hi.w;
-                apply_u_any<false>((int)oa, vr, vi, m);
-            }
-        } else if (kind == OP_CX_REG) {
-            switch (oa * 4 + ob) {
-                case 1: cx_reg<0, 1>(vr, vi); break;
-                case 2: cx_reg<0, 2>(vr, vi); break;
-                case 3: cx_reg<0, 3>(vr, vi); break;
-                case 4: cx_reg<1, 0>(vr, vi); break;
-                case 6: cx_reg<1, 2>(vr, vi); break;
-                case 7: cx_reg<1, 3>(vr, vi); break;
-                case 8: cx_reg<2, 0>(vr, vi); break;
-                case 9: cx_reg<2, 1>(vr, vi); break;
-                case 11: cx_reg<2, 3>(vr, vi); break;
-                case 12: cx_reg<3, 0>(vr, vi); break;
-                case 13: cx_reg<3, 1>(vr, vi); break;
-                case 14: cx_reg<3, 2>(vr, vi); break;
-                default: break;
-            }
-        } else if (kind == OP_CX_DYN) {
-            // conditional X: lanes whose control bit is set swap their pairs (the compiler masks
-            // the swaps with exec; when the bit is wavefront-uniform the branch is simply skipped)
-            if ((e0 >> ob) & 1ull) {
-                switch (oa) {
-                    case 0: cx_all<0>(vr, vi); break;
-                    case 1: cx_all<1>(vr, vi); break;
-                    case 2: cx_all<2>(vr, vi); break;
-                    default: cx_all<3>(vr, vi); break;
-                }
-            }
+            { const u64 nx = opp + 8; opslo = (unsigned)nx; opshi = (unsigned)(nx >> 32); }
         } else if (kind == OP_CZ) {
             const u64 mask = (u64)(unsigned)arg;
 #pragma unroll
@@ -299,6 +234,35 @@ __global__ __launch_bounds__(1 << (T - R)) void k_pass(const PassArgs a) {
                 vr[i] = __uint_as_float(__float_as_uint(vr[i]) ^ flip);
                 vi[i] = __uint_as_float(__float_as_uint(vi[i]) ^ flip);
             }
+            { const u64 nx = opp + 8; opslo = (unsigned)nx; opshi = (unsigned)(nx >> 32); }
+        } else if (kind == OP_U && !rows_uniform && ((word.x >> 16) & 0xffu)) {
+            // several rows per tile and row-dependent matrices: per-lane matrix.  The run lies
+            // inside the qubit bits (planner rule), so a lane's 16 amplitudes share one row.
+            float m[8];
+            const u64 ee = e0 < a.total ? e0 : 0;
+            const RowCtx rc = row_ctx(a.rm, ee >> a.n);
+            const float* p = (arg == rc.ovr_id)
+                ? a.ovr + (a.rowdep ? rc.sample * (u64)a.rm.two_p * 8 : 0) + rc.ovr_off
+                : a.mats + ((a.rowdep ? rc.sample * (u64)a.n_mats : 0) + (u64)arg) * 8;
+            const float4 lo = *reinterpret_cast<const float4*>(p);
+            const float4 hi = *reinterpret_cast<const float4*>(p + 4);
+            m[0] = lo.x; m[1] = lo.y; m[2] = lo.z; m[3] = lo.w;
+            m[4] = hi.x; m[5] = hi.y; m[6] = hi.z; m[7] = hi.w;
+            apply_u_any<false>((int)oa, vr, vi, m);
+            { const u64 nx = opp + 8; opslo = (unsigned)nx; opshi = (unsigned)(nx >> 32); }
+        } else {
+            // a run of gate operations: handled in place by the assembly interpreter, which
+            // returns with opp on the first operation that is not a gate
+            float t0, t1, t2, t3, tc;
+            const unsigned e0lo = (unsigned)e0, e0hi = (unsigned)(e0 >> 32);
+            asm volatile(QSV_GATE_LOOP_ASM
+                         : QSV_RV(0), QSV_RV(1), QSV_RV(2), QSV_RV(3), QSV_RV(4), QSV_RV(5), QSV_RV(6),
+                           QSV_RV(7), QSV_RV(8), QSV_RV(9), QSV_RV(10), QSV_RV(11), QSV_RV(12),
+                           QSV_RV(13), QSV_RV(14), QSV_RV(15), [t0] "=&v"(t0), [t1] "=&v"(t1),
+                           [t2] "=&v"(t2), [t3] "=&v"(t3), [tc] "=&v"(tc), [opslo] "+s"(opslo), [opshi] "+s"(opshi)
+                         : [mlo] "s"(mlo), [mhi] "s"(mhi), [olo] "s"(olo), [ohi] "s"(ohi),
+                           [ovrid] "s"(ovr_id), [nonuni] "s"(nonuni), [e0lo] "v"(e0lo), [e0hi] "v"(e0hi)
+                         : QSV_GATE_LOOP_CLOBBERS);
         }
     }
     if (full) {
