@@ -151,7 +151,7 @@ qsv_status qsv_param_shift_grad(qsv_ctx* ctx, const qsv_circuit* c, const float*
 int64_t qsv_plan_describe(const qsv_circuit* c, int n_qubits, int batch, int inverse,
                           int tile_log2, char* buf, int64_t buf_bytes);
 
-/* Testing/tuning knobs: tile_log2 in 10..14 (0 = default) forces the tile size of the fused pass
+/* Testing/tuning knobs: tile_log2 in 10..13 (0 = default) forces the tile size of the fused pass
  * kernel; naive = 1 routes qsv_apply_layers through the one-gate-per-launch kernels. */
 qsv_status qsv_set_option(qsv_ctx* ctx, const char* name, int64_t value);
 

@@ -5,21 +5,35 @@ tree compiles as it stands.
 
 Why assembly: the 32 amplitude registers of a lane must stay where they are across the whole
 operation list.  A C++ switch over operation kinds makes the compiler copy all of them at every
-merge point; one asm block with tied operands and its own scalar dispatch does not.
+merge point; one asm block with tied operands and its own scalar dispatch does not.  It also
+lets the next operation word and the next matrix be fetched while the current gate computes.
 
-The block executes consecutive gate operations (2x2 unitary on a register bit, CNOT with the
-control in a register bit, CNOT with the control elsewhere in the index) and returns at the first
-operation of any other kind, leaving the operation pointer on it.
+The block executes consecutive operations (2x2 unitary on a register bit, CNOT with the control
+in a register bit, CNOT with the control elsewhere in the index, and the transpose through LDS
+that moves the register run) and returns at the first operation of any other kind, leaving the
+operation pointer on it and no scalar load or LDS access in flight.
 
-Fixed scalar registers (declared as clobbers): s[80:81] operation word, s82 kind, s83 field a,
-s[84:85] scratch / saved exec, s[86:87] matrix address, s[88:95] matrix, s[96:97] operation
-pointer.  Operation word: x = kind | a<<8 | b<<16 | c<<24, y = arg.
+LDS layout: two planes of floats (real, imaginary), each with one pad element after every 16
+(index tau + tau/16), so that every layout reads and writes without bank conflicts and the
+address of register element k is the lane's base plus pad(k << s) * 4, a scalar.
+
+Operation word: x = kind | a<<8 | b<<16 | c<<24, y = arg.  For a unitary, arg is the index of its
+matrix in execution order, so consecutive unitaries read consecutive 32-byte matrices and the
+next one can be prefetched (the table is padded by one entry for the last prefetch).
+
+Fixed scalar registers (declared as clobbers):
+  s[70:71] address whose matrix sits in the prefetch buffer (0 = none)
+  s[72:79] prefetch buffer            s[80:81] current operation word
+  s82 kind   s83 field a              s[84:85] scratch / saved exec
+  s[86:87] matrix address             s[88:95] matrix in use
+  s[96:97] operation pointer          s[98:99] next operation word
 """
 import os
 
 R = 4
 NR = 1 << R
-OP_U, OP_CX_REG, OP_CX_DYN = 3, 4, 5
+OP_XPOSE, OP_U, OP_CX_REG, OP_CX_DYN = 2, 3, 4, 5
+FIRST_SGPR, LAST_SGPR = 70, 99
 
 
 def u_pair(a, b):
@@ -57,11 +71,16 @@ def gen():
     emit = L.append
     lab = lambda name: "L_%s_%%=" % name
 
+    def prefetch_next_word():
+        emit("s_load_dwordx2 s[98:99], s[96:97], 0x8")
+
     emit("s_mov_b32 s96, %[opslo]")
     emit("s_mov_b32 s97, %[opshi]")
-    emit(lab("fetch") + ":")
-    emit("s_load_dwordx2 s[80:81], s[96:97], 0x0")
-    emit("s_waitcnt lgkmcnt(0)")
+    emit("s_mov_b64 s[70:71], 0")
+    emit("s_load_dwordx2 s[98:99], s[96:97], 0x0")
+    emit(lab("top") + ":")
+    emit("s_waitcnt lgkmcnt(0)")                  # next word and prefetched matrix have landed
+    emit("s_mov_b64 s[80:81], s[98:99]")
     emit("s_and_b32 s82, s80, 0xff")
     emit("s_bfe_u32 s83, s80, 0x80008")
     emit("s_cmp_eq_u32 s82, %d" % OP_U)
@@ -70,9 +89,11 @@ def gen():
     emit("s_cbranch_scc1 " + lab("cxr"))
     emit("s_cmp_eq_u32 s82, %d" % OP_CX_DYN)
     emit("s_cbranch_scc1 " + lab("cxd"))
+    emit("s_cmp_eq_u32 s82, %d" % OP_XPOSE)
+    emit("s_cbranch_scc1 " + lab("xp"))
     emit("s_branch " + lab("exit"))
 
-    # ---- 2x2 unitary on register bit a; matrix = (arg == ovr_id) ? *ovr : mbase[arg]
+    # ---- 2x2 unitary on register bit a; matrix = (arg == ovrid) ? *ovr : mbase[arg]
     emit(lab("u") + ":")
     emit("s_bfe_u32 s84, s80, 0x80010")          # b: matrix depends on the state row
     emit("s_and_b32 s84, s84, %[nonuni]")        # ... and rows differ per lane: not ours
@@ -85,13 +106,28 @@ def gen():
     emit("s_mov_b32 s87, %[mhi]")
     emit("s_add_u32 s86, s86, s84")
     emit("s_addc_u32 s87, s87, 0")
-    emit("s_branch " + lab("uld"))
+    emit("s_cmp_eq_u64 s[86:87], s[70:71]")
+    emit("s_cbranch_scc0 " + lab("uld"))
+    emit("s_mov_b64 s[88:89], s[72:73]")          # prefetched: move into the working set
+    emit("s_mov_b64 s[90:91], s[74:75]")
+    emit("s_mov_b64 s[92:93], s[76:77]")
+    emit("s_mov_b64 s[94:95], s[78:79]")
+    emit("s_branch " + lab("uhave"))
     emit(lab("uovr") + ":")
     emit("s_mov_b32 s86, %[olo]")
     emit("s_mov_b32 s87, %[ohi]")
+    emit("s_load_dwordx8 s[88:95], s[86:87], 0x0")
+    emit("s_waitcnt lgkmcnt(0)")
+    emit("s_branch " + lab("unopf"))              # the shifted matrix is not part of the stream
     emit(lab("uld") + ":")
     emit("s_load_dwordx8 s[88:95], s[86:87], 0x0")
     emit("s_waitcnt lgkmcnt(0)")
+    emit(lab("uhave") + ":")
+    emit("s_add_u32 s70, s86, 32")                # prefetch the next matrix of the stream
+    emit("s_addc_u32 s71, s87, 0")
+    emit("s_load_dwordx8 s[72:79], s[70:71], 0x0")
+    emit(lab("unopf") + ":")
+    prefetch_next_word()
     for j in range(R - 1):
         emit("s_cmp_eq_u32 s83, %d" % j)
         emit("s_cbranch_scc1 " + lab("u%d" % j))
@@ -105,6 +141,7 @@ def gen():
 
     # ---- CNOT, control = register bit b, target = register bit a
     emit(lab("cxr") + ":")
+    prefetch_next_word()
     emit("s_bfe_u32 s84, s80, 0x80010")
     emit("s_lshl_b32 s85, s83, 2")
     emit("s_add_u32 s84, s84, s85")
@@ -122,6 +159,7 @@ def gen():
 
     # ---- CNOT, control = index bit b outside the register run (lane-dependent), target = a
     emit(lab("cxd") + ":")
+    prefetch_next_word()
     emit("s_bfe_u32 s86, s80, 0x80010")
     emit("s_lshl_b64 s[84:85], 1, s86")
     emit("v_and_b32 %[tc], s84, %[e0lo]")
@@ -142,12 +180,66 @@ def gen():
             emit("s_branch " + lab("cxdone"))
     emit(lab("cxdone") + ":")
     emit("s_mov_b64 exec, s[84:85]")
+    emit("s_branch " + lab("next"))
+
+
+    # ---- transpose: move the register run from layout scur to layout a (field a of the word)
+    def elem_addr(k, tmp):
+        # tmp = ldsb + pad(k << scur) * 4
+        if k == 0:
+            emit("v_mov_b32 %s, %%[ldsb]" % tmp)
+            return
+        emit("s_lshl_b32 s84, %d, %%[scur]" % k)
+        emit("s_lshr_b32 s85, s84, 4")
+        emit("s_add_u32 s84, s84, s85")
+        emit("s_lshl_b32 s84, s84, 2")
+        emit("v_add_u32 %s, s84, %%[ldsb]" % tmp)
+
+    emit(lab("xp") + ":")
+    prefetch_next_word()
+    emit("s_barrier")                             # everybody is done reading the previous contents
+    tmps = ["%[t0]", "%[t1]", "%[t2]", "%[t3]"]
+    for k in range(NR):
+        t = tmps[k % 4]
+        elem_addr(k, t)
+        emit("ds_write_b32 %s, %%[r%d]" % (t, k))
+        emit("ds_write_b32 %s, %%[i%d] offset:%%[plane4]" % (t, k))
+    emit("s_waitcnt lgkmcnt(0)")
+    emit("s_barrier")
+    # new layout: tau = ((thr >> s) << (s + 4)) | (thr & ((1 << s) - 1))
+    emit("s_mov_b32 %[scur], s83")
+    emit("v_lshrrev_b32 %[t0], %[scur], %[thr]")
+    emit("s_add_u32 s84, %[scur], 4")
+    emit("v_lshlrev_b32 %[t0], s84, %[t0]")
+    emit("s_lshl_b32 s85, 1, %[scur]")
+    emit("s_sub_u32 s85, s85, 1")
+    emit("v_and_b32 %[t1], s85, %[thr]")
+    emit("v_or_b32 %[t0], %[t0], %[t1]")          # t0 = tau of the lane (register bits zero)
+    emit("v_lshrrev_b32 %[t1], 4, %[t0]")
+    emit("v_add_u32 %[t1], %[t1], %[t0]")
+    emit("v_lshlrev_b32 %[t1], 2, %[t1]")
+    emit("v_add_u32 %[ldsb], %[lds0], %[t1]")     # ldsb = lds0 + pad(tau) * 4
+    # extended index of the lane: e0 = tile_base | (tau & cmask) | ((tau >> c) << w), w < 32
+    emit("v_lshrrev_b32 %[t1], %[c], %[t0]")
+    emit("v_and_b32 %[t2], %[cmask], %[t0]")
+    emit("v_lshlrev_b32 %[t3], %[w], %[t1]")
+    emit("v_or_b32 %[t2], %[t2], %[t3]")
+    emit("v_or_b32 %[e0lo], %[tblo], %[t2]")
+    emit("s_sub_u32 s84, 32, %[w]")
+    emit("v_lshrrev_b32 %[t1], s84, %[t1]")
+    emit("v_or_b32 %[e0hi], %[tbhi], %[t1]")
+    for k in range(NR):
+        t = tmps[k % 4]
+        elem_addr(k, t)
+        emit("ds_read_b32 %%[r%d], %s" % (k, t))
+        emit("ds_read_b32 %%[i%d], %s offset:%%[plane4]" % (k, t))
+    emit("s_branch " + lab("next"))               # the wait at the top covers the reads
 
     emit(lab("next") + ":")
     emit("s_add_u32 s96, s96, 8")
     emit("s_addc_u32 s97, s97, 0")
-    emit("s_branch " + lab("fetch"))
-    emit(lab("exit") + ":")
+    emit("s_branch " + lab("top"))
+    emit(lab("exit") + ":")                       # reached right after the wait: nothing in flight
     emit("s_mov_b32 %[opslo], s96")
     emit("s_mov_b32 %[opshi], s97")
     return L
@@ -163,7 +255,7 @@ def render():
     for ln in lines:
         out.append('    "%s\\n\\t" \\' % ln)
     out.append('    ""')
-    regs = ", ".join('"s%d"' % i for i in range(80, 98))
+    regs = ", ".join('"s%d"' % i for i in range(FIRST_SGPR, LAST_SGPR + 1))
     out.append("#define QSV_GATE_LOOP_CLOBBERS %s, \"vcc\", \"scc\", \"memory\"" % regs)
     return "\n".join(out) + "\n"
 

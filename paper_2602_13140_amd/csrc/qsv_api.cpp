@@ -33,7 +33,10 @@ struct CachedPlan {
     qsv_circuit c;
     int inverse, tile, grad;
     Plan plan;
-    size_t dev_off;  // byte offset of the ops inside the ops region
+    size_t dev_off;     // byte offset of the ops inside the ops region
+    size_t order_off;   // int32[n_mats]: execution order -> (layer*n + qubit)
+    size_t execof_off;  // int32[n_mats]: (layer*n + qubit) -> execution order
+    std::vector<int32_t> exec_of;
 };
 
 }  // namespace
@@ -132,7 +135,12 @@ qsv_status get_plan(qsv_ctx* ctx, const qsv_circuit& c, int64_t rows, int invers
     // rows only matter through the tile default (small states pack several rows per tile)
     cp.plan = build_plan(c, ctx->n, rows, inverse != 0, tile, grad != 0);
     if (!cp.plan.complete) return fail(ctx, QSV_ERR_UNSUPPORTED, "internal: pass planner failed");
-    const size_t bytes = align_up(cp.plan.ops.size() * sizeof(Op) + sizeof(Op));
+    const size_t nm = cp.plan.mat_order.size();
+    cp.exec_of.assign(nm, 0);
+    for (size_t k = 0; k < nm; ++k) cp.exec_of[cp.plan.mat_order[k]] = (int32_t)k;
+    const size_t ops_bytes = align_up(cp.plan.ops.size() * sizeof(Op) + sizeof(Op));
+    const size_t tab_bytes = align_up(nm * sizeof(int32_t) + 4);
+    const size_t bytes = ops_bytes + 2 * tab_bytes;
     if (bytes > kOpsRegion) return fail(ctx, QSV_ERR_UNSUPPORTED, "circuit too long for the plan buffer");
     if (ctx->ops_used + bytes > kOpsRegion) {
         // recycle the region; wait first so no pending upload still reads a cached plan's memory
@@ -141,10 +149,20 @@ qsv_status get_plan(qsv_ctx* ctx, const qsv_circuit& c, int64_t rows, int invers
         ctx->ops_used = 0;
     }
     cp.dev_off = ctx->ops_used;
+    cp.order_off = cp.dev_off + ops_bytes;
+    cp.execof_off = cp.order_off + tab_bytes;
     if (!cp.plan.ops.empty())
         QSV_HIP(ctx, hipMemcpyAsync(ctx->ws + cp.dev_off, cp.plan.ops.data(),
                                     cp.plan.ops.size() * sizeof(Op), hipMemcpyHostToDevice, ctx->stream),
                 "upload plan");
+    if (nm) {
+        QSV_HIP(ctx, hipMemcpyAsync(ctx->ws + cp.order_off, cp.plan.mat_order.data(), nm * sizeof(int32_t),
+                                    hipMemcpyHostToDevice, ctx->stream),
+                "upload matrix order");
+        QSV_HIP(ctx, hipMemcpyAsync(ctx->ws + cp.execof_off, cp.exec_of.data(), nm * sizeof(int32_t),
+                                    hipMemcpyHostToDevice, ctx->stream),
+                "upload matrix order");
+    }
     ctx->ops_used += bytes;
     ctx->cache.push_back(std::move(cp));
     *out = &ctx->cache.back();
@@ -157,13 +175,45 @@ RowMap plain_rows(int n) {
     return rm;
 }
 
-// Runs the circuit on `rows` state rows starting at `state`.
-qsv_status run_circuit(qsv_ctx* ctx, const qsv_circuit& c, float2* state, int64_t rows, int inverse,
-                       const float* mats, const float* ovr, const RowMap& rm, int grad) {
+// What a circuit needs before it can run: the pass plan (fused path) and the fused matrices, which
+// are laid out in the plan's execution order (natural order on the one-gate-per-launch path).
+struct Prepared {
+    const CachedPlan* cp = nullptr;  // null: one-gate-per-launch path
+    float* mats = nullptr;
+};
+
+size_t mats_bytes(const qsv_circuit& c, int n, int64_t samples) {
+    // one extra entry: the interpreter prefetches the matrix after the one it is using
+    return ((size_t)(c.reupload ? samples : 1) * c.n_layers * n + 1) * 32;
+}
+
+qsv_status prepare_circuit(qsv_ctx* ctx, const qsv_circuit& c, int64_t rows, int inverse, int grad,
+                           const float* params, const float* feats, int64_t samples, float* mats,
+                           Prepared* out) {
+    const int n = ctx->n;
+    const bool has_u = (c.reupload + c.n_rot) > 0 && c.n_layers > 0;
+    out->mats = mats;
+    out->cp = nullptr;
+    const int* order = nullptr;
+    if (!(ctx->opt_naive || n < kRegBits)) {
+        qsv_status st = get_plan(ctx, c, rows, inverse, grad, &out->cp);
+        if (st != QSV_OK) return st;
+        order = reinterpret_cast<const int*>(ctx->ws + out->cp->order_off);
+    }
+    if (has_u)
+        QSV_HIP(ctx, launch_build_mats(to_dev(c, n), params, feats, samples, inverse, order, mats, ctx->stream),
+                "build matrices");
+    return QSV_OK;
+}
+
+// Runs the prepared circuit on `rows` state rows starting at `state`.
+qsv_status run_circuit(qsv_ctx* ctx, const qsv_circuit& c, const Prepared& pr, float2* state, int64_t rows,
+                       int inverse, const float* ovr, const RowMap& rm) {
     const int n = ctx->n;
     const bool has_u = (c.reupload + c.n_rot) > 0;
     const int n_mats = has_u ? c.n_layers * n : 0;
-    if (ctx->opt_naive || n < kRegBits) {
+    const float* mats = pr.mats;
+    if (!pr.cp) {
         auto layer_u = [&](int l) -> hipError_t {
             if (!has_u) return hipSuccess;
             for (int q = 0; q < n; ++q) {
@@ -189,9 +239,7 @@ qsv_status run_circuit(qsv_ctx* ctx, const qsv_circuit& c, float2* state, int64_
         }
         return QSV_OK;
     }
-    const CachedPlan* cp = nullptr;
-    qsv_status st = get_plan(ctx, c, rows, inverse, grad, &cp);
-    if (st != QSV_OK) return st;
+    const CachedPlan* cp = pr.cp;
     const Plan& pl = cp->plan;
     const int ext = n + ceil_log2_i64(rows);
     const uint64_t n_tiles = ext > pl.tile ? (1ull << (ext - pl.tile)) : 1ull;
@@ -201,6 +249,7 @@ qsv_status run_circuit(qsv_ctx* ctx, const qsv_circuit& c, float2* state, int64_
         a.state = state;
         a.ops = dev_ops + ps.op_begin;
         a.mats = mats;
+        a.exec_of = reinterpret_cast<const int*>(ctx->ws + cp->execof_off);
         a.ovr = ovr;
         a.total = (uint64_t)rows << n;
         a.n = n; a.c = ps.c; a.w = ps.w;
@@ -286,7 +335,7 @@ qsv_status qsv_set_option(qsv_ctx* ctx, const char* name, int64_t value) {
     if (!ctx || !name) return QSV_ERR_INVALID_ARG;
     if (!strcmp(name, "tile_log2")) {
         if (value != 0 && (value < kMinTile || value > kMaxTile))
-            return fail(ctx, QSV_ERR_INVALID_ARG, "tile_log2 must be 0 or in 10..14");
+            return fail(ctx, QSV_ERR_INVALID_ARG, "tile_log2 must be 0 or in 10..13");
         ctx->opt_tile = (int)value;
         return QSV_OK;
     }
@@ -329,16 +378,12 @@ qsv_status qsv_apply_layers(qsv_ctx* ctx, const qsv_circuit* c, const float* par
     qsv_status st = bind_device(ctx);
     if (st != QSV_OK) return st;
     Arena ar(ctx);
-    const CircDev cd = to_dev(*c, ctx->n);
-    float* mats = nullptr;
-    if (P > 0) {
-        const size_t count = (size_t)(c->reupload ? ctx->batch : 1) * c->n_layers * ctx->n;
-        mats = (float*)ar.take(count * 32);
-        if (!mats) return ws_fail(ctx, ar, "qsv_apply_layers");
-        QSV_HIP(ctx, launch_build_mats(cd, params_dev, feats_dev, ctx->batch, inverse, mats, ctx->stream),
-                "build matrices");
-    }
-    return run_circuit(ctx, *c, ctx->state, ctx->batch, inverse, mats, nullptr, plain_rows(ctx->n), 0);
+    float* mats = (float*)ar.take(mats_bytes(*c, ctx->n, ctx->batch));
+    if (!mats) return ws_fail(ctx, ar, "qsv_apply_layers");
+    Prepared pr;
+    st = prepare_circuit(ctx, *c, ctx->batch, inverse, 0, params_dev, feats_dev, ctx->batch, mats, &pr);
+    if (st != QSV_OK) return st;
+    return run_circuit(ctx, *c, pr, ctx->state, ctx->batch, inverse, nullptr, plain_rows(ctx->n));
 }
 
 qsv_status qsv_measure(qsv_ctx* ctx, const qsv_measure_req* req) {
@@ -456,7 +501,7 @@ qsv_status qsv_param_shift_grad(qsv_ctx* ctx, const qsv_circuit* c, const float*
     if (nblk > 1024) nblk = 1024;
     double* npart = (double*)ar.take((size_t)B * nblk * 8);
     double* inv = (double*)ar.take((size_t)B * 8);
-    float* mats = (float*)ar.take(msamples * (size_t)c->n_layers * n * 32);
+    float* mats = (float*)ar.take(mats_bytes(*c, n, B));
     float* ovr = (float*)ar.take(msamples * (size_t)(2 * P) * 32);
     double* f = (double*)ar.take((size_t)circuits * 8);
     if (!npart || !inv || !mats || !ovr || !f) return ws_fail(ctx, ar, "qsv_param_shift_grad");
@@ -474,10 +519,11 @@ qsv_status qsv_param_shift_grad(qsv_ctx* ctx, const qsv_circuit* c, const float*
 
     QSV_HIP(ctx, launch_sumsq(x_dev, B, dim, npart, nblk, ctx->stream), "sumsq");
     QSV_HIP(ctx, launch_norm_finish(npart, nblk, B, inv, nullptr, ctx->stream), "norm");
-    if (P > 0) {
-        QSV_HIP(ctx, launch_build_mats(cd, params_dev, feats_dev, B, 0, mats, ctx->stream), "build matrices");
+    Prepared pr;
+    st = prepare_circuit(ctx, *c, chunk, 0, 1, params_dev, feats_dev, B, mats, &pr);
+    if (st != QSV_OK) return st;
+    if (P > 0)
         QSV_HIP(ctx, launch_build_shifted(cd, params_dev, feats_dev, B, ovr, ctx->stream), "build shifted");
-    }
     for (int64_t row0 = 0; row0 < circuits; row0 += chunk) {
         const int64_t rows = (circuits - row0) < chunk ? (circuits - row0) : chunk;
         RowMap rm;
@@ -488,7 +534,7 @@ qsv_status qsv_param_shift_grad(qsv_ctx* ctx, const qsv_circuit* c, const float*
         if (rm.slots_n < 1) rm.slots_n = 1;
         rm.n = n;
         QSV_HIP(ctx, launch_encode_write(x_dev, dim, n, rows, inv, rm, states, ctx->stream), "encode rows");
-        st = run_circuit(ctx, *c, states, rows, 0, mats, ovr, rm, 1);
+        st = run_circuit(ctx, *c, pr, states, rows, 0, ovr, rm);
         if (st != QSV_OK) return st;
         QSV_HIP(ctx, launch_expz_block(states, rows, n, zpart, ctx->stream), "expz block");
         QSV_HIP(ctx, launch_expz_finish(zpart, rows, n, obs_qubit, nullptr, f + row0, ctx->stream),

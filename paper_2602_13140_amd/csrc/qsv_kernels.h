@@ -28,7 +28,8 @@ struct RowMap {
 struct PassArgs {
     float2* state;
     const Op* ops;
-    const float* mats;   // [samples if rowdep][n_mats][8]
+    const float* mats;   // [samples if rowdep][n_mats][8], matrices in execution order
+    const int* exec_of;  // [n_mats]: (layer * n + qubit) -> execution-order index
     const float* ovr;    // gradient: [samples if rowdep][2P][8] shifted matrices
     uint64_t total;      // valid extended indices = rows * 2^n
     int n, c, w;
@@ -47,9 +48,12 @@ hipError_t launch_naive_u(float2* state, int64_t rows, int n, int q, const float
 hipError_t launch_naive_cnot(float2* state, int64_t rows, int n, int ctrl, int tgt, hipStream_t st);
 hipError_t launch_naive_cz_ladder(float2* state, int64_t rows, int n, hipStream_t st);
 
-// fused per-(layer, qubit) matrices; out: [samples if reupload][n_layers*n][8] floats
+// fused per-(layer, qubit) matrices; out: [samples if reupload][n_layers*n][8] floats.  order
+// (device, [n_layers*n], may be NULL = natural order) gives the (layer*n + qubit) id stored at
+// each position of a sample's table.
 hipError_t launch_build_mats(const CircDev& c, const float* params, const float* feats,
-                             int64_t samples, int inverse, float* out, hipStream_t st);
+                             int64_t samples, int inverse, const int* order, float* out,
+                             hipStream_t st);
 // shifted matrices for the parameter-shift rule; out: [samples if reupload][2P][8]
 hipError_t launch_build_shifted(const CircDev& c, const float* params, const float* feats,
                                 int64_t samples, float* out, hipStream_t st);

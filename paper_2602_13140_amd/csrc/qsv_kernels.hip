@@ -71,7 +71,6 @@ __device__ __forceinline__ RowCtx row_ctx(const RowMap& rm, u64 row) {
 // ((tau >> c) << w).  In layout s a lane holds the 16 amplitudes tau = thr_part | (i << s),
 // i = 0..15, where thr_part spreads the thread index over the other T-4 bits.
 
-__device__ __forceinline__ unsigned swz(unsigned tau) { return tau ^ ((tau >> R) & 15u); }
 
 // One 2x2 complex matrix times one amplitude pair, in place.  (a,b) = (re,im) of the amplitude
 // whose target bit is 0, (c,d) of the one whose bit is 1; m = (m00r,m00i,m01r,m01i,m10r,m10i,m11r,
@@ -149,11 +148,26 @@ __device__ __forceinline__ unsigned to_sgpr(unsigned v) {
     return r;
 }
 
-#define QSV_RV(k) [r##k] "+v"(vr[k]), [i##k] "+v"(vi[k])
+// The 16 amplitudes of a lane live in 32 separately named scalars (vr0..vr15, vi0..vi15): as an
+// array the compiler turns them into one 16-wide vector value and copies the whole tuple around
+// the asm block.  QSV_16 applies a statement macro to every index.
+#define QSV_16(X) X(0) X(1) X(2) X(3) X(4) X(5) X(6) X(7) X(8) X(9) X(10) X(11) X(12) X(13) X(14) X(15)
+#define QSV_DECL(k) float vr##k, vi##k;
+#define QSV_RV(k) [r##k] "+v"(vr##k), [i##k] "+v"(vi##k),
 
-template <int T>
+// PERLANE = true is the variant for tiles that hold several state rows (n < T): it adds the
+// per-lane-matrix path; the main variant keeps its operation loop minimal.
+//
+// Structure of a pass: the first operation loads the tile; the assembly interpreter then runs
+// gates and LDS transposes in place until it meets an operation it does not handle (a CZ sign
+// flip, a per-lane unitary, or the end), which the C++ loop handles before re-entering it.
+template <int T, bool PERLANE>
 __global__ __launch_bounds__(1 << (T - R)) void k_pass(const PassArgs a) {
-    extern __shared__ float2 lds[];
+    // two planes (real, imaginary) of 2^T + 2^T/16 floats each; see the interpreter's generator
+    extern __shared__ float lds[];
+    constexpr unsigned PLANE = (1u << T) + (1u << (T - 4));
+    static_assert(PLANE * 4u < 65536u, "plane offset must fit the 16-bit LDS offset field");
+    const unsigned lds_byte0 = (unsigned)(uintptr_t)(__attribute__((address_space(3))) float*)lds;
     const unsigned thr = threadIdx.x;
     const u64 tb = blockIdx.x;
     const int c = a.c, w = a.w;
@@ -167,114 +181,102 @@ __global__ __launch_bounds__(1 << (T - R)) void k_pass(const PassArgs a) {
     // every element of the tile in range? (false only for the last tile of a ragged batch)
     const bool full = (tile_base | expand((1u << T) - 1u)) < a.total;
     // tiles never straddle a state row unless T > n, in which case rows are per lane
-    const bool rows_uniform = a.n >= T;
+    const bool rows_uniform = !PERLANE;
     const RowCtx urc = row_ctx(a.rm, tile_base >> a.n);
-    // scalar operands of the gate interpreter
+    // scalar operands of the interpreter
     const u64 mbase = (u64)(uintptr_t)(a.mats + (a.rowdep && rows_uniform ? urc.sample * (u64)a.n_mats * 8 : 0));
     const u64 ovrp = (u64)(uintptr_t)(a.ovr + (a.rowdep && rows_uniform ? urc.sample * (u64)a.rm.two_p * 8 : 0) + urc.ovr_off);
     const unsigned mlo = to_sgpr((unsigned)mbase), mhi = to_sgpr((unsigned)(mbase >> 32));
     const unsigned olo = to_sgpr((unsigned)ovrp), ohi = to_sgpr((unsigned)(ovrp >> 32));
-    const unsigned ovr_id = to_sgpr((unsigned)(rows_uniform ? urc.ovr_id : -1));
+    // unitaries are numbered in execution order; exec_of maps (layer, qubit) ids to that order
+    const unsigned ovr_id = to_sgpr((unsigned)((rows_uniform && urc.ovr_id >= 0) ? a.exec_of[urc.ovr_id] : -1));
     const unsigned nonuni = to_sgpr(rows_uniform ? 0u : 1u);
+    const unsigned sc_c = to_sgpr((unsigned)c), sc_w = to_sgpr((unsigned)w), sc_cmask = to_sgpr(cmask);
+    const unsigned tblo = to_sgpr((unsigned)tile_base), tbhi = to_sgpr((unsigned)(tile_base >> 32));
+    const unsigned lds0 = to_sgpr(lds_byte0);
     unsigned opslo = to_sgpr((unsigned)(uintptr_t)a.ops), opshi = to_sgpr((unsigned)((u64)(uintptr_t)a.ops >> 32));
 
-    float vr[NR], vi[NR];
-    int s = 0;
-    unsigned tau_thr = 0;
-    u64 e0 = 0;
-    auto set_layout = [&](int ns) {
-        s = ns;
-        tau_thr = ((thr >> s) << (s + R)) | (thr & ((1u << s) - 1u));
-        e0 = tile_base | expand(tau_thr);
-    };
+    QSV_16(QSV_DECL)
+    // ---- first operation: load the tile in layout s (register run at tile bits s..s+3)
+    const u32x2 first = *(cuint2_p)(uintptr_t)a.ops;
+    unsigned scur = to_sgpr((first.x >> 8) & 0xffu);
+    const unsigned tau0 = ((thr >> scur) << (scur + R)) | (thr & ((1u << scur) - 1u));
+    u64 e0 = tile_base | expand(tau0);
+    if (full) {
+#define QSV_LD(k) { const float2 v = a.state[e0 | expand((unsigned)k << scur)]; vr##k = v.x; vi##k = v.y; }
+        QSV_16(QSV_LD)
+#undef QSV_LD
+    } else {
+#define QSV_LD(k) { const u64 e = e0 | expand((unsigned)k << scur); const float2 v = a.state[e < a.total ? e : 0]; \
+                    vr##k = e < a.total ? v.x : 0.f; vi##k = e < a.total ? v.y : 0.f; }
+        QSV_16(QSV_LD)
+#undef QSV_LD
+    }
+    { const u64 nx = (u64)(uintptr_t)a.ops + 8; opslo = to_sgpr((unsigned)nx); opshi = to_sgpr((unsigned)(nx >> 32)); }
+    unsigned e0lo = (unsigned)e0, e0hi = (unsigned)(e0 >> 32);
+    unsigned ldsb = lds_byte0 + (tau0 + (tau0 >> 4)) * 4u;
 
     for (;;) {
+        {
+            float t0, t1, t2, t3, tc;
+            asm volatile(QSV_GATE_LOOP_ASM
+                         : QSV_16(QSV_RV) [t0] "=&v"(t0), [t1] "=&v"(t1), [t2] "=&v"(t2),
+                           [t3] "=&v"(t3), [tc] "=&v"(tc), [opslo] "+s"(opslo), [opshi] "+s"(opshi),
+                           [scur] "+s"(scur), [ldsb] "+v"(ldsb), [e0lo] "+v"(e0lo), [e0hi] "+v"(e0hi)
+                         : [mlo] "s"(mlo), [mhi] "s"(mhi), [olo] "s"(olo), [ohi] "s"(ohi),
+                           [ovrid] "s"(ovr_id), [nonuni] "s"(nonuni), [thr] "v"(thr), [c] "s"(sc_c),
+                           [w] "s"(sc_w), [cmask] "s"(sc_cmask), [tblo] "s"(tblo), [tbhi] "s"(tbhi),
+                           [lds0] "s"(lds0), [plane4] "n"(PLANE * 4u)
+                         : QSV_GATE_LOOP_CLOBBERS);
+        }
         // Operations are read as one aligned 64-bit word each and decoded with shifts.
         const u64 opp = ((u64)opshi << 32) | opslo;
         const u32x2 word = *(cuint2_p)(uintptr_t)opp;
-        const unsigned kind = word.x & 0xffu, oa = (word.x >> 8) & 0xffu;
+        const unsigned kind = word.x & 0xffu;
         const int arg = (int)word.y;
-        if (kind == OP_END) break;
-        if (kind == OP_LOAD) {
-            set_layout((int)oa);
-            if (full) {
-#pragma unroll
-                for (int i = 0; i < NR; ++i) {
-                    const float2 v = a.state[e0 | expand((unsigned)i << s)];
-                    vr[i] = v.x; vi[i] = v.y;
-                }
-            } else {
-#pragma unroll
-                for (int i = 0; i < NR; ++i) {
-                    const u64 e = e0 | expand((unsigned)i << s);
-                    const float2 v = a.state[e < a.total ? e : 0];
-                    vr[i] = e < a.total ? v.x : 0.f; vi[i] = e < a.total ? v.y : 0.f;
-                }
-            }
-            { const u64 nx = opp + 8; opslo = (unsigned)nx; opshi = (unsigned)(nx >> 32); }
-        } else if (kind == OP_XPOSE) {
-            __syncthreads();
-#pragma unroll
-            for (int i = 0; i < NR; ++i)
-                lds[swz(tau_thr | ((unsigned)i << s))] = make_float2(vr[i], vi[i]);
-            __syncthreads();
-            set_layout((int)oa);
-#pragma unroll
-            for (int i = 0; i < NR; ++i) {
-                const float2 v = lds[swz(tau_thr | ((unsigned)i << s))];
-                vr[i] = v.x; vi[i] = v.y;
-            }
-            { const u64 nx = opp + 8; opslo = (unsigned)nx; opshi = (unsigned)(nx >> 32); }
-        } else if (kind == OP_CZ) {
+        e0 = ((u64)e0hi << 32) | e0lo;
+        if (kind == OP_CZ) {
             const u64 mask = (u64)(unsigned)arg;
-#pragma unroll
-            for (int i = 0; i < NR; ++i) {
-                const u64 k = e0 | expand((unsigned)i << s);
-                const unsigned flip = (unsigned)(__popcll(k & (k >> 1) & mask) & 1) << 31;
-                vr[i] = __uint_as_float(__float_as_uint(vr[i]) ^ flip);
-                vi[i] = __uint_as_float(__float_as_uint(vi[i]) ^ flip);
-            }
-            { const u64 nx = opp + 8; opslo = (unsigned)nx; opshi = (unsigned)(nx >> 32); }
-        } else if (kind == OP_U && !rows_uniform && ((word.x >> 16) & 0xffu)) {
+#define QSV_CZ(k) { const u64 kk = e0 | expand((unsigned)k << scur); \
+                    const unsigned flip = (unsigned)(__popcll(kk & (kk >> 1) & mask) & 1) << 31; \
+                    vr##k = __uint_as_float(__float_as_uint(vr##k) ^ flip); \
+                    vi##k = __uint_as_float(__float_as_uint(vi##k) ^ flip); }
+            QSV_16(QSV_CZ)
+#undef QSV_CZ
+        } else if (PERLANE && kind == OP_U) {
             // several rows per tile and row-dependent matrices: per-lane matrix.  The run lies
             // inside the qubit bits (planner rule), so a lane's 16 amplitudes share one row.
-            float m[8];
+            float m[8], xr[NR], xi[NR];
             const u64 ee = e0 < a.total ? e0 : 0;
             const RowCtx rc = row_ctx(a.rm, ee >> a.n);
-            const float* p = (arg == rc.ovr_id)
+            const int lane_ovr = rc.ovr_id >= 0 ? a.exec_of[rc.ovr_id] : -1;
+            const float* p = (arg == lane_ovr)
                 ? a.ovr + (a.rowdep ? rc.sample * (u64)a.rm.two_p * 8 : 0) + rc.ovr_off
                 : a.mats + ((a.rowdep ? rc.sample * (u64)a.n_mats : 0) + (u64)arg) * 8;
             const float4 lo = *reinterpret_cast<const float4*>(p);
             const float4 hi = *reinterpret_cast<const float4*>(p + 4);
             m[0] = lo.x; m[1] = lo.y; m[2] = lo.z; m[3] = lo.w;
             m[4] = hi.x; m[5] = hi.y; m[6] = hi.z; m[7] = hi.w;
-            apply_u_any<false>((int)oa, vr, vi, m);
-            { const u64 nx = opp + 8; opslo = (unsigned)nx; opshi = (unsigned)(nx >> 32); }
+#define QSV_IN(k) xr[k] = vr##k; xi[k] = vi##k;
+            QSV_16(QSV_IN)
+#undef QSV_IN
+            apply_u_any<false>((int)((word.x >> 8) & 0xffu), xr, xi, m);
+#define QSV_OUT(k) vr##k = xr[k]; vi##k = xi[k];
+            QSV_16(QSV_OUT)
+#undef QSV_OUT
         } else {
-            // a run of gate operations: handled in place by the assembly interpreter, which
-            // returns with opp on the first operation that is not a gate
-            float t0, t1, t2, t3, tc;
-            const unsigned e0lo = (unsigned)e0, e0hi = (unsigned)(e0 >> 32);
-            asm volatile(QSV_GATE_LOOP_ASM
-                         : QSV_RV(0), QSV_RV(1), QSV_RV(2), QSV_RV(3), QSV_RV(4), QSV_RV(5), QSV_RV(6),
-                           QSV_RV(7), QSV_RV(8), QSV_RV(9), QSV_RV(10), QSV_RV(11), QSV_RV(12),
-                           QSV_RV(13), QSV_RV(14), QSV_RV(15), [t0] "=&v"(t0), [t1] "=&v"(t1),
-                           [t2] "=&v"(t2), [t3] "=&v"(t3), [tc] "=&v"(tc), [opslo] "+s"(opslo), [opshi] "+s"(opshi)
-                         : [mlo] "s"(mlo), [mhi] "s"(mhi), [olo] "s"(olo), [ohi] "s"(ohi),
-                           [ovrid] "s"(ovr_id), [nonuni] "s"(nonuni), [e0lo] "v"(e0lo), [e0hi] "v"(e0hi)
-                         : QSV_GATE_LOOP_CLOBBERS);
+            break;  // OP_END (the interpreter never stops on anything else)
         }
+        { const u64 nx = opp + 8; opslo = (unsigned)nx; opshi = (unsigned)(nx >> 32); }
     }
     if (full) {
-#pragma unroll
-        for (int i = 0; i < NR; ++i)
-            a.state[e0 | expand((unsigned)i << s)] = make_float2(vr[i], vi[i]);
+#define QSV_ST(k) a.state[e0 | expand((unsigned)k << scur)] = make_float2(vr##k, vi##k);
+        QSV_16(QSV_ST)
+#undef QSV_ST
     } else {
-#pragma unroll
-        for (int i = 0; i < NR; ++i) {
-            const u64 e = e0 | expand((unsigned)i << s);
-            if (e < a.total) a.state[e] = make_float2(vr[i], vi[i]);
-        }
+#define QSV_ST(k) { const u64 e = e0 | expand((unsigned)k << scur); if (e < a.total) a.state[e] = make_float2(vr##k, vi##k); }
+        QSV_16(QSV_ST)
+#undef QSV_ST
     }
 }
 
@@ -382,12 +384,14 @@ __device__ void fused_u(const CircDev& c, const float* params, const float* feat
 }
 
 __global__ __launch_bounds__(256) void k_build_mats(CircDev c, const float* params, const float* feats,
-                                                    u64 count, int inverse, float* out) {
+                                                    u64 count, int inverse, const int* order,
+                                                    float* out) {
     const u64 idx = (u64)blockIdx.x * 256 + threadIdx.x;
     if (idx >= count) return;
     const u64 per = (u64)c.n_layers * c.n;
     const u64 sample = idx / per;
-    const int lq = (int)(idx % per);
+    const int pos = (int)(idx % per);
+    const int lq = order ? order[pos] : pos;
     fused_u(c, params, feats, sample, lq / c.n, lq % c.n, -1, 0.0, inverse, out + idx * 8);
 }
 
@@ -788,26 +792,36 @@ inline unsigned blocks_for(u64 items, unsigned per) { return (unsigned)((items +
 
 // ============================================================================================
 // Launchers.
-hipError_t set_pass_attributes() {
-    hipError_t e;
-    e = hipFuncSetAttribute(reinterpret_cast<const void*>(k_pass<13>),
-                            hipFuncAttributeMaxDynamicSharedMemorySize, (1 << 13) * 8);
+template <int T>
+static hipError_t set_attr_for() {
+    const int bytes = 2 * ((1 << T) + (1 << (T - 4))) * 4;
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(k_pass<T, false>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
     if (e != hipSuccess) return e;
-    e = hipFuncSetAttribute(reinterpret_cast<const void*>(k_pass<14>),
-                            hipFuncAttributeMaxDynamicSharedMemorySize, (1 << 14) * 8);
-    return e;
+    return hipFuncSetAttribute(reinterpret_cast<const void*>(k_pass<T, true>),
+                               hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+}
+
+hipError_t set_pass_attributes() {
+    return set_attr_for<13>();
+}
+
+template <int T>
+static void launch_pass_t(const PassArgs& a, dim3 grid, size_t lds, hipStream_t st) {
+    if (a.n >= T) hipLaunchKernelGGL((k_pass<T, false>), grid, dim3(1 << (T - R)), lds, st, a);
+    else hipLaunchKernelGGL((k_pass<T, true>), grid, dim3(1 << (T - R)), lds, st, a);
 }
 
 hipError_t launch_pass(int tile, const PassArgs& a, uint64_t n_tiles, hipStream_t st) {
     if (n_tiles == 0 || n_tiles > 0x7fffffffull) return hipErrorInvalidValue;
     const dim3 grid((unsigned)n_tiles);
-    const size_t lds = ((size_t)1 << tile) * sizeof(float2);
+    // two padded planes of floats (see k_pass)
+    const size_t lds = 2 * (((size_t)1 << tile) + ((size_t)1 << (tile - 4))) * sizeof(float);
     switch (tile) {
-        case 10: hipLaunchKernelGGL(k_pass<10>, grid, dim3(1 << 6), lds, st, a); break;
-        case 11: hipLaunchKernelGGL(k_pass<11>, grid, dim3(1 << 7), lds, st, a); break;
-        case 12: hipLaunchKernelGGL(k_pass<12>, grid, dim3(1 << 8), lds, st, a); break;
-        case 13: hipLaunchKernelGGL(k_pass<13>, grid, dim3(1 << 9), lds, st, a); break;
-        case 14: hipLaunchKernelGGL(k_pass<14>, grid, dim3(1 << 10), lds, st, a); break;
+        case 10: launch_pass_t<10>(a, grid, lds, st); break;
+        case 11: launch_pass_t<11>(a, grid, lds, st); break;
+        case 12: launch_pass_t<12>(a, grid, lds, st); break;
+        case 13: launch_pass_t<13>(a, grid, lds, st); break;
         default: return hipErrorInvalidValue;
     }
     return hipGetLastError();
@@ -837,11 +851,12 @@ hipError_t launch_naive_cz_ladder(float2* state, int64_t rows, int n, hipStream_
 }
 
 hipError_t launch_build_mats(const CircDev& c, const float* params, const float* feats,
-                             int64_t samples, int inverse, float* out, hipStream_t st) {
+                             int64_t samples, int inverse, const int* order, float* out,
+                             hipStream_t st) {
     const u64 count = (u64)(c.reupload ? samples : 1) * c.n_layers * c.n;
     if (count == 0) return hipSuccess;
     hipLaunchKernelGGL(k_build_mats, dim3(blocks_for(count, 256)), dim3(256), 0, st, c, params, feats,
-                       count, inverse, out);
+                       count, inverse, order, out);
     return hipGetLastError();
 }
 

@@ -101,7 +101,7 @@ int scan_round(const Geom& gm, int s, int n, const std::vector<Gate>& G,
 }
 
 void emit_round(const Geom& gm, int s, const std::vector<Gate>& G, const std::vector<int>& exec,
-                bool rowdep, std::vector<Op>* ops) {
+                bool rowdep, std::vector<Op>* ops, std::vector<int32_t>* mat_order) {
     bool last_cz = false;
     for (int i : exec) {
         const Gate& g = G[i];
@@ -117,7 +117,8 @@ void emit_round(const Geom& gm, int s, const std::vector<Gate>& G, const std::ve
         last_cz = false;
         const int jt = gm.pos(g.q0) - s;
         if (g.kind == G_U) {
-            ops->push_back({OP_U, (uint8_t)jt, (uint8_t)(rowdep ? 1 : 0), 0, g.mat});
+            ops->push_back({OP_U, (uint8_t)jt, (uint8_t)(rowdep ? 1 : 0), 0, (int32_t)mat_order->size()});
+            mat_order->push_back(g.mat);
             continue;
         }
         const int qc = g.q1;
@@ -138,7 +139,8 @@ void emit_round(const Geom& gm, int s, const std::vector<Gate>& G, const std::ve
 // Greedy rounds of one pass.  Marks executed gates in done; emits ops when ops != nullptr.
 // Returns the pass score; *n_exec receives the number of gates executed.
 int run_pass(const Geom& gm, int n, const std::vector<Gate>& G, std::vector<uint8_t>& done,
-             size_t first, bool rowdep, std::vector<Op>* ops, int* n_exec) {
+             size_t first, bool rowdep, std::vector<Op>* ops, std::vector<int32_t>* mat_order,
+             int* n_exec) {
     const int smax = gm.t - kRegBits;
     const int smin_io = std::min(kLowBits, smax);  // layouts with coalesced global access
     // When one tile holds several state rows and matrices differ per row, a lane's 16 amplitudes
@@ -149,7 +151,7 @@ int run_pass(const Geom& gm, int n, const std::vector<Gate>& G, std::vector<uint
     auto commit = [&](int s, const std::vector<int>& ex) {
         for (int i : ex) done[i] = 1;
         cnt += (int)ex.size();
-        if (ops) emit_round(gm, s, G, ex, rowdep, ops);
+        if (ops) emit_round(gm, s, G, ex, rowdep, ops, mat_order);
         while (first < G.size() && done[first]) ++first;
     };
     // first round: loaded straight from global memory
@@ -269,7 +271,7 @@ Plan build_plan(const qsv_circuit& c, int n, int64_t batch, bool inverse, int ti
                 Geom gm{t, cl, w};
                 std::vector<uint8_t> tmp(done);
                 int ne = 0;
-                const int sc = run_pass(gm, n, G, tmp, first, rowdep, nullptr, &ne);
+                const int sc = run_pass(gm, n, G, tmp, first, rowdep, nullptr, nullptr, &ne);
                 if (sc > best) { best = sc; bestg = gm; }
             }
             if (n <= t) break;  // the whole state row is local: one geometry
@@ -278,7 +280,7 @@ Plan build_plan(const qsv_circuit& c, int n, int64_t batch, bool inverse, int ti
         ps.t = bestg.t; ps.c = bestg.c; ps.w = bestg.w;
         ps.op_begin = (int)p.ops.size();
         int ne = 0;
-        run_pass(bestg, n, G, done, first, rowdep, &p.ops, &ne);
+        run_pass(bestg, n, G, done, first, rowdep, &p.ops, &p.mat_order, &ne);
         ps.op_count = (int)p.ops.size() - ps.op_begin;
         ps.n_gates = ne;
         p.passes.push_back(ps);
@@ -303,7 +305,7 @@ std::string describe_plan(const Plan& p) {
                 case OP_END: snprintf(buf, sizeof buf, " E"); break;
                 case OP_LOAD: snprintf(buf, sizeof buf, " L%d", o.a); break;
                 case OP_XPOSE: snprintf(buf, sizeof buf, " T%d", o.a); break;
-                case OP_U: snprintf(buf, sizeof buf, " U%d:%d:%d", o.a, o.arg, o.b); break;
+                case OP_U: snprintf(buf, sizeof buf, " U%d:%d:%d", o.a, p.mat_order[o.arg], o.b); break;
                 case OP_CX_REG: snprintf(buf, sizeof buf, " X%d:%d", o.a, o.b); break;
                 case OP_CX_DYN: snprintf(buf, sizeof buf, " D%d:%d:%d", o.a, o.b, o.c); break;
                 case OP_CZ: snprintf(buf, sizeof buf, " Z%x", (unsigned)o.arg); break;

@@ -17,14 +17,15 @@ namespace qsv {
 
 constexpr int kRegBits = 4;      // R: amplitudes per lane = 2^R
 constexpr int kMinTile = 10;     // 64 lanes x 16 amplitudes
-constexpr int kMaxTile = 14;     // 2^14 complex64 = 128 KiB of LDS
+constexpr int kMaxTile = 13;     // two padded float planes of 2^13: 68 KiB of LDS, two workgroups per CU
 constexpr int kLowBits = 4;      // c: 2^4 complex64 = one 128-byte line per contiguous run
 
 enum OpKind : uint8_t {
     OP_END = 0,     // store the tile from the current layout
     OP_LOAD = 1,    // a = run start s: load the tile from global memory in layout s
     OP_XPOSE = 2,   // a = new run start: move the register run through LDS
-    OP_U = 3,       // a = register bit j, b = 1 if the matrix depends on the state row, arg = matrix id
+    OP_U = 3,       // a = register bit j, b = 1 if the matrix depends on the state row,
+                    // arg = index of the matrix in execution order (see Plan::mat_order)
     OP_CX_REG = 4,  // a = target register bit, b = control register bit
     OP_CX_DYN = 5,  // a = target register bit, b = control index bit (extended index),
                     // c = 1 if the control bit is the same for a whole wavefront
@@ -53,6 +54,9 @@ struct Plan {
     bool complete = true;        // false only on an internal scheduling failure
     std::vector<Pass> passes;
     std::vector<Op> ops;
+    // Unitaries are numbered in the order the passes execute them, so that a tile reads its
+    // matrices front to back: mat_order[k] = layer * n + qubit of the k-th executed unitary.
+    std::vector<int32_t> mat_order;
 };
 
 // Validates a circuit descriptor; returns false and fills why on failure.

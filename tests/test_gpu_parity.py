@@ -75,7 +75,7 @@ SMALL = [
 
 
 @pytest.mark.parametrize("n,B,L,rot,ent,reup", SMALL)
-@pytest.mark.parametrize("mode", ["default", "t10", "t11", "t12", "t13", "t14", "naive"])
+@pytest.mark.parametrize("mode", ["default", "t10", "t11", "t12", "t13", "naive"])
 def test_apply_layers_small(oracle, n, B, L, rot, ent, reup, mode):
     g = rng(31 * n + B + L)
     spec = wl.CircuitSpec(L, tuple(rot), ent, reup)
