@@ -151,6 +151,13 @@ qsv_status qsv_param_shift_grad(qsv_ctx* ctx, const qsv_circuit* c, const float*
 int64_t qsv_plan_describe(const qsv_circuit* c, int n_qubits, int batch, int inverse,
                           int tile_log2, char* buf, int64_t buf_bytes);
 
+/* Measurement aid: one pass of the fused-pass kernel that only loads every tile (low_bits low index
+ * bits plus a window starting at bit window_start, as the planner would choose), moves the
+ * register run through LDS `transposes` times and stores the tile back unchanged.  It gives the
+ * streaming ceiling of the pass kernel's access pattern, with no gate arithmetic.  The state is
+ * left as it was. */
+qsv_status qsv_probe_pass(qsv_ctx* ctx, int low_bits, int window_start, int transposes);
+
 /* Testing/tuning knobs: tile_log2 in 10..13 (0 = default) forces the tile size of the fused pass
  * kernel; naive = 1 routes qsv_apply_layers through the one-gate-per-launch kernels. */
 qsv_status qsv_set_option(qsv_ctx* ctx, const char* name, int64_t value);

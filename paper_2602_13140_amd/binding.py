@@ -72,6 +72,8 @@ def load():
                                        vp, vp, vp, vp]
     L.qsv_plan_describe.restype = i64
     L.qsv_plan_describe.argtypes = [ctypes.POINTER(qsv_circuit), i32, i32, i32, i32, ctypes.c_char_p, i64]
+    L.qsv_probe_pass.restype = i32
+    L.qsv_probe_pass.argtypes = [vp, i32, i32, i32]
     L.qsv_set_option.restype = i32
     L.qsv_set_option.argtypes = [vp, ctypes.c_char_p, i64]
     _lib = L
@@ -158,6 +160,9 @@ class Context:
 
     def qsv_set_option(self, name, value):
         self._check(self.L.qsv_set_option(self.h, name.encode(), int(value)))
+
+    def qsv_probe_pass(self, low_bits, window_start, transposes=0):
+        self._check(self.L.qsv_probe_pass(self.h, low_bits, window_start, transposes))
 
     def qsv_amp_encode(self, x, norm_out=None):
         assert x.is_cuda and x.dtype.is_floating_point and x.is_contiguous() and x.shape[0] == self.batch

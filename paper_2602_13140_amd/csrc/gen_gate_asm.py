@@ -13,9 +13,11 @@ in a register bit, CNOT with the control elsewhere in the index, and the transpo
 that moves the register run) and returns at the first operation of any other kind, leaving the
 operation pointer on it and no scalar load or LDS access in flight.
 
-LDS layout: two planes of floats (real, imaginary), each with one pad element after every 16
-(index tau + tau/16), so that every layout reads and writes without bank conflicts and the
-address of register element k is the lane's base plus pad(k << s) * 4, a scalar.
+LDS layout: two planes of 2^T floats (real, imaginary).  Element tau of a plane sits at index
+tau ^ ((tau >> 4) & 31): the XOR spreads every layout's 32 consecutive lanes over the 32 banks,
+costs no space (five 2^12 tiles fit one CU's 160 KiB), and, XOR being linear, the address of
+register element k is (lane's part) ^ (a scalar that depends on k and the layout): one v_xor.
+The dynamic LDS segment starts at byte 0 (the kernel has no static LDS), so no base is added.
 
 Operation word: x = kind | a<<8 | b<<16 | c<<24, y = arg.  For a unitary, arg is the index of its
 matrix in execution order, so consecutive unitaries read consecutive 32-byte matrices and the
@@ -185,15 +187,16 @@ def gen():
 
     # ---- transpose: move the register run from layout scur to layout a (field a of the word)
     def elem_addr(k, tmp):
-        # tmp = ldsb + pad(k << scur) * 4
+        # tmp = ldsb ^ (swz(k << scur) * 4), swz(x) = x ^ ((x >> 4) & 31)
         if k == 0:
             emit("v_mov_b32 %s, %%[ldsb]" % tmp)
             return
         emit("s_lshl_b32 s84, %d, %%[scur]" % k)
         emit("s_lshr_b32 s85, s84, 4")
-        emit("s_add_u32 s84, s84, s85")
+        emit("s_and_b32 s85, s85, 31")
+        emit("s_xor_b32 s84, s84, s85")
         emit("s_lshl_b32 s84, s84, 2")
-        emit("v_add_u32 %s, s84, %%[ldsb]" % tmp)
+        emit("v_xor_b32 %s, s84, %%[ldsb]" % tmp)
 
     emit(lab("xp") + ":")
     prefetch_next_word()
@@ -216,9 +219,9 @@ def gen():
     emit("v_and_b32 %[t1], s85, %[thr]")
     emit("v_or_b32 %[t0], %[t0], %[t1]")          # t0 = tau of the lane (register bits zero)
     emit("v_lshrrev_b32 %[t1], 4, %[t0]")
-    emit("v_add_u32 %[t1], %[t1], %[t0]")
-    emit("v_lshlrev_b32 %[t1], 2, %[t1]")
-    emit("v_add_u32 %[ldsb], %[lds0], %[t1]")     # ldsb = lds0 + pad(tau) * 4
+    emit("v_and_b32 %[t1], 31, %[t1]")
+    emit("v_xor_b32 %[t1], %[t1], %[t0]")
+    emit("v_lshlrev_b32 %[ldsb], 2, %[t1]")       # ldsb = swz(tau) * 4
     # extended index of the lane: e0 = tile_base | (tau & cmask) | ((tau >> c) << w), w < 32
     emit("v_lshrrev_b32 %[t1], %[c], %[t0]")
     emit("v_and_b32 %[t2], %[cmask], %[t0]")

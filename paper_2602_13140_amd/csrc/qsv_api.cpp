@@ -546,6 +546,47 @@ qsv_status qsv_param_shift_grad(qsv_ctx* ctx, const qsv_circuit* c, const float*
     return QSV_OK;
 }
 
+qsv_status qsv_probe_pass(qsv_ctx* ctx, int low_bits, int window_start, int transposes) {
+    if (!ctx) return QSV_ERR_INVALID_ARG;
+    const int n = ctx->n;
+    if (n < kRegBits) return fail(ctx, QSV_ERR_UNSUPPORTED, "probe needs n_qubits >= 4");
+    const int tile = ctx->opt_tile ? ctx->opt_tile : default_tile(n, ctx->batch);
+    const int ext = n + ceil_log2_i64(ctx->batch);
+    if (low_bits < kLowBits || low_bits > tile || window_start < low_bits ||
+        (ext > tile && window_start + (tile - low_bits) > ext) || (ext <= tile && window_start != low_bits))
+        return fail(ctx, QSV_ERR_INVALID_ARG, "probe geometry does not fit the state");
+    if (transposes < 0 || transposes > 16) return fail(ctx, QSV_ERR_INVALID_ARG, "transposes must be in 0..16");
+    qsv_status st = bind_device(ctx);
+    if (st != QSV_OK) return st;
+    Arena ar(ctx);
+    Op* dev = (Op*)ar.take(32 * sizeof(Op));
+    if (!dev) return ws_fail(ctx, ar, "qsv_probe_pass");
+    std::vector<Op> ops;
+    const int smax = tile - kRegBits;
+    ops.push_back({OP_LOAD, (uint8_t)smax, 0, 0, 0});
+    for (int i = 0; i < transposes; ++i)
+        ops.push_back({OP_XPOSE, (uint8_t)((i & 1) ? smax : 0), 0, 0, 0});
+    ops.push_back({OP_END, 0, 0, 0, 0});
+    // a small synchronous upload: this is a measurement aid, not part of the hot path
+    QSV_HIP(ctx, hipMemcpyAsync(dev, ops.data(), ops.size() * sizeof(Op), hipMemcpyHostToDevice, ctx->stream),
+            "upload probe");
+    QSV_HIP(ctx, hipStreamSynchronize(ctx->stream), "upload probe");
+    PassArgs a;
+    a.state = ctx->state;
+    a.ops = dev;
+    a.mats = nullptr;
+    a.exec_of = nullptr;
+    a.ovr = nullptr;
+    a.total = (uint64_t)ctx->batch << n;
+    a.n = n; a.c = low_bits; a.w = window_start;
+    a.n_mats = 0;
+    a.rowdep = 0;
+    a.rm = plain_rows(n);
+    const uint64_t n_tiles = ext > tile ? (1ull << (ext - tile)) : 1ull;
+    QSV_HIP(ctx, launch_pass(tile, a, n_tiles, ctx->stream), "probe pass");
+    return QSV_OK;
+}
+
 int64_t qsv_plan_describe(const qsv_circuit* c, int n_qubits, int batch, int inverse, int tile_log2,
                           char* buf, int64_t buf_bytes) {
     if (!check_circuit(c, n_qubits, nullptr) || batch < 1) return -1;

@@ -163,9 +163,10 @@ __device__ __forceinline__ unsigned to_sgpr(unsigned v) {
 // flip, a per-lane unitary, or the end), which the C++ loop handles before re-entering it.
 template <int T, bool PERLANE>
 __global__ __launch_bounds__(1 << (T - R)) void k_pass(const PassArgs a) {
-    // two planes (real, imaginary) of 2^T + 2^T/16 floats each; see the interpreter's generator
+    // two planes (real, imaginary) of 2^T floats each, XOR-swizzled; see the interpreter's
+    // generator.  The segment must start at LDS byte 0 (no static LDS in this kernel).
     extern __shared__ float lds[];
-    constexpr unsigned PLANE = (1u << T) + (1u << (T - 4));
+    constexpr unsigned PLANE = 1u << T;
     static_assert(PLANE * 4u < 65536u, "plane offset must fit the 16-bit LDS offset field");
     const unsigned lds_byte0 = (unsigned)(uintptr_t)(__attribute__((address_space(3))) float*)lds;
     const unsigned thr = threadIdx.x;
@@ -178,6 +179,7 @@ __global__ __launch_bounds__(1 << (T - R)) void k_pass(const PassArgs a) {
         return (u64)(tau & cmask) | ((u64)(tau >> c) << w);
     };
     if (tile_base >= a.total) return;  // padding tile (batch not a power of two): nothing to do
+    if (lds_byte0 != 0) return;        // cannot happen; the swizzled addressing relies on it
     // every element of the tile in range? (false only for the last tile of a ragged batch)
     const bool full = (tile_base | expand((1u << T) - 1u)) < a.total;
     // tiles never straddle a state row unless T > n, in which case rows are per lane
@@ -193,7 +195,6 @@ __global__ __launch_bounds__(1 << (T - R)) void k_pass(const PassArgs a) {
     const unsigned nonuni = to_sgpr(rows_uniform ? 0u : 1u);
     const unsigned sc_c = to_sgpr((unsigned)c), sc_w = to_sgpr((unsigned)w), sc_cmask = to_sgpr(cmask);
     const unsigned tblo = to_sgpr((unsigned)tile_base), tbhi = to_sgpr((unsigned)(tile_base >> 32));
-    const unsigned lds0 = to_sgpr(lds_byte0);
     unsigned opslo = to_sgpr((unsigned)(uintptr_t)a.ops), opshi = to_sgpr((unsigned)((u64)(uintptr_t)a.ops >> 32));
 
     QSV_16(QSV_DECL)
@@ -214,7 +215,7 @@ __global__ __launch_bounds__(1 << (T - R)) void k_pass(const PassArgs a) {
     }
     { const u64 nx = (u64)(uintptr_t)a.ops + 8; opslo = to_sgpr((unsigned)nx); opshi = to_sgpr((unsigned)(nx >> 32)); }
     unsigned e0lo = (unsigned)e0, e0hi = (unsigned)(e0 >> 32);
-    unsigned ldsb = lds_byte0 + (tau0 + (tau0 >> 4)) * 4u;
+    unsigned ldsb = (tau0 ^ ((tau0 >> 4) & 31u)) * 4u;
 
     for (;;) {
         {
@@ -226,7 +227,7 @@ __global__ __launch_bounds__(1 << (T - R)) void k_pass(const PassArgs a) {
                          : [mlo] "s"(mlo), [mhi] "s"(mhi), [olo] "s"(olo), [ohi] "s"(ohi),
                            [ovrid] "s"(ovr_id), [nonuni] "s"(nonuni), [thr] "v"(thr), [c] "s"(sc_c),
                            [w] "s"(sc_w), [cmask] "s"(sc_cmask), [tblo] "s"(tblo), [tbhi] "s"(tbhi),
-                           [lds0] "s"(lds0), [plane4] "n"(PLANE * 4u)
+                           [plane4] "n"(PLANE * 4u)
                          : QSV_GATE_LOOP_CLOBBERS);
         }
         // Operations are read as one aligned 64-bit word each and decoded with shifts.
@@ -794,7 +795,7 @@ inline unsigned blocks_for(u64 items, unsigned per) { return (unsigned)((items +
 // Launchers.
 template <int T>
 static hipError_t set_attr_for() {
-    const int bytes = 2 * ((1 << T) + (1 << (T - 4))) * 4;
+    const int bytes = 2 * (1 << T) * 4;
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(k_pass<T, false>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
     if (e != hipSuccess) return e;
@@ -815,8 +816,8 @@ static void launch_pass_t(const PassArgs& a, dim3 grid, size_t lds, hipStream_t 
 hipError_t launch_pass(int tile, const PassArgs& a, uint64_t n_tiles, hipStream_t st) {
     if (n_tiles == 0 || n_tiles > 0x7fffffffull) return hipErrorInvalidValue;
     const dim3 grid((unsigned)n_tiles);
-    // two padded planes of floats (see k_pass)
-    const size_t lds = 2 * (((size_t)1 << tile) + ((size_t)1 << (tile - 4))) * sizeof(float);
+    // two planes of floats (see k_pass)
+    const size_t lds = 2 * ((size_t)1 << tile) * sizeof(float);
     switch (tile) {
         case 10: launch_pass_t<10>(a, grid, lds, st); break;
         case 11: launch_pass_t<11>(a, grid, lds, st); break;
