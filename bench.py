@@ -32,6 +32,7 @@ def parse_args():
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--configs", default="4,3,2,1,0", help="which configs to time (4 is the headline)")
     ap.add_argument("--tile", type=int, default=0, help="force the pass kernel's tile_log2 (0 = default)")
+    ap.add_argument("--low", type=int, default=0, help="force the planner's minimum number of low index bits per tile")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
     ap.add_argument("--cpu-layers", type=int, default=4, help="layers of config 4 the oracle is timed on")
     return ap.parse_args()
@@ -77,6 +78,8 @@ def bench_c4(torch, qb, wl, args):
     ctx = qb.Context(n, 1)
     if args.tile:
         ctx.qsv_set_option("tile_log2", args.tile)
+    if args.low:
+        ctx.qsv_set_option("low_bits", args.low)
     circ = qb.circuit_from_spec(w.circuit)
     xd = torch.from_numpy(w.x).cuda()
     pd = torch.from_numpy(w.params).cuda()
@@ -117,6 +120,8 @@ def bench_c3(torch, qb, wl, args):
     ctx = qb.Context(n, B)
     if args.tile:
         ctx.qsv_set_option("tile_log2", args.tile)
+    if args.low:
+        ctx.qsv_set_option("low_bits", args.low)
     circ = qb.circuit_from_spec(w.circuit)
     xd = torch.from_numpy(w.x).cuda()
     pd = torch.from_numpy(w.params).cuda()
@@ -165,6 +170,8 @@ def bench_c2(torch, qb, wl, args):
     ctx = qb.Context(n, B)
     if args.tile:
         ctx.qsv_set_option("tile_log2", args.tile)
+    if args.low:
+        ctx.qsv_set_option("low_bits", args.low)
     circ = qb.circuit_from_spec(w.circuit)
     xd = torch.from_numpy(w.x).cuda()
     pd = torch.from_numpy(w.params).cuda()

@@ -13,9 +13,9 @@ in a register bit, CNOT with the control elsewhere in the index, and the transpo
 that moves the register run) and returns at the first operation of any other kind, leaving the
 operation pointer on it and no scalar load or LDS access in flight.
 
-LDS layout: two planes of 2^T floats (real, imaginary).  Element tau of a plane sits at index
-tau ^ ((tau >> 4) & 31): the XOR spreads every layout's 32 consecutive lanes over the 32 banks,
-costs no space (five 2^12 tiles fit one CU's 160 KiB), and, XOR being linear, the address of
+LDS layout: one plane of 2^T floats, used for the real parts and then for the imaginary parts of
+each transpose.  Element tau sits at index tau ^ ((tau >> 4) & 31): the XOR spreads every layout's 32 consecutive lanes over the 32 banks,
+costs no space, and, XOR being linear, the address of
 register element k is (lane's part) ^ (a scalar that depends on k and the layout): one v_xor.
 The dynamic LDS segment starts at byte 0 (the kernel has no static LDS), so no base is added.
 
@@ -185,30 +185,41 @@ def gen():
     emit("s_branch " + lab("next"))
 
 
-    # ---- transpose: move the register run from layout scur to layout a (field a of the word)
-    def elem_addr(k, tmp):
-        # tmp = ldsb ^ (swz(k << scur) * 4), swz(x) = x ^ ((x >> 4) & 31)
+    # ---- transpose: move the register run from layout scur to layout a (field a of the word).
+    # Real parts first, then imaginary parts, through the same 2^T floats of LDS: half the
+    # footprint of exchanging both at once, which is what lets more workgroups share a CU.
+    def elem_addr(k, tmp, base, sreg):
+        # tmp = base ^ (swz(k << s) * 4), swz(x) = x ^ ((x >> 4) & 31)
         if k == 0:
-            emit("v_mov_b32 %s, %%[ldsb]" % tmp)
+            emit("v_mov_b32 %s, %s" % (tmp, base))
             return
-        emit("s_lshl_b32 s84, %d, %%[scur]" % k)
+        emit("s_lshl_b32 s84, %d, %s" % (k, sreg))
         emit("s_lshr_b32 s85, s84, 4")
         emit("s_and_b32 s85, s85, 31")
         emit("s_xor_b32 s84, s84, s85")
         emit("s_lshl_b32 s84, s84, 2")
-        emit("v_xor_b32 %s, s84, %%[ldsb]" % tmp)
+        emit("v_xor_b32 %s, s84, %s" % (tmp, base))
+
+    tmps = ["%[t0]", "%[t1]", "%[t2]", "%[t3]"]
+
+    def write_plane(part, base, sreg):
+        for k in range(NR):
+            t = tmps[k % 4]
+            elem_addr(k, t, base, sreg)
+            emit("ds_write_b32 %s, %%[%s%d]" % (t, part, k))
+
+    def read_plane(part, base, sreg):
+        for k in range(NR):
+            t = tmps[k % 4]
+            elem_addr(k, t, base, sreg)
+            emit("ds_read_b32 %%[%s%d], %s" % (part, k, t))
 
     emit(lab("xp") + ":")
     prefetch_next_word()
+    emit("s_mov_b32 s86, %[scur]")                # old layout
+    emit("v_mov_b32 %[tc], %[ldsb]")              # old per-lane address part
     emit("s_barrier")                             # everybody is done reading the previous contents
-    tmps = ["%[t0]", "%[t1]", "%[t2]", "%[t3]"]
-    for k in range(NR):
-        t = tmps[k % 4]
-        elem_addr(k, t)
-        emit("ds_write_b32 %s, %%[r%d]" % (t, k))
-        emit("ds_write_b32 %s, %%[i%d] offset:%%[plane4]" % (t, k))
-    emit("s_waitcnt lgkmcnt(0)")
-    emit("s_barrier")
+    write_plane("r", "%[tc]", "s86")
     # new layout: tau = ((thr >> s) << (s + 4)) | (thr & ((1 << s) - 1))
     emit("s_mov_b32 %[scur], s83")
     emit("v_lshrrev_b32 %[t0], %[scur], %[thr]")
@@ -231,11 +242,15 @@ def gen():
     emit("s_sub_u32 s84, 32, %[w]")
     emit("v_lshrrev_b32 %[t1], s84, %[t1]")
     emit("v_or_b32 %[e0hi], %[tbhi], %[t1]")
-    for k in range(NR):
-        t = tmps[k % 4]
-        elem_addr(k, t)
-        emit("ds_read_b32 %%[r%d], %s" % (k, t))
-        emit("ds_read_b32 %%[i%d], %s offset:%%[plane4]" % (k, t))
+    emit("s_waitcnt lgkmcnt(0)")
+    emit("s_barrier")
+    read_plane("r", "%[ldsb]", "%[scur]")
+    emit("s_waitcnt lgkmcnt(0)")
+    emit("s_barrier")                             # all real parts are out: reuse the space
+    write_plane("i", "%[tc]", "s86")
+    emit("s_waitcnt lgkmcnt(0)")
+    emit("s_barrier")
+    read_plane("i", "%[ldsb]", "%[scur]")
     emit("s_branch " + lab("next"))               # the wait at the top covers the reads
 
     emit(lab("next") + ":")

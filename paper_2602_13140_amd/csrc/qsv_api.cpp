@@ -31,7 +31,7 @@ int ceil_log2_i64(int64_t v) {
 
 struct CachedPlan {
     qsv_circuit c;
-    int inverse, tile, grad;
+    int inverse, tile, grad, low;
     Plan plan;
     size_t dev_off;     // byte offset of the ops inside the ops region
     size_t order_off;   // int32[n_mats]: execution order -> (layer*n + qubit)
@@ -52,6 +52,7 @@ struct qsv_ctx {
     std::string err;
     int opt_tile = 0;
     int opt_naive = 0;
+    int opt_low = 0;
     std::vector<CachedPlan> cache;
     size_t ops_used = 0;
 };
@@ -123,7 +124,8 @@ qsv_status get_plan(qsv_ctx* ctx, const qsv_circuit& c, int64_t rows, int invers
                     const CachedPlan** out) {
     const int tile = ctx->opt_tile;
     for (const CachedPlan& cp : ctx->cache)
-        if (cp.inverse == inverse && cp.tile == tile && cp.grad == grad && same_circuit(cp.c, c)) {
+        if (cp.inverse == inverse && cp.tile == tile && cp.grad == grad && cp.low == ctx->opt_low &&
+            same_circuit(cp.c, c)) {
             *out = &cp;
             return QSV_OK;
         }
@@ -132,8 +134,9 @@ qsv_status get_plan(qsv_ctx* ctx, const qsv_circuit& c, int64_t rows, int invers
     cp.inverse = inverse;
     cp.tile = tile;
     cp.grad = grad;
+    cp.low = ctx->opt_low;
     // rows only matter through the tile default (small states pack several rows per tile)
-    cp.plan = build_plan(c, ctx->n, rows, inverse != 0, tile, grad != 0);
+    cp.plan = build_plan(c, ctx->n, rows, inverse != 0, tile, grad != 0, ctx->opt_low);
     if (!cp.plan.complete) return fail(ctx, QSV_ERR_UNSUPPORTED, "internal: pass planner failed");
     const size_t nm = cp.plan.mat_order.size();
     cp.exec_of.assign(nm, 0);
@@ -337,6 +340,12 @@ qsv_status qsv_set_option(qsv_ctx* ctx, const char* name, int64_t value) {
         if (value != 0 && (value < kMinTile || value > kMaxTile))
             return fail(ctx, QSV_ERR_INVALID_ARG, "tile_log2 must be 0 or in 10..13");
         ctx->opt_tile = (int)value;
+        return QSV_OK;
+    }
+    if (!strcmp(name, "low_bits")) {
+        if (value != 0 && (value < kLowBits || value > kMinTile))
+            return fail(ctx, QSV_ERR_INVALID_ARG, "low_bits must be 0 or in 4..10");
+        ctx->opt_low = (int)value;
         return QSV_OK;
     }
     if (!strcmp(name, "naive")) {

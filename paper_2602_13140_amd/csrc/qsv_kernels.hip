@@ -163,11 +163,9 @@ __device__ __forceinline__ unsigned to_sgpr(unsigned v) {
 // flip, a per-lane unitary, or the end), which the C++ loop handles before re-entering it.
 template <int T, bool PERLANE>
 __global__ __launch_bounds__(1 << (T - R)) void k_pass(const PassArgs a) {
-    // two planes (real, imaginary) of 2^T floats each, XOR-swizzled; see the interpreter's
-    // generator.  The segment must start at LDS byte 0 (no static LDS in this kernel).
+    // one XOR-swizzled plane of 2^T floats (real parts, then imaginary parts of a transpose); see
+    // the interpreter's generator.  The segment must start at LDS byte 0 (no static LDS here).
     extern __shared__ float lds[];
-    constexpr unsigned PLANE = 1u << T;
-    static_assert(PLANE * 4u < 65536u, "plane offset must fit the 16-bit LDS offset field");
     const unsigned lds_byte0 = (unsigned)(uintptr_t)(__attribute__((address_space(3))) float*)lds;
     const unsigned thr = threadIdx.x;
     const u64 tb = blockIdx.x;
@@ -226,8 +224,7 @@ __global__ __launch_bounds__(1 << (T - R)) void k_pass(const PassArgs a) {
                            [scur] "+s"(scur), [ldsb] "+v"(ldsb), [e0lo] "+v"(e0lo), [e0hi] "+v"(e0hi)
                          : [mlo] "s"(mlo), [mhi] "s"(mhi), [olo] "s"(olo), [ohi] "s"(ohi),
                            [ovrid] "s"(ovr_id), [nonuni] "s"(nonuni), [thr] "v"(thr), [c] "s"(sc_c),
-                           [w] "s"(sc_w), [cmask] "s"(sc_cmask), [tblo] "s"(tblo), [tbhi] "s"(tbhi),
-                           [plane4] "n"(PLANE * 4u)
+                           [w] "s"(sc_w), [cmask] "s"(sc_cmask), [tblo] "s"(tblo), [tbhi] "s"(tbhi)
                          : QSV_GATE_LOOP_CLOBBERS);
         }
         // Operations are read as one aligned 64-bit word each and decoded with shifts.
@@ -795,7 +792,7 @@ inline unsigned blocks_for(u64 items, unsigned per) { return (unsigned)((items +
 // Launchers.
 template <int T>
 static hipError_t set_attr_for() {
-    const int bytes = 2 * (1 << T) * 4;
+    const int bytes = (1 << T) * 4;
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(k_pass<T, false>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
     if (e != hipSuccess) return e;
@@ -816,8 +813,8 @@ static void launch_pass_t(const PassArgs& a, dim3 grid, size_t lds, hipStream_t 
 hipError_t launch_pass(int tile, const PassArgs& a, uint64_t n_tiles, hipStream_t st) {
     if (n_tiles == 0 || n_tiles > 0x7fffffffull) return hipErrorInvalidValue;
     const dim3 grid((unsigned)n_tiles);
-    // two planes of floats (see k_pass)
-    const size_t lds = 2 * ((size_t)1 << tile) * sizeof(float);
+    // one plane of floats (see k_pass)
+    const size_t lds = ((size_t)1 << tile) * sizeof(float);
     switch (tile) {
         case 10: launch_pass_t<10>(a, grid, lds, st); break;
         case 11: launch_pass_t<11>(a, grid, lds, st); break;

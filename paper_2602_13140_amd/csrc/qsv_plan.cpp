@@ -243,7 +243,8 @@ int default_tile(int n, int64_t batch) {
     return std::max(kMinTile, std::min(13, ext));
 }
 
-Plan build_plan(const qsv_circuit& c, int n, int64_t batch, bool inverse, int tile_log2, bool grad) {
+Plan build_plan(const qsv_circuit& c, int n, int64_t batch, bool inverse, int tile_log2, bool grad,
+                int min_low_bits) {
     Plan p;
     p.n = n;
     p.ext_bits = n + ceil_log2(batch);
@@ -258,7 +259,7 @@ Plan build_plan(const qsv_circuit& c, int n, int64_t batch, bool inverse, int ti
     const std::vector<Gate> G = lower(c, n, inverse);
     std::vector<uint8_t> done(G.size(), 0);
     size_t first = 0;
-    const int cmin = std::min(kLowBits, t);
+    const int cmin = std::min(std::max(kLowBits, min_low_bits), t);
     while (first < G.size()) {
         Geom bestg{t, cmin, cmin};
         int best = -1;

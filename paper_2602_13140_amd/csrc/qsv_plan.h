@@ -64,7 +64,8 @@ bool check_circuit(const qsv_circuit* c, int n, std::string* why);
 
 // tile_log2 = 0 picks the default.  grad = true marks every rotation matrix as row-dependent
 // (a shifted circuit overrides one matrix per state row).
-Plan build_plan(const qsv_circuit& c, int n, int64_t batch, bool inverse, int tile_log2, bool grad);
+Plan build_plan(const qsv_circuit& c, int n, int64_t batch, bool inverse, int tile_log2, bool grad,
+                int min_low_bits = 0);
 
 std::string describe_plan(const Plan& p);
 
