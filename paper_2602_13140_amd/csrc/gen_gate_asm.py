@@ -13,8 +13,8 @@ in a register bit, CNOT with the control elsewhere in the index, and the transpo
 that moves the register run) and returns at the first operation of any other kind, leaving the
 operation pointer on it and no scalar load or LDS access in flight.
 
-LDS layout: one plane of 2^T floats, used for the real parts and then for the imaginary parts of
-each transpose.  Element tau sits at index tau ^ ((tau >> 4) & 31): the XOR spreads every layout's 32 consecutive lanes over the 32 banks,
+LDS layout: two planes of 2^T floats (real, imaginary).  Element tau of a plane sits at index
+tau ^ ((tau >> 4) & 31): the XOR spreads every layout's 32 consecutive lanes over the 32 banks,
 costs no space, and, XOR being linear, the address of
 register element k is (lane's part) ^ (a scalar that depends on k and the layout): one v_xor.
 The dynamic LDS segment starts at byte 0 (the kernel has no static LDS), so no base is added.
@@ -24,6 +24,7 @@ matrix in execution order, so consecutive unitaries read consecutive 32-byte mat
 next one can be prefetched (the table is padded by one entry for the last prefetch).
 
 Fixed scalar registers (declared as clobbers):
+  s[52:67] address offsets of the 16 register elements in layout s68 (s68 = -1: not loaded)
   s[70:71] address whose matrix sits in the prefetch buffer (0 = none)
   s[72:79] prefetch buffer            s[80:81] current operation word
   s82 kind   s83 field a              s[84:85] scratch / saved exec
@@ -35,7 +36,7 @@ import os
 R = 4
 NR = 1 << R
 OP_XPOSE, OP_U, OP_CX_REG, OP_CX_DYN = 2, 3, 4, 5
-FIRST_SGPR, LAST_SGPR = 70, 99
+FIRST_SGPR, LAST_SGPR = 52, 99
 
 
 def u_pair(a, b):
@@ -79,6 +80,7 @@ def gen():
     emit("s_mov_b32 s96, %[opslo]")
     emit("s_mov_b32 s97, %[opshi]")
     emit("s_mov_b64 s[70:71], 0")
+    emit("s_mov_b32 s68, -1")
     emit("s_load_dwordx2 s[98:99], s[96:97], 0x0")
     emit(lab("top") + ":")
     emit("s_waitcnt lgkmcnt(0)")                  # next word and prefetched matrix have landed
@@ -186,42 +188,37 @@ def gen():
 
 
     # ---- transpose: move the register run from layout scur to layout a (field a of the word).
-    # Real parts first, then imaginary parts, through the same 2^T floats of LDS: half the
-    # footprint of exchanging both at once, which is what lets more workgroups share a CU.
-    def elem_addr(k, tmp, base, sreg):
-        # tmp = base ^ (swz(k << s) * 4), swz(x) = x ^ ((x >> 4) & 31)
-        if k == 0:
-            emit("v_mov_b32 %s, %s" % (tmp, base))
-            return
-        emit("s_lshl_b32 s84, %d, %s" % (k, sreg))
-        emit("s_lshr_b32 s85, s84, 4")
-        emit("s_and_b32 s85, s85, 31")
-        emit("s_xor_b32 s84, s84, s85")
-        emit("s_lshl_b32 s84, s84, 2")
-        emit("v_xor_b32 %s, s84, %s" % (tmp, base))
+    # The per-element address offsets of a layout come from a 16-dword table row (one scalar
+    # load); s[52:67] holds the row of the layout named in s68 (-1: none, the compiler may have
+    # used these registers since the block was last left).
+    def load_offsets(sreg):
+        emit("s_lshl_b32 s84, %s, 6" % sreg)
+        emit("s_add_u32 s86, %[tablo], s84")
+        emit("s_addc_u32 s87, %[tabhi], 0")
+        emit("s_load_dwordx16 s[52:67], s[86:87], 0x0")
+        emit("s_mov_b32 s68, %s" % sreg)
 
     tmps = ["%[t0]", "%[t1]", "%[t2]", "%[t3]"]
-
-    def write_plane(part, base, sreg):
-        for k in range(NR):
-            t = tmps[k % 4]
-            elem_addr(k, t, base, sreg)
-            emit("ds_write_b32 %s, %%[%s%d]" % (t, part, k))
-
-    def read_plane(part, base, sreg):
-        for k in range(NR):
-            t = tmps[k % 4]
-            elem_addr(k, t, base, sreg)
-            emit("ds_read_b32 %%[%s%d], %s" % (part, k, t))
-
     emit(lab("xp") + ":")
     prefetch_next_word()
-    emit("s_mov_b32 s86, %[scur]")                # old layout
-    emit("v_mov_b32 %[tc], %[ldsb]")              # old per-lane address part
-    emit("s_barrier")                             # everybody is done reading the previous contents
-    write_plane("r", "%[tc]", "s86")
-    # new layout: tau = ((thr >> s) << (s + 4)) | (thr & ((1 << s) - 1))
+    emit("s_cmp_eq_u32 s68, %[scur]")
+    emit("s_cbranch_scc1 " + lab("xphave"))
+    load_offsets("%[scur]")
+    emit("s_waitcnt lgkmcnt(0)")
+    emit(lab("xphave") + ":")
+    emit("s_bfe_u32 s84, s80, 0x80018")           # c: barrier before the writes
+    emit("s_cmp_eq_u32 s84, 0")
+    emit("s_cbranch_scc1 " + lab("xpw"))
+    emit("s_barrier")
+    emit(lab("xpw") + ":")
+    for k in range(NR):
+        t = tmps[k % 4]
+        emit("v_xor_b32 %s, s%d, %%[ldsb]" % (t, 52 + k))
+        emit("ds_write2st64_b32 %s, %%[r%d], %%[i%d] offset1:%%[pl64]" % (t, k, k))
+    # new layout: its offsets first (they arrive while the lane's own part is computed)
     emit("s_mov_b32 %[scur], s83")
+    load_offsets("%[scur]")
+    # tau = ((thr >> s) << (s + 4)) | (thr & ((1 << s) - 1))
     emit("v_lshrrev_b32 %[t0], %[scur], %[thr]")
     emit("s_add_u32 s84, %[scur], 4")
     emit("v_lshlrev_b32 %[t0], s84, %[t0]")
@@ -242,15 +239,17 @@ def gen():
     emit("s_sub_u32 s84, 32, %[w]")
     emit("v_lshrrev_b32 %[t1], s84, %[t1]")
     emit("v_or_b32 %[e0hi], %[tbhi], %[t1]")
-    emit("s_waitcnt lgkmcnt(0)")
+    emit("s_waitcnt lgkmcnt(0)")                  # own writes are in LDS, new offsets are here
+    emit("s_bfe_u32 s84, s80, 0x80010")           # b: the exchange crosses wavefronts
+    emit("s_cmp_eq_u32 s84, 0")
+    emit("s_cbranch_scc1 " + lab("xpr"))
     emit("s_barrier")
-    read_plane("r", "%[ldsb]", "%[scur]")
-    emit("s_waitcnt lgkmcnt(0)")
-    emit("s_barrier")                             # all real parts are out: reuse the space
-    write_plane("i", "%[tc]", "s86")
-    emit("s_waitcnt lgkmcnt(0)")
-    emit("s_barrier")
-    read_plane("i", "%[ldsb]", "%[scur]")
+    emit(lab("xpr") + ":")
+    for k in range(NR):
+        t = tmps[k % 4]
+        emit("v_xor_b32 %s, s%d, %%[ldsb]" % (t, 52 + k))
+        emit("ds_read_b32 %%[r%d], %s" % (k, t))
+        emit("ds_read_b32 %%[i%d], %s offset:%%[plane4]" % (k, t))
     emit("s_branch " + lab("next"))               # the wait at the top covers the reads
 
     emit(lab("next") + ":")

@@ -155,6 +155,21 @@ __device__ __forceinline__ unsigned to_sgpr(unsigned v) {
 #define QSV_DECL(k) float vr##k, vi##k;
 #define QSV_RV(k) [r##k] "+v"(vr##k), [i##k] "+v"(vi##k),
 
+// Byte offsets of register element k in layout s inside an LDS plane, as XORed onto the lane's
+// own address part: swz(k << s) * 4 with swz(x) = x ^ ((x >> 4) & 31).  One 64-byte row per layout.
+struct XpOffsets {
+    unsigned v[12][16];
+    constexpr XpOffsets() : v() {
+        for (int s = 0; s < 12; ++s)
+            for (int k = 0; k < 16; ++k) {
+                const unsigned x = (unsigned)k << s;
+                v[s][k] = (x ^ ((x >> 4) & 31u)) * 4u;
+            }
+    }
+};
+__device__ __attribute__((aligned(64))) const XpOffsets k_xp_tab = XpOffsets();
+#define k_xp_off k_xp_tab.v
+
 // PERLANE = true is the variant for tiles that hold several state rows (n < T): it adds the
 // per-lane-matrix path; the main variant keeps its operation loop minimal.
 //
@@ -163,9 +178,11 @@ __device__ __forceinline__ unsigned to_sgpr(unsigned v) {
 // flip, a per-lane unitary, or the end), which the C++ loop handles before re-entering it.
 template <int T, bool PERLANE>
 __global__ __launch_bounds__(1 << (T - R)) void k_pass(const PassArgs a) {
-    // one XOR-swizzled plane of 2^T floats (real parts, then imaginary parts of a transpose); see
-    // the interpreter's generator.  The segment must start at LDS byte 0 (no static LDS here).
+    // two XOR-swizzled planes (real, imaginary) of 2^T floats each; see the interpreter's
+    // generator.  The segment must start at LDS byte 0 (no static LDS in this kernel).
     extern __shared__ float lds[];
+    constexpr unsigned PLANE = 1u << T;
+    static_assert(PLANE * 4u < 65536u && PLANE / 64u < 256u, "plane offsets must fit the LDS offset fields");
     const unsigned lds_byte0 = (unsigned)(uintptr_t)(__attribute__((address_space(3))) float*)lds;
     const unsigned thr = threadIdx.x;
     const u64 tb = blockIdx.x;
@@ -193,6 +210,8 @@ __global__ __launch_bounds__(1 << (T - R)) void k_pass(const PassArgs a) {
     const unsigned nonuni = to_sgpr(rows_uniform ? 0u : 1u);
     const unsigned sc_c = to_sgpr((unsigned)c), sc_w = to_sgpr((unsigned)w), sc_cmask = to_sgpr(cmask);
     const unsigned tblo = to_sgpr((unsigned)tile_base), tbhi = to_sgpr((unsigned)(tile_base >> 32));
+    const u64 tab = (u64)(uintptr_t)&k_xp_off[0][0];
+    const unsigned tablo = to_sgpr((unsigned)tab), tabhi = to_sgpr((unsigned)(tab >> 32));
     unsigned opslo = to_sgpr((unsigned)(uintptr_t)a.ops), opshi = to_sgpr((unsigned)((u64)(uintptr_t)a.ops >> 32));
 
     QSV_16(QSV_DECL)
@@ -224,7 +243,9 @@ __global__ __launch_bounds__(1 << (T - R)) void k_pass(const PassArgs a) {
                            [scur] "+s"(scur), [ldsb] "+v"(ldsb), [e0lo] "+v"(e0lo), [e0hi] "+v"(e0hi)
                          : [mlo] "s"(mlo), [mhi] "s"(mhi), [olo] "s"(olo), [ohi] "s"(ohi),
                            [ovrid] "s"(ovr_id), [nonuni] "s"(nonuni), [thr] "v"(thr), [c] "s"(sc_c),
-                           [w] "s"(sc_w), [cmask] "s"(sc_cmask), [tblo] "s"(tblo), [tbhi] "s"(tbhi)
+                           [w] "s"(sc_w), [cmask] "s"(sc_cmask), [tblo] "s"(tblo), [tbhi] "s"(tbhi),
+                           [tablo] "s"(tablo), [tabhi] "s"(tabhi), [plane4] "n"(PLANE * 4u),
+                           [pl64] "n"(PLANE / 64u)
                          : QSV_GATE_LOOP_CLOBBERS);
         }
         // Operations are read as one aligned 64-bit word each and decoded with shifts.
@@ -792,7 +813,7 @@ inline unsigned blocks_for(u64 items, unsigned per) { return (unsigned)((items +
 // Launchers.
 template <int T>
 static hipError_t set_attr_for() {
-    const int bytes = (1 << T) * 4;
+    const int bytes = 2 * (1 << T) * 4;
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(k_pass<T, false>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
     if (e != hipSuccess) return e;
@@ -813,8 +834,8 @@ static void launch_pass_t(const PassArgs& a, dim3 grid, size_t lds, hipStream_t 
 hipError_t launch_pass(int tile, const PassArgs& a, uint64_t n_tiles, hipStream_t st) {
     if (n_tiles == 0 || n_tiles > 0x7fffffffull) return hipErrorInvalidValue;
     const dim3 grid((unsigned)n_tiles);
-    // one plane of floats (see k_pass)
-    const size_t lds = ((size_t)1 << tile) * sizeof(float);
+    // two planes of floats (see k_pass)
+    const size_t lds = 2 * ((size_t)1 << tile) * sizeof(float);
     switch (tile) {
         case 10: launch_pass_t<10>(a, grid, lds, st); break;
         case 11: launch_pass_t<11>(a, grid, lds, st); break;

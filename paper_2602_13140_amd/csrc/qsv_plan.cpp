@@ -100,6 +100,8 @@ int scan_round(const Geom& gm, int s, int n, const std::vector<Gate>& G,
     return score;
 }
 
+void mark_transposes(std::vector<Op>& ops, size_t begin);
+
 void emit_round(const Geom& gm, int s, const std::vector<Gate>& G, const std::vector<int>& exec,
                 bool rowdep, std::vector<Op>* ops, std::vector<int32_t>* mat_order) {
     bool last_cz = false;
@@ -208,12 +210,31 @@ int run_pass(const Geom& gm, int n, const std::vector<Gate>& G, std::vector<uint
         commit(s, best_exec);
     }
     if (s < smin_io) {
-        s = smax;
+        s = smin_io;  // lowest layout that stores coalesced; it also keeps the exchange inside wavefronts
         if (ops) ops->push_back({OP_XPOSE, (uint8_t)s, 0, 0, 0});
     }
     if (ops) ops->push_back({OP_END, 0, 0, 0, 0});
     if (n_exec) *n_exec = cnt;
     return total;
+}
+
+// Lanes hold the six lowest tile bits outside the register run, so while the run stays below tile
+// bit 10 every wavefront keeps the same upper tile bits and exchanges only inside its own part of
+// LDS: such a transpose needs no workgroup barrier.
+void mark_transposes(std::vector<Op>& ops, size_t begin) {
+    int s = -1;
+    bool any_before = false, prev_cross = false;
+    for (size_t i = begin; i < ops.size(); ++i) {
+        Op& o = ops[i];
+        if (o.kind == OP_LOAD) { s = o.a; continue; }
+        if (o.kind != OP_XPOSE) continue;
+        const bool cross = (s + kRegBits > 10) || (o.a + kRegBits > 10);
+        o.b = cross ? 1 : 0;
+        o.c = (any_before && (cross || prev_cross)) ? 1 : 0;
+        any_before = true;
+        prev_cross = cross;
+        s = o.a;
+    }
 }
 
 int ceil_log2(int64_t v) {
@@ -282,6 +303,7 @@ Plan build_plan(const qsv_circuit& c, int n, int64_t batch, bool inverse, int ti
         ps.op_begin = (int)p.ops.size();
         int ne = 0;
         run_pass(bestg, n, G, done, first, rowdep, &p.ops, &p.mat_order, &ne);
+        mark_transposes(p.ops, (size_t)ps.op_begin);
         ps.op_count = (int)p.ops.size() - ps.op_begin;
         ps.n_gates = ne;
         p.passes.push_back(ps);
@@ -305,7 +327,7 @@ std::string describe_plan(const Plan& p) {
             switch (o.kind) {
                 case OP_END: snprintf(buf, sizeof buf, " E"); break;
                 case OP_LOAD: snprintf(buf, sizeof buf, " L%d", o.a); break;
-                case OP_XPOSE: snprintf(buf, sizeof buf, " T%d", o.a); break;
+                case OP_XPOSE: snprintf(buf, sizeof buf, " T%d:%d", o.a, o.b | (o.c << 1)); break;
                 case OP_U: snprintf(buf, sizeof buf, " U%d:%d:%d", o.a, p.mat_order[o.arg], o.b); break;
                 case OP_CX_REG: snprintf(buf, sizeof buf, " X%d:%d", o.a, o.b); break;
                 case OP_CX_DYN: snprintf(buf, sizeof buf, " D%d:%d:%d", o.a, o.b, o.c); break;

@@ -23,7 +23,10 @@ constexpr int kLowBits = 4;      // c: 2^4 complex64 = one 128-byte line per con
 enum OpKind : uint8_t {
     OP_END = 0,     // store the tile from the current layout
     OP_LOAD = 1,    // a = run start s: load the tile from global memory in layout s
-    OP_XPOSE = 2,   // a = new run start: move the register run through LDS
+    OP_XPOSE = 2,   // a = new run start: move the register run through LDS.  b = 1 if the exchange
+                    // crosses wavefronts (a run above tile bit 9 is involved) and needs a workgroup
+                    // barrier between writes and reads; c = 1 if a barrier is needed before the
+                    // writes (an earlier exchange of this pass may still be read by other wavefronts)
     OP_U = 3,       // a = register bit j, b = 1 if the matrix depends on the state row,
                     // arg = index of the matrix in execution order (see Plan::mat_order)
     OP_CX_REG = 4,  // a = target register bit, b = control register bit

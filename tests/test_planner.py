@@ -70,10 +70,19 @@ def replay(text, n, rows, L, rot, ent, reupload, params, feats, inverse, st):
         for tok in ops:
             kind = tok[0]
             if kind in "LT":
-                s = int(tok[1:])
+                s_prev = s
+                s = int(tok[1:].split(":")[0])
                 assert 0 <= s <= t - R
                 if kind == "L":
                     assert s >= min(4, t - R)
+                    seen_xpose, prev_cross = False, False
+                else:
+                    # barrier flags: bit 0 = exchange crosses wavefronts, bit 1 = barrier first
+                    flags = int(tok.split(":")[1])
+                    cross = s_prev + R > 10 or s + R > 10
+                    assert (flags & 1) == int(cross)
+                    assert (flags >> 1) == int(seen_xpose and (cross or prev_cross))
+                    seen_xpose, prev_cross = True, cross
             elif kind == "U":
                 j, mat, rowdep = (int(x) for x in tok[1:].split(":"))
                 q = bit(s + j)
