@@ -23,6 +23,9 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
+# HBM bytes per pass-kernel launch from rocprofv3 FETCH_SIZE / WRITE_SIZE (profiles/), each scaled by
+# what the same counter reads for the load/store-only probe pass of known size; None = not measured.
+TRAFFIC_BYTES_PER_LAUNCH = {"c4": None, "c3": None}
 
 
 def parse_args():
@@ -33,6 +36,10 @@ def parse_args():
     ap.add_argument("--configs", default="4,3,2,1,0", help="which configs to time (4 is the headline)")
     ap.add_argument("--tile", type=int, default=0, help="force the pass kernel's tile_log2 (0 = default)")
     ap.add_argument("--low", type=int, default=0, help="force the planner's minimum number of low index bits per tile")
+    ap.add_argument("--probe", action="store_true",
+                    help="only time the load/store-only probe pass on config 4's state (streaming ceiling "
+                         "of the pass kernel's access pattern; also the known-size copy used to scale "
+                         "rocprofv3's FETCH_SIZE/WRITE_SIZE counters)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
     ap.add_argument("--cpu-layers", type=int, default=4, help="layers of config 4 the oracle is timed on")
     return ap.parse_args()
@@ -233,6 +240,33 @@ def bench_c0(torch, qb, wl, args):
             "ms_per_step": ms, "updates": updates, "updates_per_s": updates / (ms * 1e-3)}
 
 
+def probe(torch, qb, args):
+    """Load/store-only passes over a 2^26-amplitude state (512 MiB read + 512 MiB written per
+    launch), for a few tile geometries (low bits c, window start w)."""
+    n = 26
+    ctx = qb.Context(n, 1)
+    if args.tile:
+        ctx.qsv_set_option("tile_log2", args.tile)
+    tile = args.tile or 12
+    ctx.state.normal_()
+    nbytes = 2 * 8 * (1 << n)
+    out = []
+    for c, w in ((tile, tile), (8, n - (tile - 8)), (6, n - (tile - 6)), (5, n - (tile - 5)), (4, 10), (4, n - (tile - 4))):
+        for _ in range(3):
+            ctx.qsv_probe_pass(c, w, 0)
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        for _ in range(args.steps):
+            ctx.qsv_probe_pass(c, w, 0)
+        b.record()
+        torch.cuda.synchronize()
+        ms = a.elapsed_time(b) / args.steps
+        out.append({"low_bits": c, "window_start": w, "ms": ms, "gbs": nbytes / ms / 1e6})
+    ctx.close()
+    return {"probe": "load/store-only pass, 26 qubits", "bytes_per_launch": nbytes, "tile_log2": tile,
+            "geometries": out}
+
+
 def cpu_baseline(wl, w4, layers):
     """The oracle as it stands, timed on this machine's host cores on a bounded sample of config 4:
     encode + the first `layers` layers on the same 2^26-amplitude state."""
@@ -264,10 +298,20 @@ def main():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(1)
     qb.load()  # fails loudly if libqsv.so is missing: there is no fallback path
+    if args.probe:
+        print(json.dumps(probe(torch, qb, args)))
+        return
     which = [int(c) for c in args.configs.split(",") if c != ""]
     others = {}
-    c4, w4 = bench_c4(torch, qb, wl, args)
-    if 3 in which:
+    w4 = None
+    if 4 in which or not which:
+        head, w4 = bench_c4(torch, qb, wl, args)
+    elif which[0] == 3:
+        head = bench_c3(torch, qb, wl, args)     # profiling aid: config 3 as the only workload
+    else:
+        print("bench.py: --configs must include 4 (the headline) or start with 3", file=sys.stderr)
+        sys.exit(2)
+    if 3 in which and w4 is not None:
         others["c3"] = bench_c3(torch, qb, wl, args)
     if 2 in which:
         others["c2"] = bench_c2(torch, qb, wl, args)
@@ -276,19 +320,19 @@ def main():
     if 0 in which:
         others["c0"] = bench_c0(torch, qb, wl, args)
     cpu = None
-    if not args.no_cpu:
+    if not args.no_cpu and w4 is not None:
         cpu = cpu_baseline(wl, w4, args.cpu_layers)
     out = {
         "metric": "gate-amplitude updates/sec (batched, complex64) + achieved HBM GB/s vs peak",
-        "value": c4["updates_per_s"], "unit": "updates/s", "n_gpus": 1, "steps": args.steps,
-        "warmup": args.warmup, "ms_per_step": c4["ms_per_step"], "higher_is_better": True,
+        "value": head["updates_per_s"], "unit": "updates/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": head["ms_per_step"], "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
-        "config": {"workload": c4["workload"], "tile_log2": args.tile, "passes": c4["passes"],
-                   "apply_ms": c4["apply_ms"], "apply_updates_per_s": c4["apply_updates_per_s"]},
-        "roofline": {"bound": "hbm", "kernel": "k_pass (fused gate pass)", "achieved": c4["pass_gbs"],
-                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": c4["pass_gbs"] / HBM_PEAK_GBS,
-                     "traffic": None, "bytes_per_launch": c4["pass_bytes"],
-                     "avg_launch_ms": c4["pass_avg_ms"]},
+        "config": {"workload": head["workload"], "tile_log2": args.tile, "passes": head["passes"],
+                   "apply_ms": head["apply_ms"], "apply_updates_per_s": head["apply_updates_per_s"]},
+        "roofline": {"bound": "hbm", "kernel": "k_pass (fused gate pass)", "achieved": head["pass_gbs"],
+                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": head["pass_gbs"] / HBM_PEAK_GBS,
+                     "traffic": TRAFFIC_BYTES_PER_LAUNCH.get(head["workload"][:2]),
+                     "bytes_per_launch": head["pass_bytes"], "avg_launch_ms": head["pass_avg_ms"]},
         "cpu_baseline": cpu,
         "others": others,
     }

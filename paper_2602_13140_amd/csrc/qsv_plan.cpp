@@ -261,7 +261,8 @@ bool check_circuit(const qsv_circuit* c, int n, std::string* why) {
 
 int default_tile(int n, int64_t batch) {
     const int ext = n + ceil_log2(batch);
-    return std::max(kMinTile, std::min(13, ext));
+    // 2^12 amplitudes per tile: five workgroups share a CU's LDS, which measured best
+    return std::max(kMinTile, std::min(12, ext));
 }
 
 Plan build_plan(const qsv_circuit& c, int n, int64_t batch, bool inverse, int tile_log2, bool grad,
