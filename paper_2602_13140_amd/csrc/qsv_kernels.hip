@@ -220,7 +220,17 @@ __global__ __launch_bounds__(1 << (T - R)) void k_pass(const PassArgs a) {
     unsigned scur = to_sgpr((first.x >> 8) & 0xffu);
     const unsigned tau0 = ((thr >> scur) << (scur + R)) | (thr & ((1u << scur) - 1u));
     u64 e0 = tile_base | expand(tau0);
-    if (full) {
+    // A tile's index bits span less than 2^29 elements unless n > 28: then an element's address is
+    // a scalar base (tile and register part) plus one 32-bit per-lane byte offset, which costs no
+    // vector arithmetic per element.
+    const bool off32 = (expand((1u << T) - 1u) >> 29) == 0;
+    if (full && off32) {
+        const unsigned lane_byte = (unsigned)expand(tau0) * 8u;
+#define QSV_LD(k) { const char* bp = (const char*)(a.state + (tile_base | expand((unsigned)k << scur))); \
+                    const float2 v = *(const float2*)(bp + lane_byte); vr##k = v.x; vi##k = v.y; }
+        QSV_16(QSV_LD)
+#undef QSV_LD
+    } else if (full) {
 #define QSV_LD(k) { const float2 v = a.state[e0 | expand((unsigned)k << scur)]; vr##k = v.x; vi##k = v.y; }
         QSV_16(QSV_LD)
 #undef QSV_LD
@@ -288,7 +298,13 @@ __global__ __launch_bounds__(1 << (T - R)) void k_pass(const PassArgs a) {
         }
         { const u64 nx = opp + 8; opslo = (unsigned)nx; opshi = (unsigned)(nx >> 32); }
     }
-    if (full) {
+    if (full && off32) {
+        const unsigned lane_byte = (unsigned)(e0 ^ tile_base) * 8u;   // the lane's own index bits
+#define QSV_ST(k) { char* bp = (char*)(a.state + (tile_base | expand((unsigned)k << scur))); \
+                    *(float2*)(bp + lane_byte) = make_float2(vr##k, vi##k); }
+        QSV_16(QSV_ST)
+#undef QSV_ST
+    } else if (full) {
 #define QSV_ST(k) a.state[e0 | expand((unsigned)k << scur)] = make_float2(vr##k, vi##k);
         QSV_16(QSV_ST)
 #undef QSV_ST
