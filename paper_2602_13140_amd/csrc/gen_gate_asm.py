@@ -9,8 +9,8 @@ merge point; one asm block with tied operands and its own scalar dispatch does n
 lets the next operation word and the next matrix be fetched while the current gate computes.
 
 The block executes consecutive operations (2x2 unitary on a register bit, CNOT with the control
-in a register bit, CNOT with the control elsewhere in the index, and the transpose through LDS
-that moves the register run) and returns at the first operation of any other kind, leaving the
+in a register bit, CNOT with the control elsewhere in the index, the three forms of CZ sign flips,
+and the transpose through LDS that moves the register run) and returns at the first operation of any other kind, leaving the
 operation pointer on it and no scalar load or LDS access in flight.
 
 LDS layout: two planes of 2^T floats (real, imaginary).  Element tau of a plane sits at index
@@ -35,7 +35,7 @@ import os
 
 R = 4
 NR = 1 << R
-OP_XPOSE, OP_U, OP_CX_REG, OP_CX_DYN = 2, 3, 4, 5
+OP_XPOSE, OP_U, OP_CX_REG, OP_CX_DYN, OP_CZ_REG, OP_CZ_MIX, OP_CZ_LANE = 2, 3, 4, 5, 6, 7, 8
 FIRST_SGPR, LAST_SGPR = 52, 99
 
 
@@ -95,6 +95,12 @@ def gen():
     emit("s_cbranch_scc1 " + lab("cxd"))
     emit("s_cmp_eq_u32 s82, %d" % OP_XPOSE)
     emit("s_cbranch_scc1 " + lab("xp"))
+    emit("s_cmp_eq_u32 s82, %d" % OP_CZ_REG)
+    emit("s_cbranch_scc1 " + lab("zr"))
+    emit("s_cmp_eq_u32 s82, %d" % OP_CZ_MIX)
+    emit("s_cbranch_scc1 " + lab("zm"))
+    emit("s_cmp_eq_u32 s82, %d" % OP_CZ_LANE)
+    emit("s_cbranch_scc1 " + lab("zl"))
     emit("s_branch " + lab("exit"))
 
     # ---- 2x2 unitary on register bit a; matrix = (arg == ovrid) ? *ovr : mbase[arg]
@@ -186,6 +192,71 @@ def gen():
     emit("s_mov_b64 exec, s[84:85]")
     emit("s_branch " + lab("next"))
 
+
+
+    def flip(part, k):
+        return "v_xor_b32 %%[%s%d], 0x80000000, %%[%s%d]" % (part, k, part, k)
+
+    # ---- CZ between register bits a < b: the amplitudes with both bits set change sign
+    emit(lab("zr") + ":")
+    prefetch_next_word()
+    emit("s_bfe_u32 s84, s80, 0x80010")
+    emit("s_lshl_b32 s85, s83, 2")
+    emit("s_add_u32 s84, s84, s85")
+    pairs = [(ja, jb) for ja in range(R) for jb in range(ja + 1, R)]
+    for ja, jb in pairs:
+        emit("s_cmp_eq_u32 s84, %d" % (ja * 4 + jb))
+        emit("s_cbranch_scc1 " + lab("zr%d%d" % (ja, jb)))
+    emit("s_branch " + lab("next"))               # unknown combination: no-op (never planned)
+    for ja, jb in pairs:
+        emit(lab("zr%d%d" % (ja, jb)) + ":")
+        for k in range(NR):
+            if (k >> ja) & 1 and (k >> jb) & 1:
+                emit(flip("r", k))
+                emit(flip("i", k))
+        emit("s_branch " + lab("next"))
+
+    # ---- CZ between register bit a and index bit b outside the run: lanes whose bit b is set
+    # flip the sign of the amplitudes with register bit a set
+    emit(lab("zm") + ":")
+    prefetch_next_word()
+    emit("s_bfe_u32 s86, s80, 0x80010")
+    emit("s_lshl_b64 s[84:85], 1, s86")
+    emit("v_and_b32 %[tc], s84, %[e0lo]")
+    emit("v_and_b32 %[t0], s85, %[e0hi]")
+    emit("v_or_b32 %[tc], %[tc], %[t0]")
+    emit("v_cmp_ne_u32 vcc, 0, %[tc]")
+    emit("s_and_saveexec_b64 s[84:85], vcc")
+    emit("s_cbranch_execz " + lab("zdone"))
+    for j in range(R - 1):
+        emit("s_cmp_eq_u32 s83, %d" % j)
+        emit("s_cbranch_scc1 " + lab("zm%d" % j))
+    for j in reversed(range(R)):
+        emit(lab("zm%d" % j) + ":")
+        for k in range(NR):
+            if (k >> j) & 1:
+                emit(flip("r", k))
+                emit(flip("i", k))
+        emit("s_branch " + lab("zdone"))
+
+    # ---- CZ rungs (mask in arg, bit q = rung (q, q+1)) between index bits outside the run: one
+    # sign per lane, parity of popcount(e0 & (e0 >> 1) & mask); the mask lies below bit 31
+    emit(lab("zl") + ":")
+    prefetch_next_word()
+    emit("v_lshrrev_b32 %[t0], 1, %[e0lo]")
+    emit("v_and_b32 %[t0], %[t0], %[e0lo]")
+    emit("v_and_b32 %[t0], s81, %[t0]")
+    emit("v_bcnt_u32_b32 %[t0], %[t0], 0")
+    emit("v_and_b32 %[t0], 1, %[t0]")
+    emit("v_cmp_ne_u32 vcc, 0, %[t0]")
+    emit("s_and_saveexec_b64 s[84:85], vcc")
+    emit("s_cbranch_execz " + lab("zdone"))
+    for k in range(NR):
+        emit(flip("r", k))
+        emit(flip("i", k))
+    emit(lab("zdone") + ":")
+    emit("s_mov_b64 exec, s[84:85]")
+    emit("s_branch " + lab("next"))
 
     # ---- transpose: move the register run from layout scur to layout a (field a of the word).
     # The per-element address offsets of a layout come from a 16-dword table row (one scalar

@@ -174,8 +174,8 @@ __device__ __attribute__((aligned(64))) const XpOffsets k_xp_tab = XpOffsets();
 // per-lane-matrix path; the main variant keeps its operation loop minimal.
 //
 // Structure of a pass: the first operation loads the tile; the assembly interpreter then runs
-// gates and LDS transposes in place until it meets an operation it does not handle (a CZ sign
-// flip, a per-lane unitary, or the end), which the C++ loop handles before re-entering it.
+// gates, sign flips and LDS transposes in place until it meets an operation it does not handle
+// (a per-lane unitary, or the end), which the C++ loop handles before re-entering it.
 template <int T, bool PERLANE>
 __global__ __launch_bounds__(1 << (T - R)) void k_pass(const PassArgs a) {
     // two XOR-swizzled planes (real, imaginary) of 2^T floats each; see the interpreter's
@@ -264,15 +264,7 @@ __global__ __launch_bounds__(1 << (T - R)) void k_pass(const PassArgs a) {
         const unsigned kind = word.x & 0xffu;
         const int arg = (int)word.y;
         e0 = ((u64)e0hi << 32) | e0lo;
-        if (kind == OP_CZ) {
-            const u64 mask = (u64)(unsigned)arg;
-#define QSV_CZ(k) { const u64 kk = e0 | expand((unsigned)k << scur); \
-                    const unsigned flip = (unsigned)(__popcll(kk & (kk >> 1) & mask) & 1) << 31; \
-                    vr##k = __uint_as_float(__float_as_uint(vr##k) ^ flip); \
-                    vi##k = __uint_as_float(__float_as_uint(vi##k) ^ flip); }
-            QSV_16(QSV_CZ)
-#undef QSV_CZ
-        } else if (PERLANE && kind == OP_U) {
+        if (PERLANE && kind == OP_U) {
             // several rows per tile and row-dependent matrices: per-lane matrix.  The run lies
             // inside the qubit bits (planner rule), so a lane's 16 amplitudes share one row.
             float m[8], xr[NR], xi[NR];

@@ -104,19 +104,34 @@ void mark_transposes(std::vector<Op>& ops, size_t begin);
 
 void emit_round(const Geom& gm, int s, const std::vector<Gate>& G, const std::vector<int>& exec,
                 bool rowdep, std::vector<Op>* ops, std::vector<int32_t>* mat_order) {
-    bool last_cz = false;
+    bool last_lane = false;
+    auto in_run = [&](int q) {
+        if (!gm.local(q)) return false;
+        const int p = gm.pos(q);
+        return p >= s && p < s + kRegBits;
+    };
     for (int i : exec) {
         const Gate& g = G[i];
         if (g.kind == G_CZ) {
-            if (last_cz) {
+            // rungs commute, so each goes to the cheapest form for where its two qubits sit
+            const bool r0 = in_run(g.q0), r1 = in_run(g.q1);
+            if (r0 && r1) {
+                const int ja = gm.pos(g.q0) - s, jb = gm.pos(g.q1) - s;
+                ops->push_back({OP_CZ_REG, (uint8_t)std::min(ja, jb), (uint8_t)std::max(ja, jb), 0, 0});
+                last_lane = false;
+            } else if (r0 || r1) {
+                const int qr = r0 ? g.q0 : g.q1, qo = r0 ? g.q1 : g.q0;
+                ops->push_back({OP_CZ_MIX, (uint8_t)(gm.pos(qr) - s), (uint8_t)qo, 0, 0});
+                last_lane = false;
+            } else if (last_lane) {
                 ops->back().arg |= (int32_t)(1u << g.q0);
             } else {
-                ops->push_back({OP_CZ, 0, 0, 0, (int32_t)(1u << g.q0)});
-                last_cz = true;
+                ops->push_back({OP_CZ_LANE, 0, 0, 0, (int32_t)(1u << g.q0)});
+                last_lane = true;
             }
             continue;
         }
-        last_cz = false;
+        last_lane = false;
         const int jt = gm.pos(g.q0) - s;
         if (g.kind == G_U) {
             ops->push_back({OP_U, (uint8_t)jt, (uint8_t)(rowdep ? 1 : 0), 0, (int32_t)mat_order->size()});
@@ -332,7 +347,9 @@ std::string describe_plan(const Plan& p) {
                 case OP_U: snprintf(buf, sizeof buf, " U%d:%d:%d", o.a, p.mat_order[o.arg], o.b); break;
                 case OP_CX_REG: snprintf(buf, sizeof buf, " X%d:%d", o.a, o.b); break;
                 case OP_CX_DYN: snprintf(buf, sizeof buf, " D%d:%d:%d", o.a, o.b, o.c); break;
-                case OP_CZ: snprintf(buf, sizeof buf, " Z%x", (unsigned)o.arg); break;
+                case OP_CZ_REG: snprintf(buf, sizeof buf, " Zr%d:%d", o.a, o.b); break;
+                case OP_CZ_MIX: snprintf(buf, sizeof buf, " Zm%d:%d", o.a, o.b); break;
+                case OP_CZ_LANE: snprintf(buf, sizeof buf, " Zl%x", (unsigned)o.arg); break;
                 default: snprintf(buf, sizeof buf, " ?"); break;
             }
             s += buf;

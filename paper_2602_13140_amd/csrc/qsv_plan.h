@@ -32,7 +32,10 @@ enum OpKind : uint8_t {
     OP_CX_REG = 4,  // a = target register bit, b = control register bit
     OP_CX_DYN = 5,  // a = target register bit, b = control index bit (extended index),
                     // c = 1 if the control bit is the same for a whole wavefront
-    OP_CZ = 6       // arg = rung mask: bit q set -> CZ(q, q+1)
+    OP_CZ_REG = 6,  // CZ between register bits a and b: sign flip of the 4 amplitudes with both set
+    OP_CZ_MIX = 7,  // CZ between register bit a and index bit b outside the run (lane-dependent)
+    OP_CZ_LANE = 8  // arg = rung mask (bit q -> CZ(q, q+1)), all rungs between index bits outside
+                    // the run: one lane-dependent sign for all 16 amplitudes
 };
 
 struct Op {

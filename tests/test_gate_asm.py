@@ -7,7 +7,7 @@ import re
 from paper_2602_13140_amd.csrc import gen_gate_asm as g
 
 INTENDED_FALLTHROUGH = {"L_top", "L_uhave", "L_unopf", "L_u3", "L_d3", "L_cxdone", "L_xphave", "L_xpw",
-                        "L_xpr"}
+                        "L_xpr", "L_zm3", "L_zdone"}
 
 
 def test_no_unintended_fall_through():

@@ -120,11 +120,26 @@ def replay(text, n, rows, L, rot, ent, reupload, params, feats, inverse, st):
                 st = apply_cnot(st, n, qc, qt)
                 n_gates += 1
             elif kind == "Z":
-                mask = int(tok[1:], 16)
+                form, body = tok[1], tok[2:]
+                run_bits = [bit(s + j) for j in range(R)]
+                if form == "r":                       # both qubits in the register run
+                    ja, jb = (int(x) for x in body.split(":"))
+                    assert 0 <= ja < jb < R
+                    rungs = [(run_bits[ja], run_bits[jb])]
+                elif form == "m":                     # one in the run, one elsewhere
+                    ja, qo = (int(x) for x in body.split(":"))
+                    assert qo not in run_bits and qo < n
+                    rungs = [(run_bits[ja], qo)]
+                else:                                 # mask of rungs (q, q+1), none in the run
+                    assert form == "l"
+                    mask = int(body, 16)
+                    rungs = [(q, q + 1) for q in range(n) if (mask >> q) & 1]
+                    assert all(q0 not in run_bits and q1 not in run_bits for q0, q1 in rungs)
                 k = np.arange(1 << n)
-                sign = 1 - 2 * (np.array([bin(v).count("1") for v in (k & (k >> 1) & mask)]) & 1)
-                st = st * sign[None, :]
-                n_gates += bin(mask).count("1")
+                for q0, q1 in rungs:
+                    assert abs(q0 - q1) == 1 and max(q0, q1) < n       # a ladder rung
+                    st = st * (1 - 2 * (((k >> q0) & 1) & ((k >> q1) & 1)))[None, :]
+                    n_gates += 1
             else:
                 assert tok == "E"
         assert sum(1 for o in ops if o == "E") == 1
