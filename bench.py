@@ -36,12 +36,13 @@ def parse_args():
     ap.add_argument("--configs", default="4,3,2,1,0", help="which configs to time (4 is the headline)")
     ap.add_argument("--tile", type=int, default=0, help="force the pass kernel's tile_log2 (0 = default)")
     ap.add_argument("--low", type=int, default=0, help="force the planner's minimum number of low index bits per tile")
+    ap.add_argument("--planes", type=int, default=0, help="force the pass kernel's LDS planes (1 or 2; 0 = default)")
     ap.add_argument("--probe", action="store_true",
                     help="only time the load/store-only probe pass on config 4's state (streaming ceiling "
                          "of the pass kernel's access pattern; also the known-size copy used to scale "
                          "rocprofv3's FETCH_SIZE/WRITE_SIZE counters)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
-    ap.add_argument("--cpu-layers", type=int, default=4, help="layers of config 4 the oracle is timed on")
+    ap.add_argument("--cpu-layers", type=int, default=20, help="layers of config 4 the oracle is timed on")
     return ap.parse_args()
 
 
@@ -87,6 +88,8 @@ def bench_c4(torch, qb, wl, args):
         ctx.qsv_set_option("tile_log2", args.tile)
     if args.low:
         ctx.qsv_set_option("low_bits", args.low)
+    if args.planes:
+        ctx.qsv_set_option("lds_planes", args.planes)
     circ = qb.circuit_from_spec(w.circuit)
     xd = torch.from_numpy(w.x).cuda()
     pd = torch.from_numpy(w.params).cuda()
@@ -129,6 +132,8 @@ def bench_c3(torch, qb, wl, args):
         ctx.qsv_set_option("tile_log2", args.tile)
     if args.low:
         ctx.qsv_set_option("low_bits", args.low)
+    if args.planes:
+        ctx.qsv_set_option("lds_planes", args.planes)
     circ = qb.circuit_from_spec(w.circuit)
     xd = torch.from_numpy(w.x).cuda()
     pd = torch.from_numpy(w.params).cuda()
@@ -179,6 +184,8 @@ def bench_c2(torch, qb, wl, args):
         ctx.qsv_set_option("tile_log2", args.tile)
     if args.low:
         ctx.qsv_set_option("low_bits", args.low)
+    if args.planes:
+        ctx.qsv_set_option("lds_planes", args.planes)
     circ = qb.circuit_from_spec(w.circuit)
     xd = torch.from_numpy(w.x).cuda()
     pd = torch.from_numpy(w.params).cuda()

@@ -159,7 +159,11 @@ int64_t qsv_plan_describe(const qsv_circuit* c, int n_qubits, int batch, int inv
 qsv_status qsv_probe_pass(qsv_ctx* ctx, int low_bits, int window_start, int transposes);
 
 /* Testing/tuning knobs: tile_log2 in 10..13 (0 = default) forces the tile size of the fused pass
- * kernel; naive = 1 routes qsv_apply_layers through the one-gate-per-launch kernels. */
+ * kernel; low_bits in 4..10 (0 = default) forces the planner's minimum number of low index bits
+ * per tile; lds_planes = 1 (default) moves real and imaginary parts through one LDS plane one
+ * after the other, 2 through two planes at once; naive = 1 routes qsv_apply_layers through the
+ * one-gate-per-launch kernels.  Unknown names and values out of range return
+ * QSV_ERR_INVALID_ARG. */
 qsv_status qsv_set_option(qsv_ctx* ctx, const char* name, int64_t value);
 
 #ifdef __cplusplus

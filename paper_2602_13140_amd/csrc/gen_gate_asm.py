@@ -24,7 +24,9 @@ matrix in execution order, so consecutive unitaries read consecutive 32-byte mat
 next one can be prefetched (the table is padded by one entry for the last prefetch).
 
 Fixed scalar registers (declared as clobbers):
+  s[36:51] one-plane transposes: address offsets of the layout being moved to
   s[52:67] address offsets of the 16 register elements in layout s68 (s68 = -1: not loaded)
+  s69 one-plane transposes: the exchange crosses wavefronts
   s[70:71] address whose matrix sits in the prefetch buffer (0 = none)
   s[72:79] prefetch buffer            s[80:81] current operation word
   s82 kind   s83 field a              s[84:85] scratch / saved exec
@@ -36,32 +38,57 @@ import os
 R = 4
 NR = 1 << R
 OP_XPOSE, OP_U, OP_CX_REG, OP_CX_DYN, OP_CZ_REG, OP_CZ_MIX, OP_CZ_LANE = 2, 3, 4, 5, 6, 7, 8
-FIRST_SGPR, LAST_SGPR = 52, 99
+# The map above is written with the block's registers at s36..s99; SHIFT moves the whole block
+# down (a kernel limited to 96 scalar registers, i.e. 8 waves per SIMD, then still has s0..s23
+# for the compiler; measured: no faster than the 7 waves the unlimited kernel gets).
+SHIFT = 12
+FIRST_SGPR, LAST_SGPR = 36 - SHIFT, 99 - SHIFT
 
 
-def u_pair(a, b):
+def u_pair(a, b, variant="g"):
     """(r_a,i_a) has the target bit 0, (r_b,i_b) has it 1; matrix m0..m7 = s88..s95 =
     (m00r, m00i, m01r, m01i, m10r, m10i, m11r, m11i).  Four interleaved chains; the last step of
-    each overwrites an input that is dead by then."""
+    each overwrites an input that is dead by then.  Variants leave out the products with
+    imaginary parts that are stored as exact zeros: "g" none (16 instructions), "a" m00i (14),
+    "r" m00i and m01i (first row real, 12), "c" m00i and m10i (first column real, 12)."""
     ra, ia, rb, ib = "%%[r%d]" % a, "%%[i%d]" % a, "%%[r%d]" % b, "%%[i%d]" % b
     t = ["%[t0]", "%[t1]", "%[t2]", "%[t3]"]
+    mul = lambda d, m, x: "v_mul_f32 %s, %s, %s" % (d, m, x)
+    fma = lambda d, m, x, acc: "v_fma_f32 %s, %s, %s, %s" % (d, m, x, acc)
+    if variant == "g":
+        return [
+            mul(t[0], "s88", ra), mul(t[1], "s89", ra), mul(t[2], "s92", ra), mul(t[3], "s93", ra),
+            fma(t[0], "-s89", ia, t[0]), fma(t[1], "s88", ia, t[1]),
+            fma(t[2], "-s93", ia, t[2]), fma(t[3], "s92", ia, t[3]),
+            fma(t[0], "s90", rb, t[0]), fma(t[1], "s91", rb, t[1]),
+            fma(t[2], "s94", rb, t[2]), fma(t[3], "s95", rb, t[3]),
+            fma(ra, "-s91", ib, t[0]), fma(ia, "s90", ib, t[1]),
+            fma(rb, "-s95", ib, t[2]), fma(ib, "s94", ib, t[3]),
+        ]
+    if variant == "a":
+        return [
+            mul(t[0], "s88", ra), mul(t[1], "s88", ia), mul(t[2], "s92", ra), mul(t[3], "s93", ra),
+            fma(t[2], "-s93", ia, t[2]), fma(t[3], "s92", ia, t[3]),
+            fma(t[0], "s90", rb, t[0]), fma(t[1], "s91", rb, t[1]),
+            fma(t[2], "s94", rb, t[2]), fma(t[3], "s95", rb, t[3]),
+            fma(ra, "-s91", ib, t[0]), fma(ia, "s90", ib, t[1]),
+            fma(rb, "-s95", ib, t[2]), fma(ib, "s94", ib, t[3]),
+        ]
+    if variant == "r":
+        return [
+            mul(t[0], "s88", ra), mul(t[1], "s88", ia), mul(t[2], "s92", ra), mul(t[3], "s93", ra),
+            fma(t[2], "-s93", ia, t[2]), fma(t[3], "s92", ia, t[3]),
+            fma(t[2], "s94", rb, t[2]), fma(t[3], "s95", rb, t[3]),
+            fma(ra, "s90", rb, t[0]), fma(ia, "s90", ib, t[1]),
+            fma(rb, "-s95", ib, t[2]), fma(ib, "s94", ib, t[3]),
+        ]
+    assert variant == "c"
     return [
-        "v_mul_f32 %s, s88, %s" % (t[0], ra),
-        "v_mul_f32 %s, s89, %s" % (t[1], ra),
-        "v_mul_f32 %s, s92, %s" % (t[2], ra),
-        "v_mul_f32 %s, s93, %s" % (t[3], ra),
-        "v_fma_f32 %s, -s89, %s, %s" % (t[0], ia, t[0]),
-        "v_fma_f32 %s, s88, %s, %s" % (t[1], ia, t[1]),
-        "v_fma_f32 %s, -s93, %s, %s" % (t[2], ia, t[2]),
-        "v_fma_f32 %s, s92, %s, %s" % (t[3], ia, t[3]),
-        "v_fma_f32 %s, s90, %s, %s" % (t[0], rb, t[0]),
-        "v_fma_f32 %s, s91, %s, %s" % (t[1], rb, t[1]),
-        "v_fma_f32 %s, s94, %s, %s" % (t[2], rb, t[2]),
-        "v_fma_f32 %s, s95, %s, %s" % (t[3], rb, t[3]),
-        "v_fma_f32 %s, -s91, %s, %s" % (ra, ib, t[0]),
-        "v_fma_f32 %s, s90, %s, %s" % (ia, ib, t[1]),
-        "v_fma_f32 %s, -s95, %s, %s" % (rb, ib, t[2]),
-        "v_fma_f32 %s, s94, %s, %s" % (ib, ib, t[3]),
+        mul(t[0], "s88", ra), mul(t[1], "s88", ia), mul(t[2], "s92", ra), mul(t[3], "s92", ia),
+        fma(t[0], "s90", rb, t[0]), fma(t[1], "s91", rb, t[1]),
+        fma(t[2], "s94", rb, t[2]), fma(t[3], "s95", rb, t[3]),
+        fma(ra, "-s91", ib, t[0]), fma(ia, "s90", ib, t[1]),
+        fma(rb, "-s95", ib, t[2]), fma(ib, "s94", ib, t[3]),
     ]
 
 
@@ -69,7 +96,8 @@ def swap_pair(a, b):
     return ["v_swap_b32 %%[r%d], %%[r%d]" % (a, b), "v_swap_b32 %%[i%d], %%[i%d]" % (a, b)]
 
 
-def gen():
+def gen(planes=2):
+    assert planes in (1, 2)
     L = []
     emit = L.append
     lab = lambda name: "L_%s_%%=" % name
@@ -138,16 +166,25 @@ def gen():
     emit("s_load_dwordx8 s[72:79], s[70:71], 0x0")
     emit(lab("unopf") + ":")
     prefetch_next_word()
-    for j in range(R - 1):
-        emit("s_cmp_eq_u32 s83, %d" % j)
-        emit("s_cbranch_scc1 " + lab("u%d" % j))
-    for j in reversed(range(R)):
-        emit(lab("u%d" % j) + ":")
-        for i in range(NR):
-            if i & (1 << j):
-                continue
-            L.extend(u_pair(i, i | (1 << j)))
-        emit("s_branch " + lab("next"))
+    # pick the multiply sequence from the zeros the matrix builder stored
+    emit("s_cmp_lg_u32 s89, 0")
+    emit("s_cbranch_scc1 " + lab("ug"))
+    emit("s_cmp_eq_u32 s91, 0")
+    emit("s_cbranch_scc1 " + lab("ur"))
+    emit("s_cmp_eq_u32 s93, 0")
+    emit("s_cbranch_scc1 " + lab("uc"))
+    for variant in "argc":
+        emit(lab("u" + variant) + ":")
+        for j in range(R - 1):
+            emit("s_cmp_eq_u32 s83, %d" % j)
+            emit("s_cbranch_scc1 " + lab("u%s%d" % (variant, j)))
+        for j in reversed(range(R)):
+            emit(lab("u%s%d" % (variant, j)) + ":")
+            for i in range(NR):
+                if i & (1 << j):
+                    continue
+                L.extend(u_pair(i, i | (1 << j), variant))
+            emit("s_branch " + lab("next"))
 
     # ---- CNOT, control = register bit b, target = register bit a
     emit(lab("cxr") + ":")
@@ -270,6 +307,31 @@ def gen():
         emit("s_mov_b32 s68, %s" % sreg)
 
     tmps = ["%[t0]", "%[t1]", "%[t2]", "%[t3]"]
+
+    def lane_part(dst):
+        """dst = byte address part of the lane in layout scur; also refreshes e0."""
+        # tau = ((thr >> s) << (s + 4)) | (thr & ((1 << s) - 1))
+        emit("v_lshrrev_b32 %[t0], %[scur], %[thr]")
+        emit("s_add_u32 s84, %[scur], 4")
+        emit("v_lshlrev_b32 %[t0], s84, %[t0]")
+        emit("s_lshl_b32 s85, 1, %[scur]")
+        emit("s_sub_u32 s85, s85, 1")
+        emit("v_and_b32 %[t1], s85, %[thr]")
+        emit("v_or_b32 %[t0], %[t0], %[t1]")          # t0 = tau of the lane (register bits zero)
+        emit("v_lshrrev_b32 %[t1], 4, %[t0]")
+        emit("v_and_b32 %[t1], 31, %[t1]")
+        emit("v_xor_b32 %[t1], %[t1], %[t0]")
+        emit("v_lshlrev_b32 " + dst + ", 2, %[t1]")   # swz(tau) * 4
+        # extended index of the lane: e0 = tile_base | (tau & cmask) | ((tau >> c) << w), w < 32
+        emit("v_lshrrev_b32 %[t1], %[c], %[t0]")
+        emit("v_and_b32 %[t2], %[cmask], %[t0]")
+        emit("v_lshlrev_b32 %[t3], %[w], %[t1]")
+        emit("v_or_b32 %[t2], %[t2], %[t3]")
+        emit("v_or_b32 %[e0lo], %[tblo], %[t2]")
+        emit("s_sub_u32 s84, 32, %[w]")
+        emit("v_lshrrev_b32 %[t1], s84, %[t1]")
+        emit("v_or_b32 %[e0hi], %[tbhi], %[t1]")
+
     emit(lab("xp") + ":")
     prefetch_next_word()
     emit("s_cmp_eq_u32 s68, %[scur]")
@@ -282,46 +344,74 @@ def gen():
     emit("s_cbranch_scc1 " + lab("xpw"))
     emit("s_barrier")
     emit(lab("xpw") + ":")
-    for k in range(NR):
-        t = tmps[k % 4]
-        emit("v_xor_b32 %s, s%d, %%[ldsb]" % (t, 52 + k))
-        emit("ds_write2st64_b32 %s, %%[r%d], %%[i%d] offset1:%%[pl64]" % (t, k, k))
-    # new layout: its offsets first (they arrive while the lane's own part is computed)
-    emit("s_mov_b32 %[scur], s83")
-    load_offsets("%[scur]")
-    # tau = ((thr >> s) << (s + 4)) | (thr & ((1 << s) - 1))
-    emit("v_lshrrev_b32 %[t0], %[scur], %[thr]")
-    emit("s_add_u32 s84, %[scur], 4")
-    emit("v_lshlrev_b32 %[t0], s84, %[t0]")
-    emit("s_lshl_b32 s85, 1, %[scur]")
-    emit("s_sub_u32 s85, s85, 1")
-    emit("v_and_b32 %[t1], s85, %[thr]")
-    emit("v_or_b32 %[t0], %[t0], %[t1]")          # t0 = tau of the lane (register bits zero)
-    emit("v_lshrrev_b32 %[t1], 4, %[t0]")
-    emit("v_and_b32 %[t1], 31, %[t1]")
-    emit("v_xor_b32 %[t1], %[t1], %[t0]")
-    emit("v_lshlrev_b32 %[ldsb], 2, %[t1]")       # ldsb = swz(tau) * 4
-    # extended index of the lane: e0 = tile_base | (tau & cmask) | ((tau >> c) << w), w < 32
-    emit("v_lshrrev_b32 %[t1], %[c], %[t0]")
-    emit("v_and_b32 %[t2], %[cmask], %[t0]")
-    emit("v_lshlrev_b32 %[t3], %[w], %[t1]")
-    emit("v_or_b32 %[t2], %[t2], %[t3]")
-    emit("v_or_b32 %[e0lo], %[tblo], %[t2]")
-    emit("s_sub_u32 s84, 32, %[w]")
-    emit("v_lshrrev_b32 %[t1], s84, %[t1]")
-    emit("v_or_b32 %[e0hi], %[tbhi], %[t1]")
-    emit("s_waitcnt lgkmcnt(0)")                  # own writes are in LDS, new offsets are here
-    emit("s_bfe_u32 s84, s80, 0x80010")           # b: the exchange crosses wavefronts
-    emit("s_cmp_eq_u32 s84, 0")
-    emit("s_cbranch_scc1 " + lab("xpr"))
-    emit("s_barrier")
-    emit(lab("xpr") + ":")
-    for k in range(NR):
-        t = tmps[k % 4]
-        emit("v_xor_b32 %s, s%d, %%[ldsb]" % (t, 52 + k))
-        emit("ds_read_b32 %%[r%d], %s" % (k, t))
-        emit("ds_read_b32 %%[i%d], %s offset:%%[plane4]" % (k, t))
-    emit("s_branch " + lab("next"))               # the wait at the top covers the reads
+    if planes == 2:
+        for k in range(NR):
+            t = tmps[k % 4]
+            emit("v_xor_b32 %s, s%d, %%[ldsb]" % (t, 52 + k))
+            emit("ds_write2st64_b32 %s, %%[r%d], %%[i%d] offset1:%%[pl64]" % (t, k, k))
+        # new layout: its offsets first (they arrive while the lane's own part is computed)
+        emit("s_mov_b32 %[scur], s83")
+        load_offsets("%[scur]")
+        lane_part("%[ldsb]")
+        emit("s_waitcnt lgkmcnt(0)")              # own writes are in LDS, new offsets are here
+        emit("s_bfe_u32 s84, s80, 0x80010")       # b: the exchange crosses wavefronts
+        emit("s_cmp_eq_u32 s84, 0")
+        emit("s_cbranch_scc1 " + lab("xpr"))
+        emit("s_barrier")
+        emit(lab("xpr") + ":")
+        for k in range(NR):
+            t = tmps[k % 4]
+            emit("v_xor_b32 %s, s%d, %%[ldsb]" % (t, 52 + k))
+            emit("ds_read_b32 %%[r%d], %s" % (k, t))
+            emit("ds_read_b32 %%[i%d], %s offset:%%[plane4]" % (k, t))
+        emit("s_branch " + lab("next"))           # the wait at the top covers the reads
+    else:
+        # One plane: real parts go through it first, then the imaginary parts.  The offsets of the
+        # new layout sit in s[36:51] until the end, the lane's new address part in ldsn.  A
+        # wavefront's LDS operations execute in order, so the steps need a wait and a barrier
+        # between them only when the exchange crosses wavefronts (flag b, kept in s69).
+        def sync(name):
+            emit("s_cmp_eq_u32 s69, 0")
+            emit("s_cbranch_scc1 " + lab(name))
+            emit("s_waitcnt lgkmcnt(0)")
+            emit("s_barrier")
+            emit(lab(name) + ":")
+
+        def writes(part):
+            for k in range(NR):
+                t = tmps[k % 4]
+                emit("v_xor_b32 %s, s%d, %%[ldsb]" % (t, 52 + k))
+                emit("ds_write_b32 %s, %%[%s%d]" % (t, part, k))
+
+        def reads(part):
+            for k in range(NR):
+                t = tmps[k % 4]
+                emit("v_xor_b32 %s, s%d, %%[ldsn]" % (t, 36 + k))
+                emit("ds_read_b32 %%[%s%d], %s" % (part, k, t))
+
+        emit("s_bfe_u32 s69, s80, 0x80010")
+        writes("r")
+        emit("s_mov_b32 %[scur], s83")
+        emit("s_lshl_b32 s84, %[scur], 6")
+        emit("s_add_u32 s86, %[tablo], s84")
+        emit("s_addc_u32 s87, %[tabhi], 0")
+        emit("s_load_dwordx16 s[36:51], s[86:87], 0x0")
+        lane_part("%[ldsn]")
+        emit("s_waitcnt lgkmcnt(0)")              # new offsets are here (and own writes landed)
+        emit("s_cmp_eq_u32 s69, 0")
+        emit("s_cbranch_scc1 " + lab("xpr"))
+        emit("s_barrier")
+        emit(lab("xpr") + ":")
+        reads("r")
+        sync("xpw2")
+        writes("i")
+        sync("xpr2")
+        reads("i")
+        for k in range(0, NR, 2):                 # the new layout's offsets become the current ones
+            emit("s_mov_b64 s[%d:%d], s[%d:%d]" % (52 + k, 53 + k, 36 + k, 37 + k))
+        emit("s_mov_b32 s68, %[scur]")
+        emit("v_mov_b32 %[ldsb], %[ldsn]")
+        emit("s_branch " + lab("next"))           # the wait at the top covers the reads
 
     emit(lab("next") + ":")
     emit("s_add_u32 s96, s96, 8")
@@ -330,19 +420,28 @@ def gen():
     emit(lab("exit") + ":")                       # reached right after the wait: nothing in flight
     emit("s_mov_b32 %[opslo], s96")
     emit("s_mov_b32 %[opshi], s97")
-    return L
+    return [_shifted(ln) for ln in L]
+
+
+def _shifted(line):
+    """Renumbers the block's scalar registers (written as s36..s99) down by SHIFT."""
+    import re
+    line = re.sub(r"\bs\[(\d+):(\d+)\]",
+                  lambda m: "s[%d:%d]" % (int(m.group(1)) - SHIFT, int(m.group(2)) - SHIFT), line)
+    return re.sub(r"\bs(\d+)\b", lambda m: "s%d" % (int(m.group(1)) - SHIFT), line)
 
 
 def render():
-    lines = gen()
     out = ["// Generated by gen_gate_asm.py -- do not edit by hand.",
            "// Inline-assembly gate interpreter of the fused pass kernel; see the generator for the",
-           "// register map and the reason it is assembly.",
-           "#pragma once",
-           "#define QSV_GATE_LOOP_ASM \\"]
-    for ln in lines:
-        out.append('    "%s\\n\\t" \\' % ln)
-    out.append('    ""')
+           "// register map and the reason it is assembly.  _2P: transposes through two LDS planes",
+           "// (real, imaginary) at once; _1P: through one plane, real parts first.",
+           "#pragma once"]
+    for planes in (2, 1):
+        out.append("#define QSV_GATE_LOOP_ASM_%dP \\" % planes)
+        for ln in gen(planes):
+            out.append('    "%s\\n\\t" \\' % ln)
+        out.append('    ""')
     regs = ", ".join('"s%d"' % i for i in range(FIRST_SGPR, LAST_SGPR + 1))
     out.append("#define QSV_GATE_LOOP_CLOBBERS %s, \"vcc\", \"scc\", \"memory\"" % regs)
     return "\n".join(out) + "\n"

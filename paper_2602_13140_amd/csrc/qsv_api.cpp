@@ -53,6 +53,7 @@ struct qsv_ctx {
     int opt_tile = 0;
     int opt_naive = 0;
     int opt_low = 0;
+    int opt_planes = 1;
     std::vector<CachedPlan> cache;
     size_t ops_used = 0;
 };
@@ -259,7 +260,7 @@ qsv_status run_circuit(qsv_ctx* ctx, const qsv_circuit& c, const Prepared& pr, f
         a.n_mats = n_mats;
         a.rowdep = c.reupload;
         a.rm = rm;
-        QSV_HIP(ctx, launch_pass(pl.tile, a, n_tiles, ctx->stream), "fused pass");
+        QSV_HIP(ctx, launch_pass(pl.tile, ctx->opt_planes, a, n_tiles, ctx->stream), "fused pass");
     }
     return QSV_OK;
 }
@@ -346,6 +347,12 @@ qsv_status qsv_set_option(qsv_ctx* ctx, const char* name, int64_t value) {
         if (value != 0 && (value < kLowBits || value > kMinTile))
             return fail(ctx, QSV_ERR_INVALID_ARG, "low_bits must be 0 or in 4..10");
         ctx->opt_low = (int)value;
+        return QSV_OK;
+    }
+    if (!strcmp(name, "lds_planes")) {
+        if (value != 1 && value != 2)
+            return fail(ctx, QSV_ERR_INVALID_ARG, "lds_planes must be 1 or 2");
+        ctx->opt_planes = (int)value;
         return QSV_OK;
     }
     if (!strcmp(name, "naive")) {
@@ -592,7 +599,7 @@ qsv_status qsv_probe_pass(qsv_ctx* ctx, int low_bits, int window_start, int tran
     a.rowdep = 0;
     a.rm = plain_rows(n);
     const uint64_t n_tiles = ext > tile ? (1ull << (ext - tile)) : 1ull;
-    QSV_HIP(ctx, launch_pass(tile, a, n_tiles, ctx->stream), "probe pass");
+    QSV_HIP(ctx, launch_pass(tile, ctx->opt_planes, a, n_tiles, ctx->stream), "probe pass");
     return QSV_OK;
 }
 

@@ -38,7 +38,7 @@ struct PassArgs {
     RowMap rm;
 };
 
-hipError_t launch_pass(int tile, const PassArgs& a, uint64_t n_tiles, hipStream_t st);
+hipError_t launch_pass(int tile, int planes, const PassArgs& a, uint64_t n_tiles, hipStream_t st);
 hipError_t set_pass_attributes();
 
 // one-gate-per-launch kernels (fallback for n < 4 and cross-check path)

@@ -176,10 +176,11 @@ __device__ __attribute__((aligned(64))) const XpOffsets k_xp_tab = XpOffsets();
 // Structure of a pass: the first operation loads the tile; the assembly interpreter then runs
 // gates, sign flips and LDS transposes in place until it meets an operation it does not handle
 // (a per-lane unitary, or the end), which the C++ loop handles before re-entering it.
-template <int T, bool PERLANE>
+template <int T, bool PERLANE, int PLANES>
 __global__ __launch_bounds__(1 << (T - R)) void k_pass(const PassArgs a) {
-    // two XOR-swizzled planes (real, imaginary) of 2^T floats each; see the interpreter's
-    // generator.  The segment must start at LDS byte 0 (no static LDS in this kernel).
+    // PLANES XOR-swizzled planes of 2^T floats each (real and imaginary parts at once, or one
+    // after the other through a single plane, which halves the LDS a workgroup holds); see the
+    // interpreter's generator.  The segment must start at LDS byte 0 (no static LDS here).
     extern __shared__ float lds[];
     constexpr unsigned PLANE = 1u << T;
     static_assert(PLANE * 4u < 65536u && PLANE / 64u < 256u, "plane offsets must fit the LDS offset fields");
@@ -247,16 +248,27 @@ __global__ __launch_bounds__(1 << (T - R)) void k_pass(const PassArgs a) {
     for (;;) {
         {
             float t0, t1, t2, t3, tc;
-            asm volatile(QSV_GATE_LOOP_ASM
-                         : QSV_16(QSV_RV) [t0] "=&v"(t0), [t1] "=&v"(t1), [t2] "=&v"(t2),
-                           [t3] "=&v"(t3), [tc] "=&v"(tc), [opslo] "+s"(opslo), [opshi] "+s"(opshi),
-                           [scur] "+s"(scur), [ldsb] "+v"(ldsb), [e0lo] "+v"(e0lo), [e0hi] "+v"(e0hi)
-                         : [mlo] "s"(mlo), [mhi] "s"(mhi), [olo] "s"(olo), [ohi] "s"(ohi),
-                           [ovrid] "s"(ovr_id), [nonuni] "s"(nonuni), [thr] "v"(thr), [c] "s"(sc_c),
-                           [w] "s"(sc_w), [cmask] "s"(sc_cmask), [tblo] "s"(tblo), [tbhi] "s"(tbhi),
-                           [tablo] "s"(tablo), [tabhi] "s"(tabhi), [plane4] "n"(PLANE * 4u),
-                           [pl64] "n"(PLANE / 64u)
-                         : QSV_GATE_LOOP_CLOBBERS);
+#define QSV_LOOP_OUT QSV_16(QSV_RV) [t0] "=&v"(t0), [t1] "=&v"(t1), [t2] "=&v"(t2),                 \
+                     [t3] "=&v"(t3), [tc] "=&v"(tc), [opslo] "+s"(opslo), [opshi] "+s"(opshi),     \
+                     [scur] "+s"(scur), [ldsb] "+v"(ldsb), [e0lo] "+v"(e0lo), [e0hi] "+v"(e0hi)
+#define QSV_LOOP_IN [mlo] "s"(mlo), [mhi] "s"(mhi), [olo] "s"(olo), [ohi] "s"(ohi),                 \
+                    [ovrid] "s"(ovr_id), [nonuni] "s"(nonuni), [thr] "v"(thr), [c] "s"(sc_c),       \
+                    [w] "s"(sc_w), [cmask] "s"(sc_cmask), [tblo] "s"(tblo), [tbhi] "s"(tbhi),       \
+                    [tablo] "s"(tablo), [tabhi] "s"(tabhi)
+            if constexpr (PLANES == 2) {
+                asm volatile(QSV_GATE_LOOP_ASM_2P
+                             : QSV_LOOP_OUT
+                             : QSV_LOOP_IN, [plane4] "n"(PLANE * 4u), [pl64] "n"(PLANE / 64u)
+                             : QSV_GATE_LOOP_CLOBBERS);
+            } else {
+                unsigned ldsn;
+                asm volatile(QSV_GATE_LOOP_ASM_1P
+                             : QSV_LOOP_OUT, [ldsn] "=&v"(ldsn)
+                             : QSV_LOOP_IN
+                             : QSV_GATE_LOOP_CLOBBERS);
+            }
+#undef QSV_LOOP_OUT
+#undef QSV_LOOP_IN
         }
         // Operations are read as one aligned 64-bit word each and decoded with shifts.
         const u64 opp = ((u64)opshi << 32) | opslo;
@@ -386,8 +398,8 @@ __device__ __forceinline__ M2 mul_m(const M2& a, const M2& b) {  // a * b
 
 // U(l,q) for one sample: slots applied in order (re-upload RX first), i.e. U = R_last ... R_first.
 // shift_slot >= 0 adds shift to that slot's angle.
-__device__ void fused_u(const CircDev& c, const float* params, const float* feats, u64 sample, int l,
-                        int q, int shift_slot, double shift, int inverse, float* out8) {
+__device__ M2 fused_raw(const CircDev& c, const float* params, const float* feats, u64 sample, int l,
+                        int q, int shift_slot, double shift, int inverse) {
     M2 u;
     for (int k = 0; k < 4; ++k) { u.r[k] = (k == 0 || k == 3) ? 1.0 : 0.0; u.i[k] = 0.0; }
     const int slots = c.reupload + c.n_rot;
@@ -407,6 +419,57 @@ __device__ void fused_u(const CircDev& c, const float* params, const float* feat
         d.r[3] = u.r[3]; d.i[3] = -u.i[3];
         u = d;
     }
+    return u;
+}
+
+// Phase bookkeeping.  Within one layer the single-qubit unitaries act on different qubits, so a
+// scalar factor may move freely between them.  Every matrix but the one of the last qubit is
+// stored as W = conj(p) U with p = m00 / |m00|, which makes m00 real (and, for the common
+// rotation sequences, a whole row or column real: the interpreter tests the stored zeros and
+// picks a shorter multiply sequence).  The last qubit's matrix takes the product of the removed
+// factors, so the layer as a whole, and hence the state, is unchanged.
+struct Ph { double r, i; };
+
+__device__ __forceinline__ Ph phase_of(const M2& u) {
+    const double mag = hypot(u.r[0], u.i[0]);
+    if (mag < 1e-6) return {1.0, 0.0};
+    return {u.r[0] / mag, u.i[0] / mag};
+}
+
+__device__ __forceinline__ void scale_m(M2& u, double pr, double pi) {  // u *= (pr + i pi)
+    for (int k = 0; k < 4; ++k) {
+        const double a = u.r[k], b = u.i[k];
+        u.r[k] = a * pr - b * pi;
+        u.i[k] = a * pi + b * pr;
+    }
+}
+
+__device__ __forceinline__ void strip_phase(M2& u) {
+    const Ph p = phase_of(u);
+    if (p.r == 1.0 && p.i == 0.0) return;
+    const double mag = hypot(u.r[0], u.i[0]);
+    scale_m(u, p.r, -p.i);
+    u.r[0] = mag; u.i[0] = 0.0;
+}
+
+// Product of the factors removed from qubits 0..n-2 of layer l.
+__device__ Ph layer_phase(const CircDev& c, const float* params, const float* feats, u64 sample,
+                          int l, int inverse) {
+    Ph acc = {1.0, 0.0};
+    for (int q = 0; q + 1 < c.n; ++q) {
+        const Ph p = phase_of(fused_raw(c, params, feats, sample, l, q, -1, 0.0, inverse));
+        const double r = acc.r * p.r - acc.i * p.i;
+        acc.i = acc.r * p.i + acc.i * p.r;
+        acc.r = r;
+    }
+    return acc;
+}
+
+__device__ __forceinline__ void store_m(M2& u, float* out8) {
+    // imaginary parts that vanish by structure come out as rounding noise of a few 1e-17:
+    // store them as exact zeros so that the fast paths apply
+    for (int k = 0; k < 4; ++k)
+        if (fabs(u.i[k]) < 1e-14) u.i[k] = 0.0;
     for (int k = 0; k < 4; ++k) { out8[2 * k] = (float)u.r[k]; out8[2 * k + 1] = (float)u.i[k]; }
 }
 
@@ -419,9 +482,15 @@ __global__ __launch_bounds__(256) void k_build_mats(CircDev c, const float* para
     const u64 sample = idx / per;
     const int pos = (int)(idx % per);
     const int lq = order ? order[pos] : pos;
-    fused_u(c, params, feats, sample, lq / c.n, lq % c.n, -1, 0.0, inverse, out + idx * 8);
+    const int l = lq / c.n, q = lq % c.n;
+    M2 u = fused_raw(c, params, feats, sample, l, q, -1, 0.0, inverse);
+    if (q + 1 < c.n) strip_phase(u);
+    else { const Ph p = layer_phase(c, params, feats, sample, l, inverse); scale_m(u, p.r, p.i); }
+    store_m(u, out + idx * 8);
 }
 
+// Matrices with one angle shifted by +-pi/2 (parameter-shift rule), consistent with the phase
+// bookkeeping of the unshifted table they are substituted into.
 __global__ __launch_bounds__(256) void k_build_shifted(CircDev c, const float* params,
                                                        const float* feats, u64 count, float* out) {
     const u64 idx = (u64)blockIdx.x * 256 + threadIdx.x;
@@ -435,7 +504,15 @@ __global__ __launch_bounds__(256) void k_build_shifted(CircDev c, const float* p
     const int sl = (p / c.n) % slots;
     const int l = p / (c.n * slots);
     const double shift = (v & 1) ? -1.57079632679489661923 : 1.57079632679489661923;
-    fused_u(c, params, feats, sample, l, q, sl, shift, 0, out + idx * 8);
+    M2 u = fused_raw(c, params, feats, sample, l, q, sl, shift, 0);
+    if (q + 1 < c.n) {
+        const Ph ph = phase_of(fused_raw(c, params, feats, sample, l, q, -1, 0.0, 0));
+        scale_m(u, ph.r, -ph.i);
+    } else {
+        const Ph ph = layer_phase(c, params, feats, sample, l, 0);
+        scale_m(u, ph.r, ph.i);
+    }
+    store_m(u, out + idx * 8);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -822,10 +899,10 @@ inline unsigned blocks_for(u64 items, unsigned per) { return (unsigned)((items +
 template <int T>
 static hipError_t set_attr_for() {
     const int bytes = 2 * (1 << T) * 4;
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(k_pass<T, false>),
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(k_pass<T, false, 2>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
     if (e != hipSuccess) return e;
-    return hipFuncSetAttribute(reinterpret_cast<const void*>(k_pass<T, true>),
+    return hipFuncSetAttribute(reinterpret_cast<const void*>(k_pass<T, true, 2>),
                                hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
 }
 
@@ -833,22 +910,26 @@ hipError_t set_pass_attributes() {
     return set_attr_for<13>();
 }
 
-template <int T>
-static void launch_pass_t(const PassArgs& a, dim3 grid, size_t lds, hipStream_t st) {
-    if (a.n >= T) hipLaunchKernelGGL((k_pass<T, false>), grid, dim3(1 << (T - R)), lds, st, a);
-    else hipLaunchKernelGGL((k_pass<T, true>), grid, dim3(1 << (T - R)), lds, st, a);
+template <int T, int PLANES>
+static void launch_pass_t(const PassArgs& a, dim3 grid, hipStream_t st) {
+    const size_t lds = (size_t)PLANES * ((size_t)1 << T) * sizeof(float);
+    if (a.n >= T) hipLaunchKernelGGL((k_pass<T, false, PLANES>), grid, dim3(1 << (T - R)), lds, st, a);
+    else hipLaunchKernelGGL((k_pass<T, true, PLANES>), grid, dim3(1 << (T - R)), lds, st, a);
 }
 
-hipError_t launch_pass(int tile, const PassArgs& a, uint64_t n_tiles, hipStream_t st) {
+hipError_t launch_pass(int tile, int planes, const PassArgs& a, uint64_t n_tiles, hipStream_t st) {
     if (n_tiles == 0 || n_tiles > 0x7fffffffull) return hipErrorInvalidValue;
+    if (planes != 1 && planes != 2) return hipErrorInvalidValue;
     const dim3 grid((unsigned)n_tiles);
-    // two planes of floats (see k_pass)
-    const size_t lds = 2 * ((size_t)1 << tile) * sizeof(float);
-    switch (tile) {
-        case 10: launch_pass_t<10>(a, grid, lds, st); break;
-        case 11: launch_pass_t<11>(a, grid, lds, st); break;
-        case 12: launch_pass_t<12>(a, grid, lds, st); break;
-        case 13: launch_pass_t<13>(a, grid, lds, st); break;
+    switch (tile * 2 + planes - 1) {
+        case 20: launch_pass_t<10, 1>(a, grid, st); break;
+        case 21: launch_pass_t<10, 2>(a, grid, st); break;
+        case 22: launch_pass_t<11, 1>(a, grid, st); break;
+        case 23: launch_pass_t<11, 2>(a, grid, st); break;
+        case 24: launch_pass_t<12, 1>(a, grid, st); break;
+        case 25: launch_pass_t<12, 2>(a, grid, st); break;
+        case 26: launch_pass_t<13, 1>(a, grid, st); break;
+        case 27: launch_pass_t<13, 2>(a, grid, st); break;
         default: return hipErrorInvalidValue;
     }
     return hipGetLastError();

@@ -6,12 +6,18 @@ import re
 
 from paper_2602_13140_amd.csrc import gen_gate_asm as g
 
-INTENDED_FALLTHROUGH = {"L_top", "L_uhave", "L_unopf", "L_u3", "L_d3", "L_cxdone", "L_xphave", "L_xpw",
-                        "L_xpr", "L_zm3", "L_zdone"}
+INTENDED_FALLTHROUGH = {"L_top", "L_uhave", "L_unopf", "L_ua", "L_ua3", "L_ur3", "L_ug3", "L_uc3",
+                        "L_d3", "L_cxdone", "L_xphave", "L_xpw", "L_xpr", "L_xpw2", "L_xpr2", "L_zm3", "L_zdone"}
 
 
-def test_no_unintended_fall_through():
-    lines = g.gen()
+import pytest
+
+PLANES = pytest.mark.parametrize("planes", [1, 2])
+
+
+@PLANES
+def test_no_unintended_fall_through(planes):
+    lines = g.gen(planes)
     for i, ln in enumerate(lines):
         if ln.endswith(":") and i > 0:
             prev = lines[i - 1]
@@ -21,8 +27,9 @@ def test_no_unintended_fall_through():
             assert name in INTENDED_FALLTHROUGH, (name, prev)
 
 
-def test_labels_defined_once_and_targets_exist():
-    lines = g.gen()
+@PLANES
+def test_labels_defined_once_and_targets_exist(planes):
+    lines = g.gen(planes)
     labels = [ln[:-1] for ln in lines if ln.endswith(":")]
     assert len(labels) == len(set(labels))
     for ln in lines:
@@ -31,10 +38,11 @@ def test_labels_defined_once_and_targets_exist():
             assert m.group(1) in labels, ln
 
 
-def test_exit_is_reached_only_with_nothing_in_flight():
+@PLANES
+def test_exit_is_reached_only_with_nothing_in_flight(planes):
     """Every jump to the exit comes from the dispatch right after the wait at the top, or from the
     unitary's early test, which sits before any load of that operation is issued."""
-    lines = g.gen()
+    lines = g.gen(planes)
     top = lines.index("L_top_%=:")
     assert lines[top + 1] == "s_waitcnt lgkmcnt(0)"
     for i, ln in enumerate(lines):
@@ -43,8 +51,9 @@ def test_exit_is_reached_only_with_nothing_in_flight():
             assert not any(x.startswith(("s_load", "ds_read", "ds_write")) for x in seg[2:]), ln
 
 
-def test_only_fixed_scalar_registers_in_the_clobber_range_are_used():
-    text = "\n".join(g.gen())
+@PLANES
+def test_only_fixed_scalar_registers_in_the_clobber_range_are_used(planes):
+    text = "\n".join(g.gen(planes))
     for m in re.finditer(r"\bs\[?(\d+)", text):
         assert g.FIRST_SGPR <= int(m.group(1)) <= g.LAST_SGPR, m.group(0)
 
@@ -52,3 +61,38 @@ def test_only_fixed_scalar_registers_in_the_clobber_range_are_used():
 def test_committed_header_is_current():
     path = os.path.join(os.path.dirname(os.path.abspath(g.__file__)), "qsv_gate_asm.h")
     assert open(path).read() == g.render()
+
+
+def _run_valu(lines, regs, sregs):
+    """Executes v_mul_f32 / v_fma_f32 lines (scalar first operand, optional negation) on floats."""
+    val = lambda tok: -sregs[tok[1:]] if tok.startswith("-") else sregs[tok]
+    for ln in lines:
+        op, rest = ln.split(" ", 1)
+        a = [x.strip() for x in rest.split(",")]
+        if op == "v_mul_f32":
+            regs[a[0]] = val(a[1]) * regs[a[2]]
+        else:
+            assert op == "v_fma_f32"
+            regs[a[0]] = val(a[1]) * regs[a[2]] + regs[a[3]]
+
+
+def test_unitary_multiply_sequences_compute_the_matrix_product():
+    """Each variant of the 2x2 update equals the complex matrix-vector product when the imaginary
+    parts it leaves out are zero, and the variants have 16/14/12/12 instructions."""
+    import numpy as np
+    g0 = np.random.Generator(np.random.PCG64(5))
+    zero = {"g": [], "a": [1], "r": [1, 3], "c": [1, 5]}        # indices into m00r..m11i
+    size = {"g": 16, "a": 14, "r": 12, "c": 12}
+    for variant in "garc":
+        m = g0.standard_normal(8)
+        m[zero[variant]] = 0.0
+        sregs = {"s%d" % (88 + k): m[k] for k in range(8)}
+        a = g0.standard_normal(2) + 1j * g0.standard_normal(2)
+        regs = {"%[r2]": a[0].real, "%[i2]": a[0].imag, "%[r6]": a[1].real, "%[i6]": a[1].imag}
+        lines = g.u_pair(2, 6, variant)
+        assert len(lines) == size[variant]
+        _run_valu(lines, regs, sregs)
+        mat = (m[0::2] + 1j * m[1::2]).reshape(2, 2)
+        want = mat @ a
+        got = np.array([regs["%[r2]"] + 1j * regs["%[i2]"], regs["%[r6]"] + 1j * regs["%[i6]"]])
+        assert np.allclose(got, want, atol=1e-13), variant

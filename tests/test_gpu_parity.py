@@ -75,7 +75,8 @@ SMALL = [
 
 
 @pytest.mark.parametrize("n,B,L,rot,ent,reup", SMALL)
-@pytest.mark.parametrize("mode", ["default", "t10", "t11", "t12", "t13", "naive"])
+@pytest.mark.parametrize("mode", ["default", "t10", "t11", "t12", "t13", "naive",
+                                  "t10p1", "t11p2", "t12p1", "t13p1", "t12p2"])
 def test_apply_layers_small(oracle, n, B, L, rot, ent, reup, mode):
     g = rng(31 * n + B + L)
     spec = wl.CircuitSpec(L, tuple(rot), ent, reup)
@@ -83,8 +84,9 @@ def test_apply_layers_small(oracle, n, B, L, rot, ent, reup, mode):
     x = g.standard_normal((B, 1 << n)).astype(np.float32)
     feats = g.standard_normal((B, n)).astype(np.float32) if reup else None
     oc = ocirc(oracle, spec)
-    ctx = gu.make_ctx(n, B, tile=int(mode[1:]) if mode.startswith("t") else 0,
-                      naive=1 if mode == "naive" else 0)
+    ctx = gu.make_ctx(n, B, tile=int(mode[1:3]) if mode.startswith("t") else 0,
+                      naive=1 if mode == "naive" else 0,
+                      planes=int(mode[4]) if mode[3:4] == "p" else 0)
     circ = qb.circuit_from_spec(spec)
     xd, pd = gu.dev(x), gu.dev(params)
     fd = gu.dev(feats) if reup else None
