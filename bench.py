@@ -23,9 +23,10 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
-# HBM bytes per pass-kernel launch from rocprofv3 FETCH_SIZE / WRITE_SIZE (profiles/), each scaled by
-# what the same counter reads for the load/store-only probe pass of known size; None = not measured.
-TRAFFIC_BYTES_PER_LAUNCH = {"c4": None, "c3": None}
+# HBM bytes per pass-kernel launch from rocprofv3 FETCH_SIZE / WRITE_SIZE, each scaled by what the same
+# counter reads for the load/store-only probe pass of known size (FETCH_SIZE x 2.000, WRITE_SIZE x
+# 1.000); the runs and their figures are in profiles/k_pass_hbm_traffic_counters.md.
+TRAFFIC_BYTES_PER_LAUNCH = {"c4": 1073868910, "c3": 537070332}
 
 
 def parse_args():

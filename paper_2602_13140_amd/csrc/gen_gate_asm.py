@@ -38,10 +38,10 @@ import os
 R = 4
 NR = 1 << R
 OP_XPOSE, OP_U, OP_CX_REG, OP_CX_DYN, OP_CZ_REG, OP_CZ_MIX, OP_CZ_LANE = 2, 3, 4, 5, 6, 7, 8
-# The map above is written with the block's registers at s36..s99; SHIFT moves the whole block
-# down (a kernel limited to 96 scalar registers, i.e. 8 waves per SIMD, then still has s0..s23
-# for the compiler; measured: no faster than the 7 waves the unlimited kernel gets).
-SHIFT = 12
+# The map above is written with the block's registers at s36..s99; SHIFT would move the whole
+# block down.  It stays 0: lower numbers run into s32/s33, which the compiler reserves, and a
+# kernel limited to 96 scalar registers (8 waves per SIMD) measured no faster than 7 waves.
+SHIFT = 0
 FIRST_SGPR, LAST_SGPR = 36 - SHIFT, 99 - SHIFT
 
 
