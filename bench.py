@@ -177,17 +177,19 @@ def bench_c3(torch, qb, wl, args):
 
 
 def bench_c2(torch, qb, wl, args):
+    """Config 2: the full parameter-shift gradient, timed twice: layer by layer from kept states
+    (the default when the workspace has room for them) and with every shifted circuit run whole."""
     w = wl.config(2)
     n, B = w.n, w.batch
     P = w.circuit.num_params(n)
-    ctx = qb.Context(n, B)
+    circ = qb.circuit_from_spec(w.circuit)
+    ctx = qb.Context(n, B, ws_bytes=qb.qsv_grad_workspace_bytes(n, B, circ))
     if args.tile:
         ctx.qsv_set_option("tile_log2", args.tile)
     if args.low:
         ctx.qsv_set_option("low_bits", args.low)
     if args.planes:
         ctx.qsv_set_option("lds_planes", args.planes)
-    circ = qb.circuit_from_spec(w.circuit)
     xd = torch.from_numpy(w.x).cuda()
     pd = torch.from_numpy(w.params).cuda()
     loss = torch.empty(B, dtype=torch.float32, device="cuda")
@@ -198,13 +200,23 @@ def bench_c2(torch, qb, wl, args):
         ctx.qsv_param_shift_grad(circ, xd, pd, None, 0, loss, grad, None, mg)
 
     steps = max(1, min(args.steps, 3))
-    ms, _ = run_steps(torch, step, steps, 1)
     circuits = B * (2 * P + 1)
     updates = wl.nominal_updates(w.circuit, n, circuits)
+    L = w.circuit.n_layers
+    layer_updates = wl.nominal_updates(w.circuit, n, 1) // L      # gate-amplitude updates of one layer
+    per_layer = 2 * P // L                                         # shifted circuits per sample and layer
+    executed = B * layer_updates * (L + sum(per_layer * (L - l) for l in range(L)))
+    ms, _ = run_steps(torch, step, steps, 1)
+    ctx.qsv_set_option("grad_layered", 0)
+    ms_whole, _ = run_steps(torch, step, steps, 1)
     ctx.close()
     return {"workload": "c2: 16 qubits, batch 256, 10 layers RY,RZ + CZ ladder, full parameter-shift gradient",
+            "method": "layer by layer from kept states: a circuit that shifts a parameter of layer l runs layers l..L-1",
             "ms_per_step": ms, "steps": steps, "circuits": circuits, "params": P, "updates": updates,
-            "updates_per_s": updates / (ms * 1e-3)}
+            "updates_per_s": updates / (ms * 1e-3),
+            "executed_updates": executed, "executed_updates_per_s": executed / (ms * 1e-3),
+            "whole_circuits": {"ms_per_step": ms_whole, "executed_updates": updates,
+                               "executed_updates_per_s": updates / (ms_whole * 1e-3)}}
 
 
 def bench_c1(torch, qb, wl, args):

@@ -70,6 +70,11 @@ int64_t qsv_num_params(const qsv_circuit* c, int n_qubits);
  * qsv_param_shift_grad run more circuits per launch. */
 size_t qsv_workspace_bytes(int n_qubits, int batch);
 
+/* Workspace size in bytes with which qsv_param_shift_grad can work layer by layer on circuit c:
+ * qsv_workspace_bytes plus room for n_layers + 1 states per sample.  Returns 0 on bad arguments.
+ * With less, qsv_param_shift_grad still works and runs every shifted circuit whole. */
+size_t qsv_grad_workspace_bytes(int n_qubits, int batch, const qsv_circuit* c);
+
 /* Create a context bound to (n_qubits, batch), a device ordinal, a HIP stream (hipStream_t cast
  * to void*, NULL = default stream), the caller's state buffer complex64 [batch][2^n] and the
  * caller's workspace (256-byte aligned device memory of at least qsv_workspace_bytes bytes).
@@ -138,7 +143,11 @@ qsv_status qsv_measure(qsv_ctx* ctx, const qsv_measure_req* req);
  * (times feats[b][q] when p is a re-upload weight, whose angle is w*feat).  x_dev float32
  * [batch][dim]; loss_dev float32 [batch] receives the unshifted f_b; grad_dev float32 [batch][P];
  * mean_loss_dev [1] and mean_grad_dev [P] receive the batch means when not NULL.  Uses the
- * workspace for the shifted circuits' states; the context's state buffer is left untouched. */
+ * workspace for the shifted circuits' states; the context's state buffer is left untouched.
+ * When the workspace has room for n_layers + 1 states per sample (qsv_grad_workspace_bytes), the
+ * unshifted circuit's state before every layer is kept and a circuit that shifts a parameter of
+ * layer l runs layers l..L-1 only, from that state: the same values with about half the gate
+ * applications (option grad_layered = 0 switches this off). */
 qsv_status qsv_param_shift_grad(qsv_ctx* ctx, const qsv_circuit* c, const float* x_dev, int64_t dim,
                                 const float* params_dev, const float* feats_dev, int32_t obs_qubit,
                                 float* loss_dev, float* grad_dev, float* mean_loss_dev,
@@ -162,7 +171,9 @@ qsv_status qsv_probe_pass(qsv_ctx* ctx, int low_bits, int window_start, int tran
  * kernel; low_bits in 4..10 (0 = default) forces the planner's minimum number of low index bits
  * per tile; lds_planes = 1 (default) moves real and imaginary parts through one LDS plane one
  * after the other, 2 through two planes at once; naive = 1 routes qsv_apply_layers through the
- * one-gate-per-launch kernels.  Unknown names and values out of range return
+ * one-gate-per-launch kernels; grad_layered = 0 makes qsv_param_shift_grad run every shifted
+ * circuit whole; grad_chunk_rows in 1..32768 (0 = as many as fit) caps the circuits per launch of
+ * qsv_param_shift_grad.  Unknown names and values out of range return
  * QSV_ERR_INVALID_ARG. */
 qsv_status qsv_set_option(qsv_ctx* ctx, const char* name, int64_t value);
 

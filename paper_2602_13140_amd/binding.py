@@ -55,6 +55,8 @@ def load():
     L.qsv_num_params.argtypes = [ctypes.POINTER(qsv_circuit), i32]
     L.qsv_workspace_bytes.restype = ctypes.c_size_t
     L.qsv_workspace_bytes.argtypes = [i32, i32]
+    L.qsv_grad_workspace_bytes.restype = ctypes.c_size_t
+    L.qsv_grad_workspace_bytes.argtypes = [i32, i32, ctypes.POINTER(qsv_circuit)]
     L.qsv_create.restype = i32
     L.qsv_create.argtypes = [ctypes.POINTER(vp), i32, i32, i32, vp, vp, vp, ctypes.c_size_t]
     L.qsv_destroy.restype = None
@@ -102,6 +104,10 @@ def qsv_num_params(circ, n):
 
 def qsv_workspace_bytes(n, batch):
     return int(load().qsv_workspace_bytes(n, batch))
+
+
+def qsv_grad_workspace_bytes(n, batch, circ):
+    return int(load().qsv_grad_workspace_bytes(n, batch, ctypes.byref(circ)))
 
 
 def qsv_plan_describe(circ, n, batch=1, inverse=0, tile_log2=0):

@@ -54,6 +54,8 @@ struct qsv_ctx {
     int opt_naive = 0;
     int opt_low = 0;
     int opt_planes = 1;
+    int opt_grad_layered = 1;
+    int64_t opt_grad_chunk = 0;
     std::vector<CachedPlan> cache;
     size_t ops_used = 0;
 };
@@ -175,7 +177,7 @@ qsv_status get_plan(qsv_ctx* ctx, const qsv_circuit& c, int64_t rows, int invers
 
 RowMap plain_rows(int n) {
     RowMap rm;
-    rm.grad = 0; rm.two_p = 0; rm.row0 = 0; rm.slots_n = 1; rm.n = n;
+    rm.grad = 0; rm.two_p = 0; rm.per = 1; rm.row0 = 0; rm.slots_n = 1; rm.n = n;
     return rm;
 }
 
@@ -295,6 +297,13 @@ size_t qsv_workspace_bytes(int n_qubits, int batch) {
     return total;
 }
 
+size_t qsv_grad_workspace_bytes(int n_qubits, int batch, const qsv_circuit* c) {
+    const size_t base = qsv_workspace_bytes(n_qubits, batch);
+    if (base == 0 || !check_circuit(c, n_qubits, nullptr)) return 0;
+    const size_t state_bytes = (size_t)8 << n_qubits;
+    return base + align_up((size_t)batch * (size_t)(c->n_layers + 1) * state_bytes) + 4 * kAlign;
+}
+
 qsv_status qsv_create(qsv_ctx** out, int n_qubits, int batch, int device, void* hip_stream,
                       void* state_dev, void* ws_dev, size_t ws_bytes) {
     if (!out) { g_create_error = "out is NULL"; return QSV_ERR_INVALID_ARG; }
@@ -353,6 +362,15 @@ qsv_status qsv_set_option(qsv_ctx* ctx, const char* name, int64_t value) {
         if (value != 1 && value != 2)
             return fail(ctx, QSV_ERR_INVALID_ARG, "lds_planes must be 1 or 2");
         ctx->opt_planes = (int)value;
+        return QSV_OK;
+    }
+    if (!strcmp(name, "grad_chunk_rows")) {
+        if (value < 0 || value > 32768) return fail(ctx, QSV_ERR_INVALID_ARG, "grad_chunk_rows must be in 0..32768");
+        ctx->opt_grad_chunk = value;
+        return QSV_OK;
+    }
+    if (!strcmp(name, "grad_layered")) {
+        ctx->opt_grad_layered = value != 0;
         return QSV_OK;
     }
     if (!strcmp(name, "naive")) {
@@ -513,6 +531,7 @@ qsv_status qsv_param_shift_grad(qsv_ctx* ctx, const qsv_circuit* c, const float*
     const int64_t per = 2 * P + 1;
     const int64_t circuits = B * per;
     const size_t msamples = (size_t)(c->reupload ? B : 1);
+    const size_t state_bytes = (size_t)8 << n;
     int nblk = (int)((dim + 4095) / 4096);
     if (nblk > 1024) nblk = 1024;
     double* npart = (double*)ar.take((size_t)B * nblk * 8);
@@ -521,20 +540,96 @@ qsv_status qsv_param_shift_grad(qsv_ctx* ctx, const qsv_circuit* c, const float*
     float* ovr = (float*)ar.take(msamples * (size_t)(2 * P) * 32);
     double* f = (double*)ar.take((size_t)circuits * 8);
     if (!npart || !inv || !mats || !ovr || !f) return ws_fail(ctx, ar, "qsv_param_shift_grad");
-    // the rest holds the states of one chunk of circuits and their reduction partials
-    const size_t row_bytes = ((size_t)8 << n) + (size_t)chunk_blocks(n) * 13 * 8 + 2 * kAlign;
-    int64_t chunk = (int64_t)(ar.remaining() / row_bytes);
-    if (chunk < 1) { ar.need = ar.off + row_bytes; return ws_fail(ctx, ar, "qsv_param_shift_grad"); }
-    if (chunk > circuits) chunk = circuits;
-    if (chunk > 32768) chunk = 32768;  // rows index a grid dimension
-    // keep the row count a power of two when several rows share a tile (extended-index tiling)
-    if (chunk < circuits) { int64_t p2 = 1; while (p2 * 2 <= chunk) p2 *= 2; chunk = p2; }
-    float2* states = (float2*)ar.take((size_t)chunk * ((size_t)8 << n));
-    double* zpart = (double*)ar.take((size_t)chunk * chunk_blocks(n) * 13 * 8);
-    if (!states || !zpart) return ws_fail(ctx, ar, "qsv_param_shift_grad");
-
     QSV_HIP(ctx, launch_sumsq(x_dev, B, dim, npart, nblk, ctx->stream), "sumsq");
     QSV_HIP(ctx, launch_norm_finish(npart, nblk, B, inv, nullptr, ctx->stream), "norm");
+
+    // a chunk of circuit states plus their reduction partials, sized to what is left of the workspace
+    const size_t row_bytes = state_bytes + (size_t)chunk_blocks(n) * 13 * 8 + 2 * kAlign;
+    auto chunk_rows = [&](int64_t want) -> int64_t {
+        int64_t chunk = (int64_t)(ar.remaining() / row_bytes);
+        if (chunk > want) chunk = want;
+        if (chunk > 32768) chunk = 32768;  // rows index a grid dimension
+        if (ctx->opt_grad_chunk > 0 && chunk > ctx->opt_grad_chunk) chunk = ctx->opt_grad_chunk;
+        // keep the row count a power of two when several rows share a tile (extended-index tiling)
+        if (chunk >= 1 && chunk < want) { int64_t p2 = 1; while (p2 * 2 <= chunk) p2 *= 2; chunk = p2; }
+        return chunk;
+    };
+
+    // ---- layer by layer: the circuits that shift a parameter of layer l share layers 0..l-1 with
+    // the unshifted circuit, so its state before layer l is kept per sample and each shifted
+    // circuit runs layers l..L-1 only.  Needs room for (L+1) states per sample; otherwise every
+    // shifted circuit is run whole (below).
+    const int L = c->n_layers;
+    const int slots_n = (c->reupload + c->n_rot) * n;
+    const size_t ckpt_bytes = (size_t)B * (size_t)(L + 1) * state_bytes;
+    if (ctx->opt_grad_layered && P > 0 && ar.remaining() >= align_up(ckpt_bytes) + row_bytes + 2 * kAlign) {
+        float2* ckpt = (float2*)ar.take(ckpt_bytes);
+        const int64_t per_l = 2 * (int64_t)slots_n;          // shifted circuits per sample and layer
+        const int64_t want = B * per_l > B ? B * per_l : B;
+        const int64_t chunk = chunk_rows(want);
+        float2* states = (float2*)ar.take((size_t)chunk * state_bytes);
+        double* zpart = (double*)ar.take((size_t)(chunk > B ? chunk : B) * chunk_blocks(n) * 13 * 8);
+        if (!ckpt || chunk < 1 || !states || !zpart) return ws_fail(ctx, ar, "qsv_param_shift_grad");
+        const size_t sample_stride = (size_t)1 << n;          // amplitudes per state
+        auto ck = [&](int l) { return ckpt + (size_t)l * (size_t)B * sample_stride; };
+        qsv_circuit one = *c;
+        one.n_layers = 1;
+        // unshifted circuit, one layer at a time: ck(l) = state of every sample before layer l
+        QSV_HIP(ctx, launch_encode_write(x_dev, dim, n, B, inv, plain_rows(n), ck(0), ctx->stream), "encode");
+        for (int l = 0; l < L; ++l) {
+            QSV_HIP(ctx, hipMemcpyAsync(ck(l + 1), ck(l), (size_t)B * state_bytes, hipMemcpyDeviceToDevice,
+                                        ctx->stream),
+                    "copy checkpoint");
+            Prepared pr;
+            st = prepare_circuit(ctx, one, B, 0, 0, params_dev + (size_t)l * slots_n, feats_dev, B, mats, &pr);
+            if (st != QSV_OK) return st;
+            st = run_circuit(ctx, one, pr, ck(l + 1), B, 0, nullptr, plain_rows(n));
+            if (st != QSV_OK) return st;
+        }
+        QSV_HIP(ctx, launch_expz_block(ck(L), B, n, zpart, ctx->stream), "expz block");
+        QSV_HIP(ctx, launch_expz_finish_scatter(zpart, B, n, obs_qubit, f, Scatter{0, 1, per, 2 * P}, ctx->stream),
+                "expz finish");
+        // shifted circuits of layer l: start from ck(l), run layers l..L-1 with one matrix replaced
+        const CircDev cd1 = to_dev(one, n);
+        for (int l = 0; l < L; ++l) {
+            qsv_circuit tail = *c;
+            tail.n_layers = L - l;
+            const float* p_l = params_dev + (size_t)l * slots_n;
+            Prepared pr;
+            st = prepare_circuit(ctx, tail, chunk, 0, 1, p_l, feats_dev, B, mats, &pr);
+            if (st != QSV_OK) return st;
+            QSV_HIP(ctx, launch_build_shifted(cd1, p_l, feats_dev, B, ovr, ctx->stream), "build shifted");
+            const int64_t circuits_l = B * per_l;
+            for (int64_t row0 = 0; row0 < circuits_l; row0 += chunk) {
+                const int64_t rows = (circuits_l - row0) < chunk ? (circuits_l - row0) : chunk;
+                RowMap rm;
+                rm.grad = 1;
+                rm.two_p = (int)per_l;
+                rm.per = (int)per_l;
+                rm.row0 = row0;
+                rm.slots_n = slots_n;
+                rm.n = n;
+                QSV_HIP(ctx, launch_gather_rows(ck(l), n, rows, rm, states, ctx->stream), "gather rows");
+                st = run_circuit(ctx, tail, pr, states, rows, 0, ovr, rm);
+                if (st != QSV_OK) return st;
+                QSV_HIP(ctx, launch_expz_block(states, rows, n, zpart, ctx->stream), "expz block");
+                QSV_HIP(ctx, launch_expz_finish_scatter(zpart, rows, n, obs_qubit, f,
+                                                        Scatter{row0, per_l, per, (int64_t)l * per_l}, ctx->stream),
+                        "expz finish");
+            }
+        }
+        QSV_HIP(ctx, launch_grad_finish(f, B, P, cd, feats_dev, loss_dev, grad_dev, mean_loss_dev,
+                                        mean_grad_dev, ctx->stream),
+                "grad finish");
+        return QSV_OK;
+    }
+
+    // ---- every shifted circuit whole
+    const int64_t chunk = chunk_rows(circuits);
+    if (chunk < 1) { ar.need = ar.off + row_bytes; return ws_fail(ctx, ar, "qsv_param_shift_grad"); }
+    float2* states = (float2*)ar.take((size_t)chunk * state_bytes);
+    double* zpart = (double*)ar.take((size_t)chunk * chunk_blocks(n) * 13 * 8);
+    if (!states || !zpart) return ws_fail(ctx, ar, "qsv_param_shift_grad");
     Prepared pr;
     st = prepare_circuit(ctx, *c, chunk, 0, 1, params_dev, feats_dev, B, mats, &pr);
     if (st != QSV_OK) return st;
@@ -545,9 +640,9 @@ qsv_status qsv_param_shift_grad(qsv_ctx* ctx, const qsv_circuit* c, const float*
         RowMap rm;
         rm.grad = 1;
         rm.two_p = (int)(2 * P);
+        rm.per = (int)per;
         rm.row0 = row0;
-        rm.slots_n = (c->reupload + c->n_rot) * n;
-        if (rm.slots_n < 1) rm.slots_n = 1;
+        rm.slots_n = slots_n < 1 ? 1 : slots_n;
         rm.n = n;
         QSV_HIP(ctx, launch_encode_write(x_dev, dim, n, rows, inv, rm, states, ctx->stream), "encode rows");
         st = run_circuit(ctx, *c, pr, states, rows, 0, ovr, rm);

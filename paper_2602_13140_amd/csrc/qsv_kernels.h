@@ -15,11 +15,15 @@ struct CircDev {
 };
 
 // How state rows map to samples.  Plain calls: row = sample.  Gradient launches: row r of the
-// chunk is circuit gid = row0 + r of the B*(2P+1) shifted circuits; sample = gid / (2P+1),
-// variant v = gid % (2P+1); v < 2P shifts parameter v/2 by +pi/2 (v even) or -pi/2 (v odd).
+// chunk is circuit gid = row0 + r; sample = gid / per, variant v = gid % per; v < two_p replaces
+// the matrix of parameter v/2 of the circuit being run by its +pi/2 (v even) or -pi/2 (v odd)
+// shifted version.  Whole-circuit gradients use per = 2P+1 (variant 2P is the unshifted circuit);
+// the layer-by-layer gradient runs the circuit's last layers only and shifts parameters of their
+// first layer: per = two_p = 2 * slots * n.
 struct RowMap {
     int grad;        // 0 plain, 1 gradient
-    int two_p;       // 2P
+    int two_p;       // variants that replace a matrix: v < two_p (also the row stride of the shifted table)
+    int per;         // circuits per sample (two_p + 1 when the unshifted circuit is among them)
     int64_t row0;
     int slots_n;     // (reupload + n_rot) * n
     int n;
@@ -72,6 +76,14 @@ hipError_t launch_probs(const float2* state, uint64_t total, float* out, hipStre
 hipError_t launch_expz_block(const float2* state, int64_t rows, int n, double* partial, hipStream_t st);
 hipError_t launch_expz_finish(const double* partial, int64_t rows, int n, int q_only, float* out_f,
                               double* out_d, hipStream_t st);
+// Where one-qubit results of gradient rows go: circuit gid = row0 + r lands at
+// out[(gid / per) * stride + offset + gid % per].
+struct Scatter { int64_t row0, per, stride, offset; };
+hipError_t launch_expz_finish_scatter(const double* partial, int64_t rows, int n, int q, double* out,
+                                      const Scatter& sc, hipStream_t st);
+// states[r] = src[sample of row r] for the rows of a gradient chunk (src: [samples][2^n])
+hipError_t launch_gather_rows(const float2* src, int n, int64_t rows, const RowMap& rm, float2* states,
+                              hipStream_t st);
 // partial: [rows][n_v][nblk] doubles with nblk = max(1, 2^(n-m) / 4096)
 hipError_t launch_marginal_block(const float2* state, int64_t rows, int n, uint64_t mask, int64_t n_v,
                                  double* partial, hipStream_t st);

@@ -50,7 +50,7 @@ __device__ __forceinline__ RowCtx row_ctx(const RowMap& rm, u64 row) {
     rc.ovr_off = 0;
     if (rm.grad) {
         const u64 gid = (u64)rm.row0 + row;
-        const u64 per = (u64)rm.two_p + 1;
+        const u64 per = (u64)rm.per;
         rc.sample = gid / per;
         const int v = (int)(gid % per);
         if (v < rm.two_p) {
@@ -632,7 +632,8 @@ __global__ __launch_bounds__(256) void k_expz_block(const float2* state, int n, 
 // One wavefront per (row, qubit): combine block partials.  Bits below 12 use the blocks' signed
 // sums; higher bits are constant inside a block, so they sign the block totals.
 __global__ __launch_bounds__(256) void k_expz_finish(const double* partial, u64 rows, int n, int nblk,
-                                                     int q_only, float* out_f, double* out_d) {
+                                                     int q_only, float* out_f, double* out_d,
+                                                     Scatter sc) {
     const int lane = threadIdx.x & 63;
     const u64 job = (u64)blockIdx.x * 4 + (threadIdx.x >> 6);
     const int nq = q_only >= 0 ? 1 : n;
@@ -651,9 +652,25 @@ __global__ __launch_bounds__(256) void k_expz_finish(const double* partial, u64 
     }
     acc = wave_sum(acc);
     if (lane == 0) {
-        if (out_f) out_f[job] = (float)acc;
-        if (out_d) out_d[job] = acc;
+        u64 o = job;
+        if (sc.per > 0) {  // one qubit per row (q_only >= 0): job = row of the chunk
+            const u64 gid = (u64)sc.row0 + job;
+            o = (gid / (u64)sc.per) * (u64)sc.stride + (u64)sc.offset + gid % (u64)sc.per;
+        }
+        if (out_f) out_f[o] = (float)acc;
+        if (out_d) out_d[o] = acc;
     }
+}
+
+// Copies each row's starting state from the per-sample source (16 bytes per lane and step).
+__global__ __launch_bounds__(256) void k_gather_rows(const float2* src, int n, u64 total, RowMap rm,
+                                                     float2* states) {
+    const u64 e2 = ((u64)blockIdx.x * 256 + threadIdx.x) * 2;
+    if (e2 >= total) return;
+    const u64 row = e2 >> n;
+    const u64 k = e2 & ((1ull << n) - 1);
+    const u64 sample = row_ctx(rm, row).sample;
+    *reinterpret_cast<float4*>(states + e2) = *reinterpret_cast<const float4*>(src + ((sample << n) | k));
 }
 
 __device__ __forceinline__ u64 deposit(u64 v, u64 mask, int n) {  // spread the bits of v over mask
@@ -1019,7 +1036,24 @@ hipError_t launch_expz_finish(const double* partial, int64_t rows, int n, int q_
                               double* out_d, hipStream_t st) {
     const u64 jobs = (u64)rows * (q_only >= 0 ? 1 : n);
     hipLaunchKernelGGL(k_expz_finish, dim3(blocks_for(jobs, 4)), dim3(256), 0, st, partial, (u64)rows, n,
-                       chunk_blocks(n), q_only, out_f, out_d);
+                       chunk_blocks(n), q_only, out_f, out_d, Scatter{0, 0, 0, 0});
+    return hipGetLastError();
+}
+
+hipError_t launch_expz_finish_scatter(const double* partial, int64_t rows, int n, int q, double* out,
+                                      const Scatter& sc, hipStream_t st) {
+    if (q < 0 || sc.per < 1) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(k_expz_finish, dim3(blocks_for((u64)rows, 4)), dim3(256), 0, st, partial, (u64)rows,
+                       n, chunk_blocks(n), q, (float*)nullptr, out, sc);
+    return hipGetLastError();
+}
+
+hipError_t launch_gather_rows(const float2* src, int n, int64_t rows, const RowMap& rm, float2* states,
+                              hipStream_t st) {
+    if (n < 1) return hipErrorInvalidValue;   // rows of one amplitude cannot be copied in pairs
+    const u64 total = (u64)rows << n;
+    hipLaunchKernelGGL(k_gather_rows, dim3(blocks_for(total / 2, 256)), dim3(256), 0, st, src, n, total, rm,
+                       states);
     return hipGetLastError();
 }
 

@@ -20,9 +20,9 @@ def state_np(ctx):
     return (s[..., 0].astype(np.float64) + 1j * s[..., 1].astype(np.float64))
 
 
-def make_ctx(n, batch, tile=0, naive=0, planes=0):
+def make_ctx(n, batch, tile=0, naive=0, planes=0, ws_bytes=None):
     from paper_2602_13140_amd import binding as qb
-    ctx = qb.Context(n, batch)
+    ctx = qb.Context(n, batch, ws_bytes=ws_bytes)
     if tile:
         ctx.qsv_set_option("tile_log2", tile)
     if planes:

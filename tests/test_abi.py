@@ -49,3 +49,7 @@ def test_create_rejects_bad_arguments_without_a_gpu():
 def test_workspace_size_grows_with_the_state():
     assert qb.qsv_workspace_bytes(26, 1) > qb.qsv_workspace_bytes(20, 1) > 0
     assert qb.qsv_workspace_bytes(10, 1024) > qb.qsv_workspace_bytes(10, 1)
+    c = qb.make_circuit(10, [2, 3], 2)
+    extra = qb.qsv_grad_workspace_bytes(16, 256, c) - qb.qsv_workspace_bytes(16, 256)
+    assert 256 * 11 * (8 << 16) <= extra <= 256 * 11 * (8 << 16) + 4096
+    assert qb.qsv_grad_workspace_bytes(16, 256, qb.make_circuit(1, [9], 1)) == 0

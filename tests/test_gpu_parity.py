@@ -206,8 +206,9 @@ def test_sampling_special_states():
 @pytest.mark.parametrize("n,B,L,rot,ent,reup,obs", [
     (2, 3, 2, (RY, RZ), RING, 0, 1), (4, 5, 2, (RY, RZ), LADDER, 0, 0), (5, 3, 2, (RX, RY, RZ), RING, 0, 2),
     (6, 4, 2, (RY, RZ), RING, 1, 0), (10, 2, 2, (RY, RZ), LADDER, 0, 0), (12, 2, 1, (RY, RZ), RING, 1, 3),
-    (13, 1, 2, (RY,), LADDER, 0, 0)])
-@pytest.mark.parametrize("mode", ["default", "naive"])
+    (13, 1, 2, (RY,), LADDER, 0, 0), (1, 4, 3, (RX, RZ), RING, 0, 0), (7, 3, 4, (RY, RZ), RING, 0, 6),
+    (8, 5, 3, (RX, RZ), LADDER, 1, 2), (11, 2, 3, (RY, RZ), LADDER, 0, 10)])
+@pytest.mark.parametrize("mode", ["default", "naive", "whole", "chunk5", "whole-chunk4", "naive-whole"])
 def test_param_shift_grad_small(oracle, n, B, L, rot, ent, reup, obs, mode):
     torch = gu.torch_cuda()
     g = rng(40 + n)
@@ -217,7 +218,13 @@ def test_param_shift_grad_small(oracle, n, B, L, rot, ent, reup, obs, mode):
     x = g.standard_normal((B, 1 << n)).astype(np.float32)
     feats = g.standard_normal((B, n)).astype(np.float32) if reup else None
     lref, gref = oracle.param_shift_grad(x, n, ocirc(oracle, spec), params, feats, obs_qubit=obs)
-    ctx = gu.make_ctx(n, B, naive=1 if mode == "naive" else 0)
+    # default: layer by layer from kept states; "whole": every shifted circuit from the start;
+    # "chunk": a cap on circuits per launch so that chunks end inside a sample's rows
+    ctx = gu.make_ctx(n, B, naive=1 if "naive" in mode else 0)
+    if "whole" in mode:
+        ctx.qsv_set_option("grad_layered", 0)
+    if "chunk" in mode:
+        ctx.qsv_set_option("grad_chunk_rows", int(mode[-1]))
     ctx.state.fill_(3.0)
     loss = torch.zeros(B, dtype=torch.float32, device="cuda")
     grad = torch.zeros((B, P), dtype=torch.float32, device="cuda")
