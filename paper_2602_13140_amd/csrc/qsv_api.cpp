@@ -213,12 +213,18 @@ qsv_status prepare_circuit(qsv_ctx* ctx, const qsv_circuit& c, int64_t rows, int
 }
 
 // Runs the prepared circuit on `rows` state rows starting at `state`.
+// src (optional): per-sample start states [samples][2^n]; the rows then start from the state of
+// their sample.  The fused path reads them in its first pass when a tile never spans two rows,
+// otherwise a copy pass fills the rows first.
 qsv_status run_circuit(qsv_ctx* ctx, const qsv_circuit& c, const Prepared& pr, float2* state, int64_t rows,
-                       int inverse, const float* ovr, const RowMap& rm) {
+                       int inverse, const float* ovr, const RowMap& rm, const float2* src = nullptr) {
     const int n = ctx->n;
     const bool has_u = (c.reupload + c.n_rot) > 0;
     const int n_mats = has_u ? c.n_layers * n : 0;
     const float* mats = pr.mats;
+    const bool src_in_pass = src && pr.cp && n >= pr.cp->plan.tile && !pr.cp->plan.passes.empty();
+    if (src && !src_in_pass)
+        QSV_HIP(ctx, launch_gather_rows(src, n, rows, rm, state, ctx->stream), "gather rows");
     if (!pr.cp) {
         auto layer_u = [&](int l) -> hipError_t {
             if (!has_u) return hipSuccess;
@@ -250,9 +256,12 @@ qsv_status run_circuit(qsv_ctx* ctx, const qsv_circuit& c, const Prepared& pr, f
     const int ext = n + ceil_log2_i64(rows);
     const uint64_t n_tiles = ext > pl.tile ? (1ull << (ext - pl.tile)) : 1ull;
     const Op* dev_ops = reinterpret_cast<const Op*>(ctx->ws + cp->dev_off);
+    bool first = true;
     for (const Pass& ps : pl.passes) {
         PassArgs a;
         a.state = state;
+        a.src = (first && src_in_pass) ? src : nullptr;
+        first = false;
         a.ops = dev_ops + ps.op_begin;
         a.mats = mats;
         a.exec_of = reinterpret_cast<const int*>(ctx->ws + cp->execof_off);
@@ -609,8 +618,7 @@ qsv_status qsv_param_shift_grad(qsv_ctx* ctx, const qsv_circuit* c, const float*
                 rm.row0 = row0;
                 rm.slots_n = slots_n;
                 rm.n = n;
-                QSV_HIP(ctx, launch_gather_rows(ck(l), n, rows, rm, states, ctx->stream), "gather rows");
-                st = run_circuit(ctx, tail, pr, states, rows, 0, ovr, rm);
+                st = run_circuit(ctx, tail, pr, states, rows, 0, ovr, rm, ck(l));
                 if (st != QSV_OK) return st;
                 QSV_HIP(ctx, launch_expz_block(states, rows, n, zpart, ctx->stream), "expz block");
                 QSV_HIP(ctx, launch_expz_finish_scatter(zpart, rows, n, obs_qubit, f,
@@ -684,6 +692,7 @@ qsv_status qsv_probe_pass(qsv_ctx* ctx, int low_bits, int window_start, int tran
     QSV_HIP(ctx, hipStreamSynchronize(ctx->stream), "upload probe");
     PassArgs a;
     a.state = ctx->state;
+    a.src = nullptr;
     a.ops = dev;
     a.mats = nullptr;
     a.exec_of = nullptr;

@@ -31,6 +31,7 @@ struct RowMap {
 
 struct PassArgs {
     float2* state;
+    const float2* src;   // not NULL: tiles are read from src[sample of the row] instead of state (needs n >= tile)
     const Op* ops;
     const float* mats;   // [samples if rowdep][n_mats][8], matrices in execution order
     const int* exec_of;  // [n_mats]: (layer * n + qubit) -> execution-order index

@@ -225,18 +225,26 @@ __global__ __launch_bounds__(1 << (T - R)) void k_pass(const PassArgs a) {
     // a scalar base (tile and register part) plus one 32-bit per-lane byte offset, which costs no
     // vector arithmetic per element.
     const bool off32 = (expand((1u << T) - 1u) >> 29) == 0;
+    // Where the tile is read from: the state itself, or (first pass of a gradient chunk, rows
+    // uniform per tile) the kept start state of the row's sample, so that no copy pass is needed.
+    const float2* ld = a.state;
+    if (a.src && rows_uniform) {
+        const u64 d = (u64)(((long long)urc.sample - (long long)(tile_base >> a.n)) << a.n);
+        const long long ds = (long long)(((u64)to_sgpr((unsigned)(d >> 32)) << 32) | to_sgpr((unsigned)d));
+        ld = a.src + ds;
+    }
     if (full && off32) {
         const unsigned lane_byte = (unsigned)expand(tau0) * 8u;
-#define QSV_LD(k) { const char* bp = (const char*)(a.state + (tile_base | expand((unsigned)k << scur))); \
+#define QSV_LD(k) { const char* bp = (const char*)(ld + (tile_base | expand((unsigned)k << scur))); \
                     const float2 v = *(const float2*)(bp + lane_byte); vr##k = v.x; vi##k = v.y; }
         QSV_16(QSV_LD)
 #undef QSV_LD
     } else if (full) {
-#define QSV_LD(k) { const float2 v = a.state[e0 | expand((unsigned)k << scur)]; vr##k = v.x; vi##k = v.y; }
+#define QSV_LD(k) { const float2 v = ld[e0 | expand((unsigned)k << scur)]; vr##k = v.x; vi##k = v.y; }
         QSV_16(QSV_LD)
 #undef QSV_LD
     } else {
-#define QSV_LD(k) { const u64 e = e0 | expand((unsigned)k << scur); const float2 v = a.state[e < a.total ? e : 0]; \
+#define QSV_LD(k) { const u64 e = e0 | expand((unsigned)k << scur); const float2 v = ld[e < a.total ? e : tile_base]; \
                     vr##k = e < a.total ? v.x : 0.f; vi##k = e < a.total ? v.y : 0.f; }
         QSV_16(QSV_LD)
 #undef QSV_LD
