@@ -216,8 +216,14 @@ qsv_status prepare_circuit(qsv_ctx* ctx, const qsv_circuit& c, int64_t rows, int
 // src (optional): per-sample start states [samples][2^n]; the rows then start from the state of
 // their sample.  The fused path reads them in its first pass when a tile never spans two rows,
 // otherwise a copy pass fills the rows first.
+// zs (optional): what the gradient wants of the final states, <Z_q> per row scattered into out.
+// The fused path computes it in its last pass (which then stores nothing) when a tile never spans
+// two rows; otherwise the reduction kernels read the final states.  zpart: room for partials.
+struct ZSpec { int q; double* out; Scatter sc; double* zpart; };
+
 qsv_status run_circuit(qsv_ctx* ctx, const qsv_circuit& c, const Prepared& pr, float2* state, int64_t rows,
-                       int inverse, const float* ovr, const RowMap& rm, const float2* src = nullptr) {
+                       int inverse, const float* ovr, const RowMap& rm, const float2* src = nullptr,
+                       const ZSpec* zs = nullptr) {
     const int n = ctx->n;
     const bool has_u = (c.reupload + c.n_rot) > 0;
     const int n_mats = has_u ? c.n_layers * n : 0;
@@ -225,6 +231,13 @@ qsv_status run_circuit(qsv_ctx* ctx, const qsv_circuit& c, const Prepared& pr, f
     const bool src_in_pass = src && pr.cp && n >= pr.cp->plan.tile && !pr.cp->plan.passes.empty();
     if (src && !src_in_pass)
         QSV_HIP(ctx, launch_gather_rows(src, n, rows, rm, state, ctx->stream), "gather rows");
+    auto z_after = [&]() -> qsv_status {
+        if (!zs) return QSV_OK;
+        QSV_HIP(ctx, launch_expz_block(state, rows, n, zs->zpart, ctx->stream), "expz block");
+        QSV_HIP(ctx, launch_expz_finish_scatter(zs->zpart, rows, n, zs->q, zs->out, zs->sc, ctx->stream),
+                "expz finish");
+        return QSV_OK;
+    };
     if (!pr.cp) {
         auto layer_u = [&](int l) -> hipError_t {
             if (!has_u) return hipSuccess;
@@ -249,19 +262,25 @@ qsv_status run_circuit(qsv_ctx* ctx, const qsv_circuit& c, const Prepared& pr, f
                 QSV_HIP(ctx, launch_naive_cz_ladder(state, rows, n, ctx->stream), "naive cz");
             if (inverse) QSV_HIP(ctx, layer_u(l), "naive rotation");
         }
-        return QSV_OK;
+        return z_after();
     }
     const CachedPlan* cp = pr.cp;
     const Plan& pl = cp->plan;
     const int ext = n + ceil_log2_i64(rows);
     const uint64_t n_tiles = ext > pl.tile ? (1ull << (ext - pl.tile)) : 1ull;
     const Op* dev_ops = reinterpret_cast<const Op*>(ctx->ws + cp->dev_off);
+    const bool z_in_pass = zs && n >= pl.tile && !pl.passes.empty();
     bool first = true;
-    for (const Pass& ps : pl.passes) {
+    for (size_t pi = 0; pi < pl.passes.size(); ++pi) {
+        const Pass& ps = pl.passes[pi];
         PassArgs a;
         a.state = state;
         a.src = (first && src_in_pass) ? src : nullptr;
         first = false;
+        const bool last = pi + 1 == pl.passes.size();
+        a.zout = (last && z_in_pass) ? zs->zpart : nullptr;
+        a.zq = zs ? zs->q : 0;
+        a.nostore = a.zout ? 1 : 0;
         a.ops = dev_ops + ps.op_begin;
         a.mats = mats;
         a.exec_of = reinterpret_cast<const int*>(ctx->ws + cp->execof_off);
@@ -273,7 +292,14 @@ qsv_status run_circuit(qsv_ctx* ctx, const qsv_circuit& c, const Prepared& pr, f
         a.rm = rm;
         QSV_HIP(ctx, launch_pass(pl.tile, ctx->opt_planes, a, n_tiles, ctx->stream), "fused pass");
     }
-    return QSV_OK;
+    if (z_in_pass) {
+        // partials per row: tiles of the row x wavefronts of a workgroup
+        const int64_t per_row = ((int64_t)1 << (n - pl.tile)) * (((int64_t)1 << (pl.tile - kRegBits)) / 64 > 0
+                                                                    ? ((int64_t)1 << (pl.tile - kRegBits)) / 64 : 1);
+        QSV_HIP(ctx, launch_zsum_finish(zs->zpart, rows, per_row, zs->out, zs->sc, ctx->stream), "z finish");
+        return QSV_OK;
+    }
+    return z_after();
 }
 
 qsv_status bind_device(qsv_ctx* ctx) {
@@ -618,12 +644,9 @@ qsv_status qsv_param_shift_grad(qsv_ctx* ctx, const qsv_circuit* c, const float*
                 rm.row0 = row0;
                 rm.slots_n = slots_n;
                 rm.n = n;
-                st = run_circuit(ctx, tail, pr, states, rows, 0, ovr, rm, ck(l));
+                const ZSpec zs{obs_qubit, f, Scatter{row0, per_l, per, (int64_t)l * per_l}, zpart};
+                st = run_circuit(ctx, tail, pr, states, rows, 0, ovr, rm, ck(l), &zs);
                 if (st != QSV_OK) return st;
-                QSV_HIP(ctx, launch_expz_block(states, rows, n, zpart, ctx->stream), "expz block");
-                QSV_HIP(ctx, launch_expz_finish_scatter(zpart, rows, n, obs_qubit, f,
-                                                        Scatter{row0, per_l, per, (int64_t)l * per_l}, ctx->stream),
-                        "expz finish");
             }
         }
         QSV_HIP(ctx, launch_grad_finish(f, B, P, cd, feats_dev, loss_dev, grad_dev, mean_loss_dev,
@@ -653,11 +676,9 @@ qsv_status qsv_param_shift_grad(qsv_ctx* ctx, const qsv_circuit* c, const float*
         rm.slots_n = slots_n < 1 ? 1 : slots_n;
         rm.n = n;
         QSV_HIP(ctx, launch_encode_write(x_dev, dim, n, rows, inv, rm, states, ctx->stream), "encode rows");
-        st = run_circuit(ctx, *c, pr, states, rows, 0, ovr, rm);
+        const ZSpec zs{obs_qubit, f, Scatter{row0, 1, 1, 0}, zpart};
+        st = run_circuit(ctx, *c, pr, states, rows, 0, ovr, rm, nullptr, &zs);
         if (st != QSV_OK) return st;
-        QSV_HIP(ctx, launch_expz_block(states, rows, n, zpart, ctx->stream), "expz block");
-        QSV_HIP(ctx, launch_expz_finish(zpart, rows, n, obs_qubit, nullptr, f + row0, ctx->stream),
-                "expz finish");
     }
     QSV_HIP(ctx, launch_grad_finish(f, B, P, cd, feats_dev, loss_dev, grad_dev, mean_loss_dev,
                                     mean_grad_dev, ctx->stream),
@@ -693,6 +714,7 @@ qsv_status qsv_probe_pass(qsv_ctx* ctx, int low_bits, int window_start, int tran
     PassArgs a;
     a.state = ctx->state;
     a.src = nullptr;
+    a.zout = nullptr; a.zq = 0; a.nostore = 0;
     a.ops = dev;
     a.mats = nullptr;
     a.exec_of = nullptr;

@@ -33,6 +33,9 @@ struct PassArgs {
     float2* state;
     const float2* src;   // not NULL: tiles are read from src[sample of the row] instead of state (needs n >= tile)
     const Op* ops;
+    double* zout;        // not NULL: the pass also writes <Z_zq> partials [tile][wavefront] (needs n >= tile)
+    int zq;
+    int nostore;         // with zout: the state is not written back
     const float* mats;   // [samples if rowdep][n_mats][8], matrices in execution order
     const int* exec_of;  // [n_mats]: (layer * n + qubit) -> execution-order index
     const float* ovr;    // gradient: [samples if rowdep][2P][8] shifted matrices
@@ -82,6 +85,9 @@ hipError_t launch_expz_finish(const double* partial, int64_t rows, int n, int q_
 struct Scatter { int64_t row0, per, stride, offset; };
 hipError_t launch_expz_finish_scatter(const double* partial, int64_t rows, int n, int q, double* out,
                                       const Scatter& sc, hipStream_t st);
+// out[scatter(row)] = sum of the row's per_row partials written by a pass with zout
+hipError_t launch_zsum_finish(const double* partial, int64_t rows, int64_t per_row, double* out,
+                              const Scatter& sc, hipStream_t st);
 // states[r] = src[sample of row r] for the rows of a gradient chunk (src: [samples][2^n])
 hipError_t launch_gather_rows(const float2* src, int n, int64_t rows, const RowMap& rm, float2* states,
                               hipStream_t st);

@@ -310,6 +310,22 @@ __global__ __launch_bounds__(1 << (T - R)) void k_pass(const PassArgs a) {
         }
         { const u64 nx = opp + 8; opslo = (unsigned)nx; opshi = (unsigned)(nx >> 32); }
     }
+    if (a.zout) {
+        // Last pass of a gradient row: <Z_q> of the tile instead of (or besides) the stored state.
+        // A lane sums its 16 probabilities with the sign of bit q (register part: per element,
+        // uniform; the rest: from the lane's index), a wavefront adds its lanes in double, and each
+        // wavefront writes one partial: [tile][wavefront], summed per row in a fixed order later.
+        const int zq = a.zq;
+        float acc = 0.f;
+#define QSV_Z(k) { const float p = vr##k * vr##k + vi##k * vi##k; \
+                   acc += ((expand((unsigned)k << scur) >> zq) & 1ull) ? -p : p; }
+        QSV_16(QSV_Z)
+#undef QSV_Z
+        if ((e0 >> zq) & 1ull) acc = -acc;
+        const double tot = wave_sum((double)acc);
+        if ((thr & 63u) == 0) a.zout[tb * (blockDim.x >> 6) + (thr >> 6)] = tot;
+        if (a.nostore) return;
+    }
     if (full && off32) {
         const unsigned lane_byte = (unsigned)(e0 ^ tile_base) * 8u;   // the lane's own index bits
 #define QSV_ST(k) { char* bp = (char*)(a.state + (tile_base | expand((unsigned)k << scur))); \
@@ -668,6 +684,18 @@ __global__ __launch_bounds__(256) void k_expz_finish(const double* partial, u64 
         if (out_f) out_f[o] = (float)acc;
         if (out_d) out_d[o] = acc;
     }
+}
+
+// Sums the per-wavefront <Z> partials the last pass wrote, one thread per row, in index order.
+__global__ __launch_bounds__(256) void k_zsum_finish(const double* partial, u64 rows, u64 per_row,
+                                                     double* out, Scatter sc) {
+    const u64 r = (u64)blockIdx.x * 256 + threadIdx.x;
+    if (r >= rows) return;
+    const double* p = partial + r * per_row;
+    double acc = 0.0;
+    for (u64 i = 0; i < per_row; ++i) acc += p[i];
+    const u64 gid = (u64)sc.row0 + r;
+    out[(gid / (u64)sc.per) * (u64)sc.stride + (u64)sc.offset + gid % (u64)sc.per] = acc;
 }
 
 // Copies each row's starting state from the per-sample source (16 bytes per lane and step).
@@ -1053,6 +1081,14 @@ hipError_t launch_expz_finish_scatter(const double* partial, int64_t rows, int n
     if (q < 0 || sc.per < 1) return hipErrorInvalidValue;
     hipLaunchKernelGGL(k_expz_finish, dim3(blocks_for((u64)rows, 4)), dim3(256), 0, st, partial, (u64)rows,
                        n, chunk_blocks(n), q, (float*)nullptr, out, sc);
+    return hipGetLastError();
+}
+
+hipError_t launch_zsum_finish(const double* partial, int64_t rows, int64_t per_row, double* out,
+                              const Scatter& sc, hipStream_t st) {
+    if (rows < 1 || per_row < 1 || sc.per < 1) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(k_zsum_finish, dim3(blocks_for((u64)rows, 256)), dim3(256), 0, st, partial, (u64)rows,
+                       (u64)per_row, out, sc);
     return hipGetLastError();
 }
 
