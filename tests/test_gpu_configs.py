@@ -143,3 +143,45 @@ def test_config4_full(oracle, capsys):
     F = gu.measure(ctx, qb.QSV_M_FIDELITY, (1,), x=xd)
     assert abs(F[0] - 1.0) <= 1e-5
     ctx.close()
+
+
+def test_largest_state_30_qubits_one_layer(oracle, capsys):
+    """Maximum size the boundary accepts (n = 30: 8 GiB of state).  Only here does a tile span 2^29
+    elements or more, which takes the pass kernel off its 32-bit addressing path.  One layer of
+    RX,RY,RZ + CNOT ring and its inverse; the comparison walks the state in slices."""
+    torch = gu.torch_cuda()
+    n = 30
+    spec = wl.CircuitSpec(1, (wl.RX, wl.RY, wl.RZ), wl.ENT_CNOT_RING)
+    params = wl.draw_params(spec, n, 2030)
+    g = np.random.Generator(np.random.PCG64(1030))
+    x = g.random(1 << n, dtype=np.float32)[None, :] - np.float32(0.5)
+    ctx = gu.make_ctx(n, 1)
+    xd = gu.dev(x)
+    ctx.qsv_amp_encode(xd)
+    ctx.qsv_apply_layers(qb.circuit_from_spec(spec), gu.dev(params), None, 0)
+    z = gu.measure(ctx, qb.QSV_M_EXPZ_ALL, (1, n))
+    torch.cuda.synchronize()
+    got = ctx.state.cpu().numpy()                      # [1][2^n][2] float32
+    with capsys.disabled():
+        print(" [n=30 gpu done]", end="", flush=True)
+    ref, _ = oracle.amp_encode(x, n)
+    oracle.apply_layers(ref, oracle.make_circuit(1, list(spec.rot), spec.entangler, 0), params)
+    with capsys.disabled():
+        print(" [n=30 oracle done]", end="", flush=True)
+    assert np.abs(z - oracle.expz_all(ref)).max() <= 1e-5
+    worst, err2, norm2 = 0.0, 0.0, 0.0
+    step = 1 << 26
+    for lo in range(0, 1 << n, step):
+        r = ref[0, lo:lo + step]
+        dr = got[0, lo:lo + step, 0].astype(np.float64) - r.real
+        di = got[0, lo:lo + step, 1].astype(np.float64) - r.imag
+        worst = max(worst, np.abs(dr).max(), np.abs(di).max())
+        err2 += float((dr * dr).sum() + (di * di).sum())
+        norm2 += float((got[0, lo:lo + step].astype(np.float64) ** 2).sum())
+    assert worst <= 1e-7 and err2 <= 1e-10            # amplitudes are about 3e-5 in size
+    assert abs(norm2 - 1.0) <= 1e-5
+    del ref, got
+    ctx.qsv_apply_layers(qb.circuit_from_spec(spec), gu.dev(params), None, 1)
+    F = gu.measure(ctx, qb.QSV_M_FIDELITY, (1,), x=xd)
+    assert abs(F[0] - 1.0) <= 1e-5
+    ctx.close()
