@@ -71,6 +71,8 @@ SMALL = [
     (7, 2, 3, (RY, RZ), LADDER, 0), (9, 5, 2, (RY, RZ), RING, 1), (10, 6, 3, (RY, RZ), RING, 1),
     (11, 3, 3, (RX, RY, RZ), RING, 0), (12, 2, 3, (RY, RZ), LADDER, 0), (13, 2, 2, (), RING, 0),
     (13, 3, 3, (RY, RZ), RING, 0), (14, 1, 3, (RZ, RX), NONE, 0),
+    (4, 65535, 1, (RY, RZ), RING, 0),      # largest batch the boundary accepts; ragged last tile
+    (5, 2, 0, (RY,), RING, 0),             # no layers: the state must come back unchanged
 ]
 
 
