@@ -209,6 +209,11 @@ def bench_c2(torch, qb, wl, args):
     ms, _ = run_steps(torch, step, steps, 1)
     ctx.qsv_set_option("grad_layered", 0)
     ms_whole, _ = run_steps(torch, step, steps, 1)
+
+    def step_adj(tm):
+        ctx.qsv_adjoint_grad(circ, xd, pd, None, 0, loss, grad, None, mg)
+
+    ms_adj, _ = run_steps(torch, step_adj, max(steps, 5), 1)
     ctx.close()
     return {"workload": "c2: 16 qubits, batch 256, 10 layers RY,RZ + CZ ladder, full parameter-shift gradient",
             "method": "layer by layer from kept states: a circuit that shifts a parameter of layer l runs layers l..L-1",
@@ -216,7 +221,10 @@ def bench_c2(torch, qb, wl, args):
             "updates_per_s": updates / (ms * 1e-3),
             "executed_updates": executed, "executed_updates_per_s": executed / (ms * 1e-3),
             "whole_circuits": {"ms_per_step": ms_whole, "executed_updates": updates,
-                               "executed_updates_per_s": updates / (ms_whole * 1e-3)}}
+                               "executed_updates_per_s": updates / (ms_whole * 1e-3)},
+            "adjoint": {"method": "qsv_adjoint_grad: same loss and gradient in reverse mode (one forward run, "
+                                  "psi and lambda taken back layer by layer, 2x2 transition sums per qubit)",
+                        "ms_per_step": ms_adj, "speedup_over_shift_rule": ms / ms_adj}}
 
 
 def bench_c1(torch, qb, wl, args):

@@ -153,6 +153,20 @@ qsv_status qsv_param_shift_grad(qsv_ctx* ctx, const qsv_circuit* c, const float*
                                 float* loss_dev, float* grad_dev, float* mean_loss_dev,
                                 float* mean_grad_dev);
 
+/* The same loss and gradient as qsv_param_shift_grad (same arguments, same outputs, equal up to
+ * rounding), evaluated in reverse mode (task statement: "gradients over the batch"; listed there
+ * as the cross-check of the shift rule).  Per sample one forward run gives psi and the loss; psi
+ * and lambda = Z_obs psi are then taken back through the layers together, and at the start of
+ * each layer the derivative with respect to an angle of slot s on qubit q is
+ * 2 Re <lambda| W^dagger (-i/2 P_s) W |psi> on that qubit, W = the layer's earlier slots on it,
+ * read off the 2x2 sums  M_q[a][b] = sum_rest conj(lambda[a, rest]) psi[b, rest].
+ * Work: about 3 L layers and L n reductions per sample instead of 2 P circuits.  Uses the workspace
+ * (three states per sample of a chunk); the context's state buffer is left untouched. */
+qsv_status qsv_adjoint_grad(qsv_ctx* ctx, const qsv_circuit* c, const float* x_dev, int64_t dim,
+                            const float* params_dev, const float* feats_dev, int32_t obs_qubit,
+                            float* loss_dev, float* grad_dev, float* mean_loss_dev,
+                            float* mean_grad_dev);
+
 /* Host-only introspection of the pass plan the library would run for a circuit (no GPU needed):
  * writes a text description (one line per pass, one token per operation) into buf and returns the
  * number of bytes needed (excluding the terminator), or -1 on a bad descriptor.  tile_log2 = 0

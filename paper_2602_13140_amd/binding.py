@@ -72,6 +72,9 @@ def load():
     L.qsv_param_shift_grad.restype = i32
     L.qsv_param_shift_grad.argtypes = [vp, ctypes.POINTER(qsv_circuit), vp, i64, vp, vp, ctypes.c_int32,
                                        vp, vp, vp, vp]
+    L.qsv_adjoint_grad.restype = i32
+    L.qsv_adjoint_grad.argtypes = [vp, ctypes.POINTER(qsv_circuit), vp, i64, vp, vp, ctypes.c_int32,
+                                       vp, vp, vp, vp]
     L.qsv_plan_describe.restype = i64
     L.qsv_plan_describe.argtypes = [ctypes.POINTER(qsv_circuit), i32, i32, i32, i32, ctypes.c_char_p, i64]
     L.qsv_probe_pass.restype = i32
@@ -187,6 +190,12 @@ class Context:
         r.shots = uniforms.shape[1] if uniforms is not None else 0
         r.out_dev = out.data_ptr()
         self._check(self.L.qsv_measure(self.h, ctypes.byref(r)))
+
+    def qsv_adjoint_grad(self, circ, x, params, feats, obs_qubit, loss, grad, mean_loss=None,
+                         mean_grad=None):
+        self._check(self.L.qsv_adjoint_grad(self.h, ctypes.byref(circ), _ptr(x), x.shape[1],
+                                            _ptr(params), _ptr(feats), obs_qubit, _ptr(loss),
+                                            _ptr(grad), _ptr(mean_loss), _ptr(mean_grad)))
 
     def qsv_param_shift_grad(self, circ, x, params, feats, obs_qubit, loss, grad, mean_loss=None,
                              mean_grad=None):

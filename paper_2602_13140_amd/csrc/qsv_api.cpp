@@ -686,6 +686,100 @@ qsv_status qsv_param_shift_grad(qsv_ctx* ctx, const qsv_circuit* c, const float*
     return QSV_OK;
 }
 
+qsv_status qsv_adjoint_grad(qsv_ctx* ctx, const qsv_circuit* c, const float* x_dev, int64_t dim,
+                            const float* params_dev, const float* feats_dev, int32_t obs_qubit,
+                            float* loss_dev, float* grad_dev, float* mean_loss_dev, float* mean_grad_dev) {
+    if (!ctx) return QSV_ERR_INVALID_ARG;
+    std::string why;
+    if (!check_circuit(c, ctx->n, &why)) return fail(ctx, QSV_ERR_INVALID_ARG, why);
+    const int n = ctx->n;
+    const int64_t B = ctx->batch;
+    if (!x_dev) return fail(ctx, QSV_ERR_INVALID_ARG, "x_dev is NULL");
+    if (dim < 1 || dim > ((int64_t)1 << n)) return fail(ctx, QSV_ERR_INVALID_ARG, "dim must be in 1..2^n");
+    if (obs_qubit < 0 || obs_qubit >= n) return fail(ctx, QSV_ERR_INVALID_ARG, "obs_qubit out of range");
+    const int64_t P = qsv_num_params(c, n);
+    if (P > 0 && !params_dev) return fail(ctx, QSV_ERR_INVALID_ARG, "params_dev is NULL");
+    if (c->reupload && !feats_dev) return fail(ctx, QSV_ERR_INVALID_ARG, "reupload = 1 needs feats_dev");
+    if (!loss_dev) return fail(ctx, QSV_ERR_INVALID_ARG, "loss_dev is NULL");
+    if (P > 0 && !grad_dev) return fail(ctx, QSV_ERR_INVALID_ARG, "grad_dev is NULL");
+    if (2 * P + 1 > 0x3fffffff) return fail(ctx, QSV_ERR_UNSUPPORTED, "too many parameters");
+    qsv_status st = bind_device(ctx);
+    if (st != QSV_OK) return st;
+
+    Arena ar(ctx);
+    const CircDev cd = to_dev(*c, n);
+    const int64_t per = 2 * P + 1;
+    const size_t state_bytes = (size_t)8 << n;
+    int nblk = (int)((dim + 4095) / 4096);
+    if (nblk > 1024) nblk = 1024;
+    double* npart = (double*)ar.take((size_t)B * nblk * 8);
+    double* inv = (double*)ar.take((size_t)B * 8);
+    float* mats = (float*)ar.take(mats_bytes(*c, n, B));
+    double* f = (double*)ar.take((size_t)B * per * 8);
+    if (!npart || !inv || !mats || !f) return ws_fail(ctx, ar, "qsv_adjoint_grad");
+    QSV_HIP(ctx, launch_sumsq(x_dev, B, dim, npart, nblk, ctx->stream), "sumsq");
+    QSV_HIP(ctx, launch_norm_finish(npart, nblk, B, inv, nullptr, ctx->stream), "norm");
+
+    // per sample of a chunk: psi alone (forward), then the (psi, lambda) pair, plus reduction partials
+    const size_t tpart = (size_t)n * adj_trans_blocks(n) * 8 * 8;
+    const size_t zbytes = (size_t)chunk_blocks(n) * 13 * 8;
+    const size_t sample_bytes = 3 * state_bytes + tpart + zbytes + 4 * kAlign;
+    int64_t chunk = (int64_t)(ar.remaining() / sample_bytes);
+    if (chunk < 1) { ar.need = ar.off + sample_bytes; return ws_fail(ctx, ar, "qsv_adjoint_grad"); }
+    if (chunk > B) chunk = B;
+    if (chunk > 16384) chunk = 16384;   // 2 * chunk rows index a grid dimension
+    if (ctx->opt_grad_chunk > 0 && chunk > ctx->opt_grad_chunk) chunk = ctx->opt_grad_chunk;
+    // keep row counts a power of two when several rows share a tile (extended-index tiling)
+    if (chunk < B) { int64_t p2 = 1; while (p2 * 2 <= chunk) p2 *= 2; chunk = p2; }
+    float2* A = (float2*)ar.take((size_t)chunk * state_bytes);
+    float2* S = (float2*)ar.take((size_t)2 * chunk * state_bytes);
+    double* tp = (double*)ar.take((size_t)chunk * tpart);
+    double* zpart = (double*)ar.take((size_t)chunk * zbytes);
+    if (!A || !S || !tp || !zpart) return ws_fail(ctx, ar, "qsv_adjoint_grad");
+
+    const int L = c->n_layers;
+    const int slots_n = (c->reupload + c->n_rot) * n;
+    qsv_circuit one = *c;
+    one.n_layers = 1;
+    for (int64_t b0 = 0; b0 < B; b0 += chunk) {
+        const int64_t bc = (B - b0) < chunk ? (B - b0) : chunk;
+        // forward: rows are samples b0..b0+bc-1
+        RowMap rm1;
+        rm1.grad = 1; rm1.two_p = 0; rm1.per = 1; rm1.row0 = b0; rm1.slots_n = slots_n < 1 ? 1 : slots_n; rm1.n = n;
+        QSV_HIP(ctx, launch_encode_write(x_dev, dim, n, bc, inv, rm1, A, ctx->stream), "encode rows");
+        {
+            Prepared pr;
+            st = prepare_circuit(ctx, *c, bc, 0, 0, params_dev, feats_dev, B, mats, &pr);
+            if (st != QSV_OK) return st;
+            st = run_circuit(ctx, *c, pr, A, bc, 0, nullptr, rm1);
+            if (st != QSV_OK) return st;
+        }
+        QSV_HIP(ctx, launch_expz_block(A, bc, n, zpart, ctx->stream), "expz block");
+        QSV_HIP(ctx, launch_expz_finish_scatter(zpart, bc, n, obs_qubit, f, Scatter{b0, 1, per, 2 * P}, ctx->stream),
+                "expz finish");
+        if (P == 0) continue;
+        // backward: row 2r = psi, row 2r+1 = lambda = Z_obs psi, both taken back layer by layer
+        QSV_HIP(ctx, launch_adj_init(A, n, obs_qubit, bc, S, ctx->stream), "adjoint init");
+        RowMap rm2 = rm1;
+        rm2.per = 2;
+        rm2.row0 = 2 * b0;
+        for (int l = L - 1; l >= 0; --l) {
+            const float* p_l = params_dev + (size_t)l * slots_n;
+            Prepared pr;
+            st = prepare_circuit(ctx, one, 2 * bc, 1, 0, p_l, feats_dev, B, mats, &pr);
+            if (st != QSV_OK) return st;
+            st = run_circuit(ctx, one, pr, S, 2 * bc, 1, nullptr, rm2);
+            if (st != QSV_OK) return st;
+            QSV_HIP(ctx, launch_adj_layer(S, n, bc, tp, cd, l, params_dev, feats_dev, b0, P, f, ctx->stream),
+                    "adjoint layer");
+        }
+    }
+    QSV_HIP(ctx, launch_grad_finish(f, B, P, cd, feats_dev, loss_dev, grad_dev, mean_loss_dev,
+                                    mean_grad_dev, ctx->stream),
+            "grad finish");
+    return QSV_OK;
+}
+
 qsv_status qsv_probe_pass(qsv_ctx* ctx, int low_bits, int window_start, int transposes) {
     if (!ctx) return QSV_ERR_INVALID_ARG;
     const int n = ctx->n;

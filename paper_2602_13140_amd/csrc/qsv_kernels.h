@@ -106,6 +106,16 @@ hipError_t launch_fidelity_finish(const double* partial, int nblk, int64_t rows,
 hipError_t launch_sample(const float2* state, int64_t rows, int n, const double* uniforms, int64_t shots,
                          unsigned long long* cum, long long* out, hipStream_t st);
 
+// Reverse-mode gradient.  launch_adj_init: S[2r] = A[r], S[2r+1] = Z_q A[r] (rows of A).
+// launch_adj_layer: for the row pairs of S (psi, lambda), both taken back to the start of `layer`,
+// the derivatives with respect to that layer's angles, written into f[sample][2p], f[sample][2p+1]
+// as (g, -g).  partial: row_pairs * n * adj_trans_blocks(n) * 8 doubles.
+hipError_t launch_adj_init(const float2* A, int n, int q, int64_t rows, float2* S, hipStream_t st);
+int adj_trans_blocks(int n);
+hipError_t launch_adj_layer(const float2* S, int n, int64_t row_pairs, double* partial, const CircDev& c,
+                            int layer, const float* params, const float* feats, int64_t sample0, int64_t P,
+                            double* f, hipStream_t st);
+
 // gradient assembly from f[B][2P+1] (double)
 hipError_t launch_grad_finish(const double* f, int64_t B, int64_t P, const CircDev& c, const float* feats,
                               float* loss, float* grad, float* mean_loss, float* mean_grad,

@@ -943,6 +943,104 @@ __global__ __launch_bounds__(256) void k_grad_mean(const double* f, u64 B, u64 P
     mean_grad[p] = (float)(acc / (double)B);
 }
 
+// ------------------------------------------------------------------------------------------
+// Reverse-mode (adjoint) gradient of <Z_obs>.  Rows come in pairs: 2r holds psi, 2r+1 holds lambda.
+
+// S[2r] = A[r], S[2r+1] = Z_q A[r]
+__global__ __launch_bounds__(256) void k_adj_init(const float2* A, int n, int q, u64 total, float2* S) {
+    const u64 e2 = ((u64)blockIdx.x * 256 + threadIdx.x) * 2;
+    if (e2 >= total) return;
+    const u64 r = e2 >> n, k = e2 & ((1ull << n) - 1);
+    const float4 v = *reinterpret_cast<const float4*>(A + e2);
+    float4 z = v;
+    if ((k >> q) & 1ull) { z.x = -z.x; z.y = -z.y; }
+    if (((k + 1) >> q) & 1ull) { z.z = -z.z; z.w = -z.w; }
+    *reinterpret_cast<float4*>(S + (((2 * r) << n) | k)) = v;
+    *reinterpret_cast<float4*>(S + (((2 * r + 1) << n) | k)) = z;
+}
+
+// M_q[a][b] = sum over the other qubits of conj(lambda[a, rest]) psi[b, rest], for one row pair
+// (blockIdx.z) and one qubit (blockIdx.y); a block covers 4096 index pairs and writes 8 doubles
+// (re, im of M00, M01, M10, M11).
+__global__ __launch_bounds__(256) void k_trans_block(const float2* S, int n, u64 pairs, int nblk,
+                                                     double* partial) {
+    __shared__ double sm[4];
+    const int q = blockIdx.y;
+    const u64 r = blockIdx.z;
+    const float2* psi = S + ((2 * r) << n);
+    const float2* lam = S + ((2 * r + 1) << n);
+    const u64 bit = 1ull << q;
+    float acc[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) acc[j] = 0.f;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+        const u64 p = (u64)blockIdx.x * 4096 + (u64)i * 256 + threadIdx.x;
+        if (p < pairs) {
+            const u64 k0 = ((p >> q) << (q + 1)) | (p & (bit - 1));
+            const u64 k1 = k0 | bit;
+            const float2 l0 = lam[k0], l1 = lam[k1], s0 = psi[k0], s1 = psi[k1];
+            acc[0] += l0.x * s0.x + l0.y * s0.y; acc[1] += l0.x * s0.y - l0.y * s0.x;
+            acc[2] += l0.x * s1.x + l0.y * s1.y; acc[3] += l0.x * s1.y - l0.y * s1.x;
+            acc[4] += l1.x * s0.x + l1.y * s0.y; acc[5] += l1.x * s0.y - l1.y * s0.x;
+            acc[6] += l1.x * s1.x + l1.y * s1.y; acc[7] += l1.x * s1.y - l1.y * s1.x;
+        }
+    }
+    double* out = partial + ((r * n + q) * (u64)nblk + blockIdx.x) * 8;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+        const double t = block_sum256((double)acc[j], sm);
+        if (threadIdx.x == 0) out[j] = t;
+    }
+}
+
+// Gradients of one layer from the transition matrices: thread = (row pair, slot, qubit).  With
+// W = R_{s-1} ... R_0 (the slots before s on that qubit) the derivative with respect to the angle of
+// slot s is 2 Re sum_ab Bt[a][b] M[a][b], Bt = W^dagger (-i/2 P_s) W.  Written as f+ = g, f- = -g so
+// that the same finishing kernels as for the shift rule apply (they halve the difference and
+// multiply re-upload weights by the feature).
+__global__ __launch_bounds__(256) void k_adj_layer(const double* partial, int nblk, CircDev c, int layer,
+                                                   const float* params, const float* feats, u64 sample0,
+                                                   u64 pairs_rows, u64 P, double* f) {
+    const u64 idx = (u64)blockIdx.x * 256 + threadIdx.x;
+    const int slots = c.reupload + c.n_rot;
+    const u64 per = (u64)slots * c.n;
+    if (idx >= pairs_rows * per) return;
+    const u64 r = idx / per;
+    const int s = (int)((idx % per) / c.n), q = (int)(idx % c.n);
+    const u64 sample = sample0 + r;
+    double M[8];
+    for (int j = 0; j < 8; ++j) M[j] = 0.0;
+    const double* pp = partial + ((r * c.n + q) * (u64)nblk) * 8;
+    for (int b = 0; b < nblk; ++b)
+        for (int j = 0; j < 8; ++j) M[j] += pp[(u64)b * 8 + j];
+    M2 w;
+    for (int k = 0; k < 4; ++k) { w.r[k] = (k == 0 || k == 3) ? 1.0 : 0.0; w.i[k] = 0.0; }
+    int axis = QSV_RX;
+    for (int sl = 0; sl <= s; ++sl) {
+        double t = (double)params[((u64)layer * slots + sl) * c.n + q];
+        if (c.reupload && sl == 0) { t *= (double)feats[sample * c.n + q]; axis = QSV_RX; }
+        else axis = c.rot[sl - c.reupload];
+        if (sl < s) w = mul_m(rot_m(axis, t), w);
+    }
+    // G = -i/2 P for the axis of slot s
+    M2 g;
+    for (int k = 0; k < 4; ++k) { g.r[k] = 0.0; g.i[k] = 0.0; }
+    if (axis == QSV_RX) { g.i[1] = -0.5; g.i[2] = -0.5; }
+    else if (axis == QSV_RY) { g.r[1] = -0.5; g.r[2] = 0.5; }
+    else { g.i[0] = -0.5; g.i[3] = 0.5; }
+    M2 wd;   // W^dagger
+    wd.r[0] = w.r[0]; wd.i[0] = -w.i[0]; wd.r[1] = w.r[2]; wd.i[1] = -w.i[2];
+    wd.r[2] = w.r[1]; wd.i[2] = -w.i[1]; wd.r[3] = w.r[3]; wd.i[3] = -w.i[3];
+    const M2 bt = mul_m(wd, mul_m(g, w));
+    double acc = 0.0;
+    for (int k = 0; k < 4; ++k) acc += bt.r[k] * M[2 * k] - bt.i[k] * M[2 * k + 1];
+    const u64 p = ((u64)layer * slots + s) * c.n + q;
+    double* fb = f + sample * (2 * P + 1);
+    fb[2 * p] = 2.0 * acc;
+    fb[2 * p + 1] = -2.0 * acc;
+}
+
 inline unsigned blocks_for(u64 items, unsigned per) { return (unsigned)((items + per - 1) / per); }
 
 }  // namespace
@@ -1155,6 +1253,31 @@ hipError_t launch_sample(const float2* state, int64_t rows, int n, const double*
     if (jobs == 0) return hipSuccess;
     hipLaunchKernelGGL(k_sample_draw, dim3(blocks_for(jobs, 4)), dim3(256), 0, st, state, n, nblk, cum,
                        uniforms, (u64)shots, jobs, out);
+    return hipGetLastError();
+}
+
+hipError_t launch_adj_init(const float2* A, int n, int q, int64_t rows, float2* S, hipStream_t st) {
+    if (n < 1 || rows < 1) return hipErrorInvalidValue;
+    const u64 total = (u64)rows << n;
+    hipLaunchKernelGGL(k_adj_init, dim3(blocks_for(total / 2, 256)), dim3(256), 0, st, A, n, q, total, S);
+    return hipGetLastError();
+}
+
+int adj_trans_blocks(int n) { return n - 1 > 12 ? 1 << (n - 1 - 12) : 1; }
+
+hipError_t launch_adj_layer(const float2* S, int n, int64_t row_pairs, double* partial, const CircDev& c,
+                            int layer, const float* params, const float* feats, int64_t sample0, int64_t P,
+                            double* f, hipStream_t st) {
+    if (row_pairs < 1 || row_pairs > 65535) return hipErrorInvalidValue;
+    const int nblk = adj_trans_blocks(n);
+    hipLaunchKernelGGL(k_trans_block, dim3(nblk, n, (unsigned)row_pairs), dim3(256), 0, st, S, n,
+                       (u64)1 << (n - 1), nblk, partial);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    const u64 jobs = (u64)row_pairs * c.slots() * c.n;
+    if (jobs == 0) return hipSuccess;
+    hipLaunchKernelGGL(k_adj_layer, dim3(blocks_for(jobs, 256)), dim3(256), 0, st, partial, nblk, c, layer,
+                       params, feats, (u64)sample0, (u64)row_pairs, (u64)P, f);
     return hipGetLastError();
 }
 

@@ -48,23 +48,26 @@ def test_config1_reupload_expz(oracle):
     ctx.close()
 
 
-@pytest.mark.parametrize("rot,layered", [((wl.RY, wl.RZ), 1), ((wl.RY, wl.RZ), 0), ((wl.RX, wl.RY, wl.RZ), 1)])
+@pytest.mark.parametrize("rot,layered", [((wl.RY, wl.RZ), 1), ((wl.RY, wl.RZ), 0), ((wl.RX, wl.RY, wl.RZ), 1),
+                                         ((wl.RY, wl.RZ), -1), ((wl.RX, wl.RY, wl.RZ), -1)])
 def test_config2_gradient_sampled(oracle, rot, layered):
     """Full 256 x P gradient on the GPU; the oracle recomputes two samples x 12 random parameters
     (plus their losses).  The three-rotation variant is the reading that gives ~480 params.
     layered = 1: workspace with room for the per-layer states, so shifted circuits start from them;
-    layered = 0: the minimum workspace, every shifted circuit runs whole."""
+    layered = 0: the minimum workspace, every shifted circuit runs whole; layered = -1: the
+    reverse-mode entry point qsv_adjoint_grad, which must give the same values."""
     torch = gu.torch_cuda()
     w = wl.config(2)
     spec = wl.CircuitSpec(w.circuit.n_layers, rot, w.circuit.entangler)
     P = spec.num_params(w.n)
     params = wl.draw_params(spec, w.n, 2002)
     circ = qb.circuit_from_spec(spec)
-    ctx = gu.make_ctx(w.n, w.batch, ws_bytes=qb.qsv_grad_workspace_bytes(w.n, w.batch, circ) if layered else None)
+    ctx = gu.make_ctx(w.n, w.batch, ws_bytes=qb.qsv_grad_workspace_bytes(w.n, w.batch, circ) if layered > 0 else None)
     loss = torch.zeros(w.batch, dtype=torch.float32, device="cuda")
     grad = torch.zeros((w.batch, P), dtype=torch.float32, device="cuda")
     mg = torch.zeros(P, dtype=torch.float32, device="cuda")
-    ctx.qsv_param_shift_grad(circ, gu.dev(w.x), gu.dev(params), None, 0, loss, grad, None, mg)
+    call = ctx.qsv_adjoint_grad if layered < 0 else ctx.qsv_param_shift_grad
+    call(circ, gu.dev(w.x), gu.dev(params), None, 0, loss, grad, None, mg)
     torch.cuda.synchronize()
     gg, ll = grad.cpu().numpy(), loss.cpu().numpy()
     g = np.random.Generator(np.random.PCG64(5))

@@ -210,7 +210,8 @@ def test_sampling_special_states():
     (6, 4, 2, (RY, RZ), RING, 1, 0), (10, 2, 2, (RY, RZ), LADDER, 0, 0), (12, 2, 1, (RY, RZ), RING, 1, 3),
     (13, 1, 2, (RY,), LADDER, 0, 0), (1, 4, 3, (RX, RZ), RING, 0, 0), (7, 3, 4, (RY, RZ), RING, 0, 6),
     (8, 5, 3, (RX, RZ), LADDER, 1, 2), (11, 2, 3, (RY, RZ), LADDER, 0, 10)])
-@pytest.mark.parametrize("mode", ["default", "naive", "whole", "chunk5", "whole-chunk4", "naive-whole"])
+@pytest.mark.parametrize("mode", ["default", "naive", "whole", "chunk5", "whole-chunk4", "naive-whole",
+                                  "adjoint", "adjoint-naive", "adjoint-chunk2"])
 def test_param_shift_grad_small(oracle, n, B, L, rot, ent, reup, obs, mode):
     torch = gu.torch_cuda()
     g = rng(40 + n)
@@ -232,8 +233,10 @@ def test_param_shift_grad_small(oracle, n, B, L, rot, ent, reup, obs, mode):
     grad = torch.zeros((B, P), dtype=torch.float32, device="cuda")
     ml = torch.zeros(1, dtype=torch.float32, device="cuda")
     mg = torch.zeros(P, dtype=torch.float32, device="cuda")
-    ctx.qsv_param_shift_grad(qb.circuit_from_spec(spec), gu.dev(x), gu.dev(params),
-                             gu.dev(feats) if reup else None, obs, loss, grad, ml, mg)
+    # "adjoint": the reverse-mode entry point; it must give the shift rule's values
+    call = ctx.qsv_adjoint_grad if "adjoint" in mode else ctx.qsv_param_shift_grad
+    call(qb.circuit_from_spec(spec), gu.dev(x), gu.dev(params), gu.dev(feats) if reup else None, obs,
+         loss, grad, ml, mg)
     torch.cuda.synchronize()
     assert np.abs(loss.cpu().numpy() - lref).max() <= 1e-5
     gg = grad.cpu().numpy()
