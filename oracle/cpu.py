@@ -223,3 +223,55 @@ def param_shift_grad(x, n, circ, params, feats=None, obs_qubit=0, subset=None):
     if rc:
         raise ValueError("oracle_param_shift_grad rc=%d" % rc)
     return loss, grad
+
+
+LOSS_TRASH, LOSS_MSE_Z = 1, 2
+
+
+def loss_grad(x, n, circ, params, feats=None, kind=LOSS_TRASH, mask=0, targets=None, subset=None):
+    """Per-sample training loss and its gradient by the shift rule (see oracle_loss_grad)."""
+    x = np.ascontiguousarray(x, dtype=np.float32)
+    B, dim = x.shape
+    params = np.ascontiguousarray(params, dtype=np.float64).ravel()
+    P = num_params(circ, n)
+    assert params.size == P
+    f = None
+    if feats is not None:
+        f = np.ascontiguousarray(feats, dtype=np.float64)
+        assert f.shape == (B, n)
+    y = None
+    if targets is not None:
+        y = np.ascontiguousarray(targets, dtype=np.float64)
+        assert y.shape == (B, n)
+    sub, nl = None, P
+    if subset is not None:
+        sub = np.ascontiguousarray(subset, dtype=np.int64)
+        nl = sub.size
+    loss = np.empty(B, dtype=np.float64)
+    grad = np.empty((B, nl), dtype=np.float64)
+    rc = lib().oracle_loss_grad(
+        _p(x), ctypes.c_int64(B), ctypes.c_int64(dim), ctypes.c_int(n), ctypes.byref(circ),
+        _p(params), _p(f) if f is not None else None, ctypes.c_int(kind), ctypes.c_uint64(mask),
+        _p(y) if y is not None else None, _p(sub) if sub is not None else None, ctypes.c_int64(nl),
+        _p(loss), _p(grad))
+    if rc:
+        raise ValueError("oracle_loss_grad rc=%d" % rc)
+    return loss, grad
+
+
+def sgd_step(params, grad, lr):
+    """theta <- theta - lr * g, in double, stored as float32 (the optimiser the training step uses)."""
+    p = np.asarray(params, dtype=np.float64) - float(lr) * np.asarray(grad, dtype=np.float64)
+    return p.astype(np.float32)
+
+
+def adam_step(params, grad, m, v, t, lr, beta1=0.9, beta2=0.999, eps=1e-8):
+    """One Adam update (Kingma & Ba, Algorithm 1) in double; returns float32 params, m, v.
+    t is the 1-based step count."""
+    g = np.asarray(grad, dtype=np.float64)
+    m = beta1 * np.asarray(m, dtype=np.float64) + (1.0 - beta1) * g
+    v = beta2 * np.asarray(v, dtype=np.float64) + (1.0 - beta2) * g * g
+    mh = m / (1.0 - beta1 ** t)
+    vh = v / (1.0 - beta2 ** t)
+    p = np.asarray(params, dtype=np.float64) - lr * mh / (np.sqrt(vh) + eps)
+    return p.astype(np.float32), m.astype(np.float32), v.astype(np.float32)

@@ -475,4 +475,91 @@ int oracle_param_shift_grad(const float* x, int64_t B, int64_t dim, int n, const
     return 0;
 }
 
+// ------------------------------------------------------------------------------------------------
+// Training losses and their gradients (task statement: "measurement (... trash-qubit marginal ...)"
+// and "parameter-shift gradients over the batch"; the two losses are the ones the workload configs
+// describe: an autoencoder that empties its trash qubits, and a regression of <Z_q> on targets).
+//   kind 1 (trash):  loss_b = 1 - P0_b,  P0 = probability that every qubit of mask reads 0.
+//                    P0 is the expectation of a projector, so the shift rule applies to it:
+//                    g = -1/2 [ P0(+) - P0(-) ].
+//   kind 2 (mse_z):  loss_b = 1/n sum_q ( <Z_q>_b - y[b][q] )^2.  Chain rule over the shift rule of
+//                    each <Z_q>:  g = 2/n sum_q ( <Z_q> - y ) 1/2 [ <Z_q>(+) - <Z_q>(-) ].
+// Re-upload weights get the factor feat_b[q] as in oracle_param_shift_grad.  subset as there.
+static double prob_mask_zero(const cplx* a, int n, uint64_t mask) {
+    const int64_t N = (int64_t)1 << n;
+    double s = 0.0;
+    for (int64_t k = 0; k < N; ++k)
+        if (((uint64_t)k & mask) == 0) s += std::norm(a[k]);
+    return s;
+}
+
+static void expz_vec(const cplx* a, int n, double* z) {
+    for (int q = 0; q < n; ++q) z[q] = expz_one(a, n, q);
+}
+
+int oracle_loss_grad(const float* x, int64_t B, int64_t dim, int n, const oracle_circuit* c,
+                     const double* params, const double* feats, int kind, uint64_t mask,
+                     const double* targets, const int64_t* subset, int64_t n_subset, double* loss,
+                     double* grad) {
+    if (check_circuit(c, n) || B < 1) return 1;
+    if (c->reupload && !feats) return 1;
+    if (kind == 1) { if (mask == 0 || (n < 64 && (mask >> n) != 0)) return 1; }
+    else if (kind == 2) { if (!targets) return 1; }
+    else return 1;
+    const int64_t N = (int64_t)1 << n;
+    if (dim < 1 || dim > N) return 1;
+    const int64_t P = oracle_num_params(c, n);
+    const int64_t nl = subset ? n_subset : P;
+    if (subset)
+        for (int64_t j = 0; j < n_subset; ++j)
+            if (subset[j] < 0 || subset[j] >= P) return 1;
+    const int slots = c->reupload + c->n_rot;
+    const double half_pi = 1.57079632679489661923;
+    for (int64_t b = 0; b < B; ++b) {
+        std::vector<cplx> enc((size_t)N), work((size_t)N);
+        std::vector<double> z0(n), zp(n), zm(n);
+        double nrm = 0.0;
+        oracle_amp_encode(x + b * dim, 1, dim, n, enc.data(), &nrm);
+        const double* fb = feats ? feats + b * n : nullptr;
+        const double* yb = targets ? targets + b * n : nullptr;
+        work = enc;
+        run_circuit(work.data(), n, c, params, fb, 0, -1, 0.0, 0);
+        if (kind == 1) {
+            if (loss) loss[b] = 1.0 - prob_mask_zero(work.data(), n, mask);
+        } else {
+            expz_vec(work.data(), n, z0.data());
+            double acc = 0.0;
+            for (int q = 0; q < n; ++q) acc += (z0[q] - yb[q]) * (z0[q] - yb[q]);
+            if (loss) loss[b] = acc / n;
+        }
+        for (int64_t j = 0; j < nl; ++j) {
+            const int64_t p = subset ? subset[j] : j;
+            double g;
+            if (kind == 1) {
+                work = enc;
+                run_circuit(work.data(), n, c, params, fb, 0, p, +half_pi, 0);
+                const double fp = prob_mask_zero(work.data(), n, mask);
+                work = enc;
+                run_circuit(work.data(), n, c, params, fb, 0, p, -half_pi, 0);
+                const double fm = prob_mask_zero(work.data(), n, mask);
+                g = -0.5 * (fp - fm);
+            } else {
+                work = enc;
+                run_circuit(work.data(), n, c, params, fb, 0, p, +half_pi, 0);
+                expz_vec(work.data(), n, zp.data());
+                work = enc;
+                run_circuit(work.data(), n, c, params, fb, 0, p, -half_pi, 0);
+                expz_vec(work.data(), n, zm.data());
+                g = 0.0;
+                for (int q = 0; q < n; ++q) g += (z0[q] - yb[q]) * 0.5 * (zp[q] - zm[q]);
+                g *= 2.0 / n;
+            }
+            const int slot = (int)((p / n) % slots);
+            if (c->reupload && slot == 0) g *= fb[p % n];
+            grad[b * nl + j] = g;
+        }
+    }
+    return 0;
+}
+
 }  // extern "C"

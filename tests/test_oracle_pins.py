@@ -391,3 +391,91 @@ def test_threads_do_not_change_results(oracle):
             outs.append(st)
         oracle.set_threads(oracle.max_threads())
         assert np.array_equal(outs[0], outs[1])
+
+
+# ------------------------------------------------------------------ training losses and optimisers
+def test_loss_grad_single_ry_closed_forms(oracle):
+    """|0> -> RY(theta): P(qubit reads 0) = cos^2(theta/2), <Z> = cos(theta)."""
+    circ = oracle.make_circuit(1, [RY], NONE)
+    x = np.array([[1.0, 0.0]], dtype=np.float32)
+    for theta in (0.3, 1.2, 2.5, 4.4):
+        loss, grad = oracle.loss_grad(x, 1, circ, [theta], kind=oracle.LOSS_TRASH, mask=1)
+        assert abs(loss[0] - np.sin(theta / 2) ** 2) < 1e-15
+        assert abs(grad[0, 0] - 0.5 * np.sin(theta)) < 1e-15
+        y = np.array([[0.37]])
+        loss, grad = oracle.loss_grad(x, 1, circ, [theta], kind=oracle.LOSS_MSE_Z, targets=y)
+        assert abs(loss[0] - (np.cos(theta) - 0.37) ** 2) < 1e-15
+        assert abs(grad[0, 0] + 2 * (np.cos(theta) - 0.37) * np.sin(theta)) < 1e-15
+
+
+@pytest.mark.parametrize("n,L,rot,ent,reup,kind", [
+    (3, 2, (RY, RZ), LADDER, 0, 1), (4, 2, (RX, RY, RZ), RING, 0, 1), (3, 2, (RY, RZ), RING, 1, 1),
+    (3, 2, (RY, RZ), LADDER, 0, 2), (4, 1, (RX, RY, RZ), RING, 0, 2), (3, 2, (RY, RZ), RING, 1, 2)])
+def test_loss_grad_vs_finite_difference(oracle, n, L, rot, ent, reup, kind):
+    """The loss is recomputed here from separately pinned pieces (apply_layers, marginal, expz_all),
+    and its central finite difference must match the shift-rule gradient."""
+    g = rng(70 + n + 2 * reup + kind)
+    circ = oracle.make_circuit(L, list(rot), ent, reup)
+    P = oracle.num_params(circ, n)
+    params = g.uniform(0, 2 * np.pi, P)
+    B = 2
+    x = g.standard_normal((B, 1 << n)).astype(np.float32)
+    feats = g.standard_normal((B, n)) if reup else None
+    mask = 0b101 if kind == 1 else 0
+    y = g.uniform(-1, 1, (B, n)) if kind == 2 else None
+    loss, grad = oracle.loss_grad(x, n, circ, params, feats, kind=kind, mask=mask, targets=y)
+
+    def f(pv):
+        st, _ = oracle.amp_encode(x, n)
+        oracle.apply_layers(st, circ, pv, feats)
+        if kind == 1:
+            return 1.0 - oracle.marginal(st, mask)[:, 0]
+        return ((oracle.expz_all(st) - y) ** 2).mean(1)
+
+    assert np.allclose(loss, f(params), atol=1e-14)
+    h = 1e-4
+    for p in range(P):
+        e = np.zeros(P)
+        e[p] = h
+        fd = (f(params + e) - f(params - e)) / (2 * h)
+        assert np.allclose(grad[:, p], fd, atol=2e-7), p
+    sub = [P - 1, 0, 2]
+    _, gs = oracle.loss_grad(x, n, circ, params, feats, kind=kind, mask=mask, targets=y, subset=sub)
+    assert np.array_equal(gs, grad[:, sub])
+
+
+def test_loss_grad_special_cases(oracle):
+    g = rng(77)
+    n = 3
+    circ = oracle.make_circuit(2, [RY, RZ], RING)
+    P = oracle.num_params(circ, n)
+    params = g.uniform(0, 2 * np.pi, P)
+    x = g.standard_normal((2, 8)).astype(np.float32)
+    # targets equal to the circuit's own <Z_q>: the loss and its gradient vanish
+    st, _ = oracle.amp_encode(x, n)
+    oracle.apply_layers(st, circ, params)
+    loss, grad = oracle.loss_grad(x, n, circ, params, kind=oracle.LOSS_MSE_Z, targets=oracle.expz_all(st))
+    assert np.all(np.abs(loss) < 1e-28) and np.all(np.abs(grad) < 1e-14)
+    # one trash qubit q: 1 - P0 = (1 - <Z_q>) / 2, so the gradient is minus half the <Z_q> gradient
+    for q in range(n):
+        lt, gt = oracle.loss_grad(x, n, circ, params, kind=oracle.LOSS_TRASH, mask=1 << q)
+        lz, gz = oracle.param_shift_grad(x, n, circ, params, obs_qubit=q)
+        assert np.allclose(lt, 0.5 * (1 - lz), atol=1e-14) and np.allclose(gt, -0.5 * gz, atol=1e-14)
+    assert np.all((lt >= 0) & (lt <= 1))
+
+
+def test_optimiser_steps_closed_forms(oracle):
+    p = np.array([1.0, -2.0, 0.5], dtype=np.float32)
+    g = np.array([0.25, -4.0, 0.0], dtype=np.float32)
+    assert np.array_equal(oracle.sgd_step(p, g, 0.5), np.array([0.875, 0.0, 0.5], dtype=np.float32))
+    # first Adam step from zero moments: m_hat = g, v_hat = g^2, so the step is lr * g / (|g| + eps)
+    lr, eps = 0.01, 1e-8
+    p1, m1, v1 = oracle.adam_step(p, g, np.zeros(3), np.zeros(3), 1, lr, 0.9, 0.999, eps)
+    want = p.astype(np.float64) - lr * g / (np.abs(g) + eps)
+    assert np.allclose(p1, want, atol=1e-7) and p1[2] == p[2]
+    assert np.allclose(m1, 0.1 * g, atol=1e-9) and np.allclose(v1, 0.001 * g.astype(np.float64) ** 2, atol=1e-9)
+    # constant gradient: the bias-corrected moments stay at g and g^2, every step has the same size
+    q, m, v = p.copy(), np.zeros(3), np.zeros(3)
+    for t in range(1, 6):
+        q, m, v = oracle.adam_step(q, g, m, v, t, lr)
+    assert np.allclose(q, p - 5 * lr * np.sign(g), atol=1e-5)
