@@ -247,6 +247,50 @@ def bench_c1(torch, qb, wl, args):
             "ms_per_step": ms, "updates": updates, "updates_per_s": updates / (ms * 1e-3)}
 
 
+def bench_train(torch, qb, wl, args, idx):
+    """A training step on config 3 (loss 1 - P0 on the trash qubits after the encoder) or config 1
+    (mean squared error of <Z_q> against seeded targets): loss and gradient of every sample for
+    every parameter in reverse mode, batch means, one Adam step, all on the device."""
+    import numpy as np
+    w = wl.config(idx)
+    n, B = w.n, w.batch
+    circ = qb.circuit_from_spec(w.circuit)
+    P = w.circuit.num_params(n)
+    ctx = qb.Context(n, B, ws_bytes=qb.qsv_grad_workspace_bytes(n, B, circ))
+    xd = torch.from_numpy(w.x).cuda()
+    pd = torch.from_numpy(w.params.copy()).cuda()
+    fd = torch.from_numpy(w.feats).cuda() if w.feats is not None else None
+    y = np.random.Generator(np.random.PCG64(4001)).uniform(-1, 1, (B, n)).astype(np.float32)
+    yd = torch.from_numpy(y).cuda()
+    loss = torch.empty(B, dtype=torch.float32, device="cuda")
+    grad = torch.empty((B, P), dtype=torch.float32, device="cuda")
+    ml = torch.empty(1, dtype=torch.float32, device="cuda")
+    mg = torch.empty(P, dtype=torch.float32, device="cuda")
+    m = torch.zeros(P, dtype=torch.float32, device="cuda")
+    v = torch.zeros(P, dtype=torch.float32, device="cuda")
+    t = [0]
+
+    def step(tm):
+        if idx == 3:
+            ctx.qsv_loss_grad(circ, xd, pd, None, qb.QSV_LOSS_TRASH, loss, grad, ml, mg, mask=w.trash_mask)
+        else:
+            ctx.qsv_loss_grad(circ, xd, pd, fd, qb.QSV_LOSS_MSE_Z, loss, grad, ml, mg, targets=yd)
+        t[0] += 1
+        ctx.qsv_adam_step(pd, mg, m, v, t[0], 0.01)
+
+    steps = max(1, min(args.steps, 5))
+    ms, _ = run_steps(torch, step, steps, 1)
+    torch.cuda.synchronize()
+    out = {"workload": ("c3 training step: 20 qubits, batch 32, 20-layer encoder, loss 1 - P0 on 4 trash qubits"
+                        if idx == 3 else
+                        "c1 training step: 10 qubits, batch 1024, 6 re-uploading layers, squared error on <Z_q>"),
+           "method": "qsv_loss_grad (reverse mode) + qsv_adam_step", "params": P, "steps": steps,
+           "ms_per_step": ms, "mean_loss_after": float(ml.item()),
+           "shift_rule_circuits_replaced": B * (2 * P + 1)}
+    ctx.close()
+    return out
+
+
 def bench_c0(torch, qb, wl, args):
     w = wl.config(0)
     n, B = w.n, w.batch
@@ -341,10 +385,12 @@ def main():
         sys.exit(2)
     if 3 in which and w4 is not None:
         others["c3"] = bench_c3(torch, qb, wl, args)
+        others["c3_train"] = bench_train(torch, qb, wl, args, 3)
     if 2 in which:
         others["c2"] = bench_c2(torch, qb, wl, args)
     if 1 in which:
         others["c1"] = bench_c1(torch, qb, wl, args)
+        others["c1_train"] = bench_train(torch, qb, wl, args, 1)
     if 0 in which:
         others["c0"] = bench_c0(torch, qb, wl, args)
     cpu = None

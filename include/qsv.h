@@ -167,6 +167,34 @@ qsv_status qsv_adjoint_grad(qsv_ctx* ctx, const qsv_circuit* c, const float* x_d
                             float* loss_dev, float* grad_dev, float* mean_loss_dev,
                             float* mean_grad_dev);
 
+/* Training losses built from the measured quantities (task statement: the autoencoder of workload
+ * config 3 empties its trash qubits; the re-uploading model of config 1 regresses <Z_q>).
+ *   QSV_LOSS_TRASH: loss_b = 1 - P0_b, P0 = probability that every qubit of mask reads 0.
+ *   QSV_LOSS_MSE_Z: loss_b = 1/n sum_q (<Z_q>_b - targets[b][q])^2, targets_dev float [batch][n]. */
+typedef enum { QSV_LOSS_TRASH = 1, QSV_LOSS_MSE_Z = 2 } qsv_loss_kind;
+typedef struct {
+    int32_t kind;             /* qsv_loss_kind */
+    int32_t reserved;         /* 0 */
+    uint64_t mask;            /* QSV_LOSS_TRASH: trash qubits, bit q = qubit q; at least one, all < n_qubits */
+    const float* targets_dev; /* QSV_LOSS_MSE_Z: [batch][n_qubits]; else ignored */
+} qsv_loss;
+
+/* Per-sample loss [batch] and gradient [batch][P] of a training loss, and optionally their batch
+ * means, evaluated in reverse mode as in qsv_adjoint_grad (lambda = O psi with O = -P0 projector,
+ * or sum_q 2/n (<Z_q> - y) Z_q); the values are those of the shift rule.  Arguments as
+ * qsv_param_shift_grad; loss is a host struct read during the call. */
+qsv_status qsv_loss_grad(qsv_ctx* ctx, const qsv_circuit* c, const float* x_dev, int64_t dim,
+                         const float* params_dev, const float* feats_dev, const qsv_loss* loss,
+                         float* loss_dev, float* grad_dev, float* mean_loss_dev, float* mean_grad_dev);
+
+/* Optimiser steps on the device, asynchronous on the context's stream; arithmetic in double, storage
+ * float.  qsv_sgd_step: params -= lr * grad.  qsv_adam_step (Kingma and Ba, Algorithm 1): m, v are
+ * the caller's moment buffers [count] (zero before the first step), t >= 1 the step count.
+ * count = 0 is a no-op; bad arguments return QSV_ERR_INVALID_ARG. */
+qsv_status qsv_sgd_step(qsv_ctx* ctx, float* params_dev, const float* grad_dev, int64_t count, double lr);
+qsv_status qsv_adam_step(qsv_ctx* ctx, float* params_dev, const float* grad_dev, float* m_dev, float* v_dev,
+                         int64_t count, int64_t t, double lr, double beta1, double beta2, double eps);
+
 /* Host-only introspection of the pass plan the library would run for a circuit (no GPU needed):
  * writes a text description (one line per pass, one token per operation) into buf and returns the
  * number of bytes needed (excluding the terminator), or -1 on a bad descriptor.  tile_log2 = 0

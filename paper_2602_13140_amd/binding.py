@@ -31,6 +31,14 @@ class qsv_measure_req(ctypes.Structure):
                 ("out_dev", ctypes.c_void_p)]
 
 
+class qsv_loss(ctypes.Structure):
+    _fields_ = [("kind", ctypes.c_int32), ("reserved", ctypes.c_int32), ("mask", ctypes.c_uint64),
+                ("targets_dev", ctypes.c_void_p)]
+
+
+QSV_LOSS_TRASH, QSV_LOSS_MSE_Z = 1, 2
+
+
 class QsvError(RuntimeError):
     def __init__(self, status, message):
         super().__init__("qsv status %d: %s" % (status, message))
@@ -75,6 +83,14 @@ def load():
     L.qsv_adjoint_grad.restype = i32
     L.qsv_adjoint_grad.argtypes = [vp, ctypes.POINTER(qsv_circuit), vp, i64, vp, vp, ctypes.c_int32,
                                        vp, vp, vp, vp]
+    L.qsv_loss_grad.restype = i32
+    L.qsv_loss_grad.argtypes = [vp, ctypes.POINTER(qsv_circuit), vp, i64, vp, vp, ctypes.POINTER(qsv_loss),
+                                vp, vp, vp, vp]
+    L.qsv_sgd_step.restype = i32
+    L.qsv_sgd_step.argtypes = [vp, vp, vp, i64, ctypes.c_double]
+    L.qsv_adam_step.restype = i32
+    L.qsv_adam_step.argtypes = [vp, vp, vp, vp, vp, i64, i64, ctypes.c_double, ctypes.c_double,
+                                ctypes.c_double, ctypes.c_double]
     L.qsv_plan_describe.restype = i64
     L.qsv_plan_describe.argtypes = [ctypes.POINTER(qsv_circuit), i32, i32, i32, i32, ctypes.c_char_p, i64]
     L.qsv_probe_pass.restype = i32
@@ -190,6 +206,20 @@ class Context:
         r.shots = uniforms.shape[1] if uniforms is not None else 0
         r.out_dev = out.data_ptr()
         self._check(self.L.qsv_measure(self.h, ctypes.byref(r)))
+
+    def qsv_loss_grad(self, circ, x, params, feats, kind, loss, grad, mean_loss=None, mean_grad=None,
+                      mask=0, targets=None):
+        spec = qsv_loss(kind, 0, mask, None if targets is None else targets.data_ptr())
+        self._check(self.L.qsv_loss_grad(self.h, ctypes.byref(circ), _ptr(x), x.shape[1], _ptr(params),
+                                         _ptr(feats), ctypes.byref(spec), _ptr(loss), _ptr(grad),
+                                         _ptr(mean_loss), _ptr(mean_grad)))
+
+    def qsv_sgd_step(self, params, grad, lr):
+        self._check(self.L.qsv_sgd_step(self.h, _ptr(params), _ptr(grad), params.numel(), lr))
+
+    def qsv_adam_step(self, params, grad, m, v, t, lr, beta1=0.9, beta2=0.999, eps=1e-8):
+        self._check(self.L.qsv_adam_step(self.h, _ptr(params), _ptr(grad), _ptr(m), _ptr(v), params.numel(),
+                                         t, lr, beta1, beta2, eps))
 
     def qsv_adjoint_grad(self, circ, x, params, feats, obs_qubit, loss, grad, mean_loss=None,
                          mean_grad=None):

@@ -686,9 +686,12 @@ qsv_status qsv_param_shift_grad(qsv_ctx* ctx, const qsv_circuit* c, const float*
     return QSV_OK;
 }
 
-qsv_status qsv_adjoint_grad(qsv_ctx* ctx, const qsv_circuit* c, const float* x_dev, int64_t dim,
-                            const float* params_dev, const float* feats_dev, int32_t obs_qubit,
-                            float* loss_dev, float* grad_dev, float* mean_loss_dev, float* mean_grad_dev) {
+// Reverse-mode loss and gradient for a diagonal observable: kind 0 <Z_q>; 1 the loss 1 - P0(mask);
+// 2 the mean squared error of <Z_q> against targets [batch][n].
+static qsv_status adjoint_impl(qsv_ctx* ctx, const qsv_circuit* c, const float* x_dev, int64_t dim,
+                               const float* params_dev, const float* feats_dev, int kind, int32_t obs_qubit,
+                               uint64_t mask, const float* targets_dev, float* loss_dev, float* grad_dev,
+                               float* mean_loss_dev, float* mean_grad_dev) {
     if (!ctx) return QSV_ERR_INVALID_ARG;
     std::string why;
     if (!check_circuit(c, ctx->n, &why)) return fail(ctx, QSV_ERR_INVALID_ARG, why);
@@ -696,7 +699,10 @@ qsv_status qsv_adjoint_grad(qsv_ctx* ctx, const qsv_circuit* c, const float* x_d
     const int64_t B = ctx->batch;
     if (!x_dev) return fail(ctx, QSV_ERR_INVALID_ARG, "x_dev is NULL");
     if (dim < 1 || dim > ((int64_t)1 << n)) return fail(ctx, QSV_ERR_INVALID_ARG, "dim must be in 1..2^n");
-    if (obs_qubit < 0 || obs_qubit >= n) return fail(ctx, QSV_ERR_INVALID_ARG, "obs_qubit out of range");
+    if (kind == 0 && (obs_qubit < 0 || obs_qubit >= n)) return fail(ctx, QSV_ERR_INVALID_ARG, "obs_qubit out of range");
+    if (kind == 1 && (mask == 0 || (mask >> n) != 0))
+        return fail(ctx, QSV_ERR_INVALID_ARG, "mask must name at least one qubit and none beyond n_qubits");
+    if (kind == 2 && !targets_dev) return fail(ctx, QSV_ERR_INVALID_ARG, "targets_dev is NULL");
     const int64_t P = qsv_num_params(c, n);
     if (P > 0 && !params_dev) return fail(ctx, QSV_ERR_INVALID_ARG, "params_dev is NULL");
     if (c->reupload && !feats_dev) return fail(ctx, QSV_ERR_INVALID_ARG, "reupload = 1 needs feats_dev");
@@ -723,7 +729,7 @@ qsv_status qsv_adjoint_grad(qsv_ctx* ctx, const qsv_circuit* c, const float* x_d
     // per sample of a chunk: psi alone (forward), then the (psi, lambda) pair, plus reduction partials
     const size_t tpart = (size_t)n * adj_trans_blocks(n) * 8 * 8;
     const size_t zbytes = (size_t)chunk_blocks(n) * 13 * 8;
-    const size_t sample_bytes = 3 * state_bytes + tpart + zbytes + 4 * kAlign;
+    const size_t sample_bytes = 3 * state_bytes + tpart + zbytes + 2 * (size_t)n * 8 + 6 * kAlign;
     int64_t chunk = (int64_t)(ar.remaining() / sample_bytes);
     if (chunk < 1) { ar.need = ar.off + sample_bytes; return ws_fail(ctx, ar, "qsv_adjoint_grad"); }
     if (chunk > B) chunk = B;
@@ -735,7 +741,9 @@ qsv_status qsv_adjoint_grad(qsv_ctx* ctx, const qsv_circuit* c, const float* x_d
     float2* S = (float2*)ar.take((size_t)2 * chunk * state_bytes);
     double* tp = (double*)ar.take((size_t)chunk * tpart);
     double* zpart = (double*)ar.take((size_t)chunk * zbytes);
-    if (!A || !S || !tp || !zpart) return ws_fail(ctx, ar, "qsv_adjoint_grad");
+    double* zall = (double*)ar.take((size_t)chunk * n * 8);
+    double* coef = (double*)ar.take((size_t)chunk * n * 8);
+    if (!A || !S || !tp || !zpart || !zall || !coef) return ws_fail(ctx, ar, "qsv_adjoint_grad");
 
     const int L = c->n_layers;
     const int slots_n = (c->reupload + c->n_rot) * n;
@@ -754,12 +762,22 @@ qsv_status qsv_adjoint_grad(qsv_ctx* ctx, const qsv_circuit* c, const float* x_d
             st = run_circuit(ctx, *c, pr, A, bc, 0, nullptr, rm1);
             if (st != QSV_OK) return st;
         }
-        QSV_HIP(ctx, launch_expz_block(A, bc, n, zpart, ctx->stream), "expz block");
-        QSV_HIP(ctx, launch_expz_finish_scatter(zpart, bc, n, obs_qubit, f, Scatter{b0, 1, per, 2 * P}, ctx->stream),
-                "expz finish");
+        // the loss of every sample of the chunk into f[sample][2P]
+        if (kind == 0) {
+            QSV_HIP(ctx, launch_expz_block(A, bc, n, zpart, ctx->stream), "expz block");
+            QSV_HIP(ctx, launch_expz_finish_scatter(zpart, bc, n, obs_qubit, f, Scatter{b0, 1, per, 2 * P},
+                                                    ctx->stream),
+                    "expz finish");
+        } else if (kind == 1) {
+            QSV_HIP(ctx, launch_trash_loss(A, n, mask, bc, b0, P, zpart, f, ctx->stream), "trash loss");
+        } else {
+            QSV_HIP(ctx, launch_expz_block(A, bc, n, zpart, ctx->stream), "expz block");
+            QSV_HIP(ctx, launch_expz_finish(zpart, bc, n, -1, nullptr, zall, ctx->stream), "expz finish");
+            QSV_HIP(ctx, launch_mse_coef(zall, targets_dev, n, bc, b0, P, coef, f, ctx->stream), "mse loss");
+        }
         if (P == 0) continue;
-        // backward: row 2r = psi, row 2r+1 = lambda = Z_obs psi, both taken back layer by layer
-        QSV_HIP(ctx, launch_adj_init(A, n, obs_qubit, bc, S, ctx->stream), "adjoint init");
+        // backward: row 2r = psi, row 2r+1 = lambda = O psi, both taken back layer by layer
+        QSV_HIP(ctx, launch_adj_init(A, n, kind, obs_qubit, mask, coef, bc, S, ctx->stream), "adjoint init");
         RowMap rm2 = rm1;
         rm2.per = 2;
         rm2.row0 = 2 * b0;
@@ -777,6 +795,47 @@ qsv_status qsv_adjoint_grad(qsv_ctx* ctx, const qsv_circuit* c, const float* x_d
     QSV_HIP(ctx, launch_grad_finish(f, B, P, cd, feats_dev, loss_dev, grad_dev, mean_loss_dev,
                                     mean_grad_dev, ctx->stream),
             "grad finish");
+    return QSV_OK;
+}
+
+qsv_status qsv_adjoint_grad(qsv_ctx* ctx, const qsv_circuit* c, const float* x_dev, int64_t dim,
+                            const float* params_dev, const float* feats_dev, int32_t obs_qubit,
+                            float* loss_dev, float* grad_dev, float* mean_loss_dev, float* mean_grad_dev) {
+    return adjoint_impl(ctx, c, x_dev, dim, params_dev, feats_dev, 0, obs_qubit, 0, nullptr, loss_dev,
+                        grad_dev, mean_loss_dev, mean_grad_dev);
+}
+
+qsv_status qsv_loss_grad(qsv_ctx* ctx, const qsv_circuit* c, const float* x_dev, int64_t dim,
+                         const float* params_dev, const float* feats_dev, const qsv_loss* loss,
+                         float* loss_dev, float* grad_dev, float* mean_loss_dev, float* mean_grad_dev) {
+    if (!ctx) return QSV_ERR_INVALID_ARG;
+    if (!loss) return fail(ctx, QSV_ERR_INVALID_ARG, "loss is NULL");
+    if (loss->kind != QSV_LOSS_TRASH && loss->kind != QSV_LOSS_MSE_Z)
+        return fail(ctx, QSV_ERR_INVALID_ARG, "unknown loss kind");
+    return adjoint_impl(ctx, c, x_dev, dim, params_dev, feats_dev, loss->kind == QSV_LOSS_TRASH ? 1 : 2, 0,
+                        loss->mask, loss->targets_dev, loss_dev, grad_dev, mean_loss_dev, mean_grad_dev);
+}
+
+qsv_status qsv_sgd_step(qsv_ctx* ctx, float* params_dev, const float* grad_dev, int64_t count, double lr) {
+    if (!ctx) return QSV_ERR_INVALID_ARG;
+    if (count < 0 || (count > 0 && (!params_dev || !grad_dev)))
+        return fail(ctx, QSV_ERR_INVALID_ARG, "qsv_sgd_step: bad arguments");
+    qsv_status st = bind_device(ctx);
+    if (st != QSV_OK) return st;
+    QSV_HIP(ctx, launch_sgd(params_dev, grad_dev, count, lr, ctx->stream), "sgd step");
+    return QSV_OK;
+}
+
+qsv_status qsv_adam_step(qsv_ctx* ctx, float* params_dev, const float* grad_dev, float* m_dev, float* v_dev,
+                         int64_t count, int64_t t, double lr, double beta1, double beta2, double eps) {
+    if (!ctx) return QSV_ERR_INVALID_ARG;
+    if (count < 0 || t < 1 || (count > 0 && (!params_dev || !grad_dev || !m_dev || !v_dev)) ||
+        !(beta1 >= 0.0 && beta1 < 1.0) || !(beta2 >= 0.0 && beta2 < 1.0) || !(eps > 0.0))
+        return fail(ctx, QSV_ERR_INVALID_ARG, "qsv_adam_step: bad arguments");
+    qsv_status st = bind_device(ctx);
+    if (st != QSV_OK) return st;
+    QSV_HIP(ctx, launch_adam(params_dev, grad_dev, m_dev, v_dev, count, t, lr, beta1, beta2, eps, ctx->stream),
+            "adam step");
     return QSV_OK;
 }
 

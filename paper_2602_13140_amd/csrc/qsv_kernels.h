@@ -106,11 +106,24 @@ hipError_t launch_fidelity_finish(const double* partial, int nblk, int64_t rows,
 hipError_t launch_sample(const float2* state, int64_t rows, int n, const double* uniforms, int64_t shots,
                          unsigned long long* cum, long long* out, hipStream_t st);
 
-// Reverse-mode gradient.  launch_adj_init: S[2r] = A[r], S[2r+1] = Z_q A[r] (rows of A).
+// Reverse-mode gradient.  launch_adj_init: S[2r] = A[r], S[2r+1] = O A[r] (rows of A) for the
+// diagonal observable O: kind 0 Z_q; kind 1 -P0(mask); kind 2 sum_q coef[r][q] Z_q.
+// launch_trash_loss: f[sample0+r][2P] = 1 - P0(mask) of row r (partial: rows * blocks doubles, blocks
+// as for the <Z> reductions).  launch_mse_coef: from z[rows][n] and targets y[samples][n], the loss
+// 1/n sum (z-y)^2 into f[.][2P] and coef = 2/n (z-y).
 // launch_adj_layer: for the row pairs of S (psi, lambda), both taken back to the start of `layer`,
 // the derivatives with respect to that layer's angles, written into f[sample][2p], f[sample][2p+1]
 // as (g, -g).  partial: row_pairs * n * adj_trans_blocks(n) * 8 doubles.
-hipError_t launch_adj_init(const float2* A, int n, int q, int64_t rows, float2* S, hipStream_t st);
+hipError_t launch_adj_init(const float2* A, int n, int kind, int q, uint64_t mask, const double* coef,
+                           int64_t rows, float2* S, hipStream_t st);
+hipError_t launch_trash_loss(const float2* A, int n, uint64_t mask, int64_t rows, int64_t sample0, int64_t P,
+                             double* partial, double* f, hipStream_t st);
+hipError_t launch_mse_coef(const double* z, const float* y, int n, int64_t rows, int64_t sample0, int64_t P,
+                           double* coef, double* f, hipStream_t st);
+// optimiser steps in double on float storage; t is the 1-based step count of Adam
+hipError_t launch_sgd(float* p, const float* g, int64_t count, double lr, hipStream_t st);
+hipError_t launch_adam(float* p, const float* g, float* m, float* v, int64_t count, int64_t t, double lr,
+                       double b1, double b2, double eps, hipStream_t st);
 int adj_trans_blocks(int n);
 hipError_t launch_adj_layer(const float2* S, int n, int64_t row_pairs, double* partial, const CircDev& c,
                             int layer, const float* params, const float* feats, int64_t sample0, int64_t P,

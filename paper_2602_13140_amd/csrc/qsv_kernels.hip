@@ -946,17 +946,70 @@ __global__ __launch_bounds__(256) void k_grad_mean(const double* f, u64 B, u64 P
 // ------------------------------------------------------------------------------------------
 // Reverse-mode (adjoint) gradient of <Z_obs>.  Rows come in pairs: 2r holds psi, 2r+1 holds lambda.
 
-// S[2r] = A[r], S[2r+1] = Z_q A[r]
-__global__ __launch_bounds__(256) void k_adj_init(const float2* A, int n, int q, u64 total, float2* S) {
+// S[2r] = A[r], S[2r+1] = O A[r] for a diagonal observable O given by its weight w(k):
+//   kind 0: Z_q,             w = +1 / -1 by bit q
+//   kind 1: -P0(mask),       w = -1 where no bit of mask is set, else 0  (loss 1 - P0)
+//   kind 2: sum_q c[r][q] Z_q, w = sum_q c[r][q] (1 - 2 bit_q(k))        (chain rule of the squared error)
+struct AdjObs { int kind; int q; u64 mask; const double* coef; };
+
+__device__ __forceinline__ float adj_weight(const AdjObs& o, u64 r, u64 k, int n) {
+    if (o.kind == 0) return ((k >> o.q) & 1ull) ? -1.f : 1.f;
+    if (o.kind == 1) return (k & o.mask) ? 0.f : -1.f;
+    double w = 0.0;
+    const double* c = o.coef + r * n;
+    for (int q = 0; q < n; ++q) w += ((k >> q) & 1ull) ? -c[q] : c[q];
+    return (float)w;
+}
+
+__global__ __launch_bounds__(256) void k_adj_init(const float2* A, int n, AdjObs o, u64 total, float2* S) {
     const u64 e2 = ((u64)blockIdx.x * 256 + threadIdx.x) * 2;
     if (e2 >= total) return;
     const u64 r = e2 >> n, k = e2 & ((1ull << n) - 1);
     const float4 v = *reinterpret_cast<const float4*>(A + e2);
-    float4 z = v;
-    if ((k >> q) & 1ull) { z.x = -z.x; z.y = -z.y; }
-    if (((k + 1) >> q) & 1ull) { z.z = -z.z; z.w = -z.w; }
+    const float w0 = adj_weight(o, r, k, n), w1 = adj_weight(o, r, k + 1, n);
+    float4 z;
+    z.x = w0 * v.x; z.y = w0 * v.y; z.z = w1 * v.z; z.w = w1 * v.w;
     *reinterpret_cast<float4*>(S + (((2 * r) << n) | k)) = v;
     *reinterpret_cast<float4*>(S + (((2 * r + 1) << n) | k)) = z;
+}
+
+// P0(mask) of every row: block partials, then one thread per row; f[sample][2P] = 1 - P0.
+__global__ __launch_bounds__(256) void k_p0_block(const float2* A, int n, u64 mask, int nblk, double* partial) {
+    __shared__ double sm[4];
+    const u64 r = blockIdx.y, N = 1ull << n;
+    const float2* a = A + (r << n);
+    float acc = 0.f;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+        const u64 k = (u64)blockIdx.x * 4096 + (u64)i * 256 + threadIdx.x;
+        if (k < N && (k & mask) == 0) { const float2 v = a[k]; acc += v.x * v.x + v.y * v.y; }
+    }
+    const double t = block_sum256((double)acc, sm);
+    if (threadIdx.x == 0) partial[r * nblk + blockIdx.x] = t;
+}
+
+__global__ __launch_bounds__(256) void k_trash_loss(const double* partial, int nblk, u64 rows, u64 sample0,
+                                                    u64 P, double* f) {
+    const u64 r = (u64)blockIdx.x * 256 + threadIdx.x;
+    if (r >= rows) return;
+    double acc = 0.0;
+    for (int b = 0; b < nblk; ++b) acc += partial[r * nblk + b];
+    f[(sample0 + r) * (2 * P + 1) + 2 * P] = 1.0 - acc;
+}
+
+// Squared-error loss on <Z_q>: z [rows][n] (double), y [samples][n] (float):
+// f[sample][2P] = 1/n sum (z - y)^2 and coef[r][q] = 2/n (z - y), the weights of the Z_q in lambda.
+__global__ __launch_bounds__(256) void k_mse_coef(const double* z, const float* y, int n, u64 rows,
+                                                  u64 sample0, u64 P, double* coef, double* f) {
+    const u64 r = (u64)blockIdx.x * 256 + threadIdx.x;
+    if (r >= rows) return;
+    double acc = 0.0;
+    for (int q = 0; q < n; ++q) {
+        const double d = z[r * n + q] - (double)y[(sample0 + r) * n + q];
+        acc += d * d;
+        coef[r * n + q] = 2.0 * d / n;
+    }
+    f[(sample0 + r) * (2 * P + 1) + 2 * P] = acc / n;
 }
 
 // M_q[a][b] = sum over the other qubits of conj(lambda[a, rest]) psi[b, rest], for one row pair
@@ -1039,6 +1092,26 @@ __global__ __launch_bounds__(256) void k_adj_layer(const double* partial, int nb
     double* fb = f + sample * (2 * P + 1);
     fb[2 * p] = 2.0 * acc;
     fb[2 * p + 1] = -2.0 * acc;
+}
+
+// ------------------------------------------------------------------------------------------
+// Optimiser steps on the parameter vector, in double, stored as float.
+__global__ __launch_bounds__(256) void k_sgd(float* p, const float* g, u64 count, double lr) {
+    const u64 i = (u64)blockIdx.x * 256 + threadIdx.x;
+    if (i < count) p[i] = (float)((double)p[i] - lr * (double)g[i]);
+}
+
+__global__ __launch_bounds__(256) void k_adam(float* p, const float* g, float* m, float* v, u64 count,
+                                              double lr, double b1, double b2, double eps, double c1,
+                                              double c2) {
+    const u64 i = (u64)blockIdx.x * 256 + threadIdx.x;
+    if (i >= count) return;
+    const double gi = (double)g[i];
+    const double mi = b1 * (double)m[i] + (1.0 - b1) * gi;
+    const double vi = b2 * (double)v[i] + (1.0 - b2) * gi * gi;
+    p[i] = (float)((double)p[i] - lr * (mi / c1) / (sqrt(vi / c2) + eps));
+    m[i] = (float)mi;
+    v[i] = (float)vi;
 }
 
 inline unsigned blocks_for(u64 items, unsigned per) { return (unsigned)((items + per - 1) / per); }
@@ -1256,10 +1329,46 @@ hipError_t launch_sample(const float2* state, int64_t rows, int n, const double*
     return hipGetLastError();
 }
 
-hipError_t launch_adj_init(const float2* A, int n, int q, int64_t rows, float2* S, hipStream_t st) {
-    if (n < 1 || rows < 1) return hipErrorInvalidValue;
+hipError_t launch_adj_init(const float2* A, int n, int kind, int q, uint64_t mask, const double* coef,
+                           int64_t rows, float2* S, hipStream_t st) {
+    if (n < 1 || rows < 1 || kind < 0 || kind > 2 || (kind == 2 && !coef)) return hipErrorInvalidValue;
     const u64 total = (u64)rows << n;
-    hipLaunchKernelGGL(k_adj_init, dim3(blocks_for(total / 2, 256)), dim3(256), 0, st, A, n, q, total, S);
+    const AdjObs o{kind, q, (u64)mask, coef};
+    hipLaunchKernelGGL(k_adj_init, dim3(blocks_for(total / 2, 256)), dim3(256), 0, st, A, n, o, total, S);
+    return hipGetLastError();
+}
+
+hipError_t launch_trash_loss(const float2* A, int n, uint64_t mask, int64_t rows, int64_t sample0, int64_t P,
+                             double* partial, double* f, hipStream_t st) {
+    if (rows < 1 || rows > 65535) return hipErrorInvalidValue;
+    const int nblk = chunk_blocks(n);
+    hipLaunchKernelGGL(k_p0_block, dim3(nblk, (unsigned)rows), dim3(256), 0, st, A, n, (u64)mask, nblk, partial);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(k_trash_loss, dim3(blocks_for((u64)rows, 256)), dim3(256), 0, st, partial, nblk,
+                       (u64)rows, (u64)sample0, (u64)P, f);
+    return hipGetLastError();
+}
+
+hipError_t launch_mse_coef(const double* z, const float* y, int n, int64_t rows, int64_t sample0, int64_t P,
+                           double* coef, double* f, hipStream_t st) {
+    hipLaunchKernelGGL(k_mse_coef, dim3(blocks_for((u64)rows, 256)), dim3(256), 0, st, z, y, n, (u64)rows,
+                       (u64)sample0, (u64)P, coef, f);
+    return hipGetLastError();
+}
+
+hipError_t launch_sgd(float* p, const float* g, int64_t count, double lr, hipStream_t st) {
+    if (count < 1) return hipSuccess;
+    hipLaunchKernelGGL(k_sgd, dim3(blocks_for((u64)count, 256)), dim3(256), 0, st, p, g, (u64)count, lr);
+    return hipGetLastError();
+}
+
+hipError_t launch_adam(float* p, const float* g, float* m, float* v, int64_t count, int64_t t, double lr,
+                       double b1, double b2, double eps, hipStream_t st) {
+    if (count < 1) return hipSuccess;
+    const double c1 = 1.0 - pow(b1, (double)t), c2 = 1.0 - pow(b2, (double)t);
+    hipLaunchKernelGGL(k_adam, dim3(blocks_for((u64)count, 256)), dim3(256), 0, st, p, g, m, v, (u64)count,
+                       lr, b1, b2, eps, c1, c2);
     return hipGetLastError();
 }
 

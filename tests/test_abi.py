@@ -27,6 +27,7 @@ def test_every_declared_symbol_is_exported():
 def test_binding_struct_layouts_match_header():
     assert ctypes.sizeof(qb.qsv_circuit) == 7 * 4
     assert ctypes.sizeof(qb.qsv_measure_req) == 64
+    assert ctypes.sizeof(qb.qsv_loss) == 24 and qb.qsv_loss.targets_dev.offset == 16
     assert qb.qsv_measure_req.out_dev.offset == 56
 
 

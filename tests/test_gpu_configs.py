@@ -188,3 +188,68 @@ def test_largest_state_30_qubits_one_layer(oracle, capsys):
     F = gu.measure(ctx, qb.QSV_M_FIDELITY, (1,), x=xd)
     assert abs(F[0] - 1.0) <= 1e-5
     ctx.close()
+
+
+def test_config3_training_step_sampled(oracle):
+    """Config 3 as a training step: loss 1 - P0 on the four trash qubits after the 20-layer encoder,
+    its gradient for all 800 parameters and 32 samples in reverse mode, one Adam step.  The oracle
+    recomputes the loss of two samples and their gradient for six parameters by the shift rule."""
+    torch = gu.torch_cuda()
+    w = wl.config(3)
+    n, B = w.n, w.batch
+    circ = qb.circuit_from_spec(w.circuit)
+    P = w.circuit.num_params(n)
+    ctx = gu.make_ctx(n, B, ws_bytes=qb.qsv_grad_workspace_bytes(n, B, circ))
+    xd, pd = gu.dev(w.x), gu.dev(w.params)
+    loss = torch.zeros(B, dtype=torch.float32, device="cuda")
+    grad = torch.zeros((B, P), dtype=torch.float32, device="cuda")
+    ml = torch.zeros(1, dtype=torch.float32, device="cuda")
+    mg = torch.zeros(P, dtype=torch.float32, device="cuda")
+    ctx.qsv_loss_grad(circ, xd, pd, None, qb.QSV_LOSS_TRASH, loss, grad, ml, mg, mask=w.trash_mask)
+    torch.cuda.synchronize()
+    gg, ll = grad.cpu().numpy(), loss.cpu().numpy()
+    g = np.random.Generator(np.random.PCG64(6))
+    rows = sorted(g.choice(B, 2, replace=False).tolist())
+    sub = sorted(g.choice(P, 4, replace=False).tolist()) + [0, P - 1]
+    lref, gref = oracle.loss_grad(w.x[rows], n, ocirc(oracle, w.circuit), w.params, kind=oracle.LOSS_TRASH,
+                                  mask=w.trash_mask, subset=sub)
+    assert np.abs(ll[rows] - lref).max() <= 1e-5
+    assert np.abs(gg[rows][:, sub] - gref).max() <= 1e-4
+    assert np.linalg.norm(gg[rows][:, sub] - gref) <= 1e-3 * np.linalg.norm(gref)
+    assert abs(ml.item() - ll.astype(np.float64).mean()) <= 1e-6
+    assert np.abs(mg.cpu().numpy() - gg.astype(np.float64).mean(0)).max() <= 1e-6
+    m = torch.zeros(P, dtype=torch.float32, device="cuda")
+    v = torch.zeros(P, dtype=torch.float32, device="cuda")
+    ctx.qsv_adam_step(pd, mg, m, v, 1, 0.01)
+    torch.cuda.synchronize()
+    want, _, _ = oracle.adam_step(w.params, mg.cpu().numpy(), np.zeros(P), np.zeros(P), 1, 0.01)
+    assert np.abs(pd.cpu().numpy() - want).max() <= 1e-6
+    ctx.close()
+
+
+def test_config1_training_step(oracle):
+    """Config 1 as a training step: mean squared error of <Z_q> against seeded targets, gradient
+    for all 180 parameters (re-upload weights included) and 1024 samples.  The oracle recomputes
+    16 samples in full."""
+    torch = gu.torch_cuda()
+    w = wl.config(1)
+    n, B = w.n, w.batch
+    circ = qb.circuit_from_spec(w.circuit)
+    P = w.circuit.num_params(n)
+    y = np.random.Generator(np.random.PCG64(4001)).uniform(-1, 1, (B, n)).astype(np.float32)
+    ctx = gu.make_ctx(n, B)
+    loss = torch.zeros(B, dtype=torch.float32, device="cuda")
+    grad = torch.zeros((B, P), dtype=torch.float32, device="cuda")
+    mg = torch.zeros(P, dtype=torch.float32, device="cuda")
+    ctx.qsv_loss_grad(circ, gu.dev(w.x), gu.dev(w.params), gu.dev(w.feats), qb.QSV_LOSS_MSE_Z, loss, grad,
+                      None, mg, targets=gu.dev(y))
+    torch.cuda.synchronize()
+    gg, ll = grad.cpu().numpy(), loss.cpu().numpy()
+    rows = list(range(0, B, 64))
+    lref, gref = oracle.loss_grad(w.x[rows], n, ocirc(oracle, w.circuit), w.params, w.feats[rows],
+                                  kind=oracle.LOSS_MSE_Z, targets=y[rows])
+    assert np.abs(ll[rows] - lref).max() <= 1e-5
+    assert np.abs(gg[rows] - gref).max() <= 1e-4
+    assert np.linalg.norm(gg[rows] - gref) <= 1e-3 * np.linalg.norm(gref)
+    assert np.abs(mg.cpu().numpy() - gg.astype(np.float64).mean(0)).max() <= 1e-6
+    ctx.close()

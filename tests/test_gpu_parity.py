@@ -248,6 +248,101 @@ def test_param_shift_grad_small(oracle, n, B, L, rot, ent, reup, obs, mode):
     ctx.close()
 
 
+# ------------------------------------------------------------------ training losses, optimiser steps
+@pytest.mark.parametrize("n,B,L,rot,ent,reup", [
+    (1, 3, 2, (RY, RZ), RING, 0), (3, 4, 2, (RY, RZ), LADDER, 0), (5, 3, 2, (RX, RY, RZ), RING, 0),
+    (6, 5, 2, (RY, RZ), RING, 1), (10, 3, 2, (RY, RZ), RING, 1), (12, 2, 2, (RY, RZ), RING, 0),
+    (13, 2, 1, (RX, RZ), LADDER, 0)])
+@pytest.mark.parametrize("kind", ["trash", "mse"])
+@pytest.mark.parametrize("mode", ["default", "naive", "chunk2"])
+def test_loss_grad_small(oracle, n, B, L, rot, ent, reup, kind, mode):
+    torch = gu.torch_cuda()
+    g = rng(90 + n)
+    spec = wl.CircuitSpec(L, tuple(rot), ent, reup)
+    P = spec.num_params(n)
+    params = wl.draw_params(spec, n, 91 + n)
+    x = g.standard_normal((B, 1 << n)).astype(np.float32)
+    feats = g.standard_normal((B, n)).astype(np.float32) if reup else None
+    mask = ((1 << n) - 1) & 0b1010010000101 if n > 1 else 1
+    mask = mask or 1
+    y = g.uniform(-1, 1, (B, n)).astype(np.float32)
+    if kind == "trash":
+        lref, gref = oracle.loss_grad(x, n, ocirc(oracle, spec), params, feats, kind=oracle.LOSS_TRASH, mask=mask)
+    else:
+        lref, gref = oracle.loss_grad(x, n, ocirc(oracle, spec), params, feats, kind=oracle.LOSS_MSE_Z, targets=y)
+    ctx = gu.make_ctx(n, B, naive=1 if mode == "naive" else 0)
+    if mode.startswith("chunk"):
+        ctx.qsv_set_option("grad_chunk_rows", int(mode[-1]))
+    ctx.state.fill_(3.0)
+    loss = torch.zeros(B, dtype=torch.float32, device="cuda")
+    grad = torch.zeros((B, P), dtype=torch.float32, device="cuda")
+    ml = torch.zeros(1, dtype=torch.float32, device="cuda")
+    mg = torch.zeros(P, dtype=torch.float32, device="cuda")
+    ctx.qsv_loss_grad(qb.circuit_from_spec(spec), gu.dev(x), gu.dev(params), gu.dev(feats) if reup else None,
+                      qb.QSV_LOSS_TRASH if kind == "trash" else qb.QSV_LOSS_MSE_Z, loss, grad, ml, mg,
+                      mask=mask, targets=gu.dev(y))
+    torch.cuda.synchronize()
+    assert np.abs(loss.cpu().numpy() - lref).max() <= 1e-5
+    gg = grad.cpu().numpy()
+    assert np.abs(gg - gref).max() <= 1e-4
+    assert np.linalg.norm(gg - gref) <= 1e-3 * np.linalg.norm(gref) + 1e-7
+    assert abs(ml.item() - lref.mean()) <= 1e-5
+    assert np.abs(mg.cpu().numpy() - gref.mean(0)).max() <= 1e-4
+    assert torch.all(ctx.state == 3.0)
+    ctx.close()
+
+
+def test_optimiser_steps(oracle):
+    torch = gu.torch_cuda()
+    g0 = rng(95)
+    ctx = gu.make_ctx(4, 1)
+    for count in (1, 7, 1000):
+        p = g0.standard_normal(count).astype(np.float32)
+        pd = gu.dev(p.copy())
+        ctx.qsv_sgd_step(pd, gu.dev(p[::-1].copy()), 0.05)
+        torch.cuda.synchronize()
+        assert np.array_equal(pd.cpu().numpy(), oracle.sgd_step(p, p[::-1], 0.05))   # same double arithmetic
+        q, m, v = p.copy(), np.zeros(count, np.float32), np.zeros(count, np.float32)
+        qd, md, vd = gu.dev(q.copy()), gu.dev(m.copy()), gu.dev(v.copy())
+        for t in range(1, 5):
+            gt = g0.standard_normal(count).astype(np.float32)
+            ctx.qsv_adam_step(qd, gu.dev(gt), md, vd, t, 0.01)
+            q, m, v = oracle.adam_step(q, gt, m, v, t, 0.01)
+        torch.cuda.synchronize()
+        assert np.abs(qd.cpu().numpy() - q).max() <= 1e-6
+        assert np.abs(md.cpu().numpy() - m).max() <= 1e-7 and np.abs(vd.cpu().numpy() - v).max() <= 1e-7
+    ctx.close()
+
+
+def test_training_steps_lower_the_loss(oracle):
+    """A few SGD steps on the trash loss, each checked against the oracle's loss at the GPU's own
+    parameters: the loop (loss + gradient + step, all on the device) goes downhill."""
+    torch = gu.torch_cuda()
+    n, B = 6, 8
+    g = rng(96)
+    spec = wl.CircuitSpec(2, (RY, RZ), RING, 0)
+    P = spec.num_params(n)
+    x = g.standard_normal((B, 1 << n)).astype(np.float32)
+    pd = gu.dev(wl.draw_params(spec, n, 97))
+    ctx = gu.make_ctx(n, B)
+    loss = torch.zeros(B, dtype=torch.float32, device="cuda")
+    grad = torch.zeros((B, P), dtype=torch.float32, device="cuda")
+    ml = torch.zeros(1, dtype=torch.float32, device="cuda")
+    mg = torch.zeros(P, dtype=torch.float32, device="cuda")
+    seen = []
+    for step in range(6):
+        ctx.qsv_loss_grad(qb.circuit_from_spec(spec), gu.dev(x), pd, None, qb.QSV_LOSS_TRASH, loss, grad, ml, mg,
+                          mask=0b110000)
+        torch.cuda.synchronize()
+        lref, _ = oracle.loss_grad(x, n, ocirc(oracle, spec), pd.cpu().numpy(), kind=oracle.LOSS_TRASH,
+                                   mask=0b110000, subset=[0])
+        assert abs(ml.item() - lref.mean()) <= 1e-5
+        seen.append(ml.item())
+        ctx.qsv_sgd_step(pd, mg, 0.5)
+    assert seen[-1] < seen[0] - 0.005 and all(b < a for a, b in zip(seen, seen[1:]))
+    ctx.close()
+
+
 # ------------------------------------------------------------------ error paths (host-detected)
 def test_argument_errors():
     torch = gu.torch_cuda()
