@@ -187,6 +187,18 @@ def fidelity(state, x):
     return F
 
 
+def pauli_expect(state, xmask=0, ymask=0, zmask=0, with_imag=False):
+    """<P> for the Pauli string with X on xmask, Y on ymask, Z on zmask (bit q = qubit q)."""
+    B, n = _state(state)
+    re = np.empty(B, dtype=np.float64)
+    im = np.empty(B, dtype=np.float64)
+    rc = lib().oracle_pauli_expect(_p(state), ctypes.c_int64(B), ctypes.c_int(n), ctypes.c_uint64(xmask),
+                                   ctypes.c_uint64(ymask), ctypes.c_uint64(zmask), _p(re), _p(im))
+    if rc:
+        raise ValueError("oracle_pauli_expect rc=%d" % rc)
+    return (re, im) if with_imag else re
+
+
 def sample(p32, uniforms):
     """p32: float32 [B, 2**n]; uniforms: float64 [B, shots] in [0,1).  Returns int64 [B, shots]."""
     p32 = np.ascontiguousarray(p32, dtype=np.float32)

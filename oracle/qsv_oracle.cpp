@@ -377,6 +377,42 @@ int oracle_fidelity(const cplx* state, int64_t B, int n, const float* x, int64_t
     return 0;
 }
 
+// ---------------------------------------------------------------- Pauli strings
+// E[b] = <a_b| P |a_b> for P = product over qubits of X (bit in xmask), Y (ymask) or Z (zmask);
+// the masks must not overlap.  Written as the definition: copy the state, apply the one-qubit
+// Pauli matrices one qubit at a time (X: swap the pair; Y: (a0, a1) -> (-i a1, i a0); Z: negate a1),
+// then take the inner product with the original.  The result of a Hermitian operator is real; the
+// imaginary part is returned too so that tests can see it vanish.
+int oracle_pauli_expect(const cplx* state, int64_t B, int n, uint64_t xmask, uint64_t ymask,
+                        uint64_t zmask, double* re, double* im) {
+    if ((xmask & ymask) || (xmask & zmask) || (ymask & zmask)) return 1;
+    if (n < 64 && ((xmask | ymask | zmask) >> n)) return 1;
+    const int64_t N = (int64_t)1 << n;
+    const cplx I(0.0, 1.0);
+#pragma omp parallel for schedule(static)
+    for (int64_t b = 0; b < B; ++b) {
+        std::vector<cplx> w(state + b * N, state + (b + 1) * N);
+        for (int q = 0; q < n; ++q) {
+            const int64_t bit = (int64_t)1 << q;
+            const bool X = (xmask >> q) & 1, Y = (ymask >> q) & 1, Z = (zmask >> q) & 1;
+            if (!X && !Y && !Z) continue;
+            for (int64_t k0 = 0; k0 < N; ++k0) {
+                if (k0 & bit) continue;
+                const int64_t k1 = k0 | bit;
+                const cplx a0 = w[k0], a1 = w[k1];
+                if (X) { w[k0] = a1; w[k1] = a0; }
+                else if (Y) { w[k0] = -I * a1; w[k1] = I * a0; }
+                else { w[k1] = -a1; }
+            }
+        }
+        cplx acc(0.0, 0.0);
+        for (int64_t k = 0; k < N; ++k) acc += std::conj(state[b * N + k]) * w[k];
+        re[b] = acc.real();
+        if (im) im[b] = acc.imag();
+    }
+    return 0;
+}
+
 // ---------------------------------------------------------------- sampling
 // Integer inverse CDF over a float32 probability vector:
 //   w_k = floor(double(p32_k) * 2^60)            (exact: a float times a power of two)

@@ -479,3 +479,67 @@ def test_optimiser_steps_closed_forms(oracle):
     for t in range(1, 6):
         q, m, v = oracle.adam_step(q, g, m, v, t, lr)
     assert np.allclose(q, p - 5 * lr * np.sign(g), atol=1e-5)
+
+
+# ------------------------------------------------------------------ Pauli strings
+def test_pauli_single_qubit_closed_forms(oracle):
+    x = np.array([[1.0, 0.0]], dtype=np.float32)
+    for theta in (0.4, 1.3, 2.2, 5.1):
+        st, _ = oracle.amp_encode(x, 1)
+        oracle.gate_rot(st, RY, 0, theta)                   # cos(t/2)|0> + sin(t/2)|1>
+        assert abs(oracle.pauli_expect(st, xmask=1)[0] - np.sin(theta)) < 1e-15
+        assert abs(oracle.pauli_expect(st, ymask=1)[0]) < 1e-15
+        assert abs(oracle.pauli_expect(st, zmask=1)[0] - np.cos(theta)) < 1e-15
+        st, _ = oracle.amp_encode(x, 1)
+        oracle.gate_rot(st, RX, 0, theta)                   # cos(t/2)|0> - i sin(t/2)|1>
+        assert abs(oracle.pauli_expect(st, ymask=1)[0] + np.sin(theta)) < 1e-15
+        assert abs(oracle.pauli_expect(st, xmask=1)[0]) < 1e-15
+
+
+def test_pauli_strings_on_ghz(oracle):
+    """(|0..0> + |1..1>)/sqrt(2): <X..X> = 1, <Z_i Z_j> = 1, <Z_i> = 0; for the Bell pair <YY> = -1;
+    an X string with an even number of X replaced by Y picks up (-1)^(pairs)."""
+    n = 4
+    x = np.zeros((1, 16), dtype=np.float32)
+    x[0, 0] = x[0, 15] = 1.0
+    st, _ = oracle.amp_encode(x, n)
+    assert abs(oracle.pauli_expect(st, xmask=0b1111)[0] - 1.0) < 1e-15
+    assert abs(oracle.pauli_expect(st, zmask=0b0101)[0] - 1.0) < 1e-15
+    assert abs(oracle.pauli_expect(st, zmask=0b0100)[0]) < 1e-15
+    assert abs(oracle.pauli_expect(st, xmask=0b0011, ymask=0b1100)[0] + 1.0) < 1e-15
+    assert abs(oracle.pauli_expect(st, ymask=0b1111)[0] - 1.0) < 1e-15
+    assert abs(oracle.pauli_expect(st, xmask=0b0111)[0]) < 1e-15       # not all qubits flipped
+    bell = np.zeros((1, 4), dtype=np.float32)
+    bell[0, 0] = bell[0, 3] = 1.0
+    sb, _ = oracle.amp_encode(bell, 2)
+    assert abs(oracle.pauli_expect(sb, ymask=0b11)[0] + 1.0) < 1e-15
+
+
+def test_pauli_strings_vs_dense_kronecker(oracle):
+    g = rng(120)
+    paulis = {"I": np.eye(2), "X": np.array([[0, 1], [1, 0]]), "Y": np.array([[0, -1j], [1j, 0]]),
+              "Z": np.diag([1.0, -1.0])}
+    for n in (1, 2, 3, 5):
+        st = (g.standard_normal((3, 1 << n)) + 1j * g.standard_normal((3, 1 << n)))
+        st /= np.linalg.norm(st, axis=1, keepdims=True)
+        st = np.ascontiguousarray(st)
+        for _ in range(12):
+            letters = g.choice(list("IXYZ"), n)
+            full = np.eye(1)
+            for q in range(n):                                # qubit n-1 is the leftmost factor
+                full = np.kron(paulis[letters[q]], full)
+            masks = {c: sum(1 << q for q in range(n) if letters[q] == c) for c in "XYZ"}
+            re, im = oracle.pauli_expect(st, masks["X"], masks["Y"], masks["Z"], with_imag=True)
+            want = np.einsum("bi,ij,bj->b", st.conj(), full, st)
+            assert np.allclose(re, want.real, atol=1e-13) and np.allclose(im, 0, atol=1e-13)
+            assert np.allclose(want.imag, 0, atol=1e-13)
+    # Z-only strings are parity sums of the probabilities, and single Z reproduces expz_all
+    p = oracle.probs(st)
+    k = np.arange(1 << n)
+    par = lambda m: 1 - 2 * (np.array([bin(int(v) & m).count("1") for v in k]) & 1)
+    assert np.allclose(oracle.pauli_expect(st, zmask=0b10110), (p * par(0b10110)).sum(1), atol=1e-13)
+    z = oracle.expz_all(st)
+    for q in range(n):
+        assert np.allclose(oracle.pauli_expect(st, zmask=1 << q), z[:, q], atol=1e-13)
+    with pytest.raises(ValueError):
+        oracle.pauli_expect(st, xmask=1, zmask=1)
