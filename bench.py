@@ -121,6 +121,16 @@ def bench_c4(torch, qb, wl, args):
         "pass_avg_ms": apply_ms / passes, "pass_bytes": 2 * state_bytes,
         "pass_gbs": 2 * state_bytes / (apply_ms / passes * 1e-3) / 1e9,
     }
+    # a Pauli-string expectation on the final state: one read pass (8 bytes per amplitude)
+    ev = torch.empty(1, dtype=torch.float32, device="cuda")
+    xm, ym, zm = 0x0092492, 0x1124924, 0x2249249          # X, Y, Z on every third qubit each
+
+    def pauli(tm):
+        ctx.qsv_pauli_expect(ev, xm, ym, zm)
+
+    pms, _ = run_steps(torch, pauli, max(args.steps, 5), 1)
+    res["pauli_string"] = {"ms": pms, "gbs": state_bytes / (pms * 1e-3) / 1e9,
+                           "what": "<P> of a 26-qubit mixed X/Y/Z string on the final state, 8 B per amplitude"}
     ctx.close()
     return res, w
 
@@ -408,7 +418,7 @@ def main():
                      "traffic": TRAFFIC_BYTES_PER_LAUNCH.get(head["workload"][:2]),
                      "bytes_per_launch": head["pass_bytes"], "avg_launch_ms": head["pass_avg_ms"]},
         "cpu_baseline": cpu,
-        "others": others,
+        "others": dict(others, **({"pauli_string": head["pauli_string"]} if "pauli_string" in head else {})),
     }
     print(json.dumps(out))
 

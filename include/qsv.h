@@ -137,6 +137,13 @@ typedef struct {
 
 qsv_status qsv_measure(qsv_ctx* ctx, const qsv_measure_req* req);
 
+/* Expectation value of a Pauli string on the current state (task statement: "measurement
+ * (... <Z> ...)", widened to X and Y): P = product over qubits of X (bit set in xmask), Y (ymask)
+ * or Z (zmask), identity elsewhere; the masks must not overlap and name qubits < n_qubits.
+ * out_dev: float [batch].  Computed directly as sum_k conj(a[k ^ f]) i^nY (-1)^popcount(k & s) a[k]
+ * with f = xmask | ymask, s = ymask | zmask: one read pass, the state is not modified. */
+qsv_status qsv_pauli_expect(qsv_ctx* ctx, uint64_t xmask, uint64_t ymask, uint64_t zmask, float* out_dev);
+
 /* Parameter-shift gradient of f_b = <Z_obs> after encode + circuit (task statement: "parameter-
  * shift gradients over the batch"; config 2: "2 circuits per param per sample"):
  *   grad[b][p] = 1/2 [ f_b(angle_p + pi/2) - f_b(angle_p - pi/2) ]

@@ -91,6 +91,8 @@ def load():
     L.qsv_adam_step.restype = i32
     L.qsv_adam_step.argtypes = [vp, vp, vp, vp, vp, i64, i64, ctypes.c_double, ctypes.c_double,
                                 ctypes.c_double, ctypes.c_double]
+    L.qsv_pauli_expect.restype = i32
+    L.qsv_pauli_expect.argtypes = [vp, ctypes.c_uint64, ctypes.c_uint64, ctypes.c_uint64, vp]
     L.qsv_plan_describe.restype = i64
     L.qsv_plan_describe.argtypes = [ctypes.POINTER(qsv_circuit), i32, i32, i32, i32, ctypes.c_char_p, i64]
     L.qsv_probe_pass.restype = i32
@@ -213,6 +215,9 @@ class Context:
         self._check(self.L.qsv_loss_grad(self.h, ctypes.byref(circ), _ptr(x), x.shape[1], _ptr(params),
                                          _ptr(feats), ctypes.byref(spec), _ptr(loss), _ptr(grad),
                                          _ptr(mean_loss), _ptr(mean_grad)))
+
+    def qsv_pauli_expect(self, out, xmask=0, ymask=0, zmask=0):
+        self._check(self.L.qsv_pauli_expect(self.h, xmask, ymask, zmask, _ptr(out)))
 
     def qsv_sgd_step(self, params, grad, lr):
         self._check(self.L.qsv_sgd_step(self.h, _ptr(params), _ptr(grad), params.numel(), lr))

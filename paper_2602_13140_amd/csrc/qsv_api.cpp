@@ -540,6 +540,23 @@ qsv_status qsv_measure(qsv_ctx* ctx, const qsv_measure_req* req) {
     }
 }
 
+qsv_status qsv_pauli_expect(qsv_ctx* ctx, uint64_t xmask, uint64_t ymask, uint64_t zmask, float* out_dev) {
+    if (!ctx) return QSV_ERR_INVALID_ARG;
+    const int n = ctx->n;
+    if (!out_dev) return fail(ctx, QSV_ERR_INVALID_ARG, "out_dev is NULL");
+    if ((xmask & ymask) || (xmask & zmask) || (ymask & zmask))
+        return fail(ctx, QSV_ERR_INVALID_ARG, "xmask, ymask and zmask must not overlap");
+    if ((xmask | ymask | zmask) >> n) return fail(ctx, QSV_ERR_INVALID_ARG, "mask names a qubit >= n_qubits");
+    qsv_status st = bind_device(ctx);
+    if (st != QSV_OK) return st;
+    Arena ar(ctx);
+    double* partial = (double*)ar.take((size_t)ctx->batch * chunk_blocks(n) * 2 * 8);
+    if (!partial) return ws_fail(ctx, ar, "qsv_pauli_expect");
+    QSV_HIP(ctx, launch_pauli(ctx->state, ctx->batch, n, xmask, ymask, zmask, partial, out_dev, ctx->stream),
+            "pauli expectation");
+    return QSV_OK;
+}
+
 qsv_status qsv_param_shift_grad(qsv_ctx* ctx, const qsv_circuit* c, const float* x_dev, int64_t dim,
                                 const float* params_dev, const float* feats_dev, int32_t obs_qubit,
                                 float* loss_dev, float* grad_dev, float* mean_loss_dev,

@@ -106,6 +106,10 @@ hipError_t launch_fidelity_finish(const double* partial, int nblk, int64_t rows,
 hipError_t launch_sample(const float2* state, int64_t rows, int n, const double* uniforms, int64_t shots,
                          unsigned long long* cum, long long* out, hipStream_t st);
 
+// <P> of a Pauli string (X on xmask, Y on ymask, Z on zmask) per row; partial: rows * blocks * 2 doubles
+hipError_t launch_pauli(const float2* state, int64_t rows, int n, uint64_t xmask, uint64_t ymask,
+                        uint64_t zmask, double* partial, float* out, hipStream_t st);
+
 // Reverse-mode gradient.  launch_adj_init: S[2r] = A[r], S[2r+1] = O A[r] (rows of A) for the
 // diagonal observable O: kind 0 Z_q; kind 1 -P0(mask); kind 2 sum_q coef[r][q] Z_q.
 // launch_trash_loss: f[sample0+r][2P] = 1 - P0(mask) of row r (partial: rows * blocks doubles, blocks

@@ -770,6 +770,43 @@ __global__ __launch_bounds__(256) void k_project(float2* state, u64 total, int n
     state[e] = v;
 }
 
+// Pauli string: T = sum_k conj(a[k ^ f]) (-1)^popcount(k & s) a[k], f = X and Y bits, s = Y and Z
+// bits; <P> = Re(i^nY T).  One block per 4096 amplitudes and row; partial: [row][blk][2].
+__global__ __launch_bounds__(256) void k_pauli_block(const float2* state, int n, u64 f, u64 s, int nblk,
+                                                     double* partial) {
+    __shared__ double sm[4];
+    const u64 row = blockIdx.y, N = 1ull << n;
+    const float2* a = state + (row << n);
+    float tr = 0.f, ti = 0.f;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+        const u64 k = (u64)blockIdx.x * CHUNK + (u64)i * 256 + threadIdx.x;
+        if (k < N) {
+            const float2 v = a[k], u = a[k ^ f];
+            float cr = u.x * v.x + u.y * v.y, ci = u.x * v.y - u.y * v.x;   // conj(u) v
+            if (__popcll(k & s) & 1) { cr = -cr; ci = -ci; }
+            tr += cr; ti += ci;
+        }
+    }
+    const double t0 = block_sum256((double)tr, sm);
+    const double t1 = block_sum256((double)ti, sm);
+    if (threadIdx.x == 0) { double* o = partial + (row * nblk + blockIdx.x) * 2; o[0] = t0; o[1] = t1; }
+}
+
+__global__ __launch_bounds__(256) void k_pauli_finish(const double* partial, int nblk, int ny, float* out) {
+    __shared__ double sm[4];
+    const u64 row = blockIdx.x;
+    double tr = 0.0, ti = 0.0;
+    for (int i = threadIdx.x; i < nblk; i += 256) {
+        const double* p = partial + (row * nblk + i) * 2;
+        tr += p[0]; ti += p[1];
+    }
+    const double t0 = block_sum256(tr, sm);
+    const double t1 = block_sum256(ti, sm);
+    // Re(i^ny (t0 + i t1)): ny mod 4 = 0: t0; 1: -t1; 2: -t0; 3: t1
+    if (threadIdx.x == 0) out[row] = (float)((ny & 3) == 0 ? t0 : (ny & 3) == 1 ? -t1 : (ny & 3) == 2 ? -t0 : t1);
+}
+
 __global__ __launch_bounds__(256) void k_fidelity_block(const float2* state, int n, const float* x,
                                                         u64 dim, int nblk, double* partial) {
     __shared__ double sm[4];
@@ -1309,6 +1346,18 @@ hipError_t launch_fidelity_block(const float2* state, int64_t rows, int n, const
 hipError_t launch_fidelity_finish(const double* partial, int nblk, int64_t rows, float* out,
                                   hipStream_t st) {
     hipLaunchKernelGGL(k_fidelity_finish, dim3((unsigned)rows), dim3(256), 0, st, partial, nblk, out);
+    return hipGetLastError();
+}
+
+hipError_t launch_pauli(const float2* state, int64_t rows, int n, uint64_t xmask, uint64_t ymask,
+                        uint64_t zmask, double* partial, float* out, hipStream_t st) {
+    const int nblk = chunk_blocks(n);
+    hipLaunchKernelGGL(k_pauli_block, dim3(nblk, (unsigned)rows), dim3(256), 0, st, state, n,
+                       (u64)(xmask | ymask), (u64)(ymask | zmask), nblk, partial);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(k_pauli_finish, dim3((unsigned)rows), dim3(256), 0, st, partial, nblk,
+                       __builtin_popcountll(ymask), out);
     return hipGetLastError();
 }
 

@@ -248,6 +248,49 @@ def test_param_shift_grad_small(oracle, n, B, L, rot, ent, reup, obs, mode):
     ctx.close()
 
 
+# ------------------------------------------------------------------ Pauli strings
+@pytest.mark.parametrize("n,B", [(1, 3), (2, 2), (5, 4), (9, 3), (12, 2), (13, 3), (16, 2)])
+def test_pauli_strings(oracle, n, B):
+    torch = gu.torch_cuda()
+    g = rng(130 + n)
+    spec = wl.CircuitSpec(2, (RX, RY, RZ), RING, 0)
+    params = wl.draw_params(spec, n, 131 + n)
+    x = g.standard_normal((B, 1 << n)).astype(np.float32)
+    ctx = gu.make_ctx(n, B)
+    ctx.qsv_amp_encode(gu.dev(x))
+    ctx.qsv_apply_layers(qb.circuit_from_spec(spec), gu.dev(params), None, 0)
+    ref = gu.state_np(ctx)                    # the GPU's own state in double: isolates this kernel
+    before = ctx.state.clone()
+    out = torch.zeros(B, dtype=torch.float32, device="cuda")
+    strings = [(1, 0, 0), (0, 1, 0), (0, 0, 1), (0, 0, (1 << n) - 1), ((1 << n) - 1, 0, 0), (0, (1 << n) - 1, 0)]
+    for _ in range(10):
+        letters = g.integers(0, 4, n)
+        strings.append(tuple(sum(1 << q for q in range(n) if letters[q] == c) for c in (1, 2, 3)))
+    for xm, ym, zm in strings:
+        ctx.qsv_pauli_expect(out, xm, ym, zm)
+        torch.cuda.synchronize()
+        want = oracle.pauli_expect(ref, xm, ym, zm)
+        assert np.abs(out.cpu().numpy() - want).max() <= 1e-5, (xm, ym, zm)
+    assert torch.equal(ctx.state, before)      # measuring does not touch the state
+    # end to end against the oracle's own state
+    oref, _ = oracle.amp_encode(x, n)
+    oracle.apply_layers(oref, ocirc(oracle, spec), params)
+    for xm, ym, zm in strings[:8]:
+        ctx.qsv_pauli_expect(out, xm, ym, zm)
+        torch.cuda.synchronize()
+        assert np.abs(out.cpu().numpy() - oracle.pauli_expect(oref, xm, ym, zm)).max() <= 1e-5
+    z = gu.measure(ctx, qb.QSV_M_EXPZ_ALL, (B, n))
+    for q in range(n):
+        ctx.qsv_pauli_expect(out, 0, 0, 1 << q)
+        torch.cuda.synchronize()
+        assert np.abs(out.cpu().numpy() - z[:, q]).max() <= 1e-5
+    with pytest.raises(qb.QsvError):
+        ctx.qsv_pauli_expect(out, 1, 1, 0)
+    with pytest.raises(qb.QsvError):
+        ctx.qsv_pauli_expect(out, 0, 0, 1 << n)
+    ctx.close()
+
+
 # ------------------------------------------------------------------ training losses, optimiser steps
 @pytest.mark.parametrize("n,B,L,rot,ent,reup", [
     (1, 3, 2, (RY, RZ), RING, 0), (3, 4, 2, (RY, RZ), LADDER, 0), (5, 3, 2, (RX, RY, RZ), RING, 0),
