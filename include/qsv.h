@@ -221,7 +221,8 @@ qsv_status qsv_probe_pass(qsv_ctx* ctx, int low_bits, int window_start, int tran
  * per tile; lds_planes = 1 (default) moves real and imaginary parts through one LDS plane one
  * after the other, 2 through two planes at once; naive = 1 routes qsv_apply_layers through the
  * one-gate-per-launch kernels; grad_layered = 0 makes qsv_param_shift_grad run every shifted
- * circuit whole; grad_chunk_rows in 1..32768 (0 = as many as fit) caps the circuits per launch of
+ * circuit whole; nt_store = 1 / 0 forces nontemporal / ordinary tile stores in the fused pass (-1,
+ * the default, chooses by the size of the state); grad_chunk_rows in 1..32768 (0 = as many as fit) caps the circuits per launch of
  * qsv_param_shift_grad.  Unknown names and values out of range return
  * QSV_ERR_INVALID_ARG. */
 qsv_status qsv_set_option(qsv_ctx* ctx, const char* name, int64_t value);

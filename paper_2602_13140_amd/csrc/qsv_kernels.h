@@ -36,6 +36,7 @@ struct PassArgs {
     double* zout;        // not NULL: the pass also writes <Z_zq> partials [tile][wavefront] (needs n >= tile)
     int zq;
     int nostore;         // with zout: the state is not written back
+    int nt_store;        // nontemporal tile stores (states much larger than the last-level cache)
     const float* mats;   // [samples if rowdep][n_mats][8], matrices in execution order
     const int* exec_of;  // [n_mats]: (layer * n + qubit) -> execution-order index
     const float* ovr;    // gradient: [samples if rowdep][2P][8] shifted matrices

@@ -135,6 +135,7 @@ __device__ __forceinline__ void apply_u_any(int j, float (&vr)[NR], float (&vi)[
 // constant-address-space views: uniform loads through them become scalar loads
 typedef unsigned u32x2 __attribute__((ext_vector_type(2)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
 typedef const __attribute__((address_space(4))) u32x2* cuint2_p;
 typedef const __attribute__((address_space(4))) f32x4* cfloat4_p;
 
@@ -326,8 +327,16 @@ __global__ __launch_bounds__(1 << (T - R)) void k_pass(const PassArgs a) {
         if ((thr & 63u) == 0) a.zout[tb * (blockDim.x >> 6) + (thr >> 6)] = tot;
         if (a.nostore) return;
     }
-    if (full && off32) {
+    if (full && off32 && a.nt_store) {
+        // States much larger than the last-level cache: nontemporal stores, so that the lines written
+        // now (read again only a whole pass later) do not displace what the pass still has to read.
         const unsigned lane_byte = (unsigned)(e0 ^ tile_base) * 8u;   // the lane's own index bits
+#define QSV_ST(k) { char* bp = (char*)(a.state + (tile_base | expand((unsigned)k << scur))); \
+                    f32x2 v; v.x = vr##k; v.y = vi##k; __builtin_nontemporal_store(v, (f32x2*)(bp + lane_byte)); }
+        QSV_16(QSV_ST)
+#undef QSV_ST
+    } else if (full && off32) {
+        const unsigned lane_byte = (unsigned)(e0 ^ tile_base) * 8u;
 #define QSV_ST(k) { char* bp = (char*)(a.state + (tile_base | expand((unsigned)k << scur))); \
                     *(float2*)(bp + lane_byte) = make_float2(vr##k, vi##k); }
         QSV_16(QSV_ST)
