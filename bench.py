@@ -38,6 +38,7 @@ def parse_args():
     ap.add_argument("--tile", type=int, default=0, help="force the pass kernel's tile_log2 (0 = default)")
     ap.add_argument("--low", type=int, default=0, help="force the planner's minimum number of low index bits per tile")
     ap.add_argument("--planes", type=int, default=0, help="force the pass kernel's LDS planes (1 or 2; 0 = default)")
+    ap.add_argument("--nt", type=int, default=-1, help="force nontemporal tile stores (1) or ordinary ones (0)")
     ap.add_argument("--probe", action="store_true",
                     help="only time the load/store-only probe pass on config 4's state (streaming ceiling "
                          "of the pass kernel's access pattern; also the known-size copy used to scale "
@@ -91,6 +92,8 @@ def bench_c4(torch, qb, wl, args):
         ctx.qsv_set_option("low_bits", args.low)
     if args.planes:
         ctx.qsv_set_option("lds_planes", args.planes)
+    if args.nt >= 0:
+        ctx.qsv_set_option("nt_store", args.nt)
     circ = qb.circuit_from_spec(w.circuit)
     xd = torch.from_numpy(w.x).cuda()
     pd = torch.from_numpy(w.params).cuda()
@@ -145,6 +148,8 @@ def bench_c3(torch, qb, wl, args):
         ctx.qsv_set_option("low_bits", args.low)
     if args.planes:
         ctx.qsv_set_option("lds_planes", args.planes)
+    if args.nt >= 0:
+        ctx.qsv_set_option("nt_store", args.nt)
     circ = qb.circuit_from_spec(w.circuit)
     xd = torch.from_numpy(w.x).cuda()
     pd = torch.from_numpy(w.params).cuda()
@@ -200,6 +205,8 @@ def bench_c2(torch, qb, wl, args):
         ctx.qsv_set_option("low_bits", args.low)
     if args.planes:
         ctx.qsv_set_option("lds_planes", args.planes)
+    if args.nt >= 0:
+        ctx.qsv_set_option("nt_store", args.nt)
     xd = torch.from_numpy(w.x).cuda()
     pd = torch.from_numpy(w.params).cuda()
     loss = torch.empty(B, dtype=torch.float32, device="cuda")
