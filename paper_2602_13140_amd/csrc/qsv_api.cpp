@@ -193,9 +193,14 @@ struct Prepared {
     float* mats = nullptr;
 };
 
-size_t mats_bytes(const qsv_circuit& c, int n, int64_t samples) {
+size_t mats_table_bytes(const qsv_circuit& c, int n, int64_t samples) {
     // one extra entry: the interpreter prefetches the matrix after the one it is using
-    return ((size_t)(c.reupload ? samples : 1) * c.n_layers * n + 1) * 32;
+    return align_up(((size_t)(c.reupload ? samples : 1) * c.n_layers * n + 1) * 32);
+}
+
+// the matrix table followed by the builder's side buffer
+size_t mats_bytes(const qsv_circuit& c, int n, int64_t samples) {
+    return mats_table_bytes(c, n, samples) + align_up(build_mats_side_bytes(to_dev(c, n), samples));
 }
 
 qsv_status prepare_circuit(qsv_ctx* ctx, const qsv_circuit& c, int64_t rows, int inverse, int grad,
@@ -206,14 +211,19 @@ qsv_status prepare_circuit(qsv_ctx* ctx, const qsv_circuit& c, int64_t rows, int
     out->mats = mats;
     out->cp = nullptr;
     const int* order = nullptr;
+    const int* exec_of = nullptr;
     if (!(ctx->opt_naive || n < kRegBits)) {
         qsv_status st = get_plan(ctx, c, rows, inverse, grad, &out->cp);
         if (st != QSV_OK) return st;
         order = reinterpret_cast<const int*>(ctx->ws + out->cp->order_off);
+        exec_of = reinterpret_cast<const int*>(ctx->ws + out->cp->execof_off);
     }
-    if (has_u)
-        QSV_HIP(ctx, launch_build_mats(to_dev(c, n), params, feats, samples, inverse, order, mats, ctx->stream),
+    if (has_u) {
+        double* side = reinterpret_cast<double*>(reinterpret_cast<char*>(mats) + mats_table_bytes(c, n, samples));
+        QSV_HIP(ctx, launch_build_mats(to_dev(c, n), params, feats, samples, inverse, order, exec_of, mats, side,
+                                       ctx->stream),
                 "build matrices");
+    }
     return QSV_OK;
 }
 
@@ -328,7 +338,7 @@ size_t qsv_workspace_bytes(int n_qubits, int batch) {
     const size_t n = (size_t)n_qubits, B = (size_t)batch;
     const size_t row_bytes = ((size_t)8) << n;
     size_t total = kOpsRegion;
-    total += align_up(B * 64 * n * 32);                       // per-sample matrices, 64 layers
+    total += align_up(B * 64 * n * 32 + 32) + align_up(B * 64 * (n * 16 + 64));  // per-sample matrices + builder's side buffer, 64 layers
     total += align_up(B * 2 * (16 * 4 * n) * 32);             // shifted matrices, 16 layers x 4 slots
     total += align_up(B * (2 * 64 * 4 * n + 1) * 8);          // gradient values f[B][2P+1]
     total += align_up(B * (size_t)chunk_blocks(n_qubits) * 13 * 8 * 2);  // reduction partials

@@ -506,9 +506,14 @@ __device__ __forceinline__ void store_m(M2& u, float* out8) {
     for (int k = 0; k < 4; ++k) { out8[2 * k] = (float)u.r[k]; out8[2 * k + 1] = (float)u.i[k]; }
 }
 
+// Two steps, so that every thread does the same amount of work.  Step 1, one thread per matrix:
+// build it, and for every qubit but the last store it without its phase factor and note the factor;
+// the last qubit's matrix is kept in double.  Step 2, one thread per (sample, layer): multiply the
+// last qubit's matrix by the product of the layer's factors and store it.
+// side: [tables][L*n] factors (2 doubles each), then [tables][L] matrices (8 doubles each).
 __global__ __launch_bounds__(256) void k_build_mats(CircDev c, const float* params, const float* feats,
                                                     u64 count, int inverse, const int* order,
-                                                    float* out) {
+                                                    float* out, double* side) {
     const u64 idx = (u64)blockIdx.x * 256 + threadIdx.x;
     if (idx >= count) return;
     const u64 per = (u64)c.n_layers * c.n;
@@ -517,9 +522,40 @@ __global__ __launch_bounds__(256) void k_build_mats(CircDev c, const float* para
     const int lq = order ? order[pos] : pos;
     const int l = lq / c.n, q = lq % c.n;
     M2 u = fused_raw(c, params, feats, sample, l, q, -1, 0.0, inverse);
-    if (q + 1 < c.n) strip_phase(u);
-    else { const Ph p = layer_phase(c, params, feats, sample, l, inverse); scale_m(u, p.r, p.i); }
-    store_m(u, out + idx * 8);
+    if (q + 1 < c.n) {
+        const Ph p = phase_of(u);
+        double* ps = side + (sample * per + (u64)lq) * 2;
+        ps[0] = p.r; ps[1] = p.i;
+        strip_phase(u);
+        store_m(u, out + idx * 8);
+    } else {
+        const u64 tables = count / per;
+        double* ms = side + tables * per * 2 + (sample * c.n_layers + (u64)l) * 8;
+        for (int k = 0; k < 4; ++k) { ms[2 * k] = u.r[k]; ms[2 * k + 1] = u.i[k]; }
+    }
+}
+
+__global__ __launch_bounds__(256) void k_build_mats_last(CircDev c, u64 tables, const int* exec_of,
+                                                         float* out, const double* side) {
+    const u64 idx = (u64)blockIdx.x * 256 + threadIdx.x;
+    if (idx >= tables * c.n_layers) return;
+    const u64 per = (u64)c.n_layers * c.n;
+    const u64 sample = idx / c.n_layers;
+    const int l = (int)(idx % c.n_layers);
+    Ph acc = {1.0, 0.0};
+    for (int q = 0; q + 1 < c.n; ++q) {      // same order of multiplication as layer_phase
+        const double* ps = side + (sample * per + (u64)l * c.n + q) * 2;
+        const double r = acc.r * ps[0] - acc.i * ps[1];
+        acc.i = acc.r * ps[1] + acc.i * ps[0];
+        acc.r = r;
+    }
+    const double* ms = side + tables * per * 2 + idx * 8;
+    M2 u;
+    for (int k = 0; k < 4; ++k) { u.r[k] = ms[2 * k]; u.i[k] = ms[2 * k + 1]; }
+    scale_m(u, acc.r, acc.i);
+    const int lq = l * c.n + c.n - 1;
+    const u64 pos = exec_of ? (u64)exec_of[lq] : (u64)lq;
+    store_m(u, out + (sample * per + pos) * 8);
 }
 
 // Matrices with one angle shifted by +-pi/2 (parameter-shift rule), consistent with the phase
@@ -964,29 +1000,32 @@ __global__ __launch_bounds__(256) void k_grad_finish(const double* f, u64 B, u64
     grad[b * P + p] = (float)g;
 }
 
-// Batch means in a fixed order (one thread per parameter; thread P does the loss).
+// Batch means in a fixed order: one block per parameter (block P does the loss); thread t adds the
+// samples t, t + 256, ... and the block adds its threads.
 __global__ __launch_bounds__(256) void k_grad_mean(const double* f, u64 B, u64 P, CircDev c,
                                                    const float* feats, float* mean_loss,
                                                    float* mean_grad) {
-    const u64 p = (u64)blockIdx.x * 256 + threadIdx.x;
-    if (p > P) return;
+    __shared__ double sm[4];
+    const u64 p = blockIdx.x;
     const int slots = c.reupload + c.n_rot;
     double acc = 0.0;
     if (p == P) {
         if (!mean_loss) return;
-        for (u64 b = 0; b < B; ++b) acc += f[b * (2 * P + 1) + 2 * P];
-        mean_loss[0] = (float)(acc / (double)B);
+        for (u64 b = threadIdx.x; b < B; b += 256) acc += f[b * (2 * P + 1) + 2 * P];
+        const double tot = block_sum256(acc, sm);
+        if (threadIdx.x == 0) mean_loss[0] = (float)(tot / (double)B);
         return;
     }
     if (!mean_grad) return;
     const bool isw = c.reupload && ((p / c.n) % slots) == 0;
-    for (u64 b = 0; b < B; ++b) {
+    for (u64 b = threadIdx.x; b < B; b += 256) {
         const double* fb = f + b * (2 * P + 1);
         double g = 0.5 * (fb[2 * p] - fb[2 * p + 1]);
         if (isw) g *= (double)feats[b * c.n + (p % c.n)];
         acc += g;
     }
-    mean_grad[p] = (float)(acc / (double)B);
+    const double tot = block_sum256(acc, sm);
+    if (threadIdx.x == 0) mean_grad[p] = (float)(tot / (double)B);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -1229,12 +1268,18 @@ hipError_t launch_naive_cz_ladder(float2* state, int64_t rows, int n, hipStream_
 }
 
 hipError_t launch_build_mats(const CircDev& c, const float* params, const float* feats,
-                             int64_t samples, int inverse, const int* order, float* out,
-                             hipStream_t st) {
-    const u64 count = (u64)(c.reupload ? samples : 1) * c.n_layers * c.n;
+                             int64_t samples, int inverse, const int* order, const int* exec_of, float* out,
+                             double* side, hipStream_t st) {
+    const u64 tables = (u64)(c.reupload ? samples : 1);
+    const u64 count = tables * c.n_layers * c.n;
     if (count == 0) return hipSuccess;
+    if ((order == nullptr) != (exec_of == nullptr)) return hipErrorInvalidValue;
     hipLaunchKernelGGL(k_build_mats, dim3(blocks_for(count, 256)), dim3(256), 0, st, c, params, feats,
-                       count, inverse, order, out);
+                       count, inverse, order, out, side);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(k_build_mats_last, dim3(blocks_for(tables * c.n_layers, 256)), dim3(256), 0, st, c,
+                       tables, exec_of, out, side);
     return hipGetLastError();
 }
 
@@ -1456,7 +1501,7 @@ hipError_t launch_grad_finish(const double* f, int64_t B, int64_t P, const CircD
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     if (mean_loss || mean_grad) {
-        hipLaunchKernelGGL(k_grad_mean, dim3(blocks_for((u64)P + 1, 256)), dim3(256), 0, st, f, (u64)B,
+        hipLaunchKernelGGL(k_grad_mean, dim3((unsigned)(P + 1)), dim3(256), 0, st, f, (u64)B,
                            (u64)P, c, feats, mean_loss, mean_grad);
         e = hipGetLastError();
     }

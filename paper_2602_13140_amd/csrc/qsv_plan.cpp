@@ -276,8 +276,11 @@ bool check_circuit(const qsv_circuit* c, int n, std::string* why) {
 
 int default_tile(int n, int64_t batch) {
     const int ext = n + ceil_log2(batch);
-    // 2^12 amplitudes per tile: five workgroups share a CU's LDS, which measured best
-    return std::max(kMinTile, std::min(12, ext));
+    // 2^12 amplitudes per tile measured best for large states.  For 10 or 11 qubits a tile is one
+    // state row instead: matrices are then uniform per tile (no per-lane matrix path), and a batch
+    // gives four times (twice) as many workgroups to spread over the compute units.
+    const int t = std::max(kMinTile, std::min(12, ext));
+    return (n < t && n >= kMinTile) ? n : t;
 }
 
 Plan build_plan(const qsv_circuit& c, int n, int64_t batch, bool inverse, int tile_log2, bool grad,
