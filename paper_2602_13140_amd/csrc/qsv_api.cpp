@@ -448,8 +448,7 @@ qsv_status qsv_amp_encode(qsv_ctx* ctx, const float* x_dev, int64_t dim, float* 
     double* partial = (double*)ar.take((size_t)ctx->batch * nblk * 8);
     double* inv = (double*)ar.take((size_t)ctx->batch * 8);
     if (!partial || !inv) return ws_fail(ctx, ar, "qsv_amp_encode");
-    QSV_HIP(ctx, launch_sumsq(x_dev, ctx->batch, dim, partial, nblk, ctx->stream), "sumsq");
-    QSV_HIP(ctx, launch_norm_finish(partial, nblk, ctx->batch, inv, norm_out_dev, ctx->stream), "norm");
+    QSV_HIP(ctx, launch_norms(x_dev, ctx->batch, dim, partial, nblk, inv, norm_out_dev, ctx->stream), "norms");
     QSV_HIP(ctx, launch_encode_write(x_dev, dim, ctx->n, ctx->batch, inv, plain_rows(ctx->n), ctx->state,
                                      ctx->stream),
             "encode");
@@ -613,8 +612,7 @@ qsv_status qsv_param_shift_grad(qsv_ctx* ctx, const qsv_circuit* c, const float*
     float* ovr = (float*)ar.take(msamples * (size_t)(2 * P) * 32);
     double* f = (double*)ar.take((size_t)circuits * 8);
     if (!npart || !inv || !mats || !ovr || !f) return ws_fail(ctx, ar, "qsv_param_shift_grad");
-    QSV_HIP(ctx, launch_sumsq(x_dev, B, dim, npart, nblk, ctx->stream), "sumsq");
-    QSV_HIP(ctx, launch_norm_finish(npart, nblk, B, inv, nullptr, ctx->stream), "norm");
+    QSV_HIP(ctx, launch_norms(x_dev, B, dim, npart, nblk, inv, nullptr, ctx->stream), "norms");
 
     // a chunk of circuit states plus their reduction partials, sized to what is left of the workspace
     const size_t row_bytes = state_bytes + (size_t)chunk_blocks(n) * 13 * 8 + 2 * kAlign;
@@ -761,8 +759,7 @@ static qsv_status adjoint_impl(qsv_ctx* ctx, const qsv_circuit* c, const float* 
     float* mats = (float*)ar.take(mats_bytes(*c, n, B));
     double* f = (double*)ar.take((size_t)B * per * 8);
     if (!npart || !inv || !mats || !f) return ws_fail(ctx, ar, "qsv_adjoint_grad");
-    QSV_HIP(ctx, launch_sumsq(x_dev, B, dim, npart, nblk, ctx->stream), "sumsq");
-    QSV_HIP(ctx, launch_norm_finish(npart, nblk, B, inv, nullptr, ctx->stream), "norm");
+    QSV_HIP(ctx, launch_norms(x_dev, B, dim, npart, nblk, inv, nullptr, ctx->stream), "norms");
 
     // per sample of a chunk: psi alone (forward), then the (psi, lambda) pair, plus reduction partials
     const size_t tpart = (size_t)n * adj_trans_blocks(n) * 8 * 8;

@@ -73,10 +73,8 @@ hipError_t launch_build_shifted(const CircDev& c, const float* params, const flo
                                 int64_t samples, float* out, hipStream_t st);
 
 // encoding
-hipError_t launch_sumsq(const float* x, int64_t samples, int64_t dim, double* partial, int nblk,
-                        hipStream_t st);
-hipError_t launch_norm_finish(const double* partial, int nblk, int64_t samples, double* inv_norm,
-                              float* norm_out, hipStream_t st);
+hipError_t launch_norms(const float* x, int64_t samples, int64_t dim, double* partial, int nblk,
+                        double* inv_norm, float* norm_out, hipStream_t st);
 hipError_t launch_encode_write(const float* x, int64_t dim, int n, int64_t rows, const double* inv_norm,
                                const RowMap& rm, float2* state, hipStream_t st);
 

@@ -535,6 +535,20 @@ __global__ __launch_bounds__(256) void k_build_mats(CircDev c, const float* para
     }
 }
 
+// One table shared by the whole batch: few matrices, so one launch in which the thread of a layer's
+// last qubit recomputes that layer's factors itself.
+__global__ __launch_bounds__(256) void k_build_mats_shared(CircDev c, const float* params, u64 count,
+                                                           int inverse, const int* order, float* out) {
+    const u64 idx = (u64)blockIdx.x * 256 + threadIdx.x;
+    if (idx >= count) return;
+    const int lq = order ? order[idx] : (int)idx;
+    const int l = lq / c.n, q = lq % c.n;
+    M2 u = fused_raw(c, params, nullptr, 0, l, q, -1, 0.0, inverse);
+    if (q + 1 < c.n) strip_phase(u);
+    else { const Ph p = layer_phase(c, params, nullptr, 0, l, inverse); scale_m(u, p.r, p.i); }
+    store_m(u, out + idx * 8);
+}
+
 __global__ __launch_bounds__(256) void k_build_mats_last(CircDev c, u64 tables, const int* exec_of,
                                                          float* out, const double* side) {
     const u64 idx = (u64)blockIdx.x * 256 + threadIdx.x;
@@ -586,7 +600,9 @@ __global__ __launch_bounds__(256) void k_build_shifted(CircDev c, const float* p
 
 // ------------------------------------------------------------------------------------------
 // Amplitude encoding.
-__global__ __launch_bounds__(256) void k_sumsq(const float* x, u64 dim, double* partial, int nblk) {
+// inv_norm != NULL (only with nblk = 1): the block is the whole sample and finishes the norm itself.
+__global__ __launch_bounds__(256) void k_sumsq(const float* x, u64 dim, double* partial, int nblk,
+                                               double* inv_norm, float* norm_out) {
     __shared__ double sm[4];
     const u64 b = blockIdx.y;
     const float* xb = x + b * dim;
@@ -599,7 +615,14 @@ __global__ __launch_bounds__(256) void k_sumsq(const float* x, u64 dim, double* 
         }
     }
     const double tot = block_sum256(acc, sm);
-    if (threadIdx.x == 0) partial[b * nblk + blockIdx.x] = tot;
+    if (threadIdx.x == 0) {
+        partial[b * nblk + blockIdx.x] = tot;
+        if (inv_norm) {
+            const double nrm = sqrt(tot);
+            inv_norm[b] = nrm > 0.0 ? 1.0 / nrm : 0.0;
+            if (norm_out) norm_out[b] = (float)nrm;
+        }
+    }
 }
 
 __global__ __launch_bounds__(256) void k_norm_finish(const double* partial, int nblk, double* inv_norm,
@@ -1274,6 +1297,11 @@ hipError_t launch_build_mats(const CircDev& c, const float* params, const float*
     const u64 count = tables * c.n_layers * c.n;
     if (count == 0) return hipSuccess;
     if ((order == nullptr) != (exec_of == nullptr)) return hipErrorInvalidValue;
+    if (!c.reupload) {
+        hipLaunchKernelGGL(k_build_mats_shared, dim3(blocks_for(count, 256)), dim3(256), 0, st, c, params,
+                           count, inverse, order, out);
+        return hipGetLastError();
+    }
     hipLaunchKernelGGL(k_build_mats, dim3(blocks_for(count, 256)), dim3(256), 0, st, c, params, feats,
                        count, inverse, order, out, side);
     hipError_t e = hipGetLastError();
@@ -1293,15 +1321,15 @@ hipError_t launch_build_shifted(const CircDev& c, const float* params, const flo
     return hipGetLastError();
 }
 
-hipError_t launch_sumsq(const float* x, int64_t samples, int64_t dim, double* partial, int nblk,
-                        hipStream_t st) {
-    hipLaunchKernelGGL(k_sumsq, dim3(nblk, (unsigned)samples), dim3(256), 0, st, x, (u64)dim, partial,
-                       nblk);
-    return hipGetLastError();
-}
-
-hipError_t launch_norm_finish(const double* partial, int nblk, int64_t samples, double* inv_norm,
-                              float* norm_out, hipStream_t st) {
+// ||x_b|| of every sample: inv_norm [samples] (0 for a zero vector), norm_out optional.  One launch
+// when a sample fits one block, else block partials and a finishing launch.
+hipError_t launch_norms(const float* x, int64_t samples, int64_t dim, double* partial, int nblk,
+                        double* inv_norm, float* norm_out, hipStream_t st) {
+    const bool one = nblk == 1;
+    hipLaunchKernelGGL(k_sumsq, dim3(nblk, (unsigned)samples), dim3(256), 0, st, x, (u64)dim, partial, nblk,
+                       one ? inv_norm : (double*)nullptr, one ? norm_out : (float*)nullptr);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess || one) return e;
     hipLaunchKernelGGL(k_norm_finish, dim3((unsigned)samples), dim3(256), 0, st, partial, nblk,
                        inv_norm, norm_out);
     return hipGetLastError();
