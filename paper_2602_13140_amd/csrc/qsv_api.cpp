@@ -762,7 +762,7 @@ static qsv_status adjoint_impl(qsv_ctx* ctx, const qsv_circuit* c, const float* 
     QSV_HIP(ctx, launch_norms(x_dev, B, dim, npart, nblk, inv, nullptr, ctx->stream), "norms");
 
     // per sample of a chunk: psi alone (forward), then the (psi, lambda) pair, plus reduction partials
-    const size_t tpart = (size_t)n * adj_trans_blocks(n) * 8 * 8;
+    const size_t tpart = (size_t)n * (adj_trans_blocks(n) + 1) * 8 * 8;
     const size_t zbytes = (size_t)chunk_blocks(n) * 13 * 8;
     const size_t sample_bytes = 3 * state_bytes + tpart + zbytes + 2 * (size_t)n * 8 + 6 * kAlign;
     int64_t chunk = (int64_t)(ar.remaining() / sample_bytes);

@@ -121,7 +121,7 @@ hipError_t launch_pauli(const float2* state, int64_t rows, int n, uint64_t xmask
 // 1/n sum (z-y)^2 into f[.][2P] and coef = 2/n (z-y).
 // launch_adj_layer: for the row pairs of S (psi, lambda), both taken back to the start of `layer`,
 // the derivatives with respect to that layer's angles, written into f[sample][2p], f[sample][2p+1]
-// as (g, -g).  partial: row_pairs * n * adj_trans_blocks(n) * 8 doubles.
+// as (g, -g).  partial: row_pairs * n * (adj_trans_blocks(n) + 1) * 8 doubles.
 hipError_t launch_adj_init(const float2* A, int n, int kind, int q, uint64_t mask, const double* coef,
                            int64_t rows, float2* S, hipStream_t st);
 hipError_t launch_trash_loss(const float2* A, int n, uint64_t mask, int64_t rows, int64_t sample0, int64_t P,

@@ -1155,6 +1155,92 @@ __global__ __launch_bounds__(256) void k_trans_block(const float2* S, int n, u64
     }
 }
 
+// The same sums for n >= 12, several qubits per read of the two states.  A workgroup stages a tile of
+// 2^12 amplitudes of psi and of lambda in LDS (tile = the c lowest index bits plus 12 - c bits from
+// bit w, as in the pass kernel), and every thread then walks over its 8 index pairs for each of the
+// tile bits j0..11, i.e. for up to NJ qubits at once.  A workgroup covers `per_group` consecutive
+// tiles of one row pair before it reduces its accumulators, so the reduction is amortised.
+// partial: [(pair * n + qubit) * nblk + group * 4 + wavefront][8] (nblk = 4 * groups), the layout
+// k_adj_layer reads.
+template <int NJ>
+__global__ __launch_bounds__(256) void k_trans_tile(const float2* S, int n, int c, int w, int j0,
+                                                    int per_group, int nblk, double* partial) {
+    __shared__ float2 ps[4096];
+    __shared__ float2 lm[4096];                      // 64 KiB in all
+    const u64 r = blockIdx.y;
+    const float2* psi = S + ((2 * r) << n);
+    const float2* lam = S + ((2 * r + 1) << n);
+    const unsigned t = threadIdx.x;
+    const unsigned cmask = (1u << c) - 1u;
+    const int wc = w - c;
+    float acc[NJ][8];
+#pragma unroll
+    for (int a = 0; a < NJ; ++a)
+#pragma unroll
+        for (int b = 0; b < 8; ++b) acc[a][b] = 0.f;
+    for (int g = 0; g < per_group; ++g) {
+        const u64 tb = (u64)blockIdx.x * per_group + g;      // tile of the row
+        const u64 base = ((tb & ((1ull << wc) - 1ull)) << c) | ((tb >> wc) << (w + 12 - c));
+        if (g) __syncthreads();
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+            const unsigned tau = (unsigned)i * 256u + t;
+            const u64 k = base | (u64)(tau & cmask) | ((u64)(tau >> c) << w);
+            ps[tau] = psi[k];
+            lm[tau] = lam[k];
+        }
+        __syncthreads();
+#pragma unroll
+        for (int a = 0; a < NJ; ++a) {
+            const int j = j0 + a;
+            if (j < 12) {
+                const unsigned low = (1u << j) - 1u;
+#pragma unroll 2
+                for (int i = 0; i < 8; ++i) {
+                    const unsigned p = (unsigned)i * 256u + t;
+                    const unsigned k0 = ((p >> j) << (j + 1)) | (p & low);
+                    const unsigned k1 = k0 | (1u << j);
+                    const float2 l0 = lm[k0], l1 = lm[k1], s0 = ps[k0], s1 = ps[k1];
+                    acc[a][0] += l0.x * s0.x + l0.y * s0.y; acc[a][1] += l0.x * s0.y - l0.y * s0.x;
+                    acc[a][2] += l0.x * s1.x + l0.y * s1.y; acc[a][3] += l0.x * s1.y - l0.y * s1.x;
+                    acc[a][4] += l1.x * s0.x + l1.y * s0.y; acc[a][5] += l1.x * s0.y - l1.y * s0.x;
+                    acc[a][6] += l1.x * s1.x + l1.y * s1.y; acc[a][7] += l1.x * s1.y - l1.y * s1.x;
+                }
+            }
+        }
+    }
+    // every wavefront writes its own partial: index (group, wavefront)
+#pragma unroll
+    for (int a = 0; a < NJ; ++a) {
+        const int j = j0 + a;
+        if (j >= 12) break;
+        const int q = j < c ? j : j - c + w;                 // the qubit behind tile bit j
+        double* out = partial + ((r * n + q) * (u64)nblk + (u64)blockIdx.x * 4 + (t >> 6)) * 8;
+#pragma unroll
+        for (int b = 0; b < 8; ++b) {
+            const double tot = wave_sum((double)acc[a][b]);
+            if ((t & 63u) == 0) out[b] = tot;
+        }
+    }
+}
+
+// Adds the nblk partials of every (row pair, qubit): one wavefront per job, lanes stride over the
+// partials, fixed order.  out: [jobs][8].
+__global__ __launch_bounds__(256) void k_trans_finish(const double* partial, int nblk, u64 jobs, double* out) {
+    const u64 job = (u64)blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (job >= jobs) return;
+    const int lane = threadIdx.x & 63;
+    double acc[8];
+    for (int j = 0; j < 8; ++j) acc[j] = 0.0;
+    const double* p = partial + job * (u64)nblk * 8;
+    for (int b = lane; b < nblk; b += 64)
+        for (int j = 0; j < 8; ++j) acc[j] += p[(u64)b * 8 + j];
+    for (int j = 0; j < 8; ++j) {
+        const double t = wave_sum(acc[j]);
+        if (lane == 0) out[job * 8 + j] = t;
+    }
+}
+
 // Gradients of one layer from the transition matrices: thread = (row pair, slot, qubit).  With
 // W = R_{s-1} ... R_0 (the slots before s on that qubit) the derivative with respect to the angle of
 // slot s is 2 Re sum_ab Bt[a][b] M[a][b], Bt = W^dagger (-i/2 P_s) W.  Written as f+ = g, f- = -g so
@@ -1503,20 +1589,58 @@ hipError_t launch_adam(float* p, const float* g, float* m, float* v, int64_t cou
     return hipGetLastError();
 }
 
-int adj_trans_blocks(int n) { return n - 1 > 12 ? 1 << (n - 1 - 12) : 1; }
+
+
+// Tiles of a row handled by one workgroup of k_trans_tile, and the resulting groups per row.
+static inline int trans_tiles_per_group(int n) { const int tiles = 1 << (n - 12); return tiles < 4 ? tiles : 4; }
+static inline int trans_groups(int n) { return (1 << (n - 12)) / trans_tiles_per_group(n); }
+
+// partial entries per (row pair, qubit) of the transition sums
+int adj_trans_blocks(int n) { return n < 12 ? 1 : 4 * trans_groups(n); }
 
 hipError_t launch_adj_layer(const float2* S, int n, int64_t row_pairs, double* partial, const CircDev& c,
                             int layer, const float* params, const float* feats, int64_t sample0, int64_t P,
                             double* f, hipStream_t st) {
     if (row_pairs < 1 || row_pairs > 65535) return hipErrorInvalidValue;
-    const int nblk = adj_trans_blocks(n);
-    hipLaunchKernelGGL(k_trans_block, dim3(nblk, n, (unsigned)row_pairs), dim3(256), 0, st, S, n,
-                       (u64)1 << (n - 1), nblk, partial);
-    hipError_t e = hipGetLastError();
-    if (e != hipSuccess) return e;
+    int nblk;
+    if (n < 12) {
+        nblk = adj_trans_blocks(n);
+        hipLaunchKernelGGL(k_trans_block, dim3(nblk, n, (unsigned)row_pairs), dim3(256), 0, st, S, n,
+                           (u64)1 << (n - 1), nblk, partial);
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+    } else {
+        // qubits 0..11 from contiguous tiles, then 8 more per read from tiles whose window sits higher
+        // (the last window ends at bit n and only its not yet covered qubits are taken)
+        const int groups = trans_groups(n);
+        nblk = adj_trans_blocks(n);                      // one partial per wavefront of a group
+        const int per_group = trans_tiles_per_group(n);
+        const dim3 grid(groups, (unsigned)row_pairs);
+        hipLaunchKernelGGL((k_trans_tile<12>), grid, dim3(256), 0, st, S, n, 12, 12, 0, per_group, nblk, partial);
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+        for (int done = 12; done < n;) {
+            int w = done, j0 = 4;
+            if (w + 8 > n) { w = n - 8; j0 = 4 + (done - w); }
+            hipLaunchKernelGGL((k_trans_tile<8>), grid, dim3(256), 0, st, S, n, 4, w, j0, per_group, nblk, partial);
+            e = hipGetLastError();
+            if (e != hipSuccess) return e;
+            done = w + 8;
+        }
+    }
     const u64 jobs = (u64)row_pairs * c.slots() * c.n;
     if (jobs == 0) return hipSuccess;
-    hipLaunchKernelGGL(k_adj_layer, dim3(blocks_for(jobs, 256)), dim3(256), 0, st, partial, nblk, c, layer,
+    const double* sums = partial;
+    if (nblk > 1) {   // the summed matrices go behind the partials
+        double* M = partial + (u64)row_pairs * n * nblk * 8;
+        hipLaunchKernelGGL(k_trans_finish, dim3(blocks_for((u64)row_pairs * n, 4)), dim3(256), 0, st, partial,
+                           nblk, (u64)row_pairs * n, M);
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+        sums = M;
+        nblk = 1;
+    }
+    hipLaunchKernelGGL(k_adj_layer, dim3(blocks_for(jobs, 256)), dim3(256), 0, st, sums, nblk, c, layer,
                        params, feats, (u64)sample0, (u64)row_pairs, (u64)P, f);
     return hipGetLastError();
 }
