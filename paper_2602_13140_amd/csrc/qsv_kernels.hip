@@ -535,7 +535,7 @@ __global__ __launch_bounds__(256) void k_build_mats(CircDev c, const float* para
     }
 }
 
-// One table shared by the whole batch: few matrices, so one launch in which the thread of a layer's
+// One table shared by the whole batch and few qubits: one launch in which the thread of a layer's
 // last qubit recomputes that layer's factors itself.
 __global__ __launch_bounds__(256) void k_build_mats_shared(CircDev c, const float* params, u64 count,
                                                            int inverse, const int* order, float* out) {
@@ -1383,7 +1383,7 @@ hipError_t launch_build_mats(const CircDev& c, const float* params, const float*
     const u64 count = tables * c.n_layers * c.n;
     if (count == 0) return hipSuccess;
     if ((order == nullptr) != (exec_of == nullptr)) return hipErrorInvalidValue;
-    if (!c.reupload) {
+    if (!c.reupload && c.n <= 8) {   // few qubits: the serial factor loop is shorter than a second launch
         hipLaunchKernelGGL(k_build_mats_shared, dim3(blocks_for(count, 256)), dim3(256), 0, st, c, params,
                            count, inverse, order, out);
         return hipGetLastError();
