@@ -89,6 +89,8 @@ def test_apply_layers_small(oracle, n, B, L, rot, ent, reup, mode):
     ctx = gu.make_ctx(n, B, tile=int(mode[1:3]) if mode.startswith("t") else 0,
                       naive=1 if mode == "naive" else 0,
                       planes=int(mode[4]) if mode[3:4] == "p" else 0)
+    if mode.endswith("p1"):
+        ctx.qsv_set_option("nt_store", 1)      # nontemporal tile stores, normally for large states only
     circ = qb.circuit_from_spec(spec)
     xd, pd = gu.dev(x), gu.dev(params)
     fd = gu.dev(feats) if reup else None
@@ -211,7 +213,8 @@ def test_sampling_special_states():
     (13, 1, 2, (RY,), LADDER, 0, 0), (1, 4, 3, (RX, RZ), RING, 0, 0), (7, 3, 4, (RY, RZ), RING, 0, 6),
     (8, 5, 3, (RX, RZ), LADDER, 1, 2), (11, 2, 3, (RY, RZ), LADDER, 0, 10)])
 @pytest.mark.parametrize("mode", ["default", "naive", "whole", "chunk5", "whole-chunk4", "naive-whole",
-                                  "adjoint", "adjoint-naive", "adjoint-chunk2"])
+                                  "adjoint", "adjoint-naive", "adjoint-chunk2",
+                                  "t10", "t11-whole", "t13", "t12p2", "adjoint-t10", "adjoint-t13"])
 def test_param_shift_grad_small(oracle, n, B, L, rot, ent, reup, obs, mode):
     torch = gu.torch_cuda()
     g = rng(40 + n)
@@ -223,11 +226,13 @@ def test_param_shift_grad_small(oracle, n, B, L, rot, ent, reup, obs, mode):
     lref, gref = oracle.param_shift_grad(x, n, ocirc(oracle, spec), params, feats, obs_qubit=obs)
     # default: layer by layer from kept states; "whole": every shifted circuit from the start;
     # "chunk": a cap on circuits per launch so that chunks end inside a sample's rows
-    ctx = gu.make_ctx(n, B, naive=1 if "naive" in mode else 0)
+    tile = next((int(part[1:3]) for part in mode.split("-") if part.startswith("t1")), 0)
+    ctx = gu.make_ctx(n, B, naive=1 if "naive" in mode else 0, tile=tile, planes=2 if "p2" in mode else 0)
     if "whole" in mode:
         ctx.qsv_set_option("grad_layered", 0)
     if "chunk" in mode:
         ctx.qsv_set_option("grad_chunk_rows", int(mode[-1]))
+    ctx.qsv_set_option("nt_store", 1 if n % 2 else 0)    # both store flavours, whatever the size
     ctx.state.fill_(3.0)
     loss = torch.zeros(B, dtype=torch.float32, device="cuda")
     grad = torch.zeros((B, P), dtype=torch.float32, device="cuda")
