@@ -187,6 +187,39 @@ def fidelity(state, x):
     return F
 
 
+def reset_fidelity(state, circ, params, feats, mask, x):
+    """Fidelity with the input after a true reset of the trash qubits and the decoder (circ inverse)."""
+    B, n = _state(state)
+    params = np.ascontiguousarray(params, dtype=np.float64).ravel()
+    assert params.size == num_params(circ, n)
+    f = None
+    if feats is not None:
+        f = np.ascontiguousarray(feats, dtype=np.float64)
+        assert f.shape == (B, n)
+    x = np.ascontiguousarray(x, dtype=np.float32)
+    assert x.shape[0] == B
+    F = np.empty(B, dtype=np.float64)
+    rc = lib().oracle_reset_fidelity(_p(state), ctypes.c_int64(B), ctypes.c_int(n), ctypes.byref(circ),
+                                     _p(params), _p(f) if f is not None else None, ctypes.c_uint64(mask),
+                                     _p(x), ctypes.c_int64(x.shape[1]), _p(F))
+    if rc:
+        raise ValueError("oracle_reset_fidelity rc=%d" % rc)
+    return F
+
+
+def shot_expz(samples, n):
+    """Finite-shot estimate of <Z_q> from basis-state samples [B, shots] (entries -1 are skipped):
+    the mean of (1 - 2 bit_q) over the valid shots; a row without valid shots gives 0."""
+    s = np.asarray(samples, dtype=np.int64)
+    out = np.zeros((s.shape[0], n), dtype=np.float64)
+    for b in range(s.shape[0]):
+        v = s[b][s[b] >= 0]
+        if v.size:
+            for q in range(n):
+                out[b, q] = np.mean(1.0 - 2.0 * ((v >> q) & 1))
+    return out
+
+
 def pauli_expect(state, xmask=0, ymask=0, zmask=0, with_imag=False):
     """<P> for the Pauli string with X on xmask, Y on ymask, Z on zmask (bit q = qubit q)."""
     B, n = _state(state)

@@ -377,6 +377,47 @@ int oracle_fidelity(const cplx* state, int64_t B, int n, const float* x, int64_t
     return 0;
 }
 
+// ---------------------------------------------------------------- trash reset
+// Fidelity of an autoencoder whose trash qubits are really reset to |0> (task statement, workload
+// config 3: "trash-qubit probability ..., decoder, fidelity"; the reset is the physical operation
+// the projection onto trash = 0 stands in for).  Measuring the trash qubits gives outcome t with the
+// unnormalised conditional state psi_t on the other qubits; after the reset the register holds
+// psi_t (x) |0..0>.  With D the circuit c run in inverse mode (the decoder),
+//   F[b] = sum_t | <a_in,b| D ( psi_t (x) |0> ) |^2,   a_in = x_b / ||x_b||,
+// which is <a_in| D rho D^dagger |a_in> for the reset (mixed) state rho.  state is not modified.
+int oracle_reset_fidelity(const cplx* state, int64_t B, int n, const oracle_circuit* c,
+                          const double* params, const double* feats, uint64_t mask, const float* x,
+                          int64_t dim, double* F) {
+    if (check_circuit(c, n) || B < 1) return 1;
+    if (c->reupload && !feats) return 1;
+    if (mask == 0 || (n < 64 && (mask >> n) != 0)) return 1;
+    const int64_t N = (int64_t)1 << n;
+    if (dim < 1 || dim > N) return 1;
+    int m = 0;
+    for (int q = 0; q < n; ++q) m += (int)((mask >> q) & 1);
+    if (m > 20) return 1;
+    for (int64_t b = 0; b < B; ++b) {
+        std::vector<cplx> work((size_t)N);
+        const double* fb = feats ? feats + b * n : nullptr;
+        double total = 0.0;
+        for (int64_t t = 0; t < ((int64_t)1 << m); ++t) {
+            // spread the bits of t over the mask positions
+            uint64_t tbits = 0;
+            int j = 0;
+            for (int q = 0; q < n; ++q)
+                if ((mask >> q) & 1) { if ((t >> j) & 1) tbits |= (uint64_t)1 << q; ++j; }
+            for (int64_t k = 0; k < N; ++k)
+                work[k] = (((uint64_t)k & mask) == 0) ? state[b * N + (k | (int64_t)tbits)] : cplx(0.0, 0.0);
+            run_circuit(work.data(), n, c, params, fb, 1, -1, 0.0, 0);
+            double Ft = 0.0;
+            oracle_fidelity(work.data(), 1, n, x + b * dim, dim, &Ft);
+            total += Ft;
+        }
+        F[b] = total;
+    }
+    return 0;
+}
+
 // ---------------------------------------------------------------- Pauli strings
 // E[b] = <a_b| P |a_b> for P = product over qubits of X (bit in xmask), Y (ymask) or Z (zmask);
 // the masks must not overlap.  Written as the definition: copy the state, apply the one-qubit

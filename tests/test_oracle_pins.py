@@ -543,3 +543,73 @@ def test_pauli_strings_vs_dense_kronecker(oracle):
         assert np.allclose(oracle.pauli_expect(st, zmask=1 << q), z[:, q], atol=1e-13)
     with pytest.raises(ValueError):
         oracle.pauli_expect(st, xmask=1, zmask=1)
+
+
+# ------------------------------------------------------------------ trash reset, finite shots
+@pytest.mark.parametrize("n,mask,ent", [(3, 0b100, RING), (4, 0b1010, LADDER), (5, 0b11000, RING), (4, 0b0001, RING)])
+def test_reset_fidelity_vs_density_matrix(oracle, n, mask, ent):
+    """F = <a_in| D rho D^dagger |a_in> with rho = (partial trace over the trash qubits) (x) |0><0|,
+    everything built densely with numpy."""
+    g = rng(140 + n)
+    L, rot = 2, (RY, RZ)
+    circ = oracle.make_circuit(L, list(rot), ent)
+    P = oracle.num_params(circ, n)
+    params = g.uniform(0, 2 * np.pi, P)
+    B = 3
+    x = g.standard_normal((B, 1 << n)).astype(np.float32)
+    st, _ = oracle.amp_encode(x, n)
+    a_in = st.copy()
+    oracle.apply_layers(st, circ, params)                       # encoder output
+    F = oracle.reset_fidelity(st, circ, params, None, mask, x)
+    U = dense.circuit_unitary(n, L, rot, ent, 0, params)
+    D = U.conj().T
+    k = np.arange(1 << n)
+    keep = (k & mask) == 0
+    for b in range(B):
+        rho = np.zeros((1 << n, 1 << n), dtype=np.complex128)
+        for t in sorted(set((k & mask).tolist())):
+            v = np.zeros(1 << n, dtype=np.complex128)
+            v[keep] = st[b][k[keep] | t]                         # psi_t with the trash moved to 0
+            rho += np.outer(v, v.conj())
+        assert abs(np.trace(rho).real - 1.0) < 1e-12
+        want = (a_in[b].conj() @ D @ rho @ D.conj().T @ a_in[b]).real
+        assert abs(F[b] - want) < 1e-12
+    # never below the post-selected, unnormalised value (the t = 0 term alone)
+    st0 = st.copy()
+    oracle.project_zero(st0, mask, renormalise=False)
+    oracle.apply_layers(st0, circ, params, inverse=True)
+    assert np.all(F >= oracle.fidelity(st0, x) - 1e-14)
+
+
+def test_reset_fidelity_is_one_when_trash_is_already_zero(oracle):
+    n, mask = 4, 0b1000
+    circ = oracle.make_circuit(2, [RY, RZ], RING)
+    params = rng(150).uniform(0, 2 * np.pi, oracle.num_params(circ, n))
+    # choose the input as the decoder applied to a state with qubit 3 in |0>: the encoder then
+    # produces exactly that state, the reset changes nothing, and the decoder returns the input
+    v = rng(151).standard_normal((2, 8)).astype(np.float32)
+    st, _ = oracle.amp_encode(v, n)                              # amplitudes 8..15 are zero
+    oracle.apply_layers(st, circ, params, inverse=True)
+    # a_in must be real for the encoding interface: use its real part only if it is real; instead
+    # check the identity through the state itself
+    enc = st.copy()
+    oracle.apply_layers(enc, circ, params)
+    assert np.allclose(oracle.marginal(enc, mask)[:, 0], 1.0, atol=1e-12)
+    w = enc.copy()
+    oracle.apply_layers(w, circ, params, inverse=True)
+    assert np.allclose(np.abs(np.einsum("bk,bk->b", st.conj(), w)) ** 2, 1.0, atol=1e-12)
+
+
+def test_shot_expz_closed_forms(oracle):
+    s = np.array([[0, 0, 0, 0], [5, 5, 5, 5], [0, 7, -1, -1], [-1, -1, -1, -1]], dtype=np.int64)
+    z = oracle.shot_expz(s, 3)
+    assert np.array_equal(z[0], [1, 1, 1])
+    assert np.array_equal(z[1], [-1, 1, -1])                     # 5 = 0b101
+    assert np.array_equal(z[2], [0, 0, 0])                       # one shot each way, two skipped
+    assert np.array_equal(z[3], [0, 0, 0])
+    # many shots from a known distribution approach the exact expectation
+    g = rng(152)
+    p = g.random(16); p /= p.sum()
+    smp = g.choice(16, size=(1, 200000), p=p)
+    exact = np.array([(p * (1 - 2 * ((np.arange(16) >> q) & 1))).sum() for q in range(4)])
+    assert np.abs(oracle.shot_expz(smp, 4)[0] - exact).max() < 5 / np.sqrt(200000)
