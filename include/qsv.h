@@ -137,6 +137,22 @@ typedef struct {
 
 qsv_status qsv_measure(qsv_ctx* ctx, const qsv_measure_req* req);
 
+/* Fidelity of an autoencoder with a true reset of its trash qubits (task statement, workload
+ * config 3; the projection of QSV_M_PROJECT_ZERO is the post-selected stand-in for it).  The
+ * context's state is taken as the encoder output.  For every outcome t of measuring the qubits of
+ * mask (at most 10), the unnormalised conditional state with the trash qubits set to 0 is run
+ * through circuit c in inverse mode (the decoder) and
+ *   out[b] = sum_t | <x_b / ||x_b||  |  D (psi_t (x) |0>) > |^2        (float [batch]).
+ * Works in the workspace, 2^m decoder runs per sample in chunks; the state is left as it was. */
+qsv_status qsv_reset_fidelity(qsv_ctx* ctx, const qsv_circuit* c, const float* params_dev,
+                              const float* feats_dev, uint64_t mask, const float* x_dev, int64_t dim,
+                              float* out_dev);
+
+/* Finite-shot estimate of <Z_q> for every qubit from basis-state samples as QSV_M_SAMPLE writes
+ * them: samples_dev int64 [batch][shots]; out_dev float [batch][n_qubits] = mean over the shots of
+ * (1 - 2 bit_q); entries < 0 (no valid outcome) are skipped, a row without valid shots gives 0. */
+qsv_status qsv_shot_expz(qsv_ctx* ctx, const long long* samples_dev, int64_t shots, float* out_dev);
+
 /* Expectation value of a Pauli string on the current state (task statement: "measurement
  * (... <Z> ...)", widened to X and Y): P = product over qubits of X (bit set in xmask), Y (ymask)
  * or Z (zmask), identity elsewhere; the masks must not overlap and name qubits < n_qubits.

@@ -91,6 +91,10 @@ def load():
     L.qsv_adam_step.restype = i32
     L.qsv_adam_step.argtypes = [vp, vp, vp, vp, vp, i64, i64, ctypes.c_double, ctypes.c_double,
                                 ctypes.c_double, ctypes.c_double]
+    L.qsv_reset_fidelity.restype = i32
+    L.qsv_reset_fidelity.argtypes = [vp, ctypes.POINTER(qsv_circuit), vp, vp, ctypes.c_uint64, vp, i64, vp]
+    L.qsv_shot_expz.restype = i32
+    L.qsv_shot_expz.argtypes = [vp, vp, i64, vp]
     L.qsv_pauli_expect.restype = i32
     L.qsv_pauli_expect.argtypes = [vp, ctypes.c_uint64, ctypes.c_uint64, ctypes.c_uint64, vp]
     L.qsv_plan_describe.restype = i64
@@ -215,6 +219,13 @@ class Context:
         self._check(self.L.qsv_loss_grad(self.h, ctypes.byref(circ), _ptr(x), x.shape[1], _ptr(params),
                                          _ptr(feats), ctypes.byref(spec), _ptr(loss), _ptr(grad),
                                          _ptr(mean_loss), _ptr(mean_grad)))
+
+    def qsv_reset_fidelity(self, circ, params, feats, mask, x, out):
+        self._check(self.L.qsv_reset_fidelity(self.h, ctypes.byref(circ), _ptr(params), _ptr(feats), mask,
+                                              _ptr(x), x.shape[1], _ptr(out)))
+
+    def qsv_shot_expz(self, samples, out):
+        self._check(self.L.qsv_shot_expz(self.h, _ptr(samples), samples.shape[1], _ptr(out)))
 
     def qsv_pauli_expect(self, out, xmask=0, ymask=0, zmask=0):
         self._check(self.L.qsv_pauli_expect(self.h, xmask, ymask, zmask, _ptr(out)))

@@ -538,9 +538,9 @@ qsv_status qsv_measure(qsv_ctx* ctx, const qsv_measure_req* req) {
             if (nblk > 1024) nblk = 1024;
             double* partial = (double*)ar.take((size_t)B * nblk * 3 * 8);
             if (!partial) return ws_fail(ctx, ar, "qsv_measure(FIDELITY)");
-            QSV_HIP(ctx, launch_fidelity_block(ctx->state, B, n, req->x_dev, req->dim, partial, nblk, ctx->stream),
+            QSV_HIP(ctx, launch_fidelity_block(ctx->state, B, n, req->x_dev, req->dim, partial, nblk, plain_rows(n), ctx->stream),
                     "fidelity block");
-            QSV_HIP(ctx, launch_fidelity_finish(partial, nblk, B, (float*)req->out_dev, ctx->stream),
+            QSV_HIP(ctx, launch_fidelity_finish(partial, nblk, B, (float*)req->out_dev, nullptr, ctx->stream),
                     "fidelity finish");
             return QSV_OK;
         }
@@ -574,6 +574,73 @@ qsv_status qsv_pauli_expect(qsv_ctx* ctx, uint64_t xmask, uint64_t ymask, uint64
     if (!partial) return ws_fail(ctx, ar, "qsv_pauli_expect");
     QSV_HIP(ctx, launch_pauli(ctx->state, ctx->batch, n, xmask, ymask, zmask, partial, out_dev, ctx->stream),
             "pauli expectation");
+    return QSV_OK;
+}
+
+qsv_status qsv_reset_fidelity(qsv_ctx* ctx, const qsv_circuit* c, const float* params_dev,
+                              const float* feats_dev, uint64_t mask, const float* x_dev, int64_t dim,
+                              float* out_dev) {
+    if (!ctx) return QSV_ERR_INVALID_ARG;
+    std::string why;
+    if (!check_circuit(c, ctx->n, &why)) return fail(ctx, QSV_ERR_INVALID_ARG, why);
+    const int n = ctx->n;
+    const int64_t B = ctx->batch;
+    const int64_t P = qsv_num_params(c, n);
+    if (P > 0 && !params_dev) return fail(ctx, QSV_ERR_INVALID_ARG, "params_dev is NULL");
+    if (c->reupload && !feats_dev) return fail(ctx, QSV_ERR_INVALID_ARG, "reupload = 1 needs feats_dev");
+    if (!x_dev || !out_dev) return fail(ctx, QSV_ERR_INVALID_ARG, "x_dev or out_dev is NULL");
+    if (dim < 1 || dim > ((int64_t)1 << n)) return fail(ctx, QSV_ERR_INVALID_ARG, "dim must be in 1..2^n");
+    if (mask == 0 || (mask >> n) != 0) return fail(ctx, QSV_ERR_INVALID_ARG, "mask must be a non-empty subset of the qubits");
+    const int m = __builtin_popcountll(mask);
+    if (m > 10) return fail(ctx, QSV_ERR_UNSUPPORTED, "reset of more than 10 qubits");
+    qsv_status st = bind_device(ctx);
+    if (st != QSV_OK) return st;
+    const int64_t per = (int64_t)1 << m;
+    const int64_t rows_all = B * per;
+    Arena ar(ctx);
+    const size_t state_bytes = (size_t)8 << n;
+    float* mats = (float*)ar.take(mats_bytes(*c, n, B));
+    double* Frow = (double*)ar.take((size_t)rows_all * 8);
+    if (!mats || !Frow) return ws_fail(ctx, ar, "qsv_reset_fidelity");
+    int nblk = (int)((dim + 4095) / 4096);
+    if (nblk > 1024) nblk = 1024;
+    const size_t row_bytes = state_bytes + (size_t)nblk * 3 * 8 + 2 * kAlign;
+    int64_t chunk = (int64_t)(ar.remaining() / row_bytes);
+    if (chunk < 1) { ar.need = ar.off + row_bytes; return ws_fail(ctx, ar, "qsv_reset_fidelity"); }
+    if (chunk > rows_all) chunk = rows_all;
+    if (chunk > 32768) chunk = 32768;
+    if (ctx->opt_grad_chunk > 0 && chunk > ctx->opt_grad_chunk) chunk = ctx->opt_grad_chunk;
+    if (chunk < rows_all) { int64_t p2 = 1; while (p2 * 2 <= chunk) p2 *= 2; chunk = p2; }
+    float2* work = (float2*)ar.take((size_t)chunk * state_bytes);
+    double* partial = (double*)ar.take((size_t)chunk * nblk * 3 * 8);
+    if (!work || !partial) return ws_fail(ctx, ar, "qsv_reset_fidelity");
+    Prepared pr;
+    st = prepare_circuit(ctx, *c, chunk, 1, 0, params_dev, feats_dev, B, mats, &pr);
+    if (st != QSV_OK) return st;
+    for (int64_t row0 = 0; row0 < rows_all; row0 += chunk) {
+        const int64_t rows = (rows_all - row0) < chunk ? (rows_all - row0) : chunk;
+        RowMap rm;
+        rm.grad = 1; rm.two_p = 0; rm.per = (int)per; rm.row0 = row0;
+        rm.slots_n = 1; rm.n = n;
+        QSV_HIP(ctx, launch_reset_rows(ctx->state, n, mask, rows, rm, work, ctx->stream), "reset rows");
+        st = run_circuit(ctx, *c, pr, work, rows, 1, nullptr, rm);
+        if (st != QSV_OK) return st;
+        QSV_HIP(ctx, launch_fidelity_block(work, rows, n, x_dev, dim, partial, nblk, rm, ctx->stream),
+                "fidelity block");
+        QSV_HIP(ctx, launch_fidelity_finish(partial, nblk, rows, nullptr, Frow + row0, ctx->stream),
+                "fidelity finish");
+    }
+    QSV_HIP(ctx, launch_reset_sum(Frow, per, B, out_dev, ctx->stream), "reset sum");
+    return QSV_OK;
+}
+
+qsv_status qsv_shot_expz(qsv_ctx* ctx, const long long* samples_dev, int64_t shots, float* out_dev) {
+    if (!ctx) return QSV_ERR_INVALID_ARG;
+    if (!samples_dev || !out_dev) return fail(ctx, QSV_ERR_INVALID_ARG, "samples_dev or out_dev is NULL");
+    if (shots < 0) return fail(ctx, QSV_ERR_INVALID_ARG, "shots must be >= 0");
+    qsv_status st = bind_device(ctx);
+    if (st != QSV_OK) return st;
+    QSV_HIP(ctx, launch_shot_expz(samples_dev, shots, ctx->batch, ctx->n, out_dev, ctx->stream), "shot expz");
     return QSV_OK;
 }
 

@@ -103,9 +103,16 @@ hipError_t launch_marginal_finish(const double* partial, int64_t rows_times_v, i
 hipError_t launch_project(float2* state, int64_t rows, int n, uint64_t mask, const double* scale,
                           hipStream_t st);
 hipError_t launch_fidelity_block(const float2* state, int64_t rows, int n, const float* x, int64_t dim,
-                                 double* partial, int nblk, hipStream_t st);
-hipError_t launch_fidelity_finish(const double* partial, int nblk, int64_t rows, float* out,
+                                 double* partial, int nblk, const RowMap& rm, hipStream_t st);
+hipError_t launch_fidelity_finish(const double* partial, int nblk, int64_t rows, float* out, double* out_d,
                                   hipStream_t st);
+// trash reset: rows (sample, outcome) of a chunk from the state; sum of the rows' fidelities per sample
+hipError_t launch_reset_rows(const float2* state, int n, uint64_t mask, int64_t rows, const RowMap& rm,
+                             float2* work, hipStream_t st);
+hipError_t launch_reset_sum(const double* Frow, int64_t per, int64_t B, float* out, hipStream_t st);
+// finite-shot <Z_q> from samples [rows][shots] -> out [rows][n]
+hipError_t launch_shot_expz(const long long* samples, int64_t shots, int64_t rows, int n, float* out,
+                            hipStream_t st);
 // sampling: bsum/cum are uint64 [rows][nblk], nblk = max(1, 2^n / 4096)
 hipError_t launch_sample(const float2* state, int64_t rows, int n, const double* uniforms, int64_t shots,
                          unsigned long long* cum, long long* out, hipStream_t st);

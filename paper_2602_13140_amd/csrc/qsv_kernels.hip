@@ -876,11 +876,11 @@ __global__ __launch_bounds__(256) void k_pauli_finish(const double* partial, int
 }
 
 __global__ __launch_bounds__(256) void k_fidelity_block(const float2* state, int n, const float* x,
-                                                        u64 dim, int nblk, double* partial) {
+                                                        u64 dim, int nblk, RowMap rm, double* partial) {
     __shared__ double sm[4];
     const u64 row = blockIdx.y;
     const float2* a = state + (row << n);
-    const float* xb = x + row * dim;
+    const float* xb = x + row_ctx(rm, row).sample * dim;
     double sxx = 0.0, sr = 0.0, si = 0.0;
     for (u64 base = (u64)blockIdx.x * CHUNK; base < dim; base += (u64)nblk * CHUNK) {
 #pragma unroll
@@ -904,7 +904,8 @@ __global__ __launch_bounds__(256) void k_fidelity_block(const float2* state, int
     }
 }
 
-__global__ __launch_bounds__(256) void k_fidelity_finish(const double* partial, int nblk, float* out) {
+__global__ __launch_bounds__(256) void k_fidelity_finish(const double* partial, int nblk, float* out,
+                                                         double* out_d) {
     __shared__ double sm[4];
     const u64 row = blockIdx.x;
     double sxx = 0.0, sr = 0.0, si = 0.0;
@@ -915,7 +916,56 @@ __global__ __launch_bounds__(256) void k_fidelity_finish(const double* partial, 
     const double t0 = block_sum256(sxx, sm);
     const double t1 = block_sum256(sr, sm);
     const double t2 = block_sum256(si, sm);
-    if (threadIdx.x == 0) out[row] = t0 > 0.0 ? (float)((t1 * t1 + t2 * t2) / t0) : 0.f;
+    if (threadIdx.x == 0) {
+        const double F = t0 > 0.0 ? (t1 * t1 + t2 * t2) / t0 : 0.0;
+        if (out) out[row] = (float)F;
+        if (out_d) out_d[row] = F;
+    }
+}
+
+// Trash reset: row gid = row0 + r stands for (sample, outcome t) = (gid / per, gid % per), per = 2^m.
+// work[r][k] = state[sample][k | bits of t spread over mask] where k has no mask bit, else 0.
+__global__ __launch_bounds__(256) void k_reset_rows(const float2* state, int n, u64 mask, u64 total,
+                                                    RowMap rm, float2* work) {
+    const u64 e2 = ((u64)blockIdx.x * 256 + threadIdx.x) * 2;
+    if (e2 >= total) return;
+    const u64 r = e2 >> n, k = e2 & ((1ull << n) - 1);
+    const u64 gid = (u64)rm.row0 + r;
+    const u64 sample = gid / (u64)rm.per, t = gid % (u64)rm.per;
+    const u64 tb = deposit(t, mask, n);
+    const float2* src = state + (sample << n);
+    float4 o = make_float4(0.f, 0.f, 0.f, 0.f);
+    if ((k & mask) == 0) { const float2 v = src[k | tb]; o.x = v.x; o.y = v.y; }
+    if (((k + 1) & mask) == 0) { const float2 v = src[(k + 1) | tb]; o.z = v.x; o.w = v.y; }
+    *reinterpret_cast<float4*>(work + e2) = o;
+}
+
+// out[b] = sum over the per outcomes of Frow[b * per + t], in order.
+__global__ __launch_bounds__(256) void k_reset_sum(const double* Frow, u64 per, u64 B, float* out) {
+    const u64 b = (u64)blockIdx.x * 256 + threadIdx.x;
+    if (b >= B) return;
+    double acc = 0.0;
+    for (u64 t = 0; t < per; ++t) acc += Frow[b * per + t];
+    out[b] = (float)acc;
+}
+
+// Finite-shot estimate of <Z_q>: one wavefront per (row, qubit); samples < 0 (no valid outcome) are skipped.
+__global__ __launch_bounds__(256) void k_shot_expz(const long long* samples, u64 shots, u64 rows, int n,
+                                                   float* out) {
+    const u64 job = (u64)blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (job >= rows * n) return;
+    const int lane = threadIdx.x & 63;
+    const u64 row = job / n;
+    const int q = (int)(job % n);
+    const long long* s = samples + row * shots;
+    double acc = 0.0, cnt = 0.0;
+    for (u64 i = lane; i < shots; i += 64) {
+        const long long v = s[i];
+        if (v >= 0) { acc += ((v >> q) & 1) ? -1.0 : 1.0; cnt += 1.0; }
+    }
+    acc = wave_sum(acc);
+    cnt = wave_sum(cnt);
+    if (lane == 0) out[job] = cnt > 0.0 ? (float)(acc / cnt) : 0.f;
 }
 
 // ------------------------------------------------------------------------------------------
@@ -1505,15 +1555,35 @@ hipError_t launch_project(float2* state, int64_t rows, int n, uint64_t mask, con
 }
 
 hipError_t launch_fidelity_block(const float2* state, int64_t rows, int n, const float* x, int64_t dim,
-                                 double* partial, int nblk, hipStream_t st) {
+                                 double* partial, int nblk, const RowMap& rm, hipStream_t st) {
     hipLaunchKernelGGL(k_fidelity_block, dim3(nblk, (unsigned)rows), dim3(256), 0, st, state, n, x,
-                       (u64)dim, nblk, partial);
+                       (u64)dim, nblk, rm, partial);
     return hipGetLastError();
 }
 
-hipError_t launch_fidelity_finish(const double* partial, int nblk, int64_t rows, float* out,
+hipError_t launch_fidelity_finish(const double* partial, int nblk, int64_t rows, float* out, double* out_d,
                                   hipStream_t st) {
-    hipLaunchKernelGGL(k_fidelity_finish, dim3((unsigned)rows), dim3(256), 0, st, partial, nblk, out);
+    hipLaunchKernelGGL(k_fidelity_finish, dim3((unsigned)rows), dim3(256), 0, st, partial, nblk, out, out_d);
+    return hipGetLastError();
+}
+
+hipError_t launch_reset_rows(const float2* state, int n, uint64_t mask, int64_t rows, const RowMap& rm,
+                             float2* work, hipStream_t st) {
+    const u64 total = (u64)rows << n;
+    hipLaunchKernelGGL(k_reset_rows, dim3(blocks_for(total / 2, 256)), dim3(256), 0, st, state, n, (u64)mask,
+                       total, rm, work);
+    return hipGetLastError();
+}
+
+hipError_t launch_reset_sum(const double* Frow, int64_t per, int64_t B, float* out, hipStream_t st) {
+    hipLaunchKernelGGL(k_reset_sum, dim3(blocks_for((u64)B, 256)), dim3(256), 0, st, Frow, (u64)per, (u64)B, out);
+    return hipGetLastError();
+}
+
+hipError_t launch_shot_expz(const long long* samples, int64_t shots, int64_t rows, int n, float* out,
+                            hipStream_t st) {
+    hipLaunchKernelGGL(k_shot_expz, dim3(blocks_for((u64)rows * n, 4)), dim3(256), 0, st, samples, (u64)shots,
+                       (u64)rows, n, out);
     return hipGetLastError();
 }
 

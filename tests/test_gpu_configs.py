@@ -253,3 +253,28 @@ def test_config1_training_step(oracle):
     assert np.linalg.norm(gg[rows] - gref) <= 1e-3 * np.linalg.norm(gref)
     assert np.abs(mg.cpu().numpy() - gg.astype(np.float64).mean(0)).max() <= 1e-6
     ctx.close()
+
+
+def test_config3_true_reset_fidelity_sampled(oracle):
+    """Config 3 with a real reset of the four trash qubits (16 decoder runs per sample); the oracle
+    recomputes two samples from the GPU's encoder output."""
+    torch = gu.torch_cuda()
+    w = wl.config(3)
+    n, B = w.n, w.batch
+    circ = qb.circuit_from_spec(w.circuit)
+    ctx = gu.make_ctx(n, B, ws_bytes=qb.qsv_grad_workspace_bytes(n, B, circ))
+    xd, pd = gu.dev(w.x), gu.dev(w.params)
+    ctx.qsv_amp_encode(xd)
+    ctx.qsv_apply_layers(circ, pd, None, 0)
+    F = torch.zeros(B, dtype=torch.float32, device="cuda")
+    ctx.qsv_reset_fidelity(circ, pd, None, w.trash_mask, xd, F)
+    p0 = gu.measure(ctx, qb.QSV_M_MARGINAL, (B, 16), mask=w.trash_mask)[:, 0]
+    Fg = F.cpu().numpy()
+    rows = [3, 20]
+    enc = gu.state_np(ctx)[rows]
+    want = oracle.reset_fidelity(np.ascontiguousarray(enc), ocirc(oracle, w.circuit), w.params, None,
+                                 w.trash_mask, w.x[rows])
+    assert np.abs(Fg[rows] - want).max() <= 1e-5
+    # the t = 0 term alone is P0^2 (projection without renormalising), so F >= P0^2
+    assert np.all(Fg >= p0.astype(np.float64) ** 2 - 1e-5) and np.all(Fg <= 1 + 1e-5)
+    ctx.close()

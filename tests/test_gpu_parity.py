@@ -296,6 +296,64 @@ def test_pauli_strings(oracle, n, B):
     ctx.close()
 
 
+# ------------------------------------------------------------------ trash reset, finite shots
+@pytest.mark.parametrize("n,B,mask,ent,reup,chunk", [
+    (3, 4, 0b100, RING, 0, 0), (5, 3, 0b11000, LADDER, 0, 0), (6, 5, 0b100010, RING, 1, 3),
+    (10, 3, 0b1100000000, RING, 0, 0), (12, 2, 0b110000000001, RING, 0, 5), (13, 2, 0b1000000000000, LADDER, 0, 0)])
+def test_reset_fidelity(oracle, n, B, mask, ent, reup, chunk):
+    torch = gu.torch_cuda()
+    g = rng(160 + n)
+    spec = wl.CircuitSpec(2, (RY, RZ), ent, reup)
+    params = wl.draw_params(spec, n, 161 + n)
+    x = g.standard_normal((B, 1 << n)).astype(np.float32)
+    feats = g.standard_normal((B, n)).astype(np.float32) if reup else None
+    ctx = gu.make_ctx(n, B)
+    if chunk:
+        ctx.qsv_set_option("grad_chunk_rows", chunk)
+    circ = qb.circuit_from_spec(spec)
+    xd, pd = gu.dev(x), gu.dev(params)
+    fd = gu.dev(feats) if reup else None
+    ctx.qsv_amp_encode(xd)
+    ctx.qsv_apply_layers(circ, pd, fd, 0)
+    before = ctx.state.clone()
+    out = torch.zeros(B, dtype=torch.float32, device="cuda")
+    ctx.qsv_reset_fidelity(circ, pd, fd, mask, xd, out)
+    torch.cuda.synchronize()
+    ref, _ = oracle.amp_encode(x, n)
+    oracle.apply_layers(ref, ocirc(oracle, spec), params, feats)
+    want = oracle.reset_fidelity(ref, ocirc(oracle, spec), params, feats, mask, x)
+    assert np.abs(out.cpu().numpy() - want).max() <= 1e-5
+    assert torch.equal(ctx.state, before)
+    # the post-selected, unnormalised fidelity is the t = 0 term: never larger
+    p0 = gu.measure(ctx, qb.QSV_M_PROJECT_ZERO, (B,), mask=mask, renormalise=0)
+    ctx.qsv_apply_layers(circ, pd, fd, 1)
+    F0 = gu.measure(ctx, qb.QSV_M_FIDELITY, (B,), x=xd)
+    assert np.all(out.cpu().numpy() >= F0 - 1e-5)
+    ctx.close()
+
+
+def test_shot_expz(oracle):
+    torch = gu.torch_cuda()
+    n, B, shots = 9, 3, 5000
+    g = rng(170)
+    ctx = gu.make_ctx(n, B)
+    x = g.standard_normal((B, 1 << n)).astype(np.float32)
+    x[2] = 0.0                                          # zero state: every sample is -1
+    ctx.qsv_amp_encode(gu.dev(x))
+    u = g.random((B, shots))
+    s = torch.zeros((B, shots), dtype=torch.int64, device="cuda")
+    ctx.qsv_measure(qb.QSV_M_SAMPLE, s, uniforms=gu.dev(u))
+    z = torch.zeros((B, n), dtype=torch.float32, device="cuda")
+    ctx.qsv_shot_expz(s, z)
+    torch.cuda.synchronize()
+    want = oracle.shot_expz(s.cpu().numpy(), n)
+    assert np.abs(z.cpu().numpy() - want).max() <= 1e-6
+    assert np.all(z.cpu().numpy()[2] == 0)
+    exact = gu.measure(ctx, qb.QSV_M_EXPZ_ALL, (B, n))
+    assert np.abs(z.cpu().numpy()[:2] - exact[:2]).max() <= 5 / np.sqrt(shots)     # statistical
+    ctx.close()
+
+
 # ------------------------------------------------------------------ training losses, optimiser steps
 @pytest.mark.parametrize("n,B,L,rot,ent,reup", [
     (1, 3, 2, (RY, RZ), RING, 0), (3, 4, 2, (RY, RZ), LADDER, 0), (5, 3, 2, (RX, RY, RZ), RING, 0),
