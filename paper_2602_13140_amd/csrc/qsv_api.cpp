@@ -296,12 +296,12 @@ qsv_status run_circuit(qsv_ctx* ctx, const qsv_circuit& c, const Prepared& pr, f
         a.zout = (last && z_in_pass) ? zs->zpart : nullptr;
         a.zq = zs ? zs->q : 0;
         a.nostore = a.zout ? 1 : 0;
-        a.nt_store = ctx->opt_nt_store >= 0 ? ctx->opt_nt_store : (a.total * 8 >= kNtStoreBytes ? 1 : 0);
         a.ops = dev_ops + ps.op_begin;
         a.mats = mats;
         a.exec_of = reinterpret_cast<const int*>(ctx->ws + cp->execof_off);
         a.ovr = ovr;
         a.total = (uint64_t)rows << n;
+        a.nt_store = ctx->opt_nt_store >= 0 ? ctx->opt_nt_store : (a.total * 8 >= kNtStoreBytes ? 1 : 0);
         a.n = n; a.c = ps.c; a.w = ps.w;
         a.n_mats = n_mats;
         a.rowdep = c.reupload;
