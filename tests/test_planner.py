@@ -201,3 +201,44 @@ def test_bad_descriptors_are_rejected():
     assert qb.qsv_workspace_bytes(0, 1) == 0 and qb.qsv_workspace_bytes(4, 0) == 0
     with pytest.raises(ValueError):
         qb.qsv_plan_describe(qb.make_circuit(1, [RX], RING), 4, 1, 0, 9)
+
+
+def _random_cases(count, seed):
+    g = np.random.Generator(np.random.PCG64(seed))
+    rots = [(RX,), (RY,), (RZ,), (RY, RZ), (RZ, RX), (RX, RY, RZ), (RZ, RY, RX), ()]
+    out = []
+    for _ in range(count):
+        n = int(g.integers(4, 15))
+        rows = int(g.integers(1, 6)) if n <= 11 else 1
+        L = int(g.integers(1, 5))
+        rot = rots[int(g.integers(0, len(rots)))]
+        ent = int(g.integers(0, 3))
+        reup = int(g.integers(0, 2))
+        if not rot and not reup and ent == NONE:
+            ent = RING
+        tile = int(g.choice([0, 10, 11, 12, 13]))
+        out.append((n, rows, L, rot, ent, reup, tile, int(g.integers(0, 2))))
+    return out
+
+
+@pytest.mark.parametrize("n,rows,L,rot,ent,reup,tile,inverse", _random_cases(60, 4242))
+def test_plan_replay_random_circuits(oracle, n, rows, L, rot, ent, reup, tile, inverse):
+    """Seeded sweep over qubit counts, batch sizes, rotation lists, entanglers, tile sizes and both
+    directions: every plan, replayed operation by operation, must be the oracle's circuit."""
+    g = np.random.Generator(np.random.PCG64(7000 + 31 * n + 7 * L + ent + 2 * reup + inverse + tile))
+    circ = qb.make_circuit(L, list(rot), ent, reup)
+    ocirc = oracle.make_circuit(L, list(rot), ent, reup)
+    P = qb.qsv_num_params(circ, n)
+    params = g.uniform(0, 2 * np.pi, P).astype(np.float32)
+    feats = g.standard_normal((rows, n)).astype(np.float32) if reup else None
+    x = g.standard_normal((rows, 1 << n)).astype(np.float32)
+    ref, _ = oracle.amp_encode(x, n)
+    start = ref.copy()
+    oracle.apply_layers(ref, ocirc, params, feats, inverse=bool(inverse))
+    text = qb.qsv_plan_describe(circ, n, rows, inverse, tile)
+    out, n_gates, _ = replay(text, n, rows, L, rot, ent, reup, params.astype(np.float64),
+                             None if feats is None else feats.astype(np.float64), inverse, start)
+    ent_gates = n if (ent == RING and n >= 2) else (n - 1 if ent == LADDER else 0)
+    per_layer = (n if (reup + len(rot)) else 0) + ent_gates
+    assert n_gates == L * per_layer
+    assert np.allclose(out, ref, atol=1e-12)
