@@ -206,6 +206,48 @@ def test_sampling_special_states():
     ctx.close()
 
 
+def _random_apply_cases(count, seed):
+    g = np.random.Generator(np.random.PCG64(seed))
+    rots = [(RX,), (RY,), (RZ,), (RY, RZ), (RZ, RX), (RX, RY, RZ), (RZ, RY, RX), ()]
+    out = []
+    for _ in range(count):
+        n = int(g.integers(1, 16))
+        B = int(g.integers(1, 9)) if n <= 12 else int(g.integers(1, 3))
+        L = int(g.integers(1, 5))
+        rot = rots[int(g.integers(0, len(rots)))]
+        ent = int(g.integers(0, 3))
+        reup = int(g.integers(0, 2))
+        tile = int(g.choice([0, 0, 10, 11, 12, 13]))
+        planes = int(g.choice([0, 1, 2]))
+        out.append((n, B, L, rot, ent, reup, tile, planes))
+    return out
+
+
+@pytest.mark.parametrize("n,B,L,rot,ent,reup,tile,planes", _random_apply_cases(48, 515))
+def test_apply_layers_random(oracle, n, B, L, rot, ent, reup, tile, planes):
+    """Seeded sweep: random sizes, batches, rotation lists, entanglers, tile sizes and LDS modes,
+    forward then inverse, against the oracle."""
+    g = rng(600 + 17 * n + B + L)
+    spec = wl.CircuitSpec(L, tuple(rot), ent, reup)
+    params = wl.draw_params(spec, n, 601 + n + L)
+    x = g.standard_normal((B, 1 << n)).astype(np.float32)
+    feats = g.standard_normal((B, n)).astype(np.float32) if reup else None
+    ctx = gu.make_ctx(n, B, tile=tile, planes=planes)
+    circ = qb.circuit_from_spec(spec)
+    xd, pd = gu.dev(x), gu.dev(params)
+    fd = gu.dev(feats) if reup else None
+    ref, _ = oracle.amp_encode(x, n)
+    oracle.apply_layers(ref, ocirc(oracle, spec), params, feats)
+    ctx.qsv_amp_encode(xd)
+    ctx.qsv_apply_layers(circ, pd, fd, 0)
+    got = gu.state_np(ctx)
+    assert np.abs(got - ref).max() <= amp_tol(n)
+    ctx.qsv_apply_layers(circ, pd, fd, 1)
+    back, _ = oracle.amp_encode(x, n)
+    assert np.abs(gu.state_np(ctx) - back).max() <= 2 * amp_tol(n)
+    ctx.close()
+
+
 # ------------------------------------------------------------------ parameter-shift gradient
 @pytest.mark.parametrize("n,B,L,rot,ent,reup,obs", [
     (2, 3, 2, (RY, RZ), RING, 0, 1), (4, 5, 2, (RY, RZ), LADDER, 0, 0), (5, 3, 2, (RX, RY, RZ), RING, 0, 2),
