@@ -491,6 +491,51 @@ def test_training_steps_lower_the_loss(oracle):
     ctx.close()
 
 
+# ------------------------------------------------------------------ HIP graph capture
+def test_calls_can_be_captured_in_a_hip_graph_and_replayed(oracle):
+    """After a warm-up (the first call uploads the plan) the calls are plain launches on the
+    context's stream, so a caller may capture them; every replay must equal the eager result, with
+    eager work and synchronisations in between."""
+    torch = gu.torch_cuda()
+    n, B = 6, 16
+    g = rng(180)
+    spec = wl.CircuitSpec(3, (RY, RZ), RING, 1)
+    params = wl.draw_params(spec, n, 181)
+    x = g.standard_normal((B, 1 << n)).astype(np.float32)
+    feats = g.standard_normal((B, n)).astype(np.float32)
+    side = torch.cuda.Stream()
+    with torch.cuda.stream(side):
+        ctx = gu.make_ctx(n, B)                        # binds the side stream
+        circ = qb.circuit_from_spec(spec)
+        xd, pd, fd = gu.dev(x), gu.dev(params), gu.dev(feats)
+        z = torch.zeros((B, n), dtype=torch.float32, device="cuda")
+        p = torch.zeros((B, 1 << n), dtype=torch.float32, device="cuda")
+
+        def step():
+            ctx.qsv_amp_encode(xd)
+            ctx.qsv_apply_layers(circ, pd, fd, 0)
+            ctx.qsv_measure(qb.QSV_M_EXPZ_ALL, z)
+            ctx.qsv_measure(qb.QSV_M_PROBS, p)
+
+        step()
+        side.synchronize()
+        z_eager, p_eager = z.clone(), p.clone()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=side):
+            step()
+        for _ in range(4):
+            z.zero_(); p.zero_()
+            ctx.qsv_apply_layers(circ, pd, fd, 1)      # eager work between the replays
+            side.synchronize()
+            graph.replay()
+            side.synchronize()
+            assert torch.equal(z, z_eager) and torch.equal(p, p_eager)
+        ref, _ = oracle.amp_encode(x, n)
+        oracle.apply_layers(ref, ocirc(oracle, spec), params, feats)
+        assert np.abs(z.cpu().numpy() - oracle.expz_all(ref)).max() <= 1e-5
+        ctx.close()
+
+
 # ------------------------------------------------------------------ error paths (host-detected)
 def test_argument_errors():
     torch = gu.torch_cuda()
