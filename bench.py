@@ -243,6 +243,21 @@ def bench_c2(torch, qb, wl, args):
 
     ms_adj, _ = run_steps(torch, step_adj, max(steps, 5), 1)
     ctx.close()
+
+    # The other reading of "about 480 parameters": three rotations (RX, RY, RZ) per qubit and layer.
+    spec3 = wl.CircuitSpec(L, (wl.RX, wl.RY, wl.RZ), w.circuit.entangler)
+    P3 = spec3.num_params(n)
+    circ3 = qb.circuit_from_spec(spec3)
+    ctx3 = qb.Context(n, B, ws_bytes=qb.qsv_grad_workspace_bytes(n, B, circ3))
+    p3d = torch.from_numpy(wl.draw_params(spec3, n, 2002)).cuda()
+    grad3 = torch.empty((B, P3), dtype=torch.float32, device="cuda")
+    mg3 = torch.empty(P3, dtype=torch.float32, device="cuda")
+    ms3, _ = run_steps(torch, lambda tm: ctx3.qsv_param_shift_grad(circ3, xd, p3d, None, 0, loss, grad3, None, mg3),
+                       1, 1)
+    ms3_adj, _ = run_steps(torch, lambda tm: ctx3.qsv_adjoint_grad(circ3, xd, p3d, None, 0, loss, grad3, None, mg3),
+                           max(steps, 5), 1)
+    ctx3.close()
+    updates3 = wl.nominal_updates(spec3, n, B * (2 * P3 + 1))
     return {"workload": "c2: 16 qubits, batch 256, 10 layers RY,RZ + CZ ladder, full parameter-shift gradient",
             "method": "layer by layer from kept states: a circuit that shifts a parameter of layer l runs layers l..L-1",
             "ms_per_step": ms, "steps": steps, "circuits": circuits, "params": P, "updates": updates,
@@ -252,7 +267,10 @@ def bench_c2(torch, qb, wl, args):
                                "executed_updates_per_s": updates / (ms_whole * 1e-3)},
             "adjoint": {"method": "qsv_adjoint_grad: same loss and gradient in reverse mode (one forward run, "
                                   "psi and lambda taken back layer by layer, 2x2 transition sums per qubit)",
-                        "ms_per_step": ms_adj, "speedup_over_shift_rule": ms / ms_adj}}
+                        "ms_per_step": ms_adj, "speedup_over_shift_rule": ms / ms_adj},
+            "three_rotations": {"workload": "same with RX,RY,RZ per layer: 480 parameters", "params": P3,
+                                "circuits": B * (2 * P3 + 1), "updates": updates3, "ms_per_step": ms3,
+                                "updates_per_s": updates3 / (ms3 * 1e-3), "adjoint_ms_per_step": ms3_adj}}
 
 
 def bench_c1(torch, qb, wl, args):
