@@ -1205,71 +1205,165 @@ __global__ __launch_bounds__(256) void k_trans_block(const float2* S, int n, u64
     }
 }
 
-// The same sums for n >= 12, several qubits per read of the two states.  A workgroup stages a tile of
-// 2^12 amplitudes of psi and of lambda in LDS (tile = the c lowest index bits plus 12 - c bits from
-// bit w, as in the pass kernel), and every thread then walks over its 8 index pairs for each of the
-// tile bits j0..11, i.e. for up to NJ qubits at once.  A workgroup covers `per_group` consecutive
-// tiles of one row pair before it reduces its accumulators, so the reduction is amortised.
+// The same sums for n >= 12, several qubits per read of the two states.  A workgroup takes a tile of
+// 2^12 amplitudes of psi and of lambda (tile = the c lowest index bits plus 12 - c bits from bit w,
+// as in the pass kernel).  The index pairs of a qubit are formed in registers: a lane holds, of each
+// state, a run of amplitudes that differ in a few tile bits.  Tile bits 8..11 are the run of the 16
+// amplitudes a lane loads from memory (coalesced); for the lower bits the tile goes to LDS once
+// (element tau at tau ^ ((tau >> 4) & 15): every access pattern below then spreads 16 consecutive
+// lanes over all banks) and is read back with the run at bits 4..7 and at bits 0..3.
+// Arithmetic per amplitude and qubit: the products d = conj(lambda[k]) psi[k] do not depend on the
+// qubit, M00 sums them over the indices with the bit clear, and M00 + M11 = sum of all d is the same
+// for every qubit, so it is kept once (tsum) and M11 comes out as a difference at the end; M01 and
+// M10 take 8 FMAs per pair each.
+// Only tile bits >= J0 are wanted (J0 = 0 for contiguous tiles, 4..11 for tiles with a window).  A
+// workgroup covers `per_group` consecutive tiles of one row pair before it reduces its accumulators,
+// so the reduction is amortised.
 // partial: [(pair * n + qubit) * nblk + group * 4 + wavefront][8] (nblk = 4 * groups), the layout
 // k_adj_layer reads.
-template <int NJ>
-__global__ __launch_bounds__(256) void k_trans_tile(const float2* S, int n, int c, int w, int j0,
-                                                    int per_group, int nblk, double* partial) {
+// A pointer to global memory that is the same in every lane, moved to scalar registers so that loads
+// through it take the scalar-base + 32-bit lane offset form (no 64-bit address per lane).
+typedef const __attribute__((address_space(1))) char* global_bytes;
+__device__ __forceinline__ global_bytes uniform_ptr(const void* p) {
+    const u64 v = (u64)p;
+    const unsigned lo = __builtin_amdgcn_readfirstlane((unsigned)v);
+    const unsigned hi = __builtin_amdgcn_readfirstlane((unsigned)(v >> 32));
+    return (global_bytes)(((u64)hi << 32) | lo);
+}
+__device__ __forceinline__ float2 load_f2(global_bytes base, unsigned byte_offset) {
+    const f32x2 v = *(const __attribute__((address_space(1))) f32x2*)(base + byte_offset);
+    return make_float2(v.x, v.y);
+}
+
+template <int N>
+__device__ __forceinline__ void trans_diag(const float2 (&s)[N], const float2 (&l)[N], float2 (&d)[N],
+                                           float (&tsum)[2]) {
+#pragma unroll
+    for (int i = 0; i < N; ++i) {
+        d[i].x = fmaf(l[i].y, s[i].y, l[i].x * s[i].x);
+        d[i].y = fmaf(-l[i].y, s[i].x, l[i].x * s[i].y);
+        tsum[0] += d[i].x;
+        tsum[1] += d[i].y;
+    }
+}
+
+// acc: re, im of M00, M01, M10 of the qubit behind run bit BIT
+template <int N, int BIT>
+__device__ __forceinline__ void trans_acc(const float2 (&s)[N], const float2 (&l)[N], const float2 (&d)[N],
+                                          float (&acc)[6]) {
+#pragma unroll
+    for (int i = 0; i < N; ++i) {
+        if (i & (1 << BIT)) continue;
+        constexpr int B = 1 << BIT;
+        acc[0] += d[i].x;
+        acc[1] += d[i].y;
+        acc[2] = fmaf(l[i].y, s[i | B].y, fmaf(l[i].x, s[i | B].x, acc[2]));
+        acc[3] = fmaf(-l[i].y, s[i | B].x, fmaf(l[i].x, s[i | B].y, acc[3]));
+        acc[4] = fmaf(l[i | B].y, s[i].y, fmaf(l[i | B].x, s[i].x, acc[4]));
+        acc[5] = fmaf(-l[i | B].y, s[i].x, fmaf(l[i | B].x, s[i].y, acc[5]));
+    }
+}
+
+template <int J0>
+__global__ __launch_bounds__(256, 2) void k_trans_tile(const float2* S, int n, int c, int w,
+                                                       int per_group, int nblk, double* partial) {
     __shared__ float2 ps[4096];
     __shared__ float2 lm[4096];                      // 64 KiB in all
+    constexpr int NJ = 12 - J0;                      // acc[a] belongs to tile bit J0 + a
     const u64 r = blockIdx.y;
     const float2* psi = S + ((2 * r) << n);
     const float2* lam = S + ((2 * r + 1) << n);
     const unsigned t = threadIdx.x;
     const unsigned cmask = (1u << c) - 1u;
     const int wc = w - c;
-    float acc[NJ][8];
+    float acc[NJ][6];
+    float tsum[2] = {0.f, 0.f};
 #pragma unroll
     for (int a = 0; a < NJ; ++a)
 #pragma unroll
-        for (int b = 0; b < 8; ++b) acc[a][b] = 0.f;
-    for (int g = 0; g < per_group; ++g) {
+        for (int b = 0; b < 6; ++b) acc[a][b] = 0.f;
+    const unsigned tc = t ^ ((t >> 4) & 15u);        // swizzled lane part of the layout loaded from memory
+    float2 s[16], l[16];                             // tau = i * 256 + t: the run is tile bits 8..11
+    // tau = i * 256 + t sits at index base | (tau & cmask) | (tau >> c) << w = base + i * stride + kt, both
+    // for contiguous tiles (c = 12) and for c = 4 (tau >> 4 = i * 16 + (t >> 4)); base + i * stride is the
+    // same for all lanes (scalar registers), kt a 32-bit lane offset
+    const u64 stride = c == 12 ? 256ull : (16ull << w);
+    const unsigned kt8 = ((t & cmask) | ((t >> c) << w)) * 8u;   // in bytes: below 2^(n-1)
+    auto load_tile = [&](int g) {
         const u64 tb = (u64)blockIdx.x * per_group + g;      // tile of the row
         const u64 base = ((tb & ((1ull << wc) - 1ull)) << c) | ((tb >> wc) << (w + 12 - c));
-        if (g) __syncthreads();
 #pragma unroll
         for (int i = 0; i < 16; ++i) {
-            const unsigned tau = (unsigned)i * 256u + t;
-            const u64 k = base | (u64)(tau & cmask) | ((u64)(tau >> c) << w);
-            ps[tau] = psi[k];
-            lm[tau] = lam[k];
+            s[i] = load_f2(uniform_ptr(psi + (base + (u64)i * stride)), kt8);
+            l[i] = load_f2(uniform_ptr(lam + (base + (u64)i * stride)), kt8);
         }
-        __syncthreads();
+    };
+    for (int g = 0; g < per_group; ++g) {
+        load_tile(g);
+        {
+            float2 d[16];
+            trans_diag<16>(s, l, d, tsum);
+            if constexpr (J0 <= 8) trans_acc<16, 0>(s, l, d, acc[J0 <= 8 ? 8 - J0 : 0]);
+            if constexpr (J0 <= 9) trans_acc<16, 1>(s, l, d, acc[J0 <= 9 ? 9 - J0 : 0]);
+            if constexpr (J0 <= 10) trans_acc<16, 2>(s, l, d, acc[J0 <= 10 ? 10 - J0 : 0]);
+            trans_acc<16, 3>(s, l, d, acc[11 - J0]);
+        }
+        if constexpr (J0 < 8) {
+            if (g) __syncthreads();                  // the previous tile has been read by everyone
 #pragma unroll
-        for (int a = 0; a < NJ; ++a) {
-            const int j = j0 + a;
-            if (j < 12) {
-                const unsigned low = (1u << j) - 1u;
-#pragma unroll 2
-                for (int i = 0; i < 8; ++i) {
-                    const unsigned p = (unsigned)i * 256u + t;
-                    const unsigned k0 = ((p >> j) << (j + 1)) | (p & low);
-                    const unsigned k1 = k0 | (1u << j);
-                    const float2 l0 = lm[k0], l1 = lm[k1], s0 = ps[k0], s1 = ps[k1];
-                    acc[a][0] += l0.x * s0.x + l0.y * s0.y; acc[a][1] += l0.x * s0.y - l0.y * s0.x;
-                    acc[a][2] += l0.x * s1.x + l0.y * s1.y; acc[a][3] += l0.x * s1.y - l0.y * s1.x;
-                    acc[a][4] += l1.x * s0.x + l1.y * s0.y; acc[a][5] += l1.x * s0.y - l1.y * s0.x;
-                    acc[a][6] += l1.x * s1.x + l1.y * s1.y; acc[a][7] += l1.x * s1.y - l1.y * s1.x;
+            for (int i = 0; i < 16; ++i) {
+                ps[(unsigned)i * 256u + tc] = s[i];
+                lm[(unsigned)i * 256u + tc] = l[i];
+            }
+            __syncthreads();
+            float unused[2] = {0.f, 0.f};            // tsum has counted every amplitude already
+            {
+                // registers = tile bits 4..7: tau = (t >> 4) * 256 + i * 16 + (t & 15)
+#pragma unroll
+                for (int i = 0; i < 16; ++i) {
+                    const unsigned a = (t >> 4) * 256u + (unsigned)i * 16u + ((t & 15u) ^ (unsigned)i);
+                    s[i] = ps[a];
+                    l[i] = lm[a];
                 }
+                float2 d[16];
+                trans_diag<16>(s, l, d, unused);
+                if constexpr (J0 <= 4) trans_acc<16, 0>(s, l, d, acc[J0 <= 4 ? 4 - J0 : 0]);
+                if constexpr (J0 <= 5) trans_acc<16, 1>(s, l, d, acc[J0 <= 5 ? 5 - J0 : 0]);
+                if constexpr (J0 <= 6) trans_acc<16, 2>(s, l, d, acc[J0 <= 6 ? 6 - J0 : 0]);
+                trans_acc<16, 3>(s, l, d, acc[J0 <= 7 ? 7 - J0 : 0]);
+            }
+            if constexpr (J0 == 0) {
+                // registers = tile bits 0..3: tau = t * 16 + i
+#pragma unroll
+                for (int i = 0; i < 16; ++i) {
+                    const unsigned a = t * 16u + ((unsigned)i ^ (t & 15u));
+                    s[i] = ps[a];
+                    l[i] = lm[a];
+                }
+                float2 d[16];
+                trans_diag<16>(s, l, d, unused);
+                trans_acc<16, 0>(s, l, d, acc[0]);
+                trans_acc<16, 1>(s, l, d, acc[1]);
+                trans_acc<16, 2>(s, l, d, acc[2]);
+                trans_acc<16, 3>(s, l, d, acc[3]);
             }
         }
     }
     // every wavefront writes its own partial: index (group, wavefront)
+    const double t0 = wave_sum((double)tsum[0]), t1 = wave_sum((double)tsum[1]);
 #pragma unroll
     for (int a = 0; a < NJ; ++a) {
-        const int j = j0 + a;
-        if (j >= 12) break;
+        const int j = J0 + a;
         const int q = j < c ? j : j - c + w;                 // the qubit behind tile bit j
         double* out = partial + ((r * n + q) * (u64)nblk + (u64)blockIdx.x * 4 + (t >> 6)) * 8;
+        double tot[6];
 #pragma unroll
-        for (int b = 0; b < 8; ++b) {
-            const double tot = wave_sum((double)acc[a][b]);
-            if ((t & 63u) == 0) out[b] = tot;
+        for (int b = 0; b < 6; ++b) tot[b] = wave_sum((double)acc[a][b]);
+        if ((t & 63u) == 0) {
+#pragma unroll
+            for (int b = 0; b < 6; ++b) out[b] = tot[b];
+            out[6] = t0 - tot[0];
+            out[7] = t1 - tot[1];
         }
     }
 }
@@ -1686,13 +1780,19 @@ hipError_t launch_adj_layer(const float2* S, int n, int64_t row_pairs, double* p
         nblk = adj_trans_blocks(n);                      // one partial per wavefront of a group
         const int per_group = trans_tiles_per_group(n);
         const dim3 grid(groups, (unsigned)row_pairs);
-        hipLaunchKernelGGL((k_trans_tile<12>), grid, dim3(256), 0, st, S, n, 12, 12, 0, per_group, nblk, partial);
+        hipLaunchKernelGGL((k_trans_tile<0>), grid, dim3(256), 0, st, S, n, 12, 12, per_group, nblk, partial);
         hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
         for (int done = 12; done < n;) {
             int w = done, j0 = 4;
             if (w + 8 > n) { w = n - 8; j0 = 4 + (done - w); }
-            hipLaunchKernelGGL((k_trans_tile<8>), grid, dim3(256), 0, st, S, n, 4, w, j0, per_group, nblk, partial);
+            switch (j0) {
+#define QSV_TRANS_CASE(J) case J: hipLaunchKernelGGL((k_trans_tile<J>), grid, dim3(256), 0, st, S, n, 4, w, per_group, nblk, partial); break;
+                QSV_TRANS_CASE(4) QSV_TRANS_CASE(5) QSV_TRANS_CASE(6) QSV_TRANS_CASE(7) QSV_TRANS_CASE(8)
+                QSV_TRANS_CASE(9) QSV_TRANS_CASE(10) QSV_TRANS_CASE(11)
+#undef QSV_TRANS_CASE
+                default: return hipErrorInvalidValue;
+            }
             e = hipGetLastError();
             if (e != hipSuccess) return e;
             done = w + 8;
