@@ -1205,22 +1205,19 @@ __global__ __launch_bounds__(256) void k_trans_block(const float2* S, int n, u64
     }
 }
 
-// The same sums for n >= 12, several qubits per read of the two states.  A workgroup takes a tile of
+// The same sums for n >= 12, several qubits per read of the two states: a workgroup takes a tile of
 // 2^12 amplitudes of psi and of lambda (tile = the c lowest index bits plus 12 - c bits from bit w,
-// as in the pass kernel).  The index pairs of a qubit are formed in registers: a lane holds, of each
-// state, a run of amplitudes that differ in a few tile bits.  Tile bits 8..11 are the run of the 16
-// amplitudes a lane loads from memory (coalesced); for the lower bits the tile goes to LDS once
-// (element tau at tau ^ ((tau >> 4) & 15): every access pattern below then spreads 16 consecutive
-// lanes over all banks) and is read back with the run at bits 4..7 and at bits 0..3.
+// as in the pass kernel) and forms the index pairs of a qubit in registers: a lane holds, of each
+// state, a run of amplitudes that differ in a few tile bits.
 // Arithmetic per amplitude and qubit: the products d = conj(lambda[k]) psi[k] do not depend on the
 // qubit, M00 sums them over the indices with the bit clear, and M00 + M11 = sum of all d is the same
 // for every qubit, so it is kept once (tsum) and M11 comes out as a difference at the end; M01 and
 // M10 take 8 FMAs per pair each.
-// Only tile bits >= J0 are wanted (J0 = 0 for contiguous tiles, 4..11 for tiles with a window).  A
-// workgroup covers `per_group` consecutive tiles of one row pair before it reduces its accumulators,
-// so the reduction is amortised.
+// A workgroup covers `per_group` consecutive tiles of one row pair before it reduces its
+// accumulators, so the reduction is amortised.
 // partial: [(pair * n + qubit) * nblk + group * 4 + wavefront][8] (nblk = 4 * groups), the layout
-// k_adj_layer reads.
+// k_trans_finish and k_adj_layer read.
+
 // A pointer to global memory that is the same in every lane, moved to scalar registers so that loads
 // through it take the scalar-base + 32-bit lane offset form (no 64-bit address per lane).
 typedef const __attribute__((address_space(1))) char* global_bytes;
@@ -1264,11 +1261,13 @@ __device__ __forceinline__ void trans_acc(const float2 (&s)[N], const float2 (&l
     }
 }
 
+// Tile bits J0..11, J0 >= 8 (a window of which only the top bits are still wanted): they are the run
+// of the 16 amplitudes a lane loads from memory (tau = i * 256 + lane index, coalesced), so nothing
+// goes through LDS.
 template <int J0>
-__global__ __launch_bounds__(256, 2) void k_trans_tile(const float2* S, int n, int c, int w,
-                                                       int per_group, int nblk, double* partial) {
-    __shared__ float2 ps[4096];
-    __shared__ float2 lm[4096];                      // 64 KiB in all
+__global__ __launch_bounds__(256) void k_trans_tile(const float2* S, int n, int c, int w,
+                                                    int per_group, int nblk, double* partial) {
+    static_assert(J0 >= 8 && J0 < 12, "lower tile bits are served by k_trans_wave");
     constexpr int NJ = 12 - J0;                      // acc[a] belongs to tile bit J0 + a
     const u64 r = blockIdx.y;
     const float2* psi = S + ((2 * r) << n);
@@ -1282,72 +1281,25 @@ __global__ __launch_bounds__(256, 2) void k_trans_tile(const float2* S, int n, i
     for (int a = 0; a < NJ; ++a)
 #pragma unroll
         for (int b = 0; b < 6; ++b) acc[a][b] = 0.f;
-    const unsigned tc = t ^ ((t >> 4) & 15u);        // swizzled lane part of the layout loaded from memory
-    float2 s[16], l[16];                             // tau = i * 256 + t: the run is tile bits 8..11
     // tau = i * 256 + t sits at index base | (tau & cmask) | (tau >> c) << w = base + i * stride + kt, both
     // for contiguous tiles (c = 12) and for c = 4 (tau >> 4 = i * 16 + (t >> 4)); base + i * stride is the
     // same for all lanes (scalar registers), kt a 32-bit lane offset
     const u64 stride = c == 12 ? 256ull : (16ull << w);
     const unsigned kt8 = ((t & cmask) | ((t >> c) << w)) * 8u;   // in bytes: below 2^(n-1)
-    auto load_tile = [&](int g) {
+    for (int g = 0; g < per_group; ++g) {
         const u64 tb = (u64)blockIdx.x * per_group + g;      // tile of the row
         const u64 base = ((tb & ((1ull << wc) - 1ull)) << c) | ((tb >> wc) << (w + 12 - c));
+        float2 s[16], l[16], d[16];
 #pragma unroll
         for (int i = 0; i < 16; ++i) {
             s[i] = load_f2(uniform_ptr(psi + (base + (u64)i * stride)), kt8);
             l[i] = load_f2(uniform_ptr(lam + (base + (u64)i * stride)), kt8);
         }
-    };
-    for (int g = 0; g < per_group; ++g) {
-        load_tile(g);
-        {
-            float2 d[16];
-            trans_diag<16>(s, l, d, tsum);
-            if constexpr (J0 <= 8) trans_acc<16, 0>(s, l, d, acc[J0 <= 8 ? 8 - J0 : 0]);
-            if constexpr (J0 <= 9) trans_acc<16, 1>(s, l, d, acc[J0 <= 9 ? 9 - J0 : 0]);
-            if constexpr (J0 <= 10) trans_acc<16, 2>(s, l, d, acc[J0 <= 10 ? 10 - J0 : 0]);
-            trans_acc<16, 3>(s, l, d, acc[11 - J0]);
-        }
-        if constexpr (J0 < 8) {
-            if (g) __syncthreads();                  // the previous tile has been read by everyone
-#pragma unroll
-            for (int i = 0; i < 16; ++i) {
-                ps[(unsigned)i * 256u + tc] = s[i];
-                lm[(unsigned)i * 256u + tc] = l[i];
-            }
-            __syncthreads();
-            float unused[2] = {0.f, 0.f};            // tsum has counted every amplitude already
-            {
-                // registers = tile bits 4..7: tau = (t >> 4) * 256 + i * 16 + (t & 15)
-#pragma unroll
-                for (int i = 0; i < 16; ++i) {
-                    const unsigned a = (t >> 4) * 256u + (unsigned)i * 16u + ((t & 15u) ^ (unsigned)i);
-                    s[i] = ps[a];
-                    l[i] = lm[a];
-                }
-                float2 d[16];
-                trans_diag<16>(s, l, d, unused);
-                if constexpr (J0 <= 4) trans_acc<16, 0>(s, l, d, acc[J0 <= 4 ? 4 - J0 : 0]);
-                if constexpr (J0 <= 5) trans_acc<16, 1>(s, l, d, acc[J0 <= 5 ? 5 - J0 : 0]);
-                if constexpr (J0 <= 6) trans_acc<16, 2>(s, l, d, acc[J0 <= 6 ? 6 - J0 : 0]);
-                trans_acc<16, 3>(s, l, d, acc[J0 <= 7 ? 7 - J0 : 0]);
-            }
-            if constexpr (J0 == 0) {
-                // registers = tile bits 0..3: tau = t * 16 + i
-#pragma unroll
-                for (int i = 0; i < 16; ++i) {
-                    const unsigned a = t * 16u + ((unsigned)i ^ (t & 15u));
-                    s[i] = ps[a];
-                    l[i] = lm[a];
-                }
-                float2 d[16];
-                trans_diag<16>(s, l, d, unused);
-                trans_acc<16, 0>(s, l, d, acc[0]);
-                trans_acc<16, 1>(s, l, d, acc[1]);
-                trans_acc<16, 2>(s, l, d, acc[2]);
-                trans_acc<16, 3>(s, l, d, acc[3]);
-            }
-        }
+        trans_diag<16>(s, l, d, tsum);
+        if constexpr (J0 <= 8) trans_acc<16, 0>(s, l, d, acc[J0 <= 8 ? 8 - J0 : 0]);
+        if constexpr (J0 <= 9) trans_acc<16, 1>(s, l, d, acc[J0 <= 9 ? 9 - J0 : 0]);
+        if constexpr (J0 <= 10) trans_acc<16, 2>(s, l, d, acc[J0 <= 10 ? 10 - J0 : 0]);
+        trans_acc<16, 3>(s, l, d, acc[11 - J0]);
     }
     // every wavefront writes its own partial: index (group, wavefront)
     const double t0 = wave_sum((double)tsum[0]), t1 = wave_sum((double)tsum[1]);
@@ -1364,6 +1316,163 @@ __global__ __launch_bounds__(256, 2) void k_trans_tile(const float2* S, int n, i
             for (int b = 0; b < 6; ++b) out[b] = tot[b];
             out[6] = t0 - tot[0];
             out[7] = t1 - tot[1];
+        }
+    }
+}
+
+// Where the 12 bits of a tile index come from when a wavefront reads the tile from LDS in runs of RB
+// bits starting at tile bit R0: pos[0..RB) = the run, pos[RB..RB+6) = the lane bits, the rest = the
+// step counter h.  The four low lane bits are placed so that, after the swizzle tau ^ ((tau >> 4) & 15),
+// 16 consecutive lanes fall on 16 different 8-byte slots of a 128-byte row: into the free bits of the
+// low nibble, and, for every low-nibble bit p the run occupies, into bit p + 4 (which the swizzle
+// folds onto p).
+template <int RB, int R0>
+struct TransMap {
+    int pos[12];
+    constexpr TransMap() : pos{} {
+        bool used[12] = {};
+        int k = 0;
+        for (int j = 0; j < RB; ++j) { pos[k++] = R0 + j; used[R0 + j] = true; }
+        for (int p = 0; p < 4; ++p)
+            if (!used[p]) { pos[k++] = p; used[p] = true; }
+        for (int j = 0; j < RB; ++j)
+            if (R0 + j < 4) { pos[k++] = R0 + j + 4; used[R0 + j + 4] = true; }
+        for (int p = 0; p < 12; ++p)
+            if (!used[p]) { pos[k++] = p; used[p] = true; }
+    }
+    // bits [first, first + count) of the source list take the low bits of v
+    constexpr unsigned deposit(int first, int count, unsigned v) const {
+        unsigned a = 0;
+        for (int j = 0; j < count; ++j) a |= ((v >> j) & 1u) << pos[first + j];
+        return a;
+    }
+};
+__device__ constexpr unsigned trans_swz(unsigned tau) { return tau ^ ((tau >> 4) & 15u); }
+
+// One wavefront, the whole tile in LDS, the qubits behind tile bits R0..R0+RB-1: 2^(6-RB) steps of one
+// run per lane; the reads of a step are issued before the sums of the step before it.
+template <int RB, int R0>
+__device__ __forceinline__ void trans_wave(const float2* ps, const float2* lm, unsigned lane,
+                                           float (&acc)[RB][6], float (&tsum)[2]) {
+    constexpr TransMap<RB, R0> map{};
+    constexpr int NR = 1 << RB, HB = 6 - RB, NH = 1 << HB;
+    unsigned lp = 0;
+#pragma unroll
+    for (int j = 0; j < 6; ++j) lp |= ((lane >> j) & 1u) << map.pos[RB + j];
+    lp = trans_swz(lp);                              // the swizzle is linear over XOR
+    float2 rs[2][NR], rl[2][NR];
+    auto read_step = [&](int h, float2 (&a)[NR], float2 (&b)[NR]) __attribute__((always_inline)) {
+        unsigned hp = 0;
+#pragma unroll
+        for (int j = 0; j < HB; ++j) hp |= (((unsigned)h >> j) & 1u) << map.pos[RB + 6 + j];
+        const unsigned base = lp ^ trans_swz(hp);
+#pragma unroll
+        for (int i = 0; i < NR; ++i) {
+            const unsigned ip = trans_swz(map.deposit(0, RB, (unsigned)i));
+            a[i] = ps[base ^ ip];
+            b[i] = lm[base ^ ip];
+        }
+    };
+    auto sums = [&](const float2 (&a)[NR], const float2 (&b)[NR]) __attribute__((always_inline)) {
+        float2 d[NR];
+        trans_diag<NR>(a, b, d, tsum);
+        trans_acc<NR, 0>(a, b, d, acc[0]);
+        trans_acc<NR, 1>(a, b, d, acc[1]);
+        if constexpr (RB > 2) trans_acc<NR, 2>(a, b, d, acc[RB > 2 ? 2 : 0]);
+    };
+    read_step(0, rs[0], rl[0]);
+#pragma unroll 1
+    for (int h = 0; h < NH; h += 2) {
+        read_step(h + 1, rs[1], rl[1]);
+        sums(rs[0], rl[0]);
+        if (h + 2 < NH) read_step(h + 2, rs[0], rl[0]);
+        sums(rs[1], rl[1]);
+    }
+}
+
+// The sums for tile bits JB..11 (JB = 0 with RB = 3: contiguous tiles; JB = 4 with RB = 2: tiles with
+// a window), of which bits >= j0 are wanted.  The tile of psi and of lambda goes from memory through
+// registers into LDS (64 KiB); then every wavefront reads the whole tile in runs of its own RB bits
+// (wavefront v: tile bits JB + RB v ...), so a lane carries accumulators for RB qubits only and the
+// loads of the workgroup's next tile stay in flight meanwhile (the loop is rotated for that: load
+// tile g, sums of tile g - 1, tile g into LDS).  Every wavefront sums d over the whole tile, so
+// M11 = tsum - M00 holds per wavefront.  Output layout as k_trans_tile; the wavefronts that do not own
+// a qubit write zeros for it.
+template <int RB>
+__global__ __launch_bounds__(256, 2) void k_trans_wave(const float2* S, int n, int c, int w, int j0,
+                                                       int per_group, int nblk, double* partial) {
+    __shared__ float2 ps[4096];
+    __shared__ float2 lm[4096];                      // 64 KiB in all
+    constexpr int JB = RB == 3 ? 0 : 4;
+    const u64 r = blockIdx.y;
+    const float2* psi = S + ((2 * r) << n);
+    const float2* lam = S + ((2 * r + 1) << n);
+    const unsigned t = threadIdx.x, lane = t & 63u;
+    const int wv = (int)(t >> 6);
+    const unsigned cmask = (1u << c) - 1u;
+    const int wc = w - c;
+    float acc[RB][6];
+    float tsum[2] = {0.f, 0.f};
+#pragma unroll
+    for (int a = 0; a < RB; ++a)
+#pragma unroll
+        for (int b = 0; b < 6; ++b) acc[a][b] = 0.f;
+    const unsigned tc = t ^ ((t >> 4) & 15u);        // swizzled lane part of the layout loaded from memory
+    float2 s[16], l[16];                             // tau = i * 256 + t
+    const u64 stride = c == 12 ? 256ull : (16ull << w);          // addressing as in k_trans_tile
+    const unsigned kt8 = ((t & cmask) | ((t >> c) << w)) * 8u;
+    const bool active = JB + RB * wv + RB - 1 >= j0;             // the wavefront owns a wanted bit
+    for (int g = 0; g <= per_group; ++g) {
+        if (g < per_group) {
+            const u64 tb = (u64)blockIdx.x * per_group + g;      // tile of the row
+            const u64 base = ((tb & ((1ull << wc) - 1ull)) << c) | ((tb >> wc) << (w + 12 - c));
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+                s[i] = load_f2(uniform_ptr(psi + (base + (u64)i * stride)), kt8);
+                l[i] = load_f2(uniform_ptr(lam + (base + (u64)i * stride)), kt8);
+            }
+        }
+        __builtin_amdgcn_sched_barrier(0);
+        if (g > 0 && active) {
+            switch (wv) {
+                case 0: trans_wave<RB, JB>(ps, lm, lane, acc, tsum); break;
+                case 1: trans_wave<RB, JB + RB>(ps, lm, lane, acc, tsum); break;
+                case 2: trans_wave<RB, JB + 2 * RB>(ps, lm, lane, acc, tsum); break;
+                default: trans_wave<RB, JB + 3 * RB>(ps, lm, lane, acc, tsum); break;
+            }
+        }
+        __builtin_amdgcn_sched_barrier(0);
+        if (g < per_group) {
+            if (g) __syncthreads();                  // the previous tile has been read by everyone
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+                ps[(unsigned)i * 256u + tc] = s[i];
+                lm[(unsigned)i * 256u + tc] = l[i];
+            }
+            __syncthreads();
+        }
+    }
+    const double t0 = wave_sum((double)tsum[0]), t1 = wave_sum((double)tsum[1]);
+    double tot[RB][6];
+#pragma unroll
+    for (int a = 0; a < RB; ++a)
+#pragma unroll
+        for (int b = 0; b < 6; ++b) tot[a][b] = wave_sum((double)acc[a][b]);
+    if (lane != 0) return;
+    for (int j = j0 > JB ? j0 : JB; j < 12; ++j) {
+        const int q = j < c ? j : j - c + w;                 // the qubit behind tile bit j
+        double* out = partial + ((r * n + q) * (u64)nblk + (u64)blockIdx.x * 4 + wv) * 8;
+        if ((j - JB) / RB != wv) {
+            for (int b = 0; b < 8; ++b) out[b] = 0.0;
+            continue;
+        }
+#pragma unroll
+        for (int a = 0; a < RB; ++a) {
+            if ((j - JB) % RB != a) continue;
+#pragma unroll
+            for (int b = 0; b < 6; ++b) out[b] = tot[a][b];
+            out[6] = t0 - tot[a][0];
+            out[7] = t1 - tot[a][1];
         }
     }
 }
@@ -1755,11 +1864,12 @@ hipError_t launch_adam(float* p, const float* g, float* m, float* v, int64_t cou
 
 
 
-// Tiles of a row handled by one workgroup of k_trans_tile, and the resulting groups per row.
+// The fewest tiles of a row one workgroup of the tile kernels takes, and the resulting (largest
+// number of) groups per row.
 static inline int trans_tiles_per_group(int n) { const int tiles = 1 << (n - 12); return tiles < 4 ? tiles : 4; }
 static inline int trans_groups(int n) { return (1 << (n - 12)) / trans_tiles_per_group(n); }
 
-// partial entries per (row pair, qubit) of the transition sums
+// upper bound of the partial entries per (row pair, qubit) of the transition sums
 int adj_trans_blocks(int n) { return n < 12 ? 1 : 4 * trans_groups(n); }
 
 hipError_t launch_adj_layer(const float2* S, int n, int64_t row_pairs, double* partial, const CircDev& c,
@@ -1776,11 +1886,16 @@ hipError_t launch_adj_layer(const float2* S, int n, int64_t row_pairs, double* p
     } else {
         // qubits 0..11 from contiguous tiles, then 8 more per read from tiles whose window sits higher
         // (the last window ends at bit n and only its not yet covered qubits are taken)
-        const int groups = trans_groups(n);
-        nblk = adj_trans_blocks(n);                      // one partial per wavefront of a group
-        const int per_group = trans_tiles_per_group(n);
+        // A workgroup's first load and last sums overlap with nothing, so it takes as many tiles as
+        // still leaves two workgroups per compute unit (never fewer than the buffer was sized for).
+        const int tiles = 1 << (n - 12);
+        int per_group = trans_tiles_per_group(n);
+        while (per_group * 2 <= tiles && per_group < 32 && (int64_t)(tiles / (per_group * 2)) * row_pairs >= 512)
+            per_group *= 2;
+        const int groups = tiles / per_group;
+        nblk = 4 * groups;                               // one partial per wavefront of a group
         const dim3 grid(groups, (unsigned)row_pairs);
-        hipLaunchKernelGGL((k_trans_tile<0>), grid, dim3(256), 0, st, S, n, 12, 12, per_group, nblk, partial);
+        hipLaunchKernelGGL((k_trans_wave<3>), grid, dim3(256), 0, st, S, n, 12, 12, 0, per_group, nblk, partial);
         hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
         for (int done = 12; done < n;) {
@@ -1788,8 +1903,10 @@ hipError_t launch_adj_layer(const float2* S, int n, int64_t row_pairs, double* p
             if (w + 8 > n) { w = n - 8; j0 = 4 + (done - w); }
             switch (j0) {
 #define QSV_TRANS_CASE(J) case J: hipLaunchKernelGGL((k_trans_tile<J>), grid, dim3(256), 0, st, S, n, 4, w, per_group, nblk, partial); break;
-                QSV_TRANS_CASE(4) QSV_TRANS_CASE(5) QSV_TRANS_CASE(6) QSV_TRANS_CASE(7) QSV_TRANS_CASE(8)
-                QSV_TRANS_CASE(9) QSV_TRANS_CASE(10) QSV_TRANS_CASE(11)
+                case 4: case 5: case 6: case 7:
+                    hipLaunchKernelGGL((k_trans_wave<2>), grid, dim3(256), 0, st, S, n, 4, w, j0, per_group, nblk, partial);
+                    break;
+                QSV_TRANS_CASE(8) QSV_TRANS_CASE(9) QSV_TRANS_CASE(10) QSV_TRANS_CASE(11)
 #undef QSV_TRANS_CASE
                 default: return hipErrorInvalidValue;
             }

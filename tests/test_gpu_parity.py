@@ -440,6 +440,90 @@ def test_loss_grad_small(oracle, n, B, L, rot, ent, reup, kind, mode):
     ctx.close()
 
 
+@pytest.mark.parametrize("n", [14, 15, 17, 18, 19])
+def test_loss_grad_every_transition_kernel(oracle, n):
+    """The squared-error loss touches every qubit, so every 2x2 transition sum matters.  These sizes
+    make the last window of the tiled sums start at each possible tile bit (n = 19, 18, 17: bits 5, 6,
+    7, served with the tile in LDS; n = 15, 14: bits 9, 10, straight from registers); n = 12, 13, 16
+    and 20 are covered by other tests.  The input is close to a basis state and the RY angles are small,
+    so that the expectation values, and with them every qubit's derivative, are far from zero."""
+    torch = gu.torch_cuda()
+    g = rng(300 + n)
+    spec = wl.CircuitSpec(1, (RY, RZ), RING, 0)
+    P = spec.num_params(n)
+    params = wl.draw_params(spec, n, 301 + n)
+    params[:n] = 0.3 + 0.05 * (np.arange(n) % 7)       # small RY angles: products of cosines stay large
+    x = (0.3 / np.sqrt(1 << n) * g.standard_normal((1, 1 << n))).astype(np.float32)
+    x[0, 5] = 1.0
+    y = g.uniform(-1, 1, (1, n)).astype(np.float32)
+    lref, gref = oracle.loss_grad(x, n, ocirc(oracle, spec), params, None, kind=oracle.LOSS_MSE_Z, targets=y)
+    assert np.count_nonzero(np.abs(gref[0, :n]) > 5e-4) >= n - 2   # (nearly) every qubit's sums matter
+    ctx = gu.make_ctx(n, 1)
+    loss = torch.zeros(1, dtype=torch.float32, device="cuda")
+    grad = torch.zeros((1, P), dtype=torch.float32, device="cuda")
+    ctx.qsv_loss_grad(qb.circuit_from_spec(spec), gu.dev(x), gu.dev(params), None, qb.QSV_LOSS_MSE_Z,
+                      loss, grad, None, None, targets=gu.dev(y))
+    torch.cuda.synchronize()
+    assert np.abs(loss.cpu().numpy() - lref).max() <= 1e-5
+    gg = grad.cpu().numpy()
+    assert np.abs(gg - gref).max() <= 1e-4
+    assert np.linalg.norm(gg - gref) <= 1e-3 * np.linalg.norm(gref)
+    ctx.close()
+
+
+def ring_product_state_loss(n, theta, y):
+    """Closed form for one layer RY(theta_q), RZ(anything), CNOT ring on |0...0>: taking Z_q back
+    through the ring (a CNOT turns Z on its target into Z on control and target) gives a product of
+    Z over a set S_q, whose expectation in the product state is prod_{j in S_q} cos(theta_j).
+    Returns the loss 1/n sum (z_q - y_q)^2 and its derivatives by theta (those by the RZ angles are 0)."""
+    ring = [(q, (q + 1) % n) for q in range(n)]
+    z = np.zeros(n)
+    dz = np.zeros((n, n))
+    for q in range(n):
+        m = 1 << q
+        for c, t in reversed(ring):
+            if (m >> t) & 1:
+                m ^= 1 << c
+        members = [j for j in range(n) if (m >> j) & 1]
+        z[q] = np.prod(np.cos(theta[members]))
+        for j in members:
+            dz[q, j] = -np.sin(theta[j]) * np.prod(np.cos(theta[[k for k in members if k != j]]))
+    return np.mean((z - y) ** 2), (2.0 / n) * (z - y) @ dz
+
+
+@pytest.mark.parametrize("n", [6, 21, 22])
+def test_loss_grad_several_windows_closed_form(oracle, n):
+    """n = 21 and 22 take two windows above the contiguous tiles (the second starting at tile bit 11
+    and 10); the oracle would need minutes there, so the reference is the closed form of a one-layer
+    circuit on a basis state (checked against the oracle itself at n = 6)."""
+    torch = gu.torch_cuda()
+    g = rng(320 + n)
+    spec = wl.CircuitSpec(1, (RY, RZ), RING, 0)
+    params = wl.draw_params(spec, n, 321 + n)
+    params[:n] = 0.3 + 0.05 * (np.arange(n) % 7)       # small RY angles: products of cosines stay large
+    theta = params[:n].astype(np.float64)
+    x = np.zeros((1, 1 << n), dtype=np.float32)
+    x[0, 0] = 1.0
+    y = g.uniform(-1, 1, (1, n)).astype(np.float32)
+    lref, gtheta = ring_product_state_loss(n, theta, y[0].astype(np.float64))
+    gref = np.concatenate([gtheta, np.zeros(n)])
+    assert np.count_nonzero(np.abs(gtheta) > 2e-4) >= n - 2
+    if n == 6:
+        lo, go = oracle.loss_grad(x, n, ocirc(oracle, spec), params, None, kind=oracle.LOSS_MSE_Z, targets=y)
+        assert abs(lo[0] - lref) <= 1e-12 and np.abs(go[0] - gref).max() <= 1e-12
+    ctx = gu.make_ctx(n, 1)
+    loss = torch.zeros(1, dtype=torch.float32, device="cuda")
+    grad = torch.zeros((1, 2 * n), dtype=torch.float32, device="cuda")
+    ctx.qsv_loss_grad(qb.circuit_from_spec(spec), gu.dev(x), gu.dev(params), None, qb.QSV_LOSS_MSE_Z,
+                      loss, grad, None, None, targets=gu.dev(y))
+    torch.cuda.synchronize()
+    assert abs(loss.item() - lref) <= 1e-5
+    gg = grad.cpu().numpy()[0]
+    assert np.abs(gg - gref).max() <= 1e-4
+    assert np.linalg.norm(gg - gref) <= 1e-3 * np.linalg.norm(gref)
+    ctx.close()
+
+
 def test_optimiser_steps(oracle):
     torch = gu.torch_cuda()
     g0 = rng(95)
