@@ -828,27 +828,38 @@ static qsv_status adjoint_impl(qsv_ctx* ctx, const qsv_circuit* c, const float* 
     if (!npart || !inv || !mats || !f) return ws_fail(ctx, ar, "qsv_adjoint_grad");
     QSV_HIP(ctx, launch_norms(x_dev, B, dim, npart, nblk, inv, nullptr, ctx->stream), "norms");
 
-    // per sample of a chunk: psi alone (forward), then the (psi, lambda) pair, plus reduction partials
+    // Two ways to have psi at the start of every layer on the way back.  With room for L + 1 states per
+    // sample the forward run keeps them (layer l reads state l and writes state l + 1, no copies) and
+    // only lambda is taken back: 2 L layers of gates per sample.  Otherwise psi is taken back together
+    // with lambda (rows 2r, 2r+1 of one buffer): 3 L layers, 3 states per sample of a chunk.
+    const int L = c->n_layers;
     const size_t tpart = (size_t)n * (adj_trans_blocks(n) + 1) * 8 * 8;
     const size_t zbytes = (size_t)chunk_blocks(n) * 13 * 8;
-    const size_t sample_bytes = 3 * state_bytes + tpart + zbytes + 2 * (size_t)n * 8 + 6 * kAlign;
+    const size_t small_bytes = tpart + zbytes + 2 * (size_t)n * 8 + 6 * kAlign;
+    const size_t ckpt_bytes = (size_t)B * (size_t)(L + 1) * state_bytes;
+    const bool keep = ctx->opt_grad_layered && P > 0 &&
+                      ar.remaining() >= align_up(ckpt_bytes) + state_bytes + small_bytes + 2 * kAlign;
+    float2* ckpt = keep ? (float2*)ar.take(ckpt_bytes) : nullptr;
+    if (keep && !ckpt) return ws_fail(ctx, ar, "qsv_adjoint_grad");
+    const size_t sample_bytes = (keep ? 1 : 3) * state_bytes + small_bytes;
     int64_t chunk = (int64_t)(ar.remaining() / sample_bytes);
     if (chunk < 1) { ar.need = ar.off + sample_bytes; return ws_fail(ctx, ar, "qsv_adjoint_grad"); }
     if (chunk > B) chunk = B;
-    if (chunk > 16384) chunk = 16384;   // 2 * chunk rows index a grid dimension
+    if (chunk > 16384) chunk = 16384;   // rows of a chunk index a grid dimension
     if (ctx->opt_grad_chunk > 0 && chunk > ctx->opt_grad_chunk) chunk = ctx->opt_grad_chunk;
     // keep row counts a power of two when several rows share a tile (extended-index tiling)
     if (chunk < B) { int64_t p2 = 1; while (p2 * 2 <= chunk) p2 *= 2; chunk = p2; }
-    float2* A = (float2*)ar.take((size_t)chunk * state_bytes);
-    float2* S = (float2*)ar.take((size_t)2 * chunk * state_bytes);
+    float2* Abuf = keep ? nullptr : (float2*)ar.take((size_t)chunk * state_bytes);
+    float2* S = (float2*)ar.take((size_t)(keep ? 1 : 2) * chunk * state_bytes);
     double* tp = (double*)ar.take((size_t)chunk * tpart);
     double* zpart = (double*)ar.take((size_t)chunk * zbytes);
     double* zall = (double*)ar.take((size_t)chunk * n * 8);
     double* coef = (double*)ar.take((size_t)chunk * n * 8);
-    if (!A || !S || !tp || !zpart || !zall || !coef) return ws_fail(ctx, ar, "qsv_adjoint_grad");
+    if ((!keep && !Abuf) || !S || !tp || !zpart || !zall || !coef) return ws_fail(ctx, ar, "qsv_adjoint_grad");
 
-    const int L = c->n_layers;
     const int slots_n = (c->reupload + c->n_rot) * n;
+    const size_t amps = (size_t)1 << n;
+    auto ck = [&](int l, int64_t b0) { return ckpt + ((size_t)l * (size_t)B + (size_t)b0) * amps; };
     qsv_circuit one = *c;
     one.n_layers = 1;
     for (int64_t b0 = 0; b0 < B; b0 += chunk) {
@@ -856,8 +867,19 @@ static qsv_status adjoint_impl(qsv_ctx* ctx, const qsv_circuit* c, const float* 
         // forward: rows are samples b0..b0+bc-1
         RowMap rm1;
         rm1.grad = 1; rm1.two_p = 0; rm1.per = 1; rm1.row0 = b0; rm1.slots_n = slots_n < 1 ? 1 : slots_n; rm1.n = n;
-        QSV_HIP(ctx, launch_encode_write(x_dev, dim, n, bc, inv, rm1, A, ctx->stream), "encode rows");
-        {
+        float2* A = keep ? ck(L, b0) : Abuf;                 // the final states of the chunk
+        if (keep) {
+            QSV_HIP(ctx, launch_encode_write(x_dev, dim, n, bc, inv, rm1, ck(0, b0), ctx->stream), "encode rows");
+            for (int l = 0; l < L; ++l) {
+                Prepared pr;
+                st = prepare_circuit(ctx, one, bc, 0, 0, params_dev + (size_t)l * slots_n, feats_dev, B, mats, &pr);
+                if (st != QSV_OK) return st;
+                // the start states are addressed by sample (ck(l, 0)), the rows written are the chunk's
+                st = run_circuit(ctx, one, pr, ck(l + 1, b0), bc, 0, nullptr, rm1, ck(l, 0));
+                if (st != QSV_OK) return st;
+            }
+        } else {
+            QSV_HIP(ctx, launch_encode_write(x_dev, dim, n, bc, inv, rm1, A, ctx->stream), "encode rows");
             Prepared pr;
             st = prepare_circuit(ctx, *c, bc, 0, 0, params_dev, feats_dev, B, mats, &pr);
             if (st != QSV_OK) return st;
@@ -878,19 +900,26 @@ static qsv_status adjoint_impl(qsv_ctx* ctx, const qsv_circuit* c, const float* 
             QSV_HIP(ctx, launch_mse_coef(zall, targets_dev, n, bc, b0, P, coef, f, ctx->stream), "mse loss");
         }
         if (P == 0) continue;
-        // backward: row 2r = psi, row 2r+1 = lambda = O psi, both taken back layer by layer
-        QSV_HIP(ctx, launch_adj_init(A, n, kind, obs_qubit, mask, coef, bc, S, ctx->stream), "adjoint init");
+        // backward: lambda = O psi (and psi beside it unless its states were kept), taken back layer by layer
+        QSV_HIP(ctx, launch_adj_init(A, n, kind, obs_qubit, mask, coef, bc, S, keep ? 0 : 1, ctx->stream),
+                "adjoint init");
         RowMap rm2 = rm1;
-        rm2.per = 2;
-        rm2.row0 = 2 * b0;
+        if (!keep) {
+            rm2.per = 2;
+            rm2.row0 = 2 * b0;
+        }
+        const int64_t back_rows = keep ? bc : 2 * bc;
         for (int l = L - 1; l >= 0; --l) {
             const float* p_l = params_dev + (size_t)l * slots_n;
             Prepared pr;
-            st = prepare_circuit(ctx, one, 2 * bc, 1, 0, p_l, feats_dev, B, mats, &pr);
+            st = prepare_circuit(ctx, one, back_rows, 1, 0, p_l, feats_dev, B, mats, &pr);
             if (st != QSV_OK) return st;
-            st = run_circuit(ctx, one, pr, S, 2 * bc, 1, nullptr, rm2);
+            st = run_circuit(ctx, one, pr, S, back_rows, 1, nullptr, rm2);
             if (st != QSV_OK) return st;
-            QSV_HIP(ctx, launch_adj_layer(S, n, bc, tp, cd, l, params_dev, feats_dev, b0, P, f, ctx->stream),
+            const float2* psi0 = keep ? ck(l, b0) : S;
+            const float2* lam0 = keep ? S : S + amps;
+            QSV_HIP(ctx, launch_adj_layer(psi0, lam0, keep ? 1 : 2, n, bc, tp, cd, l, params_dev, feats_dev, b0, P, f,
+                                          ctx->stream),
                     "adjoint layer");
         }
     }

@@ -126,11 +126,13 @@ hipError_t launch_pauli(const float2* state, int64_t rows, int n, uint64_t xmask
 // launch_trash_loss: f[sample0+r][2P] = 1 - P0(mask) of row r (partial: rows * blocks doubles, blocks
 // as for the <Z> reductions).  launch_mse_coef: from z[rows][n] and targets y[samples][n], the loss
 // 1/n sum (z-y)^2 into f[.][2P] and coef = 2/n (z-y).
-// launch_adj_layer: for the row pairs of S (psi, lambda), both taken back to the start of `layer`,
-// the derivatives with respect to that layer's angles, written into f[sample][2p], f[sample][2p+1]
-// as (g, -g).  partial: row_pairs * n * (adj_trans_blocks(n) + 1) * 8 doubles.
+// launch_adj_init: lambda = O psi for the rows of A; paired = 1 writes (psi, lambda) into rows 2r, 2r+1
+// of S, paired = 0 writes lambda alone into row r.
+// launch_adj_layer: for row pairs (psi0 + rstride r 2^n, lam0 + rstride r 2^n), both taken back to the
+// start of `layer`, the derivatives with respect to that layer's angles, written into f[sample][2p],
+// f[sample][2p+1] as (g, -g).  partial: row_pairs * n * (adj_trans_blocks(n) + 1) * 8 doubles.
 hipError_t launch_adj_init(const float2* A, int n, int kind, int q, uint64_t mask, const double* coef,
-                           int64_t rows, float2* S, hipStream_t st);
+                           int64_t rows, float2* S, int paired, hipStream_t st);
 hipError_t launch_trash_loss(const float2* A, int n, uint64_t mask, int64_t rows, int64_t sample0, int64_t P,
                              double* partial, double* f, hipStream_t st);
 hipError_t launch_mse_coef(const double* z, const float* y, int n, int64_t rows, int64_t sample0, int64_t P,
@@ -140,7 +142,8 @@ hipError_t launch_sgd(float* p, const float* g, int64_t count, double lr, hipStr
 hipError_t launch_adam(float* p, const float* g, float* m, float* v, int64_t count, int64_t t, double lr,
                        double b1, double b2, double eps, hipStream_t st);
 int adj_trans_blocks(int n);
-hipError_t launch_adj_layer(const float2* S, int n, int64_t row_pairs, double* partial, const CircDev& c,
+hipError_t launch_adj_layer(const float2* psi0, const float2* lam0, int rstride, int n, int64_t row_pairs,
+                            double* partial, const CircDev& c,
                             int layer, const float* params, const float* feats, int64_t sample0, int64_t P,
                             double* f, hipStream_t st);
 

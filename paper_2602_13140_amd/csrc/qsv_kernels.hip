@@ -1119,7 +1119,8 @@ __device__ __forceinline__ float adj_weight(const AdjObs& o, u64 r, u64 k, int n
     return (float)w;
 }
 
-__global__ __launch_bounds__(256) void k_adj_init(const float2* A, int n, AdjObs o, u64 total, float2* S) {
+__global__ __launch_bounds__(256) void k_adj_init(const float2* A, int n, AdjObs o, u64 total, float2* S,
+                                                  int paired) {
     const u64 e2 = ((u64)blockIdx.x * 256 + threadIdx.x) * 2;
     if (e2 >= total) return;
     const u64 r = e2 >> n, k = e2 & ((1ull << n) - 1);
@@ -1127,8 +1128,12 @@ __global__ __launch_bounds__(256) void k_adj_init(const float2* A, int n, AdjObs
     const float w0 = adj_weight(o, r, k, n), w1 = adj_weight(o, r, k + 1, n);
     float4 z;
     z.x = w0 * v.x; z.y = w0 * v.y; z.z = w1 * v.z; z.w = w1 * v.w;
-    *reinterpret_cast<float4*>(S + (((2 * r) << n) | k)) = v;
-    *reinterpret_cast<float4*>(S + (((2 * r + 1) << n) | k)) = z;
+    if (paired) {
+        *reinterpret_cast<float4*>(S + (((2 * r) << n) | k)) = v;
+        *reinterpret_cast<float4*>(S + (((2 * r + 1) << n) | k)) = z;
+    } else {
+        *reinterpret_cast<float4*>(S + e2) = z;
+    }
 }
 
 // P0(mask) of every row: block partials, then one thread per row; f[sample][2P] = 1 - P0.
@@ -1172,14 +1177,15 @@ __global__ __launch_bounds__(256) void k_mse_coef(const double* z, const float* 
 
 // M_q[a][b] = sum over the other qubits of conj(lambda[a, rest]) psi[b, rest], for one row pair
 // (blockIdx.z) and one qubit (blockIdx.y); a block covers 4096 index pairs and writes 8 doubles
-// (re, im of M00, M01, M10, M11).
-__global__ __launch_bounds__(256) void k_trans_block(const float2* S, int n, u64 pairs, int nblk,
-                                                     double* partial) {
+// (re, im of M00, M01, M10, M11).  Pair r is (psi0 + rstride r 2^n, lam0 + rstride r 2^n): the two
+// states interleaved in one buffer (lam0 = psi0 + 2^n, rstride 2) or in buffers of their own (rstride 1).
+__global__ __launch_bounds__(256) void k_trans_block(const float2* psi0, const float2* lam0, int rstride, int n,
+                                                     u64 pairs, int nblk, double* partial) {
     __shared__ double sm[4];
     const int q = blockIdx.y;
     const u64 r = blockIdx.z;
-    const float2* psi = S + ((2 * r) << n);
-    const float2* lam = S + ((2 * r + 1) << n);
+    const float2* psi = psi0 + ((rstride * r) << n);
+    const float2* lam = lam0 + ((rstride * r) << n);
     const u64 bit = 1ull << q;
     float acc[8];
 #pragma unroll
@@ -1265,13 +1271,13 @@ __device__ __forceinline__ void trans_acc(const float2 (&s)[N], const float2 (&l
 // of the 16 amplitudes a lane loads from memory (tau = i * 256 + lane index, coalesced), so nothing
 // goes through LDS.
 template <int J0>
-__global__ __launch_bounds__(256) void k_trans_tile(const float2* S, int n, int c, int w,
-                                                    int per_group, int nblk, double* partial) {
+__global__ __launch_bounds__(256) void k_trans_tile(const float2* psi0, const float2* lam0, int rstride, int n,
+                                                    int c, int w, int per_group, int nblk, double* partial) {
     static_assert(J0 >= 8 && J0 < 12, "lower tile bits are served by k_trans_wave");
     constexpr int NJ = 12 - J0;                      // acc[a] belongs to tile bit J0 + a
     const u64 r = blockIdx.y;
-    const float2* psi = S + ((2 * r) << n);
-    const float2* lam = S + ((2 * r + 1) << n);
+    const float2* psi = psi0 + ((rstride * r) << n);
+    const float2* lam = lam0 + ((rstride * r) << n);
     const unsigned t = threadIdx.x;
     const unsigned cmask = (1u << c) - 1u;
     const int wc = w - c;
@@ -1399,14 +1405,15 @@ __device__ __forceinline__ void trans_wave(const float2* ps, const float2* lm, u
 // M11 = tsum - M00 holds per wavefront.  Output layout as k_trans_tile; the wavefronts that do not own
 // a qubit write zeros for it.
 template <int RB>
-__global__ __launch_bounds__(256, 2) void k_trans_wave(const float2* S, int n, int c, int w, int j0,
-                                                       int per_group, int nblk, double* partial) {
+__global__ __launch_bounds__(256, 2) void k_trans_wave(const float2* psi0, const float2* lam0, int rstride,
+                                                       int n, int c, int w, int j0, int per_group, int nblk,
+                                                       double* partial) {
     __shared__ float2 ps[4096];
     __shared__ float2 lm[4096];                      // 64 KiB in all
     constexpr int JB = RB == 3 ? 0 : 4;
     const u64 r = blockIdx.y;
-    const float2* psi = S + ((2 * r) << n);
-    const float2* lam = S + ((2 * r + 1) << n);
+    const float2* psi = psi0 + ((rstride * r) << n);
+    const float2* lam = lam0 + ((rstride * r) << n);
     const unsigned t = threadIdx.x, lane = t & 63u;
     const int wv = (int)(t >> 6);
     const unsigned cmask = (1u << c) - 1u;
@@ -1820,11 +1827,11 @@ hipError_t launch_sample(const float2* state, int64_t rows, int n, const double*
 }
 
 hipError_t launch_adj_init(const float2* A, int n, int kind, int q, uint64_t mask, const double* coef,
-                           int64_t rows, float2* S, hipStream_t st) {
+                           int64_t rows, float2* S, int paired, hipStream_t st) {
     if (n < 1 || rows < 1 || kind < 0 || kind > 2 || (kind == 2 && !coef)) return hipErrorInvalidValue;
     const u64 total = (u64)rows << n;
     const AdjObs o{kind, q, (u64)mask, coef};
-    hipLaunchKernelGGL(k_adj_init, dim3(blocks_for(total / 2, 256)), dim3(256), 0, st, A, n, o, total, S);
+    hipLaunchKernelGGL(k_adj_init, dim3(blocks_for(total / 2, 256)), dim3(256), 0, st, A, n, o, total, S, paired);
     return hipGetLastError();
 }
 
@@ -1872,15 +1879,16 @@ static inline int trans_groups(int n) { return (1 << (n - 12)) / trans_tiles_per
 // upper bound of the partial entries per (row pair, qubit) of the transition sums
 int adj_trans_blocks(int n) { return n < 12 ? 1 : 4 * trans_groups(n); }
 
-hipError_t launch_adj_layer(const float2* S, int n, int64_t row_pairs, double* partial, const CircDev& c,
+hipError_t launch_adj_layer(const float2* psi0, const float2* lam0, int rstride, int n, int64_t row_pairs,
+                            double* partial, const CircDev& c,
                             int layer, const float* params, const float* feats, int64_t sample0, int64_t P,
                             double* f, hipStream_t st) {
     if (row_pairs < 1 || row_pairs > 65535) return hipErrorInvalidValue;
     int nblk;
     if (n < 12) {
         nblk = adj_trans_blocks(n);
-        hipLaunchKernelGGL(k_trans_block, dim3(nblk, n, (unsigned)row_pairs), dim3(256), 0, st, S, n,
-                           (u64)1 << (n - 1), nblk, partial);
+        hipLaunchKernelGGL(k_trans_block, dim3(nblk, n, (unsigned)row_pairs), dim3(256), 0, st, psi0, lam0, rstride,
+                           n, (u64)1 << (n - 1), nblk, partial);
         hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
     } else {
@@ -1895,16 +1903,18 @@ hipError_t launch_adj_layer(const float2* S, int n, int64_t row_pairs, double* p
         const int groups = tiles / per_group;
         nblk = 4 * groups;                               // one partial per wavefront of a group
         const dim3 grid(groups, (unsigned)row_pairs);
-        hipLaunchKernelGGL((k_trans_wave<3>), grid, dim3(256), 0, st, S, n, 12, 12, 0, per_group, nblk, partial);
+        hipLaunchKernelGGL((k_trans_wave<3>), grid, dim3(256), 0, st, psi0, lam0, rstride, n, 12, 12, 0, per_group,
+                           nblk, partial);
         hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
         for (int done = 12; done < n;) {
             int w = done, j0 = 4;
             if (w + 8 > n) { w = n - 8; j0 = 4 + (done - w); }
             switch (j0) {
-#define QSV_TRANS_CASE(J) case J: hipLaunchKernelGGL((k_trans_tile<J>), grid, dim3(256), 0, st, S, n, 4, w, per_group, nblk, partial); break;
+#define QSV_TRANS_CASE(J) case J: hipLaunchKernelGGL((k_trans_tile<J>), grid, dim3(256), 0, st, psi0, lam0, rstride, n, 4, w, per_group, nblk, partial); break;
                 case 4: case 5: case 6: case 7:
-                    hipLaunchKernelGGL((k_trans_wave<2>), grid, dim3(256), 0, st, S, n, 4, w, j0, per_group, nblk, partial);
+                    hipLaunchKernelGGL((k_trans_wave<2>), grid, dim3(256), 0, st, psi0, lam0, rstride, n, 4, w, j0, per_group,
+                                       nblk, partial);
                     break;
                 QSV_TRANS_CASE(8) QSV_TRANS_CASE(9) QSV_TRANS_CASE(10) QSV_TRANS_CASE(11)
 #undef QSV_TRANS_CASE

@@ -255,7 +255,7 @@ def test_apply_layers_random(oracle, n, B, L, rot, ent, reup, tile, planes):
     (13, 1, 2, (RY,), LADDER, 0, 0), (1, 4, 3, (RX, RZ), RING, 0, 0), (7, 3, 4, (RY, RZ), RING, 0, 6),
     (8, 5, 3, (RX, RZ), LADDER, 1, 2), (11, 2, 3, (RY, RZ), LADDER, 0, 10)])
 @pytest.mark.parametrize("mode", ["default", "naive", "whole", "chunk5", "whole-chunk4", "naive-whole",
-                                  "adjoint", "adjoint-naive", "adjoint-chunk2",
+                                  "adjoint", "adjoint-naive", "adjoint-chunk2", "adjoint-whole", "adjoint-whole-chunk2",
                                   "t10", "t11-whole", "t13", "t12p2", "adjoint-t10", "adjoint-t13"])
 def test_param_shift_grad_small(oracle, n, B, L, rot, ent, reup, obs, mode):
     torch = gu.torch_cuda()
@@ -280,7 +280,8 @@ def test_param_shift_grad_small(oracle, n, B, L, rot, ent, reup, obs, mode):
     grad = torch.zeros((B, P), dtype=torch.float32, device="cuda")
     ml = torch.zeros(1, dtype=torch.float32, device="cuda")
     mg = torch.zeros(P, dtype=torch.float32, device="cuda")
-    # "adjoint": the reverse-mode entry point; it must give the shift rule's values
+    # "adjoint": the reverse-mode entry point; it must give the shift rule's values (with "whole" it
+    # does not keep the forward states but takes psi back beside lambda)
     call = ctx.qsv_adjoint_grad if "adjoint" in mode else ctx.qsv_param_shift_grad
     call(qb.circuit_from_spec(spec), gu.dev(x), gu.dev(params), gu.dev(feats) if reup else None, obs,
          loss, grad, ml, mg)
@@ -402,7 +403,7 @@ def test_shot_expz(oracle):
     (6, 5, 2, (RY, RZ), RING, 1), (10, 3, 2, (RY, RZ), RING, 1), (12, 2, 2, (RY, RZ), RING, 0),
     (13, 2, 1, (RX, RZ), LADDER, 0)])
 @pytest.mark.parametrize("kind", ["trash", "mse"])
-@pytest.mark.parametrize("mode", ["default", "naive", "chunk2"])
+@pytest.mark.parametrize("mode", ["default", "naive", "chunk2", "whole", "whole-chunk2"])
 def test_loss_grad_small(oracle, n, B, L, rot, ent, reup, kind, mode):
     torch = gu.torch_cuda()
     g = rng(90 + n)
@@ -419,8 +420,10 @@ def test_loss_grad_small(oracle, n, B, L, rot, ent, reup, kind, mode):
     else:
         lref, gref = oracle.loss_grad(x, n, ocirc(oracle, spec), params, feats, kind=oracle.LOSS_MSE_Z, targets=y)
     ctx = gu.make_ctx(n, B, naive=1 if mode == "naive" else 0)
-    if mode.startswith("chunk"):
+    if "chunk" in mode:
         ctx.qsv_set_option("grad_chunk_rows", int(mode[-1]))
+    if "whole" in mode:                 # forward states not kept: psi is taken back beside lambda
+        ctx.qsv_set_option("grad_layered", 0)
     ctx.state.fill_(3.0)
     loss = torch.zeros(B, dtype=torch.float32, device="cuda")
     grad = torch.zeros((B, P), dtype=torch.float32, device="cuda")
