@@ -365,6 +365,8 @@ def probe(torch, qb, args):
     ctx = qb.Context(n, 1)
     if args.tile:
         ctx.qsv_set_option("tile_log2", args.tile)
+    if args.nt >= 0:
+        ctx.qsv_set_option("nt_store", args.nt)
     tile = args.tile or 12
     ctx.state.normal_()
     nbytes = 2 * 8 * (1 << n)
