@@ -1176,8 +1176,12 @@ __global__ __launch_bounds__(256) void k_mse_coef(const double* z, const float* 
 }
 
 // M_q[a][b] = sum over the other qubits of conj(lambda[a, rest]) psi[b, rest], for one row pair
-// (blockIdx.z) and one qubit (blockIdx.y); a block covers 4096 index pairs and writes 8 doubles
-// (re, im of M00, M01, M10, M11).  Pair r is (psi0 + rstride r 2^n, lam0 + rstride r 2^n): the two
+// (blockIdx.z) and one qubit (blockIdx.y); a block covers 4096 index pairs and writes 8 doubles in
+// the layout (re, im of M00, M01, M10, M11).  The derivative is 2 Re sum_ab Bt[a][b] M[a][b] with an
+// anti-Hermitian Bt (Bt00, Bt11 imaginary, Bt10 = -conj(Bt01)), which equals
+// -2 (Im Bt00 Im M00 + Im Bt11 Im M11) + 2 Re(Bt01 K) with K = M01 - conj(M10).  So only Im M00,
+// Im M11 and K are summed; K is stored in the place of M01 and the other entries are zero, which lets
+// k_adj_layer use the plain formula.  Pair r is (psi0 + rstride r 2^n, lam0 + rstride r 2^n): the two
 // states interleaved in one buffer (lam0 = psi0 + 2^n, rstride 2) or in buffers of their own (rstride 1).
 __global__ __launch_bounds__(256) void k_trans_block(const float2* psi0, const float2* lam0, int rstride, int n,
                                                      u64 pairs, int nblk, double* partial) {
@@ -1187,9 +1191,9 @@ __global__ __launch_bounds__(256) void k_trans_block(const float2* psi0, const f
     const float2* psi = psi0 + ((rstride * r) << n);
     const float2* lam = lam0 + ((rstride * r) << n);
     const u64 bit = 1ull << q;
-    float acc[8];
+    float acc[4];   // Im M00, Re K, Im K, Im M11
 #pragma unroll
-    for (int j = 0; j < 8; ++j) acc[j] = 0.f;
+    for (int j = 0; j < 4; ++j) acc[j] = 0.f;
 #pragma unroll
     for (int i = 0; i < 16; ++i) {
         const u64 p = (u64)blockIdx.x * 4096 + (u64)i * 256 + threadIdx.x;
@@ -1197,17 +1201,18 @@ __global__ __launch_bounds__(256) void k_trans_block(const float2* psi0, const f
             const u64 k0 = ((p >> q) << (q + 1)) | (p & (bit - 1));
             const u64 k1 = k0 | bit;
             const float2 l0 = lam[k0], l1 = lam[k1], s0 = psi[k0], s1 = psi[k1];
-            acc[0] += l0.x * s0.x + l0.y * s0.y; acc[1] += l0.x * s0.y - l0.y * s0.x;
-            acc[2] += l0.x * s1.x + l0.y * s1.y; acc[3] += l0.x * s1.y - l0.y * s1.x;
-            acc[4] += l1.x * s0.x + l1.y * s0.y; acc[5] += l1.x * s0.y - l1.y * s0.x;
-            acc[6] += l1.x * s1.x + l1.y * s1.y; acc[7] += l1.x * s1.y - l1.y * s1.x;
+            acc[0] += l0.x * s0.y - l0.y * s0.x;
+            acc[3] += l1.x * s1.y - l1.y * s1.x;
+            acc[1] += (l0.x * s1.x + l0.y * s1.y) - (l1.x * s0.x + l1.y * s0.y);
+            acc[2] += (l0.x * s1.y - l0.y * s1.x) + (l1.x * s0.y - l1.y * s0.x);
         }
     }
     double* out = partial + ((r * n + q) * (u64)nblk + blockIdx.x) * 8;
-#pragma unroll
-    for (int j = 0; j < 8; ++j) {
-        const double t = block_sum256((double)acc[j], sm);
-        if (threadIdx.x == 0) out[j] = t;
+    const double m00 = block_sum256((double)acc[0], sm), kre = block_sum256((double)acc[1], sm);
+    const double kim = block_sum256((double)acc[2], sm), m11 = block_sum256((double)acc[3], sm);
+    if (threadIdx.x == 0) {
+        out[0] = 0.0; out[1] = m00; out[2] = kre; out[3] = kim;
+        out[4] = 0.0; out[5] = 0.0; out[6] = 0.0; out[7] = m11;
     }
 }
 
@@ -1215,10 +1220,10 @@ __global__ __launch_bounds__(256) void k_trans_block(const float2* psi0, const f
 // 2^12 amplitudes of psi and of lambda (tile = the c lowest index bits plus 12 - c bits from bit w,
 // as in the pass kernel) and forms the index pairs of a qubit in registers: a lane holds, of each
 // state, a run of amplitudes that differ in a few tile bits.
-// Arithmetic per amplitude and qubit: the products d = conj(lambda[k]) psi[k] do not depend on the
-// qubit, M00 sums them over the indices with the bit clear, and M00 + M11 = sum of all d is the same
-// for every qubit, so it is kept once (tsum) and M11 comes out as a difference at the end; M01 and
-// M10 take 8 FMAs per pair each.
+// Arithmetic per amplitude and qubit (only Im M00, Im M11 and K = M01 - conj(M10) are needed, see
+// k_trans_block): d = Im conj(lambda[k]) psi[k] does not depend on the qubit, Im M00 sums it over the
+// indices with the bit clear, and Im (M00 + M11) = sum of all d is the same for every qubit, so it is
+// kept once (tsum) and Im M11 comes out as a difference at the end; K takes 8 FMAs per index pair.
 // A workgroup covers `per_group` consecutive tiles of one row pair before it reduces its
 // accumulators, so the reduction is amortised.
 // partial: [(pair * n + qubit) * nblk + group * 4 + wavefront][8] (nblk = 4 * groups), the layout
@@ -1239,32 +1244,35 @@ __device__ __forceinline__ float2 load_f2(global_bytes base, unsigned byte_offse
 }
 
 template <int N>
-__device__ __forceinline__ void trans_diag(const float2 (&s)[N], const float2 (&l)[N], float2 (&d)[N],
-                                           float (&tsum)[2]) {
+__device__ __forceinline__ void trans_diag(const float2 (&s)[N], const float2 (&l)[N], float (&d)[N],
+                                           float& tsum) {
 #pragma unroll
     for (int i = 0; i < N; ++i) {
-        d[i].x = fmaf(l[i].y, s[i].y, l[i].x * s[i].x);
-        d[i].y = fmaf(-l[i].y, s[i].x, l[i].x * s[i].y);
-        tsum[0] += d[i].x;
-        tsum[1] += d[i].y;
+        d[i] = fmaf(-l[i].y, s[i].x, l[i].x * s[i].y);      // Im conj(lambda) psi
+        tsum += d[i];
     }
 }
 
-// acc: re, im of M00, M01, M10 of the qubit behind run bit BIT
+// acc: Im M00, Re K, Im K of the qubit behind run bit BIT (K = M01 - conj(M10))
 template <int N, int BIT>
-__device__ __forceinline__ void trans_acc(const float2 (&s)[N], const float2 (&l)[N], const float2 (&d)[N],
-                                          float (&acc)[6]) {
+__device__ __forceinline__ void trans_acc(const float2 (&s)[N], const float2 (&l)[N], const float (&d)[N],
+                                          float (&acc)[3]) {
 #pragma unroll
     for (int i = 0; i < N; ++i) {
         if (i & (1 << BIT)) continue;
         constexpr int B = 1 << BIT;
-        acc[0] += d[i].x;
-        acc[1] += d[i].y;
-        acc[2] = fmaf(l[i].y, s[i | B].y, fmaf(l[i].x, s[i | B].x, acc[2]));
-        acc[3] = fmaf(-l[i].y, s[i | B].x, fmaf(l[i].x, s[i | B].y, acc[3]));
-        acc[4] = fmaf(l[i | B].y, s[i].y, fmaf(l[i | B].x, s[i].x, acc[4]));
-        acc[5] = fmaf(-l[i | B].y, s[i].x, fmaf(l[i | B].x, s[i].y, acc[5]));
+        acc[0] += d[i];
+        acc[1] = fmaf(-l[i | B].y, s[i].y, fmaf(-l[i | B].x, s[i].x,
+                 fmaf(l[i].y, s[i | B].y, fmaf(l[i].x, s[i | B].x, acc[1]))));
+        acc[2] = fmaf(-l[i | B].y, s[i].x, fmaf(l[i | B].x, s[i].y,
+                 fmaf(-l[i].y, s[i | B].x, fmaf(l[i].x, s[i | B].y, acc[2]))));
     }
+}
+
+// What a wavefront writes for one qubit: the 8-double layout of k_trans_block.
+__device__ __forceinline__ void trans_store(double* out, double m00, double kre, double kim, double tsum) {
+    out[0] = 0.0; out[1] = m00; out[2] = kre; out[3] = kim;
+    out[4] = 0.0; out[5] = 0.0; out[6] = 0.0; out[7] = tsum - m00;
 }
 
 // Tile bits J0..11, J0 >= 8 (a window of which only the top bits are still wanted): they are the run
@@ -1281,12 +1289,12 @@ __global__ __launch_bounds__(256) void k_trans_tile(const float2* psi0, const fl
     const unsigned t = threadIdx.x;
     const unsigned cmask = (1u << c) - 1u;
     const int wc = w - c;
-    float acc[NJ][6];
-    float tsum[2] = {0.f, 0.f};
+    float acc[NJ][3];
+    float tsum = 0.f;
 #pragma unroll
     for (int a = 0; a < NJ; ++a)
 #pragma unroll
-        for (int b = 0; b < 6; ++b) acc[a][b] = 0.f;
+        for (int b = 0; b < 3; ++b) acc[a][b] = 0.f;
     // tau = i * 256 + t sits at index base | (tau & cmask) | (tau >> c) << w = base + i * stride + kt, both
     // for contiguous tiles (c = 12) and for c = 4 (tau >> 4 = i * 16 + (t >> 4)); base + i * stride is the
     // same for all lanes (scalar registers), kt a 32-bit lane offset
@@ -1295,7 +1303,8 @@ __global__ __launch_bounds__(256) void k_trans_tile(const float2* psi0, const fl
     for (int g = 0; g < per_group; ++g) {
         const u64 tb = (u64)blockIdx.x * per_group + g;      // tile of the row
         const u64 base = ((tb & ((1ull << wc) - 1ull)) << c) | ((tb >> wc) << (w + 12 - c));
-        float2 s[16], l[16], d[16];
+        float2 s[16], l[16];
+        float d[16];
 #pragma unroll
         for (int i = 0; i < 16; ++i) {
             s[i] = load_f2(uniform_ptr(psi + (base + (u64)i * stride)), kt8);
@@ -1308,21 +1317,16 @@ __global__ __launch_bounds__(256) void k_trans_tile(const float2* psi0, const fl
         trans_acc<16, 3>(s, l, d, acc[11 - J0]);
     }
     // every wavefront writes its own partial: index (group, wavefront)
-    const double t0 = wave_sum((double)tsum[0]), t1 = wave_sum((double)tsum[1]);
+    const double t1 = wave_sum((double)tsum);
 #pragma unroll
     for (int a = 0; a < NJ; ++a) {
         const int j = J0 + a;
         const int q = j < c ? j : j - c + w;                 // the qubit behind tile bit j
         double* out = partial + ((r * n + q) * (u64)nblk + (u64)blockIdx.x * 4 + (t >> 6)) * 8;
-        double tot[6];
+        double tot[3];
 #pragma unroll
-        for (int b = 0; b < 6; ++b) tot[b] = wave_sum((double)acc[a][b]);
-        if ((t & 63u) == 0) {
-#pragma unroll
-            for (int b = 0; b < 6; ++b) out[b] = tot[b];
-            out[6] = t0 - tot[0];
-            out[7] = t1 - tot[1];
-        }
+        for (int b = 0; b < 3; ++b) tot[b] = wave_sum((double)acc[a][b]);
+        if ((t & 63u) == 0) trans_store(out, tot[0], tot[1], tot[2], t1);
     }
 }
 
@@ -1359,7 +1363,7 @@ __device__ constexpr unsigned trans_swz(unsigned tau) { return tau ^ ((tau >> 4)
 // run per lane; the reads of a step are issued before the sums of the step before it.
 template <int RB, int R0>
 __device__ __forceinline__ void trans_wave(const float2* ps, const float2* lm, unsigned lane,
-                                           float (&acc)[RB][6], float (&tsum)[2]) {
+                                           float (&acc)[RB][3], float& tsum) {
     constexpr TransMap<RB, R0> map{};
     constexpr int NR = 1 << RB, HB = 6 - RB, NH = 1 << HB;
     unsigned lp = 0;
@@ -1380,7 +1384,7 @@ __device__ __forceinline__ void trans_wave(const float2* ps, const float2* lm, u
         }
     };
     auto sums = [&](const float2 (&a)[NR], const float2 (&b)[NR]) __attribute__((always_inline)) {
-        float2 d[NR];
+        float d[NR];
         trans_diag<NR>(a, b, d, tsum);
         trans_acc<NR, 0>(a, b, d, acc[0]);
         trans_acc<NR, 1>(a, b, d, acc[1]);
@@ -1402,7 +1406,7 @@ __device__ __forceinline__ void trans_wave(const float2* ps, const float2* lm, u
 // (wavefront v: tile bits JB + RB v ...), so a lane carries accumulators for RB qubits only and the
 // loads of the workgroup's next tile stay in flight meanwhile (the loop is rotated for that: load
 // tile g, sums of tile g - 1, tile g into LDS).  Every wavefront sums d over the whole tile, so
-// M11 = tsum - M00 holds per wavefront.  Output layout as k_trans_tile; the wavefronts that do not own
+// Im M11 = tsum - Im M00 holds per wavefront.  Output layout as k_trans_tile; the wavefronts that do not own
 // a qubit write zeros for it.
 template <int RB>
 __global__ __launch_bounds__(256, 2) void k_trans_wave(const float2* psi0, const float2* lam0, int rstride,
@@ -1418,12 +1422,12 @@ __global__ __launch_bounds__(256, 2) void k_trans_wave(const float2* psi0, const
     const int wv = (int)(t >> 6);
     const unsigned cmask = (1u << c) - 1u;
     const int wc = w - c;
-    float acc[RB][6];
-    float tsum[2] = {0.f, 0.f};
+    float acc[RB][3];
+    float tsum = 0.f;
 #pragma unroll
     for (int a = 0; a < RB; ++a)
 #pragma unroll
-        for (int b = 0; b < 6; ++b) acc[a][b] = 0.f;
+        for (int b = 0; b < 3; ++b) acc[a][b] = 0.f;
     const unsigned tc = t ^ ((t >> 4) & 15u);        // swizzled lane part of the layout loaded from memory
     float2 s[16], l[16];                             // tau = i * 256 + t
     const u64 stride = c == 12 ? 256ull : (16ull << w);          // addressing as in k_trans_tile
@@ -1459,12 +1463,12 @@ __global__ __launch_bounds__(256, 2) void k_trans_wave(const float2* psi0, const
             __syncthreads();
         }
     }
-    const double t0 = wave_sum((double)tsum[0]), t1 = wave_sum((double)tsum[1]);
-    double tot[RB][6];
+    const double t1 = wave_sum((double)tsum);
+    double tot[RB][3];
 #pragma unroll
     for (int a = 0; a < RB; ++a)
 #pragma unroll
-        for (int b = 0; b < 6; ++b) tot[a][b] = wave_sum((double)acc[a][b]);
+        for (int b = 0; b < 3; ++b) tot[a][b] = wave_sum((double)acc[a][b]);
     if (lane != 0) return;
     for (int j = j0 > JB ? j0 : JB; j < 12; ++j) {
         const int q = j < c ? j : j - c + w;                 // the qubit behind tile bit j
@@ -1474,13 +1478,8 @@ __global__ __launch_bounds__(256, 2) void k_trans_wave(const float2* psi0, const
             continue;
         }
 #pragma unroll
-        for (int a = 0; a < RB; ++a) {
-            if ((j - JB) % RB != a) continue;
-#pragma unroll
-            for (int b = 0; b < 6; ++b) out[b] = tot[a][b];
-            out[6] = t0 - tot[a][0];
-            out[7] = t1 - tot[a][1];
-        }
+        for (int a = 0; a < RB; ++a)
+            if ((j - JB) % RB == a) trans_store(out, tot[a][0], tot[a][1], tot[a][2], t1);
     }
 }
 
