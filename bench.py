@@ -277,6 +277,10 @@ def bench_c1(torch, qb, wl, args):
     w = wl.config(1)
     n, B = w.n, w.batch
     ctx = qb.Context(n, B)
+    if args.tile:
+        ctx.qsv_set_option("tile_log2", args.tile)
+    if args.planes:
+        ctx.qsv_set_option("lds_planes", args.planes)
     circ = qb.circuit_from_spec(w.circuit)
     xd, pd, fd = (torch.from_numpy(a).cuda() for a in (w.x, w.params, w.feats))
     z = torch.empty((B, n), dtype=torch.float32, device="cuda")
