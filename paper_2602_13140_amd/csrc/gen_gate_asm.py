@@ -46,8 +46,9 @@ FIRST_SGPR, LAST_SGPR = 36 - SHIFT, 99 - SHIFT
 
 
 def u_pair(a, b, variant="g"):
-    """(r_a,i_a) has the target bit 0, (r_b,i_b) has it 1; matrix m0..m7 = s88..s95 =
-    (m00r, m00i, m01r, m01i, m10r, m10i, m11r, m11i).  Four interleaved chains; the last step of
+    """(r_a,i_a) has the target bit 0, (r_b,i_b) has it 1; matrix m0..m7 = vector copies of
+    s88..s95 = (m00r, m00i, m01r, m01i, m10r, m10i, m11r, m11i): a vector instruction with a scalar
+    operand issues at 4.2 cycles per wavefront on this chip, one with vector operands only at 2.5.  Four interleaved chains; the last step of
     each overwrites an input that is dead by then.  Variants leave out the products with
     imaginary parts that are stored as exact zeros: "g" none (16 instructions), "a" m00i (14),
     "r" m00i and m01i (first row real, 12), "c" m00i and m10i (first column real, 12)."""
@@ -57,38 +58,38 @@ def u_pair(a, b, variant="g"):
     fma = lambda d, m, x, acc: "v_fma_f32 %s, %s, %s, %s" % (d, m, x, acc)
     if variant == "g":
         return [
-            mul(t[0], "s88", ra), mul(t[1], "s89", ra), mul(t[2], "s92", ra), mul(t[3], "s93", ra),
-            fma(t[0], "-s89", ia, t[0]), fma(t[1], "s88", ia, t[1]),
-            fma(t[2], "-s93", ia, t[2]), fma(t[3], "s92", ia, t[3]),
-            fma(t[0], "s90", rb, t[0]), fma(t[1], "s91", rb, t[1]),
-            fma(t[2], "s94", rb, t[2]), fma(t[3], "s95", rb, t[3]),
-            fma(ra, "-s91", ib, t[0]), fma(ia, "s90", ib, t[1]),
-            fma(rb, "-s95", ib, t[2]), fma(ib, "s94", ib, t[3]),
+            mul(t[0], "%[m0]", ra), mul(t[1], "%[m1]", ra), mul(t[2], "%[m4]", ra), mul(t[3], "%[m5]", ra),
+            fma(t[0], "-%[m1]", ia, t[0]), fma(t[1], "%[m0]", ia, t[1]),
+            fma(t[2], "-%[m5]", ia, t[2]), fma(t[3], "%[m4]", ia, t[3]),
+            fma(t[0], "%[m2]", rb, t[0]), fma(t[1], "%[m3]", rb, t[1]),
+            fma(t[2], "%[m6]", rb, t[2]), fma(t[3], "%[m7]", rb, t[3]),
+            fma(ra, "-%[m3]", ib, t[0]), fma(ia, "%[m2]", ib, t[1]),
+            fma(rb, "-%[m7]", ib, t[2]), fma(ib, "%[m6]", ib, t[3]),
         ]
     if variant == "a":
         return [
-            mul(t[0], "s88", ra), mul(t[1], "s88", ia), mul(t[2], "s92", ra), mul(t[3], "s93", ra),
-            fma(t[2], "-s93", ia, t[2]), fma(t[3], "s92", ia, t[3]),
-            fma(t[0], "s90", rb, t[0]), fma(t[1], "s91", rb, t[1]),
-            fma(t[2], "s94", rb, t[2]), fma(t[3], "s95", rb, t[3]),
-            fma(ra, "-s91", ib, t[0]), fma(ia, "s90", ib, t[1]),
-            fma(rb, "-s95", ib, t[2]), fma(ib, "s94", ib, t[3]),
+            mul(t[0], "%[m0]", ra), mul(t[1], "%[m0]", ia), mul(t[2], "%[m4]", ra), mul(t[3], "%[m5]", ra),
+            fma(t[2], "-%[m5]", ia, t[2]), fma(t[3], "%[m4]", ia, t[3]),
+            fma(t[0], "%[m2]", rb, t[0]), fma(t[1], "%[m3]", rb, t[1]),
+            fma(t[2], "%[m6]", rb, t[2]), fma(t[3], "%[m7]", rb, t[3]),
+            fma(ra, "-%[m3]", ib, t[0]), fma(ia, "%[m2]", ib, t[1]),
+            fma(rb, "-%[m7]", ib, t[2]), fma(ib, "%[m6]", ib, t[3]),
         ]
     if variant == "r":
         return [
-            mul(t[0], "s88", ra), mul(t[1], "s88", ia), mul(t[2], "s92", ra), mul(t[3], "s93", ra),
-            fma(t[2], "-s93", ia, t[2]), fma(t[3], "s92", ia, t[3]),
-            fma(t[2], "s94", rb, t[2]), fma(t[3], "s95", rb, t[3]),
-            fma(ra, "s90", rb, t[0]), fma(ia, "s90", ib, t[1]),
-            fma(rb, "-s95", ib, t[2]), fma(ib, "s94", ib, t[3]),
+            mul(t[0], "%[m0]", ra), mul(t[1], "%[m0]", ia), mul(t[2], "%[m4]", ra), mul(t[3], "%[m5]", ra),
+            fma(t[2], "-%[m5]", ia, t[2]), fma(t[3], "%[m4]", ia, t[3]),
+            fma(t[2], "%[m6]", rb, t[2]), fma(t[3], "%[m7]", rb, t[3]),
+            fma(ra, "%[m2]", rb, t[0]), fma(ia, "%[m2]", ib, t[1]),
+            fma(rb, "-%[m7]", ib, t[2]), fma(ib, "%[m6]", ib, t[3]),
         ]
     assert variant == "c"
     return [
-        mul(t[0], "s88", ra), mul(t[1], "s88", ia), mul(t[2], "s92", ra), mul(t[3], "s92", ia),
-        fma(t[0], "s90", rb, t[0]), fma(t[1], "s91", rb, t[1]),
-        fma(t[2], "s94", rb, t[2]), fma(t[3], "s95", rb, t[3]),
-        fma(ra, "-s91", ib, t[0]), fma(ia, "s90", ib, t[1]),
-        fma(rb, "-s95", ib, t[2]), fma(ib, "s94", ib, t[3]),
+        mul(t[0], "%[m0]", ra), mul(t[1], "%[m0]", ia), mul(t[2], "%[m4]", ra), mul(t[3], "%[m4]", ia),
+        fma(t[0], "%[m2]", rb, t[0]), fma(t[1], "%[m3]", rb, t[1]),
+        fma(t[2], "%[m6]", rb, t[2]), fma(t[3], "%[m7]", rb, t[3]),
+        fma(ra, "-%[m3]", ib, t[0]), fma(ia, "%[m2]", ib, t[1]),
+        fma(rb, "-%[m7]", ib, t[2]), fma(ib, "%[m6]", ib, t[3]),
     ]
 
 
@@ -166,6 +167,8 @@ def gen(planes=2):
     emit("s_load_dwordx8 s[72:79], s[70:71], 0x0")
     emit(lab("unopf") + ":")
     prefetch_next_word()
+    for k in range(8):                            # the multiply sequences read vector registers only
+        emit("v_mov_b32 %%[m%d], s%d" % (k, 88 + k))
     # pick the multiply sequence from the zeros the matrix builder stored
     emit("s_cmp_lg_u32 s89, 0")
     emit("s_cbranch_scc1 " + lab("ug"))

@@ -256,9 +256,11 @@ __global__ __launch_bounds__(1 << (T - R)) void k_pass(const PassArgs a) {
 
     for (;;) {
         {
-            float t0, t1, t2, t3, tc;
+            float t0, t1, t2, t3, tc, m0, m1, m2, m3, m4, m5, m6, m7;
 #define QSV_LOOP_OUT QSV_16(QSV_RV) [t0] "=&v"(t0), [t1] "=&v"(t1), [t2] "=&v"(t2),                 \
-                     [t3] "=&v"(t3), [tc] "=&v"(tc), [opslo] "+s"(opslo), [opshi] "+s"(opshi),     \
+                     [t3] "=&v"(t3), [tc] "=&v"(tc), [m0] "=&v"(m0), [m1] "=&v"(m1), [m2] "=&v"(m2), \
+                     [m3] "=&v"(m3), [m4] "=&v"(m4), [m5] "=&v"(m5), [m6] "=&v"(m6), [m7] "=&v"(m7), \
+                     [opslo] "+s"(opslo), [opshi] "+s"(opshi),                                     \
                      [scur] "+s"(scur), [ldsb] "+v"(ldsb), [e0lo] "+v"(e0lo), [e0hi] "+v"(e0hi)
 #define QSV_LOOP_IN [mlo] "s"(mlo), [mhi] "s"(mhi), [olo] "s"(olo), [ohi] "s"(ohi),                 \
                     [ovrid] "s"(ovr_id), [nonuni] "s"(nonuni), [thr] "v"(thr), [c] "s"(sc_c),       \

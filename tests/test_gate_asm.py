@@ -64,7 +64,7 @@ def test_committed_header_is_current():
 
 
 def _run_valu(lines, regs, sregs):
-    """Executes v_mul_f32 / v_fma_f32 lines (scalar first operand, optional negation) on floats."""
+    """Executes v_mul_f32 / v_fma_f32 lines (matrix entry as first operand, optional negation) on floats."""
     val = lambda tok: -sregs[tok[1:]] if tok.startswith("-") else sregs[tok]
     for ln in lines:
         op, rest = ln.split(" ", 1)
@@ -86,7 +86,7 @@ def test_unitary_multiply_sequences_compute_the_matrix_product():
     for variant in "garc":
         m = g0.standard_normal(8)
         m[zero[variant]] = 0.0
-        sregs = {"s%d" % (88 + k): m[k] for k in range(8)}
+        sregs = {"%%[m%d]" % k: m[k] for k in range(8)}
         a = g0.standard_normal(2) + 1j * g0.standard_normal(2)
         regs = {"%[r2]": a[0].real, "%[i2]": a[0].imag, "%[r6]": a[1].real, "%[i6]": a[1].imag}
         lines = g.u_pair(2, 6, variant)
