@@ -15,17 +15,23 @@ operation pointer on it and no scalar load or LDS access in flight.
 
 LDS layout: two planes of 2^T floats (real, imaginary).  Element tau of a plane sits at index
 tau ^ ((tau >> 4) & 31): the XOR spreads every layout's 32 consecutive lanes over the 32 banks,
-costs no space, and, XOR being linear, the address of
-register element k is (lane's part) ^ (a scalar that depends on k and the layout): one v_xor.
+costs no space, and, XOR being linear, the address of register element k is (lane's part) ^ off(k)
+with off(k) the XOR of the offsets of k's set bits.  A layout is therefore described by four
+offsets (those of elements 1, 2, 4, 8), kept in vector registers, and the elements are visited in
+Gray-code order, so that each address is the previous one XOR one of the four: one vector-only
+v_xor per element (a vector instruction with a scalar operand issues at 4.2 cycles per wavefront
+on this chip, one with vector operands only at 2.5).
 The dynamic LDS segment starts at byte 0 (the kernel has no static LDS), so no base is added.
 
 Operation word: x = kind | a<<8 | b<<16 | c<<24, y = arg.  For a unitary, arg is the index of its
 matrix in execution order, so consecutive unitaries read consecutive 32-byte matrices and the
 next one can be prefetched (the table is padded by one entry for the last prefetch).
 
-Fixed scalar registers (declared as clobbers):
-  s[36:51] one-plane transposes: address offsets of the layout being moved to
-  s[52:67] address offsets of the 16 register elements in layout s68 (s68 = -1: not loaded)
+Fixed scalar registers (declared as clobbers; the text below names them s52..s55 and s68..s99,
+_renumbered() packs them into s36..s71 so that the kernel stays below 96 scalar registers, i.e.
+eight wavefronts per SIMD):
+  s[52:55] landing place of a layout's four offsets on their way to vector registers
+  s68 layout whose offsets sit in %[ba0..3] (-1: none, the compiler may have used them since)
   s69 one-plane transposes: the exchange crosses wavefronts
   s[70:71] address whose matrix sits in the prefetch buffer (0 = none)
   s[72:79] prefetch buffer            s[80:81] current operation word
@@ -38,11 +44,9 @@ import os
 R = 4
 NR = 1 << R
 OP_XPOSE, OP_U, OP_CX_REG, OP_CX_DYN, OP_CZ_REG, OP_CZ_MIX, OP_CZ_LANE = 2, 3, 4, 5, 6, 7, 8
-# The map above is written with the block's registers at s36..s99; SHIFT would move the whole
-# block down.  It stays 0: lower numbers run into s32/s33, which the compiler reserves, and a
-# kernel limited to 96 scalar registers (8 waves per SIMD) measured no faster than 7 waves.
-SHIFT = 0
-FIRST_SGPR, LAST_SGPR = 36 - SHIFT, 99 - SHIFT
+FIRST_SGPR, LAST_SGPR = 36, 71      # after _renumbered()
+GRAY = [i ^ (i >> 1) for i in range(NR)]        # element visited at step i
+GRAY_BIT = [0] + [(i & -i).bit_length() - 1 for i in range(1, NR)]   # bit that changes on entering step i
 
 
 def u_pair(a, b, variant="g"):
@@ -299,17 +303,30 @@ def gen(planes=2):
     emit("s_branch " + lab("next"))
 
     # ---- transpose: move the register run from layout scur to layout a (field a of the word).
-    # The per-element address offsets of a layout come from a 16-dword table row (one scalar
-    # load); s[52:67] holds the row of the layout named in s68 (-1: none, the compiler may have
-    # used these registers since the block was last left).
+    # The four address offsets of a layout come from a 4-dword table row (one scalar load) and go to
+    # vector registers: %[ba0..3] for the layout named in s68 (-1: none), %[bb0..3] for the layout
+    # being moved to.
     def load_offsets(sreg):
-        emit("s_lshl_b32 s84, %s, 6" % sreg)
+        emit("s_lshl_b32 s84, %s, 4" % sreg)
         emit("s_add_u32 s86, %[tablo], s84")
         emit("s_addc_u32 s87, %[tabhi], 0")
-        emit("s_load_dwordx16 s[52:67], s[86:87], 0x0")
-        emit("s_mov_b32 s68, %s" % sreg)
+        emit("s_load_dwordx4 s[52:55], s[86:87], 0x0")
+
+    def offsets_to(prefix):
+        for j in range(4):
+            emit("v_mov_b32 %%[%s%d], s%d" % (prefix, j, 52 + j))
 
     tmps = ["%[t0]", "%[t1]", "%[t2]", "%[t3]"]
+
+    def walk(base, prefix, access):
+        """Visits the 16 register elements in Gray-code order; access(k, address register)."""
+        prev = base
+        for i in range(NR):
+            if i:
+                t = tmps[i % 4]
+                emit("v_xor_b32 %s, %s, %%[%s%d]" % (t, prev, prefix, GRAY_BIT[i]))
+                prev = t
+            access(GRAY[i], prev)
 
     def lane_part(dst):
         """dst = byte address part of the lane in layout scur; also refreshes e0."""
@@ -341,6 +358,7 @@ def gen(planes=2):
     emit("s_cbranch_scc1 " + lab("xphave"))
     load_offsets("%[scur]")
     emit("s_waitcnt lgkmcnt(0)")
+    offsets_to("ba")
     emit(lab("xphave") + ":")
     emit("s_bfe_u32 s84, s80, 0x80018")           # c: barrier before the writes
     emit("s_cmp_eq_u32 s84, 0")
@@ -348,29 +366,29 @@ def gen(planes=2):
     emit("s_barrier")
     emit(lab("xpw") + ":")
     if planes == 2:
-        for k in range(NR):
-            t = tmps[k % 4]
-            emit("v_xor_b32 %s, s%d, %%[ldsb]" % (t, 52 + k))
-            emit("ds_write2st64_b32 %s, %%[r%d], %%[i%d] offset1:%%[pl64]" % (t, k, k))
+        walk("%[ldsb]", "ba", lambda k, t: emit(
+            "ds_write2st64_b32 %s, %%[r%d], %%[i%d] offset1:%%[pl64]" % (t, k, k)))
         # new layout: its offsets first (they arrive while the lane's own part is computed)
         emit("s_mov_b32 %[scur], s83")
         load_offsets("%[scur]")
         lane_part("%[ldsb]")
         emit("s_waitcnt lgkmcnt(0)")              # own writes are in LDS, new offsets are here
+        offsets_to("ba")
+        emit("s_mov_b32 s68, %[scur]")
         emit("s_bfe_u32 s84, s80, 0x80010")       # b: the exchange crosses wavefronts
         emit("s_cmp_eq_u32 s84, 0")
         emit("s_cbranch_scc1 " + lab("xpr"))
         emit("s_barrier")
         emit(lab("xpr") + ":")
-        for k in range(NR):
-            t = tmps[k % 4]
-            emit("v_xor_b32 %s, s%d, %%[ldsb]" % (t, 52 + k))
+
+        def read2(k, t):
             emit("ds_read_b32 %%[r%d], %s" % (k, t))
             emit("ds_read_b32 %%[i%d], %s offset:%%[plane4]" % (k, t))
+        walk("%[ldsb]", "ba", read2)
         emit("s_branch " + lab("next"))           # the wait at the top covers the reads
     else:
         # One plane: real parts go through it first, then the imaginary parts.  The offsets of the
-        # new layout sit in s[36:51] until the end, the lane's new address part in ldsn.  A
+        # new layout sit in %[bb0..3] until the end, the lane's new address part in ldsn.  A
         # wavefront's LDS operations execute in order, so the steps need a wait and a barrier
         # between them only when the exchange crosses wavefronts (flag b, kept in s69).
         def sync(name):
@@ -381,26 +399,18 @@ def gen(planes=2):
             emit(lab(name) + ":")
 
         def writes(part):
-            for k in range(NR):
-                t = tmps[k % 4]
-                emit("v_xor_b32 %s, s%d, %%[ldsb]" % (t, 52 + k))
-                emit("ds_write_b32 %s, %%[%s%d]" % (t, part, k))
+            walk("%[ldsb]", "ba", lambda k, t: emit("ds_write_b32 %s, %%[%s%d]" % (t, part, k)))
 
         def reads(part):
-            for k in range(NR):
-                t = tmps[k % 4]
-                emit("v_xor_b32 %s, s%d, %%[ldsn]" % (t, 36 + k))
-                emit("ds_read_b32 %%[%s%d], %s" % (part, k, t))
+            walk("%[ldsn]", "bb", lambda k, t: emit("ds_read_b32 %%[%s%d], %s" % (part, k, t)))
 
         emit("s_bfe_u32 s69, s80, 0x80010")
         writes("r")
         emit("s_mov_b32 %[scur], s83")
-        emit("s_lshl_b32 s84, %[scur], 6")
-        emit("s_add_u32 s86, %[tablo], s84")
-        emit("s_addc_u32 s87, %[tabhi], 0")
-        emit("s_load_dwordx16 s[36:51], s[86:87], 0x0")
+        load_offsets("%[scur]")
         lane_part("%[ldsn]")
         emit("s_waitcnt lgkmcnt(0)")              # new offsets are here (and own writes landed)
+        offsets_to("bb")
         emit("s_cmp_eq_u32 s69, 0")
         emit("s_cbranch_scc1 " + lab("xpr"))
         emit("s_barrier")
@@ -410,8 +420,8 @@ def gen(planes=2):
         writes("i")
         sync("xpr2")
         reads("i")
-        for k in range(0, NR, 2):                 # the new layout's offsets become the current ones
-            emit("s_mov_b64 s[%d:%d], s[%d:%d]" % (52 + k, 53 + k, 36 + k, 37 + k))
+        for j in range(4):                        # the new layout's offsets become the current ones
+            emit("v_mov_b32 %%[ba%d], %%[bb%d]" % (j, j))
         emit("s_mov_b32 s68, %[scur]")
         emit("v_mov_b32 %[ldsb], %[ldsn]")
         emit("s_branch " + lab("next"))           # the wait at the top covers the reads
@@ -423,15 +433,22 @@ def gen(planes=2):
     emit(lab("exit") + ":")                       # reached right after the wait: nothing in flight
     emit("s_mov_b32 %[opslo], s96")
     emit("s_mov_b32 %[opshi], s97")
-    return [_shifted(ln) for ln in L]
+    return [_renumbered(ln) for ln in L]
 
 
-def _shifted(line):
-    """Renumbers the block's scalar registers (written as s36..s99) down by SHIFT."""
+def _renumbered(line):
+    """Packs the block's scalar registers: s52..s55 -> s36..s39, s68..s99 -> s40..s71 (both shifts
+    keep the alignment that register pairs, quads and octets need)."""
     import re
-    line = re.sub(r"\bs\[(\d+):(\d+)\]",
-                  lambda m: "s[%d:%d]" % (int(m.group(1)) - SHIFT, int(m.group(2)) - SHIFT), line)
-    return re.sub(r"\bs(\d+)\b", lambda m: "s%d" % (int(m.group(1)) - SHIFT), line)
+
+    def new(n):
+        n = int(n)
+        if 52 <= n <= 55:
+            return n - 16
+        assert 68 <= n <= 99, n
+        return n - 28
+    line = re.sub(r"\bs\[(\d+):(\d+)\]", lambda m: "s[%d:%d]" % (new(m.group(1)), new(m.group(2))), line)
+    return re.sub(r"\bs(\d+)\b", lambda m: "s%d" % new(m.group(1)), line)
 
 
 def render():

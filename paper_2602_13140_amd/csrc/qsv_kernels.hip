@@ -156,15 +156,17 @@ __device__ __forceinline__ unsigned to_sgpr(unsigned v) {
 #define QSV_DECL(k) float vr##k, vi##k;
 #define QSV_RV(k) [r##k] "+v"(vr##k), [i##k] "+v"(vi##k),
 
-// Byte offsets of register element k in layout s inside an LDS plane, as XORed onto the lane's
-// own address part: swz(k << s) * 4 with swz(x) = x ^ ((x >> 4) & 31).  One 64-byte row per layout.
+// Byte offsets of register elements 1, 2, 4, 8 in layout s inside an LDS plane, as XORed onto the
+// lane's own address part: swz(k << s) * 4 with swz(x) = x ^ ((x >> 4) & 31).  swz is linear over
+// XOR, so the offset of any element is the XOR of the offsets of its set bits.  One 16-byte row per
+// layout.
 struct XpOffsets {
-    unsigned v[12][16];
+    unsigned v[12][4];
     constexpr XpOffsets() : v() {
         for (int s = 0; s < 12; ++s)
-            for (int k = 0; k < 16; ++k) {
-                const unsigned x = (unsigned)k << s;
-                v[s][k] = (x ^ ((x >> 4) & 31u)) * 4u;
+            for (int j = 0; j < 4; ++j) {
+                const unsigned x = (1u << j) << s;
+                v[s][j] = (x ^ ((x >> 4) & 31u)) * 4u;
             }
     }
 };
@@ -257,9 +259,12 @@ __global__ __launch_bounds__(1 << (T - R)) void k_pass(const PassArgs a) {
     for (;;) {
         {
             float t0, t1, t2, t3, tc, m0, m1, m2, m3, m4, m5, m6, m7;
+            unsigned ba0, ba1, ba2, ba3, bb0, bb1, bb2, bb3;
 #define QSV_LOOP_OUT QSV_16(QSV_RV) [t0] "=&v"(t0), [t1] "=&v"(t1), [t2] "=&v"(t2),                 \
                      [t3] "=&v"(t3), [tc] "=&v"(tc), [m0] "=&v"(m0), [m1] "=&v"(m1), [m2] "=&v"(m2), \
                      [m3] "=&v"(m3), [m4] "=&v"(m4), [m5] "=&v"(m5), [m6] "=&v"(m6), [m7] "=&v"(m7), \
+                     [ba0] "=&v"(ba0), [ba1] "=&v"(ba1), [ba2] "=&v"(ba2), [ba3] "=&v"(ba3),       \
+                     [bb0] "=&v"(bb0), [bb1] "=&v"(bb1), [bb2] "=&v"(bb2), [bb3] "=&v"(bb3),       \
                      [opslo] "+s"(opslo), [opshi] "+s"(opshi),                                     \
                      [scur] "+s"(scur), [ldsb] "+v"(ldsb), [e0lo] "+v"(e0lo), [e0hi] "+v"(e0hi)
 #define QSV_LOOP_IN [mlo] "s"(mlo), [mhi] "s"(mhi), [olo] "s"(olo), [ohi] "s"(ohi),                 \

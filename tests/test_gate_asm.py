@@ -96,3 +96,30 @@ def test_unitary_multiply_sequences_compute_the_matrix_product():
         want = mat @ a
         got = np.array([regs["%[r2]"] + 1j * regs["%[i2]"], regs["%[r6]"] + 1j * regs["%[i6]"]])
         assert np.allclose(got, want, atol=1e-13), variant
+
+
+def test_gray_walk_visits_every_element_at_its_swizzled_offset():
+    """The transposes reach register element GRAY[i] by XORing one of four per-layout offsets onto the
+    previous address; the result must be the element's own offset swz(k << s) * 4 in every layout."""
+    swz = lambda x: x ^ ((x >> 4) & 31)
+    assert sorted(g.GRAY) == list(range(16))
+    for s in range(12):
+        basis = [swz((1 << j) << s) * 4 for j in range(4)]
+        addr = 0
+        for i in range(16):
+            if i:
+                addr ^= basis[g.GRAY_BIT[i]]
+            assert addr == swz(g.GRAY[i] << s) * 4, (s, i)
+
+
+@pytest.mark.parametrize("planes", [1, 2])
+def test_transposes_use_vector_operands_only(planes):
+    """Address arithmetic of the transposes: every v_xor takes vector registers only (a scalar operand
+    would cost 4.2 instead of 2.5 cycles per wavefront), and every element is written and read."""
+    lines = g.gen(planes)
+    xors = [ln for ln in lines if ln.startswith("v_xor_b32 %[t") and "%[b" in ln]
+    assert xors and all(re.fullmatch(r"v_xor_b32 %\[t\d\], %\[(t\d|ldsb|ldsn)\], %\[b[ab]\d\]", ln) for ln in xors)
+    for part, count in (("r", 1), ("i", 1)):
+        for k in range(16):
+            reads = [ln for ln in lines if ln.startswith("ds_read_b32 %%[%s%d]," % (part, k))]
+            assert len(reads) == count, (part, k)
