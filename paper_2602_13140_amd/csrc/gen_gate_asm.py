@@ -40,6 +40,7 @@ eight wavefronts per SIMD):
   s[96:97] operation pointer          s[98:99] next operation word
 """
 import os
+import re
 
 R = 4
 NR = 1 << R
@@ -106,6 +107,7 @@ def gen(planes=2):
     L = []
     emit = L.append
     lab = lambda name: "L_%s_%%=" % name
+    ALIGN = ".p2align 6"                          # branch targets start an instruction-fetch line
 
     def prefetch_next_word():
         emit("s_load_dwordx2 s[98:99], s[96:97], 0x8")
@@ -115,6 +117,7 @@ def gen(planes=2):
     emit("s_mov_b64 s[70:71], 0")
     emit("s_mov_b32 s68, -1")
     emit("s_load_dwordx2 s[98:99], s[96:97], 0x0")
+    emit(ALIGN)
     emit(lab("top") + ":")
     emit("s_waitcnt lgkmcnt(0)")                  # next word and prefetched matrix have landed
     emit("s_mov_b64 s[80:81], s[98:99]")
@@ -137,6 +140,7 @@ def gen(planes=2):
     emit("s_branch " + lab("exit"))
 
     # ---- 2x2 unitary on register bit a; matrix = (arg == ovrid) ? *ovr : mbase[arg]
+    emit(ALIGN)
     emit(lab("u") + ":")
     emit("s_bfe_u32 s84, s80, 0x80010")          # b: matrix depends on the state row
     emit("s_and_b32 s84, s84, %[nonuni]")        # ... and rows differ per lane: not ours
@@ -171,8 +175,6 @@ def gen(planes=2):
     emit("s_load_dwordx8 s[72:79], s[70:71], 0x0")
     emit(lab("unopf") + ":")
     prefetch_next_word()
-    for k in range(8):                            # the multiply sequences read vector registers only
-        emit("v_mov_b32 %%[m%d], s%d" % (k, 88 + k))
     # pick the multiply sequence from the zeros the matrix builder stored
     emit("s_cmp_lg_u32 s89, 0")
     emit("s_cbranch_scc1 " + lab("ug"))
@@ -181,11 +183,17 @@ def gen(planes=2):
     emit("s_cmp_eq_u32 s93, 0")
     emit("s_cbranch_scc1 " + lab("uc"))
     for variant in "argc":
+        emit(ALIGN)
         emit(lab("u" + variant) + ":")
+        # the multiply sequences read vector registers only: stage the entries this variant uses
+        used = sorted({int(m) for ln in u_pair(0, 1, variant) for m in re.findall(r"%\[m(\d)\]", ln)})
+        for k in used:
+            emit("v_mov_b32 %%[m%d], s%d" % (k, 88 + k))
         for j in range(R - 1):
             emit("s_cmp_eq_u32 s83, %d" % j)
             emit("s_cbranch_scc1 " + lab("u%s%d" % (variant, j)))
         for j in reversed(range(R)):
+            emit(ALIGN)
             emit(lab("u%s%d" % (variant, j)) + ":")
             for i in range(NR):
                 if i & (1 << j):
@@ -194,6 +202,7 @@ def gen(planes=2):
             emit("s_branch " + lab("next"))
 
     # ---- CNOT, control = register bit b, target = register bit a
+    emit(ALIGN)
     emit(lab("cxr") + ":")
     prefetch_next_word()
     emit("s_bfe_u32 s84, s80, 0x80010")
@@ -205,6 +214,7 @@ def gen(planes=2):
         emit("s_cbranch_scc1 " + lab("x%d%d" % (jt, jc)))
     emit("s_branch " + lab("next"))               # unknown combination: no-op (never planned)
     for jt, jc in combos:
+        emit(ALIGN)
         emit(lab("x%d%d" % (jt, jc)) + ":")
         for i in range(NR):
             if (i & (1 << jc)) and not (i & (1 << jt)):
@@ -212,6 +222,7 @@ def gen(planes=2):
         emit("s_branch " + lab("next"))
 
     # ---- CNOT, control = index bit b outside the register run (lane-dependent), target = a
+    emit(ALIGN)
     emit(lab("cxd") + ":")
     prefetch_next_word()
     emit("s_bfe_u32 s86, s80, 0x80010")
@@ -226,6 +237,7 @@ def gen(planes=2):
         emit("s_cmp_eq_u32 s83, %d" % j)
         emit("s_cbranch_scc1 " + lab("d%d" % j))
     for j in reversed(range(R)):
+        emit(ALIGN)
         emit(lab("d%d" % j) + ":")
         for i in range(NR):
             if not (i & (1 << j)):
@@ -242,6 +254,7 @@ def gen(planes=2):
         return "v_xor_b32 %%[%s%d], 0x80000000, %%[%s%d]" % (part, k, part, k)
 
     # ---- CZ between register bits a < b: the amplitudes with both bits set change sign
+    emit(ALIGN)
     emit(lab("zr") + ":")
     prefetch_next_word()
     emit("s_bfe_u32 s84, s80, 0x80010")
@@ -262,6 +275,7 @@ def gen(planes=2):
 
     # ---- CZ between register bit a and index bit b outside the run: lanes whose bit b is set
     # flip the sign of the amplitudes with register bit a set
+    emit(ALIGN)
     emit(lab("zm") + ":")
     prefetch_next_word()
     emit("s_bfe_u32 s86, s80, 0x80010")
@@ -285,6 +299,7 @@ def gen(planes=2):
 
     # ---- CZ rungs (mask in arg, bit q = rung (q, q+1)) between index bits outside the run: one
     # sign per lane, parity of popcount(e0 & (e0 >> 1) & mask); the mask lies below bit 31
+    emit(ALIGN)
     emit(lab("zl") + ":")
     prefetch_next_word()
     emit("v_lshrrev_b32 %[t0], 1, %[e0lo]")
@@ -352,6 +367,7 @@ def gen(planes=2):
         emit("v_lshrrev_b32 %[t1], s84, %[t1]")
         emit("v_or_b32 %[e0hi], %[tbhi], %[t1]")
 
+    emit(ALIGN)
     emit(lab("xp") + ":")
     prefetch_next_word()
     emit("s_cmp_eq_u32 s68, %[scur]")
@@ -426,6 +442,7 @@ def gen(planes=2):
         emit("v_mov_b32 %[ldsb], %[ldsn]")
         emit("s_branch " + lab("next"))           # the wait at the top covers the reads
 
+    emit(ALIGN)
     emit(lab("next") + ":")
     emit("s_add_u32 s96, s96, 8")
     emit("s_addc_u32 s97, s97, 0")
