@@ -28,8 +28,8 @@ matrix in execution order, so consecutive unitaries read consecutive 32-byte mat
 next one can be prefetched (the table is padded by one entry for the last prefetch).
 
 Fixed scalar registers (declared as clobbers; the text below names them s52..s55 and s68..s99,
-_renumbered() packs them into s36..s71 so that the kernel stays below 96 scalar registers, i.e.
-eight wavefronts per SIMD):
+_renumbered() packs them into s36..s71, which leaves the compiler enough scalar registers to do
+without spills; the kernel runs seven wavefronts per SIMD, eight measured slower):
   s[52:55] landing place of a layout's four offsets on their way to vector registers
   s68 layout whose offsets sit in %[ba0..3] (-1: none, the compiler may have used them since)
   s69 one-plane transposes: the exchange crosses wavefronts
@@ -53,8 +53,9 @@ GRAY_BIT = [0] + [(i & -i).bit_length() - 1 for i in range(1, NR)]   # bit that 
 def u_pair(a, b, variant="g"):
     """(r_a,i_a) has the target bit 0, (r_b,i_b) has it 1; matrix m0..m7 = vector copies of
     s88..s95 = (m00r, m00i, m01r, m01i, m10r, m10i, m11r, m11i): a vector instruction with a scalar
-    operand issues at 4.2 cycles per wavefront on this chip, one with vector operands only at 2.5.  Four interleaved chains; the last step of
-    each overwrites an input that is dead by then.  Variants leave out the products with
+    operand issues at 4.2 cycles per wavefront on this chip, one with vector operands only at 2.5.
+    Four interleaved chains; the last step of each overwrites an input that is dead by then.
+    Variants leave out the products with
     imaginary parts that are stored as exact zeros: "g" none (16 instructions), "a" m00i (14),
     "r" m00i and m01i (first row real, 12), "c" m00i and m10i (first column real, 12)."""
     ra, ia, rb, ib = "%%[r%d]" % a, "%%[i%d]" % a, "%%[r%d]" % b, "%%[i%d]" % b
