@@ -236,7 +236,15 @@ __global__ __launch_bounds__(1 << (T - R)) void k_pass(const PassArgs a) {
         const long long ds = (long long)(((u64)to_sgpr((unsigned)(d >> 32)) << 32) | to_sgpr((unsigned)d));
         ld = a.src + ds;
     }
-    if (full && off32) {
+    if (full && off32 && ld == a.state) {
+        // the common case, written against the kernel argument itself: the compiler then keeps the
+        // per-element base in scalar registers and spends no vector arithmetic on addresses
+        const unsigned lane_byte = (unsigned)expand(tau0) * 8u;
+#define QSV_LD(k) { const char* bp = (const char*)(a.state + (tile_base | expand((unsigned)k << scur))); \
+                    const float2 v = *(const float2*)(bp + lane_byte); vr##k = v.x; vi##k = v.y; }
+        QSV_16(QSV_LD)
+#undef QSV_LD
+    } else if (full && off32) {
         const unsigned lane_byte = (unsigned)expand(tau0) * 8u;
 #define QSV_LD(k) { const char* bp = (const char*)(ld + (tile_base | expand((unsigned)k << scur))); \
                     const float2 v = *(const float2*)(bp + lane_byte); vr##k = v.x; vi##k = v.y; }
