@@ -28,8 +28,8 @@ matrix in execution order, so consecutive unitaries read consecutive 32-byte mat
 next one can be prefetched (the table is padded by one entry for the last prefetch).
 
 Fixed scalar registers (declared as clobbers; the text below names them s52..s55 and s68..s99,
-_renumbered() packs them into s36..s71, which leaves the compiler enough scalar registers to do
-without spills; the kernel runs seven wavefronts per SIMD, eight measured slower):
+_renumbered() packs them into s36..s71, which leaves the compiler enough of the 96 scalar registers
+the kernel is limited to (eight wavefronts per SIMD) to do without spills):
   s[52:55] landing place of a layout's four offsets on their way to vector registers
   s68 layout whose offsets sit in %[ba0..3] (-1: none, the compiler may have used them since)
   s69 one-plane transposes: the exchange crosses wavefronts

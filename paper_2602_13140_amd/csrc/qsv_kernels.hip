@@ -180,7 +180,11 @@ __device__ __attribute__((aligned(64))) const XpOffsets k_xp_tab = XpOffsets();
 // gates, sign flips and LDS transposes in place until it meets an operation it does not handle
 // (a per-lane unitary, or the end), which the C++ loop handles before re-entering it.
 template <int T, bool PERLANE, int PLANES>
-__global__ __launch_bounds__(1 << (T - R)) void k_pass(const PassArgs a) {
+// 96 scalar registers (the interpreter pins 36 of them) allow eight wavefronts per SIMD; the main
+// variant needs no scalar spills for that (the per-lane-matrix variant has some, and is limited by
+// its vector registers anyway).
+__global__ __launch_bounds__(1 << (T - R)) __attribute__((amdgpu_num_sgpr(96)))
+void k_pass(const PassArgs a) {
     // PLANES XOR-swizzled planes of 2^T floats each (real and imaginary parts at once, or one
     // after the other through a single plane, which halves the LDS a workgroup holds); see the
     // interpreter's generator.  The segment must start at LDS byte 0 (no static LDS here).
