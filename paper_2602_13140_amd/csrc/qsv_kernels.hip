@@ -834,10 +834,20 @@ __global__ __launch_bounds__(256) void k_marginal_block(const float2* state, int
     const u64 free_mask = ((1ull << n) - 1) & ~mask;
     const float2* a = state + (row << n);
     double acc = 0.0;
+    if ((free_mask & (CHUNK - 1)) == (u64)(CHUNK - 1)) {
+        // no mask bit among the low 12 index bits: a block's elements are contiguous
+        const float2* ab = a + (fixed | deposit(blk * CHUNK, free_mask, n));
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+            const u64 lo = (u64)i * 256 + threadIdx.x;
+            if (blk * CHUNK + lo < sub) acc += (double)prob32(ab[lo]);
+        }
+    } else {
 #pragma unroll 4
-    for (int i = 0; i < 16; ++i) {
-        const u64 j = blk * CHUNK + (u64)i * 256 + threadIdx.x;
-        if (j < sub) acc += (double)prob32(a[fixed | deposit(j, free_mask, n)]);
+        for (int i = 0; i < 16; ++i) {
+            const u64 j = blk * CHUNK + (u64)i * 256 + threadIdx.x;
+            if (j < sub) acc += (double)prob32(a[fixed | deposit(j, free_mask, n)]);
+        }
     }
     const double tot = block_sum256(acc, sm);
     if (threadIdx.x == 0) partial[id] = tot;
