@@ -209,7 +209,10 @@ def gen(planes=2):
     emit("s_bfe_u32 s84, s80, 0x80010")
     emit("s_lshl_b32 s85, s83, 2")
     emit("s_add_u32 s84, s84, s85")
-    combos = [(jt, jc) for jt in range(R) for jc in range(R) if jt != jc]
+    # searched in this order: first the neighbours a CNOT ring produces (target just above the
+    # control), since every compare is an instruction that competes with the vector ones for issue
+    combos = [(jc + 1, jc) for jc in range(R - 1)]
+    combos += [(jt, jc) for jt in range(R) for jc in range(R) if jt != jc and (jt, jc) not in combos]
     for jt, jc in combos:
         emit("s_cmp_eq_u32 s84, %d" % (jt * 4 + jc))
         emit("s_cbranch_scc1 " + lab("x%d%d" % (jt, jc)))
