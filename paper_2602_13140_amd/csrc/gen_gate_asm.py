@@ -27,16 +27,17 @@ Operation word: x = kind | a<<8 | b<<16 | c<<24, y = arg.  For a unitary, arg is
 matrix in execution order, so consecutive unitaries read consecutive 32-byte matrices and the
 next one can be prefetched (the table is padded by one entry for the last prefetch).
 
-Fixed scalar registers (declared as clobbers; the text below names them s52..s55 and s68..s99,
-_renumbered() packs them into s36..s71, which leaves the compiler enough of the 96 scalar registers
+Fixed scalar registers (declared as clobbers; the text below names them s52..s56 and s68..s99,
+_renumbered() packs them into s36..s72, which leaves the compiler enough of the 96 scalar registers
 the kernel is limited to (eight wavefronts per SIMD) to do without spills):
   s[52:55] landing place of a layout's four offsets on their way to vector registers
   s68 layout whose offsets sit in %[ba0..3] (-1: none, the compiler may have used them since)
   s69 one-plane transposes: the exchange crosses wavefronts
-  s[70:71] address whose matrix sits in the prefetch buffer (0 = none)
-  s[72:79] prefetch buffer            s[80:81] current operation word
-  s82 kind   s83 field a              s[84:85] scratch / saved exec
-  s[86:87] matrix address             s[88:95] matrix in use
+  s56 index (in execution order) of the matrix in s[72:79], -1: none; s[70:71] its address
+  s[72:79] matrix of the stream: the one in use until its vector copies are made, then the next
+  s[80:81] current operation word     s82 kind   s83 field a
+  s[84:85] scratch / saved exec       s[86:87] scratch address
+  s[88:95] shifted matrix of a gradient row
   s[96:97] operation pointer          s[98:99] next operation word
 """
 import os
@@ -45,7 +46,7 @@ import re
 R = 4
 NR = 1 << R
 OP_XPOSE, OP_U, OP_CX_REG, OP_CX_DYN, OP_CZ_REG, OP_CZ_MIX, OP_CZ_LANE = 2, 3, 4, 5, 6, 7, 8
-FIRST_SGPR, LAST_SGPR = 36, 71      # after _renumbered()
+FIRST_SGPR, LAST_SGPR = 36, 72      # after _renumbered()
 GRAY = [i ^ (i >> 1) for i in range(NR)]        # element visited at step i
 GRAY_BIT = [0] + [(i & -i).bit_length() - 1 for i in range(1, NR)]   # bit that changes on entering step i
 
@@ -103,7 +104,9 @@ def swap_pair(a, b):
     return ["v_swap_b32 %%[r%d], %%[r%d]" % (a, b), "v_swap_b32 %%[i%d], %%[i%d]" % (a, b)]
 
 
-def gen(planes=2):
+def gen(planes=2, perlane=False):
+    """perlane: the variant for kernels whose tiles hold several state rows, where a unitary whose
+    matrix depends on the row is left to the caller."""
     assert planes in (1, 2)
     L = []
     emit = L.append
@@ -115,10 +118,14 @@ def gen(planes=2):
 
     emit("s_mov_b32 s96, %[opslo]")
     emit("s_mov_b32 s97, %[opshi]")
-    emit("s_mov_b64 s[70:71], 0")
+    emit("s_mov_b32 s56, -1")                     # no matrix prefetched yet
     emit("s_mov_b32 s68, -1")
     emit("s_load_dwordx2 s[98:99], s[96:97], 0x0")
+    emit("s_branch " + lab("top"))
     emit(ALIGN)
+    emit(lab("next") + ":")                       # falls through to the top: one jump per operation
+    emit("s_add_u32 s96, s96, 8")
+    emit("s_addc_u32 s97, s97, 0")
     emit(lab("top") + ":")
     emit("s_waitcnt lgkmcnt(0)")                  # next word and prefetched matrix have landed
     emit("s_mov_b64 s[80:81], s[98:99]")
@@ -140,48 +147,29 @@ def gen(planes=2):
     emit("s_cbranch_scc1 " + lab("zl"))
     emit("s_branch " + lab("exit"))
 
-    # ---- 2x2 unitary on register bit a; matrix = (arg == ovrid) ? *ovr : mbase[arg]
+    # ---- 2x2 unitary on register bit a; matrix = (arg == ovrid) ? *ovr : mbase[arg].
+    # s[72:79] holds the matrix of the stream with index s56 (-1: none), s[70:71] its address; the
+    # multiply sequences read vector copies, so the buffer is free for the next matrix of the stream
+    # as soon as the copies are made.  Every scalar instruction here competes with the vector ones
+    # for issue slots, hence the short common path: two compares, the variant and bit dispatch.
     emit(ALIGN)
     emit(lab("u") + ":")
-    emit("s_bfe_u32 s84, s80, 0x80010")          # b: matrix depends on the state row
-    emit("s_and_b32 s84, s84, %[nonuni]")        # ... and rows differ per lane: not ours
-    emit("s_cmp_lg_u32 s84, 0")
-    emit("s_cbranch_scc1 " + lab("exit"))
+    if perlane:
+        emit("s_bfe_u32 s84, s80, 0x80010")      # b: matrix depends on the state row
+        emit("s_and_b32 s84, s84, %[nonuni]")    # ... and rows differ per lane: not ours
+        emit("s_cmp_lg_u32 s84, 0")
+        emit("s_cbranch_scc1 " + lab("exit"))
     emit("s_cmp_eq_u32 s81, %[ovrid]")
     emit("s_cbranch_scc1 " + lab("uovr"))
-    emit("s_lshl_b32 s84, s81, 5")
-    emit("s_mov_b32 s86, %[mlo]")
-    emit("s_mov_b32 s87, %[mhi]")
-    emit("s_add_u32 s86, s86, s84")
-    emit("s_addc_u32 s87, s87, 0")
-    emit("s_cmp_eq_u64 s[86:87], s[70:71]")
+    emit("s_cmp_eq_u32 s81, s56")
     emit("s_cbranch_scc0 " + lab("uld"))
-    emit("s_mov_b64 s[88:89], s[72:73]")          # prefetched: move into the working set
-    emit("s_mov_b64 s[90:91], s[74:75]")
-    emit("s_mov_b64 s[92:93], s[76:77]")
-    emit("s_mov_b64 s[94:95], s[78:79]")
-    emit("s_branch " + lab("uhave"))
-    emit(lab("uovr") + ":")
-    emit("s_mov_b32 s86, %[olo]")
-    emit("s_mov_b32 s87, %[ohi]")
-    emit("s_load_dwordx8 s[88:95], s[86:87], 0x0")
-    emit("s_waitcnt lgkmcnt(0)")
-    emit("s_branch " + lab("unopf"))              # the shifted matrix is not part of the stream
-    emit(lab("uld") + ":")
-    emit("s_load_dwordx8 s[88:95], s[86:87], 0x0")
-    emit("s_waitcnt lgkmcnt(0)")
     emit(lab("uhave") + ":")
-    emit("s_add_u32 s70, s86, 32")                # prefetch the next matrix of the stream
-    emit("s_addc_u32 s71, s87, 0")
-    emit("s_load_dwordx8 s[72:79], s[70:71], 0x0")
-    emit(lab("unopf") + ":")
-    prefetch_next_word()
     # pick the multiply sequence from the zeros the matrix builder stored
-    emit("s_cmp_lg_u32 s89, 0")
+    emit("s_cmp_lg_u32 s73, 0")
     emit("s_cbranch_scc1 " + lab("ug"))
-    emit("s_cmp_eq_u32 s91, 0")
+    emit("s_cmp_eq_u32 s75, 0")
     emit("s_cbranch_scc1 " + lab("ur"))
-    emit("s_cmp_eq_u32 s93, 0")
+    emit("s_cmp_eq_u32 s77, 0")
     emit("s_cbranch_scc1 " + lab("uc"))
     for variant in "argc":
         emit(ALIGN)
@@ -189,7 +177,14 @@ def gen(planes=2):
         # the multiply sequences read vector registers only: stage the entries this variant uses
         used = sorted({int(m) for ln in u_pair(0, 1, variant) for m in re.findall(r"%\[m(\d)\]", ln)})
         for k in used:
-            emit("v_mov_b32 %%[m%d], s%d" % (k, 88 + k))
+            emit("v_mov_b32 %%[m%d], s%d" % (k, 72 + k))
+        emit("s_add_u32 s70, s70, 32")            # prefetch the next matrix of the stream
+        emit("s_addc_u32 s71, s71, 0")
+        emit("s_add_u32 s56, s56, 1")
+        emit("s_load_dwordx8 s[72:79], s[70:71], 0x0")
+        if variant == "g":
+            emit(lab("ugj") + ":")                # the shifted matrix of a gradient row joins here
+        prefetch_next_word()
         for j in range(R - 1):
             emit("s_cmp_eq_u32 s83, %d" % j)
             emit("s_cbranch_scc1 " + lab("u%s%d" % (variant, j)))
@@ -201,6 +196,24 @@ def gen(planes=2):
                     continue
                 L.extend(u_pair(i, i | (1 << j), variant))
             emit("s_branch " + lab("next"))
+    # not the prefetched one (first unitary of a tile, or the one after a shifted matrix): fetch it
+    emit(lab("uld") + ":")
+    emit("s_lshl_b32 s84, s81, 5")
+    emit("s_add_u32 s70, %[mlo], s84")
+    emit("s_addc_u32 s71, %[mhi], 0")
+    emit("s_mov_b32 s56, s81")
+    emit("s_load_dwordx8 s[72:79], s[70:71], 0x0")
+    emit("s_waitcnt lgkmcnt(0)")
+    emit("s_branch " + lab("uhave"))
+    # the shifted matrix of a gradient row: not part of the stream, general multiply sequence
+    emit(lab("uovr") + ":")
+    emit("s_mov_b32 s86, %[olo]")
+    emit("s_mov_b32 s87, %[ohi]")
+    emit("s_load_dwordx8 s[88:95], s[86:87], 0x0")
+    emit("s_waitcnt lgkmcnt(0)")
+    for k in range(8):
+        emit("v_mov_b32 %%[m%d], s%d" % (k, 88 + k))
+    emit("s_branch " + lab("ugj"))
 
     # ---- CNOT, control = register bit b, target = register bit a
     emit(ALIGN)
@@ -446,11 +459,6 @@ def gen(planes=2):
         emit("v_mov_b32 %[ldsb], %[ldsn]")
         emit("s_branch " + lab("next"))           # the wait at the top covers the reads
 
-    emit(ALIGN)
-    emit(lab("next") + ":")
-    emit("s_add_u32 s96, s96, 8")
-    emit("s_addc_u32 s97, s97, 0")
-    emit("s_branch " + lab("top"))
     emit(lab("exit") + ":")                       # reached right after the wait: nothing in flight
     emit("s_mov_b32 %[opslo], s96")
     emit("s_mov_b32 %[opshi], s97")
@@ -459,13 +467,15 @@ def gen(planes=2):
 
 def _renumbered(line):
     """Packs the block's scalar registers: s52..s55 -> s36..s39, s68..s99 -> s40..s71 (both shifts
-    keep the alignment that register pairs, quads and octets need)."""
+    keep the alignment that register pairs, quads and octets need), s56 -> s72."""
     import re
 
     def new(n):
         n = int(n)
         if 52 <= n <= 55:
             return n - 16
+        if n == 56:
+            return 72
         assert 68 <= n <= 99, n
         return n - 28
     line = re.sub(r"\bs\[(\d+):(\d+)\]", lambda m: "s[%d:%d]" % (new(m.group(1)), new(m.group(2))), line)
@@ -476,13 +486,15 @@ def render():
     out = ["// Generated by gen_gate_asm.py -- do not edit by hand.",
            "// Inline-assembly gate interpreter of the fused pass kernel; see the generator for the",
            "// register map and the reason it is assembly.  _2P: transposes through two LDS planes",
-           "// (real, imaginary) at once; _1P: through one plane, real parts first.",
+           "// (real, imaginary) at once; _1P: through one plane, real parts first.  _ROWS: for tiles that",
+           "// hold several state rows (returns at a unitary whose matrix depends on the row).",
            "#pragma once"]
     for planes in (2, 1):
-        out.append("#define QSV_GATE_LOOP_ASM_%dP \\" % planes)
-        for ln in gen(planes):
-            out.append('    "%s\\n\\t" \\' % ln)
-        out.append('    ""')
+        for perlane in (False, True):
+            out.append("#define QSV_GATE_LOOP_ASM_%dP%s \\" % (planes, "_ROWS" if perlane else ""))
+            for ln in gen(planes, perlane):
+                out.append('    "%s\\n\\t" \\' % ln)
+            out.append('    ""')
     regs = ", ".join('"s%d"' % i for i in range(FIRST_SGPR, LAST_SGPR + 1))
     out.append("#define QSV_GATE_LOOP_CLOBBERS %s, \"vcc\", \"scc\", \"memory\"" % regs)
     return "\n".join(out) + "\n"

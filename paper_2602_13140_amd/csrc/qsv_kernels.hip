@@ -153,6 +153,13 @@ __device__ __forceinline__ unsigned to_sgpr(unsigned v) {
 // array the compiler turns them into one 16-wide vector value and copies the whole tuple around
 // the asm block.  QSV_16 applies a statement macro to every index.
 #define QSV_16(X) X(0) X(1) X(2) X(3) X(4) X(5) X(6) X(7) X(8) X(9) X(10) X(11) X(12) X(13) X(14) X(15)
+// The same 16 indices in Gray-code order, with the register bit that changes on the way in and the
+// direction (+: the bit turns on): X(k, bit, sign).  The address of element k of a tile then follows
+// from the previous one by adding or subtracting one of four strides, two scalar instructions
+// instead of the nine it takes to build it from k (scalar instructions compete with the vector
+// ones for issue slots).  The walk starts from "element 0 minus stride 0".
+#define QSV_16G(X) X(0, 0, +) X(1, 0, +) X(3, 1, +) X(2, 0, -) X(6, 2, +) X(7, 0, +) X(5, 1, -) X(4, 0, -) \
+                   X(12, 3, +) X(13, 0, +) X(15, 1, +) X(14, 0, -) X(10, 2, -) X(11, 0, +) X(9, 1, -) X(8, 0, -)
 #define QSV_DECL(k) float vr##k, vi##k;
 #define QSV_RV(k) [r##k] "+v"(vr##k), [i##k] "+v"(vi##k),
 
@@ -244,9 +251,12 @@ void k_pass(const PassArgs a) {
         // the common case, written against the kernel argument itself: the compiler then keeps the
         // per-element base in scalar registers and spends no vector arithmetic on addresses
         const unsigned lane_byte = (unsigned)expand(tau0) * 8u;
-#define QSV_LD(k) { const char* bp = (const char*)(a.state + (tile_base | expand((unsigned)k << scur))); \
+        const u64 st0 = expand(1u << scur) * 8u, st1 = expand(2u << scur) * 8u, st2 = expand(4u << scur) * 8u,
+                  st3 = expand(8u << scur) * 8u;
+        const char* bp = (const char*)(a.state + tile_base) - st0;
+#define QSV_LD(k, bit, sign) { bp = bp sign st##bit; \
                     const float2 v = *(const float2*)(bp + lane_byte); vr##k = v.x; vi##k = v.y; }
-        QSV_16(QSV_LD)
+        QSV_16G(QSV_LD)
 #undef QSV_LD
     } else if (full && off32) {
         const unsigned lane_byte = (unsigned)expand(tau0) * 8u;
@@ -283,10 +293,23 @@ void k_pass(const PassArgs a) {
                     [ovrid] "s"(ovr_id), [nonuni] "s"(nonuni), [thr] "v"(thr), [c] "s"(sc_c),       \
                     [w] "s"(sc_w), [cmask] "s"(sc_cmask), [tblo] "s"(tblo), [tbhi] "s"(tbhi),       \
                     [tablo] "s"(tablo), [tabhi] "s"(tabhi)
-            if constexpr (PLANES == 2) {
+            // four texts: two or one LDS plane, and whether a unitary may have to be left to the C++
+            // code below (several state rows per tile with row-dependent matrices)
+            if constexpr (PLANES == 2 && PERLANE) {
+                asm volatile(QSV_GATE_LOOP_ASM_2P_ROWS
+                             : QSV_LOOP_OUT
+                             : QSV_LOOP_IN, [plane4] "n"(PLANE * 4u), [pl64] "n"(PLANE / 64u)
+                             : QSV_GATE_LOOP_CLOBBERS);
+            } else if constexpr (PLANES == 2) {
                 asm volatile(QSV_GATE_LOOP_ASM_2P
                              : QSV_LOOP_OUT
                              : QSV_LOOP_IN, [plane4] "n"(PLANE * 4u), [pl64] "n"(PLANE / 64u)
+                             : QSV_GATE_LOOP_CLOBBERS);
+            } else if constexpr (PERLANE) {
+                unsigned ldsn;
+                asm volatile(QSV_GATE_LOOP_ASM_1P_ROWS
+                             : QSV_LOOP_OUT, [ldsn] "=&v"(ldsn)
+                             : QSV_LOOP_IN
                              : QSV_GATE_LOOP_CLOBBERS);
             } else {
                 unsigned ldsn;
@@ -350,15 +373,20 @@ void k_pass(const PassArgs a) {
         // States much larger than the last-level cache: nontemporal stores, so that the lines written
         // now (read again only a whole pass later) do not displace what the pass still has to read.
         const unsigned lane_byte = (unsigned)(e0 ^ tile_base) * 8u;   // the lane's own index bits
-#define QSV_ST(k) { char* bp = (char*)(a.state + (tile_base | expand((unsigned)k << scur))); \
+        const u64 st0 = expand(1u << scur) * 8u, st1 = expand(2u << scur) * 8u, st2 = expand(4u << scur) * 8u,
+                  st3 = expand(8u << scur) * 8u;
+        char* bp = (char*)(a.state + tile_base) - st0;
+#define QSV_ST(k, bit, sign) { bp = bp sign st##bit; \
                     f32x2 v; v.x = vr##k; v.y = vi##k; __builtin_nontemporal_store(v, (f32x2*)(bp + lane_byte)); }
-        QSV_16(QSV_ST)
+        QSV_16G(QSV_ST)
 #undef QSV_ST
     } else if (full && off32) {
         const unsigned lane_byte = (unsigned)(e0 ^ tile_base) * 8u;
-#define QSV_ST(k) { char* bp = (char*)(a.state + (tile_base | expand((unsigned)k << scur))); \
-                    *(float2*)(bp + lane_byte) = make_float2(vr##k, vi##k); }
-        QSV_16(QSV_ST)
+        const u64 st0 = expand(1u << scur) * 8u, st1 = expand(2u << scur) * 8u, st2 = expand(4u << scur) * 8u,
+                  st3 = expand(8u << scur) * 8u;
+        char* bp = (char*)(a.state + tile_base) - st0;
+#define QSV_ST(k, bit, sign) { bp = bp sign st##bit; *(float2*)(bp + lane_byte) = make_float2(vr##k, vi##k); }
+        QSV_16G(QSV_ST)
 #undef QSV_ST
     } else if (full) {
 #define QSV_ST(k) a.state[e0 | expand((unsigned)k << scur)] = make_float2(vr##k, vi##k);

@@ -6,18 +6,22 @@ import re
 
 from paper_2602_13140_amd.csrc import gen_gate_asm as g
 
-INTENDED_FALLTHROUGH = {"L_top", "L_uhave", "L_unopf", "L_ua", "L_ua3", "L_ur3", "L_ug3", "L_uc3",
+INTENDED_FALLTHROUGH = {"L_top", "L_uhave", "L_ugj", "L_ua", "L_ua3", "L_ur3", "L_ug3", "L_uc3",
                         "L_d3", "L_cxdone", "L_xphave", "L_xpw", "L_xpr", "L_xpw2", "L_xpr2", "L_zm3", "L_zdone"}
 
 
 import pytest
 
-PLANES = pytest.mark.parametrize("planes", [1, 2])
+PLANES = pytest.mark.parametrize("planes", [1, 2, -1, -2])      # negative: the several-rows-per-tile variant
+
+
+def gen(planes):
+    return g.gen(abs(planes), planes < 0)
 
 
 def code_lines(planes):
     """The generated instructions and labels, without assembler directives (alignment)."""
-    return [ln for ln in g.gen(planes) if not ln.startswith(".")]
+    return [ln for ln in gen(planes) if not ln.startswith(".")]
 
 
 @PLANES
@@ -135,6 +139,12 @@ def test_branch_targets_reached_by_jumps_are_aligned(planes):
     """Where the code of the operations sits relative to the instruction-fetch lines changed the run
     time of the whole kernel by 5 to 9 % between two otherwise equal builds; the handlers' entry
     points are therefore aligned to 64 bytes."""
-    lines = g.gen(planes)
-    for name in ("L_top_%=:", "L_next_%=:", "L_u_%=:", "L_cxr_%=:", "L_cxd_%=:", "L_xp_%=:", "L_ug3_%=:", "L_x10_%=:"):
+    lines = gen(planes)
+    for name in ("L_next_%=:", "L_u_%=:", "L_cxr_%=:", "L_cxd_%=:", "L_xp_%=:", "L_ug3_%=:", "L_x10_%=:"):
         assert lines[lines.index(name) - 1] == ".p2align 6", name
+
+
+def test_row_dependent_exit_only_in_the_variant_for_several_rows_per_tile():
+    for planes in (1, 2):
+        assert not any("%[nonuni]" in ln for ln in g.gen(planes, False))
+        assert any("%[nonuni]" in ln for ln in g.gen(planes, True))
