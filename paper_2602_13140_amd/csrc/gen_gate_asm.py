@@ -45,7 +45,10 @@ import re
 
 R = 4
 NR = 1 << R
-OP_XPOSE, OP_U, OP_CX_REG, OP_CX_DYN, OP_CZ_REG, OP_CZ_MIX, OP_CZ_LANE = 2, 3, 4, 5, 6, 7, 8
+OP_XPOSE, OP_U, OP_CX_REG, OP_CX_DYN, OP_CZ_REG, OP_CZ_MIX, OP_CZ_LANE, OP_CX_CHAIN = 2, 3, 4, 5, 6, 7, 8, 9
+# the chains of CNOTs between neighbouring register bits, numbered as in the planner:
+# (direction, control of the first, count); direction 0: controls go up, 1: down
+CX_CHAINS = [(0, 0, 3), (1, 2, 3), (0, 0, 2), (0, 1, 2), (1, 2, 2), (1, 1, 2)]
 FIRST_SGPR, LAST_SGPR = 36, 72      # after _renumbered()
 GRAY = [i ^ (i >> 1) for i in range(NR)]        # element visited at step i
 GRAY_BIT = [0] + [(i & -i).bit_length() - 1 for i in range(1, NR)]   # bit that changes on entering step i
@@ -100,6 +103,34 @@ def u_pair(a, b, variant="g"):
     ]
 
 
+def chain_swaps(direction, first, count):
+    """The chain's CNOTs (control c, target c + 1) as one permutation of the 16 register elements,
+    done with the fewest instructions: a cycle of k elements takes k - 1 swaps.  (Moves through a
+    temporary take k + 1; they are cheaper per instruction but what the heavy passes run out of is
+    issue slots: measured, the move form was 0.6 % slower on the 26-qubit configuration.)"""
+    src = list(range(NR))                  # src[i]: which old element ends up in place i
+    for k in range(count):
+        c = first + k if direction == 0 else first - k
+        t = c + 1
+        for i in range(NR):
+            if (i >> c) & 1 and not (i >> t) & 1:
+                j = i | (1 << t)
+                src[i], src[j] = src[j], src[i]
+    out, seen = [], [False] * NR
+    for s0 in range(NR):
+        if seen[s0] or src[s0] == s0:
+            continue
+        cyc, cur = [], s0
+        while not seen[cur]:
+            seen[cur] = True
+            cyc.append(cur)
+            cur = src[cur]
+        # place cyc[k] must receive the old content of cyc[k+1]: swap neighbours along the cycle
+        for a, b in zip(cyc, cyc[1:]):
+            out.extend(swap_pair(a, b))
+    return out
+
+
 def swap_pair(a, b):
     return ["v_swap_b32 %%[r%d], %%[r%d]" % (a, b), "v_swap_b32 %%[i%d], %%[i%d]" % (a, b)]
 
@@ -133,6 +164,8 @@ def gen(planes=2, perlane=False):
     emit("s_bfe_u32 s83, s80, 0x80008")
     emit("s_cmp_eq_u32 s82, %d" % OP_U)
     emit("s_cbranch_scc1 " + lab("u"))
+    emit("s_cmp_eq_u32 s82, %d" % OP_CX_CHAIN)
+    emit("s_cbranch_scc1 " + lab("cxc"))
     emit("s_cmp_eq_u32 s82, %d" % OP_CX_REG)
     emit("s_cbranch_scc1 " + lab("cxr"))
     emit("s_cmp_eq_u32 s82, %d" % OP_CX_DYN)
@@ -236,6 +269,19 @@ def gen(planes=2, perlane=False):
         for i in range(NR):
             if (i & (1 << jc)) and not (i & (1 << jt)):
                 L.extend(swap_pair(i, i | (1 << jt)))
+        emit("s_branch " + lab("next"))
+
+    # ---- chain of CNOTs between neighbouring register bits: arg numbers the chain
+    emit(ALIGN)
+    emit(lab("cxc") + ":")
+    prefetch_next_word()
+    for k in range(len(CX_CHAINS) - 1):
+        emit("s_cmp_eq_u32 s81, %d" % k)
+        emit("s_cbranch_scc1 " + lab("c%d" % k))
+    for k in reversed(range(len(CX_CHAINS))):
+        emit(ALIGN)
+        emit(lab("c%d" % k) + ":")
+        L.extend(chain_swaps(*CX_CHAINS[k]))
         emit("s_branch " + lab("next"))
 
     # ---- CNOT, control = index bit b outside the register run (lane-dependent), target = a

@@ -252,6 +252,34 @@ void mark_transposes(std::vector<Op>& ops, size_t begin) {
     }
 }
 
+// Two or three consecutive CNOTs between neighbouring register bits (what a CNOT ring leaves inside
+// a run) become one OP_CX_CHAIN: one operation to fetch and dispatch instead of three, and one
+// permutation of the registers instead of three rounds of swaps.
+void merge_cx_chains(std::vector<Op>& ops, size_t begin) {
+    std::vector<Op> out(ops.begin(), ops.begin() + (long)begin);
+    size_t i = begin;
+    auto neighbour = [](const Op& o) { return o.kind == OP_CX_REG && o.a == o.b + 1; };
+    while (i < ops.size()) {
+        if (!neighbour(ops[i])) { out.push_back(ops[i++]); continue; }
+        // longest run going up (next control = this target) or down (next target = this control)
+        size_t up = 1, down = 1;
+        while (up < 3 && i + up < ops.size() && neighbour(ops[i + up]) && ops[i + up].b == ops[i + up - 1].a) ++up;
+        while (down < 3 && i + down < ops.size() && neighbour(ops[i + down]) && ops[i + down].a == ops[i + down - 1].b) ++down;
+        const size_t len = up >= down ? up : down;
+        if (len < 2) { out.push_back(ops[i++]); continue; }
+        // arg numbers the six possible chains in the order the interpreter tests them
+        const int dir = up >= down ? 0 : 1, a0 = ops[i].b;
+        static const int combo[6][3] = {{0, 0, 3}, {1, 2, 3}, {0, 0, 2}, {0, 1, 2}, {1, 2, 2}, {1, 1, 2}};
+        int id = -1;
+        for (int k = 0; k < 6; ++k)
+            if (combo[k][0] == dir && combo[k][1] == a0 && combo[k][2] == (int)len) id = k;
+        if (id < 0) { out.push_back(ops[i++]); continue; }   // cannot happen with four register bits
+        out.push_back({OP_CX_CHAIN, (uint8_t)a0, (uint8_t)len, (uint8_t)dir, id});
+        i += len;
+    }
+    ops.swap(out);
+}
+
 int ceil_log2(int64_t v) {
     int b = 0;
     while (((int64_t)1 << b) < v) ++b;
@@ -323,6 +351,7 @@ Plan build_plan(const qsv_circuit& c, int n, int64_t batch, bool inverse, int ti
         int ne = 0;
         run_pass(bestg, n, G, done, first, rowdep, &p.ops, &p.mat_order, &ne);
         mark_transposes(p.ops, (size_t)ps.op_begin);
+        merge_cx_chains(p.ops, (size_t)ps.op_begin);
         ps.op_count = (int)p.ops.size() - ps.op_begin;
         ps.n_gates = ne;
         p.passes.push_back(ps);
@@ -353,6 +382,7 @@ std::string describe_plan(const Plan& p) {
                 case OP_CZ_REG: snprintf(buf, sizeof buf, " Zr%d:%d", o.a, o.b); break;
                 case OP_CZ_MIX: snprintf(buf, sizeof buf, " Zm%d:%d", o.a, o.b); break;
                 case OP_CZ_LANE: snprintf(buf, sizeof buf, " Zl%x", (unsigned)o.arg); break;
+                case OP_CX_CHAIN: snprintf(buf, sizeof buf, " C%c%d:%d", o.c ? 'd' : 'u', o.a, o.b); break;
                 default: snprintf(buf, sizeof buf, " ?"); break;
             }
             s += buf;

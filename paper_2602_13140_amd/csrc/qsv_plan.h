@@ -34,8 +34,12 @@ enum OpKind : uint8_t {
                     // c = 1 if the control bit is the same for a whole wavefront
     OP_CZ_REG = 6,  // CZ between register bits a and b: sign flip of the 4 amplitudes with both set
     OP_CZ_MIX = 7,  // CZ between register bit a and index bit b outside the run (lane-dependent)
-    OP_CZ_LANE = 8  // arg = rung mask (bit q -> CZ(q, q+1)), all rungs between index bits outside
+    OP_CZ_LANE = 8, // arg = rung mask (bit q -> CZ(q, q+1)), all rungs between index bits outside
                     // the run: one lane-dependent sign for all 16 amplitudes
+    OP_CX_CHAIN = 9 // b = 2 or 3 consecutive OP_CX_REG between neighbouring register bits, as a CNOT
+                    // ring produces them, done as one permutation of the registers.  a = control of
+                    // the first; c = 0: targets go up (a -> a+1, a+1 -> a+2, ...), c = 1: the same
+                    // gates in the opposite order, controls going down (a -> a+1, a-1 -> a, ...)
 };
 
 struct Op {

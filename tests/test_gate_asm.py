@@ -7,7 +7,7 @@ import re
 from paper_2602_13140_amd.csrc import gen_gate_asm as g
 
 INTENDED_FALLTHROUGH = {"L_top", "L_uhave", "L_ugj", "L_ua", "L_ua3", "L_ur3", "L_ug3", "L_uc3",
-                        "L_d3", "L_cxdone", "L_xphave", "L_xpw", "L_xpr", "L_xpw2", "L_xpr2", "L_zm3", "L_zdone"}
+                        "L_d3", "L_c5", "L_cxdone", "L_xphave", "L_xpw", "L_xpr", "L_xpw2", "L_xpr2", "L_zm3", "L_zdone"}
 
 
 import pytest
@@ -148,3 +148,31 @@ def test_row_dependent_exit_only_in_the_variant_for_several_rows_per_tile():
     for planes in (1, 2):
         assert not any("%[nonuni]" in ln for ln in g.gen(planes, False))
         assert any("%[nonuni]" in ln for ln in g.gen(planes, True))
+
+
+def test_chain_swaps_equal_the_cnots_one_after_the_other():
+    """Every chain's swap sequence, run on 16 distinct values, gives what its CNOTs give in turn, with
+    no more swaps than the CNOTs one by one would take."""
+    for direction, first, count in g.CX_CHAINS:
+        regs = {}
+        for k in range(16):
+            regs["%%[r%d]" % k] = 100 + k
+            regs["%%[i%d]" % k] = 200 + k
+        lines = g.chain_swaps(direction, first, count)
+        assert len(lines) <= 16 * count
+        for ln in lines:
+            op, rest = ln.split(" ", 1)
+            x, y = [t.strip() for t in rest.split(",")]
+            assert op == "v_swap_b32"
+            regs[x], regs[y] = regs[y], regs[x]
+        want = list(range(16))
+        for k in range(count):
+            c = first + k if direction == 0 else first - k
+            t = c + 1
+            assert 0 <= c and t < 4
+            for i in range(16):
+                if (i >> c) & 1 and not (i >> t) & 1:
+                    j = i | (1 << t)
+                    want[i], want[j] = want[j], want[i]
+        assert [regs["%%[r%d]" % k] - 100 for k in range(16)] == want, (direction, first, count)
+        assert [regs["%%[i%d]" % k] - 200 for k in range(16)] == want

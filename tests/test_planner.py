@@ -104,6 +104,16 @@ def replay(text, n, rows, L, rot, ent, reupload, params, feats, inverse, st):
                 assert jt != jc
                 st = apply_cnot(st, n, bit(s + jc), bit(s + jt))
                 n_gates += 1
+            elif kind == "C":
+                # chain of CNOTs between neighbouring register bits: "u": a->a+1, a+1->a+2, ...;
+                # "d": a->a+1, a-1->a, ...
+                jc, count = (int(x) for x in tok[2:].split(":"))
+                assert tok[1] in "ud" and count in (2, 3)
+                for i in range(count):
+                    c0 = jc + i if tok[1] == "u" else jc - i
+                    assert 0 <= c0 and c0 + 1 < R
+                    st = apply_cnot(st, n, bit(s + c0), bit(s + c0 + 1))
+                    n_gates += 1
             elif kind == "D":
                 jt, qc, uni = (int(x) for x in tok[1:].split(":"))
                 qt = bit(s + jt)
