@@ -76,7 +76,8 @@ __device__ __forceinline__ RowCtx row_ctx(const RowMap& rm, u64 row) {
 // whose target bit is 0, (c,d) of the one whose bit is 1; m = (m00r,m00i,m01r,m01i,m10r,m10i,m11r,
 // m11i).  Written as one asm block with tied operands so that the 32 amplitude registers never
 // move: four interleaved accumulation chains whose last step overwrites an input that is dead by
-// then.  16 VALU instructions per pair, none of them a copy.
+// then.  16 VALU instructions per pair, none of them a copy.  Used where the matrix differs per lane;
+// matrices shared by a wavefront are applied inside the interpreter.
 #define QSV_U_PAIR_BODY                      \
     "v_mul_f32 %4, %8, %0\n\t"               \
     "v_mul_f32 %5, %9, %0\n\t"               \
@@ -95,14 +96,6 @@ __device__ __forceinline__ RowCtx row_ctx(const RowMap& rm, u64 row) {
     "v_fma_f32 %2, -%15, %3, %6\n\t"         \
     "v_fma_f32 %3, %14, %3, %7\n\t"
 
-// matrix in scalar registers (same for the whole wavefront)
-__device__ __forceinline__ void u_pair_s(float& a, float& b, float& c, float& d, const float (&m)[8]) {
-    float t0, t1, t2, t3;
-    asm volatile(QSV_U_PAIR_BODY
-                 : "+v"(a), "+v"(b), "+v"(c), "+v"(d), "=&v"(t0), "=&v"(t1), "=&v"(t2), "=&v"(t3)
-                 : "s"(m[0]), "s"(m[1]), "s"(m[2]), "s"(m[3]), "s"(m[4]), "s"(m[5]), "s"(m[6]), "s"(m[7]));
-}
-
 // matrix in vector registers (differs per lane: several state rows share a tile)
 __device__ __forceinline__ void u_pair_v(float& a, float& b, float& c, float& d, const float (&m)[8]) {
     float t0, t1, t2, t3;
@@ -111,24 +104,22 @@ __device__ __forceinline__ void u_pair_v(float& a, float& b, float& c, float& d,
                  : "v"(m[0]), "v"(m[1]), "v"(m[2]), "v"(m[3]), "v"(m[4]), "v"(m[5]), "v"(m[6]), "v"(m[7]));
 }
 
-template <int J, bool SCALAR>
+template <int J>
 __device__ __forceinline__ void apply_u(float (&vr)[NR], float (&vi)[NR], const float (&m)[8]) {
 #pragma unroll
     for (int i = 0; i < NR; ++i) {
         if (i & (1 << J)) continue;
         const int i1 = i | (1 << J);
-        if (SCALAR) u_pair_s(vr[i], vi[i], vr[i1], vi[i1], m);
-        else u_pair_v(vr[i], vi[i], vr[i1], vi[i1], m);
+        u_pair_v(vr[i], vi[i], vr[i1], vi[i1], m);
     }
 }
 
-template <bool SCALAR>
 __device__ __forceinline__ void apply_u_any(int j, float (&vr)[NR], float (&vi)[NR], const float (&m)[8]) {
     switch (j) {
-        case 0: apply_u<0, SCALAR>(vr, vi, m); break;
-        case 1: apply_u<1, SCALAR>(vr, vi, m); break;
-        case 2: apply_u<2, SCALAR>(vr, vi, m); break;
-        default: apply_u<3, SCALAR>(vr, vi, m); break;
+        case 0: apply_u<0>(vr, vi, m); break;
+        case 1: apply_u<1>(vr, vi, m); break;
+        case 2: apply_u<2>(vr, vi, m); break;
+        default: apply_u<3>(vr, vi, m); break;
     }
 }
 
@@ -187,7 +178,7 @@ __device__ __attribute__((aligned(64))) const XpOffsets k_xp_tab = XpOffsets();
 // gates, sign flips and LDS transposes in place until it meets an operation it does not handle
 // (a per-lane unitary, or the end), which the C++ loop handles before re-entering it.
 template <int T, bool PERLANE, int PLANES>
-// 96 scalar registers (the interpreter pins 36 of them) allow eight wavefronts per SIMD; the main
+// 96 scalar registers (the interpreter pins 37 of them) allow eight wavefronts per SIMD; the main
 // variant needs no scalar spills for that (the per-lane-matrix variant has some, and is limited by
 // its vector registers anyway).
 __global__ __launch_bounds__(1 << (T - R)) __attribute__((amdgpu_num_sgpr(96)))
@@ -344,7 +335,7 @@ void k_pass(const PassArgs a) {
 #define QSV_IN(k) xr[k] = vr##k; xi[k] = vi##k;
             QSV_16(QSV_IN)
 #undef QSV_IN
-            apply_u_any<false>((int)((word.x >> 8) & 0xffu), xr, xi, m);
+            apply_u_any((int)((word.x >> 8) & 0xffu), xr, xi, m);
 #define QSV_OUT(k) vr##k = xr[k]; vi##k = xi[k];
             QSV_16(QSV_OUT)
 #undef QSV_OUT
