@@ -43,6 +43,9 @@ def parse_args():
                     help="only time the load/store-only probe pass on config 4's state (streaming ceiling "
                          "of the pass kernel's access pattern; also the known-size copy used to scale "
                          "rocprofv3's FETCH_SIZE/WRITE_SIZE counters)")
+    ap.add_argument("--rev", type=int, default=-1, help="every other pass takes its tiles in descending order (1) or not (0)")
+    ap.add_argument("--probe-layout", type=int, default=-1,
+                    help="probe pass: start of the register run the tile is loaded and stored in (-1 = highest)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
     ap.add_argument("--cpu-layers", type=int, default=20, help="layers of config 4 the oracle is timed on")
     return ap.parse_args()
@@ -94,6 +97,8 @@ def bench_c4(torch, qb, wl, args):
         ctx.qsv_set_option("lds_planes", args.planes)
     if args.nt >= 0:
         ctx.qsv_set_option("nt_store", args.nt)
+    if args.rev >= 0:
+        ctx.qsv_set_option("reverse_passes", args.rev)
     circ = qb.circuit_from_spec(w.circuit)
     xd = torch.from_numpy(w.x).cuda()
     pd = torch.from_numpy(w.params).cuda()
@@ -150,6 +155,8 @@ def bench_c3(torch, qb, wl, args):
         ctx.qsv_set_option("lds_planes", args.planes)
     if args.nt >= 0:
         ctx.qsv_set_option("nt_store", args.nt)
+    if args.rev >= 0:
+        ctx.qsv_set_option("reverse_passes", args.rev)
     circ = qb.circuit_from_spec(w.circuit)
     xd = torch.from_numpy(w.x).cuda()
     pd = torch.from_numpy(w.params).cuda()
@@ -218,6 +225,8 @@ def bench_c2(torch, qb, wl, args):
         ctx.qsv_set_option("lds_planes", args.planes)
     if args.nt >= 0:
         ctx.qsv_set_option("nt_store", args.nt)
+    if args.rev >= 0:
+        ctx.qsv_set_option("reverse_passes", args.rev)
     xd = torch.from_numpy(w.x).cuda()
     pd = torch.from_numpy(w.params).cuda()
     loss = torch.empty(B, dtype=torch.float32, device="cuda")
@@ -371,6 +380,10 @@ def probe(torch, qb, args):
         ctx.qsv_set_option("tile_log2", args.tile)
     if args.nt >= 0:
         ctx.qsv_set_option("nt_store", args.nt)
+    if args.rev >= 0:
+        ctx.qsv_set_option("reverse_passes", args.rev)
+    if args.probe_layout >= 0:
+        ctx.qsv_set_option("probe_layout", args.probe_layout)
     tile = args.tile or 12
     ctx.state.normal_()
     nbytes = 2 * 8 * (1 << n)

@@ -238,8 +238,12 @@ qsv_status qsv_probe_pass(qsv_ctx* ctx, int low_bits, int window_start, int tran
  * after the other, 2 through two planes at once; naive = 1 routes qsv_apply_layers through the
  * one-gate-per-launch kernels; grad_layered = 0 makes qsv_param_shift_grad run every shifted
  * circuit whole; nt_store = 1 / 0 forces nontemporal / ordinary tile stores in the fused pass (-1,
- * the default, chooses by the size of the state); grad_chunk_rows in 1..32768 (0 = as many as fit) caps the circuits per launch of
- * qsv_param_shift_grad.  Unknown names and values out of range return
+ * the default, chooses by the size of the state); reverse_passes = 1 / 0 makes every other fused
+ * pass take its tiles from the last to the first, so that it starts with what the pass before it
+ * wrote last, or not (-1, the default, chooses by the size of the state; the result does not
+ * depend on it); probe_layout in 0..9 (-1 = the highest) sets the register run qsv_probe_pass loads
+ * and stores the tile in; grad_chunk_rows in 1..32768 (0 = as many as fit) caps the circuits per
+ * launch of qsv_param_shift_grad.  Unknown names and values out of range return
  * QSV_ERR_INVALID_ARG. */
 qsv_status qsv_set_option(qsv_ctx* ctx, const char* name, int64_t value);
 

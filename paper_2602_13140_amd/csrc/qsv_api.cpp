@@ -60,6 +60,9 @@ struct qsv_ctx {
     int opt_planes = 1;
     int opt_grad_layered = 1;
     int opt_nt_store = -1;   // -1: by state size
+    int opt_rev = -1;        // every other pass takes its tiles in descending order; -1: by state size
+    int probe_count = 0;
+    int opt_probe_layout = -1;  // probe pass: register run of the load and the store (-1: the highest)
     int64_t opt_grad_chunk = 0;
     std::vector<CachedPlan> cache;
     size_t ops_used = 0;
@@ -302,6 +305,9 @@ qsv_status run_circuit(qsv_ctx* ctx, const qsv_circuit& c, const Prepared& pr, f
         a.ovr = ovr;
         a.total = (uint64_t)rows << n;
         a.nt_store = ctx->opt_nt_store >= 0 ? ctx->opt_nt_store : (a.total * 8 >= kNtStoreBytes ? 1 : 0);
+        // Every other pass walks the tiles downwards, so that it starts with what the pass before
+        // wrote last and may still find in the memory-side cache (256 MiB).
+        a.rev = (ctx->opt_rev >= 0 ? ctx->opt_rev : (a.total * 8 >= kNtStoreBytes ? 1 : 0)) ? (int)(pi & 1) : 0;
         a.n = n; a.c = ps.c; a.w = ps.w;
         a.n_mats = n_mats;
         a.rowdep = c.reupload;
@@ -418,6 +424,17 @@ qsv_status qsv_set_option(qsv_ctx* ctx, const char* name, int64_t value) {
     if (!strcmp(name, "grad_chunk_rows")) {
         if (value < 0 || value > 32768) return fail(ctx, QSV_ERR_INVALID_ARG, "grad_chunk_rows must be in 0..32768");
         ctx->opt_grad_chunk = value;
+        return QSV_OK;
+    }
+    if (!strcmp(name, "reverse_passes")) {
+        if (value < -1 || value > 1) return fail(ctx, QSV_ERR_INVALID_ARG, "reverse_passes must be -1, 0 or 1");
+        ctx->opt_rev = (int)value;
+        return QSV_OK;
+    }
+    if (!strcmp(name, "probe_layout")) {
+        if (value < -1 || value > kMaxTile - kRegBits)
+            return fail(ctx, QSV_ERR_INVALID_ARG, "probe_layout must be -1 or in 0..9");
+        ctx->opt_probe_layout = (int)value;
         return QSV_OK;
     }
     if (!strcmp(name, "nt_store")) {
@@ -987,9 +1004,10 @@ qsv_status qsv_probe_pass(qsv_ctx* ctx, int low_bits, int window_start, int tran
     if (!dev) return ws_fail(ctx, ar, "qsv_probe_pass");
     std::vector<Op> ops;
     const int smax = tile - kRegBits;
-    ops.push_back({OP_LOAD, (uint8_t)smax, 0, 0, 0});
+    const int sio = ctx->opt_probe_layout >= 0 ? std::min(ctx->opt_probe_layout, smax) : smax;
+    ops.push_back({OP_LOAD, (uint8_t)sio, 0, 0, 0});
     for (int i = 0; i < transposes; ++i)
-        ops.push_back({OP_XPOSE, (uint8_t)((i & 1) ? smax : 0), 0, 0, 0});
+        ops.push_back({OP_XPOSE, (uint8_t)((i & 1) ? sio : (sio ? 0 : smax)), 0, 0, 0});
     ops.push_back({OP_END, 0, 0, 0, 0});
     // a small synchronous upload: this is a measurement aid, not part of the hot path
     QSV_HIP(ctx, hipMemcpyAsync(dev, ops.data(), ops.size() * sizeof(Op), hipMemcpyHostToDevice, ctx->stream),
@@ -1000,6 +1018,8 @@ qsv_status qsv_probe_pass(qsv_ctx* ctx, int low_bits, int window_start, int tran
     a.src = nullptr;
     a.zout = nullptr; a.zq = 0; a.nostore = 0;
     a.nt_store = ctx->opt_nt_store >= 0 ? ctx->opt_nt_store : ((((uint64_t)ctx->batch << n) * 8) >= kNtStoreBytes ? 1 : 0);
+    a.rev = (ctx->opt_rev >= 0 ? ctx->opt_rev : ((((uint64_t)ctx->batch << n) * 8) >= kNtStoreBytes ? 1 : 0))
+                ? (ctx->probe_count++ & 1) : 0;
     a.ops = dev;
     a.mats = nullptr;
     a.exec_of = nullptr;

@@ -37,6 +37,7 @@ struct PassArgs {
     int zq;
     int nostore;         // with zout: the state is not written back
     int nt_store;        // nontemporal tile stores (states much larger than the last-level cache)
+    int rev;             // workgroups take the tiles in descending order (see run_circuit)
     const float* mats;   // [samples if rowdep][n_mats][8], matrices in execution order
     const int* exec_of;  // [n_mats]: (layer * n + qubit) -> execution-order index
     const float* ovr;    // gradient: [samples if rowdep][2P][8] shifted matrices

@@ -191,7 +191,7 @@ void k_pass(const PassArgs a) {
     static_assert(PLANE * 4u < 65536u && PLANE / 64u < 256u, "plane offsets must fit the LDS offset fields");
     const unsigned lds_byte0 = (unsigned)(uintptr_t)(__attribute__((address_space(3))) float*)lds;
     const unsigned thr = threadIdx.x;
-    const u64 tb = blockIdx.x;
+    const u64 tb = a.rev ? (u64)(gridDim.x - 1u - blockIdx.x) : (u64)blockIdx.x;
     const int c = a.c, w = a.w;
     const unsigned cmask = (1u << c) - 1u;
     const int wc = w - c;

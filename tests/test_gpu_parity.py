@@ -91,6 +91,7 @@ def test_apply_layers_small(oracle, n, B, L, rot, ent, reup, mode):
                       planes=int(mode[4]) if mode[3:4] == "p" else 0)
     if mode.endswith("p1"):
         ctx.qsv_set_option("nt_store", 1)      # nontemporal tile stores, normally for large states only
+        ctx.qsv_set_option("reverse_passes", 1)  # and every other pass from the last tile to the first
     circ = qb.circuit_from_spec(spec)
     xd, pd = gu.dev(x), gu.dev(params)
     fd = gu.dev(feats) if reup else None
@@ -275,6 +276,7 @@ def test_param_shift_grad_small(oracle, n, B, L, rot, ent, reup, obs, mode):
     if "chunk" in mode:
         ctx.qsv_set_option("grad_chunk_rows", int(mode[-1]))
     ctx.qsv_set_option("nt_store", 1 if n % 2 else 0)    # both store flavours, whatever the size
+    ctx.qsv_set_option("reverse_passes", 1 if n % 2 else 0)   # and both orders of the tiles
     ctx.state.fill_(3.0)
     loss = torch.zeros(B, dtype=torch.float32, device="cuda")
     grad = torch.zeros((B, P), dtype=torch.float32, device="cuda")
