@@ -1009,6 +1009,7 @@ qsv_status qsv_probe_pass(qsv_ctx* ctx, int low_bits, int window_start, int tran
     for (int i = 0; i < transposes; ++i)
         ops.push_back({OP_XPOSE, (uint8_t)((i & 1) ? sio : (sio ? 0 : smax)), 0, 0, 0});
     ops.push_back({OP_END, 0, 0, 0, 0});
+    set_transpose_barriers(ops);
     // a small synchronous upload: this is a measurement aid, not part of the hot path
     QSV_HIP(ctx, hipMemcpyAsync(dev, ops.data(), ops.size() * sizeof(Op), hipMemcpyHostToDevice, ctx->stream),
             "upload probe");

@@ -288,6 +288,8 @@ int ceil_log2(int64_t v) {
 
 }  // namespace
 
+void set_transpose_barriers(std::vector<Op>& ops) { mark_transposes(ops, 0); }
+
 bool check_circuit(const qsv_circuit* c, int n, std::string* why) {
     auto fail = [&](const char* m) { if (why) *why = m; return false; };
     if (!c) return fail("circuit descriptor is NULL");

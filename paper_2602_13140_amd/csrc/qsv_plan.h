@@ -79,6 +79,10 @@ Plan build_plan(const qsv_circuit& c, int n, int64_t batch, bool inverse, int ti
 
 std::string describe_plan(const Plan& p);
 
+// Fills in the barrier flags of the OP_XPOSE entries of one pass's operation list (starting with its
+// OP_LOAD), as build_plan does for the passes it emits.
+void set_transpose_barriers(std::vector<Op>& ops);
+
 int default_tile(int n, int64_t batch);
 
 }  // namespace qsv

@@ -651,3 +651,29 @@ def test_argument_errors():
     with pytest.raises(qb.QsvError):
         ctx.qsv_set_option("tile_log2", 9)
     ctx.close()
+
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("n,B,tile", [(14, 3, 12), (16, 1, 13), (12, 8, 10), (11, 5, 12)])
+def test_probe_pass_leaves_the_state_as_it_was(n, B, tile):
+    """The load/store-only pass (a measurement aid) moves the tile through LDS and back: whatever the
+    geometry, the number of transposes, the register run it loads in and the order of the tiles,
+    every amplitude must come back bit for bit."""
+    torch = gu.torch_cuda()
+    ctx = gu.make_ctx(n, B, tile=tile)
+    t = tile or 12
+    ext = n + int(np.ceil(np.log2(B)))
+    ctx.state.normal_()
+    want = ctx.state.clone()
+    geoms = [(t, t)] if ext <= t else [(t, t), (4, 4), (4, ext - (t - 4)), (6, ext - (t - 6))]
+    for rev in (0, 1):
+        ctx.qsv_set_option("reverse_passes", rev)
+        for layout in (-1, 0, 4, 5):
+            ctx.qsv_set_option("probe_layout", layout)
+            for c, w in geoms:
+                for transposes in (0, 1, 2, 5):
+                    ctx.qsv_probe_pass(c, w, transposes)
+                    ctx.qsv_probe_pass(c, w, transposes)      # the second one runs downwards when rev = 1
+                    torch.cuda.synchronize()
+                    assert torch.equal(ctx.state, want), (rev, layout, c, w, transposes)
+    ctx.close()
