@@ -21,8 +21,12 @@
  *   - The caller owns every device buffer (state, inputs, outputs, workspace); the context owns
  *     only host-side plans.  No call allocates or frees device memory.
  *   - All work is enqueued on the HIP stream given to qsv_create and is asynchronous with respect
- *     to the host; no call synchronises the stream.  Host structs (qsv_circuit, qsv_measure_req)
- *     are read during the call and may be reused afterwards.
+ *     to the host; no call synchronises the stream.  Part of a call's kernels may run on a second
+ *     stream that the context owns (default priority); it waits for the caller's stream at the
+ *     start of that work and the caller's stream waits for it before the call's remaining work, so
+ *     to the caller everything is ordered as if it ran on the one stream (also under stream
+ *     capture, where the second stream joins the capture and leaves it within the call).  Host
+ *     structs (qsv_circuit, qsv_measure_req) are read during the call and may be reused afterwards.
  *   - Pointers named *_dev are device pointers; everything else is host memory.
  *   - Argument errors are detected on the host before anything is launched and reported through
  *     the return code; qsv_last_error gives the text.  No exceptions, no abort.
@@ -241,7 +245,11 @@ qsv_status qsv_probe_pass(qsv_ctx* ctx, int low_bits, int window_start, int tran
  * the default, chooses by the size of the state); reverse_passes = 1 / 0 makes every other fused
  * pass take its tiles from the last to the first, so that it starts with what the pass before it
  * wrote last, or not (-1, the default, chooses by the size of the state; the result does not
- * depend on it); probe_layout in 0..9 (-1 = the highest) sets the register run qsv_probe_pass loads
+ * depend on it); split_streams = 1 / 0 sends the state rows through a sequence of fused passes as
+ * two halves, the second on a stream of the library's own that forks from and rejoins the caller's
+ * stream inside the call, or not (-1, the default: for states of at most 256 MiB; needs at least two
+ * rows and more qubits than the tile has index bits; the result does not depend on it);
+ * probe_layout in 0..9 (-1 = the highest) sets the register run qsv_probe_pass loads
  * and stores the tile in; grad_chunk_rows in 1..32768 (0 = as many as fit) caps the circuits per
  * launch of qsv_param_shift_grad.  Unknown names and values out of range return
  * QSV_ERR_INVALID_ARG. */

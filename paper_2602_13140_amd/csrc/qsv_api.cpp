@@ -21,6 +21,7 @@ constexpr size_t kOpsRegion = 4u << 20;  // persistent: uploaded pass programs
 // last-level cache is 256 MiB, and measured on a 512 MiB state such stores are 4 % faster, on a
 // 256 MiB state 3 % slower.
 constexpr uint64_t kNtStoreBytes = 384ull << 20;
+constexpr uint64_t kSplitMaxBytes = 256ull << 20;   // see run_circuit
 constexpr int kChunkBits = 12;
 
 std::string g_create_error;
@@ -64,6 +65,9 @@ struct qsv_ctx {
     int probe_count = 0;
     int opt_probe_layout = -1;  // probe pass: register run of the load and the store (-1: the highest)
     int64_t opt_grad_chunk = 0;
+    int opt_split = -1;      // state rows of a launch sequence in two halves on two streams; -1: by state size
+    hipStream_t side = nullptr;          // second stream for that (default priority, non-blocking)
+    hipEvent_t ev_fork = nullptr, ev_join = nullptr;
     std::vector<CachedPlan> cache;
     size_t ops_used = 0;
 };
@@ -288,6 +292,32 @@ qsv_status run_circuit(qsv_ctx* ctx, const qsv_circuit& c, const Prepared& pr, f
     const uint64_t n_tiles = ext > pl.tile ? (1ull << (ext - pl.tile)) : 1ull;
     const Op* dev_ops = reinterpret_cast<const Op*>(ctx->ws + cp->dev_off);
     const bool z_in_pass = zs && n >= pl.tile && !pl.passes.empty();
+    // States that fit the memory-side cache: the rows go through the passes as two halves on two
+    // streams.  The halves never meet (a tile lies inside one row when n > tile, and the geometry of
+    // the passes does not depend on the number of rows), and each one's launch gaps and tails are
+    // covered by the other's kernels: measured 7-13 % off the whole sequence from 16 to 256 MiB, and
+    // 4 % on top at 512 MiB, hence the limit.
+    const uint64_t state_bytes = ((uint64_t)rows << n) * 8;
+    const bool split = rows >= 2 && n > pl.tile && pl.passes.size() >= 2 &&
+                       (ctx->opt_split >= 0 ? ctx->opt_split == 1 : state_bytes <= kSplitMaxBytes);
+    const int64_t rows_a = split ? rows / 2 : rows, rows_b = rows - rows_a;
+    struct Join {      // the second stream always rejoins the caller's, also when a launch fails
+        qsv_ctx* c; bool on;
+        ~Join() {
+            if (!on) return;
+            if (hipEventRecord(c->ev_join, c->side) == hipSuccess) (void)hipStreamWaitEvent(c->stream, c->ev_join, 0);
+        }
+    } join{ctx, false};
+    if (split) {
+        QSV_HIP(ctx, hipEventRecord(ctx->ev_fork, ctx->stream), "fork");
+        QSV_HIP(ctx, hipStreamWaitEvent(ctx->side, ctx->ev_fork, 0), "fork");
+        join.on = true;
+    }
+    auto tiles_of = [&](int64_t r) -> uint64_t {
+        const int e = n + ceil_log2_i64(r);
+        return e > pl.tile ? (1ull << (e - pl.tile)) : 1ull;
+    };
+    const int waves_per_group = std::max(1, (1 << (pl.tile - kRegBits)) / 64);
     bool first = true;
     for (size_t pi = 0; pi < pl.passes.size(); ++pi) {
         const Pass& ps = pl.passes[pi];
@@ -303,16 +333,36 @@ qsv_status run_circuit(qsv_ctx* ctx, const qsv_circuit& c, const Prepared& pr, f
         a.mats = mats;
         a.exec_of = reinterpret_cast<const int*>(ctx->ws + cp->execof_off);
         a.ovr = ovr;
-        a.total = (uint64_t)rows << n;
-        a.nt_store = ctx->opt_nt_store >= 0 ? ctx->opt_nt_store : (a.total * 8 >= kNtStoreBytes ? 1 : 0);
+        a.total = (uint64_t)rows_a << n;
+        a.nt_store = ctx->opt_nt_store >= 0 ? ctx->opt_nt_store : (state_bytes >= kNtStoreBytes ? 1 : 0);
         // Every other pass walks the tiles downwards, so that it starts with what the pass before
         // wrote last and may still find in the memory-side cache (256 MiB).
-        a.rev = (ctx->opt_rev >= 0 ? ctx->opt_rev : (a.total * 8 >= kNtStoreBytes ? 1 : 0)) ? (int)(pi & 1) : 0;
+        a.rev = (ctx->opt_rev >= 0 ? ctx->opt_rev : (state_bytes >= kNtStoreBytes ? 1 : 0)) ? (int)(pi & 1) : 0;
         a.n = n; a.c = ps.c; a.w = ps.w;
         a.n_mats = n_mats;
         a.rowdep = c.reupload;
         a.rm = rm;
-        QSV_HIP(ctx, launch_pass(pl.tile, ctx->opt_planes, a, n_tiles, ctx->stream), "fused pass");
+        QSV_HIP(ctx, launch_pass(pl.tile, ctx->opt_planes, a, split ? tiles_of(rows_a) : n_tiles, ctx->stream), "fused pass");
+        if (!split) continue;
+        // second half: rows rows_a .. rows - 1.  With a gradient row map the kernel works with global
+        // row numbers (row0 moves); otherwise a row's matrices and start state are found relative to
+        // the launch, so those pointers move with the state.
+        PassArgs b = a;
+        b.state = state + ((uint64_t)rows_a << n);
+        b.total = (uint64_t)rows_b << n;
+        if (rm.grad) {
+            b.rm.row0 = rm.row0 + rows_a;
+        } else {
+            if (b.src) b.src = b.src + ((uint64_t)rows_a << n);
+            if (c.reupload && b.mats) b.mats = b.mats + (uint64_t)rows_a * (uint64_t)n_mats * 8;
+        }
+        if (b.zout) b.zout = b.zout + (uint64_t)rows_a * ((uint64_t)1 << (n - pl.tile)) * (uint64_t)waves_per_group;
+        QSV_HIP(ctx, launch_pass(pl.tile, ctx->opt_planes, b, tiles_of(rows_b), ctx->side), "fused pass");
+    }
+    if (split) {       // what follows on the caller's stream sees both halves
+        join.on = false;
+        QSV_HIP(ctx, hipEventRecord(ctx->ev_join, ctx->side), "join");
+        QSV_HIP(ctx, hipStreamWaitEvent(ctx->stream, ctx->ev_join, 0), "join");
     }
     if (z_in_pass) {
         // partials per row: tiles of the row x wavefronts of a workgroup
@@ -391,11 +441,27 @@ qsv_status qsv_create(qsv_ctx** out, int n_qubits, int batch, int device, void* 
     ctx->state = static_cast<float2*>(state_dev);
     ctx->ws = static_cast<char*>(ws_dev);
     ctx->ws_bytes = ws_bytes;
+    e = hipStreamCreateWithFlags(&ctx->side, hipStreamNonBlocking);
+    if (e == hipSuccess) e = hipEventCreateWithFlags(&ctx->ev_fork, hipEventDisableTiming);
+    if (e == hipSuccess) e = hipEventCreateWithFlags(&ctx->ev_join, hipEventDisableTiming);
+    if (e != hipSuccess) {
+        g_create_error = std::string("creating the second stream failed: ") + hipGetErrorString(e);
+        qsv_destroy(ctx);
+        return QSV_ERR_HIP;
+    }
     *out = ctx;
     return QSV_OK;
 }
 
-void qsv_destroy(qsv_ctx* ctx) { delete ctx; }
+void qsv_destroy(qsv_ctx* ctx) {
+    if (!ctx) return;
+    if (hipSetDevice(ctx->device) == hipSuccess) {
+        if (ctx->ev_fork) (void)hipEventDestroy(ctx->ev_fork);
+        if (ctx->ev_join) (void)hipEventDestroy(ctx->ev_join);
+        if (ctx->side) (void)hipStreamDestroy(ctx->side);
+    }
+    delete ctx;
+}
 
 const char* qsv_last_error(const qsv_ctx* ctx) {
     return ctx ? ctx->err.c_str() : g_create_error.c_str();
@@ -429,6 +495,11 @@ qsv_status qsv_set_option(qsv_ctx* ctx, const char* name, int64_t value) {
     if (!strcmp(name, "reverse_passes")) {
         if (value < -1 || value > 1) return fail(ctx, QSV_ERR_INVALID_ARG, "reverse_passes must be -1, 0 or 1");
         ctx->opt_rev = (int)value;
+        return QSV_OK;
+    }
+    if (!strcmp(name, "split_streams")) {
+        if (value < -1 || value > 1) return fail(ctx, QSV_ERR_INVALID_ARG, "split_streams must be -1, 0 or 1");
+        ctx->opt_split = (int)value;
         return QSV_OK;
     }
     if (!strcmp(name, "probe_layout")) {

@@ -581,12 +581,12 @@ def test_training_steps_lower_the_loss(oracle):
 
 
 # ------------------------------------------------------------------ HIP graph capture
-def test_calls_can_be_captured_in_a_hip_graph_and_replayed(oracle):
+@pytest.mark.parametrize("n,B,tile", [(6, 16, 0), (12, 4, 10)])   # the second: the rows go as two halves on two streams
+def test_calls_can_be_captured_in_a_hip_graph_and_replayed(oracle, n, B, tile):
     """After a warm-up (the first call uploads the plan) the calls are plain launches on the
     context's stream, so a caller may capture them; every replay must equal the eager result, with
     eager work and synchronisations in between."""
     torch = gu.torch_cuda()
-    n, B = 6, 16
     g = rng(180)
     spec = wl.CircuitSpec(3, (RY, RZ), RING, 1)
     params = wl.draw_params(spec, n, 181)
@@ -594,7 +594,7 @@ def test_calls_can_be_captured_in_a_hip_graph_and_replayed(oracle):
     feats = g.standard_normal((B, n)).astype(np.float32)
     side = torch.cuda.Stream()
     with torch.cuda.stream(side):
-        ctx = gu.make_ctx(n, B)                        # binds the side stream
+        ctx = gu.make_ctx(n, B, tile=tile)             # binds the side stream
         circ = qb.circuit_from_spec(spec)
         xd, pd, fd = gu.dev(x), gu.dev(params), gu.dev(feats)
         z = torch.zeros((B, n), dtype=torch.float32, device="cuda")
@@ -677,3 +677,42 @@ def test_probe_pass_leaves_the_state_as_it_was(n, B, tile):
                     torch.cuda.synchronize()
                     assert torch.equal(ctx.state, want), (rev, layout, c, w, transposes)
     ctx.close()
+
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("n,B,tile,reup", [(11, 2, 10, 0), (12, 5, 10, 1), (13, 3, 12, 0), (12, 7, 11, 1)])
+def test_rows_in_two_halves_on_two_streams_give_the_same_bits(oracle, n, B, tile, reup):
+    """Sending the rows through the passes as two halves on two streams must not change a single bit
+    of the state, of <Z_q> or of the shift-rule gradient (also with an odd number of rows and with
+    per-sample matrices)."""
+    torch = gu.torch_cuda()
+    g = rng(700 + n + B)
+    spec = wl.CircuitSpec(2, (RY, RZ), RING, reup)
+    params = wl.draw_params(spec, n, 701)
+    P = params.size
+    x = g.standard_normal((B, 1 << n)).astype(np.float32)
+    feats = g.standard_normal((B, n)).astype(np.float32) if reup else None
+    circ = qb.circuit_from_spec(spec)
+    xd, pd = gu.dev(x), gu.dev(params)
+    fd = gu.dev(feats) if reup else None
+    res = []
+    for split in (0, 1):
+        ctx = gu.make_ctx(n, B, tile=tile)
+        ctx.qsv_set_option("split_streams", split)
+        ctx.qsv_amp_encode(xd)
+        ctx.qsv_apply_layers(circ, pd, fd, 0)
+        z = torch.zeros((B, n), dtype=torch.float32, device="cuda")
+        ctx.qsv_measure(qb.QSV_M_EXPZ_ALL, z)
+        state = ctx.state.clone()
+        loss = torch.zeros(B, dtype=torch.float32, device="cuda")
+        grad = torch.zeros((B, P), dtype=torch.float32, device="cuda")
+        ctx.qsv_param_shift_grad(circ, xd, pd, fd, n - 1, loss, grad)
+        torch.cuda.synchronize()
+        res.append((state, z.clone(), loss.clone(), grad.clone()))
+        ctx.close()
+    for a, b in zip(*res):
+        assert torch.equal(a, b)
+    ref, _ = oracle.amp_encode(x, n)
+    oracle.apply_layers(ref, ocirc(oracle, spec), params, feats)
+    s = res[1][0].cpu().numpy()
+    assert np.abs((s[..., 0] + 1j * s[..., 1]) - ref).max() <= amp_tol(n)
