@@ -23,10 +23,10 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
-# HBM bytes per pass-kernel launch from rocprofv3 FETCH_SIZE / WRITE_SIZE, each scaled by what the same
+# HBM bytes per pass (config 3: a pair of launches) from rocprofv3 FETCH_SIZE / WRITE_SIZE, each scaled by what the same
 # counter reads for the load/store-only probe pass of known size (FETCH_SIZE x 2.000, WRITE_SIZE x
 # 1.000); the runs and their figures are in profiles/k_pass_hbm_traffic_counters.md.
-TRAFFIC_BYTES_PER_LAUNCH = {"c4": 1073868910, "c3": 537070332}
+TRAFFIC_BYTES_PER_LAUNCH = {"c4": 1074469650, "c3": 537379613}
 
 
 def parse_args():
@@ -203,6 +203,9 @@ def bench_c3(torch, qb, wl, args):
         "workload": "c3: 20 qubits, batch 32, 20-layer encoder + trash projection + decoder + fidelity",
         "ms_per_step": ms, "apply_ms": apply_ms, "passes": passes, "updates": updates,
         "updates_per_s": updates / (ms * 1e-3), "apply_updates_per_s": updates / (apply_ms * 1e-3),
+        # states of at most 256 MiB with two rows or more go through a pass as two launches (halves
+        # of the rows) side by side on two streams: the per-pass figures below are for the pair
+        "launches_per_pass": 2 if (B >= 2 and state_bytes <= (256 << 20)) else 1,
         "pass_avg_ms": apply_ms / passes, "pass_bytes": 2 * state_bytes,
         "pass_gbs": 2 * state_bytes / (apply_ms / passes * 1e-3) / 1e9,
         "pass_hbm_frac": 2 * state_bytes / (apply_ms / passes * 1e-3) / 1e9 / HBM_PEAK_GBS,
@@ -471,7 +474,8 @@ def main():
         "roofline": {"bound": "hbm", "kernel": "k_pass (fused gate pass)", "achieved": head["pass_gbs"],
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": head["pass_gbs"] / HBM_PEAK_GBS,
                      "traffic": TRAFFIC_BYTES_PER_LAUNCH.get(head["workload"][:2]),
-                     "bytes_per_launch": head["pass_bytes"], "avg_launch_ms": head["pass_avg_ms"]},
+                     "bytes_per_launch": head["pass_bytes"], "avg_launch_ms": head["pass_avg_ms"],
+                     "launches_per_pass": head.get("launches_per_pass", 1)},
         "cpu_baseline": cpu,
         "others": dict(others, **{k: head[k] for k in ("pauli_string", "true_reset") if k in head}),
     }
