@@ -203,9 +203,9 @@ def bench_c3(torch, qb, wl, args):
         "workload": "c3: 20 qubits, batch 32, 20-layer encoder + trash projection + decoder + fidelity",
         "ms_per_step": ms, "apply_ms": apply_ms, "passes": passes, "updates": updates,
         "updates_per_s": updates / (ms * 1e-3), "apply_updates_per_s": updates / (apply_ms * 1e-3),
-        # states of at most 256 MiB with two rows or more go through a pass as two launches (halves
-        # of the rows) side by side on two streams: the per-pass figures below are for the pair
-        "launches_per_pass": 2 if (B >= 2 and state_bytes <= (256 << 20)) else 1,
+        # states of two rows or more go through a pass as two launches (halves of the rows) side by
+        # side on two streams: the per-pass figures below are for the pair
+        "launches_per_pass": 2 if B >= 2 else 1,
         "pass_avg_ms": apply_ms / passes, "pass_bytes": 2 * state_bytes,
         "pass_gbs": 2 * state_bytes / (apply_ms / passes * 1e-3) / 1e9,
         "pass_hbm_frac": 2 * state_bytes / (apply_ms / passes * 1e-3) / 1e9 / HBM_PEAK_GBS,

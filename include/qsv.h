@@ -247,8 +247,8 @@ qsv_status qsv_probe_pass(qsv_ctx* ctx, int low_bits, int window_start, int tran
  * wrote last, or not (-1, the default, chooses by the size of the state; the result does not
  * depend on it); split_streams = 1 / 0 sends the state rows through a sequence of fused passes as
  * two halves, the second on a stream of the library's own that forks from and rejoins the caller's
- * stream inside the call, or not (-1, the default: for states of at most 256 MiB; needs at least two
- * rows and more qubits than the tile has index bits; the result does not depend on it);
+ * stream inside the call, or not (-1, the default, is 1; it takes at least two rows and more qubits
+ * than the tile has index bits; the result does not depend on it);
  * probe_layout in 0..9 (-1 = the highest) sets the register run qsv_probe_pass loads
  * and stores the tile in; grad_chunk_rows in 1..32768 (0 = as many as fit) caps the circuits per
  * launch of qsv_param_shift_grad.  Unknown names and values out of range return

@@ -21,7 +21,6 @@ constexpr size_t kOpsRegion = 4u << 20;  // persistent: uploaded pass programs
 // last-level cache is 256 MiB, and measured on a 512 MiB state such stores are 4 % faster, on a
 // 256 MiB state 3 % slower.
 constexpr uint64_t kNtStoreBytes = 384ull << 20;
-constexpr uint64_t kSplitMaxBytes = 256ull << 20;   // see run_circuit
 constexpr int kChunkBits = 12;
 
 std::string g_create_error;
@@ -292,14 +291,14 @@ qsv_status run_circuit(qsv_ctx* ctx, const qsv_circuit& c, const Prepared& pr, f
     const uint64_t n_tiles = ext > pl.tile ? (1ull << (ext - pl.tile)) : 1ull;
     const Op* dev_ops = reinterpret_cast<const Op*>(ctx->ws + cp->dev_off);
     const bool z_in_pass = zs && n >= pl.tile && !pl.passes.empty();
-    // States that fit the memory-side cache: the rows go through the passes as two halves on two
-    // streams.  The halves never meet (a tile lies inside one row when n > tile, and the geometry of
-    // the passes does not depend on the number of rows), and each one's launch gaps and tails are
-    // covered by the other's kernels: measured 7-13 % off the whole sequence from 16 to 256 MiB, and
-    // 4 % on top at 512 MiB, hence the limit.
+    // Two rows or more: the rows go through the passes as two halves on two streams.  The halves
+    // never meet (a tile lies inside one row when n > tile, and the geometry of the passes does not
+    // depend on the number of rows), and each one's launch gaps and tails are covered by the
+    // other's kernels: measured 7-13 % off the whole sequence from 16 to 256 MiB, 3.5 % at 384 and
+    // 512 MiB, 1.2 % at 1 GiB.
     const uint64_t state_bytes = ((uint64_t)rows << n) * 8;
     const bool split = rows >= 2 && n > pl.tile && pl.passes.size() >= 2 &&
-                       (ctx->opt_split >= 0 ? ctx->opt_split == 1 : state_bytes <= kSplitMaxBytes);
+                       ctx->opt_split != 0;
     const int64_t rows_a = split ? rows / 2 : rows, rows_b = rows - rows_a;
     struct Join {      // the second stream always rejoins the caller's, also when a launch fails
         qsv_ctx* c; bool on;
