@@ -197,6 +197,7 @@ RowMap plain_rows(int n) {
 struct Prepared {
     const CachedPlan* cp = nullptr;  // null: one-gate-per-launch path
     float* mats = nullptr;
+    int mat_stride = 0;              // matrices per sample in a per-sample table; 0: those of the circuit run
 };
 
 size_t mats_table_bytes(const qsv_circuit& c, int n, int64_t samples) {
@@ -233,6 +234,39 @@ qsv_status prepare_circuit(qsv_ctx* ctx, const qsv_circuit& c, int64_t rows, int
     return QSV_OK;
 }
 
+// The same for the layers of c run one by one as one-layer circuits (`one` = c with n_layers = 1):
+// the plan is the one-layer circuit's, and the matrices of all layers are built by one launch, every
+// layer's in that plan's order; layer l then runs with layer_of(prepared, l).
+qsv_status prepare_layers(qsv_ctx* ctx, const qsv_circuit& c, const qsv_circuit& one, int64_t rows, int inverse,
+                          const float* params, const float* feats, int64_t samples, float* mats, Prepared* out) {
+    const int n = ctx->n;
+    const bool has_u = (c.reupload + c.n_rot) > 0 && c.n_layers > 0;
+    out->mats = mats;
+    out->cp = nullptr;
+    out->mat_stride = c.n_layers * n;
+    const int* order = nullptr;
+    const int* exec_of = nullptr;
+    if (!(ctx->opt_naive || n < kRegBits)) {
+        qsv_status st = get_plan(ctx, one, rows, inverse, 0, &out->cp);
+        if (st != QSV_OK) return st;
+        order = reinterpret_cast<const int*>(ctx->ws + out->cp->order_off);
+        exec_of = reinterpret_cast<const int*>(ctx->ws + out->cp->execof_off);
+    }
+    if (has_u) {
+        double* side = reinterpret_cast<double*>(reinterpret_cast<char*>(mats) + mats_table_bytes(c, n, samples));
+        QSV_HIP(ctx, launch_build_mats(to_dev(c, n), params, feats, samples, inverse, order, exec_of, mats, side,
+                                       ctx->stream, order ? n : 0),
+                "build matrices");
+    }
+    return QSV_OK;
+}
+
+inline Prepared layer_of(const Prepared& all, int l, int n) {
+    Prepared pr = all;
+    pr.mats = all.mats + (size_t)l * n * 8;
+    return pr;
+}
+
 // Runs the prepared circuit on `rows` state rows starting at `state`.
 // src (optional): per-sample start states [samples][2^n]; the rows then start from the state of
 // their sample.  The fused path reads them in its first pass when a tile never spans two rows,
@@ -247,7 +281,7 @@ qsv_status run_circuit(qsv_ctx* ctx, const qsv_circuit& c, const Prepared& pr, f
                        const ZSpec* zs = nullptr) {
     const int n = ctx->n;
     const bool has_u = (c.reupload + c.n_rot) > 0;
-    const int n_mats = has_u ? c.n_layers * n : 0;
+    const int n_mats = has_u ? (pr.mat_stride > 0 ? pr.mat_stride : c.n_layers * n) : 0;
     const float* mats = pr.mats;
     const bool src_in_pass = src && pr.cp && n >= pr.cp->plan.tile && !pr.cp->plan.passes.empty();
     if (src && !src_in_pass)
@@ -957,12 +991,12 @@ static qsv_status adjoint_impl(qsv_ctx* ctx, const qsv_circuit* c, const float* 
         float2* A = keep ? ck(L, b0) : Abuf;                 // the final states of the chunk
         if (keep) {
             QSV_HIP(ctx, launch_encode_write(x_dev, dim, n, bc, inv, rm1, ck(0, b0), ctx->stream), "encode rows");
+            Prepared all;
+            st = prepare_layers(ctx, *c, one, bc, 0, params_dev, feats_dev, B, mats, &all);
+            if (st != QSV_OK) return st;
             for (int l = 0; l < L; ++l) {
-                Prepared pr;
-                st = prepare_circuit(ctx, one, bc, 0, 0, params_dev + (size_t)l * slots_n, feats_dev, B, mats, &pr);
-                if (st != QSV_OK) return st;
                 // the start states are addressed by sample (ck(l, 0)), the rows written are the chunk's
-                st = run_circuit(ctx, one, pr, ck(l + 1, b0), bc, 0, nullptr, rm1, ck(l, 0));
+                st = run_circuit(ctx, one, layer_of(all, l, n), ck(l + 1, b0), bc, 0, nullptr, rm1, ck(l, 0));
                 if (st != QSV_OK) return st;
             }
         } else {
@@ -996,12 +1030,11 @@ static qsv_status adjoint_impl(qsv_ctx* ctx, const qsv_circuit* c, const float* 
             rm2.row0 = 2 * b0;
         }
         const int64_t back_rows = keep ? bc : 2 * bc;
+        Prepared back;      // all layers' inverse matrices by one launch
+        st = prepare_layers(ctx, *c, one, back_rows, 1, params_dev, feats_dev, B, mats, &back);
+        if (st != QSV_OK) return st;
         for (int l = L - 1; l >= 0; --l) {
-            const float* p_l = params_dev + (size_t)l * slots_n;
-            Prepared pr;
-            st = prepare_circuit(ctx, one, back_rows, 1, 0, p_l, feats_dev, B, mats, &pr);
-            if (st != QSV_OK) return st;
-            st = run_circuit(ctx, one, pr, S, back_rows, 1, nullptr, rm2);
+            st = run_circuit(ctx, one, layer_of(back, l, n), S, back_rows, 1, nullptr, rm2);
             if (st != QSV_OK) return st;
             const float2* psi0 = keep ? ck(l, b0) : S;
             const float2* lam0 = keep ? S : S + amps;

@@ -61,9 +61,11 @@ hipError_t launch_naive_cz_ladder(float2* state, int64_t rows, int n, hipStream_
 // fused per-(layer, qubit) matrices; out: [samples if reupload][n_layers*n][8] floats.  order
 // (device, [n_layers*n], may be NULL = natural order) gives the (layer*n + qubit) id stored at
 // each position of a sample's table, exec_of (device, same length, NULL with order) its inverse.
+// period = n: the two tables have n entries, describe a one-layer circuit and repeat for every layer
+// (the table of the whole circuit as the tables of its layers, run one by one, back to back).
 hipError_t launch_build_mats(const CircDev& c, const float* params, const float* feats,
                              int64_t samples, int inverse, const int* order, const int* exec_of, float* out,
-                             double* side, hipStream_t st);
+                             double* side, hipStream_t st, int period = 0);
 // bytes of the side buffer launch_build_mats needs (phase factors and the last qubit's matrices in double)
 inline size_t build_mats_side_bytes(const CircDev& c, int64_t samples) {
     const size_t tables = (size_t)(c.reupload ? samples : 1);

@@ -544,20 +544,26 @@ __device__ __forceinline__ void store_m(M2& u, float* out8) {
     for (int k = 0; k < 4; ++k) { out8[2 * k] = (float)u.r[k]; out8[2 * k + 1] = (float)u.i[k]; }
 }
 
+// Entry pos of an order table.  period > 0: the table has `period` entries and describes one layer;
+// it repeats for every layer (entry pos of layer pos / period is that layer's entry pos % period).
+__device__ __forceinline__ int ordered(const int* table, int period, int pos) {
+    return period > 0 ? (pos / period) * period + table[pos % period] : table[pos];
+}
+
 // Two steps, so that every thread does the same amount of work.  Step 1, one thread per matrix:
 // build it, and for every qubit but the last store it without its phase factor and note the factor;
 // the last qubit's matrix is kept in double.  Step 2, one thread per (sample, layer): multiply the
 // last qubit's matrix by the product of the layer's factors and store it.
 // side: [tables][L*n] factors (2 doubles each), then [tables][L] matrices (8 doubles each).
 __global__ __launch_bounds__(256) void k_build_mats(CircDev c, const float* params, const float* feats,
-                                                    u64 count, int inverse, const int* order,
+                                                    u64 count, int inverse, const int* order, int period,
                                                     float* out, double* side) {
     const u64 idx = (u64)blockIdx.x * 256 + threadIdx.x;
     if (idx >= count) return;
     const u64 per = (u64)c.n_layers * c.n;
     const u64 sample = idx / per;
     const int pos = (int)(idx % per);
-    const int lq = order ? order[pos] : pos;
+    const int lq = order ? ordered(order, period, pos) : pos;
     const int l = lq / c.n, q = lq % c.n;
     M2 u = fused_raw(c, params, feats, sample, l, q, -1, 0.0, inverse);
     if (q + 1 < c.n) {
@@ -576,10 +582,10 @@ __global__ __launch_bounds__(256) void k_build_mats(CircDev c, const float* para
 // One table shared by the whole batch and few qubits: one launch in which the thread of a layer's
 // last qubit recomputes that layer's factors itself.
 __global__ __launch_bounds__(256) void k_build_mats_shared(CircDev c, const float* params, u64 count,
-                                                           int inverse, const int* order, float* out) {
+                                                           int inverse, const int* order, int period, float* out) {
     const u64 idx = (u64)blockIdx.x * 256 + threadIdx.x;
     if (idx >= count) return;
-    const int lq = order ? order[idx] : (int)idx;
+    const int lq = order ? ordered(order, period, (int)idx) : (int)idx;
     const int l = lq / c.n, q = lq % c.n;
     M2 u = fused_raw(c, params, nullptr, 0, l, q, -1, 0.0, inverse);
     if (q + 1 < c.n) strip_phase(u);
@@ -587,7 +593,7 @@ __global__ __launch_bounds__(256) void k_build_mats_shared(CircDev c, const floa
     store_m(u, out + idx * 8);
 }
 
-__global__ __launch_bounds__(256) void k_build_mats_last(CircDev c, u64 tables, const int* exec_of,
+__global__ __launch_bounds__(256) void k_build_mats_last(CircDev c, u64 tables, const int* exec_of, int period,
                                                          float* out, const double* side) {
     const u64 idx = (u64)blockIdx.x * 256 + threadIdx.x;
     if (idx >= tables * c.n_layers) return;
@@ -606,7 +612,7 @@ __global__ __launch_bounds__(256) void k_build_mats_last(CircDev c, u64 tables, 
     for (int k = 0; k < 4; ++k) { u.r[k] = ms[2 * k]; u.i[k] = ms[2 * k + 1]; }
     scale_m(u, acc.r, acc.i);
     const int lq = l * c.n + c.n - 1;
-    const u64 pos = exec_of ? (u64)exec_of[lq] : (u64)lq;
+    const u64 pos = exec_of ? (u64)ordered(exec_of, period, lq) : (u64)lq;
     store_m(u, out + (sample * per + pos) * 8);
 }
 
@@ -1703,22 +1709,23 @@ hipError_t launch_naive_cz_ladder(float2* state, int64_t rows, int n, hipStream_
 
 hipError_t launch_build_mats(const CircDev& c, const float* params, const float* feats,
                              int64_t samples, int inverse, const int* order, const int* exec_of, float* out,
-                             double* side, hipStream_t st) {
+                             double* side, hipStream_t st, int period) {
+    if (period < 0 || (period > 0 && period != c.n)) return hipErrorInvalidValue;
     const u64 tables = (u64)(c.reupload ? samples : 1);
     const u64 count = tables * c.n_layers * c.n;
     if (count == 0) return hipSuccess;
     if ((order == nullptr) != (exec_of == nullptr)) return hipErrorInvalidValue;
     if (!c.reupload && c.n <= 8) {   // few qubits: the serial factor loop is shorter than a second launch
         hipLaunchKernelGGL(k_build_mats_shared, dim3(blocks_for(count, 256)), dim3(256), 0, st, c, params,
-                           count, inverse, order, out);
+                           count, inverse, order, period, out);
         return hipGetLastError();
     }
     hipLaunchKernelGGL(k_build_mats, dim3(blocks_for(count, 256)), dim3(256), 0, st, c, params, feats,
-                       count, inverse, order, out, side);
+                       count, inverse, order, period, out, side);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL(k_build_mats_last, dim3(blocks_for(tables * c.n_layers, 256)), dim3(256), 0, st, c,
-                       tables, exec_of, out, side);
+                       tables, exec_of, period, out, side);
     return hipGetLastError();
 }
 
