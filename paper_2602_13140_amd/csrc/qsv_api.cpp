@@ -67,6 +67,7 @@ struct qsv_ctx {
     int opt_split = -1;      // state rows of a launch sequence in two halves on two streams; -1: by state size
     hipStream_t side = nullptr;          // second stream for that (default priority, non-blocking)
     hipEvent_t ev_fork = nullptr, ev_join = nullptr;
+    bool forked = false;                 // a caller further up already runs two halves on the two streams
     std::vector<CachedPlan> cache;
     size_t ops_used = 0;
 };
@@ -332,7 +333,7 @@ qsv_status run_circuit(qsv_ctx* ctx, const qsv_circuit& c, const Prepared& pr, f
     // 512 MiB, 1.2 % at 1 GiB.
     const uint64_t state_bytes = ((uint64_t)rows << n) * 8;
     const bool split = rows >= 2 && n > pl.tile && pl.passes.size() >= 2 &&
-                       ctx->opt_split != 0;
+                       ctx->opt_split != 0 && !ctx->forked;
     const int64_t rows_a = split ? rows / 2 : rows, rows_b = rows - rows_a;
     struct Join {      // the second stream always rejoins the caller's, also when a launch fails
         qsv_ctx* c; bool on;
@@ -944,9 +945,8 @@ static qsv_status adjoint_impl(qsv_ctx* ctx, const qsv_circuit* c, const float* 
     if (nblk > 1024) nblk = 1024;
     double* npart = (double*)ar.take((size_t)B * nblk * 8);
     double* inv = (double*)ar.take((size_t)B * 8);
-    float* mats = (float*)ar.take(mats_bytes(*c, n, B));
     double* f = (double*)ar.take((size_t)B * per * 8);
-    if (!npart || !inv || !mats || !f) return ws_fail(ctx, ar, "qsv_adjoint_grad");
+    if (!npart || !inv || !f) return ws_fail(ctx, ar, "qsv_adjoint_grad");
     QSV_HIP(ctx, launch_norms(x_dev, B, dim, npart, nblk, inv, nullptr, ctx->stream), "norms");
 
     // Two ways to have psi at the start of every layer on the way back.  With room for L + 1 states per
@@ -958,41 +958,56 @@ static qsv_status adjoint_impl(qsv_ctx* ctx, const qsv_circuit* c, const float* 
     const size_t zbytes = (size_t)chunk_blocks(n) * 13 * 8;
     const size_t small_bytes = tpart + zbytes + 2 * (size_t)n * 8 + 6 * kAlign;
     const size_t ckpt_bytes = (size_t)B * (size_t)(L + 1) * state_bytes;
+    const size_t tables = mats_bytes(*c, n, B);
     const bool keep = ctx->opt_grad_layered && P > 0 &&
-                      ar.remaining() >= align_up(ckpt_bytes) + state_bytes + small_bytes + 2 * kAlign;
+                      ar.remaining() >= align_up(ckpt_bytes) + state_bytes + small_bytes + 2 * tables + 2 * kAlign;
     float2* ckpt = keep ? (float2*)ar.take(ckpt_bytes) : nullptr;
     if (keep && !ckpt) return ws_fail(ctx, ar, "qsv_adjoint_grad");
+    // The samples go through the sweep in chunks; with two samples or more the chunks alternate
+    // between the caller's stream and the context's second one, each with scratch of its own, so that
+    // the launch gaps and tails of one chunk's kernels are covered by the other's.
     const size_t sample_bytes = (keep ? 1 : 3) * state_bytes + small_bytes;
-    int64_t chunk = (int64_t)(ar.remaining() / sample_bytes);
-    if (chunk < 1) { ar.need = ar.off + sample_bytes; return ws_fail(ctx, ar, "qsv_adjoint_grad"); }
+    const bool two = B >= 2 && ctx->opt_split != 0 && !ctx->forked &&
+                     ar.remaining() >= 2 * (sample_bytes + tables + kAlign);
+    const int sets = two ? 2 : 1;
+    if (ar.remaining() < sets * (tables + kAlign)) { ar.need = ar.off + sets * (tables + kAlign) + sample_bytes; return ws_fail(ctx, ar, "qsv_adjoint_grad"); }
+    int64_t chunk = (int64_t)((ar.remaining() - sets * (tables + kAlign)) / (sets * sample_bytes));
+    if (chunk < 1) { ar.need = ar.off + sets * (tables + kAlign + sample_bytes); return ws_fail(ctx, ar, "qsv_adjoint_grad"); }
+    if (two && chunk > (B + 1) / 2) chunk = (B + 1) / 2;
     if (chunk > B) chunk = B;
     if (chunk > 16384) chunk = 16384;   // rows of a chunk index a grid dimension
     if (ctx->opt_grad_chunk > 0 && chunk > ctx->opt_grad_chunk) chunk = ctx->opt_grad_chunk;
     // keep row counts a power of two when several rows share a tile (extended-index tiling)
     if (chunk < B) { int64_t p2 = 1; while (p2 * 2 <= chunk) p2 *= 2; chunk = p2; }
-    float2* Abuf = keep ? nullptr : (float2*)ar.take((size_t)chunk * state_bytes);
-    float2* S = (float2*)ar.take((size_t)(keep ? 1 : 2) * chunk * state_bytes);
-    double* tp = (double*)ar.take((size_t)chunk * tpart);
-    double* zpart = (double*)ar.take((size_t)chunk * zbytes);
-    double* zall = (double*)ar.take((size_t)chunk * n * 8);
-    double* coef = (double*)ar.take((size_t)chunk * n * 8);
-    if ((!keep && !Abuf) || !S || !tp || !zpart || !zall || !coef) return ws_fail(ctx, ar, "qsv_adjoint_grad");
+    struct Scratch { float* mats; float2 *Abuf, *S; double *tp, *zpart, *zall, *coef; } scr[2];
+    for (int i = 0; i < sets; ++i) {
+        Scratch& sc = scr[i];
+        sc.mats = (float*)ar.take(tables);
+        sc.Abuf = keep ? nullptr : (float2*)ar.take((size_t)chunk * state_bytes);
+        sc.S = (float2*)ar.take((size_t)(keep ? 1 : 2) * chunk * state_bytes);
+        sc.tp = (double*)ar.take((size_t)chunk * tpart);
+        sc.zpart = (double*)ar.take((size_t)chunk * zbytes);
+        sc.zall = (double*)ar.take((size_t)chunk * n * 8);
+        sc.coef = (double*)ar.take((size_t)chunk * n * 8);
+        if (!sc.mats || (!keep && !sc.Abuf) || !sc.S || !sc.tp || !sc.zpart || !sc.zall || !sc.coef)
+            return ws_fail(ctx, ar, "qsv_adjoint_grad");
+    }
 
     const int slots_n = (c->reupload + c->n_rot) * n;
     const size_t amps = (size_t)1 << n;
     auto ck = [&](int l, int64_t b0) { return ckpt + ((size_t)l * (size_t)B + (size_t)b0) * amps; };
     qsv_circuit one = *c;
     one.n_layers = 1;
-    for (int64_t b0 = 0; b0 < B; b0 += chunk) {
-        const int64_t bc = (B - b0) < chunk ? (B - b0) : chunk;
+    // one chunk of samples b0 .. b0 + bc - 1 on ctx->stream, with the scratch set sc
+    auto run_chunk = [&](int64_t b0, int64_t bc, const Scratch& sc) -> qsv_status {
         // forward: rows are samples b0..b0+bc-1
         RowMap rm1;
         rm1.grad = 1; rm1.two_p = 0; rm1.per = 1; rm1.row0 = b0; rm1.slots_n = slots_n < 1 ? 1 : slots_n; rm1.n = n;
-        float2* A = keep ? ck(L, b0) : Abuf;                 // the final states of the chunk
+        float2* A = keep ? ck(L, b0) : sc.Abuf;                 // the final states of the chunk
         if (keep) {
             QSV_HIP(ctx, launch_encode_write(x_dev, dim, n, bc, inv, rm1, ck(0, b0), ctx->stream), "encode rows");
             Prepared all;
-            st = prepare_layers(ctx, *c, one, bc, 0, params_dev, feats_dev, B, mats, &all);
+            st = prepare_layers(ctx, *c, one, bc, 0, params_dev, feats_dev, B, sc.mats, &all);
             if (st != QSV_OK) return st;
             for (int l = 0; l < L; ++l) {
                 // the start states are addressed by sample (ck(l, 0)), the rows written are the chunk's
@@ -1002,27 +1017,27 @@ static qsv_status adjoint_impl(qsv_ctx* ctx, const qsv_circuit* c, const float* 
         } else {
             QSV_HIP(ctx, launch_encode_write(x_dev, dim, n, bc, inv, rm1, A, ctx->stream), "encode rows");
             Prepared pr;
-            st = prepare_circuit(ctx, *c, bc, 0, 0, params_dev, feats_dev, B, mats, &pr);
+            st = prepare_circuit(ctx, *c, bc, 0, 0, params_dev, feats_dev, B, sc.mats, &pr);
             if (st != QSV_OK) return st;
             st = run_circuit(ctx, *c, pr, A, bc, 0, nullptr, rm1);
             if (st != QSV_OK) return st;
         }
         // the loss of every sample of the chunk into f[sample][2P]
         if (kind == 0) {
-            QSV_HIP(ctx, launch_expz_block(A, bc, n, zpart, ctx->stream), "expz block");
-            QSV_HIP(ctx, launch_expz_finish_scatter(zpart, bc, n, obs_qubit, f, Scatter{b0, 1, per, 2 * P},
+            QSV_HIP(ctx, launch_expz_block(A, bc, n, sc.zpart, ctx->stream), "expz block");
+            QSV_HIP(ctx, launch_expz_finish_scatter(sc.zpart, bc, n, obs_qubit, f, Scatter{b0, 1, per, 2 * P},
                                                     ctx->stream),
                     "expz finish");
         } else if (kind == 1) {
-            QSV_HIP(ctx, launch_trash_loss(A, n, mask, bc, b0, P, zpart, f, ctx->stream), "trash loss");
+            QSV_HIP(ctx, launch_trash_loss(A, n, mask, bc, b0, P, sc.zpart, f, ctx->stream), "trash loss");
         } else {
-            QSV_HIP(ctx, launch_expz_block(A, bc, n, zpart, ctx->stream), "expz block");
-            QSV_HIP(ctx, launch_expz_finish(zpart, bc, n, -1, nullptr, zall, ctx->stream), "expz finish");
-            QSV_HIP(ctx, launch_mse_coef(zall, targets_dev, n, bc, b0, P, coef, f, ctx->stream), "mse loss");
+            QSV_HIP(ctx, launch_expz_block(A, bc, n, sc.zpart, ctx->stream), "expz block");
+            QSV_HIP(ctx, launch_expz_finish(sc.zpart, bc, n, -1, nullptr, sc.zall, ctx->stream), "expz finish");
+            QSV_HIP(ctx, launch_mse_coef(sc.zall, targets_dev, n, bc, b0, P, sc.coef, f, ctx->stream), "mse loss");
         }
-        if (P == 0) continue;
+        if (P == 0) return QSV_OK;
         // backward: lambda = O psi (and psi beside it unless its states were kept), taken back layer by layer
-        QSV_HIP(ctx, launch_adj_init(A, n, kind, obs_qubit, mask, coef, bc, S, keep ? 0 : 1, ctx->stream),
+        QSV_HIP(ctx, launch_adj_init(A, n, kind, obs_qubit, mask, sc.coef, bc, sc.S, keep ? 0 : 1, ctx->stream),
                 "adjoint init");
         RowMap rm2 = rm1;
         if (!keep) {
@@ -1031,17 +1046,61 @@ static qsv_status adjoint_impl(qsv_ctx* ctx, const qsv_circuit* c, const float* 
         }
         const int64_t back_rows = keep ? bc : 2 * bc;
         Prepared back;      // all layers' inverse matrices by one launch
-        st = prepare_layers(ctx, *c, one, back_rows, 1, params_dev, feats_dev, B, mats, &back);
+        st = prepare_layers(ctx, *c, one, back_rows, 1, params_dev, feats_dev, B, sc.mats, &back);
         if (st != QSV_OK) return st;
         for (int l = L - 1; l >= 0; --l) {
-            st = run_circuit(ctx, one, layer_of(back, l, n), S, back_rows, 1, nullptr, rm2);
+            st = run_circuit(ctx, one, layer_of(back, l, n), sc.S, back_rows, 1, nullptr, rm2);
             if (st != QSV_OK) return st;
-            const float2* psi0 = keep ? ck(l, b0) : S;
-            const float2* lam0 = keep ? S : S + amps;
-            QSV_HIP(ctx, launch_adj_layer(psi0, lam0, keep ? 1 : 2, n, bc, tp, cd, l, params_dev, feats_dev, b0, P, f,
+            const float2* psi0 = keep ? ck(l, b0) : sc.S;
+            const float2* lam0 = keep ? sc.S : sc.S + amps;
+            QSV_HIP(ctx, launch_adj_layer(psi0, lam0, keep ? 1 : 2, n, bc, sc.tp, cd, l, params_dev, feats_dev, b0, P, f,
                                           ctx->stream),
                     "adjoint layer");
         }
+        return QSV_OK;
+    };
+    // chunk i runs on stream i % 2 with scratch set i % 2 (stream order guards the reuse of a set)
+    struct Fork {
+        qsv_ctx* c; hipStream_t main; bool on;
+        ~Fork() {
+            c->stream = main;
+            if (!on) return;
+            c->forked = false;
+            if (hipEventRecord(c->ev_join, c->side) == hipSuccess) (void)hipStreamWaitEvent(main, c->ev_join, 0);
+        }
+    } fork{ctx, ctx->stream, false};
+    if (two && chunk < B) {
+        // Plans are uploaded on the stream that first asks for them: have the ones the chunks will use
+        // in place before the second stream branches off (three calls: should the second one recycle
+        // the plan buffer, the third brings the first plan back).
+        if (!(ctx->opt_naive || n < kRegBits)) {
+            const CachedPlan* warm = nullptr;
+            for (int k = 0; k < 3; ++k) {
+                const bool inv_plan = (k == 1);
+                if (inv_plan && P == 0) continue;
+                st = get_plan(ctx, (inv_plan || keep) ? one : *c, chunk, inv_plan ? 1 : 0, 0, &warm);
+                if (st != QSV_OK) return st;
+            }
+        }
+        QSV_HIP(ctx, hipEventRecord(ctx->ev_fork, ctx->stream), "fork");
+        QSV_HIP(ctx, hipStreamWaitEvent(ctx->side, ctx->ev_fork, 0), "fork");
+        fork.on = true;
+        ctx->forked = true;
+    }
+    int64_t ci = 0;
+    for (int64_t b0 = 0; b0 < B; b0 += chunk, ++ci) {
+        const int64_t bc = (B - b0) < chunk ? (B - b0) : chunk;
+        const int set = fork.on ? (int)(ci & 1) : 0;
+        ctx->stream = set ? ctx->side : fork.main;
+        st = run_chunk(b0, bc, scr[set]);
+        if (st != QSV_OK) return st;
+    }
+    ctx->stream = fork.main;
+    if (fork.on) {        // the finishing kernel sees both streams' work
+        fork.on = false;
+        ctx->forked = false;
+        QSV_HIP(ctx, hipEventRecord(ctx->ev_join, ctx->side), "join");
+        QSV_HIP(ctx, hipStreamWaitEvent(ctx->stream, ctx->ev_join, 0), "join");
     }
     QSV_HIP(ctx, launch_grad_finish(f, B, P, cd, feats_dev, loss_dev, grad_dev, mean_loss_dev,
                                     mean_grad_dev, ctx->stream),

@@ -707,8 +707,11 @@ def test_rows_in_two_halves_on_two_streams_give_the_same_bits(oracle, n, B, tile
         loss = torch.zeros(B, dtype=torch.float32, device="cuda")
         grad = torch.zeros((B, P), dtype=torch.float32, device="cuda")
         ctx.qsv_param_shift_grad(circ, xd, pd, fd, n - 1, loss, grad)
+        # reverse mode: the samples go in chunks that alternate between the two streams
+        aloss, agrad = torch.zeros_like(loss), torch.zeros_like(grad)
+        ctx.qsv_adjoint_grad(circ, xd, pd, fd, n - 1, aloss, agrad)
         torch.cuda.synchronize()
-        res.append((state, z.clone(), loss.clone(), grad.clone()))
+        res.append((state, z.clone(), loss.clone(), grad.clone(), aloss, agrad))
         ctx.close()
     for a, b in zip(*res):
         assert torch.equal(a, b)
