@@ -970,9 +970,12 @@ static qsv_status adjoint_impl(qsv_ctx* ctx, const qsv_circuit* c, const float* 
     const bool two = B >= 2 && ctx->opt_split != 0 && !ctx->forked &&
                      ar.remaining() >= 2 * (sample_bytes + tables + kAlign);
     const int sets = two ? 2 : 1;
-    if (ar.remaining() < sets * (tables + kAlign)) { ar.need = ar.off + sets * (tables + kAlign) + sample_bytes; return ws_fail(ctx, ar, "qsv_adjoint_grad"); }
-    int64_t chunk = (int64_t)((ar.remaining() - sets * (tables + kAlign)) / (sets * sample_bytes));
-    if (chunk < 1) { ar.need = ar.off + sets * (tables + kAlign + sample_bytes); return ws_fail(ctx, ar, "qsv_adjoint_grad"); }
+    const size_t fixed = (size_t)sets * (tables + kAlign);
+    int64_t chunk = ar.remaining() > fixed ? (int64_t)((ar.remaining() - fixed) / (sets * sample_bytes)) : 0;
+    if (chunk < 1) {
+        ar.need = ar.off + fixed + sets * sample_bytes;
+        return ws_fail(ctx, ar, "qsv_adjoint_grad");
+    }
     if (two && chunk > (B + 1) / 2) chunk = (B + 1) / 2;
     if (chunk > B) chunk = B;
     if (chunk > 16384) chunk = 16384;   // rows of a chunk index a grid dimension
