@@ -719,3 +719,32 @@ def test_rows_in_two_halves_on_two_streams_give_the_same_bits(oracle, n, B, tile
     oracle.apply_layers(ref, ocirc(oracle, spec), params, feats)
     s = res[1][0].cpu().numpy()
     assert np.abs((s[..., 0] + 1j * s[..., 1]) - ref).max() <= amp_tol(n)
+
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("extra_states", [0, 1, 2, 3, 5, 8, 13, 40])
+def test_reverse_mode_with_every_amount_of_workspace(oracle, extra_states):
+    """From the smallest workspace the boundary accepts upwards, state by state: the reverse-mode
+    gradient picks between taking psi back and keeping the forward states, between one and two
+    scratch sets (one or two streams) and between chunk sizes by what fits, and every choice must
+    give the oracle's loss and gradient."""
+    torch = gu.torch_cuda()
+    n, B = 12, 5
+    g = rng(4242)
+    spec = wl.CircuitSpec(3, (RY, RZ), RING, 1)
+    P = spec.num_params(n)
+    params = wl.draw_params(spec, n, 4243)
+    x = g.standard_normal((B, 1 << n)).astype(np.float32)
+    feats = g.standard_normal((B, n)).astype(np.float32)
+    lref, gref = oracle.param_shift_grad(x, n, ocirc(oracle, spec), params, feats, obs_qubit=3)
+    ws = qb.qsv_workspace_bytes(n, B) + extra_states * (8 << n)
+    ctx = gu.make_ctx(n, B, tile=10, ws_bytes=ws)
+    loss = torch.zeros(B, dtype=torch.float32, device="cuda")
+    grad = torch.zeros((B, P), dtype=torch.float32, device="cuda")
+    ctx.qsv_adjoint_grad(qb.circuit_from_spec(spec), gu.dev(x), gu.dev(params), gu.dev(feats), 3, loss, grad)
+    torch.cuda.synchronize()
+    assert np.abs(loss.cpu().numpy() - lref).max() <= 1e-5
+    gg = grad.cpu().numpy()
+    assert np.abs(gg - gref).max() <= 1e-4
+    assert np.linalg.norm(gg - gref) <= 1e-3 * np.linalg.norm(gref) + 1e-7
+    ctx.close()
