@@ -44,6 +44,8 @@ def parse_args():
                          "of the pass kernel's access pattern; also the known-size copy used to scale "
                          "rocprofv3's FETCH_SIZE/WRITE_SIZE counters)")
     ap.add_argument("--rev", type=int, default=-1, help="every other pass takes its tiles in descending order (1) or not (0)")
+    ap.add_argument("--probe-transposes", type=int, default=0,
+                    help="probe pass: moves of the register run through LDS between the tile's load and its store")
     ap.add_argument("--probe-layout", type=int, default=-1,
                     help="probe pass: start of the register run the tile is loaded and stored in (-1 = highest)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
@@ -393,11 +395,11 @@ def probe(torch, qb, args):
     out = []
     for c, w in ((tile, tile), (8, n - (tile - 8)), (6, n - (tile - 6)), (5, n - (tile - 5)), (4, 10), (4, n - (tile - 4))):
         for _ in range(3):
-            ctx.qsv_probe_pass(c, w, 0)
+            ctx.qsv_probe_pass(c, w, args.probe_transposes)
         a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         a.record()
         for _ in range(args.steps):
-            ctx.qsv_probe_pass(c, w, 0)
+            ctx.qsv_probe_pass(c, w, args.probe_transposes)
         b.record()
         torch.cuda.synchronize()
         ms = a.elapsed_time(b) / args.steps
