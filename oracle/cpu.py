@@ -1,8 +1,10 @@
 """ctypes loader and numpy-facing wrappers for the C++ oracle (test infrastructure only).
 
-Argument marshalling only: every number comes from ``qsv_oracle.cpp``.  States are numpy
-complex128 arrays of shape [B, 2**n]; parameters and features are converted to float64 exactly
-(they are float32 on the GPU side).
+The circuit, measurement, sampling and gradient functions only marshal arguments: their numbers
+come from ``qsv_oracle.cpp``.  Three small definitions are written here in numpy instead
+(``shot_expz``, ``sgd_step``, ``adam_step``); each is pinned by closed forms in the CPU tests like
+the C++ functions.  States are numpy complex128 arrays of shape [B, 2**n]; parameters and features
+are converted to float64 exactly (they are float32 on the GPU side).
 """
 import ctypes
 import os
@@ -125,7 +127,12 @@ def gate_cz(state, q0, q1):
         raise ValueError("oracle_gate_cz rc=%d" % rc)
 
 
-def apply_layers(state, circ, params, feats=None, inverse=False):
+MODE_AUTO, MODE_PER_SAMPLE, MODE_PER_PAIR = 0, 1, 2
+
+
+def apply_layers(state, circ, params, feats=None, inverse=False, mode=MODE_AUTO):
+    """mode only chooses how the work is spread over threads (one thread per sample, or every
+    gate's pair loop split across threads; auto = the latter from 18 qubits on)."""
     B, n = _state(state)
     params = np.ascontiguousarray(params, dtype=np.float64).ravel()
     assert params.size == num_params(circ, n), (params.size, num_params(circ, n))
@@ -133,9 +140,10 @@ def apply_layers(state, circ, params, feats=None, inverse=False):
     if feats is not None:
         f = np.ascontiguousarray(feats, dtype=np.float64)
         assert f.shape == (B, n)
-    rc = lib().oracle_apply_layers(_p(state), ctypes.c_int64(B), ctypes.c_int(n),
-                                   ctypes.byref(circ), _p(params),
-                                   _p(f) if f is not None else None, ctypes.c_int(int(inverse)))
+    rc = lib().oracle_apply_layers_mode(_p(state), ctypes.c_int64(B), ctypes.c_int(n),
+                                        ctypes.byref(circ), _p(params),
+                                        _p(f) if f is not None else None, ctypes.c_int(int(inverse)),
+                                        ctypes.c_int(int(mode)))
     if rc:
         raise ValueError("oracle_apply_layers rc=%d" % rc)
 

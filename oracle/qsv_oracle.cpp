@@ -68,12 +68,17 @@ int64_t oracle_num_params(const oracle_circuit* c, int n) {
 }
 
 // ---------------------------------------------------------------- single gates
-// Rotation exp(-i theta P/2) on qubit q of every sample.  axis: 1 X, 2 Y, 3 Z.
-static void rot_one(cplx* a, int n, int axis, int q, double theta) {
+// One body per gate.  par != 0 splits the gate's loop over index pairs across threads (used for
+// large states, one sample at a time); par == 0 runs it on the calling thread (used under a loop
+// that is parallel over samples).  The pairs of one gate are disjoint and nothing is summed, so
+// the numbers do not depend on par or on the thread count.
+// Rotation exp(-i theta P/2) on qubit q.  axis: 1 X, 2 Y, 3 Z.
+static void rot_one(cplx* a, int n, int axis, int q, double theta, int par) {
     const int64_t half = (int64_t)1 << (n - 1);
     const int64_t bit = (int64_t)1 << q;
     const double c = std::cos(0.5 * theta), s = std::sin(0.5 * theta);
     const cplx I(0.0, 1.0);
+#pragma omp parallel for schedule(static) if (par)
     for (int64_t i = 0; i < half; ++i) {
         const int64_t k0 = ((i >> q) << (q + 1)) | (i & (bit - 1));
         const int64_t k1 = k0 | bit;
@@ -91,9 +96,10 @@ static void rot_one(cplx* a, int n, int axis, int q, double theta) {
     }
 }
 
-static void cnot_one(cplx* a, int n, int ctrl, int tgt) {
+static void cnot_one(cplx* a, int n, int ctrl, int tgt, int par) {
     const int64_t dim = (int64_t)1 << n;
     const int64_t cb = (int64_t)1 << ctrl, tb = (int64_t)1 << tgt;
+#pragma omp parallel for schedule(static) if (par)
     for (int64_t k = 0; k < dim; ++k) {
         if ((k & cb) && !(k & tb)) {
             const cplx t = a[k];
@@ -103,9 +109,10 @@ static void cnot_one(cplx* a, int n, int ctrl, int tgt) {
     }
 }
 
-static void cz_one(cplx* a, int n, int q0, int q1) {
+static void cz_one(cplx* a, int n, int q0, int q1, int par) {
     const int64_t dim = (int64_t)1 << n;
     const int64_t m = ((int64_t)1 << q0) | ((int64_t)1 << q1);
+#pragma omp parallel for schedule(static) if (par)
     for (int64_t k = 0; k < dim; ++k)
         if ((k & m) == m) a[k] = -a[k];
 }
@@ -114,7 +121,7 @@ int oracle_gate_rot(cplx* state, int64_t B, int n, int axis, int q, double theta
     if (n < 1 || q < 0 || q >= n || axis < 1 || axis > 3) return 1;
     const int64_t dim = (int64_t)1 << n;
 #pragma omp parallel for schedule(static)
-    for (int64_t b = 0; b < B; ++b) rot_one(state + b * dim, n, axis, q, theta);
+    for (int64_t b = 0; b < B; ++b) rot_one(state + b * dim, n, axis, q, theta, 0);
     return 0;
 }
 
@@ -122,7 +129,7 @@ int oracle_gate_cnot(cplx* state, int64_t B, int n, int ctrl, int tgt) {
     if (n < 2 || ctrl == tgt || ctrl < 0 || tgt < 0 || ctrl >= n || tgt >= n) return 1;
     const int64_t dim = (int64_t)1 << n;
 #pragma omp parallel for schedule(static)
-    for (int64_t b = 0; b < B; ++b) cnot_one(state + b * dim, n, ctrl, tgt);
+    for (int64_t b = 0; b < B; ++b) cnot_one(state + b * dim, n, ctrl, tgt, 0);
     return 0;
 }
 
@@ -130,55 +137,8 @@ int oracle_gate_cz(cplx* state, int64_t B, int n, int q0, int q1) {
     if (n < 2 || q0 == q1 || q0 < 0 || q1 < 0 || q0 >= n || q1 >= n) return 1;
     const int64_t dim = (int64_t)1 << n;
 #pragma omp parallel for schedule(static)
-    for (int64_t b = 0; b < B; ++b) cz_one(state + b * dim, n, q0, q1);
+    for (int64_t b = 0; b < B; ++b) cz_one(state + b * dim, n, q0, q1, 0);
     return 0;
-}
-
-// ------------------------------------------------- gates parallel over index pairs (large n)
-// Same arithmetic as rot_one/cnot_one/cz_one; the loop over pairs is split across threads.  The
-// pairs of one gate are disjoint, so the result does not depend on the thread count.
-static void rot_par(cplx* a, int n, int axis, int q, double theta) {
-    const int64_t half = (int64_t)1 << (n - 1);
-    const int64_t bit = (int64_t)1 << q;
-    const double c = std::cos(0.5 * theta), s = std::sin(0.5 * theta);
-    const cplx I(0.0, 1.0);
-#pragma omp parallel for schedule(static)
-    for (int64_t i = 0; i < half; ++i) {
-        const int64_t k0 = ((i >> q) << (q + 1)) | (i & (bit - 1));
-        const int64_t k1 = k0 | bit;
-        const cplx v0 = a[k0], v1 = a[k1];
-        if (axis == 1) {
-            a[k0] = c * v0 - I * s * v1;
-            a[k1] = -I * s * v0 + c * v1;
-        } else if (axis == 2) {
-            a[k0] = c * v0 - s * v1;
-            a[k1] = s * v0 + c * v1;
-        } else {
-            a[k0] = cplx(c, -s) * v0;
-            a[k1] = cplx(c, s) * v1;
-        }
-    }
-}
-
-static void cnot_par(cplx* a, int n, int ctrl, int tgt) {
-    const int64_t dim = (int64_t)1 << n;
-    const int64_t cb = (int64_t)1 << ctrl, tb = (int64_t)1 << tgt;
-#pragma omp parallel for schedule(static)
-    for (int64_t k = 0; k < dim; ++k) {
-        if ((k & cb) && !(k & tb)) {
-            const cplx t = a[k];
-            a[k] = a[k | tb];
-            a[k | tb] = t;
-        }
-    }
-}
-
-static void cz_par(cplx* a, int n, int q0, int q1) {
-    const int64_t dim = (int64_t)1 << n;
-    const int64_t m = ((int64_t)1 << q0) | ((int64_t)1 << q1);
-#pragma omp parallel for schedule(static)
-    for (int64_t k = 0; k < dim; ++k)
-        if ((k & m) == m) a[k] = -a[k];
 }
 
 // ---------------------------------------------------------------- amplitude encoding
@@ -203,8 +163,7 @@ int oracle_amp_encode(const float* x, int64_t B, int64_t dim, int n, cplx* state
 }
 
 // ---------------------------------------------------------------- layered circuit
-// One sample's circuit, gates applied one at a time.  par != 0 splits each gate's pair loop
-// across threads (for large n); par == 0 is the serial form used under a batch-parallel loop.
+// One sample's circuit, gates applied one at a time.  par is handed to every gate (see above).
 // shift_p >= 0 adds shift to the ANGLE of parameter shift_p (for a re-upload weight the angle is
 // w*feat, and the shift is added to that product).
 static void run_circuit(cplx* a, int n, const oracle_circuit* c, const double* params,
@@ -218,15 +177,9 @@ static void run_circuit(cplx* a, int n, const oracle_circuit* c, const double* p
         if (p == shift_p) t += shift;
         return t;
     };
-    auto rot = [&](int axis, int q, double t) {
-        if (par) rot_par(a, n, axis, q, t); else rot_one(a, n, axis, q, t);
-    };
-    auto cnot = [&](int cq, int tq) {
-        if (par) cnot_par(a, n, cq, tq); else cnot_one(a, n, cq, tq);
-    };
-    auto cz = [&](int q0, int q1) {
-        if (par) cz_par(a, n, q0, q1); else cz_one(a, n, q0, q1);
-    };
+    auto rot = [&](int axis, int q, double t) { rot_one(a, n, axis, q, t, par); };
+    auto cnot = [&](int cq, int tq) { cnot_one(a, n, cq, tq, par); };
+    auto cz = [&](int q0, int q1) { cz_one(a, n, q0, q1, par); };
     if (!inverse) {
         for (int l = 0; l < c->n_layers; ++l) {
             if (c->reupload)
@@ -263,14 +216,17 @@ static int check_circuit(const oracle_circuit* c, int n) {
 }
 
 // params: double[P] (shared by the batch); feats: double[B][n] or NULL when reupload = 0.
-int oracle_apply_layers(cplx* state, int64_t B, int n, const oracle_circuit* c,
-                        const double* params, const double* feats, int inverse) {
+// mode chooses how the work is spread over threads, never what is computed: 1 = one thread per
+// sample, every gate on that thread; 2 = the samples one by one, every gate's pair loop split
+// across threads; 0 = mode 2 for n >= 18 (few, large states), else mode 1.
+int oracle_apply_layers_mode(cplx* state, int64_t B, int n, const oracle_circuit* c,
+                             const double* params, const double* feats, int inverse, int mode) {
     if (check_circuit(c, n) || B < 1) return 1;
     if (c->reupload && !feats) return 1;
+    if (mode < 0 || mode > 2) return 1;
     const int64_t N = (int64_t)1 << n;
-    // Large states: go through the samples one by one and split each gate across threads.
-    // Small states: one thread per sample.  Both give the same numbers (disjoint pairs).
-    if (n >= 18) {
+    const bool pairs = mode == 2 || (mode == 0 && n >= 18);
+    if (pairs) {
         for (int64_t b = 0; b < B; ++b)
             run_circuit(state + b * N, n, c, params, feats ? feats + b * n : nullptr, inverse, -1,
                         0.0, 1);
@@ -281,6 +237,11 @@ int oracle_apply_layers(cplx* state, int64_t B, int n, const oracle_circuit* c,
                         0.0, 0);
     }
     return 0;
+}
+
+int oracle_apply_layers(cplx* state, int64_t B, int n, const oracle_circuit* c,
+                        const double* params, const double* feats, int inverse) {
+    return oracle_apply_layers_mode(state, B, n, c, params, feats, inverse, 0);
 }
 
 // ---------------------------------------------------------------- measurement

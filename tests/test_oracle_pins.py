@@ -122,11 +122,12 @@ def ring_image(k, n):
 
 
 @pytest.mark.parametrize("n", [2, 3, 4, 5, 7])
-def test_cnot_ring_permutation(oracle, n):
+@pytest.mark.parametrize("mode", [1, 2])
+def test_cnot_ring_permutation(oracle, n, mode):
     circ = oracle.make_circuit(1, [], RING)
     N = 1 << n
     st = np.eye(N, dtype=np.complex128)          # sample k = basis state k
-    oracle.apply_layers(st, circ, np.zeros(0))
+    oracle.apply_layers(st, circ, np.zeros(0), mode=mode)
     for k in range(N):
         assert st[k, ring_image(k, n)] == 1.0 and np.count_nonzero(st[k]) == 1
     # closed form of the ring: prefix XOR, then bit 0 ^= parity of all bits
@@ -135,7 +136,7 @@ def test_cnot_ring_permutation(oracle, n):
     pre = np.bitwise_xor.accumulate(b)
     pre[0] = b[0] ^ pre[n - 1]
     assert ring_image(k, n) == sum(int(v) << q for q, v in enumerate(pre))
-    oracle.apply_layers(st, circ, np.zeros(0), inverse=True)
+    oracle.apply_layers(st, circ, np.zeros(0), inverse=True, mode=mode)
     assert np.array_equal(st, np.eye(N))
 
 
@@ -153,17 +154,18 @@ def test_ghz_from_chain(oracle):
 
 
 @pytest.mark.parametrize("n", [2, 3, 5])
-def test_cz_ladder(oracle, n):
+@pytest.mark.parametrize("mode", [1, 2])
+def test_cz_ladder(oracle, n, mode):
     circ = oracle.make_circuit(1, [], LADDER)
     st = np.eye(1 << n, dtype=np.complex128)
-    oracle.apply_layers(st, circ, np.zeros(0))
+    oracle.apply_layers(st, circ, np.zeros(0), mode=mode)
     for k in range(1 << n):
         sign = (-1) ** bin(k & (k >> 1)).count("1")
         assert st[k, k] == sign and np.count_nonzero(st[k]) == 1
     plus = oracle.zero_state(1, n)
     for q in range(n):
         oracle.gate_rot(plus, RY, q, np.pi / 2)
-    oracle.apply_layers(plus, circ, np.zeros(0))
+    oracle.apply_layers(plus, circ, np.zeros(0), mode=mode)
     assert np.allclose(oracle.probs(plus), 2.0 ** -n, atol=1e-15)
     assert np.allclose(oracle.expz_all(plus), 0.0, atol=1e-15)
 
@@ -180,7 +182,8 @@ CASES = [
 
 @pytest.mark.parametrize("n,L,rot,ent,reup", CASES)
 @pytest.mark.parametrize("inverse", [False, True])
-def test_circuit_vs_dense(oracle, n, L, rot, ent, reup, inverse):
+@pytest.mark.parametrize("mode", [1, 2])          # one thread per sample; pair loops split (the n >= 18 path)
+def test_circuit_vs_dense(oracle, n, L, rot, ent, reup, inverse, mode):
     g = rng(100 + n * 7 + L + ent + reup)
     circ = oracle.make_circuit(L, list(rot), ent, reup)
     P = oracle.num_params(circ, n)
@@ -191,7 +194,7 @@ def test_circuit_vs_dense(oracle, n, L, rot, ent, reup, inverse):
     feats = g.standard_normal((B, n)) if reup else None
     st, _ = oracle.amp_encode(x, n)
     start = st.copy()
-    oracle.apply_layers(st, circ, params, feats, inverse=inverse)
+    oracle.apply_layers(st, circ, params, feats, inverse=inverse, mode=mode)
     for b in range(B):
         U = dense.circuit_unitary(n, L, rot, ent, reup, params, feats[b] if reup else None)
         if inverse:
@@ -376,11 +379,11 @@ def test_sampler_matches_python_integers_and_histogram(oracle):
     assert np.all(np.abs(hist - p[0]) <= 5 * sigma + 1e-9)
 
 
-# ------------------------------------------------------------------ threading
+# ------------------------------------------------------------------ threading, and the large-n path
 def test_threads_do_not_change_results(oracle):
     g = rng(15)
-    for n in (5, 18):
-        circ = oracle.make_circuit(2, [RX, RY, RZ], RING)
+    for n, ent in ((5, RING), (18, RING), (18, LADDER)):
+        circ = oracle.make_circuit(2, [RX, RY, RZ], ent)
         params = g.uniform(0, 6.28, oracle.num_params(circ, n))
         x = g.standard_normal((2, 1 << n)).astype(np.float32)
         outs = []
@@ -391,6 +394,141 @@ def test_threads_do_not_change_results(oracle):
             outs.append(st)
         oracle.set_threads(oracle.max_threads())
         assert np.array_equal(outs[0], outs[1])
+
+
+def apply_gate_by_gate(oracle, st, n, L, rot, ent, reup, params, feats, inverse):
+    """The circuit through the single-gate entry points (oracle_gate_rot / cnot / cz), in the order
+    the benchmark spec gives; the gate entry points are the ones the closed forms above pin."""
+    slots = reup + len(rot)
+    p = np.asarray(params, dtype=np.float64).reshape(L, slots, n)
+
+    def angle(l, slot, q, b):
+        return p[l, slot, q] * (feats[b, q] if (reup and slot == 0) else 1.0)
+
+    for b in range(st.shape[0]):
+        row = st[b:b + 1]
+        if not inverse:
+            for l in range(L):
+                for slot in range(slots):
+                    axis = RX if (reup and slot == 0) else rot[slot - reup]
+                    for q in range(n):
+                        oracle.gate_rot(row, axis, q, angle(l, slot, q, b))
+                if ent == RING and n >= 2:
+                    for q in range(n):
+                        oracle.gate_cnot(row, q, (q + 1) % n)
+                if ent == LADDER:
+                    for q in range(n - 1):
+                        oracle.gate_cz(row, q, q + 1)
+        else:
+            for l in reversed(range(L)):
+                if ent == RING and n >= 2:
+                    for q in reversed(range(n)):
+                        oracle.gate_cnot(row, q, (q + 1) % n)
+                if ent == LADDER:
+                    for q in reversed(range(n - 1)):
+                        oracle.gate_cz(row, q, q + 1)
+                for slot in reversed(range(slots)):
+                    axis = RX if (reup and slot == 0) else rot[slot - reup]
+                    for q in reversed(range(n)):
+                        oracle.gate_rot(row, axis, q, -angle(l, slot, q, b))
+
+
+@pytest.mark.parametrize("rot,ent,reup", [((RX, RY, RZ), RING, 0), ((RY, RZ), LADDER, 0), ((RZ, RX), RING, 1)])
+@pytest.mark.parametrize("inverse", [False, True])
+def test_large_n_path_equals_gate_by_gate(oracle, rot, ent, reup, inverse):
+    """n = 18 is where apply_layers switches to pair-parallel gates (the path that judges the 20-,
+    26- and 30-qubit GPU runs): it must give, bit for bit, what the single-gate entry points give,
+    and what the per-sample mode gives."""
+    n, L, B = 18, 2, 2
+    g = rng(160 + ent + reup)
+    circ = oracle.make_circuit(L, list(rot), ent, reup)
+    params = g.uniform(0, 2 * np.pi, oracle.num_params(circ, n))
+    x = g.standard_normal((B, 1 << n)).astype(np.float32)
+    feats = g.standard_normal((B, n)) if reup else None
+    st, _ = oracle.amp_encode(x, n)
+    ref = st.copy()
+    per_sample = st.copy()
+    oracle.apply_layers(st, circ, params, feats, inverse=inverse)            # auto: pair-parallel at n = 18
+    oracle.apply_layers(per_sample, circ, params, feats, inverse=inverse, mode=1)
+    apply_gate_by_gate(oracle, ref, n, L, rot, ent, reup, params, feats, inverse)
+    assert np.array_equal(st, ref)
+    assert np.array_equal(st, per_sample)
+
+
+def test_small_n_modes_agree_bit_for_bit(oracle):
+    n, g = 5, rng(170)
+    for ent in (RING, LADDER):
+        circ = oracle.make_circuit(3, [RX, RY, RZ], ent, 1)
+        params = g.uniform(0, 2 * np.pi, oracle.num_params(circ, n))
+        feats = g.standard_normal((3, n))
+        st, _ = oracle.amp_encode(g.standard_normal((3, 1 << n)).astype(np.float32), n)
+        a, b = st.copy(), st.copy()
+        oracle.apply_layers(a, circ, params, feats, mode=1)
+        oracle.apply_layers(b, circ, params, feats, mode=2)
+        assert np.array_equal(a, b)
+
+
+def test_large_n_closed_forms(oracle):
+    """Closed forms at n = 18 through the pair-parallel path."""
+    n = 18
+    N = 1 << n
+    # (1) GHZ: RY(pi/2) on qubit 0, then the ring.  The chain CNOT(0,1)..CNOT(16,17) spreads qubit 0 over
+    # all qubits; the closing CNOT(17,0) then clears qubit 0 in the |1..1> branch: (|0..0> + |01..1>)/sqrt 2
+    # in index order (qubit 0 = lowest bit), i.e. indices 0 and 2^18 - 2.
+    circ = oracle.make_circuit(1, [RY], RING)
+    params = np.zeros(n)
+    params[0] = np.pi / 2
+    st = oracle.zero_state(1, n)
+    oracle.apply_layers(st, circ, params)
+    p = oracle.probs(st)[0]
+    assert abs(p[0] - 0.5) < 1e-15 and abs(p[N - 2] - 0.5) < 1e-15 and np.count_nonzero(p) == 2
+    z = oracle.expz_all(st)[0]
+    assert abs(z[0] - 1.0) < 1e-15 and np.allclose(z[1:], 0.0, atol=1e-15)
+    # (2) the ring as a permutation of basis states, from integer bit operations
+    ring = oracle.make_circuit(1, [], RING)
+    ks = [1, 2, 0b1011, N - 1, N >> 1, 0x2A5A5, 0x15A5A]
+    st = np.zeros((len(ks), N), dtype=np.complex128)
+    for i, k in enumerate(ks):
+        st[i, k] = 1.0
+    oracle.apply_layers(st, ring, np.zeros(0))
+    for i, k in enumerate(ks):
+        assert st[i, ring_image(k, n)] == 1.0 and np.count_nonzero(st[i]) == 1
+    oracle.apply_layers(st, ring, np.zeros(0), inverse=True)
+    for i, k in enumerate(ks):
+        assert st[i, k] == 1.0 and np.count_nonzero(st[i]) == 1
+    # (3) CZ ladder: sign (-1)^popcount(k & (k >> 1)) on basis states; |+..+> stays uniform
+    lad = oracle.make_circuit(1, [], LADDER)
+    st = np.zeros((len(ks), N), dtype=np.complex128)
+    for i, k in enumerate(ks):
+        st[i, k] = 1.0
+    oracle.apply_layers(st, lad, np.zeros(0))
+    for i, k in enumerate(ks):
+        assert st[i, k] == (-1) ** bin(k & (k >> 1)).count("1") and np.count_nonzero(st[i]) == 1
+    plus = oracle.make_circuit(1, [RY], LADDER)
+    st = oracle.zero_state(1, n)
+    oracle.apply_layers(st, plus, np.full(n, np.pi / 2))
+    assert np.allclose(oracle.probs(st), 2.0 ** -n, atol=1e-18)
+    # (4) one RY, RX, RZ on a high qubit: P(bit set) = sin^2(theta/2); RZ leaves probabilities alone
+    for axis, q, theta in ((RY, 17, 0.7), (RX, 9, 2.1)):
+        one = oracle.make_circuit(1, [axis], NONE)
+        params = np.zeros(n)
+        params[q] = theta
+        st = oracle.zero_state(1, n)
+        oracle.apply_layers(st, one, params)
+        p = oracle.probs(st)[0]
+        assert abs(p[0] - np.cos(theta / 2) ** 2) < 1e-15 and abs(p[1 << q] - np.sin(theta / 2) ** 2) < 1e-15
+        want = np.sin(theta / 2) if axis == RY else -1j * np.sin(theta / 2)
+        assert abs(st[0, 1 << q] - want) < 1e-15
+    # (5) encoder then decoder is the identity; norm preserved in between
+    g = rng(171)
+    circ = oracle.make_circuit(2, [RX, RY, RZ], RING)
+    params = g.uniform(0, 2 * np.pi, oracle.num_params(circ, n))
+    st, _ = oracle.amp_encode(g.standard_normal((1, N)).astype(np.float32), n)
+    start = st.copy()
+    oracle.apply_layers(st, circ, params)
+    assert abs(oracle.probs(st).sum() - 1.0) < 1e-12 and not np.allclose(st, start, atol=1e-3)
+    oracle.apply_layers(st, circ, params, inverse=True)
+    assert np.allclose(st, start, atol=1e-13)
 
 
 # ------------------------------------------------------------------ training losses and optimisers
@@ -582,22 +720,28 @@ def test_reset_fidelity_vs_density_matrix(oracle, n, mask, ent):
 
 
 def test_reset_fidelity_is_one_when_trash_is_already_zero(oracle):
+    """If the encoder already leaves the trash qubit in |0>, the reset changes nothing and the decoder
+    returns the input: F = 1.  The input must be real (it is amplitude-encoded), so the circuit is
+    RY-only with the ring, a real orthogonal matrix: the decoder applied to a real state with qubit 3
+    in |0> is then a real input whose encoder output has that property."""
     n, mask = 4, 0b1000
-    circ = oracle.make_circuit(2, [RY, RZ], RING)
+    circ = oracle.make_circuit(2, [RY], RING)
     params = rng(150).uniform(0, 2 * np.pi, oracle.num_params(circ, n))
-    # choose the input as the decoder applied to a state with qubit 3 in |0>: the encoder then
-    # produces exactly that state, the reset changes nothing, and the decoder returns the input
-    v = rng(151).standard_normal((2, 8)).astype(np.float32)
+    v = rng(151).standard_normal((3, 8)).astype(np.float32)
     st, _ = oracle.amp_encode(v, n)                              # amplitudes 8..15 are zero
-    oracle.apply_layers(st, circ, params, inverse=True)
-    # a_in must be real for the encoding interface: use its real part only if it is real; instead
-    # check the identity through the state itself
-    enc = st.copy()
+    oracle.apply_layers(st, circ, params, inverse=True)          # the input state a_in
+    assert np.all(st.imag == 0.0)
+    x = st.real.astype(np.float32)                               # float rounding: 1e-7 relative
+    enc, _ = oracle.amp_encode(x, n)
     oracle.apply_layers(enc, circ, params)
-    assert np.allclose(oracle.marginal(enc, mask)[:, 0], 1.0, atol=1e-12)
-    w = enc.copy()
-    oracle.apply_layers(w, circ, params, inverse=True)
-    assert np.allclose(np.abs(np.einsum("bk,bk->b", st.conj(), w)) ** 2, 1.0, atol=1e-12)
+    assert np.allclose(oracle.marginal(enc, mask)[:, 0], 1.0, atol=1e-6)
+    F = oracle.reset_fidelity(enc, circ, params, None, mask, x)
+    assert np.allclose(F, 1.0, atol=1e-6)
+    # and with the trash qubit entangled the reset loses fidelity
+    w, _ = oracle.amp_encode(rng(152).standard_normal((3, 16)).astype(np.float32), n)
+    xw = w.real.astype(np.float32)
+    oracle.apply_layers(w, circ, params)
+    assert np.all(oracle.reset_fidelity(w, circ, params, None, mask, xw) < 0.999)
 
 
 def test_shot_expz_closed_forms(oracle):
