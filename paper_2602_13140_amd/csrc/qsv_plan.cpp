@@ -10,6 +10,7 @@
 
 #include <algorithm>
 #include <cstdio>
+#include <cstring>
 
 namespace qsv {
 
@@ -395,3 +396,19 @@ std::string describe_plan(const Plan& p) {
 }
 
 }  // namespace qsv
+
+// Host-only C entry point (declared in qsv.h): the text of the plan the library would run.
+extern "C" int64_t qsv_plan_describe(const qsv_circuit* c, int n_qubits, int batch, int inverse, int tile_log2,
+                                     char* buf, int64_t buf_bytes) {
+    using namespace qsv;
+    if (!check_circuit(c, n_qubits, nullptr) || batch < 1) return -1;
+    if (tile_log2 != 0 && (tile_log2 < kMinTile || tile_log2 > kMaxTile)) return -1;
+    const Plan p = build_plan(*c, n_qubits, batch, inverse != 0, tile_log2, false);
+    const std::string s = describe_plan(p);
+    if (buf && buf_bytes > 0) {
+        const size_t ncopy = s.size() < (size_t)buf_bytes - 1 ? s.size() : (size_t)buf_bytes - 1;
+        memcpy(buf, s.data(), ncopy);
+        buf[ncopy] = 0;
+    }
+    return (int64_t)s.size();
+}
