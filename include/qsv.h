@@ -21,7 +21,11 @@
  *   - The caller owns every device buffer (state, inputs, outputs, workspace); the context owns
  *     only host-side plans.  No call allocates or frees device memory.
  *   - All work is enqueued on the HIP stream given to qsv_create and is asynchronous with respect
- *     to the host; no call synchronises the stream.  Part of a call's kernels may run on a second
+ *     to the host; no call synchronises the stream (one exception, a measurement aid and no part of
+ *     the path: qsv_probe_pass).  The pass plans of the circuits a context has run are kept in host
+ *     memory until qsv_destroy and uploaded by asynchronous copies on the stream; when the plan
+ *     region of the workspace is full it is refilled from its start, in stream order.
+ *     Part of a call's kernels may run on a second
  *     stream that the context owns (default priority); it waits for the caller's stream at the
  *     start of that work and the caller's stream waits for it before the call's remaining work, so
  *     to the caller everything is ordered as if it ran on the one stream (also under stream
@@ -48,7 +52,9 @@ typedef enum {
     QSV_OK = 0,
     QSV_ERR_INVALID_ARG = 1,
     QSV_ERR_UNSUPPORTED = 2,
-    QSV_ERR_ZERO_NORM = 3,
+    QSV_ERR_ZERO_NORM = 3,   /* reserved, never returned: calls are asynchronous, so a zero vector
+                                is reported in band (norm 0 and an all-zero state from
+                                qsv_amp_encode, -1 for every shot from QSV_M_SAMPLE) */
     QSV_ERR_WORKSPACE = 4,
     QSV_ERR_HIP = 5
 } qsv_status;
@@ -82,7 +88,7 @@ size_t qsv_grad_workspace_bytes(int n_qubits, int batch, const qsv_circuit* c);
 /* Create a context bound to (n_qubits, batch), a device ordinal, a HIP stream (hipStream_t cast
  * to void*, NULL = default stream), the caller's state buffer complex64 [batch][2^n] and the
  * caller's workspace (256-byte aligned device memory of at least qsv_workspace_bytes bytes).
- * batch must be in 1..65535.  Nothing is launched. */
+ * batch must be in 1..2^24 with batch * 2^n_qubits <= 2^36.  Nothing is launched. */
 qsv_status qsv_create(qsv_ctx** out, int n_qubits, int batch, int device, void* hip_stream,
                       void* state_dev, void* ws_dev, size_t ws_bytes);
 void qsv_destroy(qsv_ctx* ctx);
@@ -233,7 +239,8 @@ int64_t qsv_plan_describe(const qsv_circuit* c, int n_qubits, int batch, int inv
  * bits plus a window starting at bit window_start, as the planner would choose), moves the
  * register run through LDS `transposes` times and stores the tile back unchanged.  It gives the
  * streaming ceiling of the pass kernel's access pattern, with no gate arithmetic.  The state is
- * left as it was. */
+ * left as it was.  Unlike every other call it synchronises the stream once (after uploading its
+ * operation list) and must not be called while the stream is being captured. */
 qsv_status qsv_probe_pass(qsv_ctx* ctx, int low_bits, int window_start, int transposes);
 
 /* Testing/tuning knobs: tile_log2 in 10..13 (0 = default) forces the tile size of the fused pass

@@ -4,6 +4,7 @@
 
 #include <cstdio>
 #include <cstring>
+#include <deque>
 #include <string>
 #include <vector>
 
@@ -22,6 +23,8 @@ constexpr size_t kOpsRegion = 4u << 20;  // persistent: uploaded pass programs
 // 256 MiB state 3 % slower.
 constexpr uint64_t kNtStoreBytes = 384ull << 20;
 constexpr int kChunkBits = 12;
+constexpr int kMaxBatch = 1 << 24;
+constexpr int64_t kMaxAmplitudes = (int64_t)1 << 36;
 
 std::string g_create_error;
 
@@ -33,10 +36,14 @@ int ceil_log2_i64(int64_t v) {
     return b;
 }
 
+// A plan the context has built.  Entries are never destroyed before qsv_destroy and never move (a
+// std::deque only grows at its end), so pointers to them, and the host arrays uploads read from,
+// stay valid for the life of the context: also for a HIP graph that recorded such an upload.
 struct CachedPlan {
     qsv_circuit c;
-    int inverse, tile, grad, low;
+    int inverse, tile, grad, low;   // tile: the resolved tile size (the default depends on the rows)
     Plan plan;
+    bool resident = false;          // its arrays are in the ops region right now
     size_t dev_off;     // byte offset of the ops inside the ops region
     size_t order_off;   // int32[n_mats]: execution order -> (layer*n + qubit)
     size_t execof_off;  // int32[n_mats]: (layer*n + qubit) -> execution order
@@ -68,7 +75,7 @@ struct qsv_ctx {
     hipStream_t side = nullptr;          // second stream for that (default priority, non-blocking)
     hipEvent_t ev_fork = nullptr, ev_join = nullptr;
     bool forked = false;                 // a caller further up already runs two halves on the two streams
-    std::vector<CachedPlan> cache;
+    std::deque<CachedPlan> cache;
     size_t ops_used = 0;
 };
 
@@ -92,24 +99,24 @@ qsv_status hip_fail(qsv_ctx* ctx, hipError_t e, const char* where) {
 // Per-call scratch carved from the workspace after the persistent ops region.  Work on one
 // stream is ordered, so consecutive calls may reuse the same bytes.
 struct Arena {
-    qsv_ctx* ctx;
-    size_t off;
-    explicit Arena(qsv_ctx* c) : ctx(c), off(kOpsRegion) {}
+    char* base;
+    size_t off, limit;
+    explicit Arena(qsv_ctx* c) : base(c->ws), off(kOpsRegion), limit(c->ws_bytes) {}
     void* take(size_t bytes) {
         const size_t a = align_up(bytes ? bytes : 1);
-        if (off + a > ctx->ws_bytes) { need = off + a; return nullptr; }
-        void* p = ctx->ws + off;
+        if (off + a > limit) { need = off + a; return nullptr; }
+        void* p = base + off;
         off += a;
         return p;
     }
-    size_t remaining() const { return ctx->ws_bytes > off ? ctx->ws_bytes - off : 0; }
+    size_t remaining() const { return limit > off ? limit - off : 0; }
     size_t need = 0;
 };
 
 qsv_status ws_fail(qsv_ctx* ctx, const Arena& ar, const char* what) {
-    char buf[160];
+    char buf[200];
     snprintf(buf, sizeof buf, "workspace too small for %s: needs at least %zu bytes, has %zu", what,
-             ar.need, ctx->ws_bytes);
+             ar.need, ar.limit);
     return fail(ctx, QSV_ERR_WORKSPACE, buf);
 }
 
@@ -134,36 +141,53 @@ bool same_circuit(const qsv_circuit& a, const qsv_circuit& b) {
     return true;
 }
 
-// Finds or builds the plan and makes sure its ops are resident in the ops region.
+// Finds or builds the plan and makes sure its arrays are resident in the ops region.  Uploads are
+// asynchronous copies on the context's stream from host arrays that live as long as the context.
+// When the region is full, every plan in it is dropped from the region (not from the host) and the
+// region is filled again from its start: the copies that overwrite it are ordered, on the stream,
+// behind every kernel that read the old contents, so nothing waits on the host.
 qsv_status get_plan(qsv_ctx* ctx, const qsv_circuit& c, int64_t rows, int inverse, int grad,
                     const CachedPlan** out) {
-    const int tile = ctx->opt_tile;
-    for (const CachedPlan& cp : ctx->cache)
+    int tile = ctx->opt_tile > 0 ? ctx->opt_tile : default_tile(ctx->n, rows);
+    tile = std::max(kMinTile, std::min(kMaxTile, tile));
+    CachedPlan* hit = nullptr;
+    for (CachedPlan& cp : ctx->cache)
         if (cp.inverse == inverse && cp.tile == tile && cp.grad == grad && cp.low == ctx->opt_low &&
             same_circuit(cp.c, c)) {
-            *out = &cp;
-            return QSV_OK;
+            hit = &cp;
+            break;
         }
-    CachedPlan cp;
-    cp.c = c;
-    cp.inverse = inverse;
-    cp.tile = tile;
-    cp.grad = grad;
-    cp.low = ctx->opt_low;
-    // rows only matter through the tile default (small states pack several rows per tile)
-    cp.plan = build_plan(c, ctx->n, rows, inverse != 0, tile, grad != 0, ctx->opt_low);
-    if (!cp.plan.complete) return fail(ctx, QSV_ERR_UNSUPPORTED, "internal: pass planner failed");
+    if (hit && hit->resident) {
+        *out = hit;
+        return QSV_OK;
+    }
+    if (!hit) {
+        CachedPlan cp;
+        cp.c = c;
+        cp.inverse = inverse;
+        cp.tile = tile;
+        cp.grad = grad;
+        cp.low = ctx->opt_low;
+        cp.plan = build_plan(c, ctx->n, rows, inverse != 0, tile, grad != 0, ctx->opt_low);
+        if (!cp.plan.complete) return fail(ctx, QSV_ERR_UNSUPPORTED, "internal: pass planner failed");
+        const size_t nm = cp.plan.mat_order.size();
+        cp.exec_of.assign(nm, 0);
+        for (size_t k = 0; k < nm; ++k) cp.exec_of[cp.plan.mat_order[k]] = (int32_t)k;
+        ctx->cache.push_back(std::move(cp));
+        hit = &ctx->cache.back();
+    }
+    CachedPlan& cp = *hit;
     const size_t nm = cp.plan.mat_order.size();
-    cp.exec_of.assign(nm, 0);
-    for (size_t k = 0; k < nm; ++k) cp.exec_of[cp.plan.mat_order[k]] = (int32_t)k;
     const size_t ops_bytes = align_up(cp.plan.ops.size() * sizeof(Op) + sizeof(Op));
     const size_t tab_bytes = align_up(nm * sizeof(int32_t) + 4);
     const size_t bytes = ops_bytes + 2 * tab_bytes;
     if (bytes > kOpsRegion) return fail(ctx, QSV_ERR_UNSUPPORTED, "circuit too long for the plan buffer");
     if (ctx->ops_used + bytes > kOpsRegion) {
-        // recycle the region; wait first so no pending upload still reads a cached plan's memory
-        QSV_HIP(ctx, hipStreamSynchronize(ctx->stream), "recycle plan buffer");
-        ctx->cache.clear();
+        // While a call has work on the second stream, kernels there may still read the region, and
+        // this upload would not be ordered behind them.
+        if (ctx->forked)
+            return fail(ctx, QSV_ERR_UNSUPPORTED, "the plans of this call do not fit the plan buffer together");
+        for (CachedPlan& other : ctx->cache) other.resident = false;
         ctx->ops_used = 0;
     }
     cp.dev_off = ctx->ops_used;
@@ -182,8 +206,8 @@ qsv_status get_plan(qsv_ctx* ctx, const qsv_circuit& c, int64_t rows, int invers
                 "upload matrix order");
     }
     ctx->ops_used += bytes;
-    ctx->cache.push_back(std::move(cp));
-    *out = &ctx->cache.back();
+    cp.resident = true;
+    *out = &cp;
     return QSV_OK;
 }
 
@@ -321,6 +345,7 @@ qsv_status run_circuit(qsv_ctx* ctx, const qsv_circuit& c, const Prepared& pr, f
         return z_after();
     }
     const CachedPlan* cp = pr.cp;
+    if (!cp->resident) return fail(ctx, QSV_ERR_UNSUPPORTED, "internal: the plan was dropped from the plan buffer before use");
     const Plan& pl = cp->plan;
     const int ext = n + ceil_log2_i64(rows);
     const uint64_t n_tiles = ext > pl.tile ? (1ull << (ext - pl.tile)) : 1ull;
@@ -450,7 +475,10 @@ qsv_status qsv_create(qsv_ctx** out, int n_qubits, int batch, int device, void* 
     if (!out) { g_create_error = "out is NULL"; return QSV_ERR_INVALID_ARG; }
     *out = nullptr;
     if (n_qubits < 1 || n_qubits > 30) { g_create_error = "n_qubits must be in 1..30"; return QSV_ERR_INVALID_ARG; }
-    if (batch < 1 || batch > 65535) { g_create_error = "batch must be in 1..65535"; return QSV_ERR_INVALID_ARG; }
+    if (batch < 1 || batch > kMaxBatch || ((int64_t)batch << n_qubits) > kMaxAmplitudes) {
+        g_create_error = "batch must be in 1..2^24 with batch * 2^n_qubits <= 2^36";
+        return QSV_ERR_INVALID_ARG;
+    }
     if (device < 0) { g_create_error = "device must be >= 0"; return QSV_ERR_INVALID_ARG; }
     if (!state_dev || !ws_dev) { g_create_error = "state_dev and ws_dev must not be NULL"; return QSV_ERR_INVALID_ARG; }
     if (((uintptr_t)state_dev & 15) || ((uintptr_t)ws_dev & 255)) {
@@ -505,7 +533,7 @@ qsv_status qsv_set_option(qsv_ctx* ctx, const char* name, int64_t value) {
     if (!ctx || !name) return QSV_ERR_INVALID_ARG;
     if (!strcmp(name, "tile_log2")) {
         if (value != 0 && (value < kMinTile || value > kMaxTile))
-            return fail(ctx, QSV_ERR_INVALID_ARG, "tile_log2 must be 0 or in 10..13");
+            return fail(ctx, QSV_ERR_INVALID_ARG, "tile_log2 must be 0 or in 10..14");
         ctx->opt_tile = (int)value;
         return QSV_OK;
     }
@@ -538,7 +566,7 @@ qsv_status qsv_set_option(qsv_ctx* ctx, const char* name, int64_t value) {
     }
     if (!strcmp(name, "probe_layout")) {
         if (value < -1 || value > kMaxTile - kRegBits)
-            return fail(ctx, QSV_ERR_INVALID_ARG, "probe_layout must be -1 or in 0..9");
+            return fail(ctx, QSV_ERR_INVALID_ARG, "probe_layout must be -1 or in 0..10");
         ctx->opt_probe_layout = (int)value;
         return QSV_OK;
     }
@@ -597,8 +625,8 @@ qsv_status qsv_apply_layers(qsv_ctx* ctx, const qsv_circuit* c, const float* par
     return run_circuit(ctx, *c, pr, ctx->state, ctx->batch, inverse, nullptr, plain_rows(ctx->n));
 }
 
-qsv_status qsv_measure(qsv_ctx* ctx, const qsv_measure_req* req) {
-    if (!ctx) return QSV_ERR_INVALID_ARG;
+// Every measurement kind; ar is where the kernels' partial results go.
+static qsv_status measure_impl(qsv_ctx* ctx, const qsv_measure_req* req, Arena& ar) {
     if (!req) return fail(ctx, QSV_ERR_INVALID_ARG, "req is NULL");
     if (!req->out_dev) return fail(ctx, QSV_ERR_INVALID_ARG, "out_dev is NULL");
     if (req->reserved != 0) return fail(ctx, QSV_ERR_INVALID_ARG, "reserved must be 0");
@@ -606,7 +634,6 @@ qsv_status qsv_measure(qsv_ctx* ctx, const qsv_measure_req* req) {
     const int64_t B = ctx->batch;
     const uint64_t full = (n >= 64) ? ~0ull : ((1ull << n) - 1);
     qsv_status st;
-    Arena ar(ctx);
     switch (req->kind) {
         case QSV_M_PROBS: {
             if ((st = bind_device(ctx)) != QSV_OK) return st;
@@ -680,6 +707,12 @@ qsv_status qsv_measure(qsv_ctx* ctx, const qsv_measure_req* req) {
         default:
             return fail(ctx, QSV_ERR_INVALID_ARG, "unknown measurement kind");
     }
+}
+
+qsv_status qsv_measure(qsv_ctx* ctx, const qsv_measure_req* req) {
+    if (!ctx) return QSV_ERR_INVALID_ARG;
+    Arena ar(ctx);
+    return measure_impl(ctx, req, ar);
 }
 
 qsv_status qsv_pauli_expect(qsv_ctx* ctx, uint64_t xmask, uint64_t ymask, uint64_t zmask, float* out_dev) {
@@ -1198,20 +1231,6 @@ qsv_status qsv_probe_pass(qsv_ctx* ctx, int low_bits, int window_start, int tran
     const uint64_t n_tiles = ext > tile ? (1ull << (ext - tile)) : 1ull;
     QSV_HIP(ctx, launch_pass(tile, ctx->opt_planes, a, n_tiles, ctx->stream), "probe pass");
     return QSV_OK;
-}
-
-int64_t qsv_plan_describe(const qsv_circuit* c, int n_qubits, int batch, int inverse, int tile_log2,
-                          char* buf, int64_t buf_bytes) {
-    if (!check_circuit(c, n_qubits, nullptr) || batch < 1) return -1;
-    if (tile_log2 != 0 && (tile_log2 < kMinTile || tile_log2 > kMaxTile)) return -1;
-    const Plan p = build_plan(*c, n_qubits, batch, inverse != 0, tile_log2, false);
-    const std::string s = describe_plan(p);
-    if (buf && buf_bytes > 0) {
-        const size_t ncopy = s.size() < (size_t)buf_bytes - 1 ? s.size() : (size_t)buf_bytes - 1;
-        memcpy(buf, s.data(), ncopy);
-        buf[ncopy] = 0;
-    }
-    return (int64_t)s.size();
 }
 
 }  // extern "C"

@@ -25,6 +25,12 @@ __device__ __forceinline__ double wave_sum(double v) {
     return v;
 }
 
+// Reduction kernels run one block per (chunk of a row, row): the chunk in grid.x, the row spread over
+// grid.y and grid.z (a grid dimension other than x holds at most 65535 blocks).
+__device__ __forceinline__ unsigned long long grid_row() {
+    return (unsigned long long)blockIdx.z * gridDim.y + blockIdx.y;
+}
+
 // Sum over a 256-thread block; result valid in thread 0.  sm: 4 doubles.
 __device__ __forceinline__ double block_sum256(double v, double* sm) {
     v = wave_sum(v);
@@ -188,7 +194,8 @@ void k_pass(const PassArgs a) {
     // interpreter's generator.  The segment must start at LDS byte 0 (no static LDS here).
     extern __shared__ float lds[];
     constexpr unsigned PLANE = 1u << T;
-    static_assert(PLANE * 4u < 65536u && PLANE / 64u < 256u, "plane offsets must fit the LDS offset fields");
+    static_assert(PLANES == 1 || (PLANE * 4u < 65536u && PLANE / 64u < 256u),
+                  "with two planes the second plane is reached through the LDS offset fields");
     const unsigned lds_byte0 = (unsigned)(uintptr_t)(__attribute__((address_space(3))) float*)lds;
     const unsigned thr = threadIdx.x;
     const u64 tb = a.rev ? (u64)(gridDim.x - 1u - blockIdx.x) : (u64)blockIdx.x;
@@ -645,10 +652,11 @@ __global__ __launch_bounds__(256) void k_build_shifted(CircDev c, const float* p
 // ------------------------------------------------------------------------------------------
 // Amplitude encoding.
 // inv_norm != NULL (only with nblk = 1): the block is the whole sample and finishes the norm itself.
-__global__ __launch_bounds__(256) void k_sumsq(const float* x, u64 dim, double* partial, int nblk,
+__global__ __launch_bounds__(256) void k_sumsq(const float* x, u64 rows, u64 dim, double* partial, int nblk,
                                                double* inv_norm, float* norm_out) {
     __shared__ double sm[4];
-    const u64 b = blockIdx.y;
+    const u64 b = grid_row();
+    if (b >= rows) return;
     const float* xb = x + b * dim;
     double acc = 0.0;
     if ((dim & 3) == 0 && ((uintptr_t)x & 15) == 0) {
@@ -734,10 +742,11 @@ __global__ __launch_bounds__(256) void k_probs(const float2* state, u64 total, f
 // Block (row, blk) reduces 4096 consecutive amplitudes to 13 doubles: total T and the signed sums
 // Z_0..Z_11 for the 12 index bits inside the chunk.  Chunk-local index = i*256 + thread
 // (bits 0-5 lane, 6-7 wavefront, 8-11 register).
-__global__ __launch_bounds__(256) void k_expz_block(const float2* state, int n, int nblk,
+__global__ __launch_bounds__(256) void k_expz_block(const float2* state, u64 rows, int n, int nblk,
                                                     double* partial) {
     __shared__ double sm[4][11];
-    const u64 row = blockIdx.y;
+    const u64 row = grid_row();
+    if (row >= rows) return;
     const u64 dimn = 1ull << n;
     const u64 base = (u64)blockIdx.x * CHUNK;
     const float2* a = state + row * dimn;
@@ -912,10 +921,11 @@ __global__ __launch_bounds__(256) void k_project(float2* state, u64 total, int n
 
 // Pauli string: T = sum_k conj(a[k ^ f]) (-1)^popcount(k & s) a[k], f = X and Y bits, s = Y and Z
 // bits; <P> = Re(i^nY T).  One block per 4096 amplitudes and row; partial: [row][blk][2].
-__global__ __launch_bounds__(256) void k_pauli_block(const float2* state, int n, u64 f, u64 s, int nblk,
+__global__ __launch_bounds__(256) void k_pauli_block(const float2* state, u64 rows, int n, u64 f, u64 s, int nblk,
                                                      double* partial) {
     __shared__ double sm[4];
-    const u64 row = blockIdx.y, N = 1ull << n;
+    const u64 row = grid_row(), N = 1ull << n;
+    if (row >= rows) return;
     const float2* a = state + (row << n);
     float tr = 0.f, ti = 0.f;
 #pragma unroll
@@ -947,10 +957,11 @@ __global__ __launch_bounds__(256) void k_pauli_finish(const double* partial, int
     if (threadIdx.x == 0) out[row] = (float)((ny & 3) == 0 ? t0 : (ny & 3) == 1 ? -t1 : (ny & 3) == 2 ? -t0 : t1);
 }
 
-__global__ __launch_bounds__(256) void k_fidelity_block(const float2* state, int n, const float* x,
+__global__ __launch_bounds__(256) void k_fidelity_block(const float2* state, u64 rows, int n, const float* x,
                                                         u64 dim, int nblk, RowMap rm, double* partial) {
     __shared__ double sm[4];
-    const u64 row = blockIdx.y;
+    const u64 row = grid_row();
+    if (row >= rows) return;
     const float2* a = state + (row << n);
     const float* xb = x + row_ctx(rm, row).sample * dim;
     double sxx = 0.0, sr = 0.0, si = 0.0;
@@ -1053,9 +1064,10 @@ __device__ __forceinline__ u64 wave_sum_u64(u64 v) {
     return v;
 }
 
-__global__ __launch_bounds__(256) void k_sample_blocksum(const float2* state, int n, int nblk, u64* bsum) {
+__global__ __launch_bounds__(256) void k_sample_blocksum(const float2* state, u64 rows, int n, int nblk, u64* bsum) {
     __shared__ u64 sm[4];
-    const u64 row = blockIdx.y;
+    const u64 row = grid_row();
+    if (row >= rows) return;
     const u64 dimn = 1ull << n;
     const float2* a = state + (row << n);
     u64 acc = 0;
@@ -1209,9 +1221,10 @@ __global__ __launch_bounds__(256) void k_adj_init(const float2* A, int n, AdjObs
 }
 
 // P0(mask) of every row: block partials, then one thread per row; f[sample][2P] = 1 - P0.
-__global__ __launch_bounds__(256) void k_p0_block(const float2* A, int n, u64 mask, int nblk, double* partial) {
+__global__ __launch_bounds__(256) void k_p0_block(const float2* A, u64 rows, int n, u64 mask, int nblk, double* partial) {
     __shared__ double sm[4];
-    const u64 r = blockIdx.y, N = 1ull << n;
+    const u64 r = grid_row(), N = 1ull << n;
+    if (r >= rows) return;
     const float2* a = A + (r << n);
     float acc = 0.f;
 #pragma unroll
@@ -1641,22 +1654,30 @@ __global__ __launch_bounds__(256) void k_adam(float* p, const float* g, float* m
 
 inline unsigned blocks_for(u64 items, unsigned per) { return (unsigned)((items + per - 1) / per); }
 
+// grid of the reduction kernels: chunks in x, rows over y and z (see grid_row)
+inline dim3 rows_grid(unsigned nblk, u64 rows) {
+    const unsigned gy = (unsigned)(rows < 32768 ? rows : 32768);
+    return dim3(nblk, gy, (unsigned)((rows + gy - 1) / gy));
+}
+
 }  // namespace
 
 // ============================================================================================
 // Launchers.
-template <int T>
+template <int T, int PLANES>
 static hipError_t set_attr_for() {
-    const int bytes = 2 * (1 << T) * 4;
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(k_pass<T, false, 2>),
+    const int bytes = PLANES * (1 << T) * 4;
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(k_pass<T, false, PLANES>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
     if (e != hipSuccess) return e;
-    return hipFuncSetAttribute(reinterpret_cast<const void*>(k_pass<T, true, 2>),
+    return hipFuncSetAttribute(reinterpret_cast<const void*>(k_pass<T, true, PLANES>),
                                hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
 }
 
+// the two variants that use 64 KiB of dynamic LDS
 hipError_t set_pass_attributes() {
-    return set_attr_for<13>();
+    const hipError_t e = set_attr_for<13, 2>();
+    return e != hipSuccess ? e : set_attr_for<14, 1>();
 }
 
 template <int T, int PLANES>
@@ -1669,6 +1690,7 @@ static void launch_pass_t(const PassArgs& a, dim3 grid, hipStream_t st) {
 hipError_t launch_pass(int tile, int planes, const PassArgs& a, uint64_t n_tiles, hipStream_t st) {
     if (n_tiles == 0 || n_tiles > 0x7fffffffull) return hipErrorInvalidValue;
     if (planes != 1 && planes != 2) return hipErrorInvalidValue;
+    if (tile == 14) planes = 1;   // the largest tile exists with one plane only
     const dim3 grid((unsigned)n_tiles);
     switch (tile * 2 + planes - 1) {
         case 20: launch_pass_t<10, 1>(a, grid, st); break;
@@ -1679,6 +1701,7 @@ hipError_t launch_pass(int tile, int planes, const PassArgs& a, uint64_t n_tiles
         case 25: launch_pass_t<12, 2>(a, grid, st); break;
         case 26: launch_pass_t<13, 1>(a, grid, st); break;
         case 27: launch_pass_t<13, 2>(a, grid, st); break;
+        case 28: launch_pass_t<14, 1>(a, grid, st); break;   // two planes of 2^14 floats do not fit the offset fields
         default: return hipErrorInvalidValue;
     }
     return hipGetLastError();
@@ -1744,7 +1767,7 @@ hipError_t launch_build_shifted(const CircDev& c, const float* params, const flo
 hipError_t launch_norms(const float* x, int64_t samples, int64_t dim, double* partial, int nblk,
                         double* inv_norm, float* norm_out, hipStream_t st) {
     const bool one = nblk == 1;
-    hipLaunchKernelGGL(k_sumsq, dim3(nblk, (unsigned)samples), dim3(256), 0, st, x, (u64)dim, partial, nblk,
+    hipLaunchKernelGGL(k_sumsq, rows_grid(nblk, (u64)samples), dim3(256), 0, st, x, (u64)samples, (u64)dim, partial, nblk,
                        one ? inv_norm : (double*)nullptr, one ? norm_out : (float*)nullptr);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess || one) return e;
@@ -1771,7 +1794,7 @@ static inline int chunk_blocks(int bits) { return bits > CHUNK_BITS ? 1 << (bits
 
 hipError_t launch_expz_block(const float2* state, int64_t rows, int n, double* partial, hipStream_t st) {
     const int nblk = chunk_blocks(n);
-    hipLaunchKernelGGL(k_expz_block, dim3(nblk, (unsigned)rows), dim3(256), 0, st, state, n, nblk,
+    hipLaunchKernelGGL(k_expz_block, rows_grid(nblk, (u64)rows), dim3(256), 0, st, state, (u64)rows, n, nblk,
                        partial);
     return hipGetLastError();
 }
@@ -1838,7 +1861,7 @@ hipError_t launch_project(float2* state, int64_t rows, int n, uint64_t mask, con
 
 hipError_t launch_fidelity_block(const float2* state, int64_t rows, int n, const float* x, int64_t dim,
                                  double* partial, int nblk, const RowMap& rm, hipStream_t st) {
-    hipLaunchKernelGGL(k_fidelity_block, dim3(nblk, (unsigned)rows), dim3(256), 0, st, state, n, x,
+    hipLaunchKernelGGL(k_fidelity_block, rows_grid(nblk, (u64)rows), dim3(256), 0, st, state, (u64)rows, n, x,
                        (u64)dim, nblk, rm, partial);
     return hipGetLastError();
 }
@@ -1872,7 +1895,7 @@ hipError_t launch_shot_expz(const long long* samples, int64_t shots, int64_t row
 hipError_t launch_pauli(const float2* state, int64_t rows, int n, uint64_t xmask, uint64_t ymask,
                         uint64_t zmask, double* partial, float* out, hipStream_t st) {
     const int nblk = chunk_blocks(n);
-    hipLaunchKernelGGL(k_pauli_block, dim3(nblk, (unsigned)rows), dim3(256), 0, st, state, n,
+    hipLaunchKernelGGL(k_pauli_block, rows_grid(nblk, (u64)rows), dim3(256), 0, st, state, (u64)rows, n,
                        (u64)(xmask | ymask), (u64)(ymask | zmask), nblk, partial);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
@@ -1884,7 +1907,7 @@ hipError_t launch_pauli(const float2* state, int64_t rows, int n, uint64_t xmask
 hipError_t launch_sample(const float2* state, int64_t rows, int n, const double* uniforms, int64_t shots,
                          unsigned long long* cum, long long* out, hipStream_t st) {
     const int nblk = chunk_blocks(n);
-    hipLaunchKernelGGL(k_sample_blocksum, dim3(nblk, (unsigned)rows), dim3(256), 0, st, state, n, nblk,
+    hipLaunchKernelGGL(k_sample_blocksum, rows_grid(nblk, (u64)rows), dim3(256), 0, st, state, (u64)rows, n, nblk,
                        cum);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
@@ -1909,9 +1932,9 @@ hipError_t launch_adj_init(const float2* A, int n, int kind, int q, uint64_t mas
 
 hipError_t launch_trash_loss(const float2* A, int n, uint64_t mask, int64_t rows, int64_t sample0, int64_t P,
                              double* partial, double* f, hipStream_t st) {
-    if (rows < 1 || rows > 65535) return hipErrorInvalidValue;
+    if (rows < 1) return hipErrorInvalidValue;
     const int nblk = chunk_blocks(n);
-    hipLaunchKernelGGL(k_p0_block, dim3(nblk, (unsigned)rows), dim3(256), 0, st, A, n, (u64)mask, nblk, partial);
+    hipLaunchKernelGGL(k_p0_block, rows_grid(nblk, (u64)rows), dim3(256), 0, st, A, (u64)rows, n, (u64)mask, nblk, partial);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL(k_trash_loss, dim3(blocks_for((u64)rows, 256)), dim3(256), 0, st, partial, nblk,

@@ -17,7 +17,7 @@ namespace qsv {
 
 constexpr int kRegBits = 4;      // R: amplitudes per lane = 2^R
 constexpr int kMinTile = 10;     // 64 lanes x 16 amplitudes
-constexpr int kMaxTile = 13;     // two padded float planes of 2^13: 68 KiB of LDS, two workgroups per CU
+constexpr int kMaxTile = 14;     // 1024 lanes x 16 amplitudes; one XOR-swizzled LDS plane of 2^14 floats = 64 KiB
 constexpr int kLowBits = 4;      // c: 2^4 complex64 = one 128-byte line per contiguous run
 
 enum OpKind : uint8_t {

@@ -71,14 +71,16 @@ SMALL = [
     (7, 2, 3, (RY, RZ), LADDER, 0), (9, 5, 2, (RY, RZ), RING, 1), (10, 6, 3, (RY, RZ), RING, 1),
     (11, 3, 3, (RX, RY, RZ), RING, 0), (12, 2, 3, (RY, RZ), LADDER, 0), (13, 2, 2, (), RING, 0),
     (13, 3, 3, (RY, RZ), RING, 0), (14, 1, 3, (RZ, RX), NONE, 0),
-    (4, 65535, 1, (RY, RZ), RING, 0),      # largest batch the boundary accepts; ragged last tile
+    (4, 65535, 1, (RY, RZ), RING, 0),      # a batch that is no power of two; ragged last tile
+    (4, 70001, 1, (RY, RZ), RING, 0),      # more rows than one grid dimension holds
+    (15, 2, 2, (RX, RY, RZ), RING, 0), (16, 1, 3, (RY, RZ), LADDER, 0),
     (5, 2, 0, (RY,), RING, 0),             # no layers: the state must come back unchanged
 ]
 
 
 @pytest.mark.parametrize("n,B,L,rot,ent,reup", SMALL)
-@pytest.mark.parametrize("mode", ["default", "t10", "t11", "t12", "t13", "naive",
-                                  "t10p1", "t11p2", "t12p1", "t13p1", "t12p2"])
+@pytest.mark.parametrize("mode", ["default", "t10", "t11", "t12", "t13", "t14", "naive",
+                                  "t10p1", "t11p2", "t12p1", "t13p1", "t12p2", "t14p1"])
 def test_apply_layers_small(oracle, n, B, L, rot, ent, reup, mode):
     g = rng(31 * n + B + L)
     spec = wl.CircuitSpec(L, tuple(rot), ent, reup)
@@ -212,13 +214,13 @@ def _random_apply_cases(count, seed):
     rots = [(RX,), (RY,), (RZ,), (RY, RZ), (RZ, RX), (RX, RY, RZ), (RZ, RY, RX), ()]
     out = []
     for _ in range(count):
-        n = int(g.integers(1, 16))
+        n = int(g.integers(1, 18))
         B = int(g.integers(1, 9)) if n <= 12 else int(g.integers(1, 3))
         L = int(g.integers(1, 5))
         rot = rots[int(g.integers(0, len(rots)))]
         ent = int(g.integers(0, 3))
         reup = int(g.integers(0, 2))
-        tile = int(g.choice([0, 0, 10, 11, 12, 13]))
+        tile = int(g.choice([0, 0, 10, 11, 12, 13, 14]))
         planes = int(g.choice([0, 1, 2]))
         out.append((n, B, L, rot, ent, reup, tile, planes))
     return out
@@ -243,9 +245,12 @@ def test_apply_layers_random(oracle, n, B, L, rot, ent, reup, tile, planes):
     ctx.qsv_apply_layers(circ, pd, fd, 0)
     got = gu.state_np(ctx)
     assert np.abs(got - ref).max() <= amp_tol(n)
+    # relative to the state's own size (rows have norm 1; amplitudes are O(2^-n/2))
+    assert np.linalg.norm(got - ref, axis=1).max() <= 1e-5
     ctx.qsv_apply_layers(circ, pd, fd, 1)
     back, _ = oracle.amp_encode(x, n)
     assert np.abs(gu.state_np(ctx) - back).max() <= 2 * amp_tol(n)
+    assert np.linalg.norm(gu.state_np(ctx) - back, axis=1).max() <= 2e-5
     ctx.close()
 
 
@@ -254,10 +259,11 @@ def test_apply_layers_random(oracle, n, B, L, rot, ent, reup, tile, planes):
     (2, 3, 2, (RY, RZ), RING, 0, 1), (4, 5, 2, (RY, RZ), LADDER, 0, 0), (5, 3, 2, (RX, RY, RZ), RING, 0, 2),
     (6, 4, 2, (RY, RZ), RING, 1, 0), (10, 2, 2, (RY, RZ), LADDER, 0, 0), (12, 2, 1, (RY, RZ), RING, 1, 3),
     (13, 1, 2, (RY,), LADDER, 0, 0), (1, 4, 3, (RX, RZ), RING, 0, 0), (7, 3, 4, (RY, RZ), RING, 0, 6),
-    (8, 5, 3, (RX, RZ), LADDER, 1, 2), (11, 2, 3, (RY, RZ), LADDER, 0, 10)])
+    (8, 5, 3, (RX, RZ), LADDER, 1, 2), (11, 2, 3, (RY, RZ), LADDER, 0, 10), (15, 1, 1, (RY, RZ), RING, 0, 14)])
 @pytest.mark.parametrize("mode", ["default", "naive", "whole", "chunk5", "whole-chunk4", "naive-whole",
                                   "adjoint", "adjoint-naive", "adjoint-chunk2", "adjoint-whole", "adjoint-whole-chunk2",
-                                  "t10", "t11-whole", "t13", "t12p2", "adjoint-t10", "adjoint-t13"])
+                                  "t10", "t11-whole", "t13", "t12p2", "adjoint-t10", "adjoint-t13", "t14",
+                                  "adjoint-t14"])
 def test_param_shift_grad_small(oracle, n, B, L, rot, ent, reup, obs, mode):
     torch = gu.torch_cuda()
     g = rng(40 + n)

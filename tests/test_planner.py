@@ -61,7 +61,7 @@ def replay(text, n, rows, L, rot, ent, reupload, params, feats, inverse, st):
     n_gates = 0
     for hdr, ops in passes:
         t, c, w = hdr["t"], hdr["c"], hdr["w"]
-        assert 10 <= t <= 13 and 4 <= c <= t and w >= c
+        assert 10 <= t <= 14 and 4 <= c <= t and w >= c
         bit = lambda pos: pos if pos < c else pos - c + w
         if n > t:
             assert w + (t - c) <= n
@@ -165,6 +165,8 @@ CASES = [
     (13, 1, 3, (RY, RZ), RING, 0, 10), (13, 1, 2, (RX,), NONE, 0, 12),
     (12, 1, 2, (), RING, 0, 10), (12, 2, 2, (RY, RZ), RING, 1, 10),
     (14, 1, 4, (RX, RY, RZ), RING, 0, 12), (14, 1, 3, (RY, RZ), LADDER, 0, 11),
+    (15, 1, 3, (RX, RY, RZ), RING, 0, 14), (14, 1, 2, (RY, RZ), LADDER, 0, 14), (13, 2, 2, (RY, RZ), RING, 1, 14),
+    (16, 1, 3, (RY, RZ), RING, 0, 14),
 ]
 
 
@@ -218,7 +220,7 @@ def _random_cases(count, seed):
     rots = [(RX,), (RY,), (RZ,), (RY, RZ), (RZ, RX), (RX, RY, RZ), (RZ, RY, RX), ()]
     out = []
     for _ in range(count):
-        n = int(g.integers(4, 15))
+        n = int(g.integers(4, 17))
         rows = int(g.integers(1, 6)) if n <= 11 else 1
         L = int(g.integers(1, 5))
         rot = rots[int(g.integers(0, len(rots)))]
@@ -226,7 +228,7 @@ def _random_cases(count, seed):
         reup = int(g.integers(0, 2))
         if not rot and not reup and ent == NONE:
             ent = RING
-        tile = int(g.choice([0, 10, 11, 12, 13]))
+        tile = int(g.choice([0, 10, 11, 12, 13, 14]))
         out.append((n, rows, L, rot, ent, reup, tile, int(g.integers(0, 2))))
     return out
 
