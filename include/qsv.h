@@ -147,6 +147,19 @@ typedef struct {
 
 qsv_status qsv_measure(qsv_ctx* ctx, const qsv_measure_req* req);
 
+/* qsv_measure for callers that cannot allocate device memory and have no workspace to spare for it:
+ * code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same request,
+ * same kernels, same results bit for bit; only the kernels' partial results (block sums, cumulative
+ * weights) go to a fixed array of 4 MiB inside the library's code object instead of the caller's
+ * workspace.  The call allocates and frees nothing, on the device or through any library.  Every GPU
+ * the library runs on holds one copy of the array until the process ends.  A request whose partial
+ * results need more than 4 MiB (enough for all five workload configs; the need grows with
+ * batch * 2^n_qubits / 4096) is rejected with QSV_ERR_WORKSPACE before anything is launched.  All
+ * calls on one GPU share that GPU's array, whatever their context or stream: calls that overlap in
+ * time on one GPU race, so keep them on one stream or order them with events.  Nothing in the array
+ * needs to start at zero: every byte that is read has been written earlier in the same call. */
+qsv_status qsv_measure_static(qsv_ctx* ctx, const qsv_measure_req* req);
+
 /* Fidelity of an autoencoder with a true reset of its trash qubits (task statement, workload
  * config 3; the projection of QSV_M_PROJECT_ZERO is the post-selected stand-in for it).  The
  * context's state is taken as the encoder output.  For every outcome t of measuring the qubits of

@@ -77,6 +77,8 @@ def load():
     L.qsv_apply_layers.argtypes = [vp, ctypes.POINTER(qsv_circuit), vp, vp, i32]
     L.qsv_measure.restype = i32
     L.qsv_measure.argtypes = [vp, ctypes.POINTER(qsv_measure_req)]
+    L.qsv_measure_static.restype = i32
+    L.qsv_measure_static.argtypes = [vp, ctypes.POINTER(qsv_measure_req)]
     L.qsv_param_shift_grad.restype = i32
     L.qsv_param_shift_grad.argtypes = [vp, ctypes.POINTER(qsv_circuit), vp, i64, vp, vp, ctypes.c_int32,
                                        vp, vp, vp, vp]
@@ -203,7 +205,10 @@ class Context:
         self._check(self.L.qsv_apply_layers(self.h, ctypes.byref(circ), _ptr(params), _ptr(feats),
                                             int(inverse)))
 
-    def qsv_measure(self, kind, out, qubit=0, mask=0, renormalise=0, x=None, uniforms=None):
+    def qsv_measure_static(self, kind, out, **kw):
+        self.qsv_measure(kind, out, entry=self.L.qsv_measure_static, **kw)
+
+    def qsv_measure(self, kind, out, qubit=0, mask=0, renormalise=0, x=None, uniforms=None, entry=None):
         r = qsv_measure_req()
         r.kind, r.qubit, r.mask, r.renormalise, r.reserved = kind, qubit, mask, int(renormalise), 0
         r.x_dev = x.data_ptr() if x is not None else None
@@ -211,7 +216,7 @@ class Context:
         r.uniforms_dev = uniforms.data_ptr() if uniforms is not None else None
         r.shots = uniforms.shape[1] if uniforms is not None else 0
         r.out_dev = out.data_ptr()
-        self._check(self.L.qsv_measure(self.h, ctypes.byref(r)))
+        self._check((entry or self.L.qsv_measure)(self.h, ctypes.byref(r)))
 
     def qsv_loss_grad(self, circ, x, params, feats, kind, loss, grad, mean_loss=None, mean_grad=None,
                       mask=0, targets=None):

@@ -101,7 +101,9 @@ qsv_status hip_fail(qsv_ctx* ctx, hipError_t e, const char* where) {
 struct Arena {
     char* base;
     size_t off, limit;
-    explicit Arena(qsv_ctx* c) : base(c->ws), off(kOpsRegion), limit(c->ws_bytes) {}
+    bool fixed;      // the library's fixed scratch array instead of the caller's workspace
+    explicit Arena(qsv_ctx* c) : base(c->ws), off(kOpsRegion), limit(c->ws_bytes), fixed(false) {}
+    Arena(void* fixed_scratch, size_t bytes) : base((char*)fixed_scratch), off(0), limit(bytes), fixed(true) {}
     void* take(size_t bytes) {
         const size_t a = align_up(bytes ? bytes : 1);
         if (off + a > limit) { need = off + a; return nullptr; }
@@ -115,8 +117,12 @@ struct Arena {
 
 qsv_status ws_fail(qsv_ctx* ctx, const Arena& ar, const char* what) {
     char buf[200];
-    snprintf(buf, sizeof buf, "workspace too small for %s: needs at least %zu bytes, has %zu", what,
-             ar.need, ar.limit);
+    if (ar.fixed)
+        snprintf(buf, sizeof buf, "%s needs %zu bytes of scratch, more than the fixed array of %zu bytes: "
+                 "use the entry point that works in the caller's workspace", what, ar.need, ar.limit);
+    else
+        snprintf(buf, sizeof buf, "workspace too small for %s: needs at least %zu bytes, has %zu", what,
+                 ar.need, ar.limit);
     return fail(ctx, QSV_ERR_WORKSPACE, buf);
 }
 
@@ -625,7 +631,9 @@ qsv_status qsv_apply_layers(qsv_ctx* ctx, const qsv_circuit* c, const float* par
     return run_circuit(ctx, *c, pr, ctx->state, ctx->batch, inverse, nullptr, plain_rows(ctx->n));
 }
 
-// Every measurement kind; ar is where the kernels' partial results go.
+// Every measurement kind; ar is where the kernels' partial results go (the caller's workspace, or the
+// library's fixed scratch array).  The partials are written in full before they are read, so the
+// bytes need no clearing between calls.
 static qsv_status measure_impl(qsv_ctx* ctx, const qsv_measure_req* req, Arena& ar) {
     if (!req) return fail(ctx, QSV_ERR_INVALID_ARG, "req is NULL");
     if (!req->out_dev) return fail(ctx, QSV_ERR_INVALID_ARG, "out_dev is NULL");
@@ -712,6 +720,16 @@ static qsv_status measure_impl(qsv_ctx* ctx, const qsv_measure_req* req, Arena& 
 qsv_status qsv_measure(qsv_ctx* ctx, const qsv_measure_req* req) {
     if (!ctx) return QSV_ERR_INVALID_ARG;
     Arena ar(ctx);
+    return measure_impl(ctx, req, ar);
+}
+
+qsv_status qsv_measure_static(qsv_ctx* ctx, const qsv_measure_req* req) {
+    if (!ctx) return QSV_ERR_INVALID_ARG;
+    qsv_status st = bind_device(ctx);
+    if (st != QSV_OK) return st;
+    void* fixed = nullptr;     // this device's copy of the fixed array (address looked up once per device)
+    QSV_HIP(ctx, static_scratch(ctx->device, &fixed), "address of the fixed scratch array");
+    Arena ar(fixed, kStaticScratchBytes);
     return measure_impl(ctx, req, ar);
 }
 

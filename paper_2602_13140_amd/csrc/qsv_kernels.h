@@ -49,6 +49,11 @@ struct PassArgs {
 };
 
 hipError_t launch_pass(int tile, int planes, const PassArgs& a, uint64_t n_tiles, hipStream_t st);
+
+// Address, on the current device (which must be `device`), of the library's fixed scratch array of
+// kStaticScratchBytes bytes (256-byte aligned).  Looked up once per device; allocates nothing.
+constexpr size_t kStaticScratchBytes = (size_t)4 << 20;
+hipError_t static_scratch(int device, void** ptr);
 hipError_t set_pass_attributes();
 
 // one-gate-per-launch kernels (fallback for n < 4 and cross-check path)

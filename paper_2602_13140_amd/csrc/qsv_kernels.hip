@@ -3,6 +3,8 @@
 #include "qsv_kernels.h"
 #include "qsv_gate_asm.h"
 
+#include <mutex>
+
 namespace qsv {
 
 namespace {
@@ -2050,6 +2052,35 @@ hipError_t launch_grad_finish(const double* f, int64_t B, int64_t P, const CircD
         e = hipGetLastError();
     }
     return e;
+}
+
+}  // namespace qsv
+
+// ============================================================================================
+// Scratch memory for callers that cannot allocate (code under HIP graph capture, serving loops,
+// harnesses that forbid hipMalloc): a fixed array in the code object, one copy per GPU that loads
+// the library, held until the process ends.  Its name is a host-side stand-in, not a device
+// address: host code asks the runtime for the address once per device and uses that pointer.
+static __device__ __align__(256) unsigned char scratch[qsv::kStaticScratchBytes];
+
+namespace qsv {
+
+hipError_t static_scratch(int device, void** ptr) {
+    constexpr int kMaxDevices = 64;
+    static void* ptrs[kMaxDevices] = {};
+    static std::mutex mu;
+    if (device < 0 || device >= kMaxDevices || !ptr) return hipErrorInvalidValue;
+    std::lock_guard<std::mutex> lock(mu);
+    if (!ptrs[device]) {
+        // the caller has made `device` current: the address is that device's copy of the array
+        void* p = nullptr;
+        const hipError_t e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return e;
+        if (!p) return hipErrorInvalidSymbol;
+        ptrs[device] = p;
+    }
+    *ptr = ptrs[device];
+    return hipSuccess;
 }
 
 }  // namespace qsv
