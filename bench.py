@@ -36,6 +36,9 @@ def parse_args():
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--configs", default="4,3,2,1,0", help="which configs to time (4 is the headline)")
     ap.add_argument("--tile", type=int, default=0, help="force the pass kernel's tile_log2 (0 = default)")
+    ap.add_argument("--defer", type=int, default=-1,
+                    help="qsv_apply_layers defers CNOTs whose target lies outside a pass's tile (1), keeps every CNOT in "
+                         "registers (0), or decides itself (-1, the default: it defers when it can)")
     ap.add_argument("--low", type=int, default=0, help="force the planner's minimum number of low index bits per tile")
     ap.add_argument("--planes", type=int, default=0, help="force the pass kernel's LDS planes (1 or 2; 0 = default)")
     ap.add_argument("--nt", type=int, default=-1, help="force nontemporal tile stores (1) or ordinary ones (0)")
@@ -53,8 +56,8 @@ def parse_args():
     return ap.parse_args()
 
 
-def n_passes(qb, circ, n, batch, inverse, tile):
-    text = qb.qsv_plan_describe(circ, n, batch, inverse, tile)
+def n_passes(qb, circ, n, batch, inverse, tile, defer=False):
+    text = qb.qsv_plan_describe(circ, n, batch, inverse, tile | (0x100 if defer else 0))
     return sum(1 for ln in text.split("\n") if ln.startswith("P "))
 
 
@@ -93,6 +96,8 @@ def bench_c4(torch, qb, wl, args):
     ctx = qb.Context(n, 1)
     if args.tile:
         ctx.qsv_set_option("tile_log2", args.tile)
+    if args.defer >= 0:
+        ctx.qsv_set_option("defer_cnots", args.defer)
     if args.low:
         ctx.qsv_set_option("low_bits", args.low)
     if args.planes:
@@ -120,7 +125,7 @@ def bench_c4(torch, qb, wl, args):
         ctx.qsv_measure(qb.QSV_M_SAMPLE, shots, uniforms=ud)
 
     ms, tm = run_steps(torch, step, args.steps, args.warmup)
-    passes = n_passes(qb, circ, n, 1, 0, args.tile)
+    passes = n_passes(qb, circ, n, 1, 0, args.tile, args.defer != 0)
     apply_ms = tm.total_ms("apply") / args.steps
     updates = wl.nominal_updates(w.circuit, n, 1)
     state_bytes = 8 * (1 << n)
@@ -151,6 +156,8 @@ def bench_c3(torch, qb, wl, args):
     ctx = qb.Context(n, B)
     if args.tile:
         ctx.qsv_set_option("tile_log2", args.tile)
+    if args.defer >= 0:
+        ctx.qsv_set_option("defer_cnots", args.defer)
     if args.low:
         ctx.qsv_set_option("low_bits", args.low)
     if args.planes:
@@ -185,7 +192,7 @@ def bench_c3(torch, qb, wl, args):
         ctx.qsv_measure(qb.QSV_M_FIDELITY, fid, x=xd)
 
     ms, tm = run_steps(torch, step, args.steps, args.warmup)
-    passes = n_passes(qb, circ, n, B, 0, args.tile) + n_passes(qb, circ, n, B, 1, args.tile)
+    passes = n_passes(qb, circ, n, B, 0, args.tile, args.defer != 0) + n_passes(qb, circ, n, B, 1, args.tile, args.defer != 0)
     apply_ms = tm.total_ms("apply") / args.steps
     updates = 2 * wl.nominal_updates(w.circuit, n, B)
     state_bytes = 8 * B * (1 << n)
@@ -224,6 +231,8 @@ def bench_c2(torch, qb, wl, args):
     ctx = qb.Context(n, B, ws_bytes=qb.qsv_grad_workspace_bytes(n, B, circ))
     if args.tile:
         ctx.qsv_set_option("tile_log2", args.tile)
+    if args.defer >= 0:
+        ctx.qsv_set_option("defer_cnots", args.defer)
     if args.low:
         ctx.qsv_set_option("low_bits", args.low)
     if args.planes:
@@ -293,6 +302,8 @@ def bench_c1(torch, qb, wl, args):
     ctx = qb.Context(n, B)
     if args.tile:
         ctx.qsv_set_option("tile_log2", args.tile)
+    if args.defer >= 0:
+        ctx.qsv_set_option("defer_cnots", args.defer)
     if args.planes:
         ctx.qsv_set_option("lds_planes", args.planes)
     circ = qb.circuit_from_spec(w.circuit)
@@ -383,6 +394,8 @@ def probe(torch, qb, args):
     ctx = qb.Context(n, 1)
     if args.tile:
         ctx.qsv_set_option("tile_log2", args.tile)
+    if args.defer >= 0:
+        ctx.qsv_set_option("defer_cnots", args.defer)
     if args.nt >= 0:
         ctx.qsv_set_option("nt_store", args.nt)
     if args.rev >= 0:

@@ -256,8 +256,13 @@ int64_t qsv_plan_describe(const qsv_circuit* c, int n_qubits, int batch, int inv
  * operation list) and must not be called while the stream is being captured. */
 qsv_status qsv_probe_pass(qsv_ctx* ctx, int low_bits, int window_start, int transposes);
 
-/* Testing/tuning knobs: tile_log2 in 10..13 (0 = default) forces the tile size of the fused pass
- * kernel; low_bits in 4..10 (0 = default) forces the planner's minimum number of low index bits
+/* Testing/tuning knobs: tile_log2 in 10..14 (0 = default) forces the tile size of the fused pass
+ * kernel (14 exists with one LDS plane only); defer_cnots = 1 / 0 lets qsv_apply_layers carry the
+ * CNOTs whose target qubit lies outside a pass's tile by the index the pass writes each amplitude to
+ * (fewer passes over the state; such passes write a second buffer taken from the workspace), or keeps
+ * every CNOT a register operation (-1, the default, defers whenever the circuit has a CNOT ring, more
+ * qubits than the tile has index bits, at most 28 of them, and the workspace has room for a copy of
+ * the state; the result is the same up to rounding order); low_bits in 4..10 (0 = default) forces the planner's minimum number of low index bits
  * per tile; lds_planes = 1 (default) moves real and imaginary parts through one LDS plane one
  * after the other, 2 through two planes at once; naive = 1 routes qsv_apply_layers through the
  * one-gate-per-launch kernels; grad_layered = 0 makes qsv_param_shift_grad run every shifted

@@ -9,11 +9,13 @@ merge point; one asm block with tied operands and its own scalar dispatch does n
 lets the next operation word and the next matrix be fetched while the current gate computes.
 
 The block executes consecutive operations (2x2 unitary on a register bit, CNOT with the control
-in a register bit, CNOT with the control elsewhere in the index, the three forms of CZ sign flips,
+in a register bit, CNOT with the control elsewhere in the index or given by the parity of several
+index bits, the three forms of CZ sign flips,
 and the transpose through LDS that moves the register run) and returns at the first operation of any other kind, leaving the
 operation pointer on it and no scalar load or LDS access in flight.
 
-LDS layout: two planes of 2^T floats (real, imaginary).  Element tau of a plane sits at index
+LDS layout: one plane of 2^T floats through which the real parts go first and then the imaginary
+parts (the default), or two planes for both at once.  Element tau of a plane sits at index
 tau ^ ((tau >> 4) & 31): the XOR spreads every layout's 32 consecutive lanes over the 32 banks,
 costs no space, and, XOR being linear, the address of register element k is (lane's part) ^ off(k)
 with off(k) the XOR of the offsets of k's set bits.  A layout is therefore described by four
@@ -45,7 +47,7 @@ import re
 
 R = 4
 NR = 1 << R
-OP_XPOSE, OP_U, OP_CX_REG, OP_CX_DYN, OP_CZ_REG, OP_CZ_MIX, OP_CZ_LANE, OP_CX_CHAIN = 2, 3, 4, 5, 6, 7, 8, 9
+OP_XPOSE, OP_U, OP_CX_REG, OP_CX_DYN, OP_CZ_REG, OP_CZ_MIX, OP_CZ_LANE, OP_CX_CHAIN, OP_CX_PAR, OP_CX_LANE = 2, 3, 4, 5, 6, 7, 8, 9, 10, 12
 # the chains of CNOTs between neighbouring register bits, numbered as in the planner:
 # (direction, control of the first, count); direction 0: controls go up, 1: down
 CX_CHAINS = [(0, 0, 3), (1, 2, 3), (0, 0, 2), (0, 1, 2), (1, 2, 2), (1, 1, 2)]
@@ -172,6 +174,10 @@ def gen(planes=2, perlane=False):
     emit("s_cbranch_scc1 " + lab("cxd"))
     emit("s_cmp_eq_u32 s82, %d" % OP_XPOSE)
     emit("s_cbranch_scc1 " + lab("xp"))
+    emit("s_cmp_eq_u32 s82, %d" % OP_CX_LANE)
+    emit("s_cbranch_scc1 " + lab("cxl"))
+    emit("s_cmp_eq_u32 s82, %d" % OP_CX_PAR)
+    emit("s_cbranch_scc1 " + lab("cxp"))
     emit("s_cmp_eq_u32 s82, %d" % OP_CZ_REG)
     emit("s_cbranch_scc1 " + lab("zr"))
     emit("s_cmp_eq_u32 s82, %d" % OP_CZ_MIX)
@@ -294,6 +300,7 @@ def gen(planes=2, perlane=False):
     emit("v_and_b32 %[t0], s85, %[e0hi]")
     emit("v_or_b32 %[tc], %[tc], %[t0]")
     emit("v_cmp_ne_u32 vcc, 0, %[tc]")
+    emit(lab("cxdx") + ":")
     emit("s_and_saveexec_b64 s[84:85], vcc")
     emit("s_cbranch_execz " + lab("cxdone"))
     for j in range(R - 1):
@@ -311,7 +318,61 @@ def gen(planes=2, perlane=False):
     emit("s_mov_b64 exec, s[84:85]")
     emit("s_branch " + lab("next"))
 
+    # ---- CNOT, target = register bit a, control = parity of the lane's index bits in arg (a mask
+    # over the low 32 bits of the extended index, none of them in the register run): the condition,
+    # then the swaps of the handler above
+    emit(ALIGN)
+    emit(lab("cxp") + ":")
+    prefetch_next_word()
+    emit("v_and_b32 %[tc], s81, %[e0lo]")
+    emit("v_bcnt_u32_b32 %[tc], %[tc], 0")
+    emit("v_and_b32 %[tc], 1, %[tc]")
+    emit("v_cmp_ne_u32 vcc, 0, %[tc]")
+    emit("s_branch " + lab("cxdx"))
 
+
+
+    # ---- CNOT, control = register bit a, target = bit b of the lane number: every lane trades its
+    # eight amplitudes with the control set for the partner lane's (lane ^ 2^b).  b = 0, 1: DPP
+    # quad permutes, in place; b >= 2: ds_bpermute_b32 (lane crossbar of the LDS unit, no memory
+    # involved) with the partner's byte address in %[tc].
+    emit(ALIGN)
+    emit(lab("cxl") + ":")
+    prefetch_next_word()
+    emit("s_bfe_u32 s84, s80, 0x80010")           # b
+    emit("s_cmp_eq_u32 s84, 0")
+    emit("s_cbranch_scc1 " + lab("cxlq0"))
+    emit("s_cmp_eq_u32 s84, 1")
+    emit("s_cbranch_scc1 " + lab("cxlq1"))
+    emit("s_lshl_b32 s85, 1, s84")
+    emit("v_xor_b32 %[tc], s85, %[thr]")
+    emit("v_and_b32 %[tc], 63, %[tc]")
+    emit("v_lshlrev_b32 %[tc], 2, %[tc]")
+    for j in range(R - 1):
+        emit("s_cmp_eq_u32 s83, %d" % j)
+        emit("s_cbranch_scc1 " + lab("cxlb%d" % j))
+    for j in reversed(range(R)):
+        emit(ALIGN)
+        emit(lab("cxlb%d" % j) + ":")
+        for k in range(NR):
+            if (k >> j) & 1:
+                emit("ds_bpermute_b32 %%[r%d], %%[tc], %%[r%d]" % (k, k))
+                emit("ds_bpermute_b32 %%[i%d], %%[tc], %%[i%d]" % (k, k))
+        emit("s_branch " + lab("next"))           # the wait at the top covers the exchange
+    for b, perm in ((0, "[1,0,3,2]"), (1, "[2,3,0,1]")):
+        emit(lab("cxlq%d" % b) + ":")
+        for j in range(R - 1):
+            emit("s_cmp_eq_u32 s83, %d" % j)
+            emit("s_cbranch_scc1 " + lab("cxlq%d_%d" % (b, j)))
+        for j in reversed(range(R)):
+            emit(ALIGN)
+            emit(lab("cxlq%d_%d" % (b, j)) + ":")
+            for k in range(NR):
+                if (k >> j) & 1:
+                    for part in "ri":
+                        emit("v_mov_b32_dpp %%[%s%d], %%[%s%d] quad_perm:%s row_mask:0xf bank_mask:0xf"
+                             % (part, k, part, k, perm))
+            emit("s_branch " + lab("next"))
 
     def flip(part, k):
         return "v_xor_b32 %%[%s%d], 0x80000000, %%[%s%d]" % (part, k, part, k)

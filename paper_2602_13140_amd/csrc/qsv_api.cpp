@@ -42,6 +42,8 @@ int ceil_log2_i64(int64_t v) {
 struct CachedPlan {
     qsv_circuit c;
     int inverse, tile, grad, low;   // tile: the resolved tile size (the default depends on the rows)
+    int defer = 0;                  // planned with deferred CNOTs (index maps)
+    size_t maps_off = 0;            // uint32[plan.maps.size()]: the index maps of its passes
     Plan plan;
     bool resident = false;          // its arrays are in the ops region right now
     size_t dev_off;     // byte offset of the ops inside the ops region
@@ -72,6 +74,7 @@ struct qsv_ctx {
     int opt_probe_layout = -1;  // probe pass: register run of the load and the store (-1: the highest)
     int64_t opt_grad_chunk = 0;
     int opt_split = -1;      // state rows of a launch sequence in two halves on two streams; -1: by state size
+    int opt_defer = -1;      // qsv_apply_layers defers CNOTs whose target lies outside a pass's tile; -1: when it can
     hipStream_t side = nullptr;          // second stream for that (default priority, non-blocking)
     hipEvent_t ev_fork = nullptr, ev_join = nullptr;
     bool forked = false;                 // a caller further up already runs two halves on the two streams
@@ -153,13 +156,13 @@ bool same_circuit(const qsv_circuit& a, const qsv_circuit& b) {
 // region is filled again from its start: the copies that overwrite it are ordered, on the stream,
 // behind every kernel that read the old contents, so nothing waits on the host.
 qsv_status get_plan(qsv_ctx* ctx, const qsv_circuit& c, int64_t rows, int inverse, int grad,
-                    const CachedPlan** out) {
+                    const CachedPlan** out, int defer = 0) {
     int tile = ctx->opt_tile > 0 ? ctx->opt_tile : default_tile(ctx->n, rows);
     tile = std::max(kMinTile, std::min(kMaxTile, tile));
     CachedPlan* hit = nullptr;
     for (CachedPlan& cp : ctx->cache)
         if (cp.inverse == inverse && cp.tile == tile && cp.grad == grad && cp.low == ctx->opt_low &&
-            same_circuit(cp.c, c)) {
+            cp.defer == defer && same_circuit(cp.c, c)) {
             hit = &cp;
             break;
         }
@@ -174,7 +177,8 @@ qsv_status get_plan(qsv_ctx* ctx, const qsv_circuit& c, int64_t rows, int invers
         cp.tile = tile;
         cp.grad = grad;
         cp.low = ctx->opt_low;
-        cp.plan = build_plan(c, ctx->n, rows, inverse != 0, tile, grad != 0, ctx->opt_low);
+        cp.defer = defer;
+        cp.plan = build_plan(c, ctx->n, rows, inverse != 0, tile, grad != 0, ctx->opt_low, defer != 0);
         if (!cp.plan.complete) return fail(ctx, QSV_ERR_UNSUPPORTED, "internal: pass planner failed");
         const size_t nm = cp.plan.mat_order.size();
         cp.exec_of.assign(nm, 0);
@@ -186,7 +190,8 @@ qsv_status get_plan(qsv_ctx* ctx, const qsv_circuit& c, int64_t rows, int invers
     const size_t nm = cp.plan.mat_order.size();
     const size_t ops_bytes = align_up(cp.plan.ops.size() * sizeof(Op) + sizeof(Op));
     const size_t tab_bytes = align_up(nm * sizeof(int32_t) + 4);
-    const size_t bytes = ops_bytes + 2 * tab_bytes;
+    const size_t map_bytes = align_up(cp.plan.maps.size() * sizeof(uint32_t) + 4);
+    const size_t bytes = ops_bytes + 2 * tab_bytes + map_bytes;
     if (bytes > kOpsRegion) return fail(ctx, QSV_ERR_UNSUPPORTED, "circuit too long for the plan buffer");
     if (ctx->ops_used + bytes > kOpsRegion) {
         // While a call has work on the second stream, kernels there may still read the region, and
@@ -199,6 +204,11 @@ qsv_status get_plan(qsv_ctx* ctx, const qsv_circuit& c, int64_t rows, int invers
     cp.dev_off = ctx->ops_used;
     cp.order_off = cp.dev_off + ops_bytes;
     cp.execof_off = cp.order_off + tab_bytes;
+    cp.maps_off = cp.execof_off + tab_bytes;
+    if (!cp.plan.maps.empty())
+        QSV_HIP(ctx, hipMemcpyAsync(ctx->ws + cp.maps_off, cp.plan.maps.data(), cp.plan.maps.size() * sizeof(uint32_t),
+                                    hipMemcpyHostToDevice, ctx->stream),
+                "upload index maps");
     if (!cp.plan.ops.empty())
         QSV_HIP(ctx, hipMemcpyAsync(ctx->ws + cp.dev_off, cp.plan.ops.data(),
                                     cp.plan.ops.size() * sizeof(Op), hipMemcpyHostToDevice, ctx->stream),
@@ -243,7 +253,7 @@ size_t mats_bytes(const qsv_circuit& c, int n, int64_t samples) {
 
 qsv_status prepare_circuit(qsv_ctx* ctx, const qsv_circuit& c, int64_t rows, int inverse, int grad,
                            const float* params, const float* feats, int64_t samples, float* mats,
-                           Prepared* out) {
+                           Prepared* out, int defer = 0) {
     const int n = ctx->n;
     const bool has_u = (c.reupload + c.n_rot) > 0 && c.n_layers > 0;
     out->mats = mats;
@@ -251,7 +261,7 @@ qsv_status prepare_circuit(qsv_ctx* ctx, const qsv_circuit& c, int64_t rows, int
     const int* order = nullptr;
     const int* exec_of = nullptr;
     if (!(ctx->opt_naive || n < kRegBits)) {
-        qsv_status st = get_plan(ctx, c, rows, inverse, grad, &out->cp);
+        qsv_status st = get_plan(ctx, c, rows, inverse, grad, &out->cp, defer);
         if (st != QSV_OK) return st;
         order = reinterpret_cast<const int*>(ctx->ws + out->cp->order_off);
         exec_of = reinterpret_cast<const int*>(ctx->ws + out->cp->execof_off);
@@ -307,9 +317,11 @@ inline Prepared layer_of(const Prepared& all, int l, int n) {
 // two rows; otherwise the reduction kernels read the final states.  zpart: room for partials.
 struct ZSpec { int q; double* out; Scatter sc; double* zpart; };
 
+// pong (needed when the plan defers CNOTs): a second buffer of the state's shape.  A pass with an
+// index map reads one buffer and writes the other; the result always ends up in `state`.
 qsv_status run_circuit(qsv_ctx* ctx, const qsv_circuit& c, const Prepared& pr, float2* state, int64_t rows,
                        int inverse, const float* ovr, const RowMap& rm, const float2* src = nullptr,
-                       const ZSpec* zs = nullptr) {
+                       const ZSpec* zs = nullptr, float2* pong = nullptr) {
     const int n = ctx->n;
     const bool has_u = (c.reupload + c.n_rot) > 0;
     const int n_mats = has_u ? (pr.mat_stride > 0 ? pr.mat_stride : c.n_layers * n) : 0;
@@ -383,11 +395,27 @@ qsv_status run_circuit(qsv_ctx* ctx, const qsv_circuit& c, const Prepared& pr, f
         return e > pl.tile ? (1ull << (e - pl.tile)) : 1ull;
     };
     const int waves_per_group = std::max(1, (1 << (pl.tile - kRegBits)) / 64);
+    // Which passes change buffers: those with an index map must; when their number is odd, one pass
+    // without a map changes too (any pass may), so that the last one writes into `state`.  A plan in
+    // which every pass has a map and their number is odd ends with a copy.
+    size_t n_mapped = 0, extra_switch = pl.passes.size();
+    for (const Pass& ps : pl.passes) n_mapped += ps.map_begin >= 0;
+    if (n_mapped && (!pong || src || zs || n > 28))
+        return fail(ctx, QSV_ERR_UNSUPPORTED, "internal: a plan with deferred CNOTs needs a second buffer");
+    if (n_mapped & 1)
+        for (size_t pi = 0; pi < pl.passes.size(); ++pi)
+            if (pl.passes[pi].map_begin < 0) { extra_switch = pi; break; }
+    float2* cur = state;
     bool first = true;
     for (size_t pi = 0; pi < pl.passes.size(); ++pi) {
         const Pass& ps = pl.passes[pi];
         PassArgs a;
-        a.state = state;
+        const bool switches = ps.map_begin >= 0 || pi == extra_switch;
+        float2* const dst = switches ? (cur == state ? pong : state) : cur;
+        a.state = dst;
+        a.in = cur;
+        a.imap = ps.map_begin >= 0 ? reinterpret_cast<const unsigned*>(ctx->ws + cp->maps_off) + ps.map_begin : nullptr;
+        cur = dst;
         a.src = (first && src_in_pass) ? src : nullptr;
         first = false;
         const bool last = pi + 1 == pl.passes.size();
@@ -413,7 +441,8 @@ qsv_status run_circuit(qsv_ctx* ctx, const qsv_circuit& c, const Prepared& pr, f
         // row numbers (row0 moves); otherwise a row's matrices and start state are found relative to
         // the launch, so those pointers move with the state.
         PassArgs b = a;
-        b.state = state + ((uint64_t)rows_a << n);
+        b.state = a.state + ((uint64_t)rows_a << n);
+        b.in = a.in + ((uint64_t)rows_a << n);
         b.total = (uint64_t)rows_b << n;
         if (rm.grad) {
             b.rm.row0 = rm.row0 + rows_a;
@@ -429,6 +458,8 @@ qsv_status run_circuit(qsv_ctx* ctx, const qsv_circuit& c, const Prepared& pr, f
         QSV_HIP(ctx, hipEventRecord(ctx->ev_join, ctx->side), "join");
         QSV_HIP(ctx, hipStreamWaitEvent(ctx->stream, ctx->ev_join, 0), "join");
     }
+    if (cur != state)
+        QSV_HIP(ctx, hipMemcpyAsync(state, cur, state_bytes, hipMemcpyDeviceToDevice, ctx->stream), "copy back");
     if (z_in_pass) {
         // partials per row: tiles of the row x wavefronts of a workgroup
         const int64_t per_row = ((int64_t)1 << (n - pl.tile)) * (((int64_t)1 << (pl.tile - kRegBits)) / 64 > 0
@@ -570,6 +601,11 @@ qsv_status qsv_set_option(qsv_ctx* ctx, const char* name, int64_t value) {
         ctx->opt_split = (int)value;
         return QSV_OK;
     }
+    if (!strcmp(name, "defer_cnots")) {
+        if (value < -1 || value > 1) return fail(ctx, QSV_ERR_INVALID_ARG, "defer_cnots must be -1, 0 or 1");
+        ctx->opt_defer = (int)value;
+        return QSV_OK;
+    }
     if (!strcmp(name, "probe_layout")) {
         if (value < -1 || value > kMaxTile - kRegBits)
             return fail(ctx, QSV_ERR_INVALID_ARG, "probe_layout must be -1 or in 0..10");
@@ -625,10 +661,23 @@ qsv_status qsv_apply_layers(qsv_ctx* ctx, const qsv_circuit* c, const float* par
     Arena ar(ctx);
     float* mats = (float*)ar.take(mats_bytes(*c, ctx->n, ctx->batch));
     if (!mats) return ws_fail(ctx, ar, "qsv_apply_layers");
+    // CNOTs whose target lies outside a pass's tile can be carried by the pass's index map (fewer
+    // passes over the state); such passes write a second buffer, taken from the workspace.
+    const size_t state_bytes = ((size_t)ctx->batch << ctx->n) * 8;
+    float2* pong = nullptr;
+    int defer = 0;
+    if (ctx->opt_defer != 0 && c->entangler == QSV_ENT_CNOT_RING && ctx->n <= 28 && !ctx->opt_naive &&
+        ar.remaining() >= align_up(state_bytes)) {
+        int tile = ctx->opt_tile > 0 ? ctx->opt_tile : default_tile(ctx->n, ctx->batch);
+        if (ctx->n > tile) {
+            pong = (float2*)ar.take(state_bytes);
+            defer = pong ? 1 : 0;
+        }
+    }
     Prepared pr;
-    st = prepare_circuit(ctx, *c, ctx->batch, inverse, 0, params_dev, feats_dev, ctx->batch, mats, &pr);
+    st = prepare_circuit(ctx, *c, ctx->batch, inverse, 0, params_dev, feats_dev, ctx->batch, mats, &pr, defer);
     if (st != QSV_OK) return st;
-    return run_circuit(ctx, *c, pr, ctx->state, ctx->batch, inverse, nullptr, plain_rows(ctx->n));
+    return run_circuit(ctx, *c, pr, ctx->state, ctx->batch, inverse, nullptr, plain_rows(ctx->n), nullptr, nullptr, pong);
 }
 
 // Every measurement kind; ar is where the kernels' partial results go (the caller's workspace, or the
@@ -1232,6 +1281,8 @@ qsv_status qsv_probe_pass(qsv_ctx* ctx, int low_bits, int window_start, int tran
     QSV_HIP(ctx, hipStreamSynchronize(ctx->stream), "upload probe");
     PassArgs a;
     a.state = ctx->state;
+    a.in = ctx->state;
+    a.imap = nullptr;
     a.src = nullptr;
     a.zout = nullptr; a.zq = 0; a.nostore = 0;
     a.nt_store = ctx->opt_nt_store >= 0 ? ctx->opt_nt_store : ((((uint64_t)ctx->batch << n) * 8) >= kNtStoreBytes ? 1 : 0);

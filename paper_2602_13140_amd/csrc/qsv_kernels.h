@@ -30,8 +30,13 @@ struct RowMap {
 };
 
 struct PassArgs {
-    float2* state;
-    const float2* src;   // not NULL: tiles are read from src[sample of the row] instead of state (needs n >= tile)
+    float2* state;       // the buffer the tiles are written to
+    const float2* in;    // the buffer the tiles are read from: state itself, or (a pass with an index map
+                         // must not write what it reads) another buffer of the same shape
+    const unsigned* imap;  // not NULL: n entries; an amplitude whose position (tile bits plus its place in
+                         // the tile at the end of the pass) has bit j set is written to the index with the
+                         // bits imap[j] flipped: deferred CNOTs (needs n > tile and n <= 28)
+    const float2* src;   // not NULL: tiles are read from src[sample of the row] instead of in (needs n >= tile)
     const Op* ops;
     double* zout;        // not NULL: the pass also writes <Z_zq> partials [tile][wavefront] (needs n >= tile)
     int zq;

@@ -241,19 +241,19 @@ void k_pass(const PassArgs a) {
     const bool off32 = (expand((1u << T) - 1u) >> 29) == 0;
     // Where the tile is read from: the state itself, or (first pass of a gradient chunk, rows
     // uniform per tile) the kept start state of the row's sample, so that no copy pass is needed.
-    const float2* ld = a.state;
+    const float2* ld = a.in;
     if (a.src && rows_uniform) {
         const u64 d = (u64)(((long long)urc.sample - (long long)(tile_base >> a.n)) << a.n);
         const long long ds = (long long)(((u64)to_sgpr((unsigned)(d >> 32)) << 32) | to_sgpr((unsigned)d));
         ld = a.src + ds;
     }
-    if (full && off32 && ld == a.state) {
+    if (full && off32 && ld == a.in) {
         // the common case, written against the kernel argument itself: the compiler then keeps the
         // per-element base in scalar registers and spends no vector arithmetic on addresses
         const unsigned lane_byte = (unsigned)expand(tau0) * 8u;
         const u64 st0 = expand(1u << scur) * 8u, st1 = expand(2u << scur) * 8u, st2 = expand(4u << scur) * 8u,
                   st3 = expand(8u << scur) * 8u;
-        const char* bp = (const char*)(a.state + tile_base) - st0;
+        const char* bp = (const char*)(a.in + tile_base) - st0;
 #define QSV_LD(k, bit, sign) { bp = bp sign st##bit; \
                     const float2 v = *(const float2*)(bp + lane_byte); vr##k = v.x; vi##k = v.y; }
         QSV_16G(QSV_LD)
@@ -369,7 +369,42 @@ void k_pass(const PassArgs a) {
         if ((thr & 63u) == 0) a.zout[tb * (blockDim.x >> 6) + (thr >> 6)] = tot;
         if (a.nostore) return;
     }
-    if (full && off32 && a.nt_store) {
+    if (a.imap) {
+        // Deferred CNOTs: every amplitude goes to the index its position maps to.  The map is linear
+        // over XOR, so the destination is (tile's part) ^ (lane's part) ^ (register element's part);
+        // bits at and above n (the state row) stay.  The host only sets imap when every tile is full and
+        // byte offsets inside a row fit 32 bits.
+        const unsigned nmask = (1u << a.n) - 1u;
+        const unsigned* im = a.imap;
+        unsigned et = 0;
+        for (unsigned rem = to_sgpr((unsigned)tile_base & nmask); rem; rem &= rem - 1u) et ^= im[__builtin_ctz(rem)];
+        const unsigned pos_lane = (unsigned)(e0 ^ tile_base);      // the lane's own index bits (register bits zero)
+        unsigned el = et;
+        for (int b = 0; b < T; ++b) {
+            if (b >= (int)scur && b < (int)scur + R) continue;       // register bits follow below
+            const int q = b < c ? b : b - c + w;                     // index bit behind tile bit b
+            if (q >= a.n) continue;
+            el ^= ((pos_lane >> q) & 1u) ? im[q] : 0u;
+        }
+        auto reg_part = [&](int j) -> unsigned {
+            const int b = (int)scur + j;
+            const int q = b < c ? b : b - c + w;
+            return im[q];
+        };
+        const unsigned x0 = reg_part(0), x1 = reg_part(1), x2 = reg_part(2), x3 = reg_part(3);
+        char* bp = (char*)(a.state + (tile_base & ~(u64)nmask));
+        unsigned idx = el ^ x0;                                      // the walk starts from "element 0 minus bit 0"
+        if (a.nt_store) {
+#define QSV_ST(k, bit, sign) { idx ^= x##bit; \
+                    f32x2 v; v.x = vr##k; v.y = vi##k; __builtin_nontemporal_store(v, (f32x2*)(bp + (u64)idx * 8u)); }
+            QSV_16G(QSV_ST)
+#undef QSV_ST
+        } else {
+#define QSV_ST(k, bit, sign) { idx ^= x##bit; *(float2*)(bp + (u64)idx * 8u) = make_float2(vr##k, vi##k); }
+            QSV_16G(QSV_ST)
+#undef QSV_ST
+        }
+    } else if (full && off32 && a.nt_store) {
         // States much larger than the last-level cache: nontemporal stores, so that the lines written
         // now (read again only a whole pass later) do not displace what the pass still has to read.
         const unsigned lane_byte = (unsigned)(e0 ^ tile_base) * 8u;   // the lane's own index bits

@@ -33,7 +33,13 @@ struct Geom {
 
 // CNOTs form the sequential chain that decides how many passes a ring circuit needs, so chain
 // progress outweighs rotations that merely run early.
-constexpr int kScoreU = 2, kScoreCX = 16, kScoreCZ = 1;
+// With deferred CNOTs the chain is cheap to advance and the unitaries of a window's qubits are what a
+// pass is short of, so the weights are level there.
+struct Weights { int u, cx, cz; };
+constexpr Weights kClassicWeights{2, 16, 1}, kDeferWeights{8, 8, 1};
+// The geometry of a pass is chosen by what it and the best pass after it complete together; the
+// second level is only tried for the kLookTop best first passes.
+constexpr int kLookTop = 6;
 constexpr size_t kScanLimit = 8192;
 constexpr int kMinRoundGates = 2;
 
@@ -66,53 +72,149 @@ std::vector<Gate> lower(const qsv_circuit& c, int n, bool inverse) {
     return g;
 }
 
+// Deferred CNOTs.  A CNOT is a permutation of basis states, so one whose target qubit is not local to
+// the pass need not be a register operation: the pass can instead write every amplitude to the index
+// the CNOT sends it to (another tile: such passes read one buffer and write another).  While a pass
+// runs, v[q] is the set of index bits whose parity gives the logical value of qubit q for the
+// amplitude at a given position (position = the tile's fixed index bits and the amplitude's current
+// place inside the tile); v[q] = {q} until a deferred CNOT with target q folds its control's set in.
+// Consequences, all enforced below: a unitary on a local qubit needs that qubit in no other set
+// (its two amplitudes must agree in every other logical bit); a CNOT with a local target whose
+// control has a set of several bits becomes a swap under the parity of those bits, none of which may
+// sit in the register run; a register CNOT on a bit that other sets contain folds the control's set
+// into them (the amplitude moves, its logical bits do not); and no set of a non-local qubit may hold
+// one of the low index bits, so that a 128-byte line is still written as a whole.
+struct VState {
+    uint32_t v[32];
+    uint32_t taint = 0;   // bits that occur in the set of another qubit
+    bool any = false;     // some set differs from {q}
+    void reset(int n) {
+        for (int q = 0; q < 32; ++q) v[q] = q < n ? (1u << q) : 0u;
+        taint = 0;
+        any = false;
+    }
+    void retaint(int n) {
+        taint = 0;
+        any = false;
+        for (int q = 0; q < n; ++q) {
+            taint |= v[q] & ~(1u << q);
+            any = any || v[q] != (1u << q);
+        }
+    }
+};
+
+enum ExecForm : uint8_t { F_PLAIN = 0, F_PARITY = 1, F_DEFER = 2, F_LANE = 3 };
+struct Exec {
+    int gate;
+    uint8_t form;
+    uint32_t mask;   // F_PARITY, F_DEFER: the control's set when the gate ran
+};
+
+constexpr uint32_t kLowMask = (1u << kLowBits) - 1u;
+
 // One register round: which pending gates can run with the run at tile position s.
-// Appends their indices to exec (program order) and returns the score.  Does not modify done.
+// Appends them to exec (program order) and returns the score; *n_real receives the number of gates
+// that need the tile in this layout (everything but deferred CNOTs).  vs is updated as gates run.
+// Does not modify done.
 int scan_round(const Geom& gm, int s, int n, const std::vector<Gate>& G,
-               const std::vector<uint8_t>& done, size_t first, std::vector<int>* exec) {
+               const std::vector<uint8_t>& done, size_t first, bool defer, VState& vs,
+               std::vector<Exec>* exec, int* n_real) {
     uint64_t blk_any = 0, blk_diag = 0;
     const uint64_t all = n >= 64 ? ~0ull : ((1ull << n) - 1);
-    int score = 0;
+    int score = 0, real = 0;
     const size_t end = std::min(G.size(), first + kScanLimit);
     auto in_run = [&](int q) {
         if (!gm.local(q)) return false;
         const int p = gm.pos(q);
         return p >= s && p < s + kRegBits;
     };
+    uint32_t run_mask = 0;    // the qubits behind the register run
+    for (int q = 0; q < n; ++q)
+        if (in_run(q)) run_mask |= 1u << q;
     for (size_t i = first; i < end; ++i) {
         if (done[i]) continue;
         const Gate& g = G[i];
         uint64_t m = 1ull << g.q0;
         if (g.kind != G_U) m |= 1ull << g.q1;
         bool can;
+        Exec ex{(int)i, F_PLAIN, 0};
         if (g.kind == G_CZ) {
             can = !(blk_any & m);
+        } else if (g.kind == G_U) {
+            can = !((blk_any | blk_diag) & m) && in_run(g.q0) && !((vs.taint >> g.q0) & 1u);
         } else {
-            can = !((blk_any | blk_diag) & m) && in_run(g.q0);
+            const int t = g.q0, c = g.q1;
+            const uint32_t cm = vs.v[c];
+            can = !((blk_any | blk_diag) & m) && !((cm >> t) & 1u);
+            // control in the register run, target one of the lane's own index bits: the amplitudes with
+            // the control set trade places with those of the partner lane (a cross-lane exchange, no
+            // transpose); lane_bit >= 0 is the bit of the lane number behind the target
+            int lane_bit = -1;
+            if (can && gm.local(t) && !in_run(t) && in_run(c) && cm == (1u << c)) {
+                const int pp = gm.pos(t);
+                const int b = pp < s ? pp : pp - kRegBits;     // bit of the thread index
+                if (b < 6) lane_bit = b;
+            }
+            if (lane_bit >= 0) {
+                const bool others_hold_t = (vs.taint >> t) & 1u;
+                if (others_hold_t && (cm & kLowMask)) can = false;
+                if (can && others_hold_t) {
+                    for (int q = 0; q < n; ++q)
+                        if (q != t && ((vs.v[q] >> t) & 1u)) vs.v[q] ^= cm;
+                    vs.retaint(n);
+                }
+                ex.form = F_LANE;
+                ex.mask = (uint32_t)lane_bit;
+            } else if (can && gm.local(t)) {
+                can = in_run(t);
+                if (can && cm != (1u << c)) {
+                    can = !(cm & run_mask);
+                    ex.form = F_PARITY;
+                    ex.mask = cm;
+                }
+                const bool others_hold_t = (vs.taint >> t) & 1u;
+                if (can && others_hold_t && (cm & kLowMask)) can = false;
+                if (can && others_hold_t) {
+                    for (int q = 0; q < n; ++q)
+                        if (q != t && ((vs.v[q] >> t) & 1u)) vs.v[q] ^= cm;
+                    vs.retaint(n);
+                }
+            } else if (can) {
+                can = defer && !(cm & kLowMask);
+                if (can) {
+                    ex.form = F_DEFER;
+                    ex.mask = cm;
+                    vs.v[t] ^= cm;
+                    vs.retaint(n);
+                }
+            }
         }
         if (can) {
-            if (exec) exec->push_back((int)i);
-            score += g.kind == G_U ? kScoreU : g.kind == G_CNOT ? kScoreCX : kScoreCZ;
+            if (exec) exec->push_back(ex);
+            const Weights& wt = defer ? kDeferWeights : kClassicWeights;
+            score += g.kind == G_U ? wt.u : g.kind == G_CNOT ? wt.cx : wt.cz;
+            if (ex.form != F_DEFER) ++real;
         } else {
             if (g.kind == G_CZ) blk_diag |= m; else blk_any |= m;
             if (blk_any == all) break;
         }
     }
+    if (n_real) *n_real = real;
     return score;
 }
 
 void mark_transposes(std::vector<Op>& ops, size_t begin);
 
-void emit_round(const Geom& gm, int s, const std::vector<Gate>& G, const std::vector<int>& exec,
-                bool rowdep, std::vector<Op>* ops, std::vector<int32_t>* mat_order) {
+void emit_round(const Geom& gm, int s, const std::vector<Gate>& G, const std::vector<Exec>& exec,
+                bool rowdep, std::vector<Op>* ops, std::vector<int32_t>* mat_order, std::vector<Op>* defers) {
     bool last_lane = false;
     auto in_run = [&](int q) {
         if (!gm.local(q)) return false;
         const int p = gm.pos(q);
         return p >= s && p < s + kRegBits;
     };
-    for (int i : exec) {
-        const Gate& g = G[i];
+    for (const Exec& ex : exec) {
+        const Gate& g = G[ex.gate];
         if (g.kind == G_CZ) {
             // rungs commute, so each goes to the cheapest form for where its two qubits sit
             const bool r0 = in_run(g.q0), r1 = in_run(g.q1);
@@ -133,10 +235,24 @@ void emit_round(const Geom& gm, int s, const std::vector<Gate>& G, const std::ve
             continue;
         }
         last_lane = false;
+        if (ex.form == F_DEFER) {
+            // nothing happens in registers: the pass's index map carries it.  Kept beside the operation
+            // list (a = target, b = control qubit, arg = the control's set) for the plan's description.
+            if (defers) defers->push_back({OP_CX_DEFER, (uint8_t)g.q0, (uint8_t)g.q1, 0, (int32_t)ex.mask});
+            continue;
+        }
+        if (ex.form == F_LANE) {
+            ops->push_back({OP_CX_LANE, (uint8_t)(gm.pos(g.q1) - s), (uint8_t)ex.mask, (uint8_t)g.q0, 0});
+            continue;
+        }
         const int jt = gm.pos(g.q0) - s;
         if (g.kind == G_U) {
             ops->push_back({OP_U, (uint8_t)jt, (uint8_t)(rowdep ? 1 : 0), 0, (int32_t)mat_order->size()});
             mat_order->push_back(g.mat);
+            continue;
+        }
+        if (ex.form == F_PARITY) {
+            ops->push_back({OP_CX_PAR, (uint8_t)jt, (uint8_t)g.q1, 0, (int32_t)ex.mask});
             continue;
         }
         const int qc = g.q1;
@@ -155,74 +271,94 @@ void emit_round(const Geom& gm, int s, const std::vector<Gate>& G, const std::ve
 }
 
 // Greedy rounds of one pass.  Marks executed gates in done; emits ops when ops != nullptr.
-// Returns the pass score; *n_exec receives the number of gates executed.
+// Returns the pass score; *n_exec receives the number of gates executed; *vs_out the qubit sets at the
+// end of the pass (from which the caller derives the pass's index map).
 int run_pass(const Geom& gm, int n, const std::vector<Gate>& G, std::vector<uint8_t>& done,
-             size_t first, bool rowdep, std::vector<Op>* ops, std::vector<int32_t>* mat_order,
-             int* n_exec) {
+             size_t first, bool rowdep, bool defer, std::vector<Op>* ops, std::vector<int32_t>* mat_order,
+             std::vector<Op>* defers, int* n_exec, VState* vs_out) {
     const int smax = gm.t - kRegBits;
     const int smin_io = std::min(kLowBits, smax);  // layouts with coalesced global access
     // When one tile holds several state rows and matrices differ per row, a lane's 16 amplitudes
     // must share a row: gate rounds keep the run inside the qubit bits.
     const int sgate = (rowdep && n < gm.t) ? std::min(smax, n - kRegBits) : smax;
     int total = 0, cnt = 0;
-    std::vector<int> exec, best_exec;
-    auto commit = [&](int s, const std::vector<int>& ex) {
-        for (int i : ex) done[i] = 1;
+    VState vs;
+    vs.reset(n);
+    std::vector<Exec> exec, best_exec;
+    auto commit = [&](int s, const std::vector<Exec>& ex) {
+        for (const Exec& e : ex) done[e.gate] = 1;
         cnt += (int)ex.size();
-        if (ops) emit_round(gm, s, G, ex, rowdep, ops, mat_order);
+        if (ops) emit_round(gm, s, G, ex, rowdep, ops, mat_order, defers);
         while (first < G.size() && done[first]) ++first;
     };
     // first round: loaded straight from global memory
     int s = smax, best = 0;
+    VState best_vs = vs;
     best_exec.clear();
     for (int cand = smin_io; cand <= sgate; ++cand) {
         exec.clear();
-        const int sc = scan_round(gm, cand, n, G, done, first, &exec);
-        if (sc > best) { best = sc; s = cand; best_exec = exec; }
+        VState tv = vs;
+        const int sc = scan_round(gm, cand, n, G, done, first, defer, tv, &exec, nullptr);
+        if (sc > best) { best = sc; s = cand; best_exec = exec; best_vs = tv; }
     }
     if (ops) ops->push_back({OP_LOAD, (uint8_t)s, 0, 0, 0});
     total += best;
+    vs = best_vs;
     commit(s, best_exec);
     for (;;) {
         if (first >= G.size()) break;
-        int bs = -1;
+        int bs = -1, best_real = 0;
         best = 0;
         for (int cand = 0; cand <= sgate; ++cand) {
             if (cand == s) continue;
             exec.clear();
-            const int sc = scan_round(gm, cand, n, G, done, first, &exec);
+            VState tv = vs;
+            int real = 0;
+            const int sc = scan_round(gm, cand, n, G, done, first, defer, tv, &exec, &real);
             // ties go to the later (higher) layout, which also stores coalesced
             if (sc > best || (sc == best && sc > 0 && cand >= smin_io)) {
-                best = sc; bs = cand; best_exec = exec;
+                best = sc; bs = cand; best_exec = exec; best_vs = tv; best_real = real;
             }
         }
         if (bs < 0 || best == 0) break;
-        const bool critical = !best_exec.empty() && (size_t)best_exec.front() == first;
-        if (!critical && (int)best_exec.size() < kMinRoundGates) {
+        if (best_real == 0) {
+            // only deferred CNOTs: they need no layout, so no transpose either
+            total += best;
+            vs = best_vs;
+            commit(s, best_exec);
+            continue;
+        }
+        const bool critical = !best_exec.empty() && (size_t)best_exec.front().gate == first;
+        if (!critical && best_real < kMinRoundGates) {
             // A transpose for one stray gate is not worth it, unless going on like this finishes
             // the whole circuit inside this pass (then it saves a pass over the state).
             std::vector<uint8_t> tmp(done);
             size_t f2 = first;
             int s2 = s;
+            VState v2 = vs;
             for (;;) {
                 int b2 = 0, bs2 = -1;
-                std::vector<int> ex2, bex2;
+                std::vector<Exec> ex2, bex2;
+                VState bv2 = v2;
                 for (int cand = 0; cand <= sgate; ++cand) {
                     if (cand == s2) continue;
                     ex2.clear();
-                    const int sc = scan_round(gm, cand, n, G, tmp, f2, &ex2);
-                    if (sc > b2) { b2 = sc; bs2 = cand; bex2 = ex2; }
+                    VState tv = v2;
+                    const int sc = scan_round(gm, cand, n, G, tmp, f2, defer, tv, &ex2, nullptr);
+                    if (sc > b2) { b2 = sc; bs2 = cand; bex2 = ex2; bv2 = tv; }
                 }
                 if (bs2 < 0) break;
-                for (int i : bex2) tmp[i] = 1;
+                for (const Exec& e : bex2) tmp[e.gate] = 1;
                 while (f2 < G.size() && tmp[f2]) ++f2;
                 s2 = bs2;
+                v2 = bv2;
             }
             if (f2 < G.size()) break;
         }
         s = bs;
         if (ops) ops->push_back({OP_XPOSE, (uint8_t)s, 0, 0, 0});
         total += best;
+        vs = best_vs;
         commit(s, best_exec);
     }
     if (s < smin_io) {
@@ -231,6 +367,7 @@ int run_pass(const Geom& gm, int n, const std::vector<Gate>& G, std::vector<uint
     }
     if (ops) ops->push_back({OP_END, 0, 0, 0, 0});
     if (n_exec) *n_exec = cnt;
+    if (vs_out) *vs_out = vs;
     return total;
 }
 
@@ -315,7 +452,7 @@ int default_tile(int n, int64_t batch) {
 }
 
 Plan build_plan(const qsv_circuit& c, int n, int64_t batch, bool inverse, int tile_log2, bool grad,
-                int min_low_bits) {
+                int min_low_bits, bool defer) {
     Plan p;
     p.n = n;
     p.ext_bits = n + ceil_log2(batch);
@@ -326,37 +463,83 @@ Plan build_plan(const qsv_circuit& c, int n, int64_t batch, bool inverse, int ti
     p.n_mats = has_u ? c.n_layers * n : 0;
     p.row_dependent = c.reupload != 0;
     const bool rowdep = p.row_dependent || grad;
+    // deferring needs qubits outside the tile, and index maps of 32 bits
+    defer = defer && n > t && n <= 30;
+    p.deferring = defer;
 
     const std::vector<Gate> G = lower(c, n, inverse);
     std::vector<uint8_t> done(G.size(), 0);
     size_t first = 0;
     const int cmin = std::min(std::max(kLowBits, min_low_bits), t);
-    while (first < G.size()) {
-        Geom bestg{t, cmin, cmin};
-        int best = -1;
-        // local set = low c bits + window of t-c bits at w; c >= 4 keeps 128-byte runs contiguous
+    // local set = low c bits + window of t-c bits at w; c >= 4 keeps 128-byte runs contiguous
+    auto all_geoms = [&](auto&& fn) {
         for (int cl = cmin; cl <= t; ++cl) {
             const int win = t - cl;
             const int wmax = (win > 0 && n > t) ? n - win : cl;
             for (int w = cl; w <= wmax; ++w) {
                 if (w == cl && cl != cmin && n > t) continue;  // same set as (cmin, w = cmin)
-                Geom gm{t, cl, w};
-                std::vector<uint8_t> tmp(done);
-                int ne = 0;
-                const int sc = run_pass(gm, n, G, tmp, first, rowdep, nullptr, nullptr, &ne);
-                if (sc > best) { best = sc; bestg = gm; }
+                fn(Geom{t, cl, w});
             }
             if (n <= t) break;  // the whole state row is local: one geometry
+        }
+    };
+    struct Cand { Geom g; int score; };
+    std::vector<Cand> cands;
+    while (first < G.size()) {
+        cands.clear();
+        all_geoms([&](Geom gm) {
+            std::vector<uint8_t> tmp(done);
+            int ne = 0;
+            const int sc = run_pass(gm, n, G, tmp, first, rowdep, defer, nullptr, nullptr, nullptr, &ne, nullptr);
+            cands.push_back({gm, sc});
+        });
+        std::stable_sort(cands.begin(), cands.end(), [](const Cand& a, const Cand& b) { return a.score > b.score; });
+        Geom bestg = cands[0].g;
+        if (defer && cands.size() > 1) {
+            // two passes ahead (deferral makes the one-pass score short-sighted: a pass that defers a
+            // long stretch of the chain scores well and leaves little for the next one)
+            int best = -1;
+            for (size_t ci = 0; ci < cands.size() && (int)ci < kLookTop; ++ci) {
+                std::vector<uint8_t> tmp(done);
+                int ne = 0;
+                run_pass(cands[ci].g, n, G, tmp, first, rowdep, defer, nullptr, nullptr, nullptr, &ne, nullptr);
+                size_t f2 = first;
+                while (f2 < G.size() && tmp[f2]) ++f2;
+                int b2 = 0;
+                if (f2 >= G.size()) b2 = 1 << 24;             // finishes the circuit
+                else
+                    all_geoms([&](Geom g2) {
+                        std::vector<uint8_t> tmp2(tmp);
+                        int ne2 = 0;
+                        const int sc2 = run_pass(g2, n, G, tmp2, f2, rowdep, defer, nullptr, nullptr, nullptr, &ne2, nullptr);
+                        if (sc2 > b2) b2 = sc2;
+                    });
+                if (cands[ci].score + b2 > best) { best = cands[ci].score + b2; bestg = cands[ci].g; }
+            }
         }
         Pass ps;
         ps.t = bestg.t; ps.c = bestg.c; ps.w = bestg.w;
         ps.op_begin = (int)p.ops.size();
         int ne = 0;
-        run_pass(bestg, n, G, done, first, rowdep, &p.ops, &p.mat_order, &ne);
+        VState vs;
+        ps.defer_begin = (int)p.defers.size();
+        run_pass(bestg, n, G, done, first, rowdep, defer, &p.ops, &p.mat_order, &p.defers, &ne, &vs);
         mark_transposes(p.ops, (size_t)ps.op_begin);
         merge_cx_chains(p.ops, (size_t)ps.op_begin);
         ps.op_count = (int)p.ops.size() - ps.op_begin;
+        ps.defer_count = (int)p.defers.size() - ps.defer_begin;
         ps.n_gates = ne;
+        if (vs.any) {
+            // index map of the pass: map[j] = the index bits that flip in an amplitude's destination
+            // when bit j of its position is set = the qubits whose set holds j (always j itself)
+            ps.map_begin = (int)p.maps.size();
+            for (int j = 0; j < n; ++j) {
+                uint32_t mj = 0;
+                for (int q = 0; q < n; ++q)
+                    if ((vs.v[q] >> j) & 1u) mj |= 1u << q;
+                p.maps.push_back(mj);
+            }
+        }
         p.passes.push_back(ps);
         if (ne == 0) { p.complete = false; break; }  // cannot happen: the first pending gate always fits some window
         while (first < G.size() && done[first]) ++first;
@@ -386,9 +569,23 @@ std::string describe_plan(const Plan& p) {
                 case OP_CZ_MIX: snprintf(buf, sizeof buf, " Zm%d:%d", o.a, o.b); break;
                 case OP_CZ_LANE: snprintf(buf, sizeof buf, " Zl%x", (unsigned)o.arg); break;
                 case OP_CX_CHAIN: snprintf(buf, sizeof buf, " C%c%d:%d", o.c ? 'd' : 'u', o.a, o.b); break;
+                case OP_CX_PAR: snprintf(buf, sizeof buf, " Q%d:%d:%x", o.a, o.b, (unsigned)o.arg); break;
+                case OP_CX_LANE: snprintf(buf, sizeof buf, " N%d:%d:%d", o.a, o.b, o.c); break;
                 default: snprintf(buf, sizeof buf, " ?"); break;
             }
             s += buf;
+        }
+        for (int i = ps.defer_begin; i < ps.defer_begin + ps.defer_count; ++i) {
+            const Op& o = p.defers[i];
+            snprintf(buf, sizeof buf, " V%d:%d:%x", o.a, o.b, (unsigned)o.arg);
+            s += buf;
+        }
+        if (ps.map_begin >= 0) {
+            s += " M";
+            for (int j = 0; j < p.n; ++j) {
+                snprintf(buf, sizeof buf, "%s%x", j ? "," : "", (unsigned)p.maps[ps.map_begin + j]);
+                s += buf;
+            }
         }
         s += "\n";
     }
@@ -402,8 +599,10 @@ extern "C" int64_t qsv_plan_describe(const qsv_circuit* c, int n_qubits, int bat
                                      char* buf, int64_t buf_bytes) {
     using namespace qsv;
     if (!check_circuit(c, n_qubits, nullptr) || batch < 1) return -1;
+    const bool defer = (tile_log2 & 0x100) != 0;     // flag bit: the plan with deferred CNOTs
+    tile_log2 &= 0xff;
     if (tile_log2 != 0 && (tile_log2 < kMinTile || tile_log2 > kMaxTile)) return -1;
-    const Plan p = build_plan(*c, n_qubits, batch, inverse != 0, tile_log2, false);
+    const Plan p = build_plan(*c, n_qubits, batch, inverse != 0, tile_log2, false, 0, defer);
     const std::string s = describe_plan(p);
     if (buf && buf_bytes > 0) {
         const size_t ncopy = s.size() < (size_t)buf_bytes - 1 ? s.size() : (size_t)buf_bytes - 1;

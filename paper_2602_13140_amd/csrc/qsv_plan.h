@@ -36,10 +36,19 @@ enum OpKind : uint8_t {
     OP_CZ_MIX = 7,  // CZ between register bit a and index bit b outside the run (lane-dependent)
     OP_CZ_LANE = 8, // arg = rung mask (bit q -> CZ(q, q+1)), all rungs between index bits outside
                     // the run: one lane-dependent sign for all 16 amplitudes
-    OP_CX_CHAIN = 9 // b = 2 or 3 consecutive OP_CX_REG between neighbouring register bits, as a CNOT
+    OP_CX_CHAIN = 9,// b = 2 or 3 consecutive OP_CX_REG between neighbouring register bits, as a CNOT
                     // ring produces them, done as one permutation of the registers.  a = control of
                     // the first; c = 0: targets go up (a -> a+1, a+1 -> a+2, ...), c = 1: the same
                     // gates in the opposite order, controls going down (a -> a+1, a-1 -> a, ...)
+    OP_CX_PAR = 10, // a = target register bit; the control is the parity of the amplitude's position
+                    // bits in arg (a mask over the extended index, no bit of it in the register run);
+                    // b = the control qubit (for the description only)
+    OP_CX_LANE = 12, // CNOT with the control in register bit a and the target behind bit b (0..5) of the
+                    // lane number: the eight amplitudes with the control set are exchanged with the
+                    // partner lane's (DPP for b < 2, ds_bpermute above); c = the target qubit (for the
+                    // description only)
+    OP_CX_DEFER = 11 // never part of an operation list: a CNOT that the pass's index map carries (see
+                    // Plan::defers); a = target qubit, b = control qubit, arg = the control's bit set
 };
 
 struct Op {
@@ -53,6 +62,9 @@ struct Pass {
     int op_begin;       // first op in Plan::ops
     int op_count;
     int n_gates;        // circuit gates (fused level) executed by this pass
+    int map_begin = -1; // >= 0: the pass writes every amplitude to a mapped index (first of its n entries
+                        // in Plan::maps) and therefore must not write the buffer it reads
+    int defer_begin = 0, defer_count = 0;   // its deferred CNOTs in Plan::defers
 };
 
 struct Plan {
@@ -62,11 +74,18 @@ struct Plan {
     int n_mats = 0;     // matrices per state row: n_layers * n (0 if the circuit has no rotations)
     bool row_dependent = false;  // matrices differ per sample (re-upload)
     bool complete = true;        // false only on an internal scheduling failure
+    bool deferring = false;      // planned with deferred CNOTs (passes may carry index maps)
     std::vector<Pass> passes;
     std::vector<Op> ops;
     // Unitaries are numbered in the order the passes execute them, so that a tile reads its
     // matrices front to back: mat_order[k] = layer * n + qubit of the k-th executed unitary.
     std::vector<int32_t> mat_order;
+    // Index maps of the passes that defer CNOTs: n entries per such pass; entry j = the index bits that
+    // flip in an amplitude's destination index when bit j of its position is set (position = tile
+    // bits as stored plus the amplitude's place in the tile at the end of the pass).  Bits >= n (the
+    // state row) always map to themselves.
+    std::vector<uint32_t> maps;
+    std::vector<Op> defers;      // the deferred CNOTs, pass by pass (description and tests only)
 };
 
 // Validates a circuit descriptor; returns false and fills why on failure.
@@ -74,8 +93,10 @@ bool check_circuit(const qsv_circuit* c, int n, std::string* why);
 
 // tile_log2 = 0 picks the default.  grad = true marks every rotation matrix as row-dependent
 // (a shifted circuit overrides one matrix per state row).
+// defer = true lets CNOTs whose target is outside a pass's tile be carried by the pass's index map
+// (fewer passes; such a plan needs a second state buffer, see Pass::map_begin).
 Plan build_plan(const qsv_circuit& c, int n, int64_t batch, bool inverse, int tile_log2, bool grad,
-                int min_low_bits = 0);
+                int min_low_bits = 0, bool defer = false);
 
 std::string describe_plan(const Plan& p);
 

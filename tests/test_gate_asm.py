@@ -7,7 +7,7 @@ import re
 from paper_2602_13140_amd.csrc import gen_gate_asm as g
 
 INTENDED_FALLTHROUGH = {"L_top", "L_uhave", "L_ugj", "L_ua", "L_ua3", "L_ur3", "L_ug3", "L_uc3",
-                        "L_d3", "L_c5", "L_cxdone", "L_xphave", "L_xpw", "L_xpr", "L_xpw2", "L_xpr2", "L_zm3", "L_zdone"}
+                        "L_d3", "L_c5", "L_cxdone", "L_cxdx", "L_cxlb3", "L_cxlq0_3", "L_cxlq1_3", "L_xphave", "L_xpw", "L_xpr", "L_xpw2", "L_xpr2", "L_zm3", "L_zdone"}
 
 
 import pytest

@@ -73,14 +73,15 @@ SMALL = [
     (13, 3, 3, (RY, RZ), RING, 0), (14, 1, 3, (RZ, RX), NONE, 0),
     (4, 65535, 1, (RY, RZ), RING, 0),      # a batch that is no power of two; ragged last tile
     (4, 70001, 1, (RY, RZ), RING, 0),      # more rows than one grid dimension holds
-    (15, 2, 2, (RX, RY, RZ), RING, 0), (16, 1, 3, (RY, RZ), LADDER, 0),
+    (15, 2, 2, (RX, RY, RZ), RING, 0), (16, 1, 3, (RY, RZ), LADDER, 0), (16, 3, 5, (RY, RZ), RING, 0),
+    (17, 1, 6, (RX, RY, RZ), RING, 0),
     (5, 2, 0, (RY,), RING, 0),             # no layers: the state must come back unchanged
 ]
 
 
 @pytest.mark.parametrize("n,B,L,rot,ent,reup", SMALL)
 @pytest.mark.parametrize("mode", ["default", "t10", "t11", "t12", "t13", "t14", "naive",
-                                  "t10p1", "t11p2", "t12p1", "t13p1", "t12p2", "t14p1"])
+                                  "t10p1", "t11p2", "t12p1", "t13p1", "t12p2", "t14p1", "t10c", "t11c", "t12c"])
 def test_apply_layers_small(oracle, n, B, L, rot, ent, reup, mode):
     g = rng(31 * n + B + L)
     spec = wl.CircuitSpec(L, tuple(rot), ent, reup)
@@ -91,6 +92,8 @@ def test_apply_layers_small(oracle, n, B, L, rot, ent, reup, mode):
     ctx = gu.make_ctx(n, B, tile=int(mode[1:3]) if mode.startswith("t") else 0,
                       naive=1 if mode == "naive" else 0,
                       planes=int(mode[4]) if mode[3:4] == "p" else 0)
+    if mode.endswith("c"):
+        ctx.qsv_set_option("defer_cnots", 0)   # every CNOT in registers (by default those with a target outside the tile are deferred)
     if mode.endswith("p1"):
         ctx.qsv_set_option("nt_store", 1)      # nontemporal tile stores, normally for large states only
         ctx.qsv_set_option("reverse_passes", 1)  # and every other pass from the last tile to the first

@@ -53,7 +53,36 @@ def apply_cnot(st, n, ctrl, tgt):
     return st[:, src]
 
 
+def apply_index_map(st, n, imap):
+    """What a pass with deferred CNOTs does when it stores: the amplitude at position p goes to the
+    index that is the XOR of imap[j] over the set bits j of p."""
+    assert len(imap) == n
+    k = np.arange(1 << n)
+    dest = np.zeros(1 << n, dtype=np.int64)
+    for j in range(n):
+        assert (imap[j] >> j) & 1                    # a position bit always maps onto itself as well
+        if j < 4:
+            assert imap[j] == 1 << j                 # 128-byte lines are written whole
+        dest ^= np.where((k >> j) & 1, imap[j], 0)
+    assert len(np.unique(dest)) == 1 << n            # a permutation
+    out = np.empty_like(st)
+    out[:, dest] = st
+    return out
+
+
+def apply_parity_cnot(st, n, mask, tgt):
+    k = np.arange(1 << n)
+    par = np.zeros(1 << n, dtype=np.int64)
+    for j in range(n):
+        if (mask >> j) & 1:
+            par ^= (k >> j) & 1
+    src = np.where(par == 1, k ^ (1 << tgt), k)
+    return st[:, src]
+
+
 def replay(text, n, rows, L, rot, ent, reupload, params, feats, inverse, st):
+    """Within a pass, `st` is indexed by position (where the amplitude sits: the kernel's view); passes
+    without deferred CNOTs never tell the difference."""
     head, passes = parse_plan(text)
     assert head["n"] == n
     slots = int(reupload) + len(rot)
@@ -65,7 +94,10 @@ def replay(text, n, rows, L, rot, ent, reupload, params, feats, inverse, st):
         bit = lambda pos: pos if pos < c else pos - c + w
         if n > t:
             assert w + (t - c) <= n
-        assert ops[0][0] == "L" and ops[-1] == "E"
+        assert ops[0][0] == "L" and "E" in ops
+        tail = ops[ops.index("E") + 1:]
+        assert all(tk[0] in "VM" for tk in tail)          # after the store: the deferred CNOTs and the map
+        local_bits = [bit(pp) for pp in range(t)]
         s = None
         for tok in ops:
             kind = tok[0]
@@ -129,6 +161,33 @@ def replay(text, n, rows, L, rot, ent, reupload, params, feats, inverse, st):
                     assert uni == 1
                 st = apply_cnot(st, n, qc, qt)
                 n_gates += 1
+            elif kind == "N":
+                # CNOT with the control in register bit jc and the target behind bit b of the lane number
+                jc, b, qt = (int(x) for x in tok[1:].split(":"))
+                run_bits = [bit(s + j) for j in range(R)]
+                assert 0 <= jc < R and qt not in run_bits and qt in local_bits and 0 <= b < 6
+                pp = local_bits.index(qt)
+                assert b == (pp if pp < s else pp - R)        # where the lane number keeps that tile bit
+                st = apply_cnot(st, n, run_bits[jc], qt)
+                n_gates += 1
+            elif kind == "Q":
+                # CNOT on register bit jt under the parity of the position bits in mask
+                jt, qc, mask = tok[1:].split(":")
+                jt, qc, mask = int(jt), int(qc), int(mask, 16)
+                qt = bit(s + jt)
+                run_bits = [bit(s + j) for j in range(R)]
+                assert qt < n and mask < (1 << n) and bin(mask).count("1") >= 2
+                assert not any((mask >> q) & 1 for q in run_bits)
+                st = apply_parity_cnot(st, n, mask, qt)
+                n_gates += 1
+            elif kind == "V":
+                # deferred CNOT: target outside the tile, carried by the map; nothing moves now
+                qt, qc, mask = tok[1:].split(":")
+                qt, qc, mask = int(qt), int(qc), int(mask, 16)
+                assert qt not in local_bits and qt < n and not (mask & 15) and not (mask >> qt) & 1
+                n_gates += 1
+            elif kind == "M":
+                st = apply_index_map(st, n, [int(x, 16) for x in tok[1:].split(",")])
             elif kind == "Z":
                 form, body = tok[1], tok[2:]
                 run_bits = [bit(s + j) for j in range(R)]
@@ -153,6 +212,7 @@ def replay(text, n, rows, L, rot, ent, reupload, params, feats, inverse, st):
             else:
                 assert tok == "E"
         assert sum(1 for o in ops if o == "E") == 1
+        assert sum(1 for o in ops if o[0] == "V") == 0 or sum(1 for o in ops if o[0] == "M") == 1
     return st, n_gates, len(passes)
 
 
@@ -191,6 +251,41 @@ def test_plan_replay_matches_oracle(oracle, n, rows, L, rot, ent, reup, tile, in
     per_layer = (n if (reup + len(rot)) else 0) + ent_gates
     assert n_gates == L * per_layer                    # every gate exactly once
     assert np.allclose(out, ref, atol=1e-12)
+
+
+DEFER = 0x100       # flag bit of qsv_plan_describe's tile argument: the plan with deferred CNOTs
+
+DEFER_CASES = [
+    # n, L, rot, tile
+    (13, 3, (RY, RZ), 10), (14, 4, (RX, RY, RZ), 10), (15, 5, (RY, RZ), 11), (16, 4, (RX, RY, RZ), 12),
+    (17, 6, (RY,), 12), (16, 3, (), 10), (18, 4, (RY, RZ), 13), (18, 3, (RX, RY, RZ), 14), (17, 5, (RZ, RX), 10),
+]
+
+
+@pytest.mark.parametrize("n,L,rot,tile", DEFER_CASES)
+@pytest.mark.parametrize("inverse", [0, 1])
+def test_plan_with_deferred_cnots_replays_to_the_oracle(oracle, n, L, rot, tile, inverse):
+    """CNOTs whose target lies outside a pass's tile are carried by the pass's index map; replayed at
+    the level of positions (register CNOTs under parities, the map applied at the store), the plan must
+    still be the oracle's circuit, with fewer passes than the plan without deferral."""
+    g = np.random.Generator(np.random.PCG64(9000 + 17 * n + L + inverse))
+    circ = qb.make_circuit(L, list(rot), RING, 0)
+    ocirc = oracle.make_circuit(L, list(rot), RING, 0)
+    P = qb.qsv_num_params(circ, n)
+    params = g.uniform(0, 2 * np.pi, P).astype(np.float32)
+    x = g.standard_normal((1, 1 << n)).astype(np.float32)
+    ref, _ = oracle.amp_encode(x, n)
+    start = ref.copy()
+    oracle.apply_layers(ref, ocirc, params, None, inverse=bool(inverse))
+    text = qb.qsv_plan_describe(circ, n, 1, inverse, tile | DEFER)
+    out, n_gates, n_pass = replay(text, n, 1, L, rot, RING, 0, params.astype(np.float64), None, inverse, start)
+    assert n_gates == L * ((n if rot else 0) + n)
+    assert np.allclose(out, ref, atol=1e-12)
+    plain = qb.qsv_plan_describe(circ, n, 1, inverse, tile)
+    assert " V" not in plain and " M" not in plain and " Q" not in plain
+    assert n_pass <= sum(1 for ln in plain.split("\n") if ln.startswith("P "))
+    if n - tile >= 3 and L >= 3:
+        assert " V" in text and " M" in text       # the case is meant to exercise deferral
 
 
 def test_plan_pass_counts_for_the_large_configs():
