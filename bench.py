@@ -52,6 +52,7 @@ def parse_args():
     ap.add_argument("--probe-layout", type=int, default=-1,
                     help="probe pass: start of the register run the tile is loaded and stored in (-1 = highest)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
+    ap.add_argument("--no-classic", action="store_true", help="skip the extra run of config 4 without deferred CNOTs")
     ap.add_argument("--cpu-layers", type=int, default=20, help="layers of config 4 the oracle is timed on")
     return ap.parse_args()
 
@@ -90,7 +91,7 @@ def run_steps(torch, step, steps, warmup):
     return (time.perf_counter() - t0) * 1e3 / steps, tm
 
 
-def bench_c4(torch, qb, wl, args):
+def bench_c4(torch, qb, wl, args, apply_only=False):
     w = wl.config(4)
     n = w.n
     ctx = qb.Context(n, 1)
@@ -136,6 +137,9 @@ def bench_c4(torch, qb, wl, args):
         "pass_avg_ms": apply_ms / passes, "pass_bytes": 2 * state_bytes,
         "pass_gbs": 2 * state_bytes / (apply_ms / passes * 1e-3) / 1e9,
     }
+    if apply_only:
+        ctx.close()
+        return res, w
     # a Pauli-string expectation on the final state: one read pass (8 bytes per amplitude)
     ev = torch.empty(1, dtype=torch.float32, device="cuda")
     xm, ym, zm = 0x0092492, 0x1124924, 0x2249249          # X, Y, Z on every third qubit each
@@ -150,8 +154,11 @@ def bench_c4(torch, qb, wl, args):
     return res, w
 
 
-def bench_c3(torch, qb, wl, args):
-    w = wl.config(3)
+def bench_c3(torch, qb, wl, args, batch=None):
+    """batch = None: config 3 as given (32 samples, 256 MiB of state: as large as the chip's memory-side
+    cache, so part of every pass is served from it).  A larger batch is the same circuit on a state the
+    cache cannot hold (supplementary: shows the pass kernel's rate against HBM alone)."""
+    w = wl.config(3) if batch is None else wl.config(3, batch=batch)
     n, B = w.n, w.batch
     ctx = qb.Context(n, B)
     if args.tile:
@@ -196,20 +203,26 @@ def bench_c3(torch, qb, wl, args):
     apply_ms = tm.total_ms("apply") / args.steps
     updates = 2 * wl.nominal_updates(w.circuit, n, B)
     state_bytes = 8 * B * (1 << n)
-    # the same autoencoder with a true reset of the trash qubits: 16 decoder runs per sample
-    ctx.qsv_amp_encode(xd)
-    ctx.qsv_apply_layers(circ, pd, None, 0)
+    extra = {}
+    if batch is None:
+        # the same autoencoder with a true reset of the trash qubits: 16 decoder runs per sample
+        ctx.qsv_amp_encode(xd)
+        ctx.qsv_apply_layers(circ, pd, None, 0)
 
-    def reset_step(tm):
-        ctx.qsv_reset_fidelity(circ, pd, None, w.trash_mask, xd, fid)
+        def reset_step(tm):
+            ctx.qsv_reset_fidelity(circ, pd, None, w.trash_mask, xd, fid)
 
-    reset_ms, _ = run_steps(torch, reset_step, 3, 1)
-    reset_updates = 16 * wl.nominal_updates(w.circuit, n, B)
+        reset_ms, _ = run_steps(torch, reset_step, 3, 1)
+        reset_updates = 16 * wl.nominal_updates(w.circuit, n, B)
+        extra["true_reset"] = {"what": "qsv_reset_fidelity: sum over the 16 trash outcomes, 16 decoder runs per sample",
+                               "ms": reset_ms, "updates": reset_updates,
+                               "updates_per_s": reset_updates / (reset_ms * 1e-3)}
+    else:
+        extra["note"] = ("supplementary, not one of the five configs: config 3's circuit at batch %d, %d MiB of "
+                         "state, which the 256 MiB memory-side cache cannot hold" % (B, state_bytes >> 20))
     ctx.close()
-    return {
-        "true_reset": {"what": "qsv_reset_fidelity: sum over the 16 trash outcomes, 16 decoder runs per sample",
-                       "ms": reset_ms, "updates": reset_updates, "updates_per_s": reset_updates / (reset_ms * 1e-3)},
-        "workload": "c3: 20 qubits, batch 32, 20-layer encoder + trash projection + decoder + fidelity",
+    return dict(extra, **{
+        "workload": "c3: 20 qubits, batch %d, 20-layer encoder + trash projection + decoder + fidelity" % B,
         "ms_per_step": ms, "apply_ms": apply_ms, "passes": passes, "updates": updates,
         "updates_per_s": updates / (ms * 1e-3), "apply_updates_per_s": updates / (apply_ms * 1e-3),
         # states of two rows or more go through a pass as two launches (halves of the rows) side by
@@ -218,7 +231,11 @@ def bench_c3(torch, qb, wl, args):
         "pass_avg_ms": apply_ms / passes, "pass_bytes": 2 * state_bytes,
         "pass_gbs": 2 * state_bytes / (apply_ms / passes * 1e-3) / 1e9,
         "pass_hbm_frac": 2 * state_bytes / (apply_ms / passes * 1e-3) / 1e9 / HBM_PEAK_GBS,
-    }
+        "state_mib": state_bytes >> 20,
+        "memory_side_cache": "state <= 256 MiB: passes are partly served by the memory-side cache, the figure is "
+                             "bandwidth between L2 and the fabric, not HBM alone" if state_bytes <= (256 << 20)
+                             else "state larger than the 256 MiB memory-side cache: HBM bandwidth",
+    })
 
 
 def bench_c2(torch, qb, wl, args):
@@ -468,7 +485,18 @@ def main():
         sys.exit(2)
     if 3 in which and w4 is not None:
         others["c3"] = bench_c3(torch, qb, wl, args)
+        others["c3_batch128"] = bench_c3(torch, qb, wl, args, batch=128)
         others["c3_train"] = bench_train(torch, qb, wl, args, 3)
+    if w4 is not None and args.defer != 0 and not args.no_classic:
+        # config 4 with every CNOT a register operation (the plan without deferral): more, lighter passes
+        cargs = argparse.Namespace(**vars(args))
+        cargs.defer, cargs.steps, cargs.warmup = 0, 5, 1
+        c4c, _ = bench_c4(torch, qb, wl, cargs, apply_only=True)
+        others["c4_no_deferral"] = {k: c4c[k] for k in ("apply_ms", "passes", "apply_updates_per_s", "pass_avg_ms",
+                                                        "pass_gbs")}
+        others["c4_no_deferral"]["pass_hbm_frac"] = c4c["pass_gbs"] / HBM_PEAK_GBS
+        others["c4_no_deferral"]["what"] = ("config 4's 30 layers with defer_cnots = 0: every CNOT in registers, "
+                                            "more and lighter passes over the state")
     if 2 in which:
         others["c2"] = bench_c2(torch, qb, wl, args)
     if 1 in which:
@@ -489,6 +517,9 @@ def main():
         "roofline": {"bound": "hbm", "kernel": "k_pass (fused gate pass)", "achieved": head["pass_gbs"],
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": head["pass_gbs"] / HBM_PEAK_GBS,
                      "traffic": TRAFFIC_BYTES_PER_LAUNCH.get(head["workload"][:2]),
+                     "traffic_source": "rocprofv3 FETCH_SIZE / WRITE_SIZE of an earlier run of this command, scaled by "
+                                       "a load/store-only pass of known size (profiles/k_pass_hbm_traffic_counters.md); "
+                                       "not re-measured in this run",
                      "bytes_per_launch": head["pass_bytes"], "avg_launch_ms": head["pass_avg_ms"],
                      "launches_per_pass": head.get("launches_per_pass", 1)},
         "cpu_baseline": cpu,

@@ -936,14 +936,14 @@ qsv_status qsv_param_shift_grad(qsv_ctx* ctx, const qsv_circuit* c, const float*
         one.n_layers = 1;
         // unshifted circuit, one layer at a time: ck(l) = state of every sample before layer l
         QSV_HIP(ctx, launch_encode_write(x_dev, dim, n, B, inv, plain_rows(n), ck(0), ctx->stream), "encode");
+        RowMap rm_fwd;    // rows are the samples: the first pass of layer l reads state l and writes state l + 1
+        rm_fwd.grad = 1; rm_fwd.two_p = 0; rm_fwd.per = 1; rm_fwd.row0 = 0;
+        rm_fwd.slots_n = slots_n < 1 ? 1 : slots_n; rm_fwd.n = n;
         for (int l = 0; l < L; ++l) {
-            QSV_HIP(ctx, hipMemcpyAsync(ck(l + 1), ck(l), (size_t)B * state_bytes, hipMemcpyDeviceToDevice,
-                                        ctx->stream),
-                    "copy checkpoint");
             Prepared pr;
             st = prepare_circuit(ctx, one, B, 0, 0, params_dev + (size_t)l * slots_n, feats_dev, B, mats, &pr);
             if (st != QSV_OK) return st;
-            st = run_circuit(ctx, one, pr, ck(l + 1), B, 0, nullptr, plain_rows(n));
+            st = run_circuit(ctx, one, pr, ck(l + 1), B, 0, nullptr, rm_fwd, ck(l));
             if (st != QSV_OK) return st;
         }
         QSV_HIP(ctx, launch_expz_block(ck(L), B, n, zpart, ctx->stream), "expz block");

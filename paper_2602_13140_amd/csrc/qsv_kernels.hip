@@ -957,22 +957,41 @@ __global__ __launch_bounds__(256) void k_project(float2* state, u64 total, int n
 }
 
 // Pauli string: T = sum_k conj(a[k ^ f]) (-1)^popcount(k & s) a[k], f = X and Y bits, s = Y and Z
-// bits; <P> = Re(i^nY T).  One block per 4096 amplitudes and row; partial: [row][blk][2].
-__global__ __launch_bounds__(256) void k_pauli_block(const float2* state, u64 rows, int n, u64 f, u64 s, int nblk,
-                                                     double* partial) {
+// bits; <P> = Re(i^nY T).  The terms of k and k ^ f are conjugates of each other up to the sign
+// (-1)^nY, so for f != 0 only the k whose highest flip bit is clear are visited, each amplitude is
+// read once, and a pair adds 2 Re t (nY even) or 2 i Im t (nY odd) with t = conj(a[k ^ f]) sign(k) a[k].
+// One block per 4096 visited indices and row; partial: [row][blk][2].
+__global__ __launch_bounds__(256) void k_pauli_block(const float2* state, u64 rows, int n, u64 f, u64 s, int ny,
+                                                     int nblk, double* partial) {
     __shared__ double sm[4];
-    const u64 row = grid_row(), N = 1ull << n;
+    const u64 row = grid_row();
     if (row >= rows) return;
     const float2* a = state + (row << n);
     float tr = 0.f, ti = 0.f;
+    if (f == 0) {
+        const u64 N = 1ull << n;
 #pragma unroll
-    for (int i = 0; i < 16; ++i) {
-        const u64 k = (u64)blockIdx.x * CHUNK + (u64)i * 256 + threadIdx.x;
-        if (k < N) {
-            const float2 v = a[k], u = a[k ^ f];
-            float cr = u.x * v.x + u.y * v.y, ci = u.x * v.y - u.y * v.x;   // conj(u) v
-            if (__popcll(k & s) & 1) { cr = -cr; ci = -ci; }
-            tr += cr; ti += ci;
+        for (int i = 0; i < 16; ++i) {
+            const u64 k = (u64)blockIdx.x * CHUNK + (u64)i * 256 + threadIdx.x;
+            if (k < N) {
+                const float2 v = a[k];
+                const float p = v.x * v.x + v.y * v.y;
+                tr += (__popcll(k & s) & 1) ? -p : p;
+            }
+        }
+    } else {
+        const int hb = 63 - __clzll(f);               // pairs differ in this bit (and the lower bits of f)
+        const u64 half = 1ull << (n - 1), low = (1ull << hb) - 1ull;
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+            const u64 j = (u64)blockIdx.x * CHUNK + (u64)i * 256 + threadIdx.x;
+            if (j < half) {
+                const u64 k = ((j & ~low) << 1) | (j & low);        // bit hb clear
+                const float2 v = a[k], u = a[k ^ f];
+                float cr = u.x * v.x + u.y * v.y, ci = u.x * v.y - u.y * v.x;   // conj(u) v
+                if (__popcll(k & s) & 1) { cr = -cr; ci = -ci; }
+                if (ny & 1) ti += 2.f * ci; else tr += 2.f * cr;
+            }
         }
     }
     const double t0 = block_sum256((double)tr, sm);
@@ -1108,10 +1127,20 @@ __global__ __launch_bounds__(256) void k_sample_blocksum(const float2* state, u6
     const u64 dimn = 1ull << n;
     const float2* a = state + (row << n);
     u64 acc = 0;
+    if (dimn >= 2) {
+        // two amplitudes per 16-byte load; integer sums do not care about the order
+        const float4* a2 = reinterpret_cast<const float4*>(a);
+        float4 v[8];
 #pragma unroll
-    for (int i = 0; i < 16; ++i) {
-        const u64 k = (u64)blockIdx.x * CHUNK + (u64)i * 256 + threadIdx.x;
-        if (k < dimn) acc += weight60(a[k]);
+        for (int i = 0; i < 8; ++i) {
+            const u64 k2 = (u64)blockIdx.x * (CHUNK / 2) + (u64)i * 256 + threadIdx.x;
+            v[i] = k2 * 2 < dimn ? a2[k2] : make_float4(0.f, 0.f, 0.f, 0.f);
+        }
+#pragma unroll
+        for (int i = 0; i < 8; ++i)
+            acc += weight60(make_float2(v[i].x, v[i].y)) + weight60(make_float2(v[i].z, v[i].w));
+    } else if (blockIdx.x == 0 && threadIdx.x == 0) {
+        acc = weight60(a[0]);
     }
     acc = wave_sum_u64(acc);
     if ((threadIdx.x & 63) == 0) sm[threadIdx.x >> 6] = acc;
@@ -1931,9 +1960,10 @@ hipError_t launch_shot_expz(const long long* samples, int64_t shots, int64_t row
 
 hipError_t launch_pauli(const float2* state, int64_t rows, int n, uint64_t xmask, uint64_t ymask,
                         uint64_t zmask, double* partial, float* out, hipStream_t st) {
-    const int nblk = chunk_blocks(n);
+    const u64 f = (u64)(xmask | ymask);
+    const int nblk = chunk_blocks(f ? n - 1 : n);    // with flips, half the indices are visited
     hipLaunchKernelGGL(k_pauli_block, rows_grid(nblk, (u64)rows), dim3(256), 0, st, state, (u64)rows, n,
-                       (u64)(xmask | ymask), (u64)(ymask | zmask), nblk, partial);
+                       f, (u64)(ymask | zmask), __builtin_popcountll(ymask), nblk, partial);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL(k_pauli_finish, dim3((unsigned)rows), dim3(256), 0, st, partial, nblk,

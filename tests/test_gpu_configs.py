@@ -82,6 +82,61 @@ def test_config2_gradient_sampled(oracle, rot, layered):
     ctx.close()
 
 
+def test_config2_gradient_wide(oracle, capsys):
+    """Config 2 at full size through all three entry points (shift rule layer by layer, shift rule with
+    whole circuits, reverse mode): every one of the 256 x 320 entries must agree between them, and the
+    oracle recomputes all 320 parameters for two samples (the first and one from the last chunk of
+    rows) and 8 seeded parameters for all 256 samples, so every chunk boundary of the full-size
+    launches is covered."""
+    torch = gu.torch_cuda()
+    w = wl.config(2)
+    spec = w.circuit
+    P = spec.num_params(w.n)
+    params = wl.draw_params(spec, w.n, 2002)
+    circ = qb.circuit_from_spec(spec)
+    xd, pd = gu.dev(w.x), gu.dev(params)
+    got = {}
+    for name in ("layered", "whole", "adjoint"):
+        ctx = gu.make_ctx(w.n, w.batch,
+                          ws_bytes=None if name == "whole" else qb.qsv_grad_workspace_bytes(w.n, w.batch, circ))
+        loss = torch.zeros(w.batch, dtype=torch.float32, device="cuda")
+        grad = torch.zeros((w.batch, P), dtype=torch.float32, device="cuda")
+        (ctx.qsv_adjoint_grad if name == "adjoint" else ctx.qsv_param_shift_grad)(circ, xd, pd, None, 0, loss, grad)
+        torch.cuda.synchronize()
+        got[name] = (loss.cpu().numpy().astype(np.float64), grad.cpu().numpy().astype(np.float64))
+        ctx.close()
+        with capsys.disabled():
+            print(" [c2 %s done]" % name, end="", flush=True)
+    l0, g0 = got["layered"]
+    for name in ("whole", "adjoint"):
+        l1, g1 = got[name]
+        assert np.abs(l1 - l0).max() <= 1e-5, name
+        assert np.abs(g1 - g0).max() <= 1e-4, name
+        assert np.linalg.norm(g1 - g0) <= 1e-3 * np.linalg.norm(g0), name
+    oc = ocirc(oracle, spec)
+    g = np.random.Generator(np.random.PCG64(77))
+    rows = [0, int(g.integers(w.batch - 16, w.batch))]
+    lref, gref = oracle.param_shift_grad(w.x[rows], w.n, oc, params, None, 0)
+    with capsys.disabled():
+        print(" [c2 oracle: all parameters of 2 samples]", end="", flush=True)
+    # <Z_0> behind a CZ ladder only sees the parameters inside qubit 0's light cone; the others have
+    # gradient zero (the oracle returns 1e-17).  Six seeded parameters from inside it, two from outside.
+    live = np.flatnonzero(np.abs(gref).max(0) > 1e-4)
+    dead = np.flatnonzero(np.abs(gref).max(0) < 1e-12)
+    assert live.size >= 6 and dead.size >= 2
+    sub = sorted(g.choice(live, 6, replace=False).tolist() + g.choice(dead, 2, replace=False).tolist())
+    lall, gall = oracle.param_shift_grad(w.x, w.n, oc, params, None, 0, subset=sub)
+    with capsys.disabled():
+        print(" [c2 oracle: 8 parameters of all samples]", end="", flush=True)
+    for name, (ll, gg) in got.items():
+        assert np.abs(ll[rows] - lref).max() <= 1e-5, name
+        assert np.abs(gg[rows] - gref).max() <= 1e-4, name
+        assert np.linalg.norm(gg[rows] - gref) <= 1e-3 * np.linalg.norm(gref), name
+        assert np.abs(ll - lall).max() <= 1e-5, name
+        assert np.abs(gg[:, sub] - gall).max() <= 1e-4, name
+        assert np.linalg.norm(gg[:, sub] - gall) <= 1e-3 * np.linalg.norm(gall), name
+
+
 def test_config3_autoencoder_full(oracle, capsys):
     w = wl.config(3)
     n, B = w.n, w.batch
@@ -140,6 +195,14 @@ def test_config4_full(oracle, capsys):
     gu.prob_checks(p32, pref)
     d = np.abs(gu.state_np(ctx) - ref)
     assert d.max() <= 1e-5 and (d ** 2).sum() <= 1e-9
+    # the same circuit with every CNOT a register operation (the default defers those whose target
+    # lies outside a pass's tile): the other plan, the same state
+    ctx.qsv_set_option("defer_cnots", 0)
+    ctx.qsv_amp_encode(xd)
+    ctx.qsv_apply_layers(circ, pd, None, 0)
+    d = np.abs(gu.state_np(ctx) - ref)
+    assert d.max() <= 1e-5 and (d ** 2).sum() <= 1e-9
+    ctx.qsv_set_option("defer_cnots", -1)
     del ref, pref, d
     # the inverse brings the state back to the encoded input
     ctx.qsv_apply_layers(circ, pd, None, 1)
