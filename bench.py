@@ -39,6 +39,7 @@ def parse_args():
     ap.add_argument("--defer", type=int, default=-1,
                     help="qsv_apply_layers defers CNOTs whose target lies outside a pass's tile (1), keeps every CNOT in "
                          "registers (0), or decides itself (-1, the default: it defers when it can)")
+    ap.add_argument("--prio", type=int, default=-1, help="load_store_priority option of the pass kernel (0 or 1)")
     ap.add_argument("--low", type=int, default=0, help="force the planner's minimum number of low index bits per tile")
     ap.add_argument("--planes", type=int, default=0, help="force the pass kernel's LDS planes (1 or 2; 0 = default)")
     ap.add_argument("--nt", type=int, default=-1, help="force nontemporal tile stores (1) or ordinary ones (0)")
@@ -99,6 +100,8 @@ def bench_c4(torch, qb, wl, args, apply_only=False):
         ctx.qsv_set_option("tile_log2", args.tile)
     if args.defer >= 0:
         ctx.qsv_set_option("defer_cnots", args.defer)
+    if args.prio >= 0:
+        ctx.qsv_set_option("load_store_priority", args.prio)
     if args.low:
         ctx.qsv_set_option("low_bits", args.low)
     if args.planes:
@@ -165,6 +168,8 @@ def bench_c3(torch, qb, wl, args, batch=None):
         ctx.qsv_set_option("tile_log2", args.tile)
     if args.defer >= 0:
         ctx.qsv_set_option("defer_cnots", args.defer)
+    if args.prio >= 0:
+        ctx.qsv_set_option("load_store_priority", args.prio)
     if args.low:
         ctx.qsv_set_option("low_bits", args.low)
     if args.planes:
@@ -250,6 +255,8 @@ def bench_c2(torch, qb, wl, args):
         ctx.qsv_set_option("tile_log2", args.tile)
     if args.defer >= 0:
         ctx.qsv_set_option("defer_cnots", args.defer)
+    if args.prio >= 0:
+        ctx.qsv_set_option("load_store_priority", args.prio)
     if args.low:
         ctx.qsv_set_option("low_bits", args.low)
     if args.planes:
@@ -321,6 +328,8 @@ def bench_c1(torch, qb, wl, args):
         ctx.qsv_set_option("tile_log2", args.tile)
     if args.defer >= 0:
         ctx.qsv_set_option("defer_cnots", args.defer)
+    if args.prio >= 0:
+        ctx.qsv_set_option("load_store_priority", args.prio)
     if args.planes:
         ctx.qsv_set_option("lds_planes", args.planes)
     circ = qb.circuit_from_spec(w.circuit)
@@ -413,6 +422,8 @@ def probe(torch, qb, args):
         ctx.qsv_set_option("tile_log2", args.tile)
     if args.defer >= 0:
         ctx.qsv_set_option("defer_cnots", args.defer)
+    if args.prio >= 0:
+        ctx.qsv_set_option("load_store_priority", args.prio)
     if args.nt >= 0:
         ctx.qsv_set_option("nt_store", args.nt)
     if args.rev >= 0:

@@ -74,6 +74,7 @@ struct qsv_ctx {
     int opt_probe_layout = -1;  // probe pass: register run of the load and the store (-1: the highest)
     int64_t opt_grad_chunk = 0;
     int opt_split = -1;      // state rows of a launch sequence in two halves on two streams; -1: by state size
+    int opt_prio = 1;        // raised issue priority around a tile's loads and stores (measured: 2 % off configs 3 and 4)
     int opt_defer = -1;      // qsv_apply_layers defers CNOTs whose target lies outside a pass's tile; -1: when it can
     hipStream_t side = nullptr;          // second stream for that (default priority, non-blocking)
     hipEvent_t ev_fork = nullptr, ev_join = nullptr;
@@ -431,6 +432,7 @@ qsv_status run_circuit(qsv_ctx* ctx, const qsv_circuit& c, const Prepared& pr, f
         // Every other pass walks the tiles downwards, so that it starts with what the pass before
         // wrote last and may still find in the memory-side cache (256 MiB).
         a.rev = (ctx->opt_rev >= 0 ? ctx->opt_rev : (state_bytes >= kNtStoreBytes ? 1 : 0)) ? (int)(pi & 1) : 0;
+        a.prio = ctx->opt_prio;
         a.n = n; a.c = ps.c; a.w = ps.w;
         a.n_mats = n_mats;
         a.rowdep = c.reupload;
@@ -601,6 +603,11 @@ qsv_status qsv_set_option(qsv_ctx* ctx, const char* name, int64_t value) {
         ctx->opt_split = (int)value;
         return QSV_OK;
     }
+    if (!strcmp(name, "load_store_priority")) {
+        if (value < 0 || value > 1) return fail(ctx, QSV_ERR_INVALID_ARG, "load_store_priority must be 0 or 1");
+        ctx->opt_prio = (int)value;
+        return QSV_OK;
+    }
     if (!strcmp(name, "defer_cnots")) {
         if (value < -1 || value > 1) return fail(ctx, QSV_ERR_INVALID_ARG, "defer_cnots must be -1, 0 or 1");
         ctx->opt_defer = (int)value;
@@ -640,6 +647,11 @@ qsv_status qsv_amp_encode(qsv_ctx* ctx, const float* x_dev, int64_t dim, float* 
     double* partial = (double*)ar.take((size_t)ctx->batch * nblk * 8);
     double* inv = (double*)ar.take((size_t)ctx->batch * 8);
     if (!partial || !inv) return ws_fail(ctx, ar, "qsv_amp_encode");
+    if (dim <= 4096 && ctx->n <= 12) {     // a block covers a sample: one launch
+        QSV_HIP(ctx, launch_encode_small(x_dev, ctx->batch, dim, ctx->n, inv, norm_out_dev, ctx->state, ctx->stream),
+                "encode");
+        return QSV_OK;
+    }
     QSV_HIP(ctx, launch_norms(x_dev, ctx->batch, dim, partial, nblk, inv, norm_out_dev, ctx->stream), "norms");
     QSV_HIP(ctx, launch_encode_write(x_dev, dim, ctx->n, ctx->batch, inv, plain_rows(ctx->n), ctx->state,
                                      ctx->stream),
@@ -1293,6 +1305,7 @@ qsv_status qsv_probe_pass(qsv_ctx* ctx, int low_bits, int window_start, int tran
     a.exec_of = nullptr;
     a.ovr = nullptr;
     a.total = (uint64_t)ctx->batch << n;
+    a.prio = ctx->opt_prio;
     a.n = n; a.c = low_bits; a.w = window_start;
     a.n_mats = 0;
     a.rowdep = 0;

@@ -43,6 +43,8 @@ struct PassArgs {
     int nostore;         // with zout: the state is not written back
     int nt_store;        // nontemporal tile stores (states much larger than the last-level cache)
     int rev;             // workgroups take the tiles in descending order (see run_circuit)
+    int prio;            // wavefronts raise their issue priority while they compute addresses and issue the
+                         // tile's loads, and again for its stores (the gates run at the base priority)
     const float* mats;   // [samples if rowdep][n_mats][8], matrices in execution order
     const int* exec_of;  // [n_mats]: (layer * n + qubit) -> execution-order index
     const float* ovr;    // gradient: [samples if rowdep][2P][8] shifted matrices
@@ -88,6 +90,9 @@ hipError_t launch_build_shifted(const CircDev& c, const float* params, const flo
 // encoding
 hipError_t launch_norms(const float* x, int64_t samples, int64_t dim, double* partial, int nblk,
                         double* inv_norm, float* norm_out, hipStream_t st);
+// norm and state rows of small samples (dim <= 4096, n <= 12) in one launch; inv_norm receives 1/||x_b||
+hipError_t launch_encode_small(const float* x, int64_t samples, int64_t dim, int n, double* inv_norm, float* norm_out,
+                               float2* state, hipStream_t st);
 hipError_t launch_encode_write(const float* x, int64_t dim, int n, int64_t rows, const double* inv_norm,
                                const RowMap& rm, float2* state, hipStream_t st);
 

@@ -195,6 +195,9 @@ void k_pass(const PassArgs a) {
     // after the other through a single plane, which halves the LDS a workgroup holds); see the
     // interpreter's generator.  The segment must start at LDS byte 0 (no static LDS here).
     extern __shared__ float lds[];
+    // A workgroup that has just started shares its SIMDs with up to seven older ones in the middle of
+    // their gates; the sooner its loads are on their way, the more of their latency those gates hide.
+    if (a.prio) __builtin_amdgcn_s_setprio(3);
     constexpr unsigned PLANE = 1u << T;
     static_assert(PLANES == 1 || (PLANE * 4u < 65536u && PLANE / 64u < 256u),
                   "with two planes the second plane is reached through the LDS offset fields");
@@ -275,6 +278,7 @@ void k_pass(const PassArgs a) {
 #undef QSV_LD
     }
     { const u64 nx = (u64)(uintptr_t)a.ops + 8; opslo = to_sgpr((unsigned)nx); opshi = to_sgpr((unsigned)(nx >> 32)); }
+    if (a.prio) __builtin_amdgcn_s_setprio(0);
     unsigned e0lo = (unsigned)e0, e0hi = (unsigned)(e0 >> 32);
     unsigned ldsb = (tau0 ^ ((tau0 >> 4) & 31u)) * 4u;
 
@@ -369,6 +373,7 @@ void k_pass(const PassArgs a) {
         if ((thr & 63u) == 0) a.zout[tb * (blockDim.x >> 6) + (thr >> 6)] = tot;
         if (a.nostore) return;
     }
+    if (a.prio) __builtin_amdgcn_s_setprio(3);
     if (a.imap) {
         // Deferred CNOTs: every amplitude goes to the index its position maps to.  The map is linear
         // over XOR, so the destination is (tile's part) ^ (lane's part) ^ (register element's part);
@@ -762,6 +767,28 @@ __global__ __launch_bounds__(256) void k_encode_write(const float* x, u64 dim, i
     o.z = (k + 1) < dim ? (float)((double)xb[k + 1] * inv) : 0.f;
     o.w = 0.f;
     *reinterpret_cast<float4*>(state + e2) = o;
+}
+
+// Small samples (one block covers a sample): norm and state row in one launch.  Same arithmetic as
+// k_sumsq + k_encode_write, so the bits are the same.
+__global__ __launch_bounds__(256) void k_encode_small(const float* x, u64 rows, u64 dim, int n, double* inv_norm,
+                                                      float* norm_out, float2* state) {
+    __shared__ double sm[4];
+    const u64 b = grid_row();
+    if (b >= rows) return;
+    const float* xb = x + b * dim;
+    double acc = 0.0;
+    for (u64 k = threadIdx.x; k < dim; k += 256) { const double v = (double)xb[k]; acc += v * v; }
+    const double tot = block_sum256(acc, sm);
+    const double nrm = sqrt(tot);
+    const double inv = nrm > 0.0 ? 1.0 / nrm : 0.0;
+    if (threadIdx.x == 0) {
+        inv_norm[b] = inv;
+        if (norm_out) norm_out[b] = (float)nrm;
+    }
+    float2* row = state + (b << n);
+    for (u64 k = threadIdx.x; k < (1ull << n); k += 256)
+        row[k] = make_float2(k < dim ? (float)((double)xb[k] * inv) : 0.f, 0.f);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -1839,6 +1866,14 @@ hipError_t launch_norms(const float* x, int64_t samples, int64_t dim, double* pa
     if (e != hipSuccess || one) return e;
     hipLaunchKernelGGL(k_norm_finish, dim3((unsigned)samples), dim3(256), 0, st, partial, nblk,
                        inv_norm, norm_out);
+    return hipGetLastError();
+}
+
+hipError_t launch_encode_small(const float* x, int64_t samples, int64_t dim, int n, double* inv_norm, float* norm_out,
+                               float2* state, hipStream_t st) {
+    if (dim > 4096 || n > 12) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(k_encode_small, rows_grid(1, (u64)samples), dim3(256), 0, st, x, (u64)samples, (u64)dim, n,
+                       inv_norm, norm_out, state);
     return hipGetLastError();
 }
 
