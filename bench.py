@@ -52,6 +52,9 @@ def parse_args():
                     help="probe pass: moves of the register run through LDS between the tile's load and its store")
     ap.add_argument("--probe-layout", type=int, default=-1,
                     help="probe pass: start of the register run the tile is loaded and stored in (-1 = highest)")
+    ap.add_argument("--c3-batch", type=int, default=0,
+                    help="with --configs 3 alone: run config 3's circuit at this batch instead of 32 (128 = 1 GiB of "
+                         "state, beyond the memory-side cache)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
     ap.add_argument("--no-classic", action="store_true", help="skip the extra run of config 4 without deferred CNOTs")
     ap.add_argument("--cpu-layers", type=int, default=20, help="layers of config 4 the oracle is timed on")
@@ -490,7 +493,7 @@ def main():
     if 4 in which or not which:
         head, w4 = bench_c4(torch, qb, wl, args)
     elif which[0] == 3:
-        head = bench_c3(torch, qb, wl, args)     # profiling aid: config 3 as the only workload
+        head = bench_c3(torch, qb, wl, args, batch=args.c3_batch or None)   # profiling aid: config 3 as the only workload
     else:
         print("bench.py: --configs must include 4 (the headline) or start with 3", file=sys.stderr)
         sys.exit(2)

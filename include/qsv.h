@@ -262,7 +262,8 @@ qsv_status qsv_probe_pass(qsv_ctx* ctx, int low_bits, int window_start, int tran
  * (fewer passes over the state; such passes write a second buffer taken from the workspace), or keeps
  * every CNOT a register operation (-1, the default, defers whenever the circuit has a CNOT ring, more
  * qubits than the tile has index bits, at most 28 of them, and the workspace has room for a copy of
- * the state; the result is the same up to rounding order); low_bits in 4..10 (0 = default) forces the planner's minimum number of low index bits
+ * the state; the result is the same up to rounding order); load_store_priority = 1 (default) / 0 makes
+ * the pass kernel's wavefronts raise their issue priority while they issue a tile's loads and stores; low_bits in 4..10 (0 = default) forces the planner's minimum number of low index bits
  * per tile; lds_planes = 1 (default) moves real and imaginary parts through one LDS plane one
  * after the other, 2 through two planes at once; naive = 1 routes qsv_apply_layers through the
  * one-gate-per-launch kernels; grad_layered = 0 makes qsv_param_shift_grad run every shifted

@@ -61,8 +61,8 @@ def apply_index_map(st, n, imap):
     dest = np.zeros(1 << n, dtype=np.int64)
     for j in range(n):
         assert (imap[j] >> j) & 1                    # a position bit always maps onto itself as well
-        if j < 4:
-            assert imap[j] == 1 << j                 # 128-byte lines are written whole
+        if j < 3:
+            assert imap[j] == 1 << j                 # runs of 64 bytes are written whole
         dest ^= np.where((k >> j) & 1, imap[j], 0)
     assert len(np.unique(dest)) == 1 << n            # a permutation
     out = np.empty_like(st)
@@ -184,7 +184,7 @@ def replay(text, n, rows, L, rot, ent, reupload, params, feats, inverse, st):
                 # deferred CNOT: target outside the tile, carried by the map; nothing moves now
                 qt, qc, mask = tok[1:].split(":")
                 qt, qc, mask = int(qt), int(qc), int(mask, 16)
-                assert qt not in local_bits and qt < n and not (mask & 15) and not (mask >> qt) & 1
+                assert qt not in local_bits and qt < n and not (mask & 7) and not (mask >> qt) & 1
                 n_gates += 1
             elif kind == "M":
                 st = apply_index_map(st, n, [int(x, 16) for x in tok[1:].split(",")])
