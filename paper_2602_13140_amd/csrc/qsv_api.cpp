@@ -577,8 +577,8 @@ qsv_status qsv_set_option(qsv_ctx* ctx, const char* name, int64_t value) {
         return QSV_OK;
     }
     if (!strcmp(name, "low_bits")) {
-        if (value != 0 && (value < kLowBits || value > kMinTile))
-            return fail(ctx, QSV_ERR_INVALID_ARG, "low_bits must be 0 or in 4..10");
+        if (value != 0 && (value < 3 || value > kMinTile))
+            return fail(ctx, QSV_ERR_INVALID_ARG, "low_bits must be 0 or in 3..10");
         ctx->opt_low = (int)value;
         return QSV_OK;
     }

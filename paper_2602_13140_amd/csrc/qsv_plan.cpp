@@ -474,7 +474,8 @@ Plan build_plan(const qsv_circuit& c, int n, int64_t batch, bool inverse, int ti
     const std::vector<Gate> G = lower(c, n, inverse);
     std::vector<uint8_t> done(G.size(), 0);
     size_t first = 0;
-    const int cmin = std::min(std::max(kLowBits, min_low_bits), t);
+    // fewest low bits of a tile: kLowBits unless the caller asks for another number (3 = 64-byte runs)
+    const int cmin = std::min(min_low_bits > 0 ? std::max(3, min_low_bits) : kLowBits, t);
     // local set = low c bits + window of t-c bits at w; c >= 4 keeps 128-byte runs contiguous
     auto all_geoms = [&](auto&& fn) {
         for (int cl = cmin; cl <= t; ++cl) {

@@ -90,7 +90,7 @@ def replay(text, n, rows, L, rot, ent, reupload, params, feats, inverse, st):
     n_gates = 0
     for hdr, ops in passes:
         t, c, w = hdr["t"], hdr["c"], hdr["w"]
-        assert 10 <= t <= 14 and 4 <= c <= t and w >= c
+        assert 10 <= t <= 14 and 3 <= c <= t and w >= c
         bit = lambda pos: pos if pos < c else pos - c + w
         if n > t:
             assert w + (t - c) <= n
