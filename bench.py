@@ -26,7 +26,7 @@ HBM_PEAK_GBS = 8000.0
 # HBM bytes per pass (config 3: a pair of launches) from rocprofv3 FETCH_SIZE / WRITE_SIZE, each scaled by what the same
 # counter reads for the load/store-only probe pass of known size (FETCH_SIZE x 2.000, WRITE_SIZE x
 # 1.000); the runs and their figures are in profiles/k_pass_hbm_traffic_counters.md.
-TRAFFIC_BYTES_PER_LAUNCH = {"c4": 1074641004, "c3": 537407134}
+TRAFFIC_BYTES_PER_LAUNCH = {"c4": 1073995377, "c3": 537499121}
 
 
 def parse_args():
@@ -142,6 +142,7 @@ def bench_c4(torch, qb, wl, args, apply_only=False):
         "updates_per_s": updates / (ms * 1e-3), "apply_updates_per_s": updates / (apply_ms * 1e-3),
         "pass_avg_ms": apply_ms / passes, "pass_bytes": 2 * state_bytes,
         "pass_gbs": 2 * state_bytes / (apply_ms / passes * 1e-3) / 1e9,
+        "unitary_flops": 13.0 * w.circuit.n_layers * n * (1 << n),
     }
     if apply_only:
         ctx.close()
@@ -471,6 +472,14 @@ def cpu_baseline(wl, w4, layers):
                       "layers (%d gates), %.1f s" % (layers, layers * spec.gates_per_layer(w4.n), dt)}
 
 
+def alu_view(head):
+    if "unitary_flops" not in head:
+        return None
+    tf = head["unitary_flops"] / (head["apply_ms"] * 1e-3) / 1e12
+    return {"achieved": tf, "peak": 157.3, "unit": "TFLOP/s", "frac": tf / 157.3,
+            "note": "fp32 vector peak of the data sheet (reached with packed instructions only, which this build does not use)"}
+
+
 def main():
     args = parse_args()
     if args.gpus != 1:
@@ -535,7 +544,10 @@ def main():
                                        "a load/store-only pass of known size (profiles/k_pass_hbm_traffic_counters.md); "
                                        "not re-measured in this run",
                      "bytes_per_launch": head["pass_bytes"], "avg_launch_ms": head["pass_avg_ms"],
-                     "launches_per_pass": head.get("launches_per_pass", 1)},
+                     "launches_per_pass": head.get("launches_per_pass", 1),
+                     # the same launches against the vector-ALU roofline: a fused unitary is 26 flops per amplitude
+                     # pair (2 multiplies + 12 FMAs), CNOTs and transposes move data and count nothing
+                     "alu_view": alu_view(head)},
         "cpu_baseline": cpu,
         "others": dict(others, **{k: head[k] for k in ("pauli_string", "true_reset") if k in head}),
     }
