@@ -509,6 +509,10 @@ def main():
     if 3 in which and w4 is not None:
         others["c3"] = bench_c3(torch, qb, wl, args)
         others["c3_batch128"] = bench_c3(torch, qb, wl, args, batch=128)
+        if args.defer != 0 and not args.no_classic:
+            cargs = argparse.Namespace(**vars(args))
+            cargs.defer, cargs.steps, cargs.warmup = 0, 5, 1
+            others["c3_batch128_no_deferral"] = bench_c3(torch, qb, wl, cargs, batch=128)
         others["c3_train"] = bench_train(torch, qb, wl, args, 3)
     if w4 is not None and args.defer != 0 and not args.no_classic:
         # config 4 with every CNOT a register operation (the plan without deferral): more, lighter passes

@@ -76,7 +76,8 @@ typedef struct {
 int64_t qsv_num_params(const qsv_circuit* c, int n_qubits);
 
 /* Workspace size in bytes that is enough for every call below at (n_qubits, batch) with up to
- * 64 layers.  Returns 0 for n_qubits outside 1..30 or batch < 1.  A larger workspace lets
+ * 64 layers, a copy of the state for qsv_apply_layers with deferred CNOTs included (up to 28
+ * qubits).  Returns 0 for n_qubits outside 1..30 or batch < 1.  A larger workspace lets
  * qsv_param_shift_grad run more circuits per launch. */
 size_t qsv_workspace_bytes(int n_qubits, int batch);
 

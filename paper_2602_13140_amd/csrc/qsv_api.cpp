@@ -499,6 +499,9 @@ size_t qsv_workspace_bytes(int n_qubits, int batch) {
     total += align_up(B * 16) * 4;                            // norms, scales
     const size_t grad_states = row_bytes * 4 > ((size_t)256 << 20) ? row_bytes * 4 : ((size_t)256 << 20);
     total += grad_states + (8u << 20);
+    // the second state buffer of qsv_apply_layers with deferred CNOTs (it shares the bytes above with the
+    // gradient's circuit states; this makes sure a copy of the whole state fits whatever the batch)
+    if (n_qubits <= 28 && B * row_bytes > grad_states) total += align_up(B * row_bytes - grad_states);
     return total;
 }
 
