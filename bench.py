@@ -95,6 +95,31 @@ def run_steps(torch, step, steps, warmup):
     return (time.perf_counter() - t0) * 1e3 / steps, tm
 
 
+def graph_replay_ms(torch, build, steps):
+    """One step captured into a HIP graph on a stream of its own (after two eager steps, which upload
+    the plans), then replayed `steps` times: what a launch-bound small configuration costs when the
+    host issues one graph launch per step instead of one launch per kernel."""
+    side = torch.cuda.Stream()
+    with torch.cuda.stream(side):
+        ctx, step = build()                      # the context binds the side stream
+        step(None)
+        step(None)
+        side.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=side):
+            step(None)
+        for _ in range(3):
+            graph.replay()
+        side.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            graph.replay()
+        side.synchronize()
+        ms = (time.perf_counter() - t0) * 1e3 / steps
+        ctx.close()
+    return ms
+
+
 def bench_c4(torch, qb, wl, args, apply_only=False):
     w = wl.config(4)
     n = w.n
@@ -327,29 +352,40 @@ def bench_c2(torch, qb, wl, args):
 def bench_c1(torch, qb, wl, args):
     w = wl.config(1)
     n, B = w.n, w.batch
-    ctx = qb.Context(n, B)
-    if args.tile:
-        ctx.qsv_set_option("tile_log2", args.tile)
-    if args.defer >= 0:
-        ctx.qsv_set_option("defer_cnots", args.defer)
-    if args.prio >= 0:
-        ctx.qsv_set_option("load_store_priority", args.prio)
-    if args.planes:
-        ctx.qsv_set_option("lds_planes", args.planes)
     circ = qb.circuit_from_spec(w.circuit)
     xd, pd, fd = (torch.from_numpy(a).cuda() for a in (w.x, w.params, w.feats))
     z = torch.empty((B, n), dtype=torch.float32, device="cuda")
 
-    def step(tm):
-        ctx.qsv_amp_encode(xd)
-        ctx.qsv_apply_layers(circ, pd, fd, 0)
-        ctx.qsv_measure(qb.QSV_M_EXPZ_ALL, z)
+    def build():
+        ctx = qb.Context(n, B)
+        if args.tile:
+            ctx.qsv_set_option("tile_log2", args.tile)
+        if args.defer >= 0:
+            ctx.qsv_set_option("defer_cnots", args.defer)
+        if args.prio >= 0:
+            ctx.qsv_set_option("load_store_priority", args.prio)
+        if args.planes:
+            ctx.qsv_set_option("lds_planes", args.planes)
 
+        def step(tm):
+            ctx.qsv_amp_encode(xd)
+            ctx.qsv_apply_layers(circ, pd, fd, 0)
+            ctx.qsv_measure(qb.QSV_M_EXPZ_ALL, z)
+        return ctx, step
+
+    ctx, step = build()
     ms, _ = run_steps(torch, step, args.steps, args.warmup)
     updates = wl.nominal_updates(w.circuit, n, B)
+    fms, _ = run_steps(torch, lambda tm: ctx.qsv_forward_small(xd, circ, pd, fd, 0, qb.QSV_M_EXPZ_ALL, z),
+                       max(args.steps, 50), args.warmup)
     ctx.close()
+    gms = graph_replay_ms(torch, build, max(args.steps, 50))
     return {"workload": "c1: 10 qubits, batch 1024, 6 re-uploading layers, <Z_q> for every qubit",
-            "ms_per_step": ms, "updates": updates, "updates_per_s": updates / (ms * 1e-3)}
+            "ms_per_step": ms, "updates": updates, "updates_per_s": updates / (ms * 1e-3),
+            "one_launch_ms_per_step": fms, "one_launch_updates_per_s": updates / (fms * 1e-3),
+            "graph_replay_ms_per_step": gms, "graph_replay_updates_per_s": updates / (gms * 1e-3),
+            "what": "ms_per_step: qsv_amp_encode + qsv_apply_layers + qsv_measure; one_launch: qsv_forward_small; "
+                    "graph_replay: the separate calls captured into one HIP graph"}
 
 
 def bench_train(torch, qb, wl, args, idx):
@@ -399,22 +435,33 @@ def bench_train(torch, qb, wl, args, idx):
 def bench_c0(torch, qb, wl, args):
     w = wl.config(0)
     n, B = w.n, w.batch
-    ctx = qb.Context(n, B)
     circ = qb.circuit_from_spec(w.circuit)
     xd, pd = torch.from_numpy(w.x).cuda(), torch.from_numpy(w.params).cuda()
     p = torch.empty((B, 1 << n), dtype=torch.float32, device="cuda")
 
-    def step(tm):
-        ctx.qsv_amp_encode(xd)
-        ctx.qsv_apply_layers(circ, pd, None, 0)
-        ctx.qsv_apply_layers(circ, pd, None, 1)
-        ctx.qsv_measure(qb.QSV_M_PROBS, p)
+    def build():
+        ctx = qb.Context(n, B)
 
+        def step(tm):
+            ctx.qsv_amp_encode(xd)
+            ctx.qsv_apply_layers(circ, pd, None, 0)
+            ctx.qsv_apply_layers(circ, pd, None, 1)
+            ctx.qsv_measure(qb.QSV_M_PROBS, p)
+        return ctx, step
+
+    ctx, step = build()
     ms, _ = run_steps(torch, step, args.steps, args.warmup)
     updates = 2 * wl.nominal_updates(w.circuit, n, B)
+    fms, _ = run_steps(torch, lambda tm: ctx.qsv_forward_small(xd, circ, pd, None, 1, qb.QSV_M_PROBS, p),
+                       max(args.steps, 50), args.warmup)
     ctx.close()
+    gms = graph_replay_ms(torch, build, max(args.steps, 50))
     return {"workload": "c0: 4 qubits, batch 64, 2-layer encoder + decoder, basis probabilities",
-            "ms_per_step": ms, "updates": updates, "updates_per_s": updates / (ms * 1e-3)}
+            "ms_per_step": ms, "updates": updates, "updates_per_s": updates / (ms * 1e-3),
+            "one_launch_ms_per_step": fms, "one_launch_updates_per_s": updates / (fms * 1e-3),
+            "graph_replay_ms_per_step": gms, "graph_replay_updates_per_s": updates / (gms * 1e-3),
+            "what": "ms_per_step: qsv_amp_encode + 2 x qsv_apply_layers + qsv_measure; one_launch: "
+                    "qsv_forward_small; graph_replay: the separate calls captured into one HIP graph"}
 
 
 def probe(torch, qb, args):

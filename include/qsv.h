@@ -148,6 +148,22 @@ typedef struct {
 
 qsv_status qsv_measure(qsv_ctx* ctx, const qsv_measure_req* req);
 
+/* A whole small workload in ONE kernel launch (task statement: "batch-parallel launches across
+ * samples"; workload configs 0 and 1, whose separate calls cost more in launches than in arithmetic):
+ * qsv_amp_encode(x), qsv_apply_layers(c, inverse = 0), with decode = 1 then qsv_apply_layers(c,
+ * inverse = 1) (encoder followed by its decoder), the final state written to the context's state
+ * buffer, and one measurement of it, kind = QSV_M_PROBS (out_dev float32 [batch][2^n]) or
+ * QSV_M_EXPZ_ALL (out_dev float32 [batch][n]).  Arguments as in those calls; norm_out_dev may be
+ * NULL.  Same definitions and tolerances as the separate calls (the probabilities are the same
+ * float32 function of the stored state; sums may differ in their last bits from the separate
+ * calls', which add in another order).  A wavefront holds 2^10 amplitudes, so this serves
+ * n_qubits <= 10 and circuits with at most 512 matrices per wavefront (n_layers * n_qubits, times
+ * the 2^(10 - max(n_qubits, 4)) samples that share a wavefront when reupload = 1); anything else
+ * returns QSV_ERR_UNSUPPORTED before a launch, and the separate calls serve it.  Needs no workspace. */
+qsv_status qsv_forward_small(qsv_ctx* ctx, const float* x_dev, int64_t dim, const qsv_circuit* c,
+                             const float* params_dev, const float* feats_dev, int decode, int kind,
+                             void* out_dev, float* norm_out_dev);
+
 /* qsv_measure for callers that cannot allocate device memory and have no workspace to spare for it:
  * code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same request,
  * same kernels, same results bit for bit; only the kernels' partial results (block sums, cumulative

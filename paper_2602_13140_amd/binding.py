@@ -77,6 +77,8 @@ def load():
     L.qsv_apply_layers.argtypes = [vp, ctypes.POINTER(qsv_circuit), vp, vp, i32]
     L.qsv_measure.restype = i32
     L.qsv_measure.argtypes = [vp, ctypes.POINTER(qsv_measure_req)]
+    L.qsv_forward_small.restype = i32
+    L.qsv_forward_small.argtypes = [vp, vp, i64, ctypes.POINTER(qsv_circuit), vp, vp, i32, i32, vp, vp]
     L.qsv_measure_static.restype = i32
     L.qsv_measure_static.argtypes = [vp, ctypes.POINTER(qsv_measure_req)]
     L.qsv_param_shift_grad.restype = i32
@@ -204,6 +206,11 @@ class Context:
     def qsv_apply_layers(self, circ, params, feats=None, inverse=0):
         self._check(self.L.qsv_apply_layers(self.h, ctypes.byref(circ), _ptr(params), _ptr(feats),
                                             int(inverse)))
+
+    def qsv_forward_small(self, x, circ, params, feats, decode, kind, out, norm_out=None):
+        assert x.is_cuda and x.is_contiguous() and x.shape[0] == self.batch and out.is_cuda and out.is_contiguous()
+        self._check(self.L.qsv_forward_small(self.h, _ptr(x), x.shape[1], ctypes.byref(circ), _ptr(params),
+                                             _ptr(feats), int(decode), int(kind), _ptr(out), _ptr(norm_out)))
 
     def qsv_measure_static(self, kind, out, **kw):
         self.qsv_measure(kind, out, entry=self.L.qsv_measure_static, **kw)

@@ -781,6 +781,36 @@ static qsv_status measure_impl(qsv_ctx* ctx, const qsv_measure_req* req, Arena& 
     }
 }
 
+qsv_status qsv_forward_small(qsv_ctx* ctx, const float* x_dev, int64_t dim, const qsv_circuit* c,
+                             const float* params_dev, const float* feats_dev, int decode, int kind, void* out_dev,
+                             float* norm_out_dev) {
+    if (!ctx) return QSV_ERR_INVALID_ARG;
+    if (!x_dev) return fail(ctx, QSV_ERR_INVALID_ARG, "x_dev is NULL");
+    if (dim < 1 || dim > ((int64_t)1 << ctx->n)) return fail(ctx, QSV_ERR_INVALID_ARG, "dim must be in 1..2^n");
+    std::string why;
+    if (!check_circuit(c, ctx->n, &why)) return fail(ctx, QSV_ERR_INVALID_ARG, why);
+    if (decode != 0 && decode != 1) return fail(ctx, QSV_ERR_INVALID_ARG, "decode must be 0 or 1");
+    if (kind != QSV_M_PROBS && kind != QSV_M_EXPZ_ALL)
+        return fail(ctx, QSV_ERR_INVALID_ARG, "kind must be QSV_M_PROBS or QSV_M_EXPZ_ALL");
+    if (!out_dev) return fail(ctx, QSV_ERR_INVALID_ARG, "out_dev is NULL");
+    const int64_t P = qsv_num_params(c, ctx->n);
+    if (P > 0 && !params_dev) return fail(ctx, QSV_ERR_INVALID_ARG, "params_dev is NULL");
+    if (c->reupload && !feats_dev) return fail(ctx, QSV_ERR_INVALID_ARG, "reupload = 1 needs feats_dev");
+    if (ctx->n > kSmallMaxQubits)
+        return fail(ctx, QSV_ERR_UNSUPPORTED, "qsv_forward_small takes at most 10 qubits: use the separate calls");
+    const CircDev cd = to_dev(*c, ctx->n);
+    if (small_mats_per_wave(cd) > kSmallMats)
+        return fail(ctx, QSV_ERR_UNSUPPORTED,
+                    "qsv_forward_small keeps at most 512 matrices per wavefront (layers * qubits, times the "
+                    "2^(10 - max(n, 4)) samples of a wavefront when the circuit re-uploads data): use the separate calls");
+    qsv_status st = bind_device(ctx);
+    if (st != QSV_OK) return st;
+    QSV_HIP(ctx, launch_forward_small(x_dev, dim, ctx->batch, cd, c->entangler, params_dev, feats_dev, decode, kind,
+                                      ctx->state, (float*)out_dev, norm_out_dev, ctx->stream),
+            "forward_small");
+    return QSV_OK;
+}
+
 qsv_status qsv_measure(qsv_ctx* ctx, const qsv_measure_req* req) {
     if (!ctx) return QSV_ERR_INVALID_ARG;
     Arena ar(ctx);

@@ -93,6 +93,19 @@ hipError_t launch_norms(const float* x, int64_t samples, int64_t dim, double* pa
 // norm and state rows of small samples (dim <= 4096, n <= 12) in one launch; inv_norm receives 1/||x_b||
 hipError_t launch_encode_small(const float* x, int64_t samples, int64_t dim, int n, double* inv_norm, float* norm_out,
                                float2* state, hipStream_t st);
+// A whole small workload in one launch: encoding, circuit (decode = 1: followed by its inverse), final
+// state, and the measurement `kind` (QSV_M_PROBS or QSV_M_EXPZ_ALL).  One wavefront holds 2^10 amplitudes,
+// i.e. 2^(10 - max(n, 4)) samples, and keeps the matrices of its samples in LDS.
+constexpr int kSmallMaxQubits = 10;
+constexpr int kSmallMats = 512;   // matrices a wavefront keeps in LDS (16 KiB)
+inline int small_rows_per_wave(int n) { return 64 >> ((n < 4 ? 4 : n) - 4); }
+inline int64_t small_mats_per_wave(const CircDev& c) {
+    if (c.reupload + c.n_rot == 0) return 0;
+    return (int64_t)(c.reupload ? small_rows_per_wave(c.n) : 1) * c.n_layers * c.n;
+}
+hipError_t launch_forward_small(const float* x, int64_t dim, int64_t batch, const CircDev& c, int entangler,
+                                const float* params, const float* feats, int decode, int kind, float2* state,
+                                float* out, float* norm_out, hipStream_t st);
 hipError_t launch_encode_write(const float* x, int64_t dim, int n, int64_t rows, const double* inv_norm,
                                const RowMap& rm, float2* state, hipStream_t st);
 

@@ -17,8 +17,10 @@ constexpr int CHUNK = 1 << CHUNK_BITS;
 typedef unsigned long long u64;
 
 __device__ __forceinline__ float prob32(float2 a) {
-    // one fixed rounding sequence so that every kernel that needs p32 gets the same bits
-    return __fadd_rn(__fmul_rn(a.x, a.x), __fmul_rn(a.y, a.y));
+    // one fixed rounding sequence so that every kernel that needs p32 gets the same bits: re * re
+    // rounded, then one fused multiply-add (written out: a plain sum of two products leaves the
+    // compiler free to fuse either product, differently from kernel to kernel)
+    return __builtin_fmaf(a.y, a.y, a.x * a.x);
 }
 
 __device__ __forceinline__ double wave_sum(double v) {
@@ -1745,6 +1747,319 @@ __global__ __launch_bounds__(256) void k_adam(float* p, const float* g, float* m
     v[i] = (float)vi;
 }
 
+// ------------------------------------------------------------------------------------------
+// A whole small workload in one launch (at most 10 qubits): amplitude encoding, the circuit (and,
+// as decoder, its exact inverse), the final state and one measurement.  One wavefront holds 2^10
+// amplitudes: 16 per lane in registers (index bits 0..3), index bits 4..n-1 in the low lane bits,
+// and the remaining lane bits number the 2^(10-n) samples that share the wavefront.  A gate on a
+// register bit pairs registers, a gate on a lane bit exchanges with the partner lane
+// (ds_bpermute); nothing goes through memory between the gates.  The matrices are built once per
+// wavefront, one per lane at a time, and kept in LDS.
+struct Amps { float re[16], im[16]; };  // every index is a compile-time constant after unrolling
+
+__device__ __forceinline__ float lane_xchg(int addr, float v) {
+    return __int_as_float(__builtin_amdgcn_ds_bpermute(addr, __float_as_int(v)));
+}
+
+// The value that the lane whose number differs in bit B holds.  Bits 0..3: DPP moves (inside a row
+// of 16 lanes; XOR 4 = reversal of 8 then of 4, XOR 8 = reversal of 16 then of 8); bit 4: the
+// swizzle of the LDS crossbar; bit 5: ds_bpermute (addr = 4 * partner lane).
+template <int B>
+__device__ __forceinline__ float lane_flip(float v, int addr) {
+    const int x = __float_as_int(v);
+    if constexpr (B == 0) return __int_as_float(__builtin_amdgcn_mov_dpp(x, 0xB1, 0xf, 0xf, true));   // quad_perm [1,0,3,2]
+    else if constexpr (B == 1) return __int_as_float(__builtin_amdgcn_mov_dpp(x, 0x4E, 0xf, 0xf, true));   // [2,3,0,1]
+    else if constexpr (B == 2)
+        return __int_as_float(__builtin_amdgcn_mov_dpp(__builtin_amdgcn_mov_dpp(x, 0x141, 0xf, 0xf, true), 0x1B, 0xf, 0xf, true));
+    else if constexpr (B == 3)
+        return __int_as_float(__builtin_amdgcn_mov_dpp(__builtin_amdgcn_mov_dpp(x, 0x140, 0xf, 0xf, true), 0x141, 0xf, 0xf, true));
+    else if constexpr (B == 4) return __int_as_float(__builtin_amdgcn_ds_swizzle(x, 0x401F));           // xor 16 within 32 lanes
+    else return lane_xchg(addr, v);
+}
+
+// m = (m00r, m00i, m01r, m01i, m10r, m10i, m11r, m11i)
+template <int J>
+__device__ __forceinline__ void small_u_reg(Amps& a, const float* m) {
+#pragma unroll
+    for (int k = 0; k < 16; ++k) {
+        if (k & (1 << J)) continue;
+        const int k1 = k | (1 << J);
+        const float ar = a.re[k], ai = a.im[k], br = a.re[k1], bi = a.im[k1];
+        a.re[k] = m[0] * ar - m[1] * ai + m[2] * br - m[3] * bi;
+        a.im[k] = m[0] * ai + m[1] * ar + m[2] * bi + m[3] * br;
+        a.re[k1] = m[4] * ar - m[5] * ai + m[6] * br - m[7] * bi;
+        a.im[k1] = m[4] * ai + m[5] * ar + m[6] * bi + m[7] * br;
+    }
+}
+
+// The qubit is lane bit B: this lane holds the amplitudes with the bit equal to its own lane bit,
+// the partner lane the ones with the other value.
+template <int B>
+__device__ __forceinline__ void small_u_lane(Amps& a, const float* m, int lane) {
+    const bool bit = (lane >> B) & 1;
+    const int addr = (lane ^ (1 << B)) << 2;
+    const float sr = bit ? m[6] : m[0], si = bit ? m[7] : m[1];   // row `bit`, own column
+    const float qr = bit ? m[4] : m[2], qi = bit ? m[5] : m[3];   // row `bit`, the partner's column
+    float pr[16], pi[16];                    // all exchanges first: their latencies overlap
+#pragma unroll
+    for (int k = 0; k < 16; ++k) { pr[k] = lane_flip<B>(a.re[k], addr); pi[k] = lane_flip<B>(a.im[k], addr); }
+#pragma unroll
+    for (int k = 0; k < 16; ++k) {
+        const float ar = a.re[k], ai = a.im[k];
+        a.re[k] = sr * ar - si * ai + qr * pr[k] - qi * pi[k];
+        a.im[k] = sr * ai + si * ar + qr * pi[k] + qi * pr[k];
+    }
+}
+
+template <int C, int T>
+__device__ __forceinline__ void small_cx_rr(Amps& a) {
+#pragma unroll
+    for (int k = 0; k < 16; ++k) {
+        if (!(k & (1 << C)) || (k & (1 << T))) continue;
+        const int k1 = k | (1 << T);
+        const float r = a.re[k], i = a.im[k];
+        a.re[k] = a.re[k1]; a.im[k] = a.im[k1];
+        a.re[k1] = r; a.im[k1] = i;
+    }
+}
+
+template <int T>
+__device__ __forceinline__ void small_cx_lr(Amps& a, bool ctrl) {  // control on a lane bit, target in registers
+#pragma unroll
+    for (int k = 0; k < 16; ++k) {
+        if (k & (1 << T)) continue;
+        const int k1 = k | (1 << T);
+        const float r0 = a.re[k], i0 = a.im[k], r1 = a.re[k1], i1 = a.im[k1];
+        a.re[k] = ctrl ? r1 : r0; a.im[k] = ctrl ? i1 : i0;
+        a.re[k1] = ctrl ? r0 : r1; a.im[k1] = ctrl ? i0 : i1;
+    }
+}
+
+// every register takes the value that lane addr / 4 holds (a permutation of the lanes)
+__device__ __forceinline__ void small_lane_perm(Amps& a, int addr) {
+    float pr[16], pi[16];
+#pragma unroll
+    for (int k = 0; k < 16; ++k) { pr[k] = lane_xchg(addr, a.re[k]); pi[k] = lane_xchg(addr, a.im[k]); }
+#pragma unroll
+    for (int k = 0; k < 16; ++k) { a.re[k] = pr[k]; a.im[k] = pi[k]; }
+}
+
+// The CNOT ring on n qubits, control q, target q + 1 (the last one's target is qubit 0), in order,
+// or with reverse = true in the opposite order (the ring's inverse).  The CNOTs between register
+// bits rename registers, the one from register bit 3 to lane bit 0 exchanges half of the registers
+// with the neighbouring lane, the CNOTs between lane bits (qubits 4..n-1) are together one
+// permutation of the lanes (chain_f / chain_r: for each lane, four times the lane it reads from),
+// and the closing one swaps register pairs in the lanes whose top index bit is set.
+__device__ __forceinline__ void small_ring(Amps& a, int n, int lane, bool reverse, int chain_f, int chain_r) {
+    auto wrap = [&]() {
+        if (n == 2) small_cx_rr<1, 0>(a);
+        else if (n == 3) small_cx_rr<2, 0>(a);
+        else if (n == 4) small_cx_rr<3, 0>(a);
+        else if (n > 4) small_cx_lr<0>(a, (lane >> (n - 5)) & 1);
+    };
+    auto bridge = [&]() {                          // control register bit 3, target lane bit 0
+        if (n > 4) {
+#pragma unroll
+            for (int k = 8; k < 16; ++k) { a.re[k] = lane_flip<0>(a.re[k], 0); a.im[k] = lane_flip<0>(a.im[k], 0); }
+        }
+    };
+    if (!reverse) {
+        if (n >= 2) small_cx_rr<0, 1>(a);
+        if (n >= 3) small_cx_rr<1, 2>(a);
+        if (n >= 4) small_cx_rr<2, 3>(a);
+        bridge();
+        if (n > 5) small_lane_perm(a, chain_f);
+        wrap();
+    } else {
+        wrap();
+        if (n > 5) small_lane_perm(a, chain_r);
+        bridge();
+        if (n >= 4) small_cx_rr<2, 3>(a);
+        if (n >= 3) small_cx_rr<1, 2>(a);
+        if (n >= 2) small_cx_rr<0, 1>(a);
+    }
+}
+
+// CZ on qubits q and q + 1 for q = 0..n-2 (the gates commute, so the order does not matter): the
+// sign of an amplitude changes once for every pair of neighbouring set bits.
+__device__ __forceinline__ void small_cz_ladder(Amps& a, int n, int lane) {
+    const int li = lane & ((1 << ((n < 4 ? 4 : n) - 4)) - 1);
+#pragma unroll
+    for (int k = 0; k < 16; ++k) {
+        const int idx = (li << 4) | k;
+        const int mask = (1 << (n - 1)) - 1;     // pairs (q, q + 1) for q = 0..n-2
+        const bool f = __builtin_popcount(idx & (idx >> 1) & mask) & 1;
+        a.re[k] = f ? -a.re[k] : a.re[k];
+        a.im[k] = f ? -a.im[k] : a.im[k];
+    }
+}
+
+struct SmallArgs {
+    const float* x;        // [batch][dim]
+    int64_t dim, batch;
+    CircDev c;
+    int entangler;         // qsv_ent
+    const float* params;
+    const float* feats;
+    int decode;            // 1: the inverse circuit follows the circuit
+    int kind;              // QSV_M_PROBS or QSV_M_EXPZ_ALL
+    float2* state;         // [batch][2^n], receives the final state
+    float* out;            // probabilities [batch][2^n] or expectations [batch][n]
+    float* norm_out;       // [batch] or NULL
+};
+
+__global__ __launch_bounds__(64) void k_forward_small(SmallArgs a) {
+    __shared__ __align__(16) float mats[kSmallMats * 8];
+    const int lane = threadIdx.x;
+    const int n = a.c.n, L = a.c.n_layers;
+    const int lb = (n < 4 ? 4 : n) - 4;          // lane bits that are index bits
+    const int rows_w = 64 >> lb;                 // samples per wavefront
+    const int r_in = lane >> lb;
+    const int li = lane & ((1 << lb) - 1);
+    const int64_t first = (int64_t)blockIdx.x * rows_w;
+    const int64_t sample = first + r_in;
+    const bool live = sample < a.batch;
+    const int per = L * n;
+    const bool has_u = a.c.reupload + a.c.n_rot > 0;
+    if (has_u) {
+        const int rows_m = a.c.reupload ? rows_w : 1;
+        for (int i = lane; i < rows_m * per; i += 64) {
+            const int r = i / per, lq = i % per;
+            const int64_t s = first + r < a.batch ? first + r : a.batch - 1;
+            const M2 u = fused_raw(a.c, a.params, a.feats, (u64)s, lq / n, lq % n, -1, 0.0, 0);
+            float* o = mats + (size_t)i * 8;
+#pragma unroll
+            for (int k = 0; k < 4; ++k) { o[2 * k] = (float)u.r[k]; o[2 * k + 1] = (float)u.i[k]; }
+        }
+    }
+    // amplitude encoding: x / ||x||, the norm in double
+    Amps A;
+    float nrm_f;
+    {
+        const float* xb = a.x + (live ? sample : 0) * a.dim;
+        float xv[16];
+        double ss = 0.0;
+#pragma unroll
+        for (int k = 0; k < 16; ++k) {
+            const int64_t idx = ((int64_t)li << 4) | k;
+            const float v = (live && idx < a.dim) ? xb[idx] : 0.f;
+            xv[k] = v;
+            ss += (double)v * (double)v;
+        }
+#pragma unroll
+        for (int b = 0; b < 6; ++b)
+            if (b < lb) ss += __shfl_xor(ss, 1 << b, 64);
+        const double nrm = sqrt(ss);
+        const double inv = nrm > 0.0 ? 1.0 / nrm : 0.0;
+#pragma unroll
+        for (int k = 0; k < 16; ++k) { A.re[k] = (float)((double)xv[k] * inv); A.im[k] = 0.f; }
+        nrm_f = (float)nrm;
+    }
+    if (a.norm_out && live && li == 0) a.norm_out[sample] = nrm_f;
+    __syncthreads();
+    // the gates: per layer the unitaries then the entangler; in the decoder layers last to first,
+    // the entangler's gates in reverse order first, then the conjugate-transposed unitaries
+    const float* mrow = mats + (size_t)(a.c.reupload ? r_in * per : 0) * 8;
+    // lane permutations of the ring's CNOTs between lane bits (qubits 4..n-1): an amplitude at
+    // lane j moves to C(j), so afterwards lane j holds what lane C_first(...C_last(j)) held
+    int chain_f = lane, chain_r = lane;
+    for (int b = lb - 2; b >= 0; --b) chain_f ^= ((chain_f >> b) & 1) << (b + 1);
+    for (int b = 0; b + 1 < lb; ++b) chain_r ^= ((chain_r >> b) & 1) << (b + 1);
+    chain_f = (chain_f | (lane & ~((1 << lb) - 1))) << 2;
+    chain_r = (chain_r | (lane & ~((1 << lb) - 1))) << 2;
+    for (int pass = 0; pass <= a.decode; ++pass) {
+        for (int ll = 0; ll < L; ++ll) {
+            const int l = pass ? L - 1 - ll : ll;
+            for (int stage = 0; stage < 2; ++stage) {
+                if ((stage == 0) == (pass == 1)) {
+                    if (a.entangler == QSV_ENT_CNOT_RING) small_ring(A, n, lane, pass != 0, chain_f, chain_r);
+                    else if (a.entangler == QSV_ENT_CZ_LADDER) small_cz_ladder(A, n, lane);
+                } else if (has_u) {
+                    const float* ml = mrow + (size_t)l * n * 8;
+                    auto load_m = [&](int q, float* m) {
+                        const float4 lo = *reinterpret_cast<const float4*>(ml + q * 8);
+                        const float4 hi = *reinterpret_cast<const float4*>(ml + q * 8 + 4);
+                        if (!pass) {
+                            m[0] = lo.x; m[1] = lo.y; m[2] = lo.z; m[3] = lo.w;
+                            m[4] = hi.x; m[5] = hi.y; m[6] = hi.z; m[7] = hi.w;
+                        } else {
+                            m[0] = lo.x; m[1] = -lo.y; m[2] = hi.x; m[3] = -hi.y;
+                            m[4] = lo.z; m[5] = -lo.w; m[6] = hi.z; m[7] = -hi.w;
+                        }
+                    };
+                    float m[8];
+#define QSV_SMALL_UR(Q) if (n > Q) { load_m(Q, m); small_u_reg<Q>(A, m); }
+#define QSV_SMALL_UL(Q) if (n > Q) { load_m(Q, m); small_u_lane<Q - 4>(A, m, lane); }
+                    QSV_SMALL_UR(0) QSV_SMALL_UR(1) QSV_SMALL_UR(2) QSV_SMALL_UR(3)
+                    QSV_SMALL_UL(4) QSV_SMALL_UL(5) QSV_SMALL_UL(6) QSV_SMALL_UL(7) QSV_SMALL_UL(8) QSV_SMALL_UL(9)
+#undef QSV_SMALL_UR
+#undef QSV_SMALL_UL
+                }
+            }
+        }
+    }
+    // final state and the measurement
+    const int dimn = 1 << n;
+    if (live) {
+        float2* srow = a.state + (sample << n) + (li << 4);
+        if (n >= 4) {
+#pragma unroll
+            for (int k = 0; k < 16; k += 2)
+                *reinterpret_cast<float4*>(srow + k) = make_float4(A.re[k], A.im[k], A.re[k + 1], A.im[k + 1]);
+        } else {
+#pragma unroll
+            for (int k = 0; k < 8; ++k)
+                if (k < dimn) srow[k] = make_float2(A.re[k], A.im[k]);
+        }
+    }
+    float p[16];
+#pragma unroll
+    for (int k = 0; k < 16; ++k) p[k] = prob32(make_float2(A.re[k], A.im[k]));
+    if (a.kind == QSV_M_PROBS) {
+        if (live) {
+            float* prow = a.out + (sample << n) + (li << 4);
+            if (n >= 4) {
+#pragma unroll
+                for (int k = 0; k < 16; k += 4)
+                    *reinterpret_cast<float4*>(prow + k) = make_float4(p[k], p[k + 1], p[k + 2], p[k + 3]);
+            } else {
+#pragma unroll
+                for (int k = 0; k < 8; ++k)
+                    if (k < dimn) prow[k] = p[k];
+            }
+        }
+        return;
+    }
+    // <Z_q> for every qubit: signed sums in double, combined over the lanes of the sample
+    double T = 0.0, zr[4] = {0.0, 0.0, 0.0, 0.0}, zl[6] = {0.0, 0.0, 0.0, 0.0, 0.0, 0.0};
+#pragma unroll
+    for (int k = 0; k < 16; ++k) {
+        const double pk = (double)p[k];
+        T += pk;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) zr[j] += ((k >> j) & 1) ? -pk : pk;
+    }
+#pragma unroll
+    for (int b = 0; b < 6; ++b) {
+        if (b < lb) {
+            const double Tp = __shfl_xor(T, 1 << b, 64);
+#pragma unroll
+            for (int j = 0; j < 4; ++j) zr[j] += __shfl_xor(zr[j], 1 << b, 64);
+#pragma unroll
+            for (int j = 0; j < 6; ++j)
+                if (j < b) zl[j] += __shfl_xor(zl[j], 1 << b, 64);
+            zl[b] = ((lane >> b) & 1) ? Tp - T : T - Tp;
+            T += Tp;
+        }
+    }
+    if (live && li == 0) {
+        float* orow = a.out + sample * n;
+#pragma unroll
+        for (int q = 0; q < 10; ++q)
+            if (q < n) orow[q] = (float)(q < 4 ? zr[q] : zl[q - 4]);
+    }
+}
+
 inline unsigned blocks_for(u64 items, unsigned per) { return (unsigned)((items + per - 1) / per); }
 
 // grid of the reduction kernels: chunks in x, rows over y and z (see grid_row)
@@ -1874,6 +2189,22 @@ hipError_t launch_encode_small(const float* x, int64_t samples, int64_t dim, int
     if (dim > 4096 || n > 12) return hipErrorInvalidValue;
     hipLaunchKernelGGL(k_encode_small, rows_grid(1, (u64)samples), dim3(256), 0, st, x, (u64)samples, (u64)dim, n,
                        inv_norm, norm_out, state);
+    return hipGetLastError();
+}
+
+hipError_t launch_forward_small(const float* x, int64_t dim, int64_t batch, const CircDev& c, int entangler,
+                                const float* params, const float* feats, int decode, int kind, float2* state,
+                                float* out, float* norm_out, hipStream_t st) {
+    if (c.n < 1 || c.n > kSmallMaxQubits || batch < 1 || dim < 1 || dim > ((int64_t)1 << c.n))
+        return hipErrorInvalidValue;
+    if (small_mats_per_wave(c) > kSmallMats) return hipErrorInvalidValue;
+    const int rows_w = small_rows_per_wave(c.n);
+    SmallArgs a;
+    a.x = x; a.dim = dim; a.batch = batch; a.c = c; a.entangler = entangler; a.params = params; a.feats = feats;
+    a.decode = decode; a.kind = kind; a.state = state; a.out = out; a.norm_out = norm_out;
+    const int64_t blocks = (batch + rows_w - 1) / rows_w;
+    if (blocks > 0x7fffffff) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(k_forward_small, dim3((unsigned)blocks), dim3(64), 0, st, a);
     return hipGetLastError();
 }
 

@@ -591,6 +591,109 @@ def test_training_steps_lower_the_loss(oracle):
     ctx.close()
 
 
+# ------------------------------------------------------------------ a small workload in one launch
+SMALL_FUSED = [
+    # n, B, dim, layers, rotations, entangler, reupload
+    (1, 3, 2, 2, (RY, RZ), RING, 0),
+    (2, 70, 3, 3, (RX, RY, RZ), RING, 1),
+    (3, 5, 8, 2, (RY,), LADDER, 0),
+    (4, 64, 16, 2, (RY, RZ), RING, 0),             # config 0's shape
+    (4, 130, 11, 2, (RZ, RX), LADDER, 1),          # three wavefronts, the last one ragged
+    (5, 33, 32, 3, (RY, RZ), RING, 1),
+    (6, 9, 50, 4, (RX, RY, RZ), LADDER, 0),
+    (7, 8, 128, 3, (RY, RZ), RING, 1),
+    (8, 5, 200, 2, (), RING, 1),                   # re-upload only
+    (9, 3, 512, 5, (RY, RZ), LADDER, 1),
+    (10, 6, 1024, 6, (RY, RZ), RING, 1),           # config 1's shape at a small batch
+    (10, 2, 777, 0, (RY,), RING, 0),               # no layers: encoding and measurement only
+    (10, 3, 1024, 3, (), NONE, 0),                 # no gates at all per layer
+    (10, 1, 1024, 51, (RZ, RY, RX), RING, 0),      # 510 matrices: the most a wavefront keeps
+]
+
+
+@pytest.mark.parametrize("n,B,dim,L,rot,ent,reup", SMALL_FUSED)
+@pytest.mark.parametrize("decode", [0, 1])
+def test_forward_small_equals_the_oracle_and_the_separate_calls(oracle, n, B, dim, L, rot, ent, reup, decode):
+    """qsv_forward_small = amp_encode, apply_layers (and its inverse when decode = 1), state, one
+    measurement, in one launch: state, probabilities and <Z_q> against the oracle at the contract's
+    tolerances, and against the separate calls of the library."""
+    torch = gu.torch_cuda()
+    g = rng(9000 + n * 37 + B)
+    spec = wl.CircuitSpec(L, tuple(rot), ent, reup)
+    params = wl.draw_params(spec, n, 9100 + n)
+    x = g.standard_normal((B, dim)).astype(np.float32)
+    if B > 1:
+        x[1] = 0.0                                   # a zero vector: all-zero state, norm 0, no NaN
+    feats = g.standard_normal((B, n)).astype(np.float32) if reup else None
+    ref, nrm = oracle.amp_encode(x, n)
+    oracle.apply_layers(ref, ocirc(oracle, spec), params, feats)
+    if decode:
+        oracle.apply_layers(ref, ocirc(oracle, spec), params, feats, inverse=1)
+    circ = qb.circuit_from_spec(spec)
+    xd, pd = gu.dev(x), gu.dev(params if params.size else np.zeros(1, np.float32))
+    fd = gu.dev(feats) if reup else None
+    ctx = gu.make_ctx(n, B)
+    for kind, shape in ((qb.QSV_M_PROBS, (B, 1 << n)), (qb.QSV_M_EXPZ_ALL, (B, n))):
+        ctx.state.fill_(9.0)
+        out = torch.full(shape, -7.0, dtype=torch.float32, device="cuda")
+        norm_out = torch.full((B,), -1.0, dtype=torch.float32, device="cuda")
+        ctx.qsv_forward_small(xd, circ, pd, fd, decode, kind, out, norm_out)
+        got = gu.state_np(ctx)
+        assert not np.isnan(got).any()
+        assert np.abs(got - ref).max() <= amp_tol(n)
+        assert np.allclose(norm_out.cpu().numpy(), nrm, rtol=2e-7)
+        o = out.cpu().numpy()
+        if kind == qb.QSV_M_PROBS:
+            live = nrm > 0
+            gu.prob_checks(o[live], oracle.probs(ref)[live])
+            assert np.all(o[~live] == 0)
+            assert np.array_equal(o, gu.measure(ctx, qb.QSV_M_PROBS, shape))   # same float32 function of the state
+        else:
+            assert np.abs(o - oracle.expz_all(ref)).max() <= 1e-5
+        # the separate calls
+        ctx2 = gu.make_ctx(n, B)
+        ctx2.qsv_amp_encode(xd)
+        ctx2.qsv_apply_layers(circ, pd, fd, 0)
+        if decode:
+            ctx2.qsv_apply_layers(circ, pd, fd, 1)
+        assert np.abs(gu.state_np(ctx2) - got).max() <= 1e-5
+        assert np.abs(gu.measure(ctx2, kind, shape) - o).max() <= 1e-5
+        ctx2.close()
+    ctx.close()
+
+
+def test_forward_small_refuses_what_it_does_not_serve():
+    torch = gu.torch_cuda()
+    circ = qb.make_circuit(2, [RY], RING, 0)
+    for n, B, c in ((11, 2, circ),                                   # more than 10 qubits
+                    (10, 1, qb.make_circuit(52, [RY], RING, 0)),     # 520 matrices
+                    (4, 64, qb.make_circuit(3, [RY], RING, 1))):     # 64 samples x 3 layers x 4 qubits
+        ctx = gu.make_ctx(n, B)
+        x = torch.ones((B, 1 << n), dtype=torch.float32, device="cuda")
+        P = max(1, qb.qsv_num_params(c, n))
+        pd = torch.zeros(P, dtype=torch.float32, device="cuda")
+        fd = torch.zeros((B, n), dtype=torch.float32, device="cuda")
+        out = torch.zeros((B, n), dtype=torch.float32, device="cuda")
+        ctx.state.fill_(5.0)
+        with pytest.raises(qb.QsvError) as e:
+            ctx.qsv_forward_small(x, c, pd, fd, 0, qb.QSV_M_EXPZ_ALL, out)
+        assert e.value.status == qb.QSV_ERR_UNSUPPORTED
+        torch.cuda.synchronize()
+        assert torch.all(ctx.state == 5.0)                           # nothing was launched
+        ctx.close()
+    ctx = gu.make_ctx(5, 2)
+    x = torch.ones((2, 32), dtype=torch.float32, device="cuda")
+    out = torch.zeros((2, 5), dtype=torch.float32, device="cuda")
+    pd = torch.zeros(20, dtype=torch.float32, device="cuda")
+    for bad in (dict(decode=2), dict(kind=qb.QSV_M_MARGINAL)):
+        kw = dict(decode=0, kind=qb.QSV_M_EXPZ_ALL)
+        kw.update(bad)
+        with pytest.raises(qb.QsvError) as e:
+            ctx.qsv_forward_small(x, circ, pd, None, kw["decode"], kw["kind"], out)
+        assert e.value.status == qb.QSV_ERR_INVALID_ARG
+    ctx.close()
+
+
 # ------------------------------------------------------------------ HIP graph capture
 @pytest.mark.parametrize("n,B,tile", [(6, 16, 0), (12, 4, 10)])   # the second: the rows go as two halves on two streams
 def test_calls_can_be_captured_in_a_hip_graph_and_replayed(oracle, n, B, tile):
