@@ -156,10 +156,12 @@ qsv_status qsv_measure(qsv_ctx* ctx, const qsv_measure_req* req);
  * QSV_M_EXPZ_ALL (out_dev float32 [batch][n]).  Arguments as in those calls; norm_out_dev may be
  * NULL.  Same definitions and tolerances as the separate calls (the probabilities are the same
  * float32 function of the stored state; sums may differ in their last bits from the separate
- * calls', which add in another order).  A wavefront holds 2^10 amplitudes, so this serves
- * n_qubits <= 10 and circuits with at most 512 matrices per wavefront (n_layers * n_qubits, times
- * the 2^(10 - max(n_qubits, 4)) samples that share a wavefront when reupload = 1); anything else
- * returns QSV_ERR_UNSUPPORTED before a launch, and the separate calls serve it.  Needs no workspace. */
+ * calls', which add in another order).  A thread keeps 4, 8 or 16 amplitudes in registers and a
+ * workgroup of at most 256 threads holds a sample, so this serves n_qubits <= 10, and circuits with
+ * at most 512 matrices per workgroup: n_layers * n_qubits, times the samples that share a
+ * wavefront when reupload = 1 (2^(8 - n_qubits) of them up to 8 qubits, one above).  Anything else
+ * returns QSV_ERR_UNSUPPORTED before a launch, and the separate calls serve it.  Needs no
+ * workspace. */
 qsv_status qsv_forward_small(qsv_ctx* ctx, const float* x_dev, int64_t dim, const qsv_circuit* c,
                              const float* params_dev, const float* feats_dev, int decode, int kind,
                              void* out_dev, float* norm_out_dev);
@@ -280,7 +282,9 @@ qsv_status qsv_probe_pass(qsv_ctx* ctx, int low_bits, int window_start, int tran
  * every CNOT a register operation (-1, the default, defers whenever the circuit has a CNOT ring, more
  * qubits than the tile has index bits, at most 28 of them, and the workspace has room for a copy of
  * the state; the result is the same up to rounding order); load_store_priority = 1 (default) / 0 makes
- * the pass kernel's wavefronts raise their issue priority while they issue a tile's loads and stores; low_bits in 4..10 (0 = default) forces the planner's minimum number of low index bits
+ * the pass kernel's wavefronts raise their issue priority while they issue a tile's loads and stores;
+ * small_regs = 2, 3 or 4 fixes the amplitudes per thread of qsv_forward_small at 4, 8 or 16 (0, the
+ * default, takes the most that still gives the chip about four wavefronts per SIMD); low_bits in 4..10 (0 = default) forces the planner's minimum number of low index bits
  * per tile; lds_planes = 1 (default) moves real and imaginary parts through one LDS plane one
  * after the other, 2 through two planes at once; naive = 1 routes qsv_apply_layers through the
  * one-gate-per-launch kernels; grad_layered = 0 makes qsv_param_shift_grad run every shifted

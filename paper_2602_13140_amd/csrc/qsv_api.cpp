@@ -75,6 +75,7 @@ struct qsv_ctx {
     int64_t opt_grad_chunk = 0;
     int opt_split = -1;      // state rows of a launch sequence in two halves on two streams; -1: by state size
     int opt_prio = 1;        // raised issue priority around a tile's loads and stores (measured: 2 % off configs 3 and 4)
+    int opt_small_regs = 0;  // qsv_forward_small: amplitudes per thread = 2^this (2..4); 0: by batch size
     int opt_defer = -1;      // qsv_apply_layers defers CNOTs whose target lies outside a pass's tile; -1: when it can
     hipStream_t side = nullptr;          // second stream for that (default priority, non-blocking)
     hipEvent_t ev_fork = nullptr, ev_join = nullptr;
@@ -611,6 +612,11 @@ qsv_status qsv_set_option(qsv_ctx* ctx, const char* name, int64_t value) {
         ctx->opt_prio = (int)value;
         return QSV_OK;
     }
+    if (!strcmp(name, "small_regs")) {
+        if (value != 0 && (value < 2 || value > 4)) return fail(ctx, QSV_ERR_INVALID_ARG, "small_regs must be 0, 2, 3 or 4");
+        ctx->opt_small_regs = (int)value;
+        return QSV_OK;
+    }
     if (!strcmp(name, "defer_cnots")) {
         if (value < -1 || value > 1) return fail(ctx, QSV_ERR_INVALID_ARG, "defer_cnots must be -1, 0 or 1");
         ctx->opt_defer = (int)value;
@@ -799,13 +805,15 @@ qsv_status qsv_forward_small(qsv_ctx* ctx, const float* x_dev, int64_t dim, cons
     if (ctx->n > kSmallMaxQubits)
         return fail(ctx, QSV_ERR_UNSUPPORTED, "qsv_forward_small takes at most 10 qubits: use the separate calls");
     const CircDev cd = to_dev(*c, ctx->n);
-    if (small_mats_per_wave(cd) > kSmallMats)
+    int regs = ctx->opt_small_regs;
+    if (regs == 0) regs = small_choose_regs(cd, ctx->batch);
+    if (regs == 0 || ctx->n - regs > 8 || small_mats_per_group(cd, regs) > kSmallMats)
         return fail(ctx, QSV_ERR_UNSUPPORTED,
-                    "qsv_forward_small keeps at most 512 matrices per wavefront (layers * qubits, times the "
-                    "2^(10 - max(n, 4)) samples of a wavefront when the circuit re-uploads data): use the separate calls");
+                    "qsv_forward_small keeps at most 512 matrices per workgroup (layers * qubits, times the samples "
+                    "that share a wavefront when the circuit re-uploads data): use the separate calls");
     qsv_status st = bind_device(ctx);
     if (st != QSV_OK) return st;
-    QSV_HIP(ctx, launch_forward_small(x_dev, dim, ctx->batch, cd, c->entangler, params_dev, feats_dev, decode, kind,
+    QSV_HIP(ctx, launch_forward_small(regs, x_dev, dim, ctx->batch, cd, c->entangler, params_dev, feats_dev, decode, kind,
                                       ctx->state, (float*)out_dev, norm_out_dev, ctx->stream),
             "forward_small");
     return QSV_OK;

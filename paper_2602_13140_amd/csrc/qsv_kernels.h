@@ -94,16 +94,35 @@ hipError_t launch_norms(const float* x, int64_t samples, int64_t dim, double* pa
 hipError_t launch_encode_small(const float* x, int64_t samples, int64_t dim, int n, double* inv_norm, float* norm_out,
                                float2* state, hipStream_t st);
 // A whole small workload in one launch: encoding, circuit (decode = 1: followed by its inverse), final
-// state, and the measurement `kind` (QSV_M_PROBS or QSV_M_EXPZ_ALL).  One wavefront holds 2^10 amplitudes,
-// i.e. 2^(10 - max(n, 4)) samples, and keeps the matrices of its samples in LDS.
+// state, and the measurement `kind` (QSV_M_PROBS or QSV_M_EXPZ_ALL).  A thread keeps 2^regs amplitudes
+// (regs = 2, 3 or 4), the other index bits are bits of the thread number (at most 8: 256 threads); with
+// fewer than 6 of them a wavefront holds 2^(6 - bits) samples.  A workgroup keeps the matrices of its
+// samples in LDS (at most kSmallMats).
 constexpr int kSmallMaxQubits = 10;
-constexpr int kSmallMats = 512;   // matrices a wavefront keeps in LDS (16 KiB)
-inline int small_rows_per_wave(int n) { return 64 >> ((n < 4 ? 4 : n) - 4); }
-inline int64_t small_mats_per_wave(const CircDev& c) {
-    if (c.reupload + c.n_rot == 0) return 0;
-    return (int64_t)(c.reupload ? small_rows_per_wave(c.n) : 1) * c.n_layers * c.n;
+constexpr int kSmallMats = 512;   // matrices a workgroup keeps in LDS (16 KiB)
+inline int small_rows_per_group(int n, int regs) {
+    const int tb = n > regs ? n - regs : 0;
+    return tb < 6 ? 64 >> tb : 1;
 }
-hipError_t launch_forward_small(const float* x, int64_t dim, int64_t batch, const CircDev& c, int entangler,
+inline int64_t small_mats_per_group(const CircDev& c, int regs) {
+    if (c.reupload + c.n_rot == 0) return 0;
+    return (int64_t)(c.reupload ? small_rows_per_group(c.n, regs) : 1) * c.n_layers * c.n;
+}
+// Amplitudes per thread: the most that still gives the chip about four wavefronts per SIMD (4096), else the
+// fewest; among those only what fits the matrix limit.  0: nothing fits.
+inline int small_choose_regs(const CircDev& c, int64_t batch) {
+    int fallback = 0;
+    for (int r = 4; r >= 2; --r) {
+        if (c.n - r > 8 || small_mats_per_group(c, r) > kSmallMats) continue;
+        const int rows_g = small_rows_per_group(c.n, r);
+        const int tb = c.n > r ? c.n - r : 0;
+        const int64_t waves = ((batch + rows_g - 1) / rows_g) * (tb > 6 ? 1 << (tb - 6) : 1);
+        if (waves >= 4096) return r;
+        fallback = r;             // the smallest that fits so far
+    }
+    return fallback;
+}
+hipError_t launch_forward_small(int regs, const float* x, int64_t dim, int64_t batch, const CircDev& c, int entangler,
                                 const float* params, const float* feats, int decode, int kind, float2* state,
                                 float* out, float* norm_out, hipStream_t st);
 hipError_t launch_encode_write(const float* x, int64_t dim, int n, int64_t rows, const double* inv_norm,

@@ -1749,13 +1749,16 @@ __global__ __launch_bounds__(256) void k_adam(float* p, const float* g, float* m
 
 // ------------------------------------------------------------------------------------------
 // A whole small workload in one launch (at most 10 qubits): amplitude encoding, the circuit (and,
-// as decoder, its exact inverse), the final state and one measurement.  One wavefront holds 2^10
-// amplitudes: 16 per lane in registers (index bits 0..3), index bits 4..n-1 in the low lane bits,
-// and the remaining lane bits number the 2^(10-n) samples that share the wavefront.  A gate on a
-// register bit pairs registers, a gate on a lane bit exchanges with the partner lane
-// (ds_bpermute); nothing goes through memory between the gates.  The matrices are built once per
-// wavefront, one per lane at a time, and kept in LDS.
-struct Amps { float re[16], im[16]; };  // every index is a compile-time constant after unrolling
+// as decoder, its exact inverse), the final state and one measurement.  A thread keeps 2^R
+// amplitudes in registers (index bits 0..R-1), the index bits above are bits of the thread number:
+// up to six inside the wavefront, the rest across the wavefronts of the workgroup; with fewer than
+// six the spare lane bits number the samples that share the wavefront.  A gate on a register bit
+// pairs registers; on a lane bit it exchanges with the partner lane (DPP, the LDS crossbar);
+// on a bit across wavefronts it exchanges through LDS.  Nothing goes to device memory between the
+// gates.  R = 2, 3 or 4 is chosen so that the batch gives the chip enough wavefronts (a lone
+// wavefront on a SIMD issues one vector instruction in about eight cycles, four of them one every
+// three).  The matrices are built once per workgroup, one per thread at a time, and kept in LDS.
+template <int R> struct Amps { float re[1 << R], im[1 << R]; };  // every index is a compile-time constant after unrolling
 
 __device__ __forceinline__ float lane_xchg(int addr, float v) {
     return __int_as_float(__builtin_amdgcn_ds_bpermute(addr, __float_as_int(v)));
@@ -1777,11 +1780,35 @@ __device__ __forceinline__ float lane_flip(float v, int addr) {
     else return lane_xchg(addr, v);
 }
 
-// m = (m00r, m00i, m01r, m01i, m10r, m10i, m11r, m11i)
-template <int J>
-__device__ __forceinline__ void small_u_reg(Amps& a, const float* m) {
+// Exchange between the wavefronts of a workgroup: every thread puts its registers into the current
+// one of two buffers [2 * 2^R][threads], and after the barrier reads another thread's.  The
+// buffers alternate, so one barrier per exchange is enough (whoever writes a buffer again has
+// passed the barrier of the exchange in between, which every reader of the old contents reaches
+// only after reading).
+struct Xchg { float* buf; int threads, cur; };
+
+template <int R>
+__device__ __forceinline__ void xchg_through_lds(const Amps<R>& a, float* pr, float* pi, Xchg& x, int tid, int src) {
+    float* b = x.buf + (size_t)x.cur * (2 << R) * x.threads;
 #pragma unroll
-    for (int k = 0; k < 16; ++k) {
+    for (int k = 0; k < (1 << R); ++k) {
+        b[(2 * k) * x.threads + tid] = a.re[k];
+        b[(2 * k + 1) * x.threads + tid] = a.im[k];
+    }
+    __syncthreads();
+#pragma unroll
+    for (int k = 0; k < (1 << R); ++k) {
+        pr[k] = b[(2 * k) * x.threads + src];
+        pi[k] = b[(2 * k + 1) * x.threads + src];
+    }
+    x.cur ^= 1;
+}
+
+// m = (m00r, m00i, m01r, m01i, m10r, m10i, m11r, m11i)
+template <int R, int J>
+__device__ __forceinline__ void small_u_reg(Amps<R>& a, const float* m) {
+#pragma unroll
+    for (int k = 0; k < (1 << R); ++k) {
         if (k & (1 << J)) continue;
         const int k1 = k | (1 << J);
         const float ar = a.re[k], ai = a.im[k], br = a.re[k1], bi = a.im[k1];
@@ -1792,102 +1819,115 @@ __device__ __forceinline__ void small_u_reg(Amps& a, const float* m) {
     }
 }
 
-// The qubit is lane bit B: this lane holds the amplitudes with the bit equal to its own lane bit,
-// the partner lane the ones with the other value.
-template <int B>
-__device__ __forceinline__ void small_u_lane(Amps& a, const float* m, int lane) {
-    const bool bit = (lane >> B) & 1;
-    const int addr = (lane ^ (1 << B)) << 2;
+// The qubit is bit B of the thread number: this thread holds the amplitudes with the bit equal to
+// its own, the partner thread the ones with the other value.
+template <int R, int B>
+__device__ __forceinline__ void small_u_thr(Amps<R>& a, const float* m, int tid, Xchg& x) {
+    constexpr int NR = 1 << R;
+    const bool bit = (tid >> B) & 1;
     const float sr = bit ? m[6] : m[0], si = bit ? m[7] : m[1];   // row `bit`, own column
     const float qr = bit ? m[4] : m[2], qi = bit ? m[5] : m[3];   // row `bit`, the partner's column
-    float pr[16], pi[16];                    // all exchanges first: their latencies overlap
+    float pr[NR], pi[NR];                    // all exchanges first: their latencies overlap
+    if constexpr (B < 6) {
+        const int addr = ((tid & 63) ^ (1 << B)) << 2;
 #pragma unroll
-    for (int k = 0; k < 16; ++k) { pr[k] = lane_flip<B>(a.re[k], addr); pi[k] = lane_flip<B>(a.im[k], addr); }
+        for (int k = 0; k < NR; ++k) { pr[k] = lane_flip<B>(a.re[k], addr); pi[k] = lane_flip<B>(a.im[k], addr); }
+    } else {
+        xchg_through_lds<R>(a, pr, pi, x, tid, tid ^ (1 << B));
+    }
 #pragma unroll
-    for (int k = 0; k < 16; ++k) {
+    for (int k = 0; k < NR; ++k) {
         const float ar = a.re[k], ai = a.im[k];
         a.re[k] = sr * ar - si * ai + qr * pr[k] - qi * pi[k];
         a.im[k] = sr * ai + si * ar + qr * pi[k] + qi * pr[k];
     }
 }
 
-template <int C, int T>
-__device__ __forceinline__ void small_cx_rr(Amps& a) {
+template <int R, int C, int T>
+__device__ __forceinline__ void small_cx_rr(Amps<R>& a) {
+    if constexpr (C < R && T < R) {
 #pragma unroll
-    for (int k = 0; k < 16; ++k) {
-        if (!(k & (1 << C)) || (k & (1 << T))) continue;
-        const int k1 = k | (1 << T);
-        const float r = a.re[k], i = a.im[k];
-        a.re[k] = a.re[k1]; a.im[k] = a.im[k1];
-        a.re[k1] = r; a.im[k1] = i;
+        for (int k = 0; k < (1 << R); ++k) {
+            if (!(k & (1 << C)) || (k & (1 << T))) continue;
+            const int k1 = k | (1 << T);
+            const float r = a.re[k], i = a.im[k];
+            a.re[k] = a.re[k1]; a.im[k] = a.im[k1];
+            a.re[k1] = r; a.im[k1] = i;
+        }
     }
 }
 
-template <int T>
-__device__ __forceinline__ void small_cx_lr(Amps& a, bool ctrl) {  // control on a lane bit, target in registers
+template <int R>
+__device__ __forceinline__ void small_cx_to_reg0(Amps<R>& a, bool ctrl) {  // control on a thread bit, target register bit 0
 #pragma unroll
-    for (int k = 0; k < 16; ++k) {
-        if (k & (1 << T)) continue;
-        const int k1 = k | (1 << T);
-        const float r0 = a.re[k], i0 = a.im[k], r1 = a.re[k1], i1 = a.im[k1];
+    for (int k = 0; k < (1 << R); k += 2) {
+        const float r0 = a.re[k], i0 = a.im[k], r1 = a.re[k + 1], i1 = a.im[k + 1];
         a.re[k] = ctrl ? r1 : r0; a.im[k] = ctrl ? i1 : i0;
-        a.re[k1] = ctrl ? r0 : r1; a.im[k1] = ctrl ? i0 : i1;
+        a.re[k + 1] = ctrl ? r0 : r1; a.im[k + 1] = ctrl ? i0 : i1;
     }
-}
-
-// every register takes the value that lane addr / 4 holds (a permutation of the lanes)
-__device__ __forceinline__ void small_lane_perm(Amps& a, int addr) {
-    float pr[16], pi[16];
-#pragma unroll
-    for (int k = 0; k < 16; ++k) { pr[k] = lane_xchg(addr, a.re[k]); pi[k] = lane_xchg(addr, a.im[k]); }
-#pragma unroll
-    for (int k = 0; k < 16; ++k) { a.re[k] = pr[k]; a.im[k] = pi[k]; }
 }
 
 // The CNOT ring on n qubits, control q, target q + 1 (the last one's target is qubit 0), in order,
 // or with reverse = true in the opposite order (the ring's inverse).  The CNOTs between register
-// bits rename registers, the one from register bit 3 to lane bit 0 exchanges half of the registers
-// with the neighbouring lane, the CNOTs between lane bits (qubits 4..n-1) are together one
-// permutation of the lanes (chain_f / chain_r: for each lane, four times the lane it reads from),
-// and the closing one swaps register pairs in the lanes whose top index bit is set.
-__device__ __forceinline__ void small_ring(Amps& a, int n, int lane, bool reverse, int chain_f, int chain_r) {
+// bits rename registers; the one from the top register bit to thread bit 0 exchanges half of the
+// registers with the neighbouring lane; the CNOTs between thread bits are together one
+// permutation of the threads (src_f / src_r: the thread each one reads from), done by
+// ds_bpermute inside a wavefront and through LDS across wavefronts; the closing one swaps register
+// pairs in the threads whose top index bit is set.
+template <int R>
+__device__ __forceinline__ void small_ring(Amps<R>& a, int n, int tid, int tb, bool reverse, int src_f, int src_r,
+                                           Xchg& x) {
+    constexpr int NR = 1 << R;
     auto wrap = [&]() {
-        if (n == 2) small_cx_rr<1, 0>(a);
-        else if (n == 3) small_cx_rr<2, 0>(a);
-        else if (n == 4) small_cx_rr<3, 0>(a);
-        else if (n > 4) small_cx_lr<0>(a, (lane >> (n - 5)) & 1);
+        if (n > R) small_cx_to_reg0<R>(a, (tid >> (tb - 1)) & 1);
+        else if (n == 2) small_cx_rr<R, 1, 0>(a);
+        else if (n == 3) small_cx_rr<R, 2, 0>(a);
+        else if (n == 4) small_cx_rr<R, 3, 0>(a);
     };
-    auto bridge = [&]() {                          // control register bit 3, target lane bit 0
-        if (n > 4) {
+    auto bridge = [&]() {                          // control register bit R - 1, target thread bit 0
+        if (n > R) {
 #pragma unroll
-            for (int k = 8; k < 16; ++k) { a.re[k] = lane_flip<0>(a.re[k], 0); a.im[k] = lane_flip<0>(a.im[k], 0); }
+            for (int k = NR / 2; k < NR; ++k) { a.re[k] = lane_flip<0>(a.re[k], 0); a.im[k] = lane_flip<0>(a.im[k], 0); }
         }
     };
+    auto chain = [&](int src) {
+        if (tb < 2) return;
+        float pr[NR], pi[NR];
+        if (tb <= 6) {
+            const int addr = src << 2;             // src differs from tid in lane bits only
+#pragma unroll
+            for (int k = 0; k < NR; ++k) { pr[k] = lane_xchg(addr, a.re[k]); pi[k] = lane_xchg(addr, a.im[k]); }
+        } else {
+            xchg_through_lds<R>(a, pr, pi, x, tid, src);
+        }
+#pragma unroll
+        for (int k = 0; k < NR; ++k) { a.re[k] = pr[k]; a.im[k] = pi[k]; }
+    };
     if (!reverse) {
-        if (n >= 2) small_cx_rr<0, 1>(a);
-        if (n >= 3) small_cx_rr<1, 2>(a);
-        if (n >= 4) small_cx_rr<2, 3>(a);
+        if (n >= 2) small_cx_rr<R, 0, 1>(a);
+        if (n >= 3) small_cx_rr<R, 1, 2>(a);
+        if (n >= 4) small_cx_rr<R, 2, 3>(a);
         bridge();
-        if (n > 5) small_lane_perm(a, chain_f);
+        chain(src_f);
         wrap();
     } else {
         wrap();
-        if (n > 5) small_lane_perm(a, chain_r);
+        chain(src_r);
         bridge();
-        if (n >= 4) small_cx_rr<2, 3>(a);
-        if (n >= 3) small_cx_rr<1, 2>(a);
-        if (n >= 2) small_cx_rr<0, 1>(a);
+        if (n >= 4) small_cx_rr<R, 2, 3>(a);
+        if (n >= 3) small_cx_rr<R, 1, 2>(a);
+        if (n >= 2) small_cx_rr<R, 0, 1>(a);
     }
 }
 
 // CZ on qubits q and q + 1 for q = 0..n-2 (the gates commute, so the order does not matter): the
-// sign of an amplitude changes once for every pair of neighbouring set bits.
-__device__ __forceinline__ void small_cz_ladder(Amps& a, int n, int lane) {
-    const int li = lane & ((1 << ((n < 4 ? 4 : n) - 4)) - 1);
+// sign of an amplitude changes once for every pair of neighbouring set bits of its index.
+template <int R>
+__device__ __forceinline__ void small_cz_ladder(Amps<R>& a, int n, int ti) {
+    const int mask = (1 << (n - 1)) - 1;           // pairs (q, q + 1) for q = 0..n-2
 #pragma unroll
-    for (int k = 0; k < 16; ++k) {
-        const int idx = (li << 4) | k;
-        const int mask = (1 << (n - 1)) - 1;     // pairs (q, q + 1) for q = 0..n-2
+    for (int k = 0; k < (1 << R); ++k) {
+        const int idx = (ti << R) | k;
         const bool f = __builtin_popcount(idx & (idx >> 1) & mask) & 1;
         a.re[k] = f ? -a.re[k] : a.re[k];
         a.im[k] = f ? -a.im[k] : a.im[k];
@@ -1908,22 +1948,33 @@ struct SmallArgs {
     float* norm_out;       // [batch] or NULL
 };
 
-__global__ __launch_bounds__(64) void k_forward_small(SmallArgs a) {
-    __shared__ __align__(16) float mats[kSmallMats * 8];
-    const int lane = threadIdx.x;
+// dynamic LDS: [64] doubles for sums across wavefronts, kSmallMats matrices, then the exchange buffers
+template <int R>
+__global__ __launch_bounds__(256) void k_forward_small(SmallArgs a) {
+    constexpr int NR = 1 << R;
+    extern __shared__ __align__(16) unsigned char small_lds[];
+    double* red = reinterpret_cast<double*>(small_lds);
+    float* mats = reinterpret_cast<float*>(small_lds + 64 * sizeof(double));
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int n = a.c.n, L = a.c.n_layers;
-    const int lb = (n < 4 ? 4 : n) - 4;          // lane bits that are index bits
-    const int rows_w = 64 >> lb;                 // samples per wavefront
-    const int r_in = lane >> lb;
-    const int li = lane & ((1 << lb) - 1);
-    const int64_t first = (int64_t)blockIdx.x * rows_w;
+    const int tb = n > R ? n - R : 0;            // index bits held by the thread number
+    const int lb = tb < 6 ? tb : 6;              // of which inside the wavefront
+    const int n_waves = (int)blockDim.x >> 6;    // 2^(tb - 6) when tb > 6, else 1
+    const int rows_g = 64 >> lb;                 // samples per workgroup (1 when tb >= 6)
+    const int r_in = tb < 6 ? lane >> tb : 0;
+    const int ti = tid & ((1 << tb) - 1);
+    Xchg xc;
+    xc.buf = mats + kSmallMats * 8;
+    xc.threads = (int)blockDim.x;
+    xc.cur = 0;
+    const int64_t first = (int64_t)blockIdx.x * rows_g;
     const int64_t sample = first + r_in;
     const bool live = sample < a.batch;
     const int per = L * n;
     const bool has_u = a.c.reupload + a.c.n_rot > 0;
     if (has_u) {
-        const int rows_m = a.c.reupload ? rows_w : 1;
-        for (int i = lane; i < rows_m * per; i += 64) {
+        const int rows_m = a.c.reupload ? rows_g : 1;
+        for (int i = tid; i < rows_m * per; i += (int)blockDim.x) {
             const int r = i / per, lq = i % per;
             const int64_t s = first + r < a.batch ? first + r : a.batch - 1;
             const M2 u = fused_raw(a.c, a.params, a.feats, (u64)s, lq / n, lq % n, -1, 0.0, 0);
@@ -1933,15 +1984,14 @@ __global__ __launch_bounds__(64) void k_forward_small(SmallArgs a) {
         }
     }
     // amplitude encoding: x / ||x||, the norm in double
-    Amps A;
-    float nrm_f;
+    Amps<R> A;
     {
         const float* xb = a.x + (live ? sample : 0) * a.dim;
-        float xv[16];
+        float xv[NR];
         double ss = 0.0;
 #pragma unroll
-        for (int k = 0; k < 16; ++k) {
-            const int64_t idx = ((int64_t)li << 4) | k;
+        for (int k = 0; k < NR; ++k) {
+            const int64_t idx = ((int64_t)ti << R) | k;
             const float v = (live && idx < a.dim) ? xb[idx] : 0.f;
             xv[k] = v;
             ss += (double)v * (double)v;
@@ -1949,31 +1999,34 @@ __global__ __launch_bounds__(64) void k_forward_small(SmallArgs a) {
 #pragma unroll
         for (int b = 0; b < 6; ++b)
             if (b < lb) ss += __shfl_xor(ss, 1 << b, 64);
+        if (n_waves > 1) {
+            if (lane == 0) red[wave] = ss;
+            __syncthreads();
+            ss = 0.0;
+            for (int w = 0; w < n_waves; ++w) ss += red[w];
+        }
         const double nrm = sqrt(ss);
         const double inv = nrm > 0.0 ? 1.0 / nrm : 0.0;
 #pragma unroll
-        for (int k = 0; k < 16; ++k) { A.re[k] = (float)((double)xv[k] * inv); A.im[k] = 0.f; }
-        nrm_f = (float)nrm;
+        for (int k = 0; k < NR; ++k) { A.re[k] = (float)((double)xv[k] * inv); A.im[k] = 0.f; }
+        if (a.norm_out && live && ti == 0) a.norm_out[sample] = (float)nrm;
     }
-    if (a.norm_out && live && li == 0) a.norm_out[sample] = nrm_f;
-    __syncthreads();
+    __syncthreads();                             // the matrices are in LDS; red[] may be written again
+    const float* mrow = mats + (size_t)(a.c.reupload ? r_in * per : 0) * 8;
+    // Thread permutations of the ring's CNOTs between thread bits (qubits R..n-1): an amplitude in
+    // thread j moves to C(j), so afterwards thread j holds what thread C_first(...C_last(j)) held.
+    int src_f = tid, src_r = tid;
+    for (int b = tb - 2; b >= 0; --b) src_f ^= ((src_f >> b) & 1) << (b + 1);
+    for (int b = 0; b + 1 < tb; ++b) src_r ^= ((src_r >> b) & 1) << (b + 1);
     // the gates: per layer the unitaries then the entangler; in the decoder layers last to first,
     // the entangler's gates in reverse order first, then the conjugate-transposed unitaries
-    const float* mrow = mats + (size_t)(a.c.reupload ? r_in * per : 0) * 8;
-    // lane permutations of the ring's CNOTs between lane bits (qubits 4..n-1): an amplitude at
-    // lane j moves to C(j), so afterwards lane j holds what lane C_first(...C_last(j)) held
-    int chain_f = lane, chain_r = lane;
-    for (int b = lb - 2; b >= 0; --b) chain_f ^= ((chain_f >> b) & 1) << (b + 1);
-    for (int b = 0; b + 1 < lb; ++b) chain_r ^= ((chain_r >> b) & 1) << (b + 1);
-    chain_f = (chain_f | (lane & ~((1 << lb) - 1))) << 2;
-    chain_r = (chain_r | (lane & ~((1 << lb) - 1))) << 2;
     for (int pass = 0; pass <= a.decode; ++pass) {
         for (int ll = 0; ll < L; ++ll) {
             const int l = pass ? L - 1 - ll : ll;
             for (int stage = 0; stage < 2; ++stage) {
                 if ((stage == 0) == (pass == 1)) {
-                    if (a.entangler == QSV_ENT_CNOT_RING) small_ring(A, n, lane, pass != 0, chain_f, chain_r);
-                    else if (a.entangler == QSV_ENT_CZ_LADDER) small_cz_ladder(A, n, lane);
+                    if (a.entangler == QSV_ENT_CNOT_RING) small_ring<R>(A, n, tid, tb, pass != 0, src_f, src_r, xc);
+                    else if (a.entangler == QSV_ENT_CZ_LADDER) small_cz_ladder<R>(A, n, ti);
                 } else if (has_u) {
                     const float* ml = mrow + (size_t)l * n * 8;
                     auto load_m = [&](int q, float* m) {
@@ -1982,18 +2035,21 @@ __global__ __launch_bounds__(64) void k_forward_small(SmallArgs a) {
                         if (!pass) {
                             m[0] = lo.x; m[1] = lo.y; m[2] = lo.z; m[3] = lo.w;
                             m[4] = hi.x; m[5] = hi.y; m[6] = hi.z; m[7] = hi.w;
-                        } else {
+                        } else {                 // conjugate transpose
                             m[0] = lo.x; m[1] = -lo.y; m[2] = hi.x; m[3] = -hi.y;
                             m[4] = lo.z; m[5] = -lo.w; m[6] = hi.z; m[7] = -hi.w;
                         }
                     };
                     float m[8];
-#define QSV_SMALL_UR(Q) if (n > Q) { load_m(Q, m); small_u_reg<Q>(A, m); }
-#define QSV_SMALL_UL(Q) if (n > Q) { load_m(Q, m); small_u_lane<Q - 4>(A, m, lane); }
-                    QSV_SMALL_UR(0) QSV_SMALL_UR(1) QSV_SMALL_UR(2) QSV_SMALL_UR(3)
-                    QSV_SMALL_UL(4) QSV_SMALL_UL(5) QSV_SMALL_UL(6) QSV_SMALL_UL(7) QSV_SMALL_UL(8) QSV_SMALL_UL(9)
-#undef QSV_SMALL_UR
-#undef QSV_SMALL_UL
+#define QSV_SMALL_U(Q)                                                      \
+    if (n > Q) {                                                            \
+        load_m(Q, m);                                                       \
+        if constexpr (Q < R) small_u_reg<R, Q>(A, m);                       \
+        else if constexpr (Q - R < 8) small_u_thr<R, Q - R>(A, m, tid, xc); \
+    }
+                    QSV_SMALL_U(0) QSV_SMALL_U(1) QSV_SMALL_U(2) QSV_SMALL_U(3) QSV_SMALL_U(4)
+                    QSV_SMALL_U(5) QSV_SMALL_U(6) QSV_SMALL_U(7) QSV_SMALL_U(8) QSV_SMALL_U(9)
+#undef QSV_SMALL_U
                 }
             }
         }
@@ -2001,50 +2057,52 @@ __global__ __launch_bounds__(64) void k_forward_small(SmallArgs a) {
     // final state and the measurement
     const int dimn = 1 << n;
     if (live) {
-        float2* srow = a.state + (sample << n) + (li << 4);
-        if (n >= 4) {
+        float2* srow = a.state + (sample << n) + ((int64_t)ti << R);
+        if (n >= R) {
 #pragma unroll
-            for (int k = 0; k < 16; k += 2)
+            for (int k = 0; k < NR; k += 2)
                 *reinterpret_cast<float4*>(srow + k) = make_float4(A.re[k], A.im[k], A.re[k + 1], A.im[k + 1]);
         } else {
 #pragma unroll
-            for (int k = 0; k < 8; ++k)
+            for (int k = 0; k < NR; ++k)
                 if (k < dimn) srow[k] = make_float2(A.re[k], A.im[k]);
         }
     }
-    float p[16];
+    float p[NR];
 #pragma unroll
-    for (int k = 0; k < 16; ++k) p[k] = prob32(make_float2(A.re[k], A.im[k]));
+    for (int k = 0; k < NR; ++k) p[k] = prob32(make_float2(A.re[k], A.im[k]));
     if (a.kind == QSV_M_PROBS) {
         if (live) {
-            float* prow = a.out + (sample << n) + (li << 4);
-            if (n >= 4) {
+            float* prow = a.out + (sample << n) + ((int64_t)ti << R);
+            if (n >= R) {
 #pragma unroll
-                for (int k = 0; k < 16; k += 4)
+                for (int k = 0; k < NR; k += 4)
                     *reinterpret_cast<float4*>(prow + k) = make_float4(p[k], p[k + 1], p[k + 2], p[k + 3]);
             } else {
 #pragma unroll
-                for (int k = 0; k < 8; ++k)
+                for (int k = 0; k < NR; ++k)
                     if (k < dimn) prow[k] = p[k];
             }
         }
         return;
     }
-    // <Z_q> for every qubit: signed sums in double, combined over the lanes of the sample
-    double T = 0.0, zr[4] = {0.0, 0.0, 0.0, 0.0}, zl[6] = {0.0, 0.0, 0.0, 0.0, 0.0, 0.0};
+    // <Z_q> for every qubit: signed sums in double, combined over the threads of the sample
+    double T = 0.0, zr[R], zl[6] = {0.0, 0.0, 0.0, 0.0, 0.0, 0.0};
 #pragma unroll
-    for (int k = 0; k < 16; ++k) {
+    for (int j = 0; j < R; ++j) zr[j] = 0.0;
+#pragma unroll
+    for (int k = 0; k < NR; ++k) {
         const double pk = (double)p[k];
         T += pk;
 #pragma unroll
-        for (int j = 0; j < 4; ++j) zr[j] += ((k >> j) & 1) ? -pk : pk;
+        for (int j = 0; j < R; ++j) zr[j] += ((k >> j) & 1) ? -pk : pk;
     }
 #pragma unroll
     for (int b = 0; b < 6; ++b) {
         if (b < lb) {
             const double Tp = __shfl_xor(T, 1 << b, 64);
 #pragma unroll
-            for (int j = 0; j < 4; ++j) zr[j] += __shfl_xor(zr[j], 1 << b, 64);
+            for (int j = 0; j < R; ++j) zr[j] += __shfl_xor(zr[j], 1 << b, 64);
 #pragma unroll
             for (int j = 0; j < 6; ++j)
                 if (j < b) zl[j] += __shfl_xor(zl[j], 1 << b, 64);
@@ -2052,11 +2110,35 @@ __global__ __launch_bounds__(64) void k_forward_small(SmallArgs a) {
             T += Tp;
         }
     }
-    if (live && li == 0) {
-        float* orow = a.out + sample * n;
+    if (n_waves == 1) {
+        if (live && ti == 0) {
+            float* orow = a.out + sample * n;
 #pragma unroll
-        for (int q = 0; q < 10; ++q)
-            if (q < n) orow[q] = (float)(q < 4 ? zr[q] : zl[q - 4]);
+            for (int q = 0; q < 10; ++q)
+                if (q < n) orow[q] = (float)(q < R ? zr[q < R ? q : 0] : zl[q >= R && q - R < 6 ? q - R : 0]);
+        }
+        return;
+    }
+    // several wavefronts hold the sample: totals per wavefront through LDS, thread q adds up qubit q
+    // (qubits beyond the lane bits take the wavefront totals signed by the wavefront's number)
+    if (lane == 0) {
+        double* o = red + wave * 16;
+        o[0] = T;
+#pragma unroll
+        for (int j = 0; j < R; ++j) o[1 + j] = zr[j];
+#pragma unroll
+        for (int j = 0; j < 6; ++j) o[1 + R + j] = zl[j];
+    }
+    __syncthreads();
+    if (tid < n && live) {
+        const int q = tid;
+        double acc = 0.0;
+        for (int w = 0; w < n_waves; ++w) {
+            const double* o = red + w * 16;
+            if (q < R + 6) acc += o[1 + q];
+            else acc += ((w >> (q - R - 6)) & 1) ? -o[0] : o[0];
+        }
+        a.out[sample * n + q] = (float)acc;
     }
 }
 
@@ -2192,19 +2274,30 @@ hipError_t launch_encode_small(const float* x, int64_t samples, int64_t dim, int
     return hipGetLastError();
 }
 
-hipError_t launch_forward_small(const float* x, int64_t dim, int64_t batch, const CircDev& c, int entangler,
+hipError_t launch_forward_small(int regs, const float* x, int64_t dim, int64_t batch, const CircDev& c, int entangler,
                                 const float* params, const float* feats, int decode, int kind, float2* state,
                                 float* out, float* norm_out, hipStream_t st) {
     if (c.n < 1 || c.n > kSmallMaxQubits || batch < 1 || dim < 1 || dim > ((int64_t)1 << c.n))
         return hipErrorInvalidValue;
-    if (small_mats_per_wave(c) > kSmallMats) return hipErrorInvalidValue;
-    const int rows_w = small_rows_per_wave(c.n);
+    if (regs < 2 || regs > 4 || c.n - regs > 8) return hipErrorInvalidValue;
+    if (small_mats_per_group(c, regs) > kSmallMats) return hipErrorInvalidValue;
+    const int rows_g = small_rows_per_group(c.n, regs);
+    const int tb = c.n > regs ? c.n - regs : 0;
+    const unsigned threads = tb > 6 ? 64u << (tb - 6) : 64u;
     SmallArgs a;
     a.x = x; a.dim = dim; a.batch = batch; a.c = c; a.entangler = entangler; a.params = params; a.feats = feats;
     a.decode = decode; a.kind = kind; a.state = state; a.out = out; a.norm_out = norm_out;
-    const int64_t blocks = (batch + rows_w - 1) / rows_w;
+    const int64_t blocks = (batch + rows_g - 1) / rows_g;
     if (blocks > 0x7fffffff) return hipErrorInvalidValue;
-    hipLaunchKernelGGL(k_forward_small, dim3((unsigned)blocks), dim3(64), 0, st, a);
+    // sums across wavefronts, the matrices, and (several wavefronts per sample only) two exchange buffers
+    size_t lds = 64 * sizeof(double) + (size_t)kSmallMats * 8 * sizeof(float);
+    if (threads > 64) lds += 2 * (size_t)(2 << regs) * threads * sizeof(float);
+    const dim3 grid((unsigned)blocks), block(threads);
+    switch (regs) {
+        case 2: hipLaunchKernelGGL(k_forward_small<2>, grid, block, lds, st, a); break;
+        case 3: hipLaunchKernelGGL(k_forward_small<3>, grid, block, lds, st, a); break;
+        default: hipLaunchKernelGGL(k_forward_small<4>, grid, block, lds, st, a); break;
+    }
     return hipGetLastError();
 }
 

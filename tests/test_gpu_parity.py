@@ -633,32 +633,41 @@ def test_forward_small_equals_the_oracle_and_the_separate_calls(oracle, n, B, di
     xd, pd = gu.dev(x), gu.dev(params if params.size else np.zeros(1, np.float32))
     fd = gu.dev(feats) if reup else None
     ctx = gu.make_ctx(n, B)
-    for kind, shape in ((qb.QSV_M_PROBS, (B, 1 << n)), (qb.QSV_M_EXPZ_ALL, (B, n))):
-        ctx.state.fill_(9.0)
-        out = torch.full(shape, -7.0, dtype=torch.float32, device="cuda")
-        norm_out = torch.full((B,), -1.0, dtype=torch.float32, device="cuda")
-        ctx.qsv_forward_small(xd, circ, pd, fd, decode, kind, out, norm_out)
-        got = gu.state_np(ctx)
-        assert not np.isnan(got).any()
-        assert np.abs(got - ref).max() <= amp_tol(n)
-        assert np.allclose(norm_out.cpu().numpy(), nrm, rtol=2e-7)
-        o = out.cpu().numpy()
-        if kind == qb.QSV_M_PROBS:
-            live = nrm > 0
-            gu.prob_checks(o[live], oracle.probs(ref)[live])
-            assert np.all(o[~live] == 0)
-            assert np.array_equal(o, gu.measure(ctx, qb.QSV_M_PROBS, shape))   # same float32 function of the state
-        else:
-            assert np.abs(o - oracle.expz_all(ref)).max() <= 1e-5
-        # the separate calls
-        ctx2 = gu.make_ctx(n, B)
-        ctx2.qsv_amp_encode(xd)
-        ctx2.qsv_apply_layers(circ, pd, fd, 0)
-        if decode:
-            ctx2.qsv_apply_layers(circ, pd, fd, 1)
-        assert np.abs(gu.state_np(ctx2) - got).max() <= 1e-5
-        assert np.abs(gu.measure(ctx2, kind, shape) - o).max() <= 1e-5
-        ctx2.close()
+    ctx2 = gu.make_ctx(n, B)                      # the separate calls
+    ctx2.qsv_amp_encode(xd)
+    ctx2.qsv_apply_layers(circ, pd, fd, 0)
+    if decode:
+        ctx2.qsv_apply_layers(circ, pd, fd, 1)
+    sep_state = gu.state_np(ctx2)
+    served = 0
+    for regs in (0, 2, 3, 4):                     # amplitudes per thread: chosen by the library, 4, 8, 16
+        ctx.qsv_set_option("small_regs", regs)
+        for kind, shape in ((qb.QSV_M_PROBS, (B, 1 << n)), (qb.QSV_M_EXPZ_ALL, (B, n))):
+            ctx.state.fill_(9.0)
+            out = torch.full(shape, -7.0, dtype=torch.float32, device="cuda")
+            norm_out = torch.full((B,), -1.0, dtype=torch.float32, device="cuda")
+            try:
+                ctx.qsv_forward_small(xd, circ, pd, fd, decode, kind, out, norm_out)
+            except qb.QsvError as e:              # a forced size may not fit the matrix limit; the default must
+                assert regs != 0 and e.status == qb.QSV_ERR_UNSUPPORTED
+                continue
+            served += 1
+            got = gu.state_np(ctx)
+            assert not np.isnan(got).any()
+            assert np.abs(got - ref).max() <= amp_tol(n), regs
+            assert np.allclose(norm_out.cpu().numpy(), nrm, rtol=2e-7)
+            o = out.cpu().numpy()
+            if kind == qb.QSV_M_PROBS:
+                live = nrm > 0
+                gu.prob_checks(o[live], oracle.probs(ref)[live])
+                assert np.all(o[~live] == 0)
+                assert np.array_equal(o, gu.measure(ctx, qb.QSV_M_PROBS, shape))   # same float32 function of the state
+            else:
+                assert np.abs(o - oracle.expz_all(ref)).max() <= 1e-5, regs
+            assert np.abs(sep_state - got).max() <= 1e-5
+            assert np.abs(gu.measure(ctx2, kind, shape) - o).max() <= 1e-5
+    assert served >= 4
+    ctx2.close()
     ctx.close()
 
 
@@ -667,7 +676,7 @@ def test_forward_small_refuses_what_it_does_not_serve():
     circ = qb.make_circuit(2, [RY], RING, 0)
     for n, B, c in ((11, 2, circ),                                   # more than 10 qubits
                     (10, 1, qb.make_circuit(52, [RY], RING, 0)),     # 520 matrices
-                    (4, 64, qb.make_circuit(3, [RY], RING, 1))):     # 64 samples x 3 layers x 4 qubits
+                    (4, 64, qb.make_circuit(40, [RY], RING, 1))):    # at best 16 samples x 40 layers x 4 qubits
         ctx = gu.make_ctx(n, B)
         x = torch.ones((B, 1 << n), dtype=torch.float32, device="cuda")
         P = max(1, qb.qsv_num_params(c, n))
