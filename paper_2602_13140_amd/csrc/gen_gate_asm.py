@@ -105,11 +105,15 @@ def u_pair(a, b, variant="g"):
     ]
 
 
+CHAIN_FORM = "move"     # "swap": every cycle by v_swap_b32
+
+
 def chain_swaps(direction, first, count):
-    """The chain's CNOTs (control c, target c + 1) as one permutation of the 16 register elements,
-    done with the fewest instructions: a cycle of k elements takes k - 1 swaps.  (Moves through a
-    temporary take k + 1; they are cheaper per instruction but what the heavy passes run out of is
-    issue slots: measured, the move form was 0.6 % slower on the 26-qubit configuration.)"""
+    """The chain's CNOTs (control c, target c + 1) as one permutation of the 16 register elements.  A cycle of
+    k elements takes k - 1 swaps (v_swap_b32, 8.2 cycles each) or k + 1 moves through a temporary (2.5
+    cycles each): cycles of two are swapped, longer ones moved.  Measured on one box, alternating the two
+    builds: moves take 0.8 % off the 26-qubit and 20-qubit configurations now that their passes are
+    heavy (when the passes were lighter and waited for memory the same change cost 0.6 %)."""
     src = list(range(NR))                  # src[i]: which old element ends up in place i
     for k in range(count):
         c = first + k if direction == 0 else first - k
@@ -127,6 +131,15 @@ def chain_swaps(direction, first, count):
             seen[cur] = True
             cyc.append(cur)
             cur = src[cur]
+        if CHAIN_FORM == "move" and len(cyc) > 2:
+            # place cyc[k] receives the old content of cyc[k+1]; the first one's goes round through a temporary
+            for part, tmp in (("r", "%[t0]"), ("i", "%[t1]")):
+                reg = lambda k: "%%[%s%d]" % (part, k)
+                out.append("v_mov_b32 %s, %s" % (tmp, reg(cyc[0])))
+                for a, b in zip(cyc, cyc[1:]):
+                    out.append("v_mov_b32 %s, %s" % (reg(a), reg(b)))
+                out.append("v_mov_b32 %s, %s" % (reg(cyc[-1]), tmp))
+            continue
         # place cyc[k] must receive the old content of cyc[k+1]: swap neighbours along the cycle
         for a, b in zip(cyc, cyc[1:]):
             out.extend(swap_pair(a, b))
