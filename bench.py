@@ -26,7 +26,7 @@ HBM_PEAK_GBS = 8000.0
 # HBM bytes per pass (config 3: a pair of launches) from rocprofv3 FETCH_SIZE / WRITE_SIZE, each scaled by what the same
 # counter reads for the load/store-only probe pass of known size (FETCH_SIZE x 2.000, WRITE_SIZE x
 # 1.000); the runs and their figures are in profiles/k_pass_hbm_traffic_counters.md.
-TRAFFIC_BYTES_PER_LAUNCH = {"c4": 1073995377, "c3": 537499121}
+TRAFFIC_BYTES_PER_LAUNCH = {"c4": 1073974797, "c3": 537444482}
 
 
 def parse_args():
