@@ -32,6 +32,13 @@ def test_config0_autoencoder_roundtrip(oracle):
     gu.prob_checks(p, oracle.probs(ref))
     xd64 = w.x.astype(np.float64)
     assert np.abs(p - xd64 ** 2 / (xd64 ** 2).sum(1, keepdims=True)).max() <= 1e-5   # closed form
+    # the same step in one launch
+    torch = gu.torch_cuda()
+    p1 = torch.full((w.batch, 1 << w.n), -7.0, dtype=torch.float32, device="cuda")
+    ctx.state.fill_(9.0)
+    ctx.qsv_forward_small(xd, circ, pd, None, 1, qb.QSV_M_PROBS, p1)
+    gu.prob_checks(p1.cpu().numpy(), oracle.probs(ref))
+    assert np.abs(gu.state_np(ctx) - ref).max() <= 2e-6
     ctx.close()
 
 
@@ -45,6 +52,16 @@ def test_config1_reupload_expz(oracle):
     oracle.apply_layers(ref, ocirc(oracle, w.circuit), w.params, w.feats)
     assert np.abs(z - oracle.expz_all(ref)).max() <= 1e-5
     assert np.abs(gu.state_np(ctx) - ref).max() <= 1e-5
+    # the same step in one launch, with every number of amplitudes per thread
+    torch = gu.torch_cuda()
+    circ, xd, pd, fd = qb.circuit_from_spec(w.circuit), gu.dev(w.x), gu.dev(w.params), gu.dev(w.feats)
+    for regs in (0, 2, 3, 4):
+        ctx.qsv_set_option("small_regs", regs)
+        z1 = torch.full((w.batch, w.n), -7.0, dtype=torch.float32, device="cuda")
+        ctx.state.fill_(9.0)
+        ctx.qsv_forward_small(xd, circ, pd, fd, 0, qb.QSV_M_EXPZ_ALL, z1)
+        assert np.abs(z1.cpu().numpy() - oracle.expz_all(ref)).max() <= 1e-5, regs
+        assert np.abs(gu.state_np(ctx) - ref).max() <= 1e-5, regs
     ctx.close()
 
 
