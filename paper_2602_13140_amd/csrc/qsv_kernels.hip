@@ -1946,9 +1946,10 @@ struct SmallArgs {
     float2* state;         // [batch][2^n], receives the final state
     float* out;            // probabilities [batch][2^n] or expectations [batch][n]
     float* norm_out;       // [batch] or NULL
+    int mat_floats;        // LDS floats set aside for the workgroup's matrices (a multiple of 8)
 };
 
-// dynamic LDS: [64] doubles for sums across wavefronts, kSmallMats matrices, then the exchange buffers
+// dynamic LDS: [64] doubles for sums across wavefronts, the workgroup's matrices, then the exchange buffers
 template <int R>
 __global__ __launch_bounds__(256) void k_forward_small(SmallArgs a) {
     constexpr int NR = 1 << R;
@@ -1964,7 +1965,7 @@ __global__ __launch_bounds__(256) void k_forward_small(SmallArgs a) {
     const int r_in = tb < 6 ? lane >> tb : 0;
     const int ti = tid & ((1 << tb) - 1);
     Xchg xc;
-    xc.buf = mats + kSmallMats * 8;
+    xc.buf = mats + a.mat_floats;
     xc.threads = (int)blockDim.x;
     xc.cur = 0;
     const int64_t first = (int64_t)blockIdx.x * rows_g;
@@ -2289,8 +2290,10 @@ hipError_t launch_forward_small(int regs, const float* x, int64_t dim, int64_t b
     a.decode = decode; a.kind = kind; a.state = state; a.out = out; a.norm_out = norm_out;
     const int64_t blocks = (batch + rows_g - 1) / rows_g;
     if (blocks > 0x7fffffff) return hipErrorInvalidValue;
-    // sums across wavefronts, the matrices, and (several wavefronts per sample only) two exchange buffers
-    size_t lds = 64 * sizeof(double) + (size_t)kSmallMats * 8 * sizeof(float);
+    // sums across wavefronts, the matrices (only as many as this circuit has: LDS per workgroup decides how
+    // many workgroups a CU holds), and (several wavefronts per sample only) two exchange buffers
+    a.mat_floats = (int)small_mats_per_group(c, regs) * 8;
+    size_t lds = 64 * sizeof(double) + (size_t)a.mat_floats * sizeof(float);
     if (threads > 64) lds += 2 * (size_t)(2 << regs) * threads * sizeof(float);
     const dim3 grid((unsigned)blocks), block(threads);
     switch (regs) {
