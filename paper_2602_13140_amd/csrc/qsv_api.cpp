@@ -725,6 +725,10 @@ static qsv_status measure_impl(qsv_ctx* ctx, const qsv_measure_req* req, Arena& 
             if (req->kind == QSV_M_EXPZ_ONE && (q < 0 || q >= n))
                 return fail(ctx, QSV_ERR_INVALID_ARG, "qubit out of range");
             if ((st = bind_device(ctx)) != QSV_OK) return st;
+            if (chunk_blocks(n) == 1) {           // a row is one chunk: no partial sums to combine
+                QSV_HIP(ctx, launch_expz_small(ctx->state, B, n, q, (float*)req->out_dev, ctx->stream), "expz");
+                return QSV_OK;
+            }
             double* partial = (double*)ar.take((size_t)B * chunk_blocks(n) * 13 * 8);
             if (!partial) return ws_fail(ctx, ar, "qsv_measure(EXPZ)");
             QSV_HIP(ctx, launch_expz_block(ctx->state, B, n, partial, ctx->stream), "expz block");

@@ -132,6 +132,8 @@ hipError_t launch_encode_write(const float* x, int64_t dim, int n, int64_t rows,
 hipError_t launch_probs(const float2* state, uint64_t total, float* out, hipStream_t st);
 // partial: [rows][nblk][13] doubles; nblk = max(1, 2^n / 4096)
 hipError_t launch_expz_block(const float2* state, int64_t rows, int n, double* partial, hipStream_t st);
+// rows of at most 4096 amplitudes: <Z_q> of every qubit (q_only < 0) or of q_only in one launch, same bits as block + finish
+hipError_t launch_expz_small(const float2* state, int64_t rows, int n, int q_only, float* out_f, hipStream_t st);
 hipError_t launch_expz_finish(const double* partial, int64_t rows, int n, int q_only, float* out_f,
                               double* out_d, hipStream_t st);
 // Where one-qubit results of gradient rows go: circuit gid = row0 + r lands at

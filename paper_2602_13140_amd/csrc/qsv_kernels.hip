@@ -808,8 +808,10 @@ __global__ __launch_bounds__(256) void k_probs(const float2* state, u64 total, f
 // Block (row, blk) reduces 4096 consecutive amplitudes to 13 doubles: total T and the signed sums
 // Z_0..Z_11 for the 12 index bits inside the chunk.  Chunk-local index = i*256 + thread
 // (bits 0-5 lane, 6-7 wavefront, 8-11 register).
+// direct != NULL (only with nblk = 1: a row is one chunk): the block writes the row's <Z_q> itself,
+// float(the sum the finishing kernel would copy), for every qubit (q_only < 0) or for q_only alone.
 __global__ __launch_bounds__(256) void k_expz_block(const float2* state, u64 rows, int n, int nblk,
-                                                    double* partial) {
+                                                    double* partial, float* direct, int q_only) {
     __shared__ double sm[4][11];
     const u64 row = grid_row();
     if (row >= rows) return;
@@ -848,13 +850,19 @@ __global__ __launch_bounds__(256) void k_expz_block(const float2* state, u64 row
     }
     __syncthreads();
     if (threadIdx.x == 0) {
-        double* o = partial + (row * nblk + blockIdx.x) * 13;
+        double loc[13];
+        double* o = direct ? loc : partial + (row * nblk + blockIdx.x) * 13;
         const double t0 = sm[0][0], t1 = sm[1][0], t2 = sm[2][0], t3 = sm[3][0];
         o[0] = (t0 + t1) + (t2 + t3);
         for (int j = 0; j < 6; ++j) o[1 + j] = (sm[0][1 + j] + sm[1][1 + j]) + (sm[2][1 + j] + sm[3][1 + j]);
         o[7] = (t0 - t1) + (t2 - t3);
         o[8] = (t0 + t1) - (t2 + t3);
         for (int j = 0; j < 4; ++j) o[9 + j] = (sm[0][7 + j] + sm[1][7 + j]) + (sm[2][7 + j] + sm[3][7 + j]);
+        if (direct) {
+            if (q_only >= 0) direct[row] = (float)o[1 + q_only];
+            else
+                for (int q = 0; q < n; ++q) direct[row * n + q] = (float)o[1 + q];
+        }
     }
 }
 
@@ -2323,7 +2331,14 @@ static inline int chunk_blocks(int bits) { return bits > CHUNK_BITS ? 1 << (bits
 hipError_t launch_expz_block(const float2* state, int64_t rows, int n, double* partial, hipStream_t st) {
     const int nblk = chunk_blocks(n);
     hipLaunchKernelGGL(k_expz_block, rows_grid(nblk, (u64)rows), dim3(256), 0, st, state, (u64)rows, n, nblk,
-                       partial);
+                       partial, (float*)nullptr, -1);
+    return hipGetLastError();
+}
+
+hipError_t launch_expz_small(const float2* state, int64_t rows, int n, int q_only, float* out_f, hipStream_t st) {
+    if (chunk_blocks(n) != 1 || !out_f || q_only >= n) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(k_expz_block, rows_grid(1, (u64)rows), dim3(256), 0, st, state, (u64)rows, n, 1,
+                       (double*)nullptr, out_f, q_only);
     return hipGetLastError();
 }
 
