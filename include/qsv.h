@@ -286,6 +286,10 @@ qsv_status qsv_probe_pass(qsv_ctx* ctx, int low_bits, int window_start, int tran
  * qubits than the tile has index bits, at most 28 of them, and the workspace has room for a copy of
  * the state; the result is the same up to rounding order); load_store_priority = 1 (default) / 0 makes
  * the pass kernel's wavefronts raise their issue priority while they issue a tile's loads and stores;
+ * small_apply = 1 (default) / 0 lets qsv_apply_layers run states of at most 10 qubits and 2^21 amplitudes in
+ * all in one launch with the gates in registers and lane exchanges (the kernel of qsv_forward_small, started
+ * from the state; measured 1.6 to 4 times faster there than the fused passes, whose launches cost more than
+ * their arithmetic on such states), or always takes the fused passes;
  * small_regs = 2, 3 or 4 fixes the amplitudes per thread of qsv_forward_small at 4, 8 or 16 (0, the
  * default, takes the most that still gives the chip about four wavefronts per SIMD); low_bits in 4..10 (0 = default) forces the planner's minimum number of low index bits
  * per tile; lds_planes = 1 (default) moves real and imaginary parts through one LDS plane one

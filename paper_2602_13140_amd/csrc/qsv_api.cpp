@@ -75,6 +75,7 @@ struct qsv_ctx {
     int64_t opt_grad_chunk = 0;
     int opt_split = -1;      // state rows of a launch sequence in two halves on two streams; -1: by state size
     int opt_prio = 1;        // raised issue priority around a tile's loads and stores (measured: 2 % off configs 3 and 4)
+    int opt_small_apply = 1; // qsv_apply_layers runs states of at most 2^21 amplitudes on at most 10 qubits in one launch
     int opt_small_regs = 0;  // qsv_forward_small: amplitudes per thread = 2^this (2..4); 0: by batch size
     int opt_defer = -1;      // qsv_apply_layers defers CNOTs whose target lies outside a pass's tile; -1: when it can
     hipStream_t side = nullptr;          // second stream for that (default priority, non-blocking)
@@ -612,6 +613,11 @@ qsv_status qsv_set_option(qsv_ctx* ctx, const char* name, int64_t value) {
         ctx->opt_prio = (int)value;
         return QSV_OK;
     }
+    if (!strcmp(name, "small_apply")) {
+        if (value < 0 || value > 1) return fail(ctx, QSV_ERR_INVALID_ARG, "small_apply must be 0 or 1");
+        ctx->opt_small_apply = (int)value;
+        return QSV_OK;
+    }
     if (!strcmp(name, "small_regs")) {
         if (value != 0 && (value < 2 || value > 4)) return fail(ctx, QSV_ERR_INVALID_ARG, "small_regs must be 0, 2, 3 or 4");
         ctx->opt_small_regs = (int)value;
@@ -679,6 +685,19 @@ qsv_status qsv_apply_layers(qsv_ctx* ctx, const qsv_circuit* c, const float* par
     if (c->reupload && !feats_dev) return fail(ctx, QSV_ERR_INVALID_ARG, "reupload = 1 needs feats_dev");
     qsv_status st = bind_device(ctx);
     if (st != QSV_OK) return st;
+    // States small enough that launches cost more than arithmetic: the whole call in one launch, gates in
+    // registers and lane exchanges (the kernel of qsv_forward_small, started from the state).
+    if (ctx->opt_small_apply != 0 && ctx->n <= kSmallMaxQubits && ctx->opt_tile == 0 && !ctx->opt_naive &&
+        ((int64_t)ctx->batch << ctx->n) <= kSmallApplyAmplitudes) {
+        const CircDev cd = to_dev(*c, ctx->n);
+        const int regs = ctx->opt_small_regs ? ctx->opt_small_regs : small_choose_regs(cd, ctx->batch);
+        if (regs != 0 && ctx->n - regs <= 8 && small_mats_per_group(cd, regs) <= kSmallMats) {
+            QSV_HIP(ctx, launch_forward_small(regs, nullptr, 0, ctx->batch, cd, c->entangler, params_dev, feats_dev, inverse,
+                                              inverse, 0, ctx->state, nullptr, nullptr, ctx->stream),
+                    "apply_small");
+            return QSV_OK;
+        }
+    }
     Arena ar(ctx);
     float* mats = (float*)ar.take(mats_bytes(*c, ctx->n, ctx->batch));
     if (!mats) return ws_fail(ctx, ar, "qsv_apply_layers");
@@ -817,7 +836,7 @@ qsv_status qsv_forward_small(qsv_ctx* ctx, const float* x_dev, int64_t dim, cons
                     "that share a wavefront when the circuit re-uploads data): use the separate calls");
     qsv_status st = bind_device(ctx);
     if (st != QSV_OK) return st;
-    QSV_HIP(ctx, launch_forward_small(regs, x_dev, dim, ctx->batch, cd, c->entangler, params_dev, feats_dev, decode, kind,
+    QSV_HIP(ctx, launch_forward_small(regs, x_dev, dim, ctx->batch, cd, c->entangler, params_dev, feats_dev, 0, decode, kind,
                                       ctx->state, (float*)out_dev, norm_out_dev, ctx->stream),
             "forward_small");
     return QSV_OK;

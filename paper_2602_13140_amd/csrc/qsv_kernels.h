@@ -99,6 +99,7 @@ hipError_t launch_encode_small(const float* x, int64_t samples, int64_t dim, int
 // fewer than 6 of them a wavefront holds 2^(6 - bits) samples.  A workgroup keeps the matrices of its
 // samples in LDS (at most kSmallMats).
 constexpr int kSmallMaxQubits = 10;
+constexpr int64_t kSmallApplyAmplitudes = (int64_t)1 << 21;   // batch * 2^n up to which one launch beats the fused passes
 constexpr int kSmallMats = 512;   // matrices a workgroup keeps in LDS (16 KiB)
 inline int small_rows_per_group(int n, int regs) {
     const int tb = n > regs ? n - regs : 0;
@@ -122,9 +123,11 @@ inline int small_choose_regs(const CircDev& c, int64_t batch) {
     }
     return fallback;
 }
+// x = NULL: start from the amplitudes in `state`; passes pass_first..pass_last (0 = the circuit, 1 = its inverse);
+// kind = 0: no measurement (the final state is always written)
 hipError_t launch_forward_small(int regs, const float* x, int64_t dim, int64_t batch, const CircDev& c, int entangler,
-                                const float* params, const float* feats, int decode, int kind, float2* state,
-                                float* out, float* norm_out, hipStream_t st);
+                                const float* params, const float* feats, int pass_first, int pass_last, int kind,
+                                float2* state, float* out, float* norm_out, hipStream_t st);
 hipError_t launch_encode_write(const float* x, int64_t dim, int n, int64_t rows, const double* inv_norm,
                                const RowMap& rm, float2* state, hipStream_t st);
 

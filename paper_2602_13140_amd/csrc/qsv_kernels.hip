@@ -1949,8 +1949,9 @@ struct SmallArgs {
     int entangler;         // qsv_ent
     const float* params;
     const float* feats;
-    int decode;            // 1: the inverse circuit follows the circuit
-    int kind;              // QSV_M_PROBS or QSV_M_EXPZ_ALL
+    int pass_first, pass_last;  // 0 = the circuit, 1 = its inverse: (0,0) circuit, (0,1) circuit then inverse, (1,1) inverse
+    int from_state;        // 1: start from the amplitudes in `state` instead of encoding x
+    int kind;              // QSV_M_PROBS, QSV_M_EXPZ_ALL, or 0: no measurement
     float2* state;         // [batch][2^n], receives the final state
     float* out;            // probabilities [batch][2^n] or expectations [batch][n]
     float* norm_out;       // [batch] or NULL
@@ -1992,9 +1993,17 @@ __global__ __launch_bounds__(256) void k_forward_small(SmallArgs a) {
             for (int k = 0; k < 4; ++k) { o[2 * k] = (float)u.r[k]; o[2 * k + 1] = (float)u.i[k]; }
         }
     }
-    // amplitude encoding: x / ||x||, the norm in double
+    // amplitude encoding: x / ||x||, the norm in double (or the amplitudes the state already holds)
     Amps<R> A;
-    {
+    if (a.from_state) {
+        const float2* srow = a.state + ((live ? sample : 0) << n) + ((int64_t)ti << R);
+#pragma unroll
+        for (int k = 0; k < NR; ++k) {
+            const int64_t idx = ((int64_t)ti << R) | k;
+            const float2 v = (live && idx < ((int64_t)1 << n)) ? srow[k] : make_float2(0.f, 0.f);
+            A.re[k] = v.x; A.im[k] = v.y;
+        }
+    } else {
         const float* xb = a.x + (live ? sample : 0) * a.dim;
         float xv[NR];
         double ss = 0.0;
@@ -2029,7 +2038,7 @@ __global__ __launch_bounds__(256) void k_forward_small(SmallArgs a) {
     for (int b = 0; b + 1 < tb; ++b) src_r ^= ((src_r >> b) & 1) << (b + 1);
     // the gates: per layer the unitaries then the entangler; in the decoder layers last to first,
     // the entangler's gates in reverse order first, then the conjugate-transposed unitaries
-    for (int pass = 0; pass <= a.decode; ++pass) {
+    for (int pass = a.pass_first; pass <= a.pass_last; ++pass) {
         for (int ll = 0; ll < L; ++ll) {
             const int l = pass ? L - 1 - ll : ll;
             for (int stage = 0; stage < 2; ++stage) {
@@ -2077,6 +2086,7 @@ __global__ __launch_bounds__(256) void k_forward_small(SmallArgs a) {
                 if (k < dimn) srow[k] = make_float2(A.re[k], A.im[k]);
         }
     }
+    if (a.kind == 0) return;
     float p[NR];
 #pragma unroll
     for (int k = 0; k < NR; ++k) p[k] = prob32(make_float2(A.re[k], A.im[k]));
@@ -2284,10 +2294,11 @@ hipError_t launch_encode_small(const float* x, int64_t samples, int64_t dim, int
 }
 
 hipError_t launch_forward_small(int regs, const float* x, int64_t dim, int64_t batch, const CircDev& c, int entangler,
-                                const float* params, const float* feats, int decode, int kind, float2* state,
-                                float* out, float* norm_out, hipStream_t st) {
-    if (c.n < 1 || c.n > kSmallMaxQubits || batch < 1 || dim < 1 || dim > ((int64_t)1 << c.n))
-        return hipErrorInvalidValue;
+                                const float* params, const float* feats, int pass_first, int pass_last, int kind,
+                                float2* state, float* out, float* norm_out, hipStream_t st) {
+    if (c.n < 1 || c.n > kSmallMaxQubits || batch < 1) return hipErrorInvalidValue;
+    if (x && (dim < 1 || dim > ((int64_t)1 << c.n))) return hipErrorInvalidValue;
+    if (pass_first < 0 || pass_last > 1 || pass_first > pass_last || (kind != 0 && !out)) return hipErrorInvalidValue;
     if (regs < 2 || regs > 4 || c.n - regs > 8) return hipErrorInvalidValue;
     if (small_mats_per_group(c, regs) > kSmallMats) return hipErrorInvalidValue;
     const int rows_g = small_rows_per_group(c.n, regs);
@@ -2295,7 +2306,8 @@ hipError_t launch_forward_small(int regs, const float* x, int64_t dim, int64_t b
     const unsigned threads = tb > 6 ? 64u << (tb - 6) : 64u;
     SmallArgs a;
     a.x = x; a.dim = dim; a.batch = batch; a.c = c; a.entangler = entangler; a.params = params; a.feats = feats;
-    a.decode = decode; a.kind = kind; a.state = state; a.out = out; a.norm_out = norm_out;
+    a.pass_first = pass_first; a.pass_last = pass_last; a.from_state = x ? 0 : 1; a.kind = kind;
+    a.state = state; a.out = out; a.norm_out = norm_out;
     const int64_t blocks = (batch + rows_g - 1) / rows_g;
     if (blocks > 0x7fffffff) return hipErrorInvalidValue;
     // sums across wavefronts, the matrices (only as many as this circuit has: LDS per workgroup decides how

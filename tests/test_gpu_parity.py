@@ -80,7 +80,7 @@ SMALL = [
 
 
 @pytest.mark.parametrize("n,B,L,rot,ent,reup", SMALL)
-@pytest.mark.parametrize("mode", ["default", "t10", "t11", "t12", "t13", "t14", "naive",
+@pytest.mark.parametrize("mode", ["default", "passes", "t10", "t11", "t12", "t13", "t14", "naive",
                                   "t10p1", "t11p2", "t12p1", "t13p1", "t12p2", "t14p1", "t10c", "t11c", "t12c", "t10l", "t12l"])
 def test_apply_layers_small(oracle, n, B, L, rot, ent, reup, mode):
     g = rng(31 * n + B + L)
@@ -92,6 +92,8 @@ def test_apply_layers_small(oracle, n, B, L, rot, ent, reup, mode):
     ctx = gu.make_ctx(n, B, tile=int(mode[1:3]) if mode.startswith("t") else 0,
                       naive=1 if mode == "naive" else 0,
                       planes=int(mode[4]) if mode[3:4] == "p" else 0)
+    if mode == "passes":
+        ctx.qsv_set_option("small_apply", 0)   # the fused passes also where the default takes the one-launch kernel (small states)
     if mode.endswith("l"):
         ctx.qsv_set_option("low_bits", 3)      # tiles made of 64-byte runs (three low index bits) instead of 128-byte ones
     if mode.endswith("c"):
