@@ -673,6 +673,37 @@ def test_forward_small_equals_the_oracle_and_the_separate_calls(oracle, n, B, di
     ctx.close()
 
 
+def test_small_states_random_sweep(oracle):
+    """Seeded sweep over what qsv_apply_layers runs in one launch (1-10 qubits, ragged batches and dims, 0-6
+    layers, any rotation list, both entanglers or none, re-uploading, every thread layout): circuit,
+    inverse, inverse, circuit in a row on one state, each compared with the oracle."""
+    torch = gu.torch_cuda()
+    g = rng(12345)
+    for it in range(80):
+        n = int(g.integers(1, 11))
+        B = int(g.choice([1, 2, 3, 5, 17, 64, 65, 130, 300]))
+        L = int(g.integers(0, 7))
+        rot = tuple(int(v) for v in g.integers(1, 4, int(g.integers(0, 4))))
+        ent, reup, regs = int(g.integers(0, 3)), int(g.integers(0, 2)), int(g.choice([0, 2, 3, 4]))
+        spec = wl.CircuitSpec(L, rot, ent, reup)
+        params = wl.draw_params(spec, n, 1000 + it)
+        x = g.standard_normal((B, int(g.integers(1, (1 << n) + 1)))).astype(np.float32)
+        feats = g.standard_normal((B, n)).astype(np.float32) if reup else None
+        ctx = gu.make_ctx(n, B)
+        ctx.qsv_set_option("small_regs", regs)
+        circ = qb.circuit_from_spec(spec)
+        pd = gu.dev(params if params.size else np.zeros(1, np.float32))
+        fd = gu.dev(feats) if reup else None
+        ref, _ = oracle.amp_encode(x, n)
+        ctx.qsv_amp_encode(gu.dev(x))
+        for inverse in (0, 1, 1, 0):
+            oracle.apply_layers(ref, ocirc(oracle, spec), params, feats, inverse=bool(inverse))
+            ctx.qsv_apply_layers(circ, pd, fd, inverse)
+            err = np.abs(gu.state_np(ctx) - ref).max()
+            assert err <= amp_tol(n), (it, n, B, L, rot, ent, reup, regs, inverse, err)
+        ctx.close()
+
+
 def test_forward_small_refuses_what_it_does_not_serve():
     torch = gu.torch_cuda()
     circ = qb.make_circuit(2, [RY], RING, 0)
