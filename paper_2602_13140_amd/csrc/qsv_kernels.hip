@@ -2133,8 +2133,11 @@ __global__ __launch_bounds__(256) void k_forward_small(SmallArgs a) {
         if (live && ti == 0) {
             float* orow = a.out + sample * n;
 #pragma unroll
-            for (int q = 0; q < 10; ++q)
-                if (q < n) orow[q] = (float)(q < R ? zr[q < R ? q : 0] : zl[q >= R && q - R < 6 ? q - R : 0]);
+            for (int q = 0; q < R; ++q)            // qubits behind register bits
+                if (q < n) orow[q] = (float)zr[q];
+#pragma unroll
+            for (int b = 0; b < 6; ++b)            // qubits behind lane bits
+                if (R + b < n) orow[R + b] = (float)zl[b];
         }
         return;
     }
